@@ -1,0 +1,9 @@
+"""MI355X-native fused multi-agent PPO training step (IPPO / MAPPO on a grid-foraging world).
+
+Everything is computed by hand-written HIP kernels in libmarl_gfx950.so (C ABI in include/marl.h);
+this package only marshals arguments.  PyTorch is used for device memory and streams.
+"""
+from .binding import (  # noqa: F401
+    Config, EnvState, Traj, MarlError, lib, make_config, query_sizes, env_reset, observe, env_step,
+    policy_forward, sample_actions, rollout, compute_gae, ppo_update, status_string, alloc_workspace,
+)

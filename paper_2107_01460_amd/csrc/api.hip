@@ -1,0 +1,174 @@
+// C ABI entry points: argument validation on the host, then the launchers.
+#include "common.h"
+
+namespace marl {
+
+int32_t validate_config(const marl_config* c) {
+  if (c == nullptr) return MARL_E_NULL;
+  if (c->grid < 2 || c->grid > 64) return MARL_E_CONFIG;
+  if (c->n_agents < 1 || c->n_agents > kMaxAgents) return MARL_E_CONFIG;
+  if (c->n_food < 1 || c->n_food > kMaxFood) return MARL_E_CONFIG;
+  if (c->n_agents + c->n_food > c->grid * c->grid) return MARL_E_CONFIG;
+  if (c->max_level < 1 || c->max_level > 15) return MARL_E_CONFIG;
+  if (c->episode_cap < 1) return MARL_E_CONFIG;
+  if (c->view != 3 && c->view != 5 && c->view != 7) return MARL_E_CONFIG;
+  if (c->n_envs < 1 || c->rollout_len < 1) return MARL_E_CONFIG;
+  for (int h : {c->actor_hidden, c->critic_hidden})
+    if (h < 32 || h > 512 || h % 32 != 0) return MARL_E_CONFIG;
+  if (c->central_critic != 0 && c->central_critic != 1) return MARL_E_CONFIG;
+  if (c->precision != 0 && c->precision != 1) return MARL_E_CONFIG;
+  if (c->n_epochs < 1 || c->n_minibatches < 1) return MARL_E_CONFIG;
+  const int64_t R = (int64_t)c->n_envs * c->rollout_len;
+  if (R % c->n_minibatches != 0) return MARL_E_CONFIG;
+  if (R * c->n_agents >= ((int64_t)1 << 31)) return MARL_E_CONFIG;  // sample and row indices are 32-bit
+  if (!(c->gamma >= 0.f && c->gamma <= 1.f) || !(c->lambda >= 0.f && c->lambda <= 1.f)) return MARL_E_CONFIG;
+  if (!(c->clip_eps > 0.f) || !(c->lr > 0.f) || !(c->adam_eps > 0.f)) return MARL_E_CONFIG;
+  if (!(c->beta1 >= 0.f && c->beta1 < 1.f) || !(c->beta2 >= 0.f && c->beta2 < 1.f)) return MARL_E_CONFIG;
+  if (!(c->ent_coef >= 0.f) || !(c->vf_coef >= 0.f)) return MARL_E_CONFIG;
+  if (c->normalize_adv != 0 && c->normalize_adv != 1) return MARL_E_CONFIG;
+  if (c->clip_value != 0 && c->clip_value != 1) return MARL_E_CONFIG;
+  return MARL_OK;
+}
+
+static int32_t check_state(const marl_env_state& st) {
+  MARL_REQUIRE_PTR(st.agent_row); MARL_REQUIRE_PTR(st.agent_col); MARL_REQUIRE_PTR(st.agent_lvl);
+  MARL_REQUIRE_PTR(st.food_row); MARL_REQUIRE_PTR(st.food_col); MARL_REQUIRE_PTR(st.food_lvl);
+  MARL_REQUIRE_PTR(st.t_in_ep); MARL_REQUIRE_PTR(st.episode_id);
+  return MARL_OK;
+}
+
+static int32_t check_traj(const marl_traj& t, bool need_gae_outputs) {
+  MARL_REQUIRE_PTR(t.obs); MARL_REQUIRE_PTR(t.action); MARL_REQUIRE_PTR(t.logp); MARL_REQUIRE_PTR(t.value);
+  MARL_REQUIRE_PTR(t.reward); MARL_REQUIRE_PTR(t.done); MARL_REQUIRE_PTR(t.last_value);
+  if (need_gae_outputs) {
+    MARL_REQUIRE_PTR(t.adv);
+    MARL_REQUIRE_PTR(t.ret);
+  }
+  MARL_OPTIONAL_PTR(t.logits);
+  MARL_OPTIONAL_PTR(t.sampled);
+  return MARL_OK;
+}
+
+}  // namespace marl
+
+using namespace marl;
+
+extern "C" {
+
+int32_t marl_query_sizes(const marl_config* cfg, marl_sizes* out) {
+  if (cfg == nullptr || out == nullptr) return MARL_E_NULL;
+  const int32_t rc = validate_config(cfg);
+  if (rc != MARL_OK) return rc;
+  const Dims d = dims_of(*cfg);
+  out->obs_dim = d.D;
+  out->critic_in_dim = d.Dc;
+  out->n_params = d.P;
+  out->n_actor_params = d.Pa;
+  out->state_entity_bytes_agents = (int64_t)d.A * d.N;
+  out->state_entity_bytes_food = (int64_t)d.F * d.N;
+  out->state_t_bytes = 4 * (int64_t)d.N;
+  out->state_episode_bytes = 4 * (int64_t)d.N;
+  out->obs_bytes = 4 * (int64_t)(d.T + 1) * d.NA * d.D;
+  out->step_scalar_bytes = 4 * (int64_t)d.T * d.NA;
+  out->done_bytes = (int64_t)d.T * d.N;
+  out->last_value_bytes = 4 * d.NA;
+  out->logits_bytes = 4 * (int64_t)d.T * d.NA * kActions;
+  out->rollout_workspace_bytes = rollout_workspace_bytes(*cfg, d.N);
+  out->update_workspace_bytes = update_workspace_bytes(*cfg);
+  return MARL_OK;
+}
+
+int32_t marl_env_reset(const marl_config* cfg, marl_env_state st, void* stream) {
+  int32_t rc = validate_config(cfg);
+  if (rc != MARL_OK) return rc;
+  if ((rc = check_state(st)) != MARL_OK) return rc;
+  return launch_env_reset(*cfg, st, (hipStream_t)stream);
+}
+
+int32_t marl_observe(const marl_config* cfg, marl_env_state st, float* obs, void* stream) {
+  int32_t rc = validate_config(cfg);
+  if (rc != MARL_OK) return rc;
+  if ((rc = check_state(st)) != MARL_OK) return rc;
+  MARL_REQUIRE_PTR(obs);
+  return launch_env_step(*cfg, st, nullptr, obs, nullptr, nullptr, false, (hipStream_t)stream);
+}
+
+int32_t marl_env_step(const marl_config* cfg, marl_env_state st, const int32_t* actions, float* obs, float* reward,
+                      uint8_t* done, void* stream) {
+  int32_t rc = validate_config(cfg);
+  if (rc != MARL_OK) return rc;
+  if ((rc = check_state(st)) != MARL_OK) return rc;
+  MARL_REQUIRE_PTR(actions); MARL_REQUIRE_PTR(reward); MARL_REQUIRE_PTR(done);
+  MARL_OPTIONAL_PTR(obs);
+  return launch_env_step(*cfg, st, actions, obs, reward, done, true, (hipStream_t)stream);
+}
+
+int32_t marl_policy_forward(const marl_config* cfg, const float* params, const float* obs, int64_t n_rows,
+                            float* logits, float* value, void* workspace, void* stream) {
+  int32_t rc = validate_config(cfg);
+  if (rc != MARL_OK) return rc;
+  MARL_REQUIRE_PTR(params); MARL_REQUIRE_PTR(obs); MARL_REQUIRE_PTR(workspace);
+  MARL_OPTIONAL_PTR(logits); MARL_OPTIONAL_PTR(value);
+  if (n_rows < 0 || n_rows * cfg->n_agents >= ((int64_t)1 << 31)) return MARL_E_SIZE;
+  if (n_rows == 0 || (logits == nullptr && value == nullptr)) return MARL_OK;
+  return launch_policy_forward(*cfg, params, obs, n_rows, logits, value, workspace, (hipStream_t)stream);
+}
+
+int32_t marl_sample_actions(const marl_config* cfg, const float* logits, const float* uniforms, const int32_t* forced,
+                            int64_t n, uint64_t step, int32_t* action, int32_t* sampled, float* logp, void* stream) {
+  int32_t rc = validate_config(cfg);
+  if (rc != MARL_OK) return rc;
+  MARL_REQUIRE_PTR(logits); MARL_REQUIRE_PTR(action); MARL_REQUIRE_PTR(logp);
+  MARL_OPTIONAL_PTR(uniforms); MARL_OPTIONAL_PTR(forced); MARL_OPTIONAL_PTR(sampled);
+  if (n < 0 || n >= ((int64_t)1 << 31)) return MARL_E_SIZE;
+  if (n == 0) return MARL_OK;
+  return launch_sample(*cfg, logits, uniforms, forced, n, step, action, sampled, logp, (hipStream_t)stream);
+}
+
+int32_t marl_rollout(const marl_config* cfg, marl_env_state st, const float* params, marl_traj traj,
+                     uint64_t step_offset, const int32_t* forced_actions, const float* forced_uniforms,
+                     void* workspace, void* stream) {
+  int32_t rc = validate_config(cfg);
+  if (rc != MARL_OK) return rc;
+  if ((rc = check_state(st)) != MARL_OK) return rc;
+  if ((rc = check_traj(traj, false)) != MARL_OK) return rc;
+  MARL_REQUIRE_PTR(params); MARL_REQUIRE_PTR(workspace);
+  MARL_OPTIONAL_PTR(forced_actions); MARL_OPTIONAL_PTR(forced_uniforms);
+  return launch_rollout(*cfg, st, params, traj, step_offset, forced_actions, forced_uniforms, workspace,
+                        (hipStream_t)stream);
+}
+
+int32_t marl_compute_gae(const marl_config* cfg, marl_traj traj, void* stream) {
+  int32_t rc = validate_config(cfg);
+  if (rc != MARL_OK) return rc;
+  if ((rc = check_traj(traj, true)) != MARL_OK) return rc;
+  return launch_gae(*cfg, traj, (hipStream_t)stream);
+}
+
+int32_t marl_ppo_update(const marl_config* cfg, marl_traj traj, float* params, float* adam_m, float* adam_v,
+                        int64_t adam_step0, const int32_t* perm, float* stats, float* grad_dump, void* workspace,
+                        void* stream) {
+  int32_t rc = validate_config(cfg);
+  if (rc != MARL_OK) return rc;
+  if ((rc = check_traj(traj, true)) != MARL_OK) return rc;
+  MARL_REQUIRE_PTR(params); MARL_REQUIRE_PTR(adam_m); MARL_REQUIRE_PTR(adam_v); MARL_REQUIRE_PTR(stats);
+  MARL_REQUIRE_PTR(workspace);
+  MARL_OPTIONAL_PTR(perm); MARL_OPTIONAL_PTR(grad_dump);
+  if (adam_step0 < 0) return MARL_E_SIZE;
+  return launch_ppo_update(*cfg, traj, params, adam_m, adam_v, adam_step0, perm, stats, grad_dump, workspace,
+                           (hipStream_t)stream);
+}
+
+const char* marl_status_string(int32_t status) {
+  switch (status) {
+    case MARL_OK: return "ok";
+    case MARL_E_NULL: return "a required pointer is null";
+    case MARL_E_ALIGN: return "a device pointer is not 16-byte aligned";
+    case MARL_E_CONFIG: return "unsupported or inconsistent configuration";
+    case MARL_E_LAUNCH: return "the HIP runtime reported a launch error";
+    case MARL_E_SIZE: return "a size argument is out of range";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

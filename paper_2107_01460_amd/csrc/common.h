@@ -1,0 +1,107 @@
+// Internal declarations shared by the translation units of libmarl_gfx950.so.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "marl.h"
+
+namespace marl {
+
+constexpr int kActions = MARL_N_ACTIONS;
+constexpr int kMaxAgents = 8;
+constexpr int kMaxFood = 8;
+
+// Sizes derived from a validated configuration.
+struct Dims {
+  int G, A, F, V, D, N, T;
+  int Ha, Hc, Dc;
+  int64_t Pa, Pc, P;   // parameter counts: actor, critic, total
+  int64_t NA;          // N * A
+  bool central, bf16;
+};
+
+inline Dims dims_of(const marl_config& c) {
+  Dims d;
+  d.G = c.grid; d.A = c.n_agents; d.F = c.n_food; d.V = c.view; d.D = 3 * c.view * c.view;
+  d.N = c.n_envs; d.T = c.rollout_len; d.Ha = c.actor_hidden; d.Hc = c.critic_hidden;
+  d.central = c.central_critic != 0;
+  d.bf16 = c.precision == 1;
+  d.Dc = d.central ? d.A * d.D : d.D;
+  d.Pa = (int64_t)d.D * d.Ha + d.Ha + (int64_t)d.Ha * d.Ha + d.Ha + (int64_t)d.Ha * kActions + kActions;
+  d.Pc = (int64_t)d.Dc * d.Hc + d.Hc + (int64_t)d.Hc * d.Hc + d.Hc + d.Hc + 1;
+  d.P = d.Pa + d.Pc;
+  d.NA = (int64_t)d.N * d.A;
+  return d;
+}
+
+// Offsets (in floats) of one network's blocks inside the flat parameter vector.
+struct NetOffsets {
+  int64_t W1, b1, W2, b2, W3, b3, end;
+};
+inline NetOffsets net_offsets(int64_t base, int Din, int H, int Dout) {
+  NetOffsets o;
+  o.W1 = base;
+  o.b1 = o.W1 + (int64_t)Din * H;
+  o.W2 = o.b1 + H;
+  o.b2 = o.W2 + (int64_t)H * H;
+  o.W3 = o.b2 + H;
+  o.b3 = o.W3 + (int64_t)H * Dout;
+  o.end = o.b3 + Dout;
+  return o;
+}
+
+int32_t validate_config(const marl_config* cfg);
+inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+#define MARL_REQUIRE_PTR(p)                 \
+  do {                                      \
+    if ((p) == nullptr) return MARL_E_NULL; \
+    if (marl::misaligned(p)) return MARL_E_ALIGN; \
+  } while (0)
+#define MARL_OPTIONAL_PTR(p)                                     \
+  do {                                                           \
+    if ((p) != nullptr && marl::misaligned(p)) return MARL_E_ALIGN; \
+  } while (0)
+
+inline int32_t launch_status() { return hipGetLastError() == hipSuccess ? MARL_OK : MARL_E_LAUNCH; }
+
+// ---- Philox4x32-10 (Salmon et al., SC'11, Section 4) -------------------------------------
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                              uint32_t k1, uint32_t out[4]) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+    const uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+    c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+    k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+__device__ __forceinline__ uint32_t rand_below(uint32_t x, uint32_t n) { return __umulhi(x, n); }
+__device__ __forceinline__ float rand_unit(uint32_t x) { return ((float)(x >> 9) + 0.5f) * (1.0f / 8388608.0f); }
+constexpr uint32_t kStreamReset = 1, kStreamSample = 2;
+
+// ---- launchers implemented in the kernel translation units ------------------------------------
+int32_t launch_env_reset(const marl_config& c, marl_env_state st, hipStream_t s);
+// do_step = false: only observe.  actions/reward/done may be null then.
+int32_t launch_env_step(const marl_config& c, marl_env_state st, const int32_t* actions, float* obs, float* reward,
+                        uint8_t* done, bool do_step, hipStream_t s);
+
+struct RolloutWs;  // opaque carve-up of the rollout workspace
+int64_t rollout_workspace_bytes(const marl_config& c, int64_t n_rows);
+int64_t update_workspace_bytes(const marl_config& c);
+
+int32_t launch_policy_forward(const marl_config& c, const float* params, const float* obs, int64_t n_rows,
+                              float* logits, float* value, void* workspace, hipStream_t s);
+int32_t launch_sample(const marl_config& c, const float* logits, const float* uniforms, const int32_t* forced,
+                      int64_t n, uint64_t step, int32_t* action, int32_t* sampled, float* logp, hipStream_t s);
+int32_t launch_rollout(const marl_config& c, marl_env_state st, const float* params, marl_traj tr,
+                       uint64_t step_offset, const int32_t* forced_actions, const float* forced_uniforms,
+                       void* workspace, hipStream_t s);
+int32_t launch_gae(const marl_config& c, marl_traj tr, hipStream_t s);
+int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, float* adam_m, float* adam_v,
+                          int64_t adam_step0, const int32_t* perm, float* stats, float* grad_dump, void* workspace,
+                          hipStream_t s);
+
+}  // namespace marl

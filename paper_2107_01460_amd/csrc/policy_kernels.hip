@@ -1,0 +1,138 @@
+// Actor / critic forward pass of the rollout, categorical sampling, and the rollout driver.
+//
+// The two hidden layers of each network are MFMA GEMMs (gemm.h); the narrow output layer
+// (6 logits or 1 value) runs on the vector ALUs of the "head" kernel, which also draws the
+// action by Gumbel-max from Philox uniforms and evaluates its log-probability.
+#include "gemm.h"
+#include "heads.h"
+
+namespace marl {
+namespace {
+
+__global__ void round_params_kernel(const float* __restrict__ src, float* __restrict__ dst, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = round_to_bf16(src[i]);
+}
+
+struct RolloutWsView {
+  float *eff_params, *h1a, *h2a, *h1c, *h2c, *logits_tmp;
+};
+
+int64_t align256(int64_t x) { return (x + 255) & ~(int64_t)255; }
+
+RolloutWsView carve_rollout_ws(const marl_config& c, int64_t n_rows, void* ws, int64_t* total) {
+  const Dims d = dims_of(c);
+  const int64_t S = n_rows * d.A, Sc = d.central ? n_rows : S;
+  char* p = static_cast<char*>(ws);
+  int64_t off = 0;
+  auto take = [&](int64_t floats) {
+    float* r = reinterpret_cast<float*>(p + off);
+    off += align256(floats * 4);
+    return r;
+  };
+  RolloutWsView v;
+  v.eff_params = take(d.P);
+  v.h1a = take(S * d.Ha);
+  v.h2a = take(S * d.Ha);
+  v.h1c = take(Sc * d.Hc);
+  v.h2c = take(Sc * d.Hc);
+  v.logits_tmp = take(S * kActions);
+  if (total) *total = off;
+  return v;
+}
+
+}  // namespace
+
+void mlp_hidden_forward(const RowSrc& X, int64_t S, int Din, int H, const float* W1, const float* b1, const float* W2,
+                        const float* b2, float* h1, float* h2, bool bf16, hipStream_t s) {
+  GemmArgs g{};
+  g.A = X; g.B = W1; g.ldb = H; g.C = h1; g.ldc = H; g.aux_vec = b1;
+  g.M = S; g.N = H; g.K = Din; g.round_bf16 = bf16;
+  launch_gemm<GEMM_NN, EPI_BIAS_TANH>(g, s);
+  GemmArgs g2{};
+  g2.A = RowSrc{h1, H, nullptr, 1, S}; g2.B = W2; g2.ldb = H; g2.C = h2; g2.ldc = H; g2.aux_vec = b2;
+  g2.M = S; g2.N = H; g2.K = H; g2.round_bf16 = bf16;
+  launch_gemm<GEMM_NN, EPI_BIAS_TANH>(g2, s);
+}
+
+const float* effective_params(const marl_config& c, const float* params, float* scratch, hipStream_t s) {
+  if (c.precision != 1) return params;
+  const Dims d = dims_of(c);
+  hipLaunchKernelGGL(round_params_kernel, dim3((unsigned)((d.P + 255) / 256)), dim3(256), 0, s, params, scratch, d.P);
+  return scratch;
+}
+
+int64_t rollout_workspace_bytes(const marl_config& c, int64_t n_rows) {
+  int64_t total = 0;
+  carve_rollout_ws(c, n_rows, nullptr, &total);
+  return total;
+}
+
+// One forward pass over n_rows observation rows.  Any of logits / value / sampling outputs may be absent.
+static int32_t forward_rows(const marl_config& c, const float* eff, const float* obs, int64_t n_rows,
+                            const RolloutWsView& w, bool want_actor, float* logits_out, const SampleArgs* sample,
+                            float* value_out, hipStream_t s) {
+  const Dims d = dims_of(c);
+  const int64_t S = n_rows * d.A;
+  if (want_actor) {
+    const NetOffsets o = net_offsets(0, d.D, d.Ha, kActions);
+    mlp_hidden_forward(RowSrc{obs, d.D, nullptr, 1, S}, S, d.D, d.Ha, eff + o.W1, eff + o.b1, eff + o.W2, eff + o.b2,
+                       w.h1a, w.h2a, d.bf16, s);
+    launch_actor_head_rollout(w.h2a, S, d.Ha, eff + o.W3, eff + o.b3, logits_out, sample, s);
+  }
+  if (value_out) {
+    const NetOffsets o = net_offsets(d.Pa, d.Dc, d.Hc, 1);
+    const int64_t Sc = d.central ? n_rows : S;
+    mlp_hidden_forward(RowSrc{obs, d.Dc, nullptr, 1, Sc}, Sc, d.Dc, d.Hc, eff + o.W1, eff + o.b1, eff + o.W2,
+                       eff + o.b2, w.h1c, w.h2c, d.bf16, s);
+    launch_critic_head_rollout(w.h2c, Sc, d.Hc, eff + o.W3, eff + o.b3, value_out, d.central ? d.A : 1, s);
+  }
+  return launch_status();
+}
+
+int32_t launch_policy_forward(const marl_config& c, const float* params, const float* obs, int64_t n_rows,
+                              float* logits, float* value, void* workspace, hipStream_t s) {
+  const RolloutWsView w = carve_rollout_ws(c, n_rows, workspace, nullptr);
+  const float* eff = effective_params(c, params, w.eff_params, s);
+  return forward_rows(c, eff, obs, n_rows, w, logits != nullptr, logits, nullptr, value, s);
+}
+
+int32_t launch_sample(const marl_config& c, const float* logits, const float* uniforms, const int32_t* forced,
+                      int64_t n, uint64_t step, int32_t* action, int32_t* sampled, float* logp, hipStream_t s) {
+  SampleArgs a{};
+  a.uniforms = uniforms; a.forced = forced; a.action = action; a.sampled = sampled; a.logp = logp;
+  a.step = step; a.k0 = (uint32_t)(c.seed & 0xffffffffu); a.k1 = (uint32_t)(c.seed >> 32);
+  launch_sample_only(logits, n, a, s);
+  return launch_status();
+}
+
+int32_t launch_rollout(const marl_config& c, marl_env_state st, const float* params, marl_traj tr,
+                       uint64_t step_offset, const int32_t* forced_actions, const float* forced_uniforms,
+                       void* workspace, hipStream_t s) {
+  const Dims d = dims_of(c);
+  const RolloutWsView w = carve_rollout_ws(c, d.N, workspace, nullptr);
+  const float* eff = effective_params(c, params, w.eff_params, s);
+  const int64_t NA = d.NA, slab = NA * d.D;
+  int32_t rc = launch_env_step(c, st, nullptr, tr.obs, nullptr, nullptr, /*do_step=*/false, s);
+  if (rc != MARL_OK) return rc;
+  for (int t = 0; t < d.T; ++t) {
+    SampleArgs a{};
+    a.uniforms = forced_uniforms ? forced_uniforms + (int64_t)t * NA * kActions : nullptr;
+    a.forced = forced_actions ? forced_actions + (int64_t)t * NA : nullptr;
+    a.action = tr.action + (int64_t)t * NA;
+    a.sampled = tr.sampled ? tr.sampled + (int64_t)t * NA : nullptr;
+    a.logp = tr.logp + (int64_t)t * NA;
+    a.step = step_offset + (uint64_t)t;
+    a.k0 = (uint32_t)(c.seed & 0xffffffffu);
+    a.k1 = (uint32_t)(c.seed >> 32);
+    rc = forward_rows(c, eff, tr.obs + (int64_t)t * slab, d.N, w, true,
+                      tr.logits ? tr.logits + (int64_t)t * NA * kActions : nullptr, &a, tr.value + (int64_t)t * NA, s);
+    if (rc != MARL_OK) return rc;
+    rc = launch_env_step(c, st, a.action, tr.obs + (int64_t)(t + 1) * slab, tr.reward + (int64_t)t * NA,
+                         tr.done + (int64_t)t * d.N, true, s);
+    if (rc != MARL_OK) return rc;
+  }
+  return forward_rows(c, eff, tr.obs + (int64_t)d.T * slab, d.N, w, false, nullptr, nullptr, tr.last_value, s);
+}
+
+}  // namespace marl

@@ -1,0 +1,496 @@
+// Clipped-PPO minibatch update: forward over the gathered minibatch, loss and its gradient with
+// respect to logits / values on the ALUs, backward through the two hidden layers as MFMA GEMMs,
+// gradient accumulation with fp32 atomics, global-norm clipping and Adam.
+#include <algorithm>
+#include <cmath>
+
+#include "gemm.h"
+#include "heads.h"
+
+namespace marl {
+
+// implemented in policy_kernels.hip
+void mlp_hidden_forward(const RowSrc& X, int64_t S, int Din, int H, const float* W1, const float* b1, const float* W2,
+                        const float* b2, float* h1, float* h2, bool bf16, hipStream_t s);
+const float* effective_params(const marl_config& c, const float* params, float* scratch, hipStream_t s);
+
+namespace {
+
+// Device scalars of one minibatch step.
+struct Scalars {
+  double adv_sum, adv_sq;  // sum of advantages, sum of squared deviations
+  float acc[8];            // 0 policy loss, 1 value loss, 2 entropy, 3 approx KL, 4 clip fraction, 5 |grad|^2
+};
+
+struct LossCommon {
+  const int32_t* rows;  // [rows_mb] trajectory row of each minibatch row
+  int A;
+  int64_t rows_mb;
+  float inv_B;  // 1 / (rows_mb * A)
+  const Scalars* sc;
+  int normalize;
+  float clip_eps, ent_coef, vf_coef;
+  int clip_value;
+};
+
+__global__ void iota_kernel(int32_t* p, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = (int32_t)i;
+}
+
+__global__ void zero_step_kernel(float* grad, int64_t P, Scalars* sc) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < P) grad[i] = 0.f;
+  if (i == 0) {
+    sc->adv_sum = 0.0;
+    sc->adv_sq = 0.0;
+    for (int k = 0; k < 8; ++k) sc->acc[k] = 0.f;
+  }
+}
+
+__device__ __forceinline__ double block_sum_f64(double v, double* red) {
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  const int wave = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) red[wave] = v;
+  __syncthreads();
+  double t = 0;
+  if (threadIdx.x == 0)
+    for (int w = 0; w < (int)(blockDim.x >> 6); ++w) t += red[w];
+  return t;  // valid in thread 0
+}
+
+// pass 0: sum; pass 1: sum of squared deviations from the mean of pass 0
+__global__ void __launch_bounds__(256) adv_stats_kernel(const float* __restrict__ adv, LossCommon lc, Scalars* sc,
+                                                        int pass) {
+  __shared__ double red[4];
+  const int64_t B = lc.rows_mb * lc.A;
+  const double mean = pass ? sc->adv_sum / (double)B : 0.0;
+  double part = 0;
+  for (int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; s < B; s += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t row = s / lc.A;
+    const int a = (int)(s - row * lc.A);
+    const double x = adv[(int64_t)lc.rows[row] * lc.A + a];
+    part += pass ? (x - mean) * (x - mean) : x;
+  }
+  const double t = block_sum_f64(part, red);
+  if (threadIdx.x == 0) atomicAdd(pass ? &sc->adv_sq : &sc->adv_sum, t);
+}
+
+struct ActorLoss {
+  LossCommon lc;
+  const int32_t* action;
+  const float* logp_old;
+  const float* adv;
+  // returns dL/dlogits in dl; adds this sample's terms to st[0..4]
+  __device__ __forceinline__ void operator()(int64_t s, const float out[kActions], float dl[kActions], float st[5]) const {
+    const int64_t row = s / lc.A;
+    const int a = (int)(s - row * lc.A);
+    const int64_t src = (int64_t)lc.rows[row] * lc.A + a;
+    const int act = action[src];
+    float m = out[0];
+#pragma unroll
+    for (int k = 1; k < kActions; ++k) m = fmaxf(m, out[k]);
+    float se = 0.f;
+#pragma unroll
+    for (int k = 0; k < kActions; ++k) se += expf(out[k] - m);
+    const float lse = m + logf(se);
+    float lp[kActions], p[kActions], ent = 0.f, logp_new = 0.f;
+#pragma unroll
+    for (int k = 0; k < kActions; ++k) {
+      lp[k] = out[k] - lse;
+      p[k] = expf(lp[k]);
+      ent -= p[k] * lp[k];
+      logp_new = (k == act) ? lp[k] : logp_new;
+    }
+    float advn = adv[src];
+    if (lc.normalize) {
+      const double B = (double)lc.rows_mb * lc.A;
+      const float mean = (float)(lc.sc->adv_sum / B);
+      const float rstd = (float)(1.0 / (sqrt(lc.sc->adv_sq / B) + 1e-8));
+      advn = (advn - mean) * rstd;
+    }
+    const float log_ratio = logp_new - logp_old[src];
+    const float ratio = expf(log_ratio);
+    const float rc = fminf(fmaxf(ratio, 1.0f - lc.clip_eps), 1.0f + lc.clip_eps);
+    const float s1 = ratio * advn, s2 = rc * advn;
+    st[0] += -fminf(s1, s2) * lc.inv_B;
+    st[2] += ent * lc.inv_B;
+    st[3] += ((ratio - 1.0f) - log_ratio) * lc.inv_B;
+    st[4] += (fabsf(ratio - 1.0f) > lc.clip_eps ? 1.0f : 0.0f) * lc.inv_B;
+    const float dlogp = (s1 <= s2) ? -(advn * ratio) * lc.inv_B : 0.0f;
+    const float ec = lc.ent_coef * lc.inv_B;
+#pragma unroll
+    for (int k = 0; k < kActions; ++k) dl[k] = dlogp * ((k == act ? 1.0f : 0.0f) - p[k]) + ec * p[k] * (lp[k] + ent);
+  }
+};
+
+struct CriticLoss {
+  LossCommon lc;
+  const float* ret;
+  const float* v_old;
+  int per_row;  // samples of the trajectory that share this prediction: A (central critic) or 1
+  __device__ __forceinline__ float term(float v, float r, float vo, float* loss) const {
+    const float e = v - r;
+    float l = 0.5f * e * e, g = e;
+    if (lc.clip_value) {
+      const float dvv = v - vo;
+      const float vc = vo + fminf(fmaxf(dvv, -lc.clip_eps), lc.clip_eps);
+      const float ec = vc - r, lcl = 0.5f * ec * ec;
+      if (lcl > l) {
+        l = lcl;
+        g = (dvv > -lc.clip_eps && dvv < lc.clip_eps) ? ec : 0.0f;
+      }
+    }
+    *loss += l * lc.inv_B;
+    return g;
+  }
+  __device__ __forceinline__ void operator()(int64_t s, const float out[1], float dl[1], float st[5]) const {
+    float g = 0.f;
+    if (per_row == 1) {
+      const int64_t row = s / lc.A;
+      const int a = (int)(s - row * lc.A);
+      const int64_t src = (int64_t)lc.rows[row] * lc.A + a;
+      g = term(out[0], ret[src], v_old[src], &st[1]);
+    } else {
+      const int64_t src0 = (int64_t)lc.rows[s] * lc.A;
+      for (int a = 0; a < lc.A; ++a) g += term(out[0], ret[src0 + a], v_old[src0 + a], &st[1]);
+    }
+    dl[0] = g * lc.vf_coef * lc.inv_B;
+  }
+};
+
+// Output layer + loss + gradient of the output layer.  Persistent over tiles of 64 samples so that the
+// W3 / b3 gradient and the loss statistics leave each workgroup once.
+template <int NOUT, class LossFn>
+__global__ void __launch_bounds__(256) loss_head_kernel(const float* __restrict__ H2, int64_t S, int H,
+                                                        const float* __restrict__ W3, const float* __restrict__ b3,
+                                                        LossFn fn, float* __restrict__ dl_out,
+                                                        float* __restrict__ gW3, float* __restrict__ gb3,
+                                                        Scalars* sc, float b3_bias_unused) {
+  __shared__ HeadLds L;
+  __shared__ float dls[kHeadTile * NOUT];
+  const int tid = threadIdx.x;
+  const int nchunks = (H + kHeadChunk - 1) / kHeadChunk;  // <= 4
+  float gw[4][NOUT];
+#pragma unroll
+  for (int c = 0; c < 4; ++c)
+#pragma unroll
+    for (int k = 0; k < NOUT; ++k) gw[c][k] = 0.f;
+  float gb[NOUT];
+#pragma unroll
+  for (int k = 0; k < NOUT; ++k) gb[k] = 0.f;
+  float st[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
+  float bias[NOUT];
+#pragma unroll
+  for (int k = 0; k < NOUT; ++k) bias[k] = b3[k];
+
+  const int64_t ntiles = (S + kHeadTile - 1) / kHeadTile;
+  for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    const int64_t s0 = tile * kHeadTile;
+    float out[NOUT];
+    head_tile<NOUT>(H2, s0, S, H, W3, L, out);
+    if (tid < kHeadTile) {
+      float dl[NOUT];
+#pragma unroll
+      for (int k = 0; k < NOUT; ++k) dl[k] = 0.f;
+      const int64_t s = s0 + tid;
+      if (s < S) {
+#pragma unroll
+        for (int k = 0; k < NOUT; ++k) out[k] += bias[k];
+        fn(s, out, dl, st);
+#pragma unroll
+        for (int k = 0; k < NOUT; ++k) {
+          dl_out[s * NOUT + k] = dl[k];
+          gb[k] += dl[k];
+        }
+      }
+#pragma unroll
+      for (int k = 0; k < NOUT; ++k) dls[tid * NOUT + k] = dl[k];
+    }
+    __syncthreads();
+    // gW3[i][k] += sum_s H2[s][i] * dl[s][k]; thread -> hidden unit i = tid % 128 of each chunk, half of the samples
+    const int i = tid & (kHeadChunk - 1), half = tid >> 7;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      if (c < nchunks) {
+        const int h0 = c * kHeadChunk, hc = min(kHeadChunk, H - h0);
+        if (nchunks > 1) {  // the tile in LDS holds the last chunk only: stage chunk c again
+          __syncthreads();
+          for (int r = tid >> 6; r < kHeadTile; r += 4) {
+            const int64_t s = s0 + r;
+            for (int cc = tid & 63; cc < hc; cc += 64) L.tile[r * (kHeadChunk + 1) + cc] = s < S ? H2[s * H + h0 + cc] : 0.f;
+          }
+          __syncthreads();
+        }
+        if (i < hc) {
+          for (int s = half * 32; s < half * 32 + 32; ++s) {
+            const float h = L.tile[s * (kHeadChunk + 1) + i];
+#pragma unroll
+            for (int k = 0; k < NOUT; ++k) gw[c][k] = fmaf(h, dls[s * NOUT + k], gw[c][k]);
+          }
+        }
+      }
+    }
+  }
+  // flush
+  const int i = tid & (kHeadChunk - 1);
+#pragma unroll
+  for (int c = 0; c < 4; ++c)
+    if (c < nchunks && c * kHeadChunk + i < H) {
+#pragma unroll
+      for (int k = 0; k < NOUT; ++k) atomicAdd(&gW3[(int64_t)(c * kHeadChunk + i) * NOUT + k], gw[c][k]);
+    }
+  if (tid < kHeadTile) {  // one wavefront: reduce across its lanes, lane 0 adds
+#pragma unroll
+    for (int k = 0; k < NOUT; ++k) {
+      float v = gb[k];
+      for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+      if (tid == 0) atomicAdd(&gb3[k], v);
+    }
+#pragma unroll
+    for (int k = 0; k < 5; ++k) {
+      float v = st[k];
+      for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+      if (tid == 0 && v != 0.f) atomicAdd(&sc->acc[k], v);
+    }
+  }
+}
+
+// In place: H2[s][j] <- (sum_k dl[s][k] W3[j][k]) * (1 - H2[s][j]^2); column sums -> gb2.
+template <int NOUT>
+__global__ void __launch_bounds__(256) dz2_kernel(float* __restrict__ H2, const float* __restrict__ dl,
+                                                  const float* __restrict__ W3, float* __restrict__ gb2, int64_t S,
+                                                  int H, int cb, int rows_per_block, int round_bf16) {
+  __shared__ float red[256];
+  const int tid = threadIdx.x;
+  const int rg_count = 256 / cb;
+  const int rg = tid / cb, jl = tid - rg * cb;
+  const int j = blockIdx.y * cb + jl;
+  const bool on = rg < rg_count && j < H;
+  float w[NOUT];
+#pragma unroll
+  for (int k = 0; k < NOUT; ++k) w[k] = on ? W3[(int64_t)j * NOUT + k] : 0.f;
+  const int64_t r0 = (int64_t)blockIdx.x * rows_per_block;
+  const int64_t r1 = min(S, r0 + rows_per_block);
+  float csum = 0.f;
+  if (on) {
+    for (int64_t r = r0 + rg; r < r1; r += rg_count) {
+      float g = 0.f;
+#pragma unroll
+      for (int k = 0; k < NOUT; ++k) g = fmaf(dl[r * NOUT + k], w[k], g);
+      const float h = H2[r * H + j];
+      float v = g * (1.0f - h * h);
+      if (round_bf16) v = round_to_bf16(v);
+      H2[r * H + j] = v;
+      csum += v;
+    }
+  }
+  red[tid] = on ? csum : 0.f;
+  __syncthreads();
+  if (tid < cb && j < H) {
+    float t = 0.f;
+    for (int g2 = 0; g2 < rg_count; ++g2) t += red[g2 * cb + tid];
+    atomicAdd(&gb2[j], t);
+  }
+}
+
+__global__ void __launch_bounds__(256) grad_norm_kernel(const float* __restrict__ grad, int64_t P, Scalars* sc) {
+  __shared__ double red[4];
+  double part = 0;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < P; i += (int64_t)gridDim.x * blockDim.x) {
+    const double g = grad[i];
+    part += g * g;
+  }
+  const double t = block_sum_f64(part, red);
+  if (threadIdx.x == 0) atomicAdd(&sc->acc[5], (float)t);
+}
+
+struct AdamArgs {
+  float lr, b1, b2, eps, bc1, bc2, max_norm, ent_coef, vf_coef;
+};
+
+__global__ void __launch_bounds__(256) adam_kernel(float* __restrict__ params, float* __restrict__ m,
+                                                   float* __restrict__ v, const float* __restrict__ grad, int64_t P,
+                                                   AdamArgs a, const Scalars* sc, float* __restrict__ stats_row,
+                                                   float* __restrict__ grad_dump) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const float norm = sqrtf(sc->acc[5]);
+  const float scale = a.max_norm > 0.f ? a.max_norm / fmaxf(norm, a.max_norm) : 1.0f;
+  if (i < P) {
+    const float g = grad[i] * scale;
+    const float mi = a.b1 * m[i] + (1.0f - a.b1) * g;
+    const float vi = a.b2 * v[i] + (1.0f - a.b2) * g * g;
+    m[i] = mi;
+    v[i] = vi;
+    params[i] -= a.lr * (mi / a.bc1) / (sqrtf(vi / a.bc2) + a.eps);
+    if (grad_dump) grad_dump[i] = g;
+  }
+  if (i == 0) {
+    const float total = sc->acc[0] - a.ent_coef * sc->acc[2] + a.vf_coef * sc->acc[1];
+    stats_row[0] = sc->acc[0];
+    stats_row[1] = sc->acc[1];
+    stats_row[2] = sc->acc[2];
+    stats_row[3] = sc->acc[3];
+    stats_row[4] = sc->acc[4];
+    stats_row[5] = norm;
+    stats_row[6] = total;
+    stats_row[7] = (isfinite(total) && isfinite(norm)) ? 0.f : 1.f;
+  }
+}
+
+struct UpdateWsView {
+  float *eff_params, *grad;
+  Scalars* sc;
+  int32_t* ident;
+  float *h1a, *h2a, *dz1a, *dla;
+  float *h1c, *h2c, *dz1c, *dlc;
+};
+
+int64_t align256(int64_t x) { return (x + 255) & ~(int64_t)255; }
+
+UpdateWsView carve_update_ws(const marl_config& c, void* ws, int64_t* total) {
+  const Dims d = dims_of(c);
+  const int64_t R = (int64_t)d.T * d.N, rows_mb = R / c.n_minibatches;
+  const int64_t Sa = rows_mb * d.A, Sc = d.central ? rows_mb : Sa;
+  char* p = static_cast<char*>(ws);
+  int64_t off = 0;
+  auto take = [&](int64_t bytes) {
+    char* r = p + off;
+    off += align256(bytes);
+    return r;
+  };
+  UpdateWsView v;
+  v.eff_params = (float*)take(d.P * 4);
+  v.grad = (float*)take(d.P * 4);
+  v.sc = (Scalars*)take(sizeof(Scalars));
+  v.ident = (int32_t*)take(R * 4);
+  v.h1a = (float*)take(Sa * d.Ha * 4);
+  v.h2a = (float*)take(Sa * d.Ha * 4);
+  v.dz1a = (float*)take(Sa * d.Ha * 4);
+  v.dla = (float*)take(Sa * kActions * 4);
+  v.h1c = (float*)take(Sc * d.Hc * 4);
+  v.h2c = (float*)take(Sc * d.Hc * 4);
+  v.dz1c = (float*)take(Sc * d.Hc * 4);
+  v.dlc = (float*)take(Sc * 4);
+  if (total) *total = off;
+  return v;
+}
+
+int64_t pick_k_split(int64_t K, int64_t tiles_mn) {
+  // enough workgroups for ~4 per CU, each with a k range that is a multiple of the k tile
+  int64_t want = std::max<int64_t>(1, 1024 / std::max<int64_t>(1, tiles_mn));
+  int64_t per = (K + want - 1) / want;
+  per = std::max<int64_t>(256, ((per + kGemmBK - 1) / kGemmBK) * kGemmBK);
+  return per;
+}
+
+// Backward through one network given dL/d(output layer) in dl; h2 is overwritten by dz2.
+template <int NOUT>
+void mlp_backward(const RowSrc& X, int64_t S, int Din, int H, const float* W2, const float* W3, float* h1, float* h2,
+                  float* dz1, const float* dl, float* gW1, float* gb1, float* gW2, float* gb2, bool bf16,
+                  hipStream_t s) {
+  {
+    const int cb = std::min(H, 256), rpb = 256;
+    dim3 grid((unsigned)((S + rpb - 1) / rpb), (unsigned)((H + cb - 1) / cb));
+    hipLaunchKernelGGL(dz2_kernel<NOUT>, grid, dim3(256), 0, s, h2, dl, W3, gb2, S, H, cb, rpb, (int)bf16);
+  }
+  {  // gW2 += h1^T dz2
+    GemmArgs g{};
+    g.A = RowSrc{h1, H, nullptr, 1, S}; g.B = h2; g.ldb = H; g.C = gW2; g.ldc = H;
+    g.M = H; g.N = H; g.K = S;
+    g.k_per_split = pick_k_split(S, ((H + 127) / 128) * ((H + 127) / 128));
+    launch_gemm<GEMM_TN, EPI_ATOMIC_ADD>(g, s);
+  }
+  {  // dz1 = (dz2 W2^T) * (1 - h1^2), gb1 += column sums
+    GemmArgs g{};
+    g.A = RowSrc{h2, H, nullptr, 1, S}; g.B = W2; g.ldb = H; g.C = dz1; g.ldc = H;
+    g.aux_mat = h1; g.ldaux = H; g.colsum = gb1;
+    g.M = S; g.N = H; g.K = H; g.round_bf16 = bf16;
+    launch_gemm<GEMM_NT, EPI_DTANH>(g, s);
+  }
+  {  // gW1 += X^T dz1
+    GemmArgs g{};
+    g.A = X; g.B = dz1; g.ldb = H; g.C = gW1; g.ldc = H;
+    g.M = Din; g.N = H; g.K = S;
+    g.k_per_split = pick_k_split(S, ((Din + 127) / 128) * ((H + 127) / 128));
+    launch_gemm<GEMM_TN, EPI_ATOMIC_ADD>(g, s);
+  }
+}
+
+}  // namespace
+
+int64_t update_workspace_bytes(const marl_config& c) {
+  int64_t total = 0;
+  carve_update_ws(c, nullptr, &total);
+  return total;
+}
+
+int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, float* adam_m, float* adam_v,
+                          int64_t adam_step0, const int32_t* perm, float* stats, float* grad_dump, void* workspace,
+                          hipStream_t s) {
+  const Dims d = dims_of(c);
+  const UpdateWsView w = carve_update_ws(c, workspace, nullptr);
+  const int64_t R = (int64_t)d.T * d.N, rows_mb = R / c.n_minibatches;
+  const int64_t Sa = rows_mb * d.A, Sc = d.central ? rows_mb : Sa;
+  if (perm == nullptr)
+    hipLaunchKernelGGL(iota_kernel, dim3((unsigned)((R + 255) / 256)), dim3(256), 0, s, w.ident, R);
+  const NetOffsets oa = net_offsets(0, d.D, d.Ha, kActions);
+  const NetOffsets oc = net_offsets(d.Pa, d.Dc, d.Hc, 1);
+  int64_t k = adam_step0;
+  for (int e = 0; e < c.n_epochs; ++e) {
+    for (int mb = 0; mb < c.n_minibatches; ++mb) {
+      const int32_t* rows = (perm ? perm + (int64_t)e * R : w.ident) + (int64_t)mb * rows_mb;
+      const float* eff = effective_params(c, params, w.eff_params, s);
+      hipLaunchKernelGGL(zero_step_kernel, dim3((unsigned)((d.P + 255) / 256)), dim3(256), 0, s, w.grad, d.P, w.sc);
+      LossCommon lc{};
+      lc.rows = rows; lc.A = d.A; lc.rows_mb = rows_mb; lc.inv_B = (float)(1.0 / (double)(rows_mb * d.A));
+      lc.sc = w.sc; lc.normalize = c.normalize_adv; lc.clip_eps = c.clip_eps; lc.ent_coef = c.ent_coef;
+      lc.vf_coef = c.vf_coef; lc.clip_value = c.clip_value;
+      if (c.normalize_adv) {
+        const unsigned nb = (unsigned)std::min<int64_t>(1024, (Sa + 255) / 256);
+        hipLaunchKernelGGL(adv_stats_kernel, dim3(nb), dim3(256), 0, s, tr.adv, lc, w.sc, 0);
+        hipLaunchKernelGGL(adv_stats_kernel, dim3(nb), dim3(256), 0, s, tr.adv, lc, w.sc, 1);
+      }
+      // ---- actor
+      const RowSrc Xa{tr.obs, d.D, rows, d.A, Sa};
+      mlp_hidden_forward(Xa, Sa, d.D, d.Ha, eff + oa.W1, eff + oa.b1, eff + oa.W2, eff + oa.b2, w.h1a, w.h2a, d.bf16, s);
+      {
+        ActorLoss fn{lc, tr.action, tr.logp, tr.adv};
+        const unsigned nb = (unsigned)std::min<int64_t>(2048, (Sa + kHeadTile - 1) / kHeadTile);
+        hipLaunchKernelGGL((loss_head_kernel<kActions, ActorLoss>), dim3(nb), dim3(256), 0, s, w.h2a, Sa, d.Ha,
+                           eff + oa.W3, eff + oa.b3, fn, w.dla, w.grad + oa.W3, w.grad + oa.b3, w.sc, 0.f);
+      }
+      mlp_backward<kActions>(Xa, Sa, d.D, d.Ha, eff + oa.W2, eff + oa.W3, w.h1a, w.h2a, w.dz1a, w.dla, w.grad + oa.W1,
+                             w.grad + oa.b1, w.grad + oa.W2, w.grad + oa.b2, d.bf16, s);
+      // ---- critic
+      const RowSrc Xc{tr.obs, d.Dc, rows, d.central ? 1 : d.A, Sc};
+      mlp_hidden_forward(Xc, Sc, d.Dc, d.Hc, eff + oc.W1, eff + oc.b1, eff + oc.W2, eff + oc.b2, w.h1c, w.h2c, d.bf16, s);
+      {
+        CriticLoss fn{lc, tr.ret, tr.value, d.central ? d.A : 1};
+        const unsigned nb = (unsigned)std::min<int64_t>(2048, (Sc + kHeadTile - 1) / kHeadTile);
+        hipLaunchKernelGGL((loss_head_kernel<1, CriticLoss>), dim3(nb), dim3(256), 0, s, w.h2c, Sc, d.Hc, eff + oc.W3,
+                           eff + oc.b3, fn, w.dlc, w.grad + oc.W3, w.grad + oc.b3, w.sc, 0.f);
+      }
+      mlp_backward<1>(Xc, Sc, d.Dc, d.Hc, eff + oc.W2, eff + oc.W3, w.h1c, w.h2c, w.dz1c, w.dlc, w.grad + oc.W1,
+                      w.grad + oc.b1, w.grad + oc.W2, w.grad + oc.b2, d.bf16, s);
+      // ---- clip + Adam
+      hipLaunchKernelGGL(grad_norm_kernel, dim3((unsigned)std::min<int64_t>(256, (d.P + 255) / 256)), dim3(256), 0, s,
+                         w.grad, d.P, w.sc);
+      ++k;
+      AdamArgs a;
+      a.lr = c.lr; a.b1 = c.beta1; a.b2 = c.beta2; a.eps = c.adam_eps;
+      a.bc1 = (float)(1.0 - std::pow((double)c.beta1, (double)k));
+      a.bc2 = (float)(1.0 - std::pow((double)c.beta2, (double)k));
+      a.max_norm = c.max_grad_norm; a.ent_coef = c.ent_coef; a.vf_coef = c.vf_coef;
+      const bool last = (e == c.n_epochs - 1 && mb == c.n_minibatches - 1);
+      hipLaunchKernelGGL(adam_kernel, dim3((unsigned)((d.P + 255) / 256)), dim3(256), 0, s, params, adam_m, adam_v,
+                         w.grad, d.P, a, w.sc, stats + (int64_t)(e * c.n_minibatches + mb) * MARL_N_STATS,
+                         (last ? grad_dump : nullptr));
+      const int32_t rc = launch_status();
+      if (rc != MARL_OK) return rc;
+    }
+  }
+  return MARL_OK;
+}
+
+}  // namespace marl

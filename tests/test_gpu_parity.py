@@ -1,0 +1,279 @@
+"""HIP path vs CPU oracle, element by element, through the C ABI.  Needs a real MI355X."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from gpu_util import REL_TOL, dev, err, load_traj, rel_err, small
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def M():
+    import paper_2107_01460_amd as m
+    assert torch.cuda.is_available()
+    m.lib()
+    return m
+
+
+def assert_state_equal(M, gstate, ostate):
+    host = gstate.to_host()
+    for f in M.EnvState.FIELDS:
+        assert np.array_equal(host[f], getattr(ostate, f)), f
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 5])
+def test_env_reset_step_observe_bit_exact(M, orc, k):
+    cfg = small(k, n_envs={1: 70, 2: 333, 3: 200, 4: 77, 5: 1000}[k], n_minibatches=1,
+                episode_cap={1: 25, 2: 50, 3: 15, 4: 12, 5: 25}[k])
+    N, A, D = cfg["n_envs"], cfg["n_agents"], W.obs_dim(cfg)
+    print("case", cfg["name"], N, flush=True)
+    os_ = orc.EnvState(cfg)
+    orc.env_reset(cfg, os_)
+    gs = M.EnvState(cfg)
+    M.env_reset(cfg, gs)
+    assert_state_equal(M, gs, os_)
+    obs = torch.empty((N, A, D), device="cuda")
+    M.observe(cfg, gs, obs)
+    assert np.array_equal(obs.cpu().numpy(), orc.observe(cfg, os_))
+    steps = 60
+    acts = W.random_actions(cfg, steps, seed=k, p_load=0.35)
+    reward = torch.empty((N, A), device="cuda")
+    done = torch.empty((N,), dtype=torch.uint8, device="cuda")
+    n_done = 0
+    rsum = 0.0
+    for t in range(steps):
+        M.env_step(cfg, gs, dev(acts[t]), obs, reward, done)
+        oobs, orew, odone = orc.env_step(cfg, os_, acts[t])
+        assert np.array_equal(done.cpu().numpy(), odone), t
+        assert np.array_equal(reward.cpu().numpy().view(np.uint32), orew.view(np.uint32)), t
+        assert np.array_equal(obs.cpu().numpy(), oobs), t
+        assert_state_equal(M, gs, os_)
+        n_done += int(odone.sum())
+        rsum += float(orew.sum())
+    assert n_done > 0 and rsum > 0     # resets and loads were exercised
+    # obs = NULL is allowed
+    M.env_step(cfg, gs, dev(acts[0]), None, reward, done)
+    orc.env_step(cfg, os_, acts[0], want_obs=False)
+    assert_state_equal(M, gs, os_)
+
+
+def test_env_single_env_and_large_grid(M, orc):
+    cfg = W.scaled(W.CONFIGS[0], grid=40, n_agents=1, n_food=8, max_level=5, view=7, n_envs=1, episode_cap=7)
+    os_, gs = orc.EnvState(cfg), M.EnvState(cfg)
+    orc.env_reset(cfg, os_)
+    M.env_reset(cfg, gs)
+    obs = torch.empty((1, 1, W.obs_dim(cfg)), device="cuda")
+    reward = torch.empty((1, 1), device="cuda")
+    done = torch.empty((1,), dtype=torch.uint8, device="cuda")
+    acts = W.random_actions(cfg, 30, seed=2)
+    for t in range(30):
+        M.env_step(cfg, gs, dev(acts[t]), obs, reward, done)
+        oobs, orew, odone = orc.env_step(cfg, os_, acts[t])
+        assert np.array_equal(obs.cpu().numpy(), oobs) and np.array_equal(done.cpu().numpy(), odone)
+    assert_state_equal(M, gs, os_)
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 5])
+def test_policy_forward(M, orc, k):
+    cfg = small(k)
+    A, D = cfg["n_agents"], W.obs_dim(cfg)
+    rows = 333
+    print("case", cfg["name"], rows, flush=True)
+    params = W.init_params(cfg, bias_scale=0.2)
+    rng = np.random.default_rng(k)
+    obs = (rng.integers(0, 4, size=(rows, A, D)) * (rng.random((rows, A, D)) < 0.3)).astype(np.float32)
+    ws = M.alloc_workspace(M.query_sizes(W.scaled(cfg, n_envs=rows, n_minibatches=1)).rollout_workspace_bytes)
+    logits = torch.empty((rows, A, 6), device="cuda")
+    value = torch.empty((rows, A), device="cuda")
+    M.policy_forward(cfg, dev(params), dev(obs), rows, logits, value, ws)
+    ol, ov = orc.policy_forward(cfg, params, obs)
+    tol = REL_TOL[cfg["precision"]]
+    assert err(logits.cpu().numpy(), ol, cfg) < tol
+    assert err(value.cpu().numpy(), ov, cfg) < tol
+    # either output alone
+    l2 = torch.empty_like(logits)
+    M.policy_forward(cfg, dev(params), dev(obs), rows, l2, None, ws)
+    assert torch.equal(l2, logits)
+
+
+def test_sampling_identical_logits_and_uniforms(M, orc):
+    cfg = small(1)
+    rng = np.random.default_rng(11)
+    n = 50000
+    logits = (rng.normal(size=(n, 6)) * 2).astype(np.float32)
+    u = W.random_uniforms(W.scaled(cfg, n_envs=n // 2), 1, seed=5).reshape(n, 6)
+    action = torch.empty(n, dtype=torch.int32, device="cuda")
+    sampled = torch.empty_like(action)
+    logp = torch.empty(n, device="cuda")
+    M.sample_actions(cfg, dev(logits), dev(u), None, n, 0, action, sampled, logp)
+    oa, osmp, olp, gap = orc.sample(logits, u)
+    mism = action.cpu().numpy() != oa
+    assert np.all(gap[mism] < 1e-5), (mism.sum(), gap[mism].max() if mism.any() else 0)
+    assert mism.mean() < 1e-3
+    ok = ~mism
+    assert rel_err(logp.cpu().numpy()[ok], olp[ok]) < 1e-4
+    assert torch.equal(action, sampled)
+    # forced actions: logp follows the forced action, the draw is still reported
+    forced = rng.integers(0, 6, size=n).astype(np.int32)
+    M.sample_actions(cfg, dev(logits), dev(u), dev(forced), n, 0, action, sampled, logp)
+    _, _, olp2, _ = orc.sample(logits, u, forced)
+    assert np.array_equal(action.cpu().numpy(), forced)
+    assert rel_err(logp.cpu().numpy(), olp2) < 1e-4
+    # Philox uniforms: same key schedule as the oracle (step, sample = env*A + agent)
+    n2, A = 600, cfg["n_agents"]
+    step = (3 << 32) + 12345
+    M.sample_actions(cfg, dev(logits[:n2]), None, None, n2, step, action[:n2], sampled[:n2], logp[:n2])
+    uu = np.array([orc.sample_uniforms(cfg, step, i // A, i % A) for i in range(n2)])
+    oa3, _, _, gap3 = orc.sample(logits[:n2], uu)
+    mism3 = action[:n2].cpu().numpy() != oa3
+    assert np.all(gap3[mism3] < 1e-5) and mism3.sum() <= 1
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 5])
+def test_rollout_teacher_forced(M, orc, k):
+    cfg = small(k)
+    N, A, T = cfg["n_envs"], cfg["n_agents"], cfg["rollout_len"]
+    print("case", cfg["name"], N, T, flush=True)
+    params = W.init_params(cfg, bias_scale=0.1)
+    os_ = orc.EnvState(cfg)
+    orc.env_reset(cfg, os_)
+    otr = orc.Traj(cfg)
+    orc.rollout(cfg, os_, params, otr, step_offset=1000)
+    gs = M.EnvState(cfg)
+    M.env_reset(cfg, gs)
+    gtr = M.Traj(cfg, debug=True)
+    sizes = M.query_sizes(cfg)
+    ws = M.alloc_workspace(sizes.rollout_workspace_bytes)
+    M.rollout(cfg, gs, dev(params), gtr, 1000, ws, forced_actions=dev(otr.action))
+    torch.cuda.synchronize()
+    tol = REL_TOL[cfg["precision"]]
+    assert np.array_equal(gtr.obs.cpu().numpy(), otr.obs)
+    assert np.array_equal(gtr.reward.cpu().numpy().view(np.uint32), otr.reward.view(np.uint32))
+    assert np.array_equal(gtr.done.cpu().numpy(), otr.done)
+    assert np.array_equal(gtr.action.cpu().numpy(), otr.action)
+    assert_state_equal(M, gs, os_)
+    assert err(gtr.logits.cpu().numpy(), otr.logits, cfg) < tol
+    assert err(gtr.value.cpu().numpy(), otr.value, cfg) < tol
+    assert err(gtr.last_value.cpu().numpy(), otr.last_value, cfg) < tol
+    assert err(gtr.logp.cpu().numpy(), otr.logp, cfg) < tol
+    if cfg["precision"] == 0:
+        # the sampler's own draw: equal to the oracle's except at near-ties of the perturbed logits
+        mism = gtr.sampled.cpu().numpy() != otr.sampled
+        lim = 1e-5 + 2e-4 * np.abs(otr.logits).max()   # logits themselves differ by up to tol
+        assert np.all(otr.gap[mism] < lim), (mism.sum(), otr.gap[mism].max())
+        assert mism.mean() < 5e-3
+    # free-running (unforced) rollout with forced uniforms equal to the oracle's Philox stream must
+    # reproduce the forced run wherever the draw agreed
+    assert otr.done.sum() > 0
+
+
+@pytest.mark.parametrize("k", [1, 3, 5])
+def test_gae(M, orc, k):
+    cfg = small(k, n_envs=300, rollout_len=37, n_minibatches=1)
+    rng = np.random.default_rng(k)
+    otr = orc.Traj(cfg)
+    otr.reward[:] = rng.random(otr.reward.shape) * (rng.random(otr.reward.shape) < 0.2)
+    otr.value[:] = rng.normal(size=otr.value.shape)
+    otr.last_value[:] = rng.normal(size=otr.last_value.shape)
+    otr.done[:] = rng.random(otr.done.shape) < 0.1
+    orc.compute_gae(cfg, otr)
+    gtr = load_traj(M, cfg, otr)
+    gtr.adv.zero_()
+    gtr.ret.zero_()
+    M.compute_gae(cfg, gtr)
+    assert rel_err(gtr.adv.cpu().numpy(), otr.adv) < 1e-4
+    assert rel_err(gtr.ret.cpu().numpy(), otr.ret) < 1e-4
+
+
+def oracle_traj(orc, cfg, bias_scale=0.1):
+    params = W.init_params(cfg, bias_scale=bias_scale)
+    s = orc.EnvState(cfg)
+    orc.env_reset(cfg, s)
+    tr = orc.Traj(cfg)
+    orc.rollout(cfg, s, params, tr, step_offset=5)
+    orc.compute_gae(cfg, tr)
+    return params, tr
+
+
+@pytest.mark.parametrize("k,clipv,norm", [(1, 0, 1), (2, 0, 1), (3, 0, 1), (4, 0, 1), (5, 0, 1), (2, 1, 0), (3, 1, 1)])
+def test_ppo_single_minibatch_gradient(M, orc, k, clipv, norm):
+    """One minibatch over the whole (small) trajectory at perturbed parameters: loss terms and gradient."""
+    cfg = small(k, n_epochs=1, n_minibatches=1, clip_value=clipv, normalize_adv=norm, max_grad_norm=0.0)
+    print("case", cfg["name"], flush=True)
+    params0, otr = oracle_traj(orc, cfg)
+    rng = np.random.default_rng(100 + k)
+    params = (params0 + 0.1 * np.abs(params0).mean() * rng.normal(size=params0.size)).astype(np.float32)
+    otr.value[:] += (0.2 * rng.normal(size=otr.value.shape)).astype(np.float32)
+    # ratios on both sides of the clip range, but well away from its edges: the branch of the min is a
+    # discrete decision that a rounding error must not flip (in bf16 the ratio carries ~1% noise)
+    otr.logp[:] += rng.choice([-0.4, 0.0, 0.0, 0.4], size=otr.logp.shape).astype(np.float32)
+    R = cfg["rollout_len"] * cfg["n_envs"]
+    perm = W.make_perm(cfg, seed=3)
+    po, mo, vo = params.copy(), np.zeros_like(params), np.zeros_like(params)
+    ostats, ograd = orc.ppo_update(cfg, otr, po, mo, vo, adam_step0=0, perm=perm)
+    gtr = load_traj(M, cfg, otr)
+    sizes = M.query_sizes(cfg)
+    ws = M.alloc_workspace(sizes.update_workspace_bytes)
+    gp, gm, gv = dev(params), torch.zeros(params.size, device="cuda"), torch.zeros(params.size, device="cuda")
+    stats = torch.zeros((1, 8), device="cuda")
+    gdump = torch.zeros(params.size, device="cuda")
+    M.ppo_update(cfg, gtr, gp, gm, gv, 0, dev(perm), stats, gdump, ws)
+    torch.cuda.synchronize()
+    tol = REL_TOL[cfg["precision"]]
+    g = gdump.cpu().numpy()
+    Pa = orc.actor_param_count(cfg)
+    assert err(g[:Pa], ograd[:Pa], cfg) < tol, "actor gradient"
+    assert err(g[Pa:], ograd[Pa:], cfg) < tol, "critic gradient"
+    st = stats.cpu().numpy()[0]
+    assert 0.0 < ostats[0, 4] < 1.0           # clip fraction: both branches of the min are exercised
+    for i in (0, 1, 2, 3, 5, 6):
+        assert abs(st[i] - ostats[0, i]) < tol * max(abs(ostats[0, i]), 1e-2), (i, st[i], ostats[0, i])
+    assert abs(st[4] - ostats[0, 4]) < 3.0 / (R * cfg["n_agents"])   # a ratio sitting on the clip edge may flip
+    assert st[7] == 0
+    # Adam: the oracle's optimiser step applied to the GPU's own gradient must land on the GPU's parameters
+    # (the step normalises by |g|, so feeding it two gradients that differ by 1e-4 of their scale would not)
+    pa, ma, va = params.copy(), np.zeros_like(params), np.zeros_like(params)
+    orc.adam_step(cfg, pa, ma, va, g.astype(np.float64), 1)
+    assert rel_err(gm.cpu().numpy(), ma) < 1e-5 and rel_err(gv.cpu().numpy(), va) < 1e-5
+    assert rel_err(gp.cpu().numpy() - params, pa - params) < 1e-3   # fp32 rounding of p - delta
+    assert np.abs(pa - params).max() > 0.5 * cfg["lr"]
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 5])
+def test_ppo_update_epochs_and_minibatches(M, orc, k):
+    cfg = small(k)
+    print("case", cfg["name"], flush=True)
+    params, otr = oracle_traj(orc, cfg)
+    perm = W.make_perm(cfg, seed=9)
+    E, Mb = cfg["n_epochs"], cfg["n_minibatches"]
+    po, mo, vo = params.copy(), np.zeros_like(params), np.zeros_like(params)
+    ostats, ograd = orc.ppo_update(cfg, otr, po, mo, vo, adam_step0=3, perm=perm)
+    gtr = load_traj(M, cfg, otr)
+    ws = M.alloc_workspace(M.query_sizes(cfg).update_workspace_bytes)
+    gp, gm, gv = dev(params), torch.zeros(params.size, device="cuda"), torch.zeros(params.size, device="cuda")
+    stats = torch.zeros((E * Mb, 8), device="cuda")
+    gdump = torch.zeros(params.size, device="cuda")
+    M.ppo_update(cfg, gtr, gp, gm, gv, 3, dev(perm), stats, gdump, ws)
+    torch.cuda.synchronize()
+    tol = REL_TOL[cfg["precision"]]
+    st = stats.cpu().numpy()
+    for i in (0, 1, 2, 5, 6):
+        assert np.all(np.abs(st[:, i] - ostats[:, i]) < 20 * tol * np.maximum(np.abs(ostats[:, i]), 1e-2)), (i, st[:, i], ostats[:, i])
+    assert np.all(st[:, 7] == 0)
+    # after E*M optimiser steps the two parameter vectors have moved the same way.  Adam divides by |g|,
+    # which magnifies the 1e-4 gradient differences of near-zero elements, so the bound is on the scale of
+    # the largest move; the per-step statistics above are the tight check of the loop itself.
+    # (bf16: the sign of a near-zero gradient element decides a full +-lr step, so only the gradient is compared)
+    if cfg["precision"] == 0:
+        assert rel_err(gp.cpu().numpy() - params, po - params, floor=1.0) < 0.05
+    assert err(gdump.cpu().numpy(), ograd, cfg) < (100 * tol if cfg["precision"] == 0 else 5 * tol)
+    # identity order when perm is NULL
+    gp2, gm2, gv2 = dev(params), torch.zeros_like(gm), torch.zeros_like(gm)
+    M.ppo_update(cfg, gtr, gp2, gm2, gv2, 3, None, stats, None, ws)
+    R = cfg["rollout_len"] * cfg["n_envs"]
+    po2, mo2, vo2 = params.copy(), np.zeros_like(params), np.zeros_like(params)
+    orc.ppo_update(cfg, otr, po2, mo2, vo2, adam_step0=3, perm=None)
+    if cfg["precision"] == 0:
+        assert rel_err(gp2.cpu().numpy() - params, po2 - params, floor=1.0) < 0.05
