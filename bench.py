@@ -1,0 +1,153 @@
+"""Throughput of the fused multi-agent PPO training step on one MI355X.
+
+A step = rollout (T env steps of N envs with policy inference and sampling) + GAE + PPO update
+(E epochs x M minibatches) on synthetic, seeded inputs that are resident in HBM before the timed region.
+Prints one JSON line: env-agent steps per second, the roofline figures of the dominant kernel measured
+live with HIP events, and the CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+# env-agent steps the CPU oracle is timed on: envs of the same config with full T, A, networks, E and M
+ORACLE_SAMPLE_ENVS = {1: 64, 2: 32, 3: 16, 4: 1, 5: 1024}
+PEAK = {"mfma_f32": 157.3, "mfma_bf16": 2500.0, "hbm": 8000.0}   # TFLOP/s, TFLOP/s, GB/s
+
+
+def gemm_flops_per_step(cfg, W):
+    """Algorithmic MLP flops of one training step (hidden-layer GEMMs only, forward and backward)."""
+    D, A, T, N = W.obs_dim(cfg), cfg["n_agents"], cfg["rollout_len"], cfg["n_envs"]
+    Ha, Hc, Dc = cfg["actor_hidden"], cfg["critic_hidden"], W.critic_in_dim(cfg)
+    S = N * A * T
+    Sc = N * T if cfg["central_critic"] else S
+    fwd_a, fwd_c = 2 * (D * Ha + Ha * Ha), 2 * (Dc * Hc + Hc * Hc)
+    roll = S * fwd_a + (Sc + Sc // T) * fwd_c
+    # update: forward + (dW2, dZ1, dW1) backward GEMMs = 2DH + 2HH + 2HH + 2HH + 2DH per sample and epoch
+    upd = cfg["n_epochs"] * (S * (2 * fwd_a + 2 * Ha * Ha) + Sc * (2 * fwd_c + 2 * Hc * Hc))
+    return roll + upd
+
+
+def run_cpu_baseline(cfg_id, cfg, W):
+    import oracle as orc
+    n_o = min(cfg["n_envs"], ORACLE_SAMPLE_ENVS[cfg_id])
+    c = W.scaled(cfg, n_envs=n_o)
+    params = W.init_params(c)
+    perm = W.make_perm(c)
+    s = orc.EnvState(c)
+    orc.env_reset(c, s)
+    tr = orc.Traj(c)
+    m, v = np.zeros_like(params), np.zeros_like(params)
+    t0 = time.perf_counter()
+    orc.rollout(c, s, params, tr, 0)
+    orc.compute_gae(c, tr)
+    orc.ppo_update(c, tr, params, m, v, 0, perm)
+    dt = time.perf_counter() - t0
+    steps = n_o * c["n_agents"] * c["rollout_len"]
+    return {"value": steps / dt, "unit": "env-agent steps/s", "cores": 1, "kind": "oracle",
+            "sample": f"{n_o} of {cfg['n_envs']} envs, full T={c['rollout_len']}, A={c['n_agents']}, networks, "
+                      f"E={c['n_epochs']}, M={c['n_minibatches']}; one training step, {dt:.1f} s, g++ -O2 single thread"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=3, help="1-based workload index (default 3: MAPPO 15x15, 16384 envs)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2107_01460_amd as M
+    import workloads as W
+
+    torch.cuda.set_device(0)
+    cfg = W.CONFIGS[args.config - 1]
+    sizes = M.query_sizes(cfg)
+    dev = lambda x: torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    state = M.EnvState(cfg)
+    traj = M.Traj(cfg)
+    params = dev(W.init_params(cfg))
+    adam_m, adam_v = torch.zeros_like(params), torch.zeros_like(params)
+    perm = dev(W.make_perm(cfg))
+    E, Mb = cfg["n_epochs"], cfg["n_minibatches"]
+    stats = torch.zeros((E * Mb, 8), device="cuda")
+    ws_r = M.alloc_workspace(sizes.rollout_workspace_bytes)
+    ws_u = M.alloc_workspace(sizes.update_workspace_bytes)
+    M.env_reset(cfg, state)
+    T = cfg["rollout_len"]
+    it = [0]
+
+    def step():
+        i = it[0]
+        M.rollout(cfg, state, params, traj, i * T, ws_r)
+        M.compute_gae(cfg, traj)
+        M.ppo_update(cfg, traj, params, adam_m, adam_v, i * E * Mb, perm, stats, None, ws_u)
+        it[0] += 1
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    M.timing_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    classes = {}
+    for name, cls in M.KERNEL_CLASSES.items():
+        ms, n, work = M.timing_read(cls)
+        classes[name] = (ms, n, work)
+    M.timing_enable(False)
+    mfma_peak = PEAK["mfma_bf16"] if cfg["precision"] == 1 else PEAK["mfma_f32"]
+
+    def line(name):
+        ms, n, work = classes[name]
+        if n == 0 or ms <= 0:
+            return None
+        if name.startswith("gemm"):
+            a = work / (ms * 1e-3) / 1e12
+            return {"kernel": name, "bound": "mfma", "achieved": a, "peak": mfma_peak, "unit": "TFLOP/s",
+                    "frac": a / mfma_peak, "traffic": None, "launches": n, "avg_us": 1e3 * ms / n,
+                    "share_of_step": ms / (1e3 * dt)}
+        a = work / (ms * 1e-3) / 1e9
+        return {"kernel": name, "bound": "hbm", "achieved": a, "peak": PEAK["hbm"], "unit": "GB/s",
+                "frac": a / PEAK["hbm"], "traffic": None, "launches": n, "avg_us": 1e3 * ms / n,
+                "share_of_step": ms / (1e3 * dt)}
+
+    lines = [l for l in (line(k) for k in M.KERNEL_CLASSES) if l]
+    roofline = max((l for l in lines if l["bound"] == "mfma"), key=lambda l: l["share_of_step"])
+    st = stats.cpu().numpy()
+    assert np.all(np.isfinite(st)) and np.all(st[:, 7] == 0), "non-finite loss"
+
+    S = cfg["n_envs"] * cfg["n_agents"] * T
+    out = {
+        "metric": "env-agent steps/sec (rollout+PPO update) on 1 MI355X",
+        "value": S * args.steps / dt, "unit": "env-agent steps/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": 1e3 * dt / args.steps, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if cfg["precision"] == 1 else "f32", "data": "synthetic",
+        "config": {"workload": cfg["name"], "config_index": args.config, "n_envs": cfg["n_envs"],
+                   "n_agents": cfg["n_agents"], "rollout_len": T, "epochs": E, "minibatches": Mb,
+                   "env_agent_steps_per_step": S,
+                   "mlp_gemm_tflop_per_step": gemm_flops_per_step(cfg, W) / 1e12},
+        "roofline": roofline,
+        "roofline_all": lines,
+    }
+    out["mlp_gemm_tflops_end_to_end"] = out["config"]["mlp_gemm_tflop_per_step"] / (dt / args.steps)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = run_cpu_baseline(args.config, cfg, W)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -167,6 +167,17 @@ int32_t marl_ppo_update(const marl_config* cfg, marl_traj traj, float* params, f
                         int64_t adam_step0, const int32_t* perm, float* stats, float* grad_dump, void* workspace,
                         void* stream);
 
+/* Measurement hook for benchmarks (host state only, not thread-safe).  While enabled, every launch of
+ * the instrumented kernel classes is bracketed by two HIP events recorded on the launch's own stream.
+ * Classes: 0 forward GEMM (activations x weights), 1 backward-data GEMM (gradient x weights^T),
+ * 2 weight-gradient GEMM (activations^T x gradient, split over samples), 3 env step / observe, 4 GAE.
+ * marl_timing_enable(1) clears earlier records; marl_timing_read waits for the class's events and
+ * returns the summed kernel time, the number of launches and the summed algorithmic work (flops for the
+ * GEMMs: 2*M*N*K of the unpadded problem; bytes for env step and GAE).  Errors: MARL_E_NULL, MARL_E_SIZE,
+ * MARL_E_LAUNCH. */
+int32_t marl_timing_enable(int32_t on);
+int32_t marl_timing_read(int32_t kernel_class, double* total_ms, int64_t* launches, double* work);
+
 /* Human-readable name of a status code (static storage, host). */
 const char* marl_status_string(int32_t status);
 

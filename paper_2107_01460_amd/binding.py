@@ -42,7 +42,8 @@ class Sizes(C.Structure):
 
 
 EXPORTS = ("marl_query_sizes", "marl_env_reset", "marl_observe", "marl_env_step", "marl_policy_forward",
-           "marl_sample_actions", "marl_rollout", "marl_compute_gae", "marl_ppo_update", "marl_status_string")
+           "marl_sample_actions", "marl_rollout", "marl_compute_gae", "marl_ppo_update", "marl_timing_enable",
+           "marl_timing_read", "marl_status_string")
 
 _lib = None
 
@@ -65,6 +66,8 @@ def lib():
         L.marl_rollout.argtypes = [cp, EnvStateC, vp, TrajC, C.c_uint64, vp, vp, vp, vp]
         L.marl_compute_gae.argtypes = [cp, TrajC, vp]
         L.marl_ppo_update.argtypes = [cp, TrajC, vp, vp, vp, C.c_int64, vp, vp, vp, vp, vp]
+        L.marl_timing_enable.argtypes = [C.c_int32]
+        L.marl_timing_read.argtypes = [C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)]
         L.marl_status_string.argtypes = [C.c_int32]
         L.marl_status_string.restype = C.c_char_p
         for name in EXPORTS[:-1]:
@@ -201,6 +204,20 @@ def rollout(cfg, state, params, traj, step_offset, workspace, forced_actions=Non
 
 def compute_gae(cfg, traj, stream=None):
     _check(lib().marl_compute_gae(C.byref(make_config(cfg)), traj.c(), _stream(stream)))
+
+
+KERNEL_CLASSES = {"gemm_nn": 0, "gemm_nt": 1, "gemm_tn": 2, "env_step": 3, "gae": 4}
+
+
+def timing_enable(on):
+    _check(lib().marl_timing_enable(1 if on else 0))
+
+
+def timing_read(kernel_class):
+    """(total_ms, launches, work) of one kernel class since timing_enable(True)."""
+    ms, n, w = C.c_double(), C.c_int64(), C.c_double()
+    _check(lib().marl_timing_read(int(kernel_class), C.byref(ms), C.byref(n), C.byref(w)))
+    return ms.value, n.value, w.value
 
 
 def ppo_update(cfg, traj, params, adam_m, adam_v, adam_step0, perm, stats, grad_dump, workspace, stream=None):

@@ -1,7 +1,42 @@
 // C ABI entry points: argument validation on the host, then the launchers.
+#include <vector>
+
 #include "common.h"
 
 namespace marl {
+
+namespace {
+struct TimerState {
+  bool on = false;
+  std::vector<hipEvent_t> pool;       // reused across reads
+  size_t used = 0;
+  struct Pair { int cls; size_t begin, end; double work; };
+  std::vector<Pair> pairs;
+  hipEvent_t get() {
+    if (used == pool.size()) {
+      hipEvent_t e;
+      (void)hipEventCreate(&e);
+      pool.push_back(e);
+    }
+    return pool[used++];
+  }
+};
+TimerState g_timer;
+}  // namespace
+
+bool timing_on() { return g_timer.on; }
+
+TimedLaunch::TimedLaunch(int c, double work, hipStream_t st) : cls(c), s(st), active(g_timer.on) {
+  if (!active) return;
+  const size_t b = g_timer.used;
+  (void)hipEventRecord(g_timer.get(), s);
+  g_timer.pairs.push_back({cls, b, 0, work});
+}
+TimedLaunch::~TimedLaunch() {
+  if (!active) return;
+  g_timer.pairs.back().end = g_timer.used;
+  (void)hipEventRecord(g_timer.get(), s);
+}
 
 int32_t validate_config(const marl_config* c) {
   if (c == nullptr) return MARL_E_NULL;
@@ -157,6 +192,33 @@ int32_t marl_ppo_update(const marl_config* cfg, marl_traj traj, float* params, f
   if (adam_step0 < 0) return MARL_E_SIZE;
   return launch_ppo_update(*cfg, traj, params, adam_m, adam_v, adam_step0, perm, stats, grad_dump, workspace,
                            (hipStream_t)stream);
+}
+
+int32_t marl_timing_enable(int32_t on) {
+  g_timer.on = on != 0;
+  g_timer.used = 0;
+  g_timer.pairs.clear();
+  return MARL_OK;
+}
+
+int32_t marl_timing_read(int32_t kernel_class, double* total_ms, int64_t* launches, double* work) {
+  if (total_ms == nullptr || launches == nullptr || work == nullptr) return MARL_E_NULL;
+  if (kernel_class < 0 || kernel_class >= KC_COUNT) return MARL_E_SIZE;
+  double ms = 0, w = 0;
+  int64_t n = 0;
+  for (const auto& p : g_timer.pairs) {
+    if (p.cls != kernel_class) continue;
+    if (hipEventSynchronize(g_timer.pool[p.end]) != hipSuccess) return MARL_E_LAUNCH;
+    float t = 0.f;
+    if (hipEventElapsedTime(&t, g_timer.pool[p.begin], g_timer.pool[p.end]) != hipSuccess) return MARL_E_LAUNCH;
+    ms += t;
+    w += p.work;
+    ++n;
+  }
+  *total_ms = ms;
+  *launches = n;
+  *work = w;
+  return MARL_OK;
 }
 
 const char* marl_status_string(int32_t status) {

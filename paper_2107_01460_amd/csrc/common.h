@@ -82,6 +82,19 @@ __device__ __forceinline__ uint32_t rand_below(uint32_t x, uint32_t n) { return 
 __device__ __forceinline__ float rand_unit(uint32_t x) { return ((float)(x >> 9) + 0.5f) * (1.0f / 8388608.0f); }
 constexpr uint32_t kStreamReset = 1, kStreamSample = 2;
 
+// ---- optional per-kernel timing with HIP events (measurement hook, host side) -----------------
+enum KernelClass { KC_GEMM_NN = 0, KC_GEMM_NT = 1, KC_GEMM_TN = 2, KC_ENV_STEP = 3, KC_GAE = 4, KC_HEAD = 5, KC_COUNT = 6 };
+bool timing_on();
+// Records an event on `s` before and after the launch bracketed by the guard's lifetime and books
+// `work` (flops or bytes) to the class.
+struct TimedLaunch {
+  int cls;
+  hipStream_t s;
+  bool active;
+  TimedLaunch(int cls, double work, hipStream_t s);
+  ~TimedLaunch();
+};
+
 // ---- launchers implemented in the kernel translation units ------------------------------------
 int32_t launch_env_reset(const marl_config& c, marl_env_state st, hipStream_t s);
 // do_step = false: only observe.  actions/reward/done may be null then.

@@ -305,6 +305,11 @@ int32_t launch_env_step(const marl_config& c, marl_env_state st, const int32_t* 
   int threads = ((epb * p.A + 63) / 64) * 64;
   const size_t lds = lds_bytes(epb);
   const dim3 grid((p.N + epb - 1) / epb), block(threads);
+  // algorithmic bytes of one transition: observation, reward, action per agent; done and the state (read + write) per env
+  const double D = 3.0 * c.view * c.view;
+  const double bytes = do_step ? (double)p.N * (p.A * (4.0 * D * (obs ? 1 : 0) + 8.0) + 1.0 + 2.0 * (3.0 * p.A + 4.0 * p.F + 8.0))
+                               : (double)p.N * p.A * 4.0 * D;
+  TimedLaunch timed(KC_ENV_STEP, bytes, s);
   switch (c.view) {
     case 3: hipLaunchKernelGGL(env_step_kernel<3>, grid, block, lds, s, p, st, actions, obs, reward, done, epb, (int)do_step); break;
     case 5: hipLaunchKernelGGL(env_step_kernel<5>, grid, block, lds, s, p, st, actions, obs, reward, done, epb, (int)do_step); break;

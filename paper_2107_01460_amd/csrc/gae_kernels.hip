@@ -52,6 +52,8 @@ int32_t launch_gae(const marl_config& c, marl_traj tr, hipStream_t s) {
   const Dims d = dims_of(c);
   const int threads = d.NA >= 256 * 1024 ? 256 : 64;
   const int64_t blocks = (d.NA + threads - 1) / threads;
+  // reward, value read; adv, ret written (4 B each per env-agent step); done 1 B per env step; last_value
+  TimedLaunch timed(KC_GAE, (double)d.T * (16.0 * d.NA + d.N) + 4.0 * d.NA, s);
   hipLaunchKernelGGL(gae_kernel, dim3((unsigned)blocks), dim3(threads), 0, s, tr.reward, tr.value, tr.done,
                      tr.last_value, tr.adv, tr.ret, d.T, d.N, d.A, c.gamma, c.lambda);
   return launch_status();

@@ -225,6 +225,8 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_f32_kernel(GemmArgs g) {
 template <int MODE, int EPI>
 inline void launch_gemm(const GemmArgs& g, hipStream_t s) {
   const int64_t M = g.M, N = g.N;
+  TimedLaunch timed(MODE == GEMM_NN ? KC_GEMM_NN : (MODE == GEMM_NT ? KC_GEMM_NT : KC_GEMM_TN),
+                    2.0 * (double)g.M * (double)g.N * (double)g.K, s);
   unsigned gz = 1;
   if (MODE == GEMM_TN) gz = (unsigned)((g.K + g.k_per_split - 1) / g.k_per_split);
   if (MODE == GEMM_TN && M <= 32) {
