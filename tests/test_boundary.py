@@ -1,0 +1,97 @@
+"""The C-ABI library loads without a GPU, exports every symbol the header declares, and rejects bad
+arguments on the host before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def M():
+    import paper_2107_01460_amd as m
+    if not os.path.exists(m.binding._LIB_PATH):
+        from paper_2107_01460_amd import build
+        build.build(verbose=False)
+    m.lib()
+    return m
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "marl.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(marl_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(M):
+    names = declared_symbols()
+    assert len(names) >= 12
+    for n in names:
+        assert hasattr(M.lib(), n), n
+    assert set(M.binding.EXPORTS) == set(names)
+
+
+def test_query_sizes_and_parameter_counts(M):
+    for cfg in W.CONFIGS:
+        s = M.query_sizes(cfg)
+        assert s.n_params == W.param_count(cfg)
+        assert s.obs_dim == W.obs_dim(cfg) and s.critic_in_dim == W.critic_in_dim(cfg)
+        T, N, A = cfg["rollout_len"], cfg["n_envs"], cfg["n_agents"]
+        assert s.obs_bytes == 4 * (T + 1) * N * A * s.obs_dim
+        assert s.step_scalar_bytes == 4 * T * N * A and s.done_bytes == T * N
+        assert s.rollout_workspace_bytes > 0 and s.update_workspace_bytes > s.n_params * 8
+
+
+@pytest.mark.parametrize("field,value", [
+    ("grid", 1), ("grid", 65), ("n_agents", 9), ("n_food", 0), ("view", 4), ("actor_hidden", 100),
+    ("critic_hidden", 1024), ("n_minibatches", 7), ("precision", 2), ("clip_eps", 0.0), ("gamma", 1.5),
+    ("max_level", 0), ("central_critic", 2), ("lr", 0.0)])
+def test_bad_config_rejected(M, field, value):
+    cfg = W.scaled(W.CONFIGS[1], **{field: value})
+    s = M.binding.Sizes()
+    rc = M.lib().marl_query_sizes(C.byref(M.make_config(cfg)), C.byref(s))
+    assert rc == -3, (field, rc)
+    st = M.binding.EnvStateC(*([0x1000] * 8))
+    assert M.lib().marl_env_reset(C.byref(M.make_config(cfg)), st, None) == -3
+
+
+def test_too_many_entities_rejected(M):
+    cfg = W.scaled(W.CONFIGS[0], grid=2, n_agents=3, n_food=2)
+    s = M.binding.Sizes()
+    assert M.lib().marl_query_sizes(C.byref(M.make_config(cfg)), C.byref(s)) == -3
+
+
+def test_null_and_misaligned_pointers_rejected_before_launch(M):
+    cfg = M.make_config(W.CONFIGS[0])
+    L = M.lib()
+    good = 0x10000
+    null_state = M.binding.EnvStateC(*([good] * 7 + [None]))
+    assert L.marl_env_reset(C.byref(cfg), null_state, None) == -1
+    odd_state = M.binding.EnvStateC(*([good] * 7 + [good + 4]))
+    assert L.marl_env_reset(C.byref(cfg), odd_state, None) == -2
+    ok_state = M.binding.EnvStateC(*([good] * 8))
+    assert L.marl_observe(C.byref(cfg), ok_state, None, None) == -1
+    assert L.marl_env_step(C.byref(cfg), ok_state, good, good + 8, good, good, None) == -2
+    traj = M.binding.TrajC(*([good] * 9 + [None, None]))
+    assert L.marl_rollout(C.byref(cfg), ok_state, None, traj, 0, None, None, good, None) == -1
+    assert L.marl_compute_gae(C.byref(cfg), M.binding.TrajC(*([good] * 7 + [None, good, None, None])), None) == -1
+    assert L.marl_ppo_update(C.byref(cfg), traj, good, good, good, -1, None, good, None, good, None) == -5
+    assert L.marl_ppo_update(C.byref(cfg), traj, good, good, good, 0, good + 2, good, None, good, None) == -2
+    assert L.marl_policy_forward(C.byref(cfg), good, good, -1, good, good, good, None) == -5
+    assert L.marl_sample_actions(C.byref(cfg), good, None, None, 1 << 31, 0, good, None, good, None) == -5
+    assert L.marl_query_sizes(None, None) == -1
+    assert M.status_string(0) == "ok" and "null" in M.status_string(-1)
+    d, n, w = C.c_double(), C.c_int64(), C.c_double()
+    assert L.marl_timing_read(99, C.byref(d), C.byref(n), C.byref(w)) == -5
+    assert L.marl_timing_read(0, None, None, None) == -1
+
+
+def test_missing_library_fails_loudly(M, monkeypatch):
+    monkeypatch.setattr(M.binding, "_lib", None)
+    monkeypatch.setattr(M.binding, "_LIB_PATH", "/nonexistent/libmarl_gfx950.so")
+    with pytest.raises(M.MarlError):
+        M.binding.lib()
