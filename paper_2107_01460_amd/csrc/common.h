@@ -50,6 +50,30 @@ inline NetOffsets net_offsets(int64_t base, int Din, int H, int Dout) {
   return o;
 }
 
+// The kernels read weights from a working copy of the parameter vector in which every block (W1, b1, ...)
+// starts on a 64-float boundary, so that 16-byte loads of weight rows are always aligned.
+struct ParamMap {
+  int64_t src[13], dst[13];  // 12 blocks (actor 6, critic 6) + end
+};
+inline ParamMap param_map(const Dims& d) {
+  ParamMap m;
+  const NetOffsets a = net_offsets(0, d.D, d.Ha, kActions), c = net_offsets(d.Pa, d.Dc, d.Hc, 1);
+  const int64_t src[13] = {a.W1, a.b1, a.W2, a.b2, a.W3, a.b3, c.W1, c.b1, c.W2, c.b2, c.W3, c.b3, c.end};
+  int64_t off = 0;
+  for (int i = 0; i < 13; ++i) {
+    m.src[i] = src[i];
+    m.dst[i] = off;
+    if (i < 12) off += ((src[i + 1] - src[i] + 63) / 64) * 64;
+  }
+  return m;
+}
+inline NetOffsets padded_offsets(const ParamMap& m, int net) {
+  const int64_t* o = m.dst + 6 * net;
+  NetOffsets r;
+  r.W1 = o[0]; r.b1 = o[1]; r.W2 = o[2]; r.b2 = o[3]; r.W3 = o[4]; r.b3 = o[5]; r.end = o[6];
+  return r;
+}
+
 int32_t validate_config(const marl_config* cfg);
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 

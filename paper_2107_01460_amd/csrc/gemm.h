@@ -7,6 +7,8 @@
 // in place from the trajectory.  Tiles are staged in LDS in their source orientation; the operand
 // fetch indexes them so that the 32 lanes of a half-wavefront hit 32 different banks.
 #pragma once
+#include <algorithm>
+
 #include "common.h"
 
 namespace marl {
@@ -45,7 +47,7 @@ struct GemmArgs {
   const float* aux_vec;  // EPI_BIAS_TANH: bias [N]
   const float* aux_mat;  // EPI_DTANH: previous activation [M][ldaux]
   int64_t ldaux;
-  float* colsum;         // EPI_DTANH: [N] (atomic), nullable
+  float* colsum;         // TN: column sums of B are added here ([N], atomic), nullable; EPI_DTANH: column sums of C
   int64_t M, N, K;
   int64_t k_per_split;   // TN: k range of one blockIdx.z
   int round_bf16;        // round stored results to bf16 precision (kept in fp32 storage)
@@ -147,6 +149,10 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_f32_kernel(GemmArgs g) {
     }
   };
 
+  // TN: column sums of B (the bias gradient).  B_COLS divides NT here, so a thread always stages the same column.
+  float bsum = 0.f;
+  const bool want_bsum = MODE == GEMM_TN && g.colsum != nullptr && blockIdx.x == 0;
+
   if (k_begin < k_end) fetch(k_begin);
   for (int64_t k0 = k_begin; k0 < k_end; k0 += BK) {
 #pragma unroll
@@ -158,6 +164,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_f32_kernel(GemmArgs g) {
     for (int j = 0; j < B_PER; ++j) {
       const int e = tid + j * NT;
       Bs[(e / B_COLS) * B_LD + (e % B_COLS)] = rb[j];
+      if (MODE == GEMM_TN && want_bsum) bsum += rb[j];
     }
     __syncthreads();
     if (k0 + BK < k_end) fetch(k0 + BK);
@@ -181,6 +188,12 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_f32_kernel(GemmArgs g) {
         for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
     }
     __syncthreads();
+  }
+
+  if (MODE == GEMM_TN && want_bsum) {
+    static_assert(MODE != GEMM_TN || NT % B_COLS == 0, "a thread must stage one column");
+    const int64_t n = n0 + tid % B_COLS;
+    if (n < g.N) atomicAdd(&g.colsum[n], bsum);
   }
 
   // Epilogue.  Accumulator register r of a lane holds C[8*(r/4) + 4*hi + r%4][lo] of its 32x32 tile.
@@ -221,6 +234,279 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_f32_kernel(GemmArgs g) {
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Second-generation kernel for the large shapes: 128 x BN tile (BN = 64 or 128), k-tile 32, four
+// wavefronts as 2 x 2, 16-byte global loads and LDS stores where the source rows are 16-byte
+// aligned (AVEC), operands fetched from LDS with one 16-byte read per four k-steps on k-contiguous
+// tiles.  Within a group of eight k values the lower half-wavefront supplies k = 0..3 and the
+// upper half k = 4..7 of both operands, so that each lane's four values are one aligned LDS read.
+// One LDS buffer; the next k-tile travels global -> registers while the current one is multiplied.
+// ---------------------------------------------------------------------------------------------
+constexpr int kG2BK = 32;
+constexpr int kG2PitchK = kG2BK + 4;  // k-contiguous tiles: pitch 36 floats keeps 16-byte alignment and spreads banks
+
+template <int MODE, int EPI, int BN, bool AVEC>
+__global__ void __launch_bounds__(256, 2) gemm2_f32_kernel(GemmArgs g) {
+  constexpr int BM = 128, BK = kG2BK, PK = kG2PitchK;
+  constexpr int TM = 2, TN = BN / 64;
+  constexpr bool A_KCONT = (MODE != GEMM_TN);  // A tile stored [m][k] (pitch PK) else [k][m] (pitch BM)
+  constexpr bool B_KCONT = (MODE == GEMM_NT);  // B tile stored [n][k] (pitch PK) else [k][n] (pitch BN)
+  constexpr int A_FLOATS = A_KCONT ? BM * PK : BK * BM;
+  constexpr int B_FLOATS = B_KCONT ? BN * PK : BK * BN;
+  __shared__ __attribute__((aligned(16))) float As[A_FLOATS];
+  __shared__ __attribute__((aligned(16))) float Bs[B_FLOATS];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int lo = lane & 31, hi = lane >> 5;
+  const int64_t n0 = (int64_t)blockIdx.y * BN;
+  // NN / NT: the workgroup is persistent over row tiles (tile, tile + gridDim.x, ...) and the first k-tile of
+  // the next row tile is already in flight while the current one finishes, so that neither the first load
+  // latency nor the epilogue of a row tile leaves the memory pipe idle.  TN: one output tile, k split over z.
+  const int64_t num_mt = (g.M + BM - 1) / BM;
+  int64_t k_begin = 0, k_end = g.K;
+  if (MODE == GEMM_TN) {
+    k_begin = (int64_t)blockIdx.z * g.k_per_split;
+    k_end = min(g.K, k_begin + g.k_per_split);
+  }
+
+  floatx16 acc[TM][TN];
+
+  // ---- global -> register staging
+  // A, k-contiguous (NN/NT): vector: thread -> (row = tid/8 + 32p, 4 floats at k = 4*(tid%8)), p < 4
+  //                          scalar: thread -> (row = tid/32 + 8p, k = tid%32), p < 16
+  // A, m-contiguous (TN):    vector: thread -> (k = tid/32 + 8p, 4 floats at m = 4*(tid%32)), p < 4
+  //                          scalar: thread -> (k = tid/128 + 2p, m = tid%128), p < 16
+  constexpr int A_REGS = 16;
+  float ra[A_REGS];
+  const float* arow[AVEC ? 4 : 16];
+  int64_t m0_fetch = (int64_t)blockIdx.x * BM;  // row tile the staging registers belong to
+  auto set_rows = [&](int64_t m0) {
+    m0_fetch = m0;
+    if (A_KCONT) {
+#pragma unroll
+      for (int p = 0; p < (AVEC ? 4 : 16); ++p) {
+        int64_t row = m0 + (AVEC ? (tid >> 3) + 32 * p : (tid >> 5) + 8 * p);
+        row = min(row, g.M - 1);  // rows past the end re-read the last row; their results are never stored
+        arow[p] = g.A.ptr(row);
+      }
+    }
+  };
+  // B, n-contiguous (NN/TN): thread -> (k = tid/(BN/4) + (1024/BN) p, 4 floats at n = 4*(tid % (BN/4)))
+  // B, k-contiguous (NT):    thread -> (n = tid/8 + 32p, 4 floats at k = 4*(tid%8)), p < BN/32
+  constexpr int B_VECS = BK * BN / 4 / 256;
+  float4 rb[B_VECS];
+
+  auto fetch = [&](int64_t k0) {
+    if (A_KCONT) {
+      if (AVEC) {
+        const int64_t k = k0 + 4 * (tid & 7);
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+          if (k < k_end) v = *reinterpret_cast<const float4*>(arow[p] + k);
+          ra[4 * p + 0] = v.x; ra[4 * p + 1] = v.y; ra[4 * p + 2] = v.z; ra[4 * p + 3] = v.w;
+        }
+      } else {
+        const int64_t k = k0 + (tid & 31);
+#pragma unroll
+        for (int p = 0; p < 16; ++p) ra[p] = k < k_end ? arow[p][k] : 0.f;
+      }
+    } else {
+      if (AVEC) {
+        const int64_t m = m0_fetch + 4 * (tid & 31);
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          const int64_t k = k0 + (tid >> 5) + 8 * p;
+          float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+          if (k < k_end && m < g.M) v = *reinterpret_cast<const float4*>(g.A.ptr(k) + m);
+          ra[4 * p + 0] = v.x; ra[4 * p + 1] = v.y; ra[4 * p + 2] = v.z; ra[4 * p + 3] = v.w;
+        }
+      } else {
+        const int64_t m = m0_fetch + (tid & 127);
+#pragma unroll
+        for (int p = 0; p < 16; ++p) {
+          const int64_t k = k0 + (tid >> 7) + 2 * p;
+          ra[p] = (k < k_end && m < g.M) ? g.A.ptr(k)[m] : 0.f;
+        }
+      }
+    }
+    if (B_KCONT) {
+      const int64_t k = k0 + 4 * (tid & 7);
+#pragma unroll
+      for (int p = 0; p < B_VECS; ++p) {
+        const int64_t n = n0 + (tid >> 3) + 32 * p;
+        rb[p] = k < k_end ? *reinterpret_cast<const float4*>(g.B + n * g.ldb + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+    } else {
+      const int64_t n = n0 + 4 * (tid % (BN / 4));
+#pragma unroll
+      for (int p = 0; p < B_VECS; ++p) {
+        const int64_t k = k0 + tid / (BN / 4) + (1024 / BN) * p;
+        rb[p] = k < k_end ? *reinterpret_cast<const float4*>(g.B + k * g.ldb + n) : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+    }
+  };
+
+  auto stage = [&]() {
+    if (A_KCONT) {
+      if (AVEC) {
+#pragma unroll
+        for (int p = 0; p < 4; ++p)
+          *reinterpret_cast<float4*>(&As[((tid >> 3) + 32 * p) * PK + 4 * (tid & 7)]) =
+              make_float4(ra[4 * p], ra[4 * p + 1], ra[4 * p + 2], ra[4 * p + 3]);
+      } else {
+#pragma unroll
+        for (int p = 0; p < 16; ++p) As[((tid >> 5) + 8 * p) * PK + (tid & 31)] = ra[p];
+      }
+    } else {
+      if (AVEC) {
+#pragma unroll
+        for (int p = 0; p < 4; ++p)
+          *reinterpret_cast<float4*>(&As[((tid >> 5) + 8 * p) * BM + 4 * (tid & 31)]) =
+              make_float4(ra[4 * p], ra[4 * p + 1], ra[4 * p + 2], ra[4 * p + 3]);
+      } else {
+#pragma unroll
+        for (int p = 0; p < 16; ++p) As[((tid >> 7) + 2 * p) * BM + (tid & 127)] = ra[p];
+      }
+    }
+    if (B_KCONT) {
+#pragma unroll
+      for (int p = 0; p < B_VECS; ++p) *reinterpret_cast<float4*>(&Bs[((tid >> 3) + 32 * p) * PK + 4 * (tid & 7)]) = rb[p];
+    } else {
+#pragma unroll
+      for (int p = 0; p < B_VECS; ++p)
+        *reinterpret_cast<float4*>(&Bs[(tid / (BN / 4) + (1024 / BN) * p) * BN + 4 * (tid % (BN / 4))]) = rb[p];
+    }
+  };
+
+  // TN: column sums of B (the bias gradient) ride along: each thread adds up the values it stages
+  float4 bsum = make_float4(0.f, 0.f, 0.f, 0.f);
+  const bool want_bsum = MODE == GEMM_TN && g.colsum != nullptr && blockIdx.x == 0;
+
+  int64_t tile = blockIdx.x;
+  if (tile < num_mt && k_begin < k_end) {
+    set_rows(tile * BM);
+    fetch(k_begin);
+  }
+  for (; tile < num_mt; tile += (MODE == GEMM_TN ? num_mt : (int64_t)gridDim.x)) {
+    const int64_t m0 = tile * BM;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    for (int64_t k0 = k_begin; k0 < k_end; k0 += BK) {
+      stage();
+      if (MODE == GEMM_TN && want_bsum) {
+#pragma unroll
+        for (int p = 0; p < B_VECS; ++p) {
+          bsum.x += rb[p].x; bsum.y += rb[p].y; bsum.z += rb[p].z; bsum.w += rb[p].w;
+        }
+      }
+      __syncthreads();
+      if (k0 + BK < k_end) {
+        fetch(k0 + BK);
+      } else if (MODE != GEMM_TN && tile + (int64_t)gridDim.x < num_mt) {
+        set_rows((tile + (int64_t)gridDim.x) * BM);
+        fetch(k_begin);
+      }
+#pragma unroll
+      for (int kb = 0; kb < BK; kb += 8) {
+        // lane (lo, hi) supplies k = kb + 4*hi + j in MFMA step j
+        float a[TM][4], b[TN][4];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+          const int m = wm * 64 + i * 32 + lo;
+          if (A_KCONT) {
+            const float4 v = *reinterpret_cast<const float4*>(&As[m * PK + kb + 4 * hi]);
+            a[i][0] = v.x; a[i][1] = v.y; a[i][2] = v.z; a[i][3] = v.w;
+          } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) a[i][j] = As[(kb + 4 * hi + j) * BM + m];
+          }
+        }
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn) {
+          const int n = wn * (BN / 2) + jn * 32 + lo;
+          if (B_KCONT) {
+            const float4 v = *reinterpret_cast<const float4*>(&Bs[n * PK + kb + 4 * hi]);
+            b[jn][0] = v.x; b[jn][1] = v.y; b[jn][2] = v.z; b[jn][3] = v.w;
+          } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) b[jn][j] = Bs[(kb + 4 * hi + j) * BN + n];
+          }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int jn = 0; jn < TN; ++jn)
+              acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][j], b[jn][j], acc[i][jn], 0, 0, 0);
+      }
+      __syncthreads();
+    }
+
+    if (MODE == GEMM_TN && want_bsum) {
+      // threads with equal tid % (BN/4) hold partial sums of the same four columns: combine them through LDS
+      float4* red = reinterpret_cast<float4*>(Bs);  // the tile is no longer needed (the loop ended with a barrier)
+      red[tid] = bsum;
+      __syncthreads();
+      constexpr int GROUPS = 256 / (BN / 4);
+      if (tid < BN / 4) {
+        float4 t = red[tid];
+#pragma unroll
+        for (int q = 1; q < GROUPS; ++q) {
+          const float4 o = red[tid + q * (BN / 4)];
+          t.x += o.x; t.y += o.y; t.z += o.z; t.w += o.w;
+        }
+        float* dst = g.colsum + n0 + 4 * tid;
+        atomicAdd(dst + 0, t.x); atomicAdd(dst + 1, t.y); atomicAdd(dst + 2, t.z); atomicAdd(dst + 3, t.w);
+      }
+    }
+
+    // Epilogue (accumulator register r of a lane holds C[8*(r/4) + 4*hi + r%4][lo] of its 32x32 tile).
+#pragma unroll
+    for (int jn = 0; jn < TN; ++jn) {
+      const int64_t n = n0 + wn * (BN / 2) + jn * 32 + lo;
+      float csum = 0.f, bias = 0.f;
+      if (EPI == EPI_BIAS_TANH) bias = g.aux_vec[n];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int64_t m = m0 + wm * 64 + i * 32 + 8 * (r / 4) + 4 * hi + (r % 4);
+          if (m < g.M) {
+            float v = acc[i][jn][r];
+            if (EPI == EPI_BIAS_TANH) {
+              v = tanh_f32(v + bias);
+              if (g.round_bf16) v = round_to_bf16(v);
+              g.C[m * g.ldc + n] = v;
+            } else if (EPI == EPI_DTANH) {
+              const float h = g.aux_mat[m * g.ldaux + n];
+              v = v * (1.0f - h * h);
+              if (g.round_bf16) v = round_to_bf16(v);
+              g.C[m * g.ldc + n] = v;
+              csum += v;
+            } else {
+              atomicAdd(&g.C[m * g.ldc + n], v);
+            }
+          }
+        }
+      }
+      if (EPI == EPI_DTANH && g.colsum != nullptr) {
+        csum += __shfl_xor(csum, 32);
+        if (hi == 0) atomicAdd(&g.colsum[n], csum);
+      }
+    }
+  }
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
 // Host-side dispatch over the tile shapes used by the library.
 template <int MODE, int EPI>
 inline void launch_gemm(const GemmArgs& g, hipStream_t s) {
@@ -229,6 +515,24 @@ inline void launch_gemm(const GemmArgs& g, hipStream_t s) {
                     2.0 * (double)g.M * (double)g.N * (double)g.K, s);
   unsigned gz = 1;
   if (MODE == GEMM_TN) gz = (unsigned)((g.K + g.k_per_split - 1) / g.k_per_split);
+  // Large shapes: N a multiple of 64, weights 16-byte aligned with a row pitch that keeps them so.
+  const bool b_ok = aligned16(g.B) && g.ldb % 4 == 0 && N % 64 == 0 && (MODE != GEMM_NT || g.K % 4 == 0);
+  if (b_ok && !(MODE == GEMM_TN && M <= 32)) {
+    const bool avec = aligned16(g.A.base) && g.A.ld % 4 == 0 && (MODE == GEMM_TN ? M % 4 == 0 : g.K % 4 == 0);
+    const int bn = N % 128 == 0 ? 128 : 64;
+    unsigned gx = (unsigned)((M + 127) / 128);
+    // (The kernel can also run persistently over row tiles with a smaller grid; measured slower here: stores
+    // share the load counter on this target, so the next tile's staged loads wait for the epilogue's stores.)
+    dim3 grid(gx, (unsigned)(N / bn), gz);
+    if (bn == 128) {
+      if (avec) hipLaunchKernelGGL((gemm2_f32_kernel<MODE, EPI, 128, true>), grid, dim3(256), 0, s, g);
+      else hipLaunchKernelGGL((gemm2_f32_kernel<MODE, EPI, 128, false>), grid, dim3(256), 0, s, g);
+    } else {
+      if (avec) hipLaunchKernelGGL((gemm2_f32_kernel<MODE, EPI, 64, true>), grid, dim3(256), 0, s, g);
+      else hipLaunchKernelGGL((gemm2_f32_kernel<MODE, EPI, 64, false>), grid, dim3(256), 0, s, g);
+    }
+    return;
+  }
   if (MODE == GEMM_TN && M <= 32) {
     // very thin output (first-layer gradient of the small networks)
     dim3 grid(1, (unsigned)((N + 63) / 64), gz);

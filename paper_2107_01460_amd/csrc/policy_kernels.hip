@@ -9,9 +9,15 @@
 namespace marl {
 namespace {
 
-__global__ void round_params_kernel(const float* __restrict__ src, float* __restrict__ dst, int64_t n) {
+// Working copy of the parameters: blocks moved to their aligned offsets, optionally rounded to bf16.
+__global__ void stage_params_kernel(const float* __restrict__ src, float* __restrict__ dst, ParamMap pm, int round) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) dst[i] = round_to_bf16(src[i]);
+  if (i >= pm.src[12]) return;
+  int b = 0;
+#pragma unroll
+  for (int k = 1; k < 12; ++k) b += (i >= pm.src[k]) ? 1 : 0;
+  const float v = src[i];
+  dst[pm.dst[b] + (i - pm.src[b])] = round ? round_to_bf16(v) : v;
 }
 
 struct RolloutWsView {
@@ -31,7 +37,7 @@ RolloutWsView carve_rollout_ws(const marl_config& c, int64_t n_rows, void* ws, i
     return r;
   };
   RolloutWsView v;
-  v.eff_params = take(d.P);
+  v.eff_params = take(param_map(d).dst[12]);
   v.h1a = take(S * d.Ha);
   v.h2a = take(S * d.Ha);
   v.h1c = take(Sc * d.Hc);
@@ -56,9 +62,9 @@ void mlp_hidden_forward(const RowSrc& X, int64_t S, int Din, int H, const float*
 }
 
 const float* effective_params(const marl_config& c, const float* params, float* scratch, hipStream_t s) {
-  if (c.precision != 1) return params;
   const Dims d = dims_of(c);
-  hipLaunchKernelGGL(round_params_kernel, dim3((unsigned)((d.P + 255) / 256)), dim3(256), 0, s, params, scratch, d.P);
+  hipLaunchKernelGGL(stage_params_kernel, dim3((unsigned)((d.P + 255) / 256)), dim3(256), 0, s, params, scratch,
+                     param_map(d), (int)d.bf16);
   return scratch;
 }
 
@@ -75,13 +81,13 @@ static int32_t forward_rows(const marl_config& c, const float* eff, const float*
   const Dims d = dims_of(c);
   const int64_t S = n_rows * d.A;
   if (want_actor) {
-    const NetOffsets o = net_offsets(0, d.D, d.Ha, kActions);
+    const NetOffsets o = padded_offsets(param_map(d), 0);
     mlp_hidden_forward(RowSrc{obs, d.D, nullptr, 1, S}, S, d.D, d.Ha, eff + o.W1, eff + o.b1, eff + o.W2, eff + o.b2,
                        w.h1a, w.h2a, d.bf16, s);
     launch_actor_head_rollout(w.h2a, S, d.Ha, eff + o.W3, eff + o.b3, logits_out, sample, s);
   }
   if (value_out) {
-    const NetOffsets o = net_offsets(d.Pa, d.Dc, d.Hc, 1);
+    const NetOffsets o = padded_offsets(param_map(d), 1);
     const int64_t Sc = d.central ? n_rows : S;
     mlp_hidden_forward(RowSrc{obs, d.Dc, nullptr, 1, Sc}, Sc, d.Dc, d.Hc, eff + o.W1, eff + o.b1, eff + o.W2,
                        eff + o.b2, w.h1c, w.h2c, d.bf16, s);

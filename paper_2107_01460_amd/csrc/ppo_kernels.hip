@@ -287,7 +287,7 @@ __global__ void __launch_bounds__(256) dz2_kernel(float* __restrict__ H2, const 
   }
   red[tid] = on ? csum : 0.f;
   __syncthreads();
-  if (tid < cb && j < H) {
+  if (gb2 != nullptr && tid < cb && j < H) {
     float t = 0.f;
     for (int g2 = 0; g2 < rg_count; ++g2) t += red[g2 * cb + tid];
     atomicAdd(&gb2[j], t);
@@ -360,7 +360,7 @@ UpdateWsView carve_update_ws(const marl_config& c, void* ws, int64_t* total) {
     return r;
   };
   UpdateWsView v;
-  v.eff_params = (float*)take(d.P * 4);
+  v.eff_params = (float*)take(param_map(d).dst[12] * 4);
   v.grad = (float*)take(d.P * 4);
   v.sc = (Scalars*)take(sizeof(Scalars));
   v.ident = (int32_t*)take(R * 4);
@@ -392,26 +392,26 @@ void mlp_backward(const RowSrc& X, int64_t S, int Din, int H, const float* W2, c
   {
     const int cb = std::min(H, 256), rpb = 256;
     dim3 grid((unsigned)((S + rpb - 1) / rpb), (unsigned)((H + cb - 1) / cb));
-    hipLaunchKernelGGL(dz2_kernel<NOUT>, grid, dim3(256), 0, s, h2, dl, W3, gb2, S, H, cb, rpb, (int)bf16);
+    hipLaunchKernelGGL(dz2_kernel<NOUT>, grid, dim3(256), 0, s, h2, dl, W3, (float*)nullptr, S, H, cb, rpb, (int)bf16);
   }
   {  // gW2 += h1^T dz2
     GemmArgs g{};
     g.A = RowSrc{h1, H, nullptr, 1, S}; g.B = h2; g.ldb = H; g.C = gW2; g.ldc = H;
-    g.M = H; g.N = H; g.K = S;
+    g.M = H; g.N = H; g.K = S; g.colsum = gb2;
     g.k_per_split = pick_k_split(S, ((H + 127) / 128) * ((H + 127) / 128));
     launch_gemm<GEMM_TN, EPI_ATOMIC_ADD>(g, s);
   }
   {  // dz1 = (dz2 W2^T) * (1 - h1^2), gb1 += column sums
     GemmArgs g{};
     g.A = RowSrc{h2, H, nullptr, 1, S}; g.B = W2; g.ldb = H; g.C = dz1; g.ldc = H;
-    g.aux_mat = h1; g.ldaux = H; g.colsum = gb1;
+    g.aux_mat = h1; g.ldaux = H; g.colsum = nullptr;
     g.M = S; g.N = H; g.K = H; g.round_bf16 = bf16;
     launch_gemm<GEMM_NT, EPI_DTANH>(g, s);
   }
   {  // gW1 += X^T dz1
     GemmArgs g{};
     g.A = X; g.B = dz1; g.ldb = H; g.C = gW1; g.ldc = H;
-    g.M = Din; g.N = H; g.K = S;
+    g.M = Din; g.N = H; g.K = S; g.colsum = gb1;
     g.k_per_split = pick_k_split(S, ((Din + 127) / 128) * ((H + 127) / 128));
     launch_gemm<GEMM_TN, EPI_ATOMIC_ADD>(g, s);
   }
@@ -434,8 +434,10 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
   const int64_t Sa = rows_mb * d.A, Sc = d.central ? rows_mb : Sa;
   if (perm == nullptr)
     hipLaunchKernelGGL(iota_kernel, dim3((unsigned)((R + 255) / 256)), dim3(256), 0, s, w.ident, R);
-  const NetOffsets oa = net_offsets(0, d.D, d.Ha, kActions);
-  const NetOffsets oc = net_offsets(d.Pa, d.Dc, d.Hc, 1);
+  // ga/gc: blocks of the gradient (parameter-vector layout); oa/oc: blocks of the aligned working copy of the weights
+  const NetOffsets ga = net_offsets(0, d.D, d.Ha, kActions), gc = net_offsets(d.Pa, d.Dc, d.Hc, 1);
+  const ParamMap pm = param_map(d);
+  const NetOffsets oa = padded_offsets(pm, 0), oc = padded_offsets(pm, 1);
   int64_t k = adam_step0;
   for (int e = 0; e < c.n_epochs; ++e) {
     for (int mb = 0; mb < c.n_minibatches; ++mb) {
@@ -458,10 +460,10 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
         ActorLoss fn{lc, tr.action, tr.logp, tr.adv};
         const unsigned nb = (unsigned)std::min<int64_t>(2048, (Sa + kHeadTile - 1) / kHeadTile);
         hipLaunchKernelGGL((loss_head_kernel<kActions, ActorLoss>), dim3(nb), dim3(256), 0, s, w.h2a, Sa, d.Ha,
-                           eff + oa.W3, eff + oa.b3, fn, w.dla, w.grad + oa.W3, w.grad + oa.b3, w.sc, 0.f);
+                           eff + oa.W3, eff + oa.b3, fn, w.dla, w.grad + ga.W3, w.grad + ga.b3, w.sc, 0.f);
       }
-      mlp_backward<kActions>(Xa, Sa, d.D, d.Ha, eff + oa.W2, eff + oa.W3, w.h1a, w.h2a, w.dz1a, w.dla, w.grad + oa.W1,
-                             w.grad + oa.b1, w.grad + oa.W2, w.grad + oa.b2, d.bf16, s);
+      mlp_backward<kActions>(Xa, Sa, d.D, d.Ha, eff + oa.W2, eff + oa.W3, w.h1a, w.h2a, w.dz1a, w.dla, w.grad + ga.W1,
+                             w.grad + ga.b1, w.grad + ga.W2, w.grad + ga.b2, d.bf16, s);
       // ---- critic
       const RowSrc Xc{tr.obs, d.Dc, rows, d.central ? 1 : d.A, Sc};
       mlp_hidden_forward(Xc, Sc, d.Dc, d.Hc, eff + oc.W1, eff + oc.b1, eff + oc.W2, eff + oc.b2, w.h1c, w.h2c, d.bf16, s);
@@ -469,10 +471,10 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
         CriticLoss fn{lc, tr.ret, tr.value, d.central ? d.A : 1};
         const unsigned nb = (unsigned)std::min<int64_t>(2048, (Sc + kHeadTile - 1) / kHeadTile);
         hipLaunchKernelGGL((loss_head_kernel<1, CriticLoss>), dim3(nb), dim3(256), 0, s, w.h2c, Sc, d.Hc, eff + oc.W3,
-                           eff + oc.b3, fn, w.dlc, w.grad + oc.W3, w.grad + oc.b3, w.sc, 0.f);
+                           eff + oc.b3, fn, w.dlc, w.grad + gc.W3, w.grad + gc.b3, w.sc, 0.f);
       }
-      mlp_backward<1>(Xc, Sc, d.Dc, d.Hc, eff + oc.W2, eff + oc.W3, w.h1c, w.h2c, w.dz1c, w.dlc, w.grad + oc.W1,
-                      w.grad + oc.b1, w.grad + oc.W2, w.grad + oc.b2, d.bf16, s);
+      mlp_backward<1>(Xc, Sc, d.Dc, d.Hc, eff + oc.W2, eff + oc.W3, w.h1c, w.h2c, w.dz1c, w.dlc, w.grad + gc.W1,
+                      w.grad + gc.b1, w.grad + gc.W2, w.grad + gc.b2, d.bf16, s);
       // ---- clip + Adam
       hipLaunchKernelGGL(grad_norm_kernel, dim3((unsigned)std::min<int64_t>(256, (d.P + 255) / 256)), dim3(256), 0, s,
                          w.grad, d.P, w.sc);
