@@ -3,6 +3,7 @@
 // The two hidden layers of each network are MFMA GEMMs (gemm.h); the narrow output layer
 // (6 logits or 1 value) runs on the vector ALUs of the "head" kernel, which also draws the
 // action by Gumbel-max from Philox uniforms and evaluates its log-probability.
+#include "fused_forward.h"
 #include "gemm.h"
 #include "heads.h"
 
@@ -18,6 +19,36 @@ __global__ void stage_params_kernel(const float* __restrict__ src, float* __rest
   for (int k = 1; k < 12; ++k) b += (i >= pm.src[k]) ? 1 : 0;
   const float v = src[i];
   dst[pm.dst[b] + (i - pm.src[b])] = round ? round_to_bf16(v) : v;
+}
+
+// What the rollout does with a sample's outputs.
+struct ActorRolloutFinish {
+  float* logits_out;  // nullable
+  SampleArgs sa;
+  int do_sample;
+  __device__ __forceinline__ void operator()(int64_t s, const float out[kActions], float*, float*) const {
+    if (logits_out) {
+#pragma unroll
+      for (int k = 0; k < kActions; ++k) logits_out[s * kActions + k] = out[k];
+    }
+    if (do_sample) sample_and_store(out, s, sa);
+  }
+};
+struct CriticRolloutFinish {
+  float* value_out;
+  int broadcast;
+  __device__ __forceinline__ void operator()(int64_t s, const float out[1], float*, float*) const {
+    for (int k = 0; k < broadcast; ++k) value_out[s * broadcast + k] = out[0];
+  }
+};
+
+FusedFwdArgs fused_args(const RowSrc& X, int64_t S, int Din, const float* eff, const NetOffsets& o, bool bf16) {
+  FusedFwdArgs a{};
+  a.X = X; a.S = S; a.Din = Din;
+  a.xvec = aligned16(X.base) && X.ld % 4 == 0 && Din % 4 == 0;
+  a.W1 = eff + o.W1; a.b1 = eff + o.b1; a.W2 = eff + o.W2; a.b2 = eff + o.b2; a.W3 = eff + o.W3; a.b3 = eff + o.b3;
+  a.round_bf16 = bf16;
+  return a;
 }
 
 struct RolloutWsView {
@@ -82,16 +113,26 @@ static int32_t forward_rows(const marl_config& c, const float* eff, const float*
   const int64_t S = n_rows * d.A;
   if (want_actor) {
     const NetOffsets o = padded_offsets(param_map(d), 0);
-    mlp_hidden_forward(RowSrc{obs, d.D, nullptr, 1, S}, S, d.D, d.Ha, eff + o.W1, eff + o.b1, eff + o.W2, eff + o.b2,
-                       w.h1a, w.h2a, d.bf16, s);
-    launch_actor_head_rollout(w.h2a, S, d.Ha, eff + o.W3, eff + o.b3, logits_out, sample, s);
+    const RowSrc X{obs, d.D, nullptr, 1, S};
+    if (fused_forward_supported(d.Ha)) {
+      ActorRolloutFinish fin{logits_out, sample ? *sample : SampleArgs{}, sample ? 1 : 0};
+      launch_fused_forward<kActions, false>(d.Ha, fused_args(X, S, d.D, eff, o, d.bf16), fin, s);
+    } else {
+      mlp_hidden_forward(X, S, d.D, d.Ha, eff + o.W1, eff + o.b1, eff + o.W2, eff + o.b2, w.h1a, w.h2a, d.bf16, s);
+      launch_actor_head_rollout(w.h2a, S, d.Ha, eff + o.W3, eff + o.b3, logits_out, sample, s);
+    }
   }
   if (value_out) {
     const NetOffsets o = padded_offsets(param_map(d), 1);
     const int64_t Sc = d.central ? n_rows : S;
-    mlp_hidden_forward(RowSrc{obs, d.Dc, nullptr, 1, Sc}, Sc, d.Dc, d.Hc, eff + o.W1, eff + o.b1, eff + o.W2,
-                       eff + o.b2, w.h1c, w.h2c, d.bf16, s);
-    launch_critic_head_rollout(w.h2c, Sc, d.Hc, eff + o.W3, eff + o.b3, value_out, d.central ? d.A : 1, s);
+    const RowSrc X{obs, d.Dc, nullptr, 1, Sc};
+    if (fused_forward_supported(d.Hc)) {
+      CriticRolloutFinish fin{value_out, d.central ? d.A : 1};
+      launch_fused_forward<1, false>(d.Hc, fused_args(X, Sc, d.Dc, eff, o, d.bf16), fin, s);
+    } else {
+      mlp_hidden_forward(X, Sc, d.Dc, d.Hc, eff + o.W1, eff + o.b1, eff + o.W2, eff + o.b2, w.h1c, w.h2c, d.bf16, s);
+      launch_critic_head_rollout(w.h2c, Sc, d.Hc, eff + o.W3, eff + o.b3, value_out, d.central ? d.A : 1, s);
+    }
   }
   return launch_status();
 }

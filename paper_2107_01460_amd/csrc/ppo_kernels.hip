@@ -4,6 +4,7 @@
 #include <algorithm>
 #include <cmath>
 
+#include "fused_forward.h"
 #include "gemm.h"
 #include "heads.h"
 
@@ -388,8 +389,8 @@ int64_t pick_k_split(int64_t K, int64_t tiles_mn) {
 template <int NOUT>
 void mlp_backward(const RowSrc& X, int64_t S, int Din, int H, const float* W2, const float* W3, float* h1, float* h2,
                   float* dz1, const float* dl, float* gW1, float* gb1, float* gW2, float* gb2, bool bf16,
-                  hipStream_t s) {
-  {
+                  bool dz2_ready, hipStream_t s) {
+  if (!dz2_ready) {
     const int cb = std::min(H, 256), rpb = 256;
     dim3 grid((unsigned)((S + rpb - 1) / rpb), (unsigned)((H + cb - 1) / cb));
     hipLaunchKernelGGL(dz2_kernel<NOUT>, grid, dim3(256), 0, s, h2, dl, W3, (float*)nullptr, S, H, cb, rpb, (int)bf16);
@@ -455,26 +456,46 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
       }
       // ---- actor
       const RowSrc Xa{tr.obs, d.D, rows, d.A, Sa};
-      mlp_hidden_forward(Xa, Sa, d.D, d.Ha, eff + oa.W1, eff + oa.b1, eff + oa.W2, eff + oa.b2, w.h1a, w.h2a, d.bf16, s);
+      const bool fused_a = fused_forward_supported(d.Ha);
       {
         ActorLoss fn{lc, tr.action, tr.logp, tr.adv};
-        const unsigned nb = (unsigned)std::min<int64_t>(2048, (Sa + kHeadTile - 1) / kHeadTile);
-        hipLaunchKernelGGL((loss_head_kernel<kActions, ActorLoss>), dim3(nb), dim3(256), 0, s, w.h2a, Sa, d.Ha,
-                           eff + oa.W3, eff + oa.b3, fn, w.dla, w.grad + ga.W3, w.grad + ga.b3, w.sc, 0.f);
+        if (fused_a) {
+          FusedFwdArgs fa{};
+          fa.X = Xa; fa.S = Sa; fa.Din = d.D; fa.xvec = aligned16(Xa.base) && Xa.ld % 4 == 0 && d.D % 4 == 0;
+          fa.W1 = eff + oa.W1; fa.b1 = eff + oa.b1; fa.W2 = eff + oa.W2; fa.b2 = eff + oa.b2; fa.W3 = eff + oa.W3;
+          fa.b3 = eff + oa.b3; fa.h1_out = w.h1a; fa.dz2_out = w.h2a; fa.gW3 = w.grad + ga.W3; fa.gb3 = w.grad + ga.b3;
+          fa.stats = w.sc->acc; fa.round_bf16 = d.bf16;
+          launch_fused_forward<kActions, true>(d.Ha, fa, fn, s);
+        } else {
+          mlp_hidden_forward(Xa, Sa, d.D, d.Ha, eff + oa.W1, eff + oa.b1, eff + oa.W2, eff + oa.b2, w.h1a, w.h2a, d.bf16, s);
+          const unsigned nb = (unsigned)std::min<int64_t>(2048, (Sa + kHeadTile - 1) / kHeadTile);
+          hipLaunchKernelGGL((loss_head_kernel<kActions, ActorLoss>), dim3(nb), dim3(256), 0, s, w.h2a, Sa, d.Ha,
+                             eff + oa.W3, eff + oa.b3, fn, w.dla, w.grad + ga.W3, w.grad + ga.b3, w.sc, 0.f);
+        }
       }
       mlp_backward<kActions>(Xa, Sa, d.D, d.Ha, eff + oa.W2, eff + oa.W3, w.h1a, w.h2a, w.dz1a, w.dla, w.grad + ga.W1,
-                             w.grad + ga.b1, w.grad + ga.W2, w.grad + ga.b2, d.bf16, s);
+                             w.grad + ga.b1, w.grad + ga.W2, w.grad + ga.b2, d.bf16, fused_a, s);
       // ---- critic
       const RowSrc Xc{tr.obs, d.Dc, rows, d.central ? 1 : d.A, Sc};
-      mlp_hidden_forward(Xc, Sc, d.Dc, d.Hc, eff + oc.W1, eff + oc.b1, eff + oc.W2, eff + oc.b2, w.h1c, w.h2c, d.bf16, s);
+      const bool fused_c = fused_forward_supported(d.Hc);
       {
         CriticLoss fn{lc, tr.ret, tr.value, d.central ? d.A : 1};
-        const unsigned nb = (unsigned)std::min<int64_t>(2048, (Sc + kHeadTile - 1) / kHeadTile);
-        hipLaunchKernelGGL((loss_head_kernel<1, CriticLoss>), dim3(nb), dim3(256), 0, s, w.h2c, Sc, d.Hc, eff + oc.W3,
-                           eff + oc.b3, fn, w.dlc, w.grad + gc.W3, w.grad + gc.b3, w.sc, 0.f);
+        if (fused_c) {
+          FusedFwdArgs fa{};
+          fa.X = Xc; fa.S = Sc; fa.Din = d.Dc; fa.xvec = aligned16(Xc.base) && Xc.ld % 4 == 0 && d.Dc % 4 == 0;
+          fa.W1 = eff + oc.W1; fa.b1 = eff + oc.b1; fa.W2 = eff + oc.W2; fa.b2 = eff + oc.b2; fa.W3 = eff + oc.W3;
+          fa.b3 = eff + oc.b3; fa.h1_out = w.h1c; fa.dz2_out = w.h2c; fa.gW3 = w.grad + gc.W3; fa.gb3 = w.grad + gc.b3;
+          fa.stats = w.sc->acc; fa.round_bf16 = d.bf16;
+          launch_fused_forward<1, true>(d.Hc, fa, fn, s);
+        } else {
+          mlp_hidden_forward(Xc, Sc, d.Dc, d.Hc, eff + oc.W1, eff + oc.b1, eff + oc.W2, eff + oc.b2, w.h1c, w.h2c, d.bf16, s);
+          const unsigned nb = (unsigned)std::min<int64_t>(2048, (Sc + kHeadTile - 1) / kHeadTile);
+          hipLaunchKernelGGL((loss_head_kernel<1, CriticLoss>), dim3(nb), dim3(256), 0, s, w.h2c, Sc, d.Hc, eff + oc.W3,
+                             eff + oc.b3, fn, w.dlc, w.grad + gc.W3, w.grad + gc.b3, w.sc, 0.f);
+        }
       }
       mlp_backward<1>(Xc, Sc, d.Dc, d.Hc, eff + oc.W2, eff + oc.W3, w.h1c, w.h2c, w.dz1c, w.dlc, w.grad + gc.W1,
-                      w.grad + gc.b1, w.grad + gc.W2, w.grad + gc.b2, d.bf16, s);
+                      w.grad + gc.b1, w.grad + gc.W2, w.grad + gc.b2, d.bf16, fused_c, s);
       // ---- clip + Adam
       hipLaunchKernelGGL(grad_norm_kernel, dim3((unsigned)std::min<int64_t>(256, (d.P + 255) / 256)), dim3(256), 0, s,
                          w.grad, d.P, w.sc);
