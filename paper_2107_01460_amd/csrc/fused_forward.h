@@ -4,8 +4,8 @@
 // backward pass needs: h1 and dz2 = dL/d(pre-activation of layer 2) go to HBM once, h2 never does, and the
 // output-layer gradient (W3, b3) is accumulated in registers across the row tiles a workgroup owns.
 //
-// Workgroup = 8 wavefronts on a tile of BM samples x H hidden units: (BM/32) x (H/32) MFMA tiles of
-// 32x32, one or two per wavefront.  Weights stream from L2 through a 32-row LDS buffer; the next chunk
+// Workgroup = 4 wavefronts on a tile of BM samples x H hidden units: (BM/32) x (H/32) MFMA tiles of
+// 32x32, one or two per wavefront; several small workgroups per CU overlap each other's phases.  Weights stream from L2 through a 32-row LDS buffer; the next chunk
 // travels global -> registers while the current one is multiplied.
 #pragma once
 #include "gemm.h"
@@ -31,7 +31,7 @@ template <int H, int BM, int NOUT>
 struct FusedFwdLds {
   static constexpr int PX = 36;     // pitch of the X chunk (k-contiguous, 16-byte reads)
   static constexpr int PH = H + 4;  // pitch of the activation tile
-  static constexpr int GROUPS = 512 / BM;
+  static constexpr int GROUPS = 256 / BM;
   float Xc[BM * PX];
   float Ws[32 * H];
   float Hs[BM * PH];
@@ -40,15 +40,16 @@ struct FusedFwdLds {
 };
 
 template <int H, int BM, int NOUT, bool TRAIN, class Finish>
-__global__ void __launch_bounds__(512) fused_forward_kernel(FusedFwdArgs a, Finish fin) {
+__global__ void __launch_bounds__(256, 2) fused_forward_kernel(FusedFwdArgs a, Finish fin) {
   using Lds = FusedFwdLds<H, BM, NOUT>;
   constexpr int PX = Lds::PX, PH = Lds::PH, GROUPS = Lds::GROUPS;
-  constexpr int NTN = H / 32, MT = BM / 32, TILES = MT * NTN, TPW = TILES / 8;
-  static_assert(TILES % 8 == 0 && (TPW == 1 || TPW == 2), "8 wavefronts share the tile evenly");
+  constexpr int NTN = H / 32, MT = BM / 32, TILES = MT * NTN, TPW = TILES / 4;
+  static_assert(TILES % 4 == 0 && (TPW == 1 || TPW == 2), "4 wavefronts share the tile evenly");
   static_assert(TPW == 1 || NTN % 2 == 0, "two tiles of a wavefront share their rows");
-  constexpr int WV = H / 64;   // 16-byte vectors of a weight chunk per thread
-  constexpr int XS = BM / 16;  // scalars of an X chunk per thread
-  constexpr int XV = BM / 64;  // 16-byte vectors of an X chunk per thread
+  constexpr int NTH = 256;
+  constexpr int WV = H / 32;   // 16-byte vectors of a weight chunk per thread
+  constexpr int XS = BM / 8;   // scalars of an X chunk per thread
+  constexpr int XV = BM / 32;  // 16-byte vectors of an X chunk per thread
   __shared__ __attribute__((aligned(16))) Lds L;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -56,7 +57,7 @@ __global__ void __launch_bounds__(512) fused_forward_kernel(FusedFwdArgs a, Fini
   const int mt = (wave * TPW) / NTN, nt0 = (wave * TPW) % NTN;  // this wavefront's tiles: (mt, nt0 .. nt0+TPW-1)
 
   // output-layer gradient, persistent over the tiles of this workgroup: thread -> hidden unit tid % H
-  constexpr int HPARTS = 512 / H;         // threads per hidden unit
+  constexpr int HPARTS = (256 / H) > 0 ? (256 / H) : 1;  // threads per hidden unit
   constexpr int SPP = BM / HPARTS;        // samples each of them sums per tile
   float gw[NOUT], gb[NOUT], st[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -73,10 +74,10 @@ __global__ void __launch_bounds__(512) fused_forward_kernel(FusedFwdArgs a, Fini
     const float* xrow[XS];
     if (a.xvec) {
 #pragma unroll
-      for (int p = 0; p < XV; ++p) xrow[p] = a.X.ptr(min(s0 + ((tid + 512 * p) >> 3), a.S - 1));
+      for (int p = 0; p < XV; ++p) xrow[p] = a.X.ptr(min(s0 + ((tid + NTH * p) >> 3), a.S - 1));
     } else {
 #pragma unroll
-      for (int p = 0; p < XS; ++p) xrow[p] = a.X.ptr(min(s0 + ((tid + 512 * p) >> 5), a.S - 1));
+      for (int p = 0; p < XS; ++p) xrow[p] = a.X.ptr(min(s0 + ((tid + NTH * p) >> 5), a.S - 1));
     }
     float xr[XS];
     float4 wr[WV];
@@ -99,17 +100,17 @@ __global__ void __launch_bounds__(512) fused_forward_kernel(FusedFwdArgs a, Fini
       if (a.xvec) {
 #pragma unroll
         for (int p = 0; p < XV; ++p)
-          *reinterpret_cast<float4*>(&L.Xc[((tid + 512 * p) >> 3) * PX + 4 * (tid & 7)]) =
+          *reinterpret_cast<float4*>(&L.Xc[((tid + NTH * p) >> 3) * PX + 4 * (tid & 7)]) =
               make_float4(xr[4 * p], xr[4 * p + 1], xr[4 * p + 2], xr[4 * p + 3]);
       } else {
 #pragma unroll
-        for (int p = 0; p < XS; ++p) L.Xc[((tid + 512 * p) >> 5) * PX + (tid & 31)] = xr[p];
+        for (int p = 0; p < XS; ++p) L.Xc[((tid + NTH * p) >> 5) * PX + (tid & 31)] = xr[p];
       }
     };
     auto fetch_w = [&](const float* W, int k0, int K) {
 #pragma unroll
       for (int p = 0; p < WV; ++p) {
-        const int f = tid + 512 * p, row = f / (H / 4), c4 = f % (H / 4);
+        const int f = tid + NTH * p, row = f / (H / 4), c4 = f % (H / 4);
         wr[p] = (k0 + row < K) ? *reinterpret_cast<const float4*>(W + (int64_t)(k0 + row) * H + 4 * c4)
                                : make_float4(0.f, 0.f, 0.f, 0.f);
       }
@@ -117,7 +118,7 @@ __global__ void __launch_bounds__(512) fused_forward_kernel(FusedFwdArgs a, Fini
     auto stage_w = [&]() {
 #pragma unroll
       for (int p = 0; p < WV; ++p) {
-        const int f = tid + 512 * p;
+        const int f = tid + NTH * p;
         *reinterpret_cast<float4*>(&L.Ws[(f / (H / 4)) * H + 4 * (f % (H / 4))]) = wr[p];
       }
     };
@@ -279,20 +280,7 @@ __global__ void __launch_bounds__(512) fused_forward_kernel(FusedFwdArgs a, Fini
     const int i = tid % H;
 #pragma unroll
     for (int k = 0; k < NOUT; ++k) atomicAdd(&a.gW3[i * NOUT + k], gw[k]);
-    if (tid < 64) {  // samples live in threads tid < BM; BM is 64 or 128
-#pragma unroll
-      for (int k = 0; k < NOUT; ++k) {
-        float v = gb[k];
-        for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-        if (lane == 0) atomicAdd(&a.gb3[k], v);
-      }
-#pragma unroll
-      for (int k = 0; k < 5; ++k) {
-        float v = st[k];
-        for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-        if (lane == 0 && v != 0.f) atomicAdd(&a.stats[k], v);
-      }
-    } else if (tid < BM) {
+    if (wave == 0) {  // samples live in threads tid < BM <= 64
 #pragma unroll
       for (int k = 0; k < NOUT; ++k) {
         float v = gb[k];
@@ -309,19 +297,19 @@ __global__ void __launch_bounds__(512) fused_forward_kernel(FusedFwdArgs a, Fini
   }
 }
 
-// Which (H, BM) pairs exist: H = 64 -> BM 128; H = 128 or 256 -> BM 64.
+// Which (H, BM) pairs exist: H = 64 -> BM 64; H = 128 or 256 -> BM 32.
 inline bool fused_forward_supported(int H) { return H == 64 || H == 128 || H == 256; }
 
 template <int NOUT, bool TRAIN, class Finish>
 inline void launch_fused_forward(int H, const FusedFwdArgs& a, const Finish& fin, hipStream_t s) {
   // algorithmic flops of the two hidden layers
   TimedLaunch timed(KC_GEMM_NN, 2.0 * (double)a.S * ((double)a.Din * H + (double)H * H), s);
-  const int64_t bm = H == 64 ? 128 : 64;
+  const int64_t bm = H == 64 ? 64 : 32;
   const int64_t tiles = (a.S + bm - 1) / bm;
-  const unsigned grid = (unsigned)std::min<int64_t>(tiles, H == 256 ? 256 : 512);
-  if (H == 64) hipLaunchKernelGGL((fused_forward_kernel<64, 128, NOUT, TRAIN, Finish>), dim3(grid), dim3(512), 0, s, a, fin);
-  else if (H == 128) hipLaunchKernelGGL((fused_forward_kernel<128, 64, NOUT, TRAIN, Finish>), dim3(grid), dim3(512), 0, s, a, fin);
-  else hipLaunchKernelGGL((fused_forward_kernel<256, 64, NOUT, TRAIN, Finish>), dim3(grid), dim3(512), 0, s, a, fin);
+  const unsigned grid = (unsigned)std::min<int64_t>(tiles, TRAIN ? 1024 : 2048);  // persistent when training (register-resident W3 gradient)
+  if (H == 64) hipLaunchKernelGGL((fused_forward_kernel<64, 64, NOUT, TRAIN, Finish>), dim3(grid), dim3(256), 0, s, a, fin);
+  else if (H == 128) hipLaunchKernelGGL((fused_forward_kernel<128, 32, NOUT, TRAIN, Finish>), dim3(grid), dim3(256), 0, s, a, fin);
+  else hipLaunchKernelGGL((fused_forward_kernel<256, 32, NOUT, TRAIN, Finish>), dim3(grid), dim3(256), 0, s, a, fin);
 }
 
 }  // namespace marl
