@@ -115,7 +115,7 @@ def main():
         ms, n, work = classes[name]
         if n == 0 or ms <= 0:
             return None
-        if name.startswith("gemm"):
+        if name.startswith("gemm") or name == "fused_train":
             a = work / (ms * 1e-3) / 1e12
             return {"kernel": name, "bound": "mfma", "achieved": a, "peak": mfma_peak, "unit": "TFLOP/s",
                     "frac": a / mfma_peak, "traffic": None, "launches": n, "avg_us": 1e3 * ms / n,

@@ -206,7 +206,7 @@ def compute_gae(cfg, traj, stream=None):
     _check(lib().marl_compute_gae(C.byref(make_config(cfg)), traj.c(), _stream(stream)))
 
 
-KERNEL_CLASSES = {"gemm_nn": 0, "gemm_nt": 1, "gemm_tn": 2, "env_step": 3, "gae": 4}
+KERNEL_CLASSES = {"gemm_nn": 0, "gemm_nt": 1, "gemm_tn": 2, "env_step": 3, "gae": 4, "fused_train": 5}
 
 
 def timing_enable(on):

@@ -107,7 +107,7 @@ __device__ __forceinline__ float rand_unit(uint32_t x) { return ((float)(x >> 9)
 constexpr uint32_t kStreamReset = 1, kStreamSample = 2;
 
 // ---- optional per-kernel timing with HIP events (measurement hook, host side) -----------------
-enum KernelClass { KC_GEMM_NN = 0, KC_GEMM_NT = 1, KC_GEMM_TN = 2, KC_ENV_STEP = 3, KC_GAE = 4, KC_HEAD = 5, KC_COUNT = 6 };
+enum KernelClass { KC_GEMM_NN = 0, KC_GEMM_NT = 1, KC_GEMM_TN = 2, KC_ENV_STEP = 3, KC_GAE = 4, KC_FUSED_TRAIN = 5, KC_COUNT = 6 };
 bool timing_on();
 // Records an event on `s` before and after the launch bracketed by the guard's lifetime and books
 // `work` (flops or bytes) to the class.

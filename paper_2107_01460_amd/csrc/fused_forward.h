@@ -151,6 +151,7 @@ __global__ void __launch_bounds__(256, 2) fused_forward_kernel(FusedFwdArgs a, F
     zero_acc();
     fetch_x(0);
     fetch_w(a.W1, 0, a.Din);
+#pragma unroll 1
     for (int c = 0; c < nk1; ++c) {
       stage_x();
       stage_w();
@@ -180,6 +181,7 @@ __global__ void __launch_bounds__(256, 2) fused_forward_kernel(FusedFwdArgs a, F
     }
     // ---- layer 2: h2 = tanh(h1 W2 + b2), kept in registers
     zero_acc();
+#pragma unroll 1
     for (int c = 0; c < H / 32; ++c) {
       stage_w();
       __syncthreads();  // also orders the h1 tile before its first use
@@ -210,6 +212,7 @@ __global__ void __launch_bounds__(256, 2) fused_forward_kernel(FusedFwdArgs a, F
       float part[NOUT];
 #pragma unroll
       for (int k = 0; k < NOUT; ++k) part[k] = 0.f;
+#pragma unroll 4
       for (int i = grp * PER; i < (grp + 1) * PER; ++i) {
         const float h = L.Hs[s * PH + i];
 #pragma unroll
@@ -267,6 +270,7 @@ __global__ void __launch_bounds__(256, 2) fused_forward_kernel(FusedFwdArgs a, F
       // ---- gW3[i][k] += sum_s h2[s][i] dl[s][k]
       {
         const int i = tid % H, part = tid / H;
+#pragma unroll 4
         for (int s = part * SPP; s < (part + 1) * SPP; ++s) {
           const float h = L.Hs[s * PH + i];
 #pragma unroll

@@ -5,6 +5,7 @@
 #include <cmath>
 
 #include "fused_forward.h"
+#include "fused_train.h"
 #include "gemm.h"
 #include "heads.h"
 
@@ -82,12 +83,20 @@ struct ActorLoss {
   const int32_t* action;
   const float* logp_old;
   const float* adv;
-  // returns dL/dlogits in dl; adds this sample's terms to st[0..4]
-  __device__ __forceinline__ void operator()(int64_t s, const float out[kActions], float dl[kActions], float st[5]) const {
+  struct In {
+    int act;
+    float logp_old, adv;
+  };
+  // the trajectory values of minibatch sample s (separate from the arithmetic so that they can be fetched early)
+  __device__ __forceinline__ In load(int64_t s) const {
     const int64_t row = s / lc.A;
     const int a = (int)(s - row * lc.A);
     const int64_t src = (int64_t)lc.rows[row] * lc.A + a;
-    const int act = action[src];
+    return In{action[src], logp_old[src], adv[src]};
+  }
+  // returns dL/dlogits in dl; adds this sample's terms to st[0..4]
+  __device__ __forceinline__ void compute(const In& in, const float out[kActions], float dl[kActions], float st[5]) const {
+    const int act = in.act;
     float m = out[0];
 #pragma unroll
     for (int k = 1; k < kActions; ++k) m = fmaxf(m, out[k]);
@@ -103,14 +112,14 @@ struct ActorLoss {
       ent -= p[k] * lp[k];
       logp_new = (k == act) ? lp[k] : logp_new;
     }
-    float advn = adv[src];
+    float advn = in.adv;
     if (lc.normalize) {
       const double B = (double)lc.rows_mb * lc.A;
       const float mean = (float)(lc.sc->adv_sum / B);
       const float rstd = (float)(1.0 / (sqrt(lc.sc->adv_sq / B) + 1e-8));
       advn = (advn - mean) * rstd;
     }
-    const float log_ratio = logp_new - logp_old[src];
+    const float log_ratio = logp_new - in.logp_old;
     const float ratio = expf(log_ratio);
     const float rc = fminf(fmaxf(ratio, 1.0f - lc.clip_eps), 1.0f + lc.clip_eps);
     const float s1 = ratio * advn, s2 = rc * advn;
@@ -123,6 +132,9 @@ struct ActorLoss {
 #pragma unroll
     for (int k = 0; k < kActions; ++k) dl[k] = dlogp * ((k == act ? 1.0f : 0.0f) - p[k]) + ec * p[k] * (lp[k] + ent);
   }
+  __device__ __forceinline__ void operator()(int64_t s, const float out[kActions], float dl[kActions], float st[5]) const {
+    compute(load(s), out, dl, st);
+  }
 };
 
 struct CriticLoss {
@@ -130,6 +142,28 @@ struct CriticLoss {
   const float* ret;
   const float* v_old;
   int per_row;  // samples of the trajectory that share this prediction: A (central critic) or 1
+  struct In {
+    float ret[kMaxAgents], v_old[kMaxAgents];
+  };
+  __device__ __forceinline__ In load(int64_t s) const {
+    In in;
+    if (per_row == 1) {
+      const int64_t row = s / lc.A;
+      const int a = (int)(s - row * lc.A);
+      const int64_t src = (int64_t)lc.rows[row] * lc.A + a;
+      in.ret[0] = ret[src];
+      in.v_old[0] = v_old[src];
+    } else {
+      const int64_t src0 = (int64_t)lc.rows[s] * lc.A;
+#pragma unroll
+      for (int a = 0; a < kMaxAgents; ++a)
+        if (a < lc.A) {
+          in.ret[a] = ret[src0 + a];
+          in.v_old[a] = v_old[src0 + a];
+        }
+    }
+    return in;
+  }
   __device__ __forceinline__ float term(float v, float r, float vo, float* loss) const {
     const float e = v - r;
     float l = 0.5f * e * e, g = e;
@@ -145,18 +179,15 @@ struct CriticLoss {
     *loss += l * lc.inv_B;
     return g;
   }
-  __device__ __forceinline__ void operator()(int64_t s, const float out[1], float dl[1], float st[5]) const {
+  __device__ __forceinline__ void compute(const In& in, const float out[1], float dl[1], float st[5]) const {
     float g = 0.f;
-    if (per_row == 1) {
-      const int64_t row = s / lc.A;
-      const int a = (int)(s - row * lc.A);
-      const int64_t src = (int64_t)lc.rows[row] * lc.A + a;
-      g = term(out[0], ret[src], v_old[src], &st[1]);
-    } else {
-      const int64_t src0 = (int64_t)lc.rows[s] * lc.A;
-      for (int a = 0; a < lc.A; ++a) g += term(out[0], ret[src0 + a], v_old[src0 + a], &st[1]);
-    }
+#pragma unroll
+    for (int a = 0; a < kMaxAgents; ++a)
+      if (a < per_row) g += term(out[0], in.ret[a], in.v_old[a], &st[1]);
     dl[0] = g * lc.vf_coef * lc.inv_B;
+  }
+  __device__ __forceinline__ void operator()(int64_t s, const float out[1], float dl[1], float st[5]) const {
+    compute(load(s), out, dl, st);
   }
 };
 
@@ -459,43 +490,65 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
       const bool fused_a = fused_forward_supported(d.Ha);
       {
         ActorLoss fn{lc, tr.action, tr.logp, tr.adv};
-        if (fused_a) {
-          FusedFwdArgs fa{};
-          fa.X = Xa; fa.S = Sa; fa.Din = d.D; fa.xvec = aligned16(Xa.base) && Xa.ld % 4 == 0 && d.D % 4 == 0;
-          fa.W1 = eff + oa.W1; fa.b1 = eff + oa.b1; fa.W2 = eff + oa.W2; fa.b2 = eff + oa.b2; fa.W3 = eff + oa.W3;
-          fa.b3 = eff + oa.b3; fa.h1_out = w.h1a; fa.dz2_out = w.h2a; fa.gW3 = w.grad + ga.W3; fa.gb3 = w.grad + ga.b3;
-          fa.stats = w.sc->acc; fa.round_bf16 = d.bf16;
-          launch_fused_forward<kActions, true>(d.Ha, fa, fn, s);
+        if (fused_train_supported(d.Ha, d.D)) {
+          FusedTrainArgs ta{};
+          ta.X = Xa; ta.S = Sa; ta.Din = d.D; ta.px = fused_train_px(d.D);
+          ta.W1 = eff + oa.W1; ta.b1 = eff + oa.b1; ta.W2 = eff + oa.W2; ta.b2 = eff + oa.b2; ta.W3 = eff + oa.W3;
+          ta.b3 = eff + oa.b3; ta.gW1 = w.grad + ga.W1; ta.gb1 = w.grad + ga.b1; ta.gW2 = w.grad + ga.W2;
+          ta.gb2 = w.grad + ga.b2; ta.gW3 = w.grad + ga.W3; ta.gb3 = w.grad + ga.b3; ta.stats = w.sc->acc;
+          ta.round_bf16 = d.bf16;
+          const int32_t rc = launch_fused_train<kActions>(d.Ha, ta, fn, s);
+          if (rc != MARL_OK) return rc;
         } else {
-          mlp_hidden_forward(Xa, Sa, d.D, d.Ha, eff + oa.W1, eff + oa.b1, eff + oa.W2, eff + oa.b2, w.h1a, w.h2a, d.bf16, s);
-          const unsigned nb = (unsigned)std::min<int64_t>(2048, (Sa + kHeadTile - 1) / kHeadTile);
-          hipLaunchKernelGGL((loss_head_kernel<kActions, ActorLoss>), dim3(nb), dim3(256), 0, s, w.h2a, Sa, d.Ha,
-                             eff + oa.W3, eff + oa.b3, fn, w.dla, w.grad + ga.W3, w.grad + ga.b3, w.sc, 0.f);
+          if (fused_a) {
+            FusedFwdArgs fa{};
+            fa.X = Xa; fa.S = Sa; fa.Din = d.D; fa.xvec = aligned16(Xa.base) && Xa.ld % 4 == 0 && d.D % 4 == 0;
+            fa.W1 = eff + oa.W1; fa.b1 = eff + oa.b1; fa.W2 = eff + oa.W2; fa.b2 = eff + oa.b2; fa.W3 = eff + oa.W3;
+            fa.b3 = eff + oa.b3; fa.h1_out = w.h1a; fa.dz2_out = w.h2a; fa.gW3 = w.grad + ga.W3; fa.gb3 = w.grad + ga.b3;
+            fa.stats = w.sc->acc; fa.round_bf16 = d.bf16;
+            launch_fused_forward<kActions, true>(d.Ha, fa, fn, s);
+          } else {
+            mlp_hidden_forward(Xa, Sa, d.D, d.Ha, eff + oa.W1, eff + oa.b1, eff + oa.W2, eff + oa.b2, w.h1a, w.h2a, d.bf16, s);
+            const unsigned nb = (unsigned)std::min<int64_t>(2048, (Sa + kHeadTile - 1) / kHeadTile);
+            hipLaunchKernelGGL((loss_head_kernel<kActions, ActorLoss>), dim3(nb), dim3(256), 0, s, w.h2a, Sa, d.Ha,
+                               eff + oa.W3, eff + oa.b3, fn, w.dla, w.grad + ga.W3, w.grad + ga.b3, w.sc, 0.f);
+          }
+          mlp_backward<kActions>(Xa, Sa, d.D, d.Ha, eff + oa.W2, eff + oa.W3, w.h1a, w.h2a, w.dz1a, w.dla, w.grad + ga.W1,
+                                 w.grad + ga.b1, w.grad + ga.W2, w.grad + ga.b2, d.bf16, fused_a, s);
         }
       }
-      mlp_backward<kActions>(Xa, Sa, d.D, d.Ha, eff + oa.W2, eff + oa.W3, w.h1a, w.h2a, w.dz1a, w.dla, w.grad + ga.W1,
-                             w.grad + ga.b1, w.grad + ga.W2, w.grad + ga.b2, d.bf16, fused_a, s);
       // ---- critic
       const RowSrc Xc{tr.obs, d.Dc, rows, d.central ? 1 : d.A, Sc};
       const bool fused_c = fused_forward_supported(d.Hc);
       {
         CriticLoss fn{lc, tr.ret, tr.value, d.central ? d.A : 1};
-        if (fused_c) {
-          FusedFwdArgs fa{};
-          fa.X = Xc; fa.S = Sc; fa.Din = d.Dc; fa.xvec = aligned16(Xc.base) && Xc.ld % 4 == 0 && d.Dc % 4 == 0;
-          fa.W1 = eff + oc.W1; fa.b1 = eff + oc.b1; fa.W2 = eff + oc.W2; fa.b2 = eff + oc.b2; fa.W3 = eff + oc.W3;
-          fa.b3 = eff + oc.b3; fa.h1_out = w.h1c; fa.dz2_out = w.h2c; fa.gW3 = w.grad + gc.W3; fa.gb3 = w.grad + gc.b3;
-          fa.stats = w.sc->acc; fa.round_bf16 = d.bf16;
-          launch_fused_forward<1, true>(d.Hc, fa, fn, s);
+        if (fused_train_supported(d.Hc, d.Dc)) {
+          FusedTrainArgs ta{};
+          ta.X = Xc; ta.S = Sc; ta.Din = d.Dc; ta.px = fused_train_px(d.Dc);
+          ta.W1 = eff + oc.W1; ta.b1 = eff + oc.b1; ta.W2 = eff + oc.W2; ta.b2 = eff + oc.b2; ta.W3 = eff + oc.W3;
+          ta.b3 = eff + oc.b3; ta.gW1 = w.grad + gc.W1; ta.gb1 = w.grad + gc.b1; ta.gW2 = w.grad + gc.W2;
+          ta.gb2 = w.grad + gc.b2; ta.gW3 = w.grad + gc.W3; ta.gb3 = w.grad + gc.b3; ta.stats = w.sc->acc;
+          ta.round_bf16 = d.bf16;
+          const int32_t rc = launch_fused_train<1>(d.Hc, ta, fn, s);
+          if (rc != MARL_OK) return rc;
         } else {
-          mlp_hidden_forward(Xc, Sc, d.Dc, d.Hc, eff + oc.W1, eff + oc.b1, eff + oc.W2, eff + oc.b2, w.h1c, w.h2c, d.bf16, s);
-          const unsigned nb = (unsigned)std::min<int64_t>(2048, (Sc + kHeadTile - 1) / kHeadTile);
-          hipLaunchKernelGGL((loss_head_kernel<1, CriticLoss>), dim3(nb), dim3(256), 0, s, w.h2c, Sc, d.Hc, eff + oc.W3,
-                             eff + oc.b3, fn, w.dlc, w.grad + gc.W3, w.grad + gc.b3, w.sc, 0.f);
+          if (fused_c) {
+            FusedFwdArgs fa{};
+            fa.X = Xc; fa.S = Sc; fa.Din = d.Dc; fa.xvec = aligned16(Xc.base) && Xc.ld % 4 == 0 && d.Dc % 4 == 0;
+            fa.W1 = eff + oc.W1; fa.b1 = eff + oc.b1; fa.W2 = eff + oc.W2; fa.b2 = eff + oc.b2; fa.W3 = eff + oc.W3;
+            fa.b3 = eff + oc.b3; fa.h1_out = w.h1c; fa.dz2_out = w.h2c; fa.gW3 = w.grad + gc.W3; fa.gb3 = w.grad + gc.b3;
+            fa.stats = w.sc->acc; fa.round_bf16 = d.bf16;
+            launch_fused_forward<1, true>(d.Hc, fa, fn, s);
+          } else {
+            mlp_hidden_forward(Xc, Sc, d.Dc, d.Hc, eff + oc.W1, eff + oc.b1, eff + oc.W2, eff + oc.b2, w.h1c, w.h2c, d.bf16, s);
+            const unsigned nb = (unsigned)std::min<int64_t>(2048, (Sc + kHeadTile - 1) / kHeadTile);
+            hipLaunchKernelGGL((loss_head_kernel<1, CriticLoss>), dim3(nb), dim3(256), 0, s, w.h2c, Sc, d.Hc, eff + oc.W3,
+                               eff + oc.b3, fn, w.dlc, w.grad + gc.W3, w.grad + gc.b3, w.sc, 0.f);
+          }
+          mlp_backward<1>(Xc, Sc, d.Dc, d.Hc, eff + oc.W2, eff + oc.W3, w.h1c, w.h2c, w.dz1c, w.dlc, w.grad + gc.W1,
+                          w.grad + gc.b1, w.grad + gc.W2, w.grad + gc.b2, d.bf16, fused_c, s);
         }
       }
-      mlp_backward<1>(Xc, Sc, d.Dc, d.Hc, eff + oc.W2, eff + oc.W3, w.h1c, w.h2c, w.dz1c, w.dlc, w.grad + gc.W1,
-                      w.grad + gc.b1, w.grad + gc.W2, w.grad + gc.b2, d.bf16, fused_c, s);
       // ---- clip + Adam
       hipLaunchKernelGGL(grad_norm_kernel, dim3((unsigned)std::min<int64_t>(256, (d.P + 255) / 256)), dim3(256), 0, s,
                          w.grad, d.P, w.sc);
