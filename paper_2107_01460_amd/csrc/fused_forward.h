@@ -37,6 +37,7 @@ struct FusedFwdLds {
   float Hs[BM * PH];
   float red[GROUPS * BM * NOUT];
   float dls[BM * 8];  // dL/d(outputs) of the tile, rows padded to 8 with zeros (MFMA operand)
+  float W3s[H * NOUT];
 };
 
 template <int H, int BM, int NOUT, bool TRAIN, class Finish>
@@ -63,6 +64,7 @@ __global__ void __launch_bounds__(256, 2) fused_forward_kernel(FusedFwdArgs a, F
 #pragma unroll
   for (int k = 0; k < NOUT; ++k) gw[k] = gb[k] = 0.f;
 
+  for (int i = tid; i < H * NOUT; i += NTH) L.W3s[i] = a.W3[i];  // ordered before its first use by the barriers of layer 1
   const int nk1 = (a.Din + 31) / 32;
   const int64_t ntiles = (a.S + BM - 1) / BM;
   for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
@@ -216,7 +218,7 @@ __global__ void __launch_bounds__(256, 2) fused_forward_kernel(FusedFwdArgs a, F
       for (int i = grp * PER; i < (grp + 1) * PER; ++i) {
         const float h = L.Hs[s * PH + i];
 #pragma unroll
-        for (int k = 0; k < NOUT; ++k) part[k] = fmaf(h, a.W3[i * NOUT + k], part[k]);
+        for (int k = 0; k < NOUT; ++k) part[k] = fmaf(h, L.W3s[i * NOUT + k], part[k]);
       }
 #pragma unroll
       for (int k = 0; k < NOUT; ++k) L.red[(grp * BM + s) * NOUT + k] = part[k];
@@ -251,7 +253,7 @@ __global__ void __launch_bounds__(256, 2) fused_forward_kernel(FusedFwdArgs a, F
         const int n = (nt0 + q) * 32 + lo;
         float bf[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) bf[j] = (4 * hi + j < NOUT) ? a.W3[n * NOUT + (4 * hi + j < NOUT ? 4 * hi + j : 0)] : 0.f;
+        for (int j = 0; j < 4; ++j) bf[j] = (4 * hi + j < NOUT) ? L.W3s[n * NOUT + (4 * hi + j < NOUT ? 4 * hi + j : 0)] : 0.f;
         floatx16 gacc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) gacc[r] = 0.f;

@@ -45,6 +45,7 @@ __global__ void __launch_bounds__(512) fused_train_kernel(FusedTrainArgs a, Loss
   float* Ws = H2 + BM * PH;                // [32][H] or [H][36]
   float* red = Ws + H * PW;                // [GROUPS][BM][NOUT]
   float* dls = red + 512 * NOUT;           // [BM][8]
+  float* W3s = dls + BM * 8;               // [H][NOUT]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lo = lane & 31, hi = lane >> 5;
@@ -56,6 +57,7 @@ __global__ void __launch_bounds__(512) fused_train_kernel(FusedTrainArgs a, Loss
   const int items1 = tiles1 * KS1;
 
   for (int i = tid; i < BM * px; i += 512) Xs[i] = 0.f;  // the padding columns stay zero for good
+  for (int i = tid; i < H * NOUT; i += 512) W3s[i] = a.W3[i];
   __syncthreads();
 
   floatx16 acc1[2], acc2[2];  // dW1 / dW2 tiles of this wavefront, persistent
@@ -209,7 +211,7 @@ __global__ void __launch_bounds__(512) fused_train_kernel(FusedTrainArgs a, Loss
       for (int i = grp * PER; i < (grp + 1) * PER; ++i) {
         const float h = H2[s * PH + i];
 #pragma unroll
-        for (int k = 0; k < NOUT; ++k) part[k] = fmaf(h, a.W3[i * NOUT + k], part[k]);
+        for (int k = 0; k < NOUT; ++k) part[k] = fmaf(h, W3s[i * NOUT + k], part[k]);
       }
 #pragma unroll
       for (int k = 0; k < NOUT; ++k) red[(grp * BM + s) * NOUT + k] = part[k];
@@ -250,7 +252,7 @@ __global__ void __launch_bounds__(512) fused_train_kernel(FusedTrainArgs a, Loss
       const float af[4] = {av.x, av.y, av.z, av.w};
       float bf[4];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) bf[j] = (4 * hi + j < NOUT) ? a.W3[n * NOUT + (4 * hi + j < NOUT ? 4 * hi + j : 0)] : 0.f;
+      for (int j = 0; j < 4; ++j) bf[j] = (4 * hi + j < NOUT) ? W3s[n * NOUT + (4 * hi + j < NOUT ? 4 * hi + j : 0)] : 0.f;
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[r] = 0.f;
 #pragma unroll
@@ -407,7 +409,7 @@ inline int fused_train_px(int Din) {
 template <int H, int BM, int NOUT, int DMAX, class LossFn>
 inline int32_t launch_fused_train_inst(const FusedTrainArgs& a, const LossFn& fn, hipStream_t s) {
   auto kern = fused_train_kernel<H, BM, NOUT, DMAX, LossFn>;
-  const size_t floats = (size_t)BM * a.px + 2 * (size_t)BM * (H + 4) + (size_t)H * 36 + 512 * NOUT + BM * 8;
+  const size_t floats = (size_t)BM * a.px + 2 * (size_t)BM * (H + 4) + (size_t)H * 36 + 512 * NOUT + BM * 8 + H * NOUT;
   const size_t bytes = floats * 4;
   static bool configured = false;  // per instantiation
   if (!configured) {
