@@ -1,10 +1,11 @@
 // Grid-foraging environment on the GPU: reset, lock-step transition and egocentric observation.
 //
-// One lane per env-agent.  A workgroup owns a contiguous block of envs; their state is staged in
-// LDS, every lane resolves its own agent (target, collision, reward), lane 0 of an env settles
-// food removal, termination and the re-seeding of a finished episode.  For the observation the
-// workgroup paints one G x G occupancy grid per env into LDS and all lanes then emit window cells
-// in output order, so the stores of a wavefront are one contiguous run of 12-byte cells.
+// One lane per env-agent, and a wavefront owns floor(64 / A) whole envs.  Every lane reads the small state of
+// its env into registers and resolves the whole transition redundantly there (targets of all agents, collisions,
+// cooperative loading, termination), so no lane waits for another; only the re-seeding of a finished episode
+// goes through LDS, executed by the env's first lane.  For the observation each lane paints its own V x V x 3
+// window into a wavefront-private LDS slab, which then leaves as one contiguous, 16-byte-coalesced run: the
+// slab of a wavefront is exactly a contiguous piece of the [N][A][D] output.
 #include <algorithm>
 
 #include "common.h"
@@ -15,263 +16,299 @@ namespace {
 struct EnvParams {
   int G, A, F, L, cap, N;
   uint32_t k0, k1;
+  uint32_t inv_g20;  // ceil(2^20 / G): (r * inv_g20) >> 20 == r / G exactly for r < G*G <= 4096
 };
 
-// LDS image of one env.
-struct __attribute__((aligned(8))) EnvLds {
-  uint8_t ar[kMaxAgents], ac[kMaxAgents], al[kMaxAgents];   // agent row / col / level
-  uint8_t fr[kMaxFood], fc[kMaxFood], fl[kMaxFood];         // food row / col / level (0 = gone)
-  uint8_t tr[kMaxAgents], tc[kMaxAgents], mv[kMaxAgents];   // target cell, move-is-valid
-  uint8_t act[kMaxAgents], ld[kMaxAgents];                  // action, bitmask of foods this agent loads
-  uint16_t chosen[kMaxAgents + kMaxFood];                   // sorted cells already taken (reset only)
-  int32_t t;
-  uint32_t episode;
-  int32_t done;
-};
+// Entity packed as row | col << 8 | level << 16.
+__device__ __forceinline__ int e_row(uint32_t e) { return (int)(e & 0xff); }
+__device__ __forceinline__ int e_col(uint32_t e) { return (int)((e >> 8) & 0xff); }
+__device__ __forceinline__ int e_lvl(uint32_t e) { return (int)((e >> 16) & 0xff); }
 
-// New episode for one env, executed by a single lane on the env's LDS image.
-__device__ void reset_one(EnvLds& e, const EnvParams& p, uint32_t env) {
-  uint32_t buf[4];
-  int have = -1;
+// New episode for one env, entirely in registers (every loop is unrolled over the at most 16 entities, so the
+// arrays never leave the register file).  Draw order: A agent levels, A + F cells (agents first), F food levels;
+// draw j is word j % 4 of Philox call j / 4 of the stream (env, episode).
+template <int CA, int CF>
+__device__ __forceinline__ void reset_regs(uint32_t ag[CA], uint32_t fd[CF], const EnvParams& p,
+                                           uint32_t env, uint32_t episode) {
+  constexpr int kMaxEnt = CA + CF;
+  uint32_t buf[4] = {0, 0, 0, 0};
   int j = 0;
-  auto draw = [&](int idx) -> uint32_t {
-    const int call = idx >> 2;
-    if (call != have) {
-      philox4x32_10(env, e.episode, (uint32_t)call, kStreamReset, p.k0, p.k1, buf);
-      have = call;
-    }
-    return buf[idx & 3];
+  auto draw = [&]() -> uint32_t {
+    if ((j & 3) == 0) philox4x32_10(env, episode, (uint32_t)(j >> 2), kStreamReset, p.k0, p.k1, buf);
+    const int w = j & 3;
+    ++j;
+    return w == 0 ? buf[0] : (w == 1 ? buf[1] : (w == 2 ? buf[2] : buf[3]));
   };
-  for (int a = 0; a < p.A; ++a) e.al[a] = (uint8_t)(1u + rand_below(draw(j++), (uint32_t)p.L));
-  const int cells = p.G * p.G;
-  int cnt = 0;
-  for (int k = 0; k < p.A + p.F; ++k) {
-    int r = (int)rand_below(draw(j++), (uint32_t)(cells - k));
-    for (int q = 0; q < cnt; ++q)
-      if ((int)e.chosen[q] <= r) ++r;
-    int pos = cnt;  // insert keeping ascending order
-    while (pos > 0 && (int)e.chosen[pos - 1] > r) {
-      e.chosen[pos] = e.chosen[pos - 1];
-      --pos;
-    }
-    e.chosen[pos] = (uint16_t)r;
-    ++cnt;
-    const uint8_t row = (uint8_t)(r / p.G), col = (uint8_t)(r - (r / p.G) * p.G);
-    if (k < p.A) {
-      e.ar[k] = row;
-      e.ac[k] = col;
-    } else {
-      e.fr[k - p.A] = row;
-      e.fc[k - p.A] = col;
+  int lvl[CA];
+#pragma unroll
+  for (int a = 0; a < CA; ++a) lvl[a] = 0;
+#pragma unroll
+  for (int a = 0; a < CA; ++a)
+    if (a < p.A) lvl[a] = 1 + (int)rand_below(draw(), (uint32_t)p.L);
+  // cells without replacement: the k-th entity draws r in [0, G*G - k) and takes the r-th free cell (ascending)
+  int chosen[kMaxEnt];  // ascending
+#pragma unroll
+  for (int q = 0; q < kMaxEnt; ++q) chosen[q] = 0x7fffffff;
+  const int cells = p.G * p.G, ne = p.A + p.F;
+#pragma unroll
+  for (int k = 0; k < kMaxEnt; ++k) {
+    if (k < ne) {
+      int r = (int)rand_below(draw(), (uint32_t)(cells - k));
+#pragma unroll
+      for (int q = 0; q < kMaxEnt; ++q) r += (q < k && chosen[q] <= r) ? 1 : 0;
+      int pos = 0;  // entries smaller than r
+#pragma unroll
+      for (int q = 0; q < kMaxEnt; ++q) pos += (q < k && chosen[q] < r) ? 1 : 0;
+#pragma unroll
+      for (int q = kMaxEnt - 1; q >= 1; --q) chosen[q] = (q > pos) ? chosen[q - 1] : chosen[q];
+#pragma unroll
+      for (int q = 0; q < kMaxEnt; ++q) chosen[q] = (q == pos) ? r : chosen[q];
+      const uint32_t row = ((uint32_t)r * p.inv_g20) >> 20, col = (uint32_t)r - row * (uint32_t)p.G;
+      const uint32_t cell = row | (col << 8);
+#pragma unroll
+      for (int a = 0; a < CA; ++a)
+        if (k == a) ag[a] = cell | ((uint32_t)lvl[a] << 16);
+#pragma unroll
+      for (int f = 0; f < CF; ++f)
+        if (k == p.A + f) fd[f] = cell;
     }
   }
-  // summed level of the (at most four) strongest agents
+  // food level in 1..Lsum, Lsum = summed level of the (at most four) strongest agents
   int lsum = 0;
   uint32_t used = 0;
-  const int take = p.A < 4 ? p.A : 4;
-  for (int k = 0; k < take; ++k) {
-    int best = -1, bl = 0;
-    for (int a = 0; a < p.A; ++a)
-      if (!((used >> a) & 1u) && (int)e.al[a] > bl) {
-        bl = e.al[a];
-        best = a;
-      }
-    used |= 1u << best;
-    lsum += bl;
+#pragma unroll
+  for (int k = 0; k < (CA < 4 ? CA : 4); ++k) {
+    int best = 0, bl = 0;
+#pragma unroll
+    for (int a = 0; a < CA; ++a) {
+      const bool better = !((used >> a) & 1u) && lvl[a] > bl;
+      bl = better ? lvl[a] : bl;
+      best = better ? a : best;
+    }
+    if (k < p.A) {
+      used |= 1u << best;
+      lsum += bl;
+    }
   }
-  for (int f = 0; f < p.F; ++f) e.fl[f] = (uint8_t)(1u + rand_below(draw(j++), (uint32_t)lsum));
-  e.t = 0;
+#pragma unroll
+  for (int f = 0; f < CF; ++f)
+    if (f < p.F) fd[f] |= (1u + rand_below(draw(), (uint32_t)lsum)) << 16;
 }
 
 __global__ void __launch_bounds__(64) env_reset_kernel(EnvParams p, marl_env_state st) {
-  __shared__ EnvLds lds[64];
   const int n = blockIdx.x * 64 + threadIdx.x;
   if (n >= p.N) return;
-  EnvLds& e = lds[threadIdx.x];
-  e.episode = 0;
-  reset_one(e, p, (uint32_t)n);
-  for (int a = 0; a < p.A; ++a) {
-    st.agent_row[(size_t)a * p.N + n] = e.ar[a];
-    st.agent_col[(size_t)a * p.N + n] = e.ac[a];
-    st.agent_lvl[(size_t)a * p.N + n] = e.al[a];
-  }
-  for (int f = 0; f < p.F; ++f) {
-    st.food_row[(size_t)f * p.N + n] = e.fr[f];
-    st.food_col[(size_t)f * p.N + n] = e.fc[f];
-    st.food_lvl[(size_t)f * p.N + n] = e.fl[f];
-  }
+  uint32_t ag[kMaxAgents], fd[kMaxFood];
+  reset_regs<kMaxAgents, kMaxFood>(ag, fd, p, (uint32_t)n, 0u);
+#pragma unroll
+  for (int a = 0; a < kMaxAgents; ++a)
+    if (a < p.A) {
+      st.agent_row[(size_t)a * p.N + n] = (uint8_t)e_row(ag[a]);
+      st.agent_col[(size_t)a * p.N + n] = (uint8_t)e_col(ag[a]);
+      st.agent_lvl[(size_t)a * p.N + n] = (uint8_t)e_lvl(ag[a]);
+    }
+#pragma unroll
+  for (int f = 0; f < kMaxFood; ++f)
+    if (f < p.F) {
+      st.food_row[(size_t)f * p.N + n] = (uint8_t)e_row(fd[f]);
+      st.food_col[(size_t)f * p.N + n] = (uint8_t)e_col(fd[f]);
+      st.food_lvl[(size_t)f * p.N + n] = (uint8_t)e_lvl(fd[f]);
+    }
   st.t_in_ep[n] = 0;
   st.episode_id[n] = 0;
 }
 
-// Dynamic LDS: EnvLds[epb] | uint32 sample_info[epb*A] | uint16 grid[epb][G*G]
-template <int V>
-__global__ void __launch_bounds__(256) env_step_kernel(EnvParams p, marl_env_state st, const int32_t* __restrict__ actions,
-                                                       float* __restrict__ obs, float* __restrict__ reward,
-                                                       uint8_t* __restrict__ done, int epb, int do_step) {
+// Dynamic LDS per workgroup of NW wavefronts: float slab[NW][64 * D]
+// CA / CF: compile-time capacity for agents / food (every loop over entities is unrolled to it)
+template <int V, int NW, int CA, int CF>
+__global__ void __launch_bounds__(64 * NW) env_step_kernel(EnvParams p, marl_env_state st,
+                                                            const int32_t* __restrict__ actions, float* __restrict__ obs,
+                                                            float* __restrict__ reward, uint8_t* __restrict__ done,
+                                                            int do_step) {
+  constexpr int D = 3 * V * V, h = (V - 1) / 2;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  EnvLds* envs = reinterpret_cast<EnvLds*>(smem);
-  uint32_t* sample_info = reinterpret_cast<uint32_t*>(smem + sizeof(EnvLds) * epb);
-  uint16_t* grid = reinterpret_cast<uint16_t*>(sample_info + epb * p.A);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int ew = 64 / p.A;  // envs per wavefront
+  float* slab = reinterpret_cast<float*>(smem) + (size_t)wave * 64 * D;
 
-  const int tid = threadIdx.x;
-  const int n0 = blockIdx.x * epb;
-  const int nenv = min(epb, p.N - n0);
-  const int le = tid / p.A, a = tid - le * p.A;
-  const bool active = le < nenv;
-  const int n = n0 + le;
+  const int le = lane / p.A, a = lane - le * p.A;
+  const int64_t wave_env0 = ((int64_t)blockIdx.x * NW + wave) * ew;
+  const int64_t n = wave_env0 + le;
+  const bool active = le < ew && n < p.N;
+  const int N = p.N;
 
-  // ---- stage state in LDS
-  if (active) {
-    EnvLds& e = envs[le];
-    e.ar[a] = st.agent_row[(size_t)a * p.N + n];
-    e.ac[a] = st.agent_col[(size_t)a * p.N + n];
-    e.al[a] = st.agent_lvl[(size_t)a * p.N + n];
-    for (int f = a; f < p.F; f += p.A) {
-      e.fr[f] = st.food_row[(size_t)f * p.N + n];
-      e.fc[f] = st.food_col[(size_t)f * p.N + n];
-      e.fl[f] = st.food_lvl[(size_t)f * p.N + n];
+  // ---- the env's state, in registers.  All loads are issued branch-free (clamped indices) so that they are in
+  // flight together; entries past A / F and inactive lanes are masked afterwards.
+  uint32_t ag[CA], fd[CF];
+  int act[CA];
+  const size_t nn = active ? (size_t)n : 0;
+  {
+    uint32_t r8[CA], c8[CA], l8[CA], fr8[CF], fc8[CF], fl8[CF];
+    int a32[CA];
+#pragma unroll
+    for (int b = 0; b < CA; ++b) {
+      const size_t i = (size_t)min(b, p.A - 1) * N + nn;
+      r8[b] = st.agent_row[i];
+      c8[b] = st.agent_col[i];
+      l8[b] = st.agent_lvl[i];
+      a32[b] = do_step ? actions[nn * p.A + min(b, p.A - 1)] : 0;
     }
-    if (do_step) e.act[a] = (uint8_t)actions[(size_t)n * p.A + a];
-    if (a == 0) {
-      e.t = st.t_in_ep[n];
-      e.episode = st.episode_id[n];
-      e.done = 0;
+#pragma unroll
+    for (int f = 0; f < CF; ++f) {
+      const size_t i = (size_t)min(f, p.F - 1) * N + nn;
+      fr8[f] = st.food_row[i];
+      fc8[f] = st.food_col[i];
+      fl8[f] = st.food_lvl[i];
     }
+#pragma unroll
+    for (int b = 0; b < CA; ++b) {
+      const bool on = active && b < p.A;
+      ag[b] = on ? (r8[b] | (c8[b] << 8) | (l8[b] << 16)) : 0xffffu;  // off-grid: never matches a cell
+      act[b] = on ? a32[b] : 0;
+    }
+#pragma unroll
+    for (int f = 0; f < CF; ++f) fd[f] = (active && f < p.F) ? (fr8[f] | (fc8[f] << 8) | (fl8[f] << 16)) : 0xffffu;  // level 0: absent
   }
-  __syncthreads();
+  int t = st.t_in_ep[nn];
+  uint32_t episode = st.episode_id[nn];
 
+  bool dn = false;
   if (do_step) {
-    int r0 = 0, c0 = 0, act = 0;
-    // ---- targets against the start-of-step state, loader flags
-    if (active) {
-      EnvLds& e = envs[le];
-      r0 = e.ar[a]; c0 = e.ac[a]; act = e.act[a];
-      int nr = r0 + (act == 2) - (act == 1), nc = c0 + (act == 4) - (act == 3);
-      bool ok = (act >= 1 && act <= 4) && nr >= 0 && nr < p.G && nc >= 0 && nc < p.G;
-      for (int b = 0; b < p.A; ++b) ok = ok && !((int)e.ar[b] == nr && (int)e.ac[b] == nc);
-      uint32_t ldmask = 0;
-      for (int f = 0; f < p.F; ++f) {
-        const int fl = e.fl[f], fr = e.fr[f], fc = e.fc[f];
-        ok = ok && !(fl != 0 && fr == nr && fc == nc);
-        const int dist = abs(r0 - fr) + abs(c0 - fc);
-        if (fl != 0 && act == 5 && dist == 1) ldmask |= 1u << f;
-      }
-      e.mv[a] = ok;
-      e.tr[a] = (uint8_t)(ok ? nr : r0);
-      e.tc[a] = (uint8_t)(ok ? nc : c0);
-      e.ld[a] = (uint8_t)ldmask;
+    // ---- targets of every agent against the start-of-step state
+    uint32_t tgt[CA];  // target cell (row | col << 8), 0xffff when the agent does not move
+#pragma unroll
+    for (int b = 0; b < CA; ++b) {
+      const int ac = act[b];
+      const int nr = e_row(ag[b]) + (ac == 2) - (ac == 1), nc = e_col(ag[b]) + (ac == 4) - (ac == 3);
+      bool ok = b < p.A && ac >= 1 && ac <= 4 && nr >= 0 && nr < p.G && nc >= 0 && nc < p.G;
+      const uint32_t cell = (uint32_t)nr | ((uint32_t)nc << 8);
+#pragma unroll
+      for (int o = 0; o < CA; ++o) ok = ok && (ag[o] & 0xffffu) != cell;
+#pragma unroll
+      for (int f = 0; f < CF; ++f) ok = ok && !(e_lvl(fd[f]) != 0 && (fd[f] & 0xffffu) == cell);
+      tgt[b] = ok ? cell : 0xffffu;
     }
-    __syncthreads();
-    // ---- collisions and rewards (read-only on the LDS image)
-    int new_r = r0, new_c = c0;
-    uint32_t eaten = 0;
-    if (active) {
-      const EnvLds& e = envs[le];
-      bool go = e.mv[a];
-      for (int b = 0; b < p.A; ++b)
-        if (b != a && e.mv[b] && e.tr[b] == e.tr[a] && e.tc[b] == e.tc[a]) go = false;
-      if (go) {
-        new_r = e.tr[a];
-        new_c = e.tc[a];
-      }
-      float rew = 0.0f;
-      const int my_lvl = e.al[a];
-      const uint32_t my_ld = e.ld[a];
-      for (int f = 0; f < p.F; ++f) {
-        const int fl = e.fl[f];
-        if (fl == 0) continue;
+    // ---- cooperative loading: summed level of the adjacent loaders of each food
+    float rew = 0.f;
+    uint32_t mine = 0;
+#pragma unroll
+    for (int b = 0; b < CA; ++b) mine = (b == a) ? ag[b] : mine;
+    int my_act = 0;
+#pragma unroll
+    for (int b = 0; b < CA; ++b) my_act = (b == a) ? act[b] : my_act;
+    bool any_food = false;
+#pragma unroll
+    for (int f = 0; f < CF; ++f) {
+      const int fl = e_lvl(fd[f]);
+      if (f < p.F && fl != 0) {
+        const int fr = e_row(fd[f]), fc = e_col(fd[f]);
         int lsum = 0;
-        for (int b = 0; b < p.A; ++b) lsum += ((e.ld[b] >> f) & 1) ? (int)e.al[b] : 0;
+#pragma unroll
+        for (int b = 0; b < CA; ++b) {
+          const int dist = abs(e_row(ag[b]) - fr) + abs(e_col(ag[b]) - fc);
+          lsum += (b < p.A && act[b] == 5 && dist == 1) ? e_lvl(ag[b]) : 0;
+        }
         if (lsum >= fl) {
-          eaten |= 1u << f;
-          if ((my_ld >> f) & 1u) rew += __fdiv_rn((float)(fl * my_lvl), (float)lsum);
+          const int mdist = abs(e_row(mine) - fr) + abs(e_col(mine) - fc);
+          if (my_act == 5 && mdist == 1) rew += __fdiv_rn((float)(fl * e_lvl(mine)), (float)lsum);
+          fd[f] &= 0xffffu;  // collected: level 0
+        } else {
+          any_food = true;
         }
       }
+    }
+    // ---- movement: two or more valid movers onto one cell all stay
+    uint32_t moved[CA];
+#pragma unroll
+    for (int b = 0; b < CA; ++b) {
+      bool go = tgt[b] != 0xffffu;
+#pragma unroll
+      for (int o = 0; o < CA; ++o) go = go && (o == b || tgt[o] != tgt[b]);
+      moved[b] = go ? ((ag[b] & 0xff0000u) | tgt[b]) : ag[b];
+    }
+#pragma unroll
+    for (int b = 0; b < CA; ++b) ag[b] = moved[b];
+    // ---- termination
+    t += 1;
+    dn = active && (!any_food || t == p.cap);
+    if (active) {
       reward[(size_t)n * p.A + a] = rew;
+      if (a == 0) done[n] = dn ? 1 : 0;
     }
-    __syncthreads();
+    // ---- auto-reset: every lane of a finished env re-seeds it in its own registers (same result in each)
+    if (dn) {
+      episode += 1;
+      reset_regs<CA, CF>(ag, fd, p, (uint32_t)n, episode);
+      t = 0;
+    }
+    // ---- write the state back: every lane its own agent, the env's lanes share the food
     if (active) {
-      EnvLds& e = envs[le];
-      e.ar[a] = (uint8_t)new_r;
-      e.ac[a] = (uint8_t)new_c;
-    }
-    __syncthreads();
-    // ---- food removal, termination, auto-reset: one lane per env
-    if (active && a == 0) {
-      EnvLds& e = envs[le];
-      bool any = false;
-      for (int f = 0; f < p.F; ++f) {
-        if ((eaten >> f) & 1u) e.fl[f] = 0;
-        any = any || e.fl[f] != 0;
-      }
-      e.t += 1;
-      const bool dn = !any || e.t == p.cap;
-      done[n] = dn ? 1 : 0;
-      if (dn) {
-        e.episode += 1;
-        reset_one(e, p, (uint32_t)n);
-      }
-      e.done = dn;
-    }
-    __syncthreads();
-    // ---- write the state back
-    if (active) {
-      const EnvLds& e = envs[le];
-      st.agent_row[(size_t)a * p.N + n] = e.ar[a];
-      st.agent_col[(size_t)a * p.N + n] = e.ac[a];
-      if (e.done) st.agent_lvl[(size_t)a * p.N + n] = e.al[a];
-      for (int f = a; f < p.F; f += p.A) {
-        st.food_lvl[(size_t)f * p.N + n] = e.fl[f];
-        if (e.done) {
-          st.food_row[(size_t)f * p.N + n] = e.fr[f];
-          st.food_col[(size_t)f * p.N + n] = e.fc[f];
+      uint32_t me = 0;
+#pragma unroll
+      for (int b = 0; b < CA; ++b) me = (b == a) ? ag[b] : me;
+      st.agent_row[(size_t)a * N + n] = (uint8_t)e_row(me);
+      st.agent_col[(size_t)a * N + n] = (uint8_t)e_col(me);
+      if (dn) st.agent_lvl[(size_t)a * N + n] = (uint8_t)e_lvl(me);
+#pragma unroll
+      for (int f = 0; f < CF; ++f)
+        if (f < p.F && (f % p.A) == a) {
+          st.food_lvl[(size_t)f * N + n] = (uint8_t)e_lvl(fd[f]);
+          if (dn) {
+            st.food_row[(size_t)f * N + n] = (uint8_t)e_row(fd[f]);
+            st.food_col[(size_t)f * N + n] = (uint8_t)e_col(fd[f]);
+          }
         }
-      }
       if (a == 0) {
-        st.t_in_ep[n] = e.t;
-        st.episode_id[n] = e.episode;
+        st.t_in_ep[n] = t;
+        st.episode_id[n] = episode;
       }
     }
   }
 
   if (obs == nullptr) return;
-  // ---- paint the occupancy grids: low byte agent level, high byte food level
-  const int cells = p.G * p.G;
+  // ---- the lane's window into the slab: walls and zeros first, then the entities that fall inside it
+  float* w = slab + lane * D;
   {
-    uint32_t* g32 = reinterpret_cast<uint32_t*>(grid);
-    const int words = (nenv * cells + 1) / 2;
-    for (int i = tid; i < words; i += blockDim.x) g32[i] = 0;
-  }
-  __syncthreads();
-  if (active) {
-    const EnvLds& e = envs[le];
-    const int r = e.ar[a], c = e.ac[a];
-    grid[le * cells + r * p.G + c] = (uint16_t)e.al[a];
-    sample_info[tid] = ((uint32_t)le << 16) | ((uint32_t)r << 8) | (uint32_t)c;
-    for (int f = a; f < p.F; f += p.A)
-      if (e.fl[f] != 0) grid[le * cells + e.fr[f] * p.G + e.fc[f]] = (uint16_t)((uint32_t)e.fl[f] << 8);
-  }
-  __syncthreads();
-  // ---- emit window cells in output order: cell index i of the block <-> 3 consecutive floats
-  constexpr int VV = V * V, h = (V - 1) / 2;
-  const int total = nenv * p.A * VV;
-  float* out = obs + (size_t)n0 * p.A * VV * 3;
-  for (int i = tid; i < total; i += blockDim.x) {
-    const int smp = i / VV, cell = i - smp * VV;
-    const int dy = cell / V - h, dx = cell % V - h;
-    const uint32_t info = sample_info[smp];
-    const int rr = (int)((info >> 8) & 0xff) + dy, cc = (int)(info & 0xff) + dx;
-    float v0 = 0.f, v1 = 0.f, v2 = 0.f;
-    if (rr < 0 || rr >= p.G || cc < 0 || cc >= p.G) {
-      v2 = 1.f;
-    } else {
-      const uint32_t g = grid[(info >> 16) * cells + rr * p.G + cc];
-      v0 = (float)(g & 0xff);
-      v1 = (float)(g >> 8);
+    uint32_t me = 0;
+#pragma unroll
+    for (int b = 0; b < CA; ++b) me = (b == a) ? ag[b] : me;
+    const int r0 = e_row(me), c0 = e_col(me);
+    if (active) {
+#pragma unroll
+      for (int dy = -h; dy <= h; ++dy)
+#pragma unroll
+        for (int dx = -h; dx <= h; ++dx) {
+          const int rr = r0 + dy, cc = c0 + dx;
+          const bool wall = rr < 0 || rr >= p.G || cc < 0 || cc >= p.G;
+          float* o = w + ((dy + h) * V + (dx + h)) * 3;
+          o[0] = 0.f;
+          o[1] = 0.f;
+          o[2] = wall ? 1.f : 0.f;
+        }
+#pragma unroll
+      for (int b = 0; b < CA; ++b) {
+        const int dy = e_row(ag[b]) - r0, dx = e_col(ag[b]) - c0;
+        if (b < p.A && dy >= -h && dy <= h && dx >= -h && dx <= h) w[((dy + h) * V + (dx + h)) * 3 + 0] = (float)e_lvl(ag[b]);
+      }
+#pragma unroll
+      for (int f = 0; f < CF; ++f) {
+        const int dy = e_row(fd[f]) - r0, dx = e_col(fd[f]) - c0;
+        if (f < p.F && e_lvl(fd[f]) != 0 && dy >= -h && dy <= h && dx >= -h && dx <= h)
+          w[((dy + h) * V + (dx + h)) * 3 + 1] = (float)e_lvl(fd[f]);
+      }
     }
-    float* o = out + (size_t)i * 3;
-    o[0] = v0; o[1] = v1; o[2] = v2;
+  }
+  __syncthreads();
+  // ---- the slab of a wavefront is one contiguous run of the output
+  const int64_t envs_here = max((int64_t)0, min((int64_t)ew, (int64_t)p.N - wave_env0));
+  const int count = (int)envs_here * p.A * D;  // floats
+  float* out = obs + (size_t)wave_env0 * p.A * D;
+  if ((reinterpret_cast<uintptr_t>(out) & 15u) == 0) {
+    const int n4 = count >> 2;
+    for (int i = lane; i < n4; i += 64) reinterpret_cast<float4*>(out)[i] = reinterpret_cast<const float4*>(slab)[i];
+    for (int i = (n4 << 2) + lane; i < count; i += 64) out[i] = slab[i];
+  } else {
+    for (int i = lane; i < count; i += 64) out[i] = slab[i];
   }
 }
 
@@ -280,6 +317,7 @@ EnvParams env_params(const marl_config& c) {
   p.G = c.grid; p.A = c.n_agents; p.F = c.n_food; p.L = c.max_level; p.cap = c.episode_cap; p.N = c.n_envs;
   p.k0 = (uint32_t)(c.seed & 0xffffffffu);
   p.k1 = (uint32_t)(c.seed >> 32);
+  p.inv_g20 = ((1u << 20) + (uint32_t)c.grid - 1u) / (uint32_t)c.grid;
   return p;
 }
 
@@ -291,32 +329,47 @@ int32_t launch_env_reset(const marl_config& c, marl_env_state st, hipStream_t s)
   return launch_status();
 }
 
+template <int V, int NW, int CA, int CF>
+static int32_t launch_env_step_inst(const EnvParams& p, marl_env_state st, const int32_t* actions, float* obs,
+                                    float* reward, uint8_t* done, bool do_step, hipStream_t s) {
+  const int ew = 64 / p.A;
+  const int64_t waves = (p.N + ew - 1) / ew;
+  const size_t lds = sizeof(float) * NW * 64 * 3 * V * V;
+  auto kern = env_step_kernel<V, NW, CA, CF>;
+  static bool configured = false;
+  if (!configured && lds > 64 * 1024) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+      return MARL_E_LAUNCH;
+    configured = true;
+  }
+  hipLaunchKernelGGL(kern, dim3((unsigned)((waves + NW - 1) / NW)), dim3(64 * NW), lds, s, p, st, actions, obs, reward, done,
+                     (int)do_step);
+  return launch_status();
+}
+
+template <int V, int NW>
+static int32_t launch_env_step_caps(const EnvParams& p, marl_env_state st, const int32_t* actions, float* obs,
+                                    float* reward, uint8_t* done, bool do_step, hipStream_t s) {
+  const int cap = std::max(p.A, p.F);
+  if (cap <= 2) return launch_env_step_inst<V, NW, 2, 2>(p, st, actions, obs, reward, done, do_step, s);
+  if (cap <= 4) return launch_env_step_inst<V, NW, 4, 4>(p, st, actions, obs, reward, done, do_step, s);
+  return launch_env_step_inst<V, NW, kMaxAgents, kMaxFood>(p, st, actions, obs, reward, done, do_step, s);
+}
+
 int32_t launch_env_step(const marl_config& c, marl_env_state st, const int32_t* actions, float* obs, float* reward,
                         uint8_t* done, bool do_step, hipStream_t s) {
   const EnvParams p = env_params(c);
-  // envs per workgroup: at most 256 lanes, and the occupancy grids must fit in ~48 KB of LDS
-  int epb = 256 / p.A;
-  const int grid_bytes = 2 * p.G * p.G;
-  epb = std::min(epb, std::max(1, 49152 / grid_bytes));
-  epb = std::min(epb, p.N);
-  while (epb * p.A > 64 && p.N / epb < 1024) epb = (epb + 1) / 2;  // enough workgroups to cover 256 CUs
-  auto lds_bytes = [&](int e) { return sizeof(EnvLds) * e + 4 * (size_t)e * p.A + (size_t)grid_bytes * e + 16; };
-  while (epb > 1 && lds_bytes(epb) > 60 * 1024) epb = (epb + 1) / 2;
-  int threads = ((epb * p.A + 63) / 64) * 64;
-  const size_t lds = lds_bytes(epb);
-  const dim3 grid((p.N + epb - 1) / epb), block(threads);
   // algorithmic bytes of one transition: observation, reward, action per agent; done and the state (read + write) per env
   const double D = 3.0 * c.view * c.view;
   const double bytes = do_step ? (double)p.N * (p.A * (4.0 * D * (obs ? 1 : 0) + 8.0) + 1.0 + 2.0 * (3.0 * p.A + 4.0 * p.F + 8.0))
                                : (double)p.N * p.A * 4.0 * D;
   TimedLaunch timed(KC_ENV_STEP, bytes, s);
   switch (c.view) {
-    case 3: hipLaunchKernelGGL(env_step_kernel<3>, grid, block, lds, s, p, st, actions, obs, reward, done, epb, (int)do_step); break;
-    case 5: hipLaunchKernelGGL(env_step_kernel<5>, grid, block, lds, s, p, st, actions, obs, reward, done, epb, (int)do_step); break;
-    case 7: hipLaunchKernelGGL(env_step_kernel<7>, grid, block, lds, s, p, st, actions, obs, reward, done, epb, (int)do_step); break;
+    case 3: return launch_env_step_caps<3, 4>(p, st, actions, obs, reward, done, do_step, s);
+    case 5: return launch_env_step_caps<5, 4>(p, st, actions, obs, reward, done, do_step, s);
+    case 7: return launch_env_step_caps<7, 2>(p, st, actions, obs, reward, done, do_step, s);
     default: return MARL_E_CONFIG;
   }
-  return launch_status();
 }
 
 }  // namespace marl
