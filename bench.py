@@ -17,8 +17,11 @@ sys.path.insert(0, ROOT)
 import numpy as np  # noqa: E402
 
 # env-agent steps the CPU oracle is timed on: envs of the same config with full T, A, networks, E and M
-ORACLE_SAMPLE_ENVS = {1: 64, 2: 32, 3: 16, 4: 1, 5: 1024}
+ORACLE_SAMPLE_ENVS = {1: 64, 2: 64, 3: 64, 4: 2, 5: 2048}
 PEAK = {"mfma_f32": 157.3, "mfma_bf16": 2500.0, "hbm": 8000.0}   # TFLOP/s, TFLOP/s, GB/s
+# HBM bytes per launch (read + write) of the dominant kernel, from the rocprofv3 PMC runs summarised in
+# profiles/bench_c3_pmc_hbm_traffic.txt (FETCH_SIZE x 2.000 and WRITE_SIZE x 1.000 after the 1 GiB copy calibration).
+PMC_TRAFFIC_BYTES = {("c3_15x15_4ag_mappo", "fused_train"): 450.1e6 + 52.0e6}
 
 
 def gemm_flops_per_step(cfg, W):
@@ -62,6 +65,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=3, help="1-based workload index (default 3: MAPPO 15x15, 16384 envs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="run one plain 1 GiB device copy before the warm-up (a kernel of known traffic for scaling PMC counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -95,6 +100,12 @@ def main():
         M.ppo_update(cfg, traj, params, adam_m, adam_v, i * E * Mb, perm, stats, None, ws_u)
         it[0] += 1
 
+    if args.calibration_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -126,7 +137,8 @@ def main():
                 "share_of_step": ms / (1e3 * dt)}
 
     lines = [l for l in (line(k) for k in M.KERNEL_CLASSES) if l]
-    roofline = max((l for l in lines if l["bound"] == "mfma"), key=lambda l: l["share_of_step"])
+    roofline = dict(max((l for l in lines if l["bound"] == "mfma"), key=lambda l: l["share_of_step"]))
+    roofline["traffic"] = PMC_TRAFFIC_BYTES.get((cfg["name"], roofline["kernel"]))
     st = stats.cpu().numpy()
     assert np.all(np.isfinite(st)) and np.all(st[:, 7] == 0), "non-finite loss"
 
