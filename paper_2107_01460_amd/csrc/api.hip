@@ -52,6 +52,7 @@ int32_t validate_config(const marl_config* c) {
     if (h < 32 || h > 512 || h % 32 != 0) return MARL_E_CONFIG;
   if (c->central_critic != 0 && c->central_critic != 1) return MARL_E_CONFIG;
   if (c->precision != 0 && c->precision != 1) return MARL_E_CONFIG;
+  if (c->precision == 1 && (c->actor_hidden % 64 != 0 || c->critic_hidden % 64 != 0)) return MARL_E_CONFIG;  // bf16 k tile
   if (c->n_epochs < 1 || c->n_minibatches < 1) return MARL_E_CONFIG;
   const int64_t R = (int64_t)c->n_envs * c->rollout_len;
   if (R % c->n_minibatches != 0) return MARL_E_CONFIG;

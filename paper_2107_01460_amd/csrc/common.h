@@ -106,6 +106,19 @@ __device__ __forceinline__ uint32_t rand_below(uint32_t x, uint32_t n) { return 
 __device__ __forceinline__ float rand_unit(uint32_t x) { return ((float)(x >> 9) + 0.5f) * (1.0f / 8388608.0f); }
 constexpr uint32_t kStreamReset = 1, kStreamSample = 2;
 
+// ---- bfloat16: round-to-nearest-even, stored as the upper 16 bits of an fp32 -------------------
+typedef uint16_t bf16_t;
+__device__ __forceinline__ float round_to_bf16(float x) {
+  uint32_t u = __float_as_uint(x);
+  if ((u & 0x7f800000u) == 0x7f800000u) return x;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return __uint_as_float(u & 0xffff0000u);
+}
+__device__ __forceinline__ bf16_t to_bf16(float x) { return (bf16_t)(__float_as_uint(round_to_bf16(x)) >> 16); }
+__device__ __forceinline__ float from_bf16(bf16_t h) { return __uint_as_float((uint32_t)h << 16); }
+__device__ __forceinline__ float load_act(const float* p, int64_t i) { return p[i]; }
+__device__ __forceinline__ float load_act(const bf16_t* p, int64_t i) { return from_bf16(p[i]); }
+
 // ---- optional per-kernel timing with HIP events (measurement hook, host side) -----------------
 enum KernelClass { KC_GEMM_NN = 0, KC_GEMM_NT = 1, KC_GEMM_TN = 2, KC_ENV_STEP = 3, KC_GAE = 4, KC_FUSED_TRAIN = 5, KC_COUNT = 6 };
 bool timing_on();

@@ -53,13 +53,6 @@ struct GemmArgs {
   int round_bf16;        // round stored results to bf16 precision (kept in fp32 storage)
 };
 
-__device__ __forceinline__ float round_to_bf16(float x) {
-  uint32_t u = __float_as_uint(x);
-  if ((u & 0x7f800000u) == 0x7f800000u) return x;
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return __uint_as_float(u & 0xffff0000u);
-}
-
 // tanh(x) = 1 - 2 / (e^{2x} + 1) with the hardware exp2 and reciprocal: absolute error ~1e-7 (the values feed
 // sums of O(1) activations, so an absolute bound is what the 1e-4 tolerance on the outputs needs); saturates
 // cleanly to +-1 when e^{2x} overflows or underflows.

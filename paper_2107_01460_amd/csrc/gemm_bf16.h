@@ -1,0 +1,225 @@
+// bf16 MFMA GEMM for the bf16 configuration (v_mfma_f32_32x32x16_bf16, fp32 accumulation).
+//
+// One operand arrangement serves every product of the training step: C[m][n] = sum_k A[m][k] * B[n][k] with
+// BOTH operands k-contiguous in memory, because the producers write each activation twice where it is needed
+// twice: row-major [sample][feature] (the A operand of the next layer / of dz1 = dz2 W2^T) and transposed
+// [feature][sample] (the operands of the weight gradients dW = act^T dz, whose contraction index is the
+// sample).  So no kernel ever has to transpose 2-byte elements on its way into the matrix cores:
+//   h1  = tanh(Xb  W1t^T + b1)      A = Xb  [S][Dp]   B = W1t [H][Dp]    -> h1 [S][H] and h1T [H][Sp]
+//   h2  = tanh(h1  W2t^T + b2)      A = h1  [S][H]    B = W2t [H][H]     -> h2 [S][H]
+//   dW2 = h1T dz2T^T                A = h1T [H][Sp]   B = dz2T [H][Sp]   -> fp32 atomics (k split over workgroups)
+//   dz1 = (dz2 W2^T) (1 - h1^2)     A = dz2 [S][H]    B = W2  [H][H]     -> dz1T [H][Sp] only
+//   dW1 = XbT dz1T^T                A = XbT [Dp][Sp]  B = dz1T [H][Sp]   -> fp32 atomics
+// Tile 128 x 128 x 64 per workgroup of four wavefronts (2 x 2, each 2 x 2 MFMA tiles of 32 x 32); operands are
+// staged in LDS with a 144-byte row pitch so that the 16-byte operand reads of eight consecutive rows fall into
+// eight different bank groups; results leave through an LDS-staged tile with 16-byte stores in both orientations.
+#pragma once
+#include "gemm.h"
+
+namespace marl {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+enum Bf16Epi {
+  BEPI_TANH = 0,     // v = tanh(acc + bias[n]) -> C [m][n] (nullable) and CT [n][m] (nullable)
+  BEPI_DTANH_T = 1,  // v = acc * (1 - aux[m][n]^2) -> CT [n][m]
+  BEPI_ATOMIC = 2    // Cf[m][n] += acc (fp32 atomics); optional row sums of B over k -> rowsum_b[n]
+};
+
+struct GemmBf16Args {
+  const bf16_t* A;  // [a_rows][lda]
+  int64_t lda, a_rows;
+  const bf16_t* B;  // [b_rows][ldb]
+  int64_t ldb, b_rows;
+  int64_t M, N, K;  // K a multiple of 64 (buffers are zero-padded along k)
+  int64_t k_per_split;
+  bf16_t* C;
+  int64_t ldc;
+  bf16_t* CT;
+  int64_t ldct, ct_cols;  // columns m in [M, ct_cols) of CT are written as zeros (ct_cols a multiple of 8)
+  float* Cf;
+  int64_t ldcf;
+  const float* bias;
+  const bf16_t* aux;
+  int64_t ldaux;
+  float* rowsum_b;
+};
+
+template <int EPI>
+__global__ void __launch_bounds__(256, 2) gemm_bf16_kernel(GemmBf16Args g) {
+  constexpr int BM = 128, BN = 128, BK = 64, P = BK + 8;  // pitch in elements (144 bytes)
+  constexpr int PT = 128 + 8;                             // pitch of the output staging tile (272 bytes)
+  static_assert(2 * BM * P >= 128 * PT, "the output tile reuses the operand buffers");
+  __shared__ __attribute__((aligned(16))) bf16_t smem[2 * BM * P];
+  bf16_t* As = smem;
+  bf16_t* Bs = smem + BM * P;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1, lo = lane & 31, hi = lane >> 5;
+  const int64_t m0 = (int64_t)blockIdx.x * BM, n0 = (int64_t)blockIdx.y * BN;
+  int64_t k_begin = 0, k_end = g.K;
+  if (EPI == BEPI_ATOMIC) {
+    k_begin = (int64_t)blockIdx.z * g.k_per_split;
+    k_end = min(g.K, k_begin + g.k_per_split);
+  }
+
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // staging: thread -> rows tid/8 + 32p (p < 4), 16-byte segment tid%8 of the 128-byte k-chunk of each row
+  const int seg = tid & 7, srow = tid >> 3;
+  const bf16_t *arow[4], *brow[4];
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    arow[p] = g.A + min(m0 + srow + 32 * p, g.a_rows - 1) * g.lda + 8 * seg;  // rows past the end re-read the last one
+    brow[p] = g.B + min(n0 + srow + 32 * p, g.b_rows - 1) * g.ldb + 8 * seg;
+  }
+  uint4 ra[4], rb[4];
+  float bsum[4] = {0.f, 0.f, 0.f, 0.f};
+  const bool want_bsum = EPI == BEPI_ATOMIC && g.rowsum_b != nullptr && blockIdx.x == 0;
+  auto fetch = [&](int64_t k0) {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      ra[p] = *reinterpret_cast<const uint4*>(arow[p] + k0);
+      rb[p] = *reinterpret_cast<const uint4*>(brow[p] + k0);
+    }
+  };
+  auto stage = [&]() {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      *reinterpret_cast<uint4*>(&As[(srow + 32 * p) * P + 8 * seg]) = ra[p];
+      *reinterpret_cast<uint4*>(&Bs[(srow + 32 * p) * P + 8 * seg]) = rb[p];
+    }
+    if (EPI == BEPI_ATOMIC && want_bsum) {
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        const uint32_t w[4] = {rb[p].x, rb[p].y, rb[p].z, rb[p].w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) bsum[p] += __uint_as_float(w[q] << 16) + __uint_as_float(w[q] & 0xffff0000u);
+      }
+    }
+  };
+
+  if (k_begin < k_end) fetch(k_begin);
+  for (int64_t k0 = k_begin; k0 < k_end; k0 += BK) {
+    stage();
+    __syncthreads();
+    if (k0 + BK < k_end) fetch(k0 + BK);
+#pragma unroll
+    for (int ks = 0; ks < BK; ks += 16) {
+      bf16x8 a[2], b[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) a[i] = *reinterpret_cast<const bf16x8*>(&As[(wm * 64 + i * 32 + lo) * P + ks + 8 * hi]);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) b[j] = *reinterpret_cast<const bf16x8*>(&Bs[(wn * 64 + j * 32 + lo) * P + ks + 8 * hi]);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+    __syncthreads();
+  }
+
+  if (EPI == BEPI_ATOMIC) {
+    if (want_bsum) {
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        float v = bsum[p];
+        v += __shfl_xor(v, 1);
+        v += __shfl_xor(v, 2);
+        v += __shfl_xor(v, 4);
+        const int64_t n = n0 + srow + 32 * p;
+        if (seg == 0 && n < g.N) atomicAdd(&g.rowsum_b[n], v);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int64_t m = m0 + wm * 64 + i * 32 + 8 * (r / 4) + 4 * hi + (r % 4), n = n0 + wn * 64 + j * 32 + lo;
+          if (m < g.M && n < g.N) atomicAdd(&g.Cf[m * g.ldcf + n], acc[i][j][r]);
+        }
+    return;
+  }
+
+  // ---- element-wise epilogue in registers
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int64_t n = n0 + wn * 64 + j * 32 + lo;
+    const int64_t nc = min(n, g.N - 1);
+    const float bias = EPI == BEPI_TANH ? g.bias[nc] : 0.f;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int64_t m = m0 + wm * 64 + i * 32 + 8 * (r / 4) + 4 * hi + (r % 4);
+        float v = acc[i][j][r];
+        if (EPI == BEPI_TANH) {
+          v = tanh_f32(v + bias);
+        } else {
+          const float h = from_bf16(g.aux[min(m, g.M - 1) * g.ldaux + nc]);
+          v = v * (1.0f - h * h);
+        }
+        acc[i][j][r] = (m < g.M) ? v : 0.f;  // rows past the end leave as zeros (padding of the transposed copy)
+      }
+  }
+  bf16_t* T = smem;  // [128][PT]; the operand buffers are free (the k loop ended with a barrier)
+  // ---- row-major copy C [m][n]
+  if (EPI == BEPI_TANH && g.C != nullptr) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          T[(wm * 64 + i * 32 + 8 * (r / 4) + 4 * hi + (r % 4)) * PT + wn * 64 + j * 32 + lo] = to_bf16(acc[i][j][r]);
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const int row = (tid >> 4) + 16 * q, sg = tid & 15;
+      const int64_t m = m0 + row, n = n0 + 8 * sg;
+      if (m < g.M && n < g.N) *reinterpret_cast<uint4*>(&g.C[m * g.ldc + n]) = *reinterpret_cast<const uint4*>(&T[row * PT + 8 * sg]);
+    }
+    __syncthreads();
+  }
+  // ---- transposed copy CT [n][m]
+  if (g.CT != nullptr) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+          const uint32_t w0 = (uint32_t)to_bf16(acc[i][j][4 * gq + 0]) | ((uint32_t)to_bf16(acc[i][j][4 * gq + 1]) << 16);
+          const uint32_t w1 = (uint32_t)to_bf16(acc[i][j][4 * gq + 2]) | ((uint32_t)to_bf16(acc[i][j][4 * gq + 3]) << 16);
+          *reinterpret_cast<uint2*>(&T[(wn * 64 + j * 32 + lo) * PT + wm * 64 + i * 32 + 8 * gq + 4 * hi]) = make_uint2(w0, w1);
+        }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const int row = (tid >> 4) + 16 * q, sg = tid & 15;
+      const int64_t n = n0 + row, m = m0 + 8 * sg;
+      if (n < g.N && m < g.ct_cols) *reinterpret_cast<uint4*>(&g.CT[n * g.ldct + m]) = *reinterpret_cast<const uint4*>(&T[row * PT + 8 * sg]);
+    }
+  }
+}
+
+template <int EPI>
+inline void launch_gemm_bf16(const GemmBf16Args& g, hipStream_t s) {
+  TimedLaunch timed(EPI == BEPI_TANH ? KC_GEMM_NN : (EPI == BEPI_DTANH_T ? KC_GEMM_NT : KC_GEMM_TN),
+                    2.0 * (double)g.M * (double)g.N * (double)g.K, s);
+  unsigned gz = 1;
+  if (EPI == BEPI_ATOMIC) gz = (unsigned)((g.K + g.k_per_split - 1) / g.k_per_split);
+  const int64_t mcover = (EPI == BEPI_ATOMIC || g.CT == nullptr) ? g.M : std::max(g.M, g.ct_cols);
+  dim3 grid((unsigned)((mcover + 127) / 128), (unsigned)((g.N + 127) / 128), gz);
+  hipLaunchKernelGGL(gemm_bf16_kernel<EPI>, grid, dim3(256), 0, s, g);
+}
+
+}  // namespace marl

@@ -25,8 +25,8 @@ struct HeadLds {
 
 // out[k] = sum_i H2[s0 + s][i] * W3[i][k] for the 64 samples of a tile; valid in threads tid < 64 (s = tid).
 // Must be called by all 256 threads of the workgroup.
-template <int NOUT>
-__device__ __forceinline__ void head_tile(const float* __restrict__ H2, int64_t s0, int64_t S, int H,
+template <int NOUT, typename HT>
+__device__ __forceinline__ void head_tile(const HT* __restrict__ H2, int64_t s0, int64_t S, int H,
                                           const float* __restrict__ W3, HeadLds& L, float out[NOUT]) {
   const int tid = threadIdx.x, lane = tid & 63, grp = tid >> 6;
   float acc[NOUT];
@@ -37,7 +37,7 @@ __device__ __forceinline__ void head_tile(const float* __restrict__ H2, int64_t 
     __syncthreads();
     for (int r = grp; r < kHeadTile; r += 4) {
       const int64_t s = s0 + r;
-      for (int c = lane; c < hc; c += 64) L.tile[r * (kHeadChunk + 1) + c] = s < S ? H2[s * H + h0 + c] : 0.f;
+      for (int c = lane; c < hc; c += 64) L.tile[r * (kHeadChunk + 1) + c] = s < S ? load_act(H2, s * H + h0 + c) : 0.f;
     }
     for (int e = tid; e < hc * NOUT; e += 256) L.w3[e] = W3[(int64_t)h0 * NOUT + e];
     __syncthreads();
@@ -112,7 +112,8 @@ __device__ __forceinline__ void sample_and_store(const float lg[kActions], int64
 
 namespace heads_detail {
 
-static __global__ void __launch_bounds__(256) actor_head_rollout_kernel(const float* __restrict__ H2, int64_t S, int H,
+template <typename HT>
+static __global__ void __launch_bounds__(256) actor_head_rollout_kernel(const HT* __restrict__ H2, int64_t S, int H,
                                                                  const float* __restrict__ W3,
                                                                  const float* __restrict__ b3, float* logits_out,
                                                                  SampleArgs a, int do_sample) {
@@ -132,7 +133,8 @@ static __global__ void __launch_bounds__(256) actor_head_rollout_kernel(const fl
   }
 }
 
-static __global__ void __launch_bounds__(256) critic_head_rollout_kernel(const float* __restrict__ H2, int64_t S, int H,
+template <typename HT>
+static __global__ void __launch_bounds__(256) critic_head_rollout_kernel(const HT* __restrict__ H2, int64_t S, int H,
                                                                   const float* __restrict__ W3,
                                                                   const float* __restrict__ b3, float* value_out,
                                                                   int broadcast) {
@@ -158,15 +160,17 @@ static __global__ void __launch_bounds__(256) sample_only_kernel(const float* __
 
 }  // namespace heads_detail
 
-inline void launch_actor_head_rollout(const float* H2, int64_t S, int H, const float* W3, const float* b3,
+template <typename HT>
+inline void launch_actor_head_rollout(const HT* H2, int64_t S, int H, const float* W3, const float* b3,
                                       float* logits_out, const SampleArgs* a, hipStream_t s) {
   SampleArgs z{};
-  hipLaunchKernelGGL(heads_detail::actor_head_rollout_kernel, dim3((unsigned)((S + kHeadTile - 1) / kHeadTile)),
+  hipLaunchKernelGGL(heads_detail::actor_head_rollout_kernel<HT>, dim3((unsigned)((S + kHeadTile - 1) / kHeadTile)),
                      dim3(256), 0, s, H2, S, H, W3, b3, logits_out, a ? *a : z, a ? 1 : 0);
 }
-inline void launch_critic_head_rollout(const float* H2, int64_t S, int H, const float* W3, const float* b3,
+template <typename HT>
+inline void launch_critic_head_rollout(const HT* H2, int64_t S, int H, const float* W3, const float* b3,
                                        float* value_out, int broadcast, hipStream_t s) {
-  hipLaunchKernelGGL(heads_detail::critic_head_rollout_kernel, dim3((unsigned)((S + kHeadTile - 1) / kHeadTile)),
+  hipLaunchKernelGGL(heads_detail::critic_head_rollout_kernel<HT>, dim3((unsigned)((S + kHeadTile - 1) / kHeadTile)),
                      dim3(256), 0, s, H2, S, H, W3, b3, value_out, broadcast);
 }
 inline void launch_sample_only(const float* logits, int64_t S, const SampleArgs& a, hipStream_t s) {

@@ -3,11 +3,15 @@
 // The two hidden layers of each network are MFMA GEMMs (gemm.h); the narrow output layer
 // (6 logits or 1 value) runs on the vector ALUs of the "head" kernel, which also draws the
 // action by Gumbel-max from Philox uniforms and evaluates its log-probability.
+#include "bf16_path.h"
 #include "fused_forward.h"
 #include "gemm.h"
 #include "heads.h"
 
 namespace marl {
+
+int64_t effective_param_floats(const marl_config& c);
+
 namespace {
 
 // Working copy of the parameters: blocks moved to their aligned offsets, optionally rounded to bf16.
@@ -52,7 +56,8 @@ FusedFwdArgs fused_args(const RowSrc& X, int64_t S, int Din, const float* eff, c
 }
 
 struct RolloutWsView {
-  float *eff_params, *h1a, *h2a, *h1c, *h2c, *logits_tmp;
+  float *eff_params, *h1a, *h2a, *h1c, *h2c;   // fp32 path
+  bf16_t *xba, *bh1a, *bh2a, *xbc, *bh1c, *bh2c;  // bf16 configuration
 };
 
 int64_t align256(int64_t x) { return (x + 255) & ~(int64_t)255; }
@@ -62,18 +67,26 @@ RolloutWsView carve_rollout_ws(const marl_config& c, int64_t n_rows, void* ws, i
   const int64_t S = n_rows * d.A, Sc = d.central ? n_rows : S;
   char* p = static_cast<char*>(ws);
   int64_t off = 0;
-  auto take = [&](int64_t floats) {
-    float* r = reinterpret_cast<float*>(p + off);
-    off += align256(floats * 4);
+  auto take = [&](int64_t bytes) {
+    char* r = p + off;
+    off += align256(bytes);
     return r;
   };
-  RolloutWsView v;
-  v.eff_params = take(param_map(d).dst[12]);
-  v.h1a = take(S * d.Ha);
-  v.h2a = take(S * d.Ha);
-  v.h1c = take(Sc * d.Hc);
-  v.h2c = take(Sc * d.Hc);
-  v.logits_tmp = take(S * kActions);
+  RolloutWsView v{};
+  v.eff_params = (float*)take(effective_param_floats(c) * 4);
+  if (!d.bf16) {
+    v.h1a = (float*)take(S * d.Ha * 4);
+    v.h2a = (float*)take(S * d.Ha * 4);
+    v.h1c = (float*)take(Sc * d.Hc * 4);
+    v.h2c = (float*)take(Sc * d.Hc * 4);
+  } else {
+    v.xba = (bf16_t*)take(S * round_up64(d.D) * 2);
+    v.bh1a = (bf16_t*)take(S * d.Ha * 2);
+    v.bh2a = (bf16_t*)take(S * d.Ha * 2);
+    v.xbc = (bf16_t*)take(Sc * round_up64(d.Dc) * 2);
+    v.bh1c = (bf16_t*)take(Sc * d.Hc * 2);
+    v.bh2c = (bf16_t*)take(Sc * d.Hc * 2);
+  }
   if (total) *total = off;
   return v;
 }
@@ -92,10 +105,30 @@ void mlp_hidden_forward(const RowSrc& X, int64_t S, int Din, int H, const float*
   launch_gemm<GEMM_NN, EPI_BIAS_TANH>(g2, s);
 }
 
+// Floats of the working copy: the aligned fp32 copy, followed (bf16 configuration) by the bf16 weight matrices.
+int64_t effective_param_floats(const marl_config& c) {
+  const Dims d = dims_of(c);
+  int64_t n = param_map(d).dst[12];
+  if (d.bf16) n += (bf16_net_weight_elems(d.D, d.Ha) + bf16_net_weight_elems(d.Dc, d.Hc) + 1) / 2 + 192;  // + alignment slack
+  return n;
+}
+
+Bf16NetWeights effective_bf16_weights(const marl_config& c, const float* eff, int net) {
+  const Dims d = dims_of(c);
+  bf16_t* base = reinterpret_cast<bf16_t*>(const_cast<float*>(eff) + ((param_map(d).dst[12] + 63) / 64) * 64);
+  if (net == 0) return bf16_net_weights(base, d.D, d.Ha);
+  return bf16_net_weights(base + ((bf16_net_weight_elems(d.D, d.Ha) + 63) / 64) * 64, d.Dc, d.Hc);
+}
+
 const float* effective_params(const marl_config& c, const float* params, float* scratch, hipStream_t s) {
   const Dims d = dims_of(c);
   hipLaunchKernelGGL(stage_params_kernel, dim3((unsigned)((d.P + 255) / 256)), dim3(256), 0, s, params, scratch,
                      param_map(d), (int)d.bf16);
+  if (d.bf16) {
+    const NetOffsets oa = net_offsets(0, d.D, d.Ha, kActions), oc = net_offsets(d.Pa, d.Dc, d.Hc, 1);
+    stage_weights_bf16(params + oa.W1, params + oa.W2, d.D, d.Ha, effective_bf16_weights(c, scratch, 0), s);
+    stage_weights_bf16(params + oc.W1, params + oc.W2, d.Dc, d.Hc, effective_bf16_weights(c, scratch, 1), s);
+  }
   return scratch;
 }
 
@@ -111,6 +144,24 @@ static int32_t forward_rows(const marl_config& c, const float* eff, const float*
                             float* value_out, hipStream_t s) {
   const Dims d = dims_of(c);
   const int64_t S = n_rows * d.A;
+  if (d.bf16) {
+    if (want_actor) {
+      const NetOffsets o = padded_offsets(param_map(d), 0);
+      const Bf16NetWeights bw = effective_bf16_weights(c, eff, 0);
+      pack_obs_bf16(RowSrc{obs, d.D, nullptr, 1, S}, S, d.D, bw.Dp, S, w.xba, nullptr, s);
+      mlp_hidden_forward_bf16(w.xba, S, S, d.Ha, bw, eff + o.b1, eff + o.b2, w.bh1a, nullptr, w.bh2a, s);
+      launch_actor_head_rollout(w.bh2a, S, d.Ha, eff + o.W3, eff + o.b3, logits_out, sample, s);
+    }
+    if (value_out) {
+      const NetOffsets o = padded_offsets(param_map(d), 1);
+      const Bf16NetWeights bw = effective_bf16_weights(c, eff, 1);
+      const int64_t Sc = d.central ? n_rows : S;
+      pack_obs_bf16(RowSrc{obs, d.Dc, nullptr, 1, Sc}, Sc, d.Dc, bw.Dp, Sc, w.xbc, nullptr, s);
+      mlp_hidden_forward_bf16(w.xbc, Sc, Sc, d.Hc, bw, eff + o.b1, eff + o.b2, w.bh1c, nullptr, w.bh2c, s);
+      launch_critic_head_rollout(w.bh2c, Sc, d.Hc, eff + o.W3, eff + o.b3, value_out, d.central ? d.A : 1, s);
+    }
+    return launch_status();
+  }
   if (want_actor) {
     const NetOffsets o = padded_offsets(param_map(d), 0);
     const RowSrc X{obs, d.D, nullptr, 1, S};

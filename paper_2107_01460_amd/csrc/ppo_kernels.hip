@@ -4,6 +4,7 @@
 #include <algorithm>
 #include <cmath>
 
+#include "bf16_path.h"
 #include "fused_forward.h"
 #include "fused_train.h"
 #include "gemm.h"
@@ -15,6 +16,8 @@ namespace marl {
 void mlp_hidden_forward(const RowSrc& X, int64_t S, int Din, int H, const float* W1, const float* b1, const float* W2,
                         const float* b2, float* h1, float* h2, bool bf16, hipStream_t s);
 const float* effective_params(const marl_config& c, const float* params, float* scratch, hipStream_t s);
+int64_t effective_param_floats(const marl_config& c);
+Bf16NetWeights effective_bf16_weights(const marl_config& c, const float* eff, int net);
 
 namespace {
 
@@ -193,8 +196,8 @@ struct CriticLoss {
 
 // Output layer + loss + gradient of the output layer.  Persistent over tiles of 64 samples so that the
 // W3 / b3 gradient and the loss statistics leave each workgroup once.
-template <int NOUT, class LossFn>
-__global__ void __launch_bounds__(256) loss_head_kernel(const float* __restrict__ H2, int64_t S, int H,
+template <int NOUT, class LossFn, typename HT>
+__global__ void __launch_bounds__(256) loss_head_kernel(const HT* __restrict__ H2, int64_t S, int H,
                                                         const float* __restrict__ W3, const float* __restrict__ b3,
                                                         LossFn fn, float* __restrict__ dl_out,
                                                         float* __restrict__ gW3, float* __restrict__ gb3,
@@ -250,7 +253,7 @@ __global__ void __launch_bounds__(256) loss_head_kernel(const float* __restrict_
           __syncthreads();
           for (int r = tid >> 6; r < kHeadTile; r += 4) {
             const int64_t s = s0 + r;
-            for (int cc = tid & 63; cc < hc; cc += 64) L.tile[r * (kHeadChunk + 1) + cc] = s < S ? H2[s * H + h0 + cc] : 0.f;
+            for (int cc = tid & 63; cc < hc; cc += 64) L.tile[r * (kHeadChunk + 1) + cc] = s < S ? load_act(H2, s * H + h0 + cc) : 0.f;
           }
           __syncthreads();
         }
@@ -376,6 +379,8 @@ struct UpdateWsView {
   int32_t* ident;
   float *h1a, *h2a, *dz1a, *dla;
   float *h1c, *h2c, *dz1c, *dlc;
+  // bf16 configuration: one set of activation buffers, used by the actor and then by the critic
+  bf16_t *xb, *xbT, *bh1, *bh1T, *bh2, *dz2T, *dz1T;
 };
 
 int64_t align256(int64_t x) { return (x + 255) & ~(int64_t)255; }
@@ -391,19 +396,33 @@ UpdateWsView carve_update_ws(const marl_config& c, void* ws, int64_t* total) {
     off += align256(bytes);
     return r;
   };
-  UpdateWsView v;
-  v.eff_params = (float*)take(param_map(d).dst[12] * 4);
+  UpdateWsView v{};
+  v.eff_params = (float*)take(effective_param_floats(c) * 4);
   v.grad = (float*)take(d.P * 4);
   v.sc = (Scalars*)take(sizeof(Scalars));
   v.ident = (int32_t*)take(R * 4);
-  v.h1a = (float*)take(Sa * d.Ha * 4);
-  v.h2a = (float*)take(Sa * d.Ha * 4);
-  v.dz1a = (float*)take(Sa * d.Ha * 4);
-  v.dla = (float*)take(Sa * kActions * 4);
-  v.h1c = (float*)take(Sc * d.Hc * 4);
-  v.h2c = (float*)take(Sc * d.Hc * 4);
-  v.dz1c = (float*)take(Sc * d.Hc * 4);
-  v.dlc = (float*)take(Sc * 4);
+  if (!d.bf16) {
+    v.h1a = (float*)take(Sa * d.Ha * 4);
+    v.h2a = (float*)take(Sa * d.Ha * 4);
+    v.dz1a = (float*)take(Sa * d.Ha * 4);
+    v.dla = (float*)take(Sa * kActions * 4);
+    v.h1c = (float*)take(Sc * d.Hc * 4);
+    v.h2c = (float*)take(Sc * d.Hc * 4);
+    v.dz1c = (float*)take(Sc * d.Hc * 4);
+    v.dlc = (float*)take(Sc * 4);
+  } else {
+    const int64_t Sp = round_up64(std::max(Sa, Sc));
+    const int64_t Dp = round_up64(std::max(d.D, d.Dc)), H = std::max(d.Ha, d.Hc);
+    v.dla = (float*)take(Sa * kActions * 4);
+    v.dlc = (float*)take(Sc * 4);
+    v.xb = (bf16_t*)take(Sp * Dp * 2);
+    v.xbT = (bf16_t*)take(Sp * Dp * 2);
+    v.bh1 = (bf16_t*)take(Sp * H * 2);
+    v.bh1T = (bf16_t*)take(Sp * H * 2);
+    v.bh2 = (bf16_t*)take(Sp * H * 2);
+    v.dz2T = (bf16_t*)take(Sp * H * 2);
+    v.dz1T = (bf16_t*)take(Sp * H * 2);
+  }
   if (total) *total = off;
   return v;
 }
@@ -449,6 +468,46 @@ void mlp_backward(const RowSrc& X, int64_t S, int Din, int H, const float* W2, c
   }
 }
 
+// Forward, loss and backward of one network in the bf16 configuration: every product runs on the bf16 matrix
+// cores; the output layer, the loss and dz2 stay on the ALUs in fp32.
+template <int NOUT, class LossFn>
+void train_net_bf16(const RowSrc& X, int64_t S, int Din, int H, const Bf16NetWeights& bw, const float* eff,
+                    const NetOffsets& o, float* grad, const NetOffsets& go, const LossFn& fn, float* dl,
+                    const UpdateWsView& w, hipStream_t s) {
+  const int64_t Sp = round_up64(S);
+  pack_obs_bf16(X, S, Din, bw.Dp, Sp, w.xb, w.xbT, s);
+  mlp_hidden_forward_bf16(w.xb, S, Sp, H, bw, eff + o.b1, eff + o.b2, w.bh1, w.bh1T, w.bh2, s);
+  const unsigned nb = (unsigned)std::min<int64_t>(2048, (S + kHeadTile - 1) / kHeadTile);
+  hipLaunchKernelGGL((loss_head_kernel<NOUT, LossFn, bf16_t>), dim3(nb), dim3(256), 0, s, w.bh2, S, H, eff + o.W3,
+                     eff + o.b3, fn, dl, grad + go.W3, grad + go.b3, w.sc, 0.f);
+  hipLaunchKernelGGL(bf16_detail::dz2_bf16_kernel<NOUT>, dim3((unsigned)(Sp / 64), (unsigned)((H + 63) / 64)), dim3(256), 0,
+                     s, w.bh2, w.dz2T, dl, eff + o.W3, S, Sp, H);
+  auto k_split = [&](int64_t tiles_mn) {  // ~4 workgroups per CU, k ranges in multiples of the k tile
+    const int64_t want = std::max<int64_t>(1, 1024 / std::max<int64_t>(1, tiles_mn));
+    return std::max<int64_t>(512, round_up64((Sp + want - 1) / want));
+  };
+  {  // gW2 += h1^T dz2, gb2 += column sums of dz2
+    GemmBf16Args g{};
+    g.A = w.bh1T; g.lda = Sp; g.a_rows = H; g.B = w.dz2T; g.ldb = Sp; g.b_rows = H;
+    g.M = H; g.N = H; g.K = Sp; g.Cf = grad + go.W2; g.ldcf = H; g.rowsum_b = grad + go.b2;
+    g.k_per_split = k_split(((H + 127) / 128) * ((H + 127) / 128));
+    launch_gemm_bf16<BEPI_ATOMIC>(g, s);
+  }
+  {  // dz1 = (dz2 W2^T) * (1 - h1^2), transposed copy only
+    GemmBf16Args g{};
+    g.A = w.bh2; g.lda = H; g.a_rows = S; g.B = bw.W2; g.ldb = H; g.b_rows = H;
+    g.M = S; g.N = H; g.K = H; g.CT = w.dz1T; g.ldct = Sp; g.ct_cols = Sp; g.aux = w.bh1; g.ldaux = H;
+    launch_gemm_bf16<BEPI_DTANH_T>(g, s);
+  }
+  {  // gW1 += X^T dz1, gb1 += column sums of dz1
+    GemmBf16Args g{};
+    g.A = w.xbT; g.lda = Sp; g.a_rows = bw.Dp; g.B = w.dz1T; g.ldb = Sp; g.b_rows = H;
+    g.M = Din; g.N = H; g.K = Sp; g.Cf = grad + go.W1; g.ldcf = H; g.rowsum_b = grad + go.b1;
+    g.k_per_split = k_split(((Din + 127) / 128) * ((H + 127) / 128));
+    launch_gemm_bf16<BEPI_ATOMIC>(g, s);
+  }
+}
+
 }  // namespace
 
 int64_t update_workspace_bytes(const marl_config& c) {
@@ -490,7 +549,9 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
       const bool fused_a = fused_forward_supported(d.Ha);
       {
         ActorLoss fn{lc, tr.action, tr.logp, tr.adv};
-        if (fused_train_supported(d.Ha, d.D)) {
+        if (d.bf16) {
+          train_net_bf16<kActions>(Xa, Sa, d.D, d.Ha, effective_bf16_weights(c, eff, 0), eff, oa, w.grad, ga, fn, w.dla, w, s);
+        } else if (fused_train_supported(d.Ha, d.D)) {
           FusedTrainArgs ta{};
           ta.X = Xa; ta.S = Sa; ta.Din = d.D; ta.px = fused_train_px(d.D);
           ta.W1 = eff + oa.W1; ta.b1 = eff + oa.b1; ta.W2 = eff + oa.W2; ta.b2 = eff + oa.b2; ta.W3 = eff + oa.W3;
@@ -510,7 +571,7 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
           } else {
             mlp_hidden_forward(Xa, Sa, d.D, d.Ha, eff + oa.W1, eff + oa.b1, eff + oa.W2, eff + oa.b2, w.h1a, w.h2a, d.bf16, s);
             const unsigned nb = (unsigned)std::min<int64_t>(2048, (Sa + kHeadTile - 1) / kHeadTile);
-            hipLaunchKernelGGL((loss_head_kernel<kActions, ActorLoss>), dim3(nb), dim3(256), 0, s, w.h2a, Sa, d.Ha,
+            hipLaunchKernelGGL((loss_head_kernel<kActions, ActorLoss, float>), dim3(nb), dim3(256), 0, s, w.h2a, Sa, d.Ha,
                                eff + oa.W3, eff + oa.b3, fn, w.dla, w.grad + ga.W3, w.grad + ga.b3, w.sc, 0.f);
           }
           mlp_backward<kActions>(Xa, Sa, d.D, d.Ha, eff + oa.W2, eff + oa.W3, w.h1a, w.h2a, w.dz1a, w.dla, w.grad + ga.W1,
@@ -522,7 +583,9 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
       const bool fused_c = fused_forward_supported(d.Hc);
       {
         CriticLoss fn{lc, tr.ret, tr.value, d.central ? d.A : 1};
-        if (fused_train_supported(d.Hc, d.Dc)) {
+        if (d.bf16) {
+          train_net_bf16<1>(Xc, Sc, d.Dc, d.Hc, effective_bf16_weights(c, eff, 1), eff, oc, w.grad, gc, fn, w.dlc, w, s);
+        } else if (fused_train_supported(d.Hc, d.Dc)) {
           FusedTrainArgs ta{};
           ta.X = Xc; ta.S = Sc; ta.Din = d.Dc; ta.px = fused_train_px(d.Dc);
           ta.W1 = eff + oc.W1; ta.b1 = eff + oc.b1; ta.W2 = eff + oc.W2; ta.b2 = eff + oc.b2; ta.W3 = eff + oc.W3;
@@ -542,7 +605,7 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
           } else {
             mlp_hidden_forward(Xc, Sc, d.Dc, d.Hc, eff + oc.W1, eff + oc.b1, eff + oc.W2, eff + oc.b2, w.h1c, w.h2c, d.bf16, s);
             const unsigned nb = (unsigned)std::min<int64_t>(2048, (Sc + kHeadTile - 1) / kHeadTile);
-            hipLaunchKernelGGL((loss_head_kernel<1, CriticLoss>), dim3(nb), dim3(256), 0, s, w.h2c, Sc, d.Hc, eff + oc.W3,
+            hipLaunchKernelGGL((loss_head_kernel<1, CriticLoss, float>), dim3(nb), dim3(256), 0, s, w.h2c, Sc, d.Hc, eff + oc.W3,
                                eff + oc.b3, fn, w.dlc, w.grad + gc.W3, w.grad + gc.b3, w.sc, 0.f);
           }
           mlp_backward<1>(Xc, Sc, d.Dc, d.Hc, eff + oc.W2, eff + oc.W3, w.h1c, w.h2c, w.dz1c, w.dlc, w.grad + gc.W1,
