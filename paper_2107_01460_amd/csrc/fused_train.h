@@ -4,8 +4,10 @@
 // written: h1, h2, dz2, dz1 live in LDS / registers for the lifetime of a row tile, and the weight
 // gradients are accumulated in registers over all row tiles a workgroup owns.
 //
-// Workgroup = 8 wavefronts, persistent, one per CU.  Row tile = BM samples (64 for H = 128, 128 for
-// H = 64), so that a layer output is exactly eight 32x32 MFMA tiles, one per wavefront.  Per tile:
+// Workgroup = NW wavefronts, persistent.  Row tile = BM samples with (BM/32)(H/32) = NW, so that a layer
+// output is exactly NW 32x32 MFMA tiles, one per wavefront.  With NW = 4 (BM 32 for H = 128, 64 for H = 64)
+// two workgroups share a CU: their phases drift apart, so the ALU phases of one (tanh epilogues, output
+// layer, loss) run in the shadow of the other's MFMA phases.  Per tile:
 //   X -> LDS | L1 (W1 streamed in 32-row chunks) -> h1 (LDS) | L2 -> h2 (registers + LDS) |
 //   output layer on the ALUs -> loss -> dL/dout | W3 gradient | dz2 = (dL/dout W3^T)(1-h2^2) -> LDS |
 //   dW2 += h1^T dz2 | dz1 = (dz2 W2^T)(1-h1^2) -> LDS (W2 streamed as k-contiguous chunks) | dW1 += X^T dz1
@@ -15,6 +17,20 @@
 #include "gemm.h"
 
 namespace marl {
+
+#ifdef MARL_PHASE_TIMERS
+__device__ long long g_phase_cycles[16];
+#define PHASE_MARK(i)                                                    \
+  do {                                                                   \
+    if (tid == 0 && blockIdx.x == 0) {                                   \
+      const long long now_ = (long long)__builtin_amdgcn_s_memtime();    \
+      g_phase_cycles[i] += now_ - phase_t0_;                             \
+      phase_t0_ = now_;                                                  \
+    }                                                                    \
+  } while (0)
+#else
+#define PHASE_MARK(i)
+#endif
 
 struct FusedTrainArgs {
   RowSrc X;  // S rows of Din floats (gathered)
@@ -27,16 +43,19 @@ struct FusedTrainArgs {
   int round_bf16;
 };
 
-template <int H, int BM, int NOUT, int DMAX, class LossFn>
-__global__ void __launch_bounds__(512) fused_train_kernel(FusedTrainArgs a, LossFn fn) {
-  constexpr int NTN = H / 32, MTF = BM / 32, PH = H + 4, GROUPS = 512 / BM, PW = 36;
-  static_assert(NTN * MTF == 8, "one forward tile per wavefront");
-  constexpr int TPR = 512 / BM;          // threads staging one row of X
+template <int H, int BM, int NOUT, int DMAX, int NW, class LossFn>
+__global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(FusedTrainArgs a, LossFn fn) {
+  constexpr int NT = 64 * NW;
+  constexpr int NTN = H / 32, MTF = BM / 32, PH = H + 4, GROUPS = NT / BM, PW = 36;
+  static_assert(NTN * MTF == NW, "one forward tile per wavefront");
+  constexpr int TPR = NT / BM;           // threads staging one row of X
   constexpr int XP = DMAX / TPR;         // X elements per thread
-  constexpr int WV = H / 64;             // 16-byte vectors of a weight chunk per thread
-  constexpr int DW2_TPW = NTN * NTN >= 16 ? 2 : 1;  // dW2 tiles per wavefront
-  constexpr int DW2_KS = NTN * NTN >= 8 ? 1 : 8 / (NTN * NTN);  // split of the sample range when there are fewer tiles than wavefronts
-  constexpr int HPARTS = 512 / H, SPP = BM / HPARTS;
+  constexpr int WV = 8 * H / NT;         // 16-byte vectors of a weight chunk per thread
+  constexpr int DW2_TPW = NTN * NTN >= NW ? NTN * NTN / NW : 1;  // dW2 tiles per wavefront (one row of tiles at most)
+  constexpr int DW2_KS = NTN * NTN >= NW ? 1 : NW / (NTN * NTN);  // split of the sample range when there are fewer tiles than wavefronts
+  static_assert(DW2_TPW <= NTN && NTN % DW2_TPW == 0, "a wavefront's dW2 tiles share their row of tiles");
+  constexpr int Q1 = ((DMAX / 32) * NTN + NW - 1) / NW;  // dW1 work items per wavefront
+  constexpr int HPARTS = NT / H, SPP = BM / HPARTS;
 
   extern __shared__ __attribute__((aligned(16))) float lds[];
   float* Xs = lds;                         // [BM][px]
@@ -44,7 +63,7 @@ __global__ void __launch_bounds__(512) fused_train_kernel(FusedTrainArgs a, Loss
   float* H2 = H1 + BM * PH;                // [BM][PH]  h2, later dz2
   float* Ws = H2 + BM * PH;                // [32][H] or [H][36]
   float* red = Ws + H * PW;                // [GROUPS][BM][NOUT]
-  float* dls = red + 512 * NOUT;           // [BM][8]
+  float* dls = red + NT * NOUT;           // [BM][8]
   float* W3s = dls + BM * 8;               // [H][NOUT]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -53,18 +72,22 @@ __global__ void __launch_bounds__(512) fused_train_kernel(FusedTrainArgs a, Loss
   const int px = a.px;
   const int MT1 = (a.Din + 31) / 32;           // 32-row tiles of dW1
   const int tiles1 = MT1 * NTN;
-  const int KS1 = tiles1 * 4 <= 16 ? 4 : (tiles1 * 2 <= 16 ? 2 : 1);
+  const int KS1 = tiles1 * 4 <= Q1 * NW ? 4 : (tiles1 * 2 <= Q1 * NW ? 2 : 1);
   const int items1 = tiles1 * KS1;
 
-  for (int i = tid; i < BM * px; i += 512) Xs[i] = 0.f;  // the padding columns stay zero for good
-  for (int i = tid; i < H * NOUT; i += 512) W3s[i] = a.W3[i];
+  for (int i = tid; i < BM * px; i += NT) Xs[i] = 0.f;  // the padding columns stay zero for good
+  for (int i = tid; i < H * NOUT; i += NT) W3s[i] = a.W3[i];
   __syncthreads();
 
-  floatx16 acc1[2], acc2[2];  // dW1 / dW2 tiles of this wavefront, persistent
+  floatx16 acc1[Q1], acc2[DW2_TPW];  // dW1 / dW2 tiles of this wavefront, persistent
 #pragma unroll
-  for (int q = 0; q < 2; ++q)
+  for (int q = 0; q < Q1; ++q)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc1[q][r] = acc2[q][r] = 0.f;
+    for (int r = 0; r < 16; ++r) acc1[q][r] = 0.f;
+#pragma unroll
+  for (int q = 0; q < DW2_TPW; ++q)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc2[q][r] = 0.f;
   float gw[NOUT], gb[NOUT], st[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int k = 0; k < NOUT; ++k) gw[k] = gb[k] = 0.f;
@@ -87,7 +110,7 @@ __global__ void __launch_bounds__(512) fused_train_kernel(FusedTrainArgs a, Loss
   auto fetch_w = [&](const float* W, int k0, int K) {  // rows k0..k0+31 of W[K][H]
 #pragma unroll
     for (int p = 0; p < WV; ++p) {
-      const int f = tid + 512 * p, row = f / (H / 4), c4 = f % (H / 4);
+      const int f = tid + NT * p, row = f / (H / 4), c4 = f % (H / 4);
       wr[p] = (k0 + row < K) ? *reinterpret_cast<const float4*>(W + (int64_t)(k0 + row) * H + 4 * c4)
                              : make_float4(0.f, 0.f, 0.f, 0.f);
     }
@@ -95,21 +118,21 @@ __global__ void __launch_bounds__(512) fused_train_kernel(FusedTrainArgs a, Loss
   auto stage_w = [&]() {
 #pragma unroll
     for (int p = 0; p < WV; ++p) {
-      const int f = tid + 512 * p;
+      const int f = tid + NT * p;
       *reinterpret_cast<float4*>(&Ws[(f / (H / 4)) * H + 4 * (f % (H / 4))]) = wr[p];
     }
   };
   auto fetch_wt = [&](int j0) {  // columns j0..j0+31 of W2, all H rows (k-contiguous chunk for the transposed product)
 #pragma unroll
     for (int p = 0; p < WV; ++p) {
-      const int f = tid + 512 * p, i = f >> 3, c4 = f & 7;
+      const int f = tid + NT * p, i = f >> 3, c4 = f & 7;
       wr[p] = *reinterpret_cast<const float4*>(a.W2 + (int64_t)i * H + j0 + 4 * c4);
     }
   };
   auto stage_wt = [&]() {
 #pragma unroll
     for (int p = 0; p < WV; ++p) {
-      const int f = tid + 512 * p;
+      const int f = tid + NT * p;
       *reinterpret_cast<float4*>(&Ws[(f >> 3) * PW + 4 * (f & 7)]) = wr[p];
     }
   };
@@ -118,6 +141,9 @@ __global__ void __launch_bounds__(512) fused_train_kernel(FusedTrainArgs a, Loss
   const int64_t ntiles = (a.S + BM - 1) / BM;
   int64_t tile = blockIdx.x;
   if (tile < ntiles) fetch_tile_inputs(tile * BM);
+#ifdef MARL_PHASE_TIMERS
+  long long phase_t0_ = (long long)__builtin_amdgcn_s_memtime();
+#endif
   for (; tile < ntiles; tile += gridDim.x) {
     const int64_t s0 = tile * BM;
     // ---- this tile's observations to LDS; next tile's on their way
@@ -131,6 +157,7 @@ __global__ void __launch_bounds__(512) fused_train_kernel(FusedTrainArgs a, Loss
     __syncthreads();
     if (tile + gridDim.x < ntiles) fetch_tile_inputs((tile + gridDim.x) * BM);
 
+    PHASE_MARK(0);
     floatx16 acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
@@ -153,6 +180,7 @@ __global__ void __launch_bounds__(512) fused_train_kernel(FusedTrainArgs a, Loss
       }
       __syncthreads();
     }
+    PHASE_MARK(1);
     {
       const int n = nt * 32 + lo;
       const float bias = a.b1[n];
@@ -166,6 +194,7 @@ __global__ void __launch_bounds__(512) fused_train_kernel(FusedTrainArgs a, Loss
         if ((r & 3) == 3) __builtin_amdgcn_sched_barrier(0);
       }
     }
+    PHASE_MARK(2);
     // ---- layer 2
 #pragma unroll 1
     for (int c = 0; c < H / 32; ++c) {
@@ -185,6 +214,7 @@ __global__ void __launch_bounds__(512) fused_train_kernel(FusedTrainArgs a, Loss
       }
       __syncthreads();
     }
+    PHASE_MARK(3);
     floatx16 h2r;  // h2 of this wavefront's tile
     {
       const int n = nt * 32 + lo;
@@ -200,6 +230,7 @@ __global__ void __launch_bounds__(512) fused_train_kernel(FusedTrainArgs a, Loss
       }
     }
     __syncthreads();
+    PHASE_MARK(4);
     // ---- output layer on the ALUs: thread -> (sample tid % BM, slice tid / BM of the hidden units)
     {
       const int s = tid % BM, grp = tid / BM;
@@ -217,6 +248,7 @@ __global__ void __launch_bounds__(512) fused_train_kernel(FusedTrainArgs a, Loss
       for (int k = 0; k < NOUT; ++k) red[(grp * BM + s) * NOUT + k] = part[k];
     }
     __syncthreads();
+    PHASE_MARK(5);
     if (tid < BM) {
       float out[NOUT], dl[NOUT];
 #pragma unroll
@@ -234,6 +266,7 @@ __global__ void __launch_bounds__(512) fused_train_kernel(FusedTrainArgs a, Loss
       for (int k = 0; k < NOUT; ++k) gb[k] += dl[k];
     }
     __syncthreads();
+    PHASE_MARK(6);
     // ---- W3 gradient: gW3[i][k] += sum_s h2[s][i] dl[s][k]   (thread -> hidden unit tid % H, a share of the samples)
     {
       const int i = tid % H, part = tid / H;
@@ -245,6 +278,7 @@ __global__ void __launch_bounds__(512) fused_train_kernel(FusedTrainArgs a, Loss
       }
     }
     __syncthreads();
+    PHASE_MARK(7);
     // ---- dz2 = (dl W3^T) * (1 - h2^2) -> LDS over h2; the rank-NOUT product runs on the matrix cores (k padded to 8)
     {
       const int n = nt * 32 + lo;
@@ -270,13 +304,14 @@ __global__ void __launch_bounds__(512) fused_train_kernel(FusedTrainArgs a, Loss
       gb2r += csum;
     }
     __syncthreads();
+    PHASE_MARK(8);
     // ---- dW2 += h1^T dz2   (k runs over the samples of the tile)
     {
       const int t0 = (wave * DW2_TPW) % (NTN * NTN);
       const int it = t0 / NTN, jt = t0 % NTN;
       const int ks = (wave * DW2_TPW) / (NTN * NTN);
       constexpr int KLEN = BM / DW2_KS;
-#pragma unroll 2
+#pragma unroll 1
       for (int kb = ks * KLEN; kb < (ks + 1) * KLEN; kb += 8) {
         float af[4], bf[DW2_TPW][4];
 #pragma unroll
@@ -291,6 +326,7 @@ __global__ void __launch_bounds__(512) fused_train_kernel(FusedTrainArgs a, Loss
           for (int q = 0; q < DW2_TPW; ++q) acc2[q] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[j], bf[q][j], acc2[q], 0, 0, 0);
       }
     }
+    PHASE_MARK(9);
     // ---- dz1 = (dz2 W2^T) * (1 - h1^2), in place over h1
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
@@ -309,6 +345,7 @@ __global__ void __launch_bounds__(512) fused_train_kernel(FusedTrainArgs a, Loss
       }
       __syncthreads();
     }
+    PHASE_MARK(10);
     {
       const int n = nt * 32 + lo;
       float csum = 0.f;
@@ -325,15 +362,16 @@ __global__ void __launch_bounds__(512) fused_train_kernel(FusedTrainArgs a, Loss
       gb1r += csum;
     }
     __syncthreads();
+    PHASE_MARK(11);
     // ---- dW1 += X^T dz1
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      const int item = wave + 8 * q;
+    for (int q = 0; q < Q1; ++q) {
+      const int item = wave + NW * q;
       if (item < items1) {
         const int t = item / KS1, ks = item - t * KS1;
         const int dt = t / NTN, jt = t % NTN;
         const int klen = BM / KS1;
-#pragma unroll 2
+#pragma unroll 1
         for (int kb = ks * klen; kb < (ks + 1) * klen; kb += 8) {
           float af[4], bf[4];
 #pragma unroll
@@ -346,7 +384,9 @@ __global__ void __launch_bounds__(512) fused_train_kernel(FusedTrainArgs a, Loss
         }
       }
     }
+    PHASE_MARK(12);
     __syncthreads();  // the tile buffers are reused by the next row tile
+    PHASE_MARK(13);
   }
 
   // ---- flush the register-resident gradients
@@ -362,8 +402,8 @@ __global__ void __launch_bounds__(512) fused_train_kernel(FusedTrainArgs a, Loss
       }
   }
 #pragma unroll
-  for (int q = 0; q < 2; ++q) {
-    const int item = wave + 8 * q;
+  for (int q = 0; q < Q1; ++q) {
+    const int item = wave + NW * q;
     if (item < items1) {
       const int t = item / KS1, dt = t / NTN, jt = t % NTN;
 #pragma unroll
@@ -382,7 +422,7 @@ __global__ void __launch_bounds__(512) fused_train_kernel(FusedTrainArgs a, Loss
 #pragma unroll
     for (int k = 0; k < NOUT; ++k) atomicAdd(&a.gW3[i * NOUT + k], gw[k]);
   }
-  if (tid < BM) {  // whole wavefronts: BM is 64 or 128
+  if (tid < (BM < 64 ? 64 : BM)) {  // whole wavefronts; lanes past BM hold zeros
 #pragma unroll
     for (int k = 0; k < NOUT; ++k) {
       float v = gb[k];
@@ -406,10 +446,10 @@ inline int fused_train_px(int Din) {
   return px;
 }
 
-template <int H, int BM, int NOUT, int DMAX, class LossFn>
+template <int H, int BM, int NOUT, int DMAX, int NW, class LossFn>
 inline int32_t launch_fused_train_inst(const FusedTrainArgs& a, const LossFn& fn, hipStream_t s) {
-  auto kern = fused_train_kernel<H, BM, NOUT, DMAX, LossFn>;
-  const size_t floats = (size_t)BM * a.px + 2 * (size_t)BM * (H + 4) + (size_t)H * 36 + 512 * NOUT + BM * 8 + H * NOUT;
+  auto kern = fused_train_kernel<H, BM, NOUT, DMAX, NW, LossFn>;
+  const size_t floats = (size_t)BM * a.px + 2 * (size_t)BM * (H + 4) + (size_t)H * 36 + 64 * NW * NOUT + BM * 8 + H * NOUT;
   const size_t bytes = floats * 4;
   static bool configured = false;  // per instantiation
   if (!configured) {
@@ -418,8 +458,8 @@ inline int32_t launch_fused_train_inst(const FusedTrainArgs& a, const LossFn& fn
     configured = true;
   }
   const int64_t tiles = (a.S + BM - 1) / BM;
-  const unsigned grid = (unsigned)std::min<int64_t>(tiles, 256);
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(512), bytes, s, a, fn);
+  const unsigned grid = (unsigned)std::min<int64_t>(tiles, NW == 4 ? 512 : 256);  // resident workgroups: two per CU with four wavefronts
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * NW), bytes, s, a, fn);
   return launch_status();
 }
 
@@ -428,11 +468,11 @@ inline int32_t launch_fused_train(int H, const FusedTrainArgs& a, const LossFn& 
   // algorithmic flops: forward 2S(DH + HH), backward 2S(HH + HH + DH)
   TimedLaunch timed(KC_FUSED_TRAIN, 2.0 * (double)a.S * (2.0 * a.Din * H + 3.0 * H * H), s);
   if (H == 128) {
-    if (a.Din <= 32) return launch_fused_train_inst<128, 64, NOUT, 32, LossFn>(a, fn, s);
-    return launch_fused_train_inst<128, 64, NOUT, 96, LossFn>(a, fn, s);
+    if (a.Din <= 32) return launch_fused_train_inst<128, 64, NOUT, 32, 8, LossFn>(a, fn, s);
+    return launch_fused_train_inst<128, 64, NOUT, 96, 8, LossFn>(a, fn, s);
   }
-  if (a.Din <= 32) return launch_fused_train_inst<64, 128, NOUT, 32, LossFn>(a, fn, s);
-  return launch_fused_train_inst<64, 128, NOUT, 96, LossFn>(a, fn, s);
+  if (a.Din <= 32) return launch_fused_train_inst<64, 128, NOUT, 32, 8, LossFn>(a, fn, s);
+  return launch_fused_train_inst<64, 128, NOUT, 96, 8, LossFn>(a, fn, s);
 }
 
 }  // namespace marl

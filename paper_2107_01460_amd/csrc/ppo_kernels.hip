@@ -633,3 +633,16 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
 }
 
 }  // namespace marl
+
+#ifdef MARL_PHASE_TIMERS
+// Development aid (not part of the built library): cycles per phase of the fused training kernel, workgroup 0.
+extern "C" int32_t marl_debug_phase_cycles(long long* out16, int32_t reset) {
+  if (hipDeviceSynchronize() != hipSuccess) return -1;
+  if (out16 && hipMemcpyFromSymbol(out16, HIP_SYMBOL(marl::g_phase_cycles), 16 * sizeof(long long)) != hipSuccess) return -1;
+  if (reset) {
+    long long z[16] = {0};
+    if (hipMemcpyToSymbol(HIP_SYMBOL(marl::g_phase_cycles), z, sizeof(z)) != hipSuccess) return -1;
+  }
+  return 0;
+}
+#endif

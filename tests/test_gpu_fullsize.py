@@ -1,0 +1,229 @@
+"""Parity at the full workload sizes, in the launch configuration the benchmark times.
+
+The oracle cannot run a full-size iteration in test time, so each stage is checked on what it can compute:
+
+* rollout: environments are independent and every random draw is keyed by (seed, env, episode / step), so the
+  oracle re-simulates the FIRST n_o environments of the full-size GPU rollout, teacher-forced with the GPU's
+  own actions: observations, rewards, dones and the final state bit for bit, log-probabilities and values
+  within tolerance.  Rows sampled anywhere in the batch (the ragged tail included) get their value and
+  log-probability recomputed by the oracle one by one, and the whole final state is checked for the
+  invariants of the rules (distinct in-grid cells, level ranges).
+* GAE: lanes are independent; the oracle recomputes sampled environments.
+* PPO update: a small oracle trajectory is tiled K times along the environment axis and the row order is
+  built so that every full-size minibatch holds exactly K copies of the rows of the matching small
+  minibatch.  Means over K identical copies are the means over one copy, so the loss statistics, the
+  gradient and the optimiser steps of the full-size GPU update must equal the oracle's on the small one.
+"""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from gpu_util import REL_TOL, dev, err, rel_err
+
+pytestmark = pytest.mark.gpu
+
+# environments the oracle simulates per configuration (prefix of the batch / width of the tiled trajectory)
+N_ORACLE = {1: 8, 2: 16, 3: 16, 4: 2, 5: 64}
+
+
+@pytest.fixture(scope="module")
+def M():
+    import paper_2107_01460_amd as m
+    return m
+
+
+def log_softmax(x):
+    x = np.asarray(x, np.float64)
+    m = x.max(axis=-1, keepdims=True)
+    return x - m - np.log(np.exp(x - m).sum(axis=-1, keepdims=True))
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 5])
+def test_full_size_rollout_and_gae(M, orc, k):
+    cfg = dict(W.CONFIGS[k - 1])
+    N, A, T, F, G = cfg["n_envs"], cfg["n_agents"], cfg["rollout_len"], cfg["n_food"], cfg["grid"]
+    n_o = N_ORACLE[k]
+    print("case", cfg["name"], "N", N, "oracle envs", n_o, flush=True)
+    tol = REL_TOL[cfg["precision"]]
+    params = W.init_params(cfg, bias_scale=0.1)
+    gs = M.EnvState(cfg)
+    M.env_reset(cfg, gs)
+    gtr = M.Traj(cfg)
+    sizes = M.query_sizes(cfg)
+    ws = M.alloc_workspace(sizes.rollout_workspace_bytes)
+    step0 = 7 * T
+    M.rollout(cfg, gs, dev(params), gtr, step0, ws)
+    M.compute_gae(cfg, gtr)
+    torch.cuda.synchronize()
+
+    # ---- the first n_o environments, re-simulated by the oracle with the GPU's actions
+    co = W.scaled(cfg, n_envs=n_o, n_minibatches=1)
+    os_ = orc.EnvState(co)
+    orc.env_reset(co, os_)
+    otr = orc.Traj(co)
+    g_action = gtr.action[:, :n_o].cpu().numpy()
+    orc.rollout(co, os_, params, otr, step_offset=step0, forced_actions=g_action)
+    assert np.array_equal(gtr.obs[:, :n_o].cpu().numpy(), otr.obs)
+    assert np.array_equal(gtr.reward[:, :n_o].cpu().numpy().view(np.uint32), otr.reward.view(np.uint32))
+    assert np.array_equal(gtr.done[:, :n_o].cpu().numpy(), otr.done)
+    host = gs.to_host()
+    for f in M.EnvState.FIELDS:
+        assert np.array_equal(host[f][..., :n_o], getattr(os_, f)), f
+    assert err(gtr.logp[:, :n_o].cpu().numpy(), otr.logp, cfg) < tol
+    assert err(gtr.value[:, :n_o].cpu().numpy(), otr.value, cfg) < tol
+    assert err(gtr.last_value[:n_o].cpu().numpy(), otr.last_value, cfg) < tol
+    if cfg["precision"] == 0:  # the GPU's own draws against the oracle's, away from near-ties
+        mism = g_action != otr.sampled
+        lim = 1e-5 + 2e-4 * np.abs(otr.logits).max()
+        assert np.all(otr.gap[mism] < lim), (mism.sum(), otr.gap[mism].max())
+        assert mism.mean() < 5e-3
+
+    # ---- rows sampled anywhere in the batch: value and log-probability recomputed one by one
+    rng = np.random.default_rng(50 + k)
+    n_rows = 96 if k != 4 else 24
+    ts = rng.integers(0, T, n_rows)
+    ns = np.concatenate([rng.integers(0, N, n_rows - 8), np.arange(N - 8, N)])  # the last environments included
+    ti, ni = torch.from_numpy(ts).cuda(), torch.from_numpy(ns).cuda()
+    obs_rows = gtr.obs[ti, ni].cpu().numpy()
+    ol, ov = orc.policy_forward(co, params, obs_rows)
+    act = gtr.action[ti, ni].cpu().numpy()
+    o_logp = np.take_along_axis(log_softmax(ol), act[..., None].astype(np.int64), axis=-1)[..., 0]
+    assert err(gtr.value[ti, ni].cpu().numpy(), ov, cfg) < tol
+    assert err(gtr.logp[ti, ni].cpu().numpy(), o_logp, cfg) < tol
+
+    # ---- invariants of the rules over every environment of the final state
+    cells_a = host["agent_row"].astype(np.int64) * G + host["agent_col"]
+    cells_f = host["food_row"].astype(np.int64) * G + host["food_col"]
+    present = host["food_lvl"] > 0
+    assert host["agent_row"].max() < G and host["agent_col"].max() < G
+    assert host["food_row"].max() < G and host["food_col"].max() < G
+    assert host["agent_lvl"].min() >= 1 and host["agent_lvl"].max() <= cfg["max_level"]
+    assert np.all(present.sum(axis=0) >= 1)                       # an episode without food has been reset
+    assert np.all((host["t_in_ep"] >= 0) & (host["t_in_ep"] < cfg["episode_cap"]))
+    allc = np.concatenate([cells_a, np.where(present, cells_f, -1 - np.arange(F)[:, None])], axis=0)
+    srt = np.sort(allc, axis=0)
+    assert np.all(srt[1:] != srt[:-1])                            # no two entities share a cell
+    done_rate = float(gtr.done.float().mean())
+    assert 0.0 < done_rate < 0.5
+    # own level at the centre of every observation of the last slab
+    last = gtr.obs[T].cpu().numpy()
+    centre = (cfg["view"] ** 2 // 2) * 3
+    assert np.array_equal(last[:, :, centre], host["agent_lvl"].T.astype(np.float32))
+
+    # ---- GAE on sampled environments (all time steps of each)
+    pick = np.concatenate([rng.integers(0, N, 60), np.arange(N - 4, N)])
+    cg = W.scaled(cfg, n_envs=len(pick), n_minibatches=1)
+    og = orc.Traj(cg)
+    pi = torch.from_numpy(pick).cuda()
+    og.reward[:] = gtr.reward[:, pi].cpu().numpy()
+    og.value[:] = gtr.value[:, pi].cpu().numpy()
+    og.done[:] = gtr.done[:, pi].cpu().numpy()
+    og.last_value[:] = gtr.last_value[pi].cpu().numpy()
+    orc.compute_gae(cg, og)
+    assert rel_err(gtr.adv[:, pi].cpu().numpy(), og.adv) < 1e-4
+    assert rel_err(gtr.ret[:, pi].cpu().numpy(), og.ret) < 1e-4
+
+
+def tiled_perm(cfg_full, cfg_small, perm_small, seed):
+    """Row order of the tiled trajectory whose minibatch m is K shuffled copies of small minibatch m."""
+    N, n_s, T = cfg_full["n_envs"], cfg_small["n_envs"], cfg_full["rollout_len"]
+    K, Mb = N // n_s, cfg_full["n_minibatches"]
+    Rs = T * n_s
+    rng = np.random.default_rng(seed)
+    out = np.empty((perm_small.shape[0], T * N), np.int32)
+    copies = np.arange(K, dtype=np.int64)[:, None] * n_s
+    for e in range(perm_small.shape[0]):
+        parts = []
+        for m in range(Mb):
+            rows = perm_small[e, m * Rs // Mb:(m + 1) * Rs // Mb].astype(np.int64)
+            t, n = rows // n_s, rows % n_s
+            full = (t * N + n)[None, :] + copies           # [K][rows of the small minibatch]
+            full = full.reshape(-1)
+            rng.shuffle(full)
+            parts.append(full)
+        out[e] = np.concatenate(parts).astype(np.int32)
+    return out
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 5])
+def test_full_size_ppo_update_tiled(M, orc, k):
+    cfg = dict(W.CONFIGS[k - 1])
+    if k == 4:
+        cfg["n_epochs"] = 2   # oracle time; the launch configuration of a minibatch does not depend on it
+    N, T, E, Mb = cfg["n_envs"], cfg["rollout_len"], cfg["n_epochs"], cfg["n_minibatches"]
+    n_s = N_ORACLE[k]
+    K = N // n_s
+    assert N % n_s == 0 and (T * n_s) % Mb == 0
+    cs = W.scaled(cfg, n_envs=n_s)
+    cf = cfg
+    print("case", cfg["name"], "N", N, "tile width", n_s, "copies", K, flush=True)
+    tol = REL_TOL[cfg["precision"]]
+
+    # ---- small oracle trajectory at perturbed parameters, both sides of the clip range exercised
+    params0 = W.init_params(cs, bias_scale=0.1)
+    s = orc.EnvState(cs)
+    orc.env_reset(cs, s)
+    otr = orc.Traj(cs)
+    orc.rollout(cs, s, params0, otr, step_offset=5)
+    orc.compute_gae(cs, otr)
+    rng = np.random.default_rng(200 + k)
+    params = (params0 + 0.1 * np.abs(params0).mean() * rng.normal(size=params0.size)).astype(np.float32)
+    otr.value[:] += (0.2 * rng.normal(size=otr.value.shape)).astype(np.float32)
+    otr.logp[:] += rng.choice([-0.4, 0.0, 0.0, 0.4], size=otr.logp.shape).astype(np.float32)
+    perm_s = W.make_perm(cs, seed=11)
+    perm_f = tiled_perm(cf, cs, perm_s, seed=12)
+    assert np.array_equal(np.sort(perm_f[0]), np.arange(T * N))
+
+    # ---- the same trajectory tiled K times along the environment axis, on the device
+    gtr = M.Traj(cf)
+    for f in ("obs", "action", "logp", "value", "reward", "adv", "ret"):
+        src = getattr(otr, f)
+        reps = (1, K) + (1,) * (src.ndim - 2)
+        getattr(gtr, f).copy_(torch.from_numpy(np.tile(src, reps)))
+    gtr.done.copy_(torch.from_numpy(np.tile(otr.done, (1, K))))
+    gtr.last_value.copy_(torch.from_numpy(np.tile(otr.last_value, (K, 1))))
+    ws = M.alloc_workspace(M.query_sizes(cf).update_workspace_bytes)
+    d_perm = dev(perm_f)
+
+    # ---- (A) one epoch with a step size too small to move any parameter: every minibatch is evaluated at the
+    # same parameters, so all M statistics rows and the last minibatch's gradient are held to the tight bound
+    tiny = dict(n_epochs=1, lr=1e-30, max_grad_norm=0.0)
+    ca_s, ca_f = dict(cs, **tiny), dict(cf, **tiny)
+    po, mo, vo = params.copy(), np.zeros_like(params), np.zeros_like(params)
+    ostats, ograd = orc.ppo_update(ca_s, otr, po, mo, vo, adam_step0=0, perm=perm_s[:1])
+    assert np.array_equal(po, params)
+    gp, gm, gv = dev(params), torch.zeros(params.size, device="cuda"), torch.zeros(params.size, device="cuda")
+    stats = torch.zeros((Mb, 8), device="cuda")
+    gdump = torch.zeros(params.size, device="cuda")
+    M.ppo_update(ca_f, gtr, gp, gm, gv, 0, d_perm[:1].contiguous(), stats, gdump, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(gp.cpu().numpy(), params)
+    g = gdump.cpu().numpy()
+    Pa = orc.actor_param_count(cs)
+    assert err(g[:Pa], ograd[:Pa], cfg) < tol, "actor gradient"
+    assert err(g[Pa:], ograd[Pa:], cfg) < tol, "critic gradient"
+    st = stats.cpu().numpy()
+    assert np.all((ostats[:, 4] > 0.0) & (ostats[:, 4] < 1.0))
+    for i in (0, 1, 2, 3, 5, 6):
+        assert np.all(np.abs(st[:, i] - ostats[:, i]) < tol * np.maximum(np.abs(ostats[:, i]), 1e-2)), (i, st[:, i], ostats[:, i])
+    assert np.all(np.abs(st[:, 4] - ostats[:, 4]) < 3.0 / (T * n_s * cfg["n_agents"] / Mb))
+    assert np.all(st[:, 7] == 0)
+
+    # ---- (B) the configuration's own E epochs x M minibatches with its step size and gradient clipping
+    po, mo, vo = params.copy(), np.zeros_like(params), np.zeros_like(params)
+    ostats, ograd = orc.ppo_update(cs, otr, po, mo, vo, adam_step0=0, perm=perm_s)
+    gp, gm, gv = dev(params), torch.zeros(params.size, device="cuda"), torch.zeros(params.size, device="cuda")
+    stats = torch.zeros((E * Mb, 8), device="cuda")
+    M.ppo_update(cf, gtr, gp, gm, gv, 0, d_perm, stats, gdump, ws)
+    torch.cuda.synchronize()
+    st = stats.cpu().numpy()
+    for i in (0, 1, 2, 5, 6):
+        assert np.all(np.abs(st[:, i] - ostats[:, i]) < 20 * tol * np.maximum(np.abs(ostats[:, i]), 1e-2)), (i, st[:, i], ostats[:, i])
+    assert np.all(st[:, 7] == 0)
+    if cfg["precision"] == 0:
+        # Adam magnifies differences of near-zero gradient elements: bound on the scale of the largest move.
+        # (bf16: the sign of a near-zero gradient element decides a full +-lr step, so after E*M steps the two
+        # parameter vectors are no longer comparable element by element; part (A) holds its gradient tightly.)
+        assert rel_err(gp.cpu().numpy() - params, po - params, floor=1.0) < 0.05
+        assert err(gdump.cpu().numpy(), ograd, cfg) < 100 * tol
