@@ -54,6 +54,14 @@ inline NetOffsets net_offsets(int64_t base, int Din, int H, int Dout) {
 // starts on a 64-float boundary, so that 16-byte loads of weight rows are always aligned.
 struct ParamMap {
   int64_t src[13], dst[13];  // 12 blocks (actor 6, critic 6) + end
+  // After the 12 blocks, per network: W1, W2 and W2 transposed once more in the order the matrix-core kernels
+  // read their B operand straight from memory: element (k, n) of a [K][H] matrix at ((k / 4) * H + n) * 4 + k % 4,
+  // so that the four k values a lane feeds to consecutive MFMAs are one 16-byte load, contiguous across lanes.
+  // W1 is zero-padded to kpad1 rows (a multiple of 16).
+  int64_t sw_w1[2], sw_w2[2], sw_w2t[2];
+  int din[2], kpad1[2];
+  int hidden[2];
+  int64_t total;             // floats of the whole working copy
 };
 inline ParamMap param_map(const Dims& d) {
   ParamMap m;
@@ -65,6 +73,21 @@ inline ParamMap param_map(const Dims& d) {
     m.dst[i] = off;
     if (i < 12) off += ((src[i + 1] - src[i] + 63) / 64) * 64;
   }
+  m.hidden[0] = d.Ha;
+  m.hidden[1] = d.Hc;
+  m.din[0] = d.D;
+  m.din[1] = d.Dc;
+  for (int n = 0; n < 2; ++n) {
+    const int64_t H = m.hidden[n];
+    m.kpad1[n] = (m.din[n] + 15) / 16 * 16;
+    m.sw_w1[n] = off;
+    off += ((m.kpad1[n] * H + 63) / 64) * 64;
+    m.sw_w2[n] = off;
+    off += ((H * H + 63) / 64) * 64;
+    m.sw_w2t[n] = off;
+    off += ((H * H + 63) / 64) * 64;
+  }
+  m.total = off;
   return m;
 }
 inline NetOffsets padded_offsets(const ParamMap& m, int net) {

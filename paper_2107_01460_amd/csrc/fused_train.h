@@ -38,19 +38,93 @@ struct FusedTrainArgs {
   int Din;
   int px;  // pitch of the X tile in LDS: multiple of 4, px/4 odd, >= 32*ceil(Din/32)
   const float *W1, *b1, *W2, *b2, *W3, *b3;  // aligned working copy, W[in][H]
+  const float *W1s, *W2s, *W2Ts;             // operand-order copies: (k, n) at ((k / 4) * H + n) * 4 + k % 4; W1s zero-padded to 16-row groups
   float *gW1, *gb1, *gW2, *gb2, *gW3, *gb3;  // gradient blocks, accumulated with atomics
   float* stats;                              // 5 floats, atomics
   int round_bf16;
 };
 
+// acc[q] += A^T B_q over the samples kb0 .. kb0 + klen of a row tile held in LDS: A column block at Ap (pitch pa),
+// B column blocks at Bp + 32 q (pitch pb).  The operands of the next k step are read before the MFMAs of the
+// current one are issued, so the LDS latency hides behind the matrix pipe even with one wavefront per SIMD.
+template <int NB>
+__device__ __forceinline__ void outer_product_accumulate(const float* __restrict__ Ap, int pa, const float* __restrict__ Bp,
+                                                         int pb, int kb0, int klen, int hi, floatx16* acc) {
+  float af[4], bf[NB][4];
+  auto read = [&](int kb, float (&x)[4], float (&y)[NB][4]) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      x[j] = Ap[(kb + 4 * hi + j) * pa];
+#pragma unroll
+      for (int q = 0; q < NB; ++q) y[q][j] = Bp[(kb + 4 * hi + j) * pb + 32 * q];
+    }
+  };
+  read(kb0, af, bf);
+#pragma unroll 2
+  for (int kb = kb0; kb < kb0 + klen; kb += 8) {
+    float an[4], bn[NB][4];
+    const int kn = kb + 8 < kb0 + klen ? kb + 8 : kb;  // the last step re-reads its own operands
+    read(kn, an, bn);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int q = 0; q < NB; ++q) acc[q] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[j], bf[q][j], acc[q], 0, 0, 0);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      af[j] = an[j];
+#pragma unroll
+      for (int q = 0; q < NB; ++q) bf[q][j] = bn[q][j];
+    }
+  }
+}
+
+// acc += A B for this wavefront's 32x32 tile: A rows in LDS (As points at this lane's row, + 4 * hi), B in global
+// memory in operand order (element (k, n) of the [K][LDB] matrix at ((k / 4) * LDB + n) * 4 + k % 4; Bg points at
+// this lane's 16 bytes of k quad `hi`), `kgroups` groups of 16 along k.  B goes straight from the cache hierarchy
+// into registers with 16-byte loads that are contiguous across the wavefront, one group ahead of its use, so a
+// layer needs no staging buffer and no barrier of its own.  Both operands must be readable (zero-padded) up to
+// 16 * kgroups along k.
+template <int LDB>
+__device__ __forceinline__ void gemm_phase_regs(const float* __restrict__ As, const float* __restrict__ Bg, int kgroups,
+                                                floatx16& acc) {
+  constexpr int kDepth = 3;  // groups in flight: the one in use and two on their way
+  float4 av[kDepth][2], bv[kDepth][2];
+  auto load = [&](int g, float4 (&a2)[2], float4 (&b2)[2]) {
+    const int gc = g < kgroups ? g : kgroups - 1;  // past the end: re-read the last group
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      a2[u] = *reinterpret_cast<const float4*>(As + 16 * gc + 8 * u);
+      b2[u] = *reinterpret_cast<const float4*>(Bg + ((int64_t)16 * gc + 8 * u) * LDB);
+    }
+  };
+#pragma unroll
+  for (int d = 0; d < kDepth - 1; ++d) load(d, av[d], bv[d]);
+#pragma unroll 1
+  for (int g0 = 0; g0 < kgroups; g0 += kDepth) {
+#pragma unroll
+    for (int d = 0; d < kDepth; ++d) {
+      const int g = g0 + d;
+      if (g < kgroups) {  // uniform
+        load(g + kDepth - 1, av[(d + kDepth - 1) % kDepth], bv[(d + kDepth - 1) % kDepth]);
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const float af[4] = {av[d][u].x, av[d][u].y, av[d][u].z, av[d][u].w};
+          const float bf[4] = {bv[d][u].x, bv[d][u].y, bv[d][u].z, bv[d][u].w};
+#pragma unroll
+          for (int j = 0; j < 4; ++j) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(af[j], bf[j], acc, 0, 0, 0);
+        }
+      }
+    }
+  }
+}
+
 template <int H, int BM, int NOUT, int DMAX, int NW, class LossFn>
 __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(FusedTrainArgs a, LossFn fn) {
   constexpr int NT = 64 * NW;
-  constexpr int NTN = H / 32, MTF = BM / 32, PH = H + 4, GROUPS = NT / BM, PW = 36;
+  constexpr int NTN = H / 32, MTF = BM / 32, PH = H + 4, GROUPS = NT / BM;
   static_assert(NTN * MTF == NW, "one forward tile per wavefront");
   constexpr int TPR = NT / BM;           // threads staging one row of X
   constexpr int XP = DMAX / TPR;         // X elements per thread
-  constexpr int WV = 8 * H / NT;         // 16-byte vectors of a weight chunk per thread
   constexpr int DW2_TPW = NTN * NTN >= NW ? NTN * NTN / NW : 1;  // dW2 tiles per wavefront (one row of tiles at most)
   constexpr int DW2_KS = NTN * NTN >= NW ? 1 : NW / (NTN * NTN);  // split of the sample range when there are fewer tiles than wavefronts
   static_assert(DW2_TPW <= NTN && NTN % DW2_TPW == 0, "a wavefront's dW2 tiles share their row of tiles");
@@ -61,8 +135,7 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
   float* Xs = lds;                         // [BM][px]
   float* H1 = Xs + BM * a.px;              // [BM][PH]  h1, later dz1
   float* H2 = H1 + BM * PH;                // [BM][PH]  h2, later dz2
-  float* Ws = H2 + BM * PH;                // [32][H] or [H][36]
-  float* red = Ws + H * PW;                // [GROUPS][BM][NOUT]
+  float* red = H2 + BM * PH;               // [GROUPS][NOUT][BM]
   float* dls = red + NT * NOUT;           // [BM][8]
   float* W3s = dls + BM * 8;               // [H][NOUT]
 
@@ -72,9 +145,27 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
   const int px = a.px;
   const int MT1 = (a.Din + 31) / 32;           // 32-row tiles of dW1
   const int tiles1 = MT1 * NTN;
+  // dW1 work items of this wavefront (slot q < Q1): 32x32 tiles of the gradient, whole or split over the samples
+  // of the row tile.  With more tiles than wavefronts (but no more than twice as many, and a remainder that
+  // divides the wavefront count) every wavefront takes one whole tile and an equal share of the remaining ones;
+  // otherwise every tile is split KS1 ways and the items are dealt round-robin.
+  const int rem1 = tiles1 - NW;
+  const bool balanced1 = Q1 >= 2 && rem1 > 0 && rem1 <= NW && NW % rem1 == 0 && (BM / (NW / rem1)) % 8 == 0;
   const int KS1 = tiles1 * 4 <= Q1 * NW ? 4 : (tiles1 * 2 <= Q1 * NW ? 2 : 1);
-  const int items1 = tiles1 * KS1;
-
+  auto dw1_item = [&](int q, int& t, int& kb0, int& klen) -> bool {
+    if (balanced1) {
+      if (q == 0) {
+        t = wave; kb0 = 0; klen = BM;
+        return true;
+      }
+      const int ks = NW / rem1;
+      t = NW + wave / ks; klen = BM / ks; kb0 = (wave % ks) * klen;
+      return q == 1;
+    }
+    const int item = wave + NW * q;
+    t = item / KS1; klen = BM / KS1; kb0 = (item - t * KS1) * klen;
+    return item < tiles1 * KS1;
+  };
   for (int i = tid; i < BM * px; i += NT) Xs[i] = 0.f;  // the padding columns stay zero for good
   for (int i = tid; i < H * NOUT; i += NT) W3s[i] = a.W3[i];
   __syncthreads();
@@ -93,93 +184,58 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
   for (int k = 0; k < NOUT; ++k) gw[k] = gb[k] = 0.f;
   float gb1r = 0.f, gb2r = 0.f;  // bias gradients of column nt*32+lo (lanes hi == 0)
 
-  // ---- staging helpers
+  // ---- staging helpers.  The inputs of the next tile come in two steps: the gather entries at the top of a
+  // tile, the rows themselves half a tile later, so that neither dependent load is ever waited for.
   float xr[XP];
   typename LossFn::In lin_next{};
+  int32_t xentry = 0, lentry = 0;
   const int xrow_l = tid / TPR, xcol0 = tid % TPR;
+  const auto prep = fn.prepare();
+  auto fetch_tile_entries = [&](int64_t s0) {
+    xentry = a.X.gather_entry(min(s0 + xrow_l, a.S - 1));
+    if (tid < BM && s0 + tid < a.S) lentry = fn.row_entry(s0 + tid);
+  };
   auto fetch_tile_inputs = [&](int64_t s0) {
-    const float* row = a.X.ptr(min(s0 + xrow_l, a.S - 1));
+    const float* row = a.X.ptr_with(min(s0 + xrow_l, a.S - 1), xentry);
 #pragma unroll
     for (int p = 0; p < XP; ++p) {
       const int c = xcol0 + TPR * p;
       xr[p] = c < a.Din ? row[c] : 0.f;
     }
-    if (tid < BM && s0 + tid < a.S) lin_next = fn.load(s0 + tid);
+    if (tid < BM && s0 + tid < a.S) lin_next = fn.load_with(s0 + tid, lentry);
   };
-  float4 wr[WV];
-  auto fetch_w = [&](const float* W, int k0, int K) {  // rows k0..k0+31 of W[K][H]
-#pragma unroll
-    for (int p = 0; p < WV; ++p) {
-      const int f = tid + NT * p, row = f / (H / 4), c4 = f % (H / 4);
-      wr[p] = (k0 + row < K) ? *reinterpret_cast<const float4*>(W + (int64_t)(k0 + row) * H + 4 * c4)
-                             : make_float4(0.f, 0.f, 0.f, 0.f);
-    }
-  };
-  auto stage_w = [&]() {
-#pragma unroll
-    for (int p = 0; p < WV; ++p) {
-      const int f = tid + NT * p;
-      *reinterpret_cast<float4*>(&Ws[(f / (H / 4)) * H + 4 * (f % (H / 4))]) = wr[p];
-    }
-  };
-  auto fetch_wt = [&](int j0) {  // columns j0..j0+31 of W2, all H rows (k-contiguous chunk for the transposed product)
-#pragma unroll
-    for (int p = 0; p < WV; ++p) {
-      const int f = tid + NT * p, i = f >> 3, c4 = f & 7;
-      wr[p] = *reinterpret_cast<const float4*>(a.W2 + (int64_t)i * H + j0 + 4 * c4);
-    }
-  };
-  auto stage_wt = [&]() {
-#pragma unroll
-    for (int p = 0; p < WV; ++p) {
-      const int f = tid + NT * p;
-      *reinterpret_cast<float4*>(&Ws[(f >> 3) * PW + 4 * (f & 7)]) = wr[p];
-    }
-  };
-
-  const int nk1 = MT1;
-  const int64_t ntiles = (a.S + BM - 1) / BM;
-  int64_t tile = blockIdx.x;
-  if (tile < ntiles) fetch_tile_inputs(tile * BM);
-#ifdef MARL_PHASE_TIMERS
-  long long phase_t0_ = (long long)__builtin_amdgcn_s_memtime();
-#endif
-  for (; tile < ntiles; tile += gridDim.x) {
-    const int64_t s0 = tile * BM;
-    // ---- this tile's observations to LDS; next tile's on their way
+  auto store_tile_inputs = [&]() {
 #pragma unroll
     for (int p = 0; p < XP; ++p) {
       const int c = xcol0 + TPR * p;
       if (c < a.Din) Xs[xrow_l * px + c] = xr[p];
     }
+  };
+  const int64_t ntiles = (a.S + BM - 1) / BM;
+  const int kpad1 = 16 * ((a.Din + 15) / 16);  // layer 1 contracts over the input width rounded up to a k group (W1 is zero-padded to it)
+  int64_t tile = blockIdx.x;
+  if (tile < ntiles) {
+    fetch_tile_entries(tile * BM);
+    fetch_tile_inputs(tile * BM);
+  }
+#ifdef MARL_PHASE_TIMERS
+  long long phase_t0_ = (long long)__builtin_amdgcn_s_memtime();
+#endif
+  for (; tile < ntiles; tile += gridDim.x) {
+    const int64_t s0 = tile * BM;
+    const bool have_next = tile + gridDim.x < ntiles;
+    // ---- this tile's observations to LDS
+    store_tile_inputs();
     const typename LossFn::In lin = lin_next;
-    fetch_w(a.W1, 0, a.Din);
+    if (have_next) fetch_tile_entries((tile + gridDim.x) * BM);
     __syncthreads();
-    if (tile + gridDim.x < ntiles) fetch_tile_inputs((tile + gridDim.x) * BM);
 
     PHASE_MARK(0);
     floatx16 acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
     // ---- layer 1
-#pragma unroll 1
-    for (int c = 0; c < nk1; ++c) {
-      stage_w();
-      __syncthreads();
-      if (c + 1 < nk1) fetch_w(a.W1, 32 * (c + 1), a.Din);
-      else fetch_w(a.W2, 0, H);
-#pragma unroll
-      for (int kb = 0; kb < 32; kb += 8) {
-        const float4 av = *reinterpret_cast<const float4*>(&Xs[(mt * 32 + lo) * px + 32 * c + kb + 4 * hi]);
-        const float af[4] = {av.x, av.y, av.z, av.w};
-        float bf[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) bf[j] = Ws[(kb + 4 * hi + j) * H + nt * 32 + lo];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(af[j], bf[j], acc, 0, 0, 0);
-      }
-      __syncthreads();
-    }
+    gemm_phase_regs<H>(Xs + (mt * 32 + lo) * px + 4 * hi, a.W1s + (hi * H + nt * 32 + lo) * 4, kpad1 / 16, acc);
     PHASE_MARK(1);
     {
       const int n = nt * 32 + lo;
@@ -196,25 +252,10 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
     }
     PHASE_MARK(2);
     // ---- layer 2
-#pragma unroll 1
-    for (int c = 0; c < H / 32; ++c) {
-      stage_w();
-      __syncthreads();  // also orders the h1 tile before its first use
-      if (c + 1 < H / 32) fetch_w(a.W2, 32 * (c + 1), H);
-      else fetch_wt(0);
-#pragma unroll
-      for (int kb = 0; kb < 32; kb += 8) {
-        const float4 av = *reinterpret_cast<const float4*>(&H1[(mt * 32 + lo) * PH + 32 * c + kb + 4 * hi]);
-        const float af[4] = {av.x, av.y, av.z, av.w};
-        float bf[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) bf[j] = Ws[(kb + 4 * hi + j) * H + nt * 32 + lo];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(af[j], bf[j], acc, 0, 0, 0);
-      }
-      __syncthreads();
-    }
+    __syncthreads();  // the h1 tile is complete
+    gemm_phase_regs<H>(H1 + (mt * 32 + lo) * PH + 4 * hi, a.W2s + (hi * H + nt * 32 + lo) * 4, H / 16, acc);
     PHASE_MARK(3);
+    if (have_next) fetch_tile_inputs((tile + gridDim.x) * BM);  // lands during the ALU phases and dW2
     floatx16 h2r;  // h2 of this wavefront's tile
     {
       const int n = nt * 32 + lo;
@@ -231,21 +272,31 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
     }
     __syncthreads();
     PHASE_MARK(4);
-    // ---- output layer on the ALUs: thread -> (sample tid % BM, slice tid / BM of the hidden units)
+    // ---- output layer on the ALUs: thread -> (sample tid % BM, slice tid / BM of the hidden units); 16-byte LDS reads
     {
       const int s = tid % BM, grp = tid / BM;
       constexpr int PER = H / GROUPS;
+      static_assert(PER % 4 == 0, "hidden units are read four at a time");
       float part[NOUT];
 #pragma unroll
       for (int k = 0; k < NOUT; ++k) part[k] = 0.f;
-#pragma unroll 4
-      for (int i = grp * PER; i < (grp + 1) * PER; ++i) {
-        const float h = H2[s * PH + i];
+#pragma unroll 2
+      for (int i = grp * PER; i < (grp + 1) * PER; i += 4) {
+        const float4 hv = *reinterpret_cast<const float4*>(&H2[s * PH + i]);
+        const float hh[4] = {hv.x, hv.y, hv.z, hv.w};
+        float wv[4 * NOUT];  // W3 rows i..i+3: 4 * NOUT consecutive floats, the same for every lane of the wavefront
 #pragma unroll
-        for (int k = 0; k < NOUT; ++k) part[k] = fmaf(h, W3s[i * NOUT + k], part[k]);
+        for (int q = 0; q < NOUT; ++q) {
+          const float4 t = *reinterpret_cast<const float4*>(&W3s[i * NOUT + 4 * q]);
+          wv[4 * q] = t.x; wv[4 * q + 1] = t.y; wv[4 * q + 2] = t.z; wv[4 * q + 3] = t.w;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int k = 0; k < NOUT; ++k) part[k] = fmaf(hh[j], wv[j * NOUT + k], part[k]);
       }
 #pragma unroll
-      for (int k = 0; k < NOUT; ++k) red[(grp * BM + s) * NOUT + k] = part[k];
+      for (int k = 0; k < NOUT; ++k) red[(grp * NOUT + k) * BM + s] = part[k];
     }
     __syncthreads();
     PHASE_MARK(5);
@@ -255,13 +306,16 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
       for (int k = 0; k < NOUT; ++k) {
         float v = a.b3[k];
 #pragma unroll
-        for (int gq = 0; gq < GROUPS; ++gq) v += red[(gq * BM + tid) * NOUT + k];
+        for (int gq = 0; gq < GROUPS; ++gq) v += red[(gq * NOUT + k) * BM + tid];
         out[k] = v;
         dl[k] = 0.f;
       }
-      if (s0 + tid < a.S) fn.compute(lin, out, dl, st);
+      if (s0 + tid < a.S) fn.compute(lin, prep, out, dl, st);
+      float d8[8];
 #pragma unroll
-      for (int k = 0; k < 8; ++k) dls[tid * 8 + k] = k < NOUT ? dl[k < NOUT ? k : 0] : 0.f;
+      for (int k = 0; k < 8; ++k) d8[k] = k < NOUT ? dl[k < NOUT ? k : 0] : 0.f;
+      *reinterpret_cast<float4*>(&dls[tid * 8]) = make_float4(d8[0], d8[1], d8[2], d8[3]);
+      *reinterpret_cast<float4*>(&dls[tid * 8 + 4]) = make_float4(d8[4], d8[5], d8[6], d8[7]);
 #pragma unroll
       for (int k = 0; k < NOUT; ++k) gb[k] += dl[k];
     }
@@ -273,8 +327,14 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
 #pragma unroll 4
       for (int s = part * SPP; s < (part + 1) * SPP; ++s) {
         const float h = H2[s * PH + i];
+        const float4 d0 = *reinterpret_cast<const float4*>(&dls[s * 8]);
+        float dv[8] = {d0.x, d0.y, d0.z, d0.w, 0.f, 0.f, 0.f, 0.f};
+        if (NOUT > 4) {
+          const float4 d1 = *reinterpret_cast<const float4*>(&dls[s * 8 + 4]);
+          dv[4] = d1.x; dv[5] = d1.y; dv[6] = d1.z; dv[7] = d1.w;
+        }
 #pragma unroll
-        for (int k = 0; k < NOUT; ++k) gw[k] = fmaf(h, dls[s * 8 + k], gw[k]);
+        for (int k = 0; k < NOUT; ++k) gw[k] = fmaf(h, dv[k], gw[k]);
       }
     }
     __syncthreads();
@@ -311,40 +371,14 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
       const int it = t0 / NTN, jt = t0 % NTN;
       const int ks = (wave * DW2_TPW) / (NTN * NTN);
       constexpr int KLEN = BM / DW2_KS;
-#pragma unroll 1
-      for (int kb = ks * KLEN; kb < (ks + 1) * KLEN; kb += 8) {
-        float af[4], bf[DW2_TPW][4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          af[j] = H1[(kb + 4 * hi + j) * PH + it * 32 + lo];
-#pragma unroll
-          for (int q = 0; q < DW2_TPW; ++q) bf[q][j] = H2[(kb + 4 * hi + j) * PH + (jt + q) * 32 + lo];
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-          for (int q = 0; q < DW2_TPW; ++q) acc2[q] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[j], bf[q][j], acc2[q], 0, 0, 0);
-      }
+      outer_product_accumulate<DW2_TPW>(H1 + it * 32 + lo, PH, H2 + jt * 32 + lo, PH, ks * KLEN, KLEN, hi, acc2);
     }
     PHASE_MARK(9);
     // ---- dz1 = (dz2 W2^T) * (1 - h1^2), in place over h1
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-#pragma unroll 1
-    for (int c = 0; c < H / 32; ++c) {
-      stage_wt();
-      __syncthreads();
-      if (c + 1 < H / 32) fetch_wt(32 * (c + 1));
-#pragma unroll
-      for (int kb = 0; kb < 32; kb += 8) {
-        const float4 av = *reinterpret_cast<const float4*>(&H2[(mt * 32 + lo) * PH + 32 * c + kb + 4 * hi]);
-        const float4 bv = *reinterpret_cast<const float4*>(&Ws[(nt * 32 + lo) * PW + kb + 4 * hi]);
-        const float af[4] = {av.x, av.y, av.z, av.w}, bf[4] = {bv.x, bv.y, bv.z, bv.w};
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(af[j], bf[j], acc, 0, 0, 0);
-      }
-      __syncthreads();
-    }
+    gemm_phase_regs<H>(H2 + (mt * 32 + lo) * PH + 4 * hi, a.W2Ts + (hi * H + nt * 32 + lo) * 4, H / 16, acc);
+    __syncthreads();  // every wavefront is done reading h1 (dW2) before its tiles are overwritten
     PHASE_MARK(10);
     {
       const int n = nt * 32 + lo;
@@ -366,22 +400,9 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
     // ---- dW1 += X^T dz1
 #pragma unroll
     for (int q = 0; q < Q1; ++q) {
-      const int item = wave + NW * q;
-      if (item < items1) {
-        const int t = item / KS1, ks = item - t * KS1;
-        const int dt = t / NTN, jt = t % NTN;
-        const int klen = BM / KS1;
-#pragma unroll 1
-        for (int kb = ks * klen; kb < (ks + 1) * klen; kb += 8) {
-          float af[4], bf[4];
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            af[j] = Xs[(kb + 4 * hi + j) * px + dt * 32 + lo];
-            bf[j] = H1[(kb + 4 * hi + j) * PH + jt * 32 + lo];
-          }
-#pragma unroll
-          for (int j = 0; j < 4; ++j) acc1[q] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[j], bf[j], acc1[q], 0, 0, 0);
-        }
+      int t, kb0, klen;
+      if (dw1_item(q, t, kb0, klen)) {
+        outer_product_accumulate<1>(Xs + (t / NTN) * 32 + lo, px, H1 + (t % NTN) * 32 + lo, PH, kb0, klen, hi, &acc1[q]);
       }
     }
     PHASE_MARK(12);
@@ -403,9 +424,9 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
   }
 #pragma unroll
   for (int q = 0; q < Q1; ++q) {
-    const int item = wave + NW * q;
-    if (item < items1) {
-      const int t = item / KS1, dt = t / NTN, jt = t % NTN;
+    int t, kb0, klen;
+    if (dw1_item(q, t, kb0, klen)) {
+      const int dt = t / NTN, jt = t % NTN;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int d = dt * 32 + 8 * (r / 4) + 4 * hi + (r % 4), j = jt * 32 + lo;
@@ -449,7 +470,7 @@ inline int fused_train_px(int Din) {
 template <int H, int BM, int NOUT, int DMAX, int NW, class LossFn>
 inline int32_t launch_fused_train_inst(const FusedTrainArgs& a, const LossFn& fn, hipStream_t s) {
   auto kern = fused_train_kernel<H, BM, NOUT, DMAX, NW, LossFn>;
-  const size_t floats = (size_t)BM * a.px + 2 * (size_t)BM * (H + 4) + (size_t)H * 36 + 64 * NW * NOUT + BM * 8 + H * NOUT;
+  const size_t floats = (size_t)BM * a.px + 2 * (size_t)BM * (H + 4) + 64 * NW * NOUT + BM * 8 + H * NOUT;
   const size_t bytes = floats * 4;
   static bool configured = false;  // per instantiation
   if (!configured) {

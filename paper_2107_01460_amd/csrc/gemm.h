@@ -29,6 +29,13 @@ struct RowSrc {
     const int a = (int)(r - g * per);
     return base + ((int64_t)gather[g] * per + a) * ld;
   }
+  // The same address in two steps, so that the gather entry can be fetched long before the row is.
+  __device__ __forceinline__ int32_t gather_entry(int64_t r) const { return gather == nullptr ? 0 : gather[r / per]; }
+  __device__ __forceinline__ const float* ptr_with(int64_t r, int32_t entry) const {
+    if (gather == nullptr) return base + r * ld;
+    const int a = (int)(r % per);
+    return base + ((int64_t)entry * per + a) * ld;
+  }
 };
 
 enum GemmMode { GEMM_NN = 0, GEMM_NT = 1, GEMM_TN = 2 };

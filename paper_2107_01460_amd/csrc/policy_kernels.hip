@@ -14,15 +14,32 @@ int64_t effective_param_floats(const marl_config& c);
 
 namespace {
 
-// Working copy of the parameters: blocks moved to their aligned offsets, optionally rounded to bf16.
+// Working copy of the parameters: blocks moved to their aligned offsets, optionally rounded to bf16, plus the
+// operand-order copies of W1, W2 and W2 transposed that the fused training kernel streams from memory.
 __global__ void stage_params_kernel(const float* __restrict__ src, float* __restrict__ dst, ParamMap pm, int round) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= pm.src[12]) return;
+#pragma unroll
+  for (int net = 0; net < 2; ++net) {  // zero rows of the operand-order W1 (fewer than 16 rows: far fewer floats than parameters)
+    const int H = pm.hidden[net];
+    if (i < (int64_t)(pm.kpad1[net] - pm.din[net]) * H) {
+      const int64_t k = pm.din[net] + i / H, n = i % H;
+      dst[pm.sw_w1[net] + ((k / 4) * H + n) * 4 + k % 4] = 0.f;
+    }
+  }
   int b = 0;
 #pragma unroll
   for (int k = 1; k < 12; ++k) b += (i >= pm.src[k]) ? 1 : 0;
-  const float v = src[i];
-  dst[pm.dst[b] + (i - pm.src[b])] = round ? round_to_bf16(v) : v;
+  const float v = round ? round_to_bf16(src[i]) : src[i];
+  const int64_t e = i - pm.src[b];
+  dst[pm.dst[b] + e] = v;
+  const int net = b >= 6, H = pm.hidden[net];
+  const int64_t r = e / H, c = e - r * H;
+  if (b == 0 || b == 6) dst[pm.sw_w1[net] + ((r / 4) * H + c) * 4 + r % 4] = v;
+  if (b == 2 || b == 8) {
+    dst[pm.sw_w2[net] + ((r / 4) * H + c) * 4 + r % 4] = v;
+    dst[pm.sw_w2t[net] + ((c / 4) * H + r) * 4 + c % 4] = v;
+  }
 }
 
 // What the rollout does with a sample's outputs.
@@ -108,14 +125,14 @@ void mlp_hidden_forward(const RowSrc& X, int64_t S, int Din, int H, const float*
 // Floats of the working copy: the aligned fp32 copy, followed (bf16 configuration) by the bf16 weight matrices.
 int64_t effective_param_floats(const marl_config& c) {
   const Dims d = dims_of(c);
-  int64_t n = param_map(d).dst[12];
+  int64_t n = param_map(d).total;
   if (d.bf16) n += (bf16_net_weight_elems(d.D, d.Ha) + bf16_net_weight_elems(d.Dc, d.Hc) + 1) / 2 + 192;  // + alignment slack
   return n;
 }
 
 Bf16NetWeights effective_bf16_weights(const marl_config& c, const float* eff, int net) {
   const Dims d = dims_of(c);
-  bf16_t* base = reinterpret_cast<bf16_t*>(const_cast<float*>(eff) + ((param_map(d).dst[12] + 63) / 64) * 64);
+  bf16_t* base = reinterpret_cast<bf16_t*>(const_cast<float*>(eff) + ((param_map(d).total + 63) / 64) * 64);
   if (net == 0) return bf16_net_weights(base, d.D, d.Ha);
   return bf16_net_weights(base + ((bf16_net_weight_elems(d.D, d.Ha) + 63) / 64) * 64, d.Dc, d.Hc);
 }

@@ -81,6 +81,15 @@ __global__ void __launch_bounds__(256) adv_stats_kernel(const float* __restrict_
   if (threadIdx.x == 0) atomicAdd(pass ? &sc->adv_sq : &sc->adv_sum, t);
 }
 
+// exp and log on the hardware exp2 / log2 units (1 ulp each; the arguments here are O(1))
+__device__ __forceinline__ float fast_exp(float x) { return __builtin_amdgcn_exp2f(x * 1.4426950408889634f); }
+__device__ __forceinline__ float fast_log(float x) { return __builtin_amdgcn_logf(x) * 0.6931471805599453f; }
+
+// Per-minibatch constants of a loss, computed once per thread instead of once per sample.
+struct LossPrep {
+  float mean, rstd;
+};
+
 struct ActorLoss {
   LossCommon lc;
   const int32_t* action;
@@ -90,40 +99,50 @@ struct ActorLoss {
     int act;
     float logp_old, adv;
   };
-  // the trajectory values of minibatch sample s (separate from the arithmetic so that they can be fetched early)
-  __device__ __forceinline__ In load(int64_t s) const {
-    const int64_t row = s / lc.A;
-    const int a = (int)(s - row * lc.A);
-    const int64_t src = (int64_t)lc.rows[row] * lc.A + a;
+  // the trajectory values of minibatch sample s (separate from the arithmetic so that they can be fetched early);
+  // row_entry / load_with split the dependent pair of loads so that the first can be issued a phase ahead
+  __device__ __forceinline__ int32_t row_entry(int64_t s) const { return lc.rows[s / lc.A]; }
+  __device__ __forceinline__ In load_with(int64_t s, int32_t entry) const {
+    const int a = (int)(s % lc.A);
+    const int64_t src = (int64_t)entry * lc.A + a;
     return In{action[src], logp_old[src], adv[src]};
   }
+  __device__ __forceinline__ In load(int64_t s) const { return load_with(s, row_entry(s)); }
+  __device__ __forceinline__ LossPrep prepare() const {
+    LossPrep p{0.f, 1.f};
+    if (lc.normalize) {
+      const double B = (double)lc.rows_mb * lc.A;
+      p.mean = (float)(lc.sc->adv_sum / B);
+      p.rstd = (float)(1.0 / (sqrt(lc.sc->adv_sq / B) + 1e-8));
+    }
+    return p;
+  }
   // returns dL/dlogits in dl; adds this sample's terms to st[0..4]
-  __device__ __forceinline__ void compute(const In& in, const float out[kActions], float dl[kActions], float st[5]) const {
+  __device__ __forceinline__ void compute(const In& in, const LossPrep& prep, const float out[kActions], float dl[kActions],
+                                          float st[5]) const {
     const int act = in.act;
     float m = out[0];
 #pragma unroll
     for (int k = 1; k < kActions; ++k) m = fmaxf(m, out[k]);
-    float se = 0.f;
+    float ex[kActions], se = 0.f;
 #pragma unroll
-    for (int k = 0; k < kActions; ++k) se += expf(out[k] - m);
-    const float lse = m + logf(se);
+    for (int k = 0; k < kActions; ++k) {
+      ex[k] = fast_exp(out[k] - m);
+      se += ex[k];
+    }
+    const float lse = m + fast_log(se), rse = __builtin_amdgcn_rcpf(se);
     float lp[kActions], p[kActions], ent = 0.f, logp_new = 0.f;
 #pragma unroll
     for (int k = 0; k < kActions; ++k) {
       lp[k] = out[k] - lse;
-      p[k] = expf(lp[k]);
+      p[k] = ex[k] * rse;
       ent -= p[k] * lp[k];
       logp_new = (k == act) ? lp[k] : logp_new;
     }
     float advn = in.adv;
-    if (lc.normalize) {
-      const double B = (double)lc.rows_mb * lc.A;
-      const float mean = (float)(lc.sc->adv_sum / B);
-      const float rstd = (float)(1.0 / (sqrt(lc.sc->adv_sq / B) + 1e-8));
-      advn = (advn - mean) * rstd;
-    }
+    if (lc.normalize) advn = (advn - prep.mean) * prep.rstd;
     const float log_ratio = logp_new - in.logp_old;
-    const float ratio = expf(log_ratio);
+    const float ratio = fast_exp(log_ratio);
     const float rc = fminf(fmaxf(ratio, 1.0f - lc.clip_eps), 1.0f + lc.clip_eps);
     const float s1 = ratio * advn, s2 = rc * advn;
     st[0] += -fminf(s1, s2) * lc.inv_B;
@@ -136,7 +155,7 @@ struct ActorLoss {
     for (int k = 0; k < kActions; ++k) dl[k] = dlogp * ((k == act ? 1.0f : 0.0f) - p[k]) + ec * p[k] * (lp[k] + ent);
   }
   __device__ __forceinline__ void operator()(int64_t s, const float out[kActions], float dl[kActions], float st[5]) const {
-    compute(load(s), out, dl, st);
+    compute(load(s), prepare(), out, dl, st);
   }
 };
 
@@ -148,16 +167,18 @@ struct CriticLoss {
   struct In {
     float ret[kMaxAgents], v_old[kMaxAgents];
   };
-  __device__ __forceinline__ In load(int64_t s) const {
+  __device__ __forceinline__ int32_t row_entry(int64_t s) const { return lc.rows[per_row == 1 ? s / lc.A : s]; }
+  __device__ __forceinline__ In load(int64_t s) const { return load_with(s, row_entry(s)); }
+  __device__ __forceinline__ LossPrep prepare() const { return LossPrep{0.f, 1.f}; }
+  __device__ __forceinline__ In load_with(int64_t s, int32_t entry) const {
     In in;
     if (per_row == 1) {
-      const int64_t row = s / lc.A;
-      const int a = (int)(s - row * lc.A);
-      const int64_t src = (int64_t)lc.rows[row] * lc.A + a;
+      const int a = (int)(s % lc.A);
+      const int64_t src = (int64_t)entry * lc.A + a;
       in.ret[0] = ret[src];
       in.v_old[0] = v_old[src];
     } else {
-      const int64_t src0 = (int64_t)lc.rows[s] * lc.A;
+      const int64_t src0 = (int64_t)entry * lc.A;
 #pragma unroll
       for (int a = 0; a < kMaxAgents; ++a)
         if (a < lc.A) {
@@ -182,7 +203,7 @@ struct CriticLoss {
     *loss += l * lc.inv_B;
     return g;
   }
-  __device__ __forceinline__ void compute(const In& in, const float out[1], float dl[1], float st[5]) const {
+  __device__ __forceinline__ void compute(const In& in, const LossPrep&, const float out[1], float dl[1], float st[5]) const {
     float g = 0.f;
 #pragma unroll
     for (int a = 0; a < kMaxAgents; ++a)
@@ -190,7 +211,7 @@ struct CriticLoss {
     dl[0] = g * lc.vf_coef * lc.inv_B;
   }
   __device__ __forceinline__ void operator()(int64_t s, const float out[1], float dl[1], float st[5]) const {
-    compute(load(s), out, dl, st);
+    compute(load(s), prepare(), out, dl, st);
   }
 };
 
@@ -555,6 +576,7 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
           FusedTrainArgs ta{};
           ta.X = Xa; ta.S = Sa; ta.Din = d.D; ta.px = fused_train_px(d.D);
           ta.W1 = eff + oa.W1; ta.b1 = eff + oa.b1; ta.W2 = eff + oa.W2; ta.b2 = eff + oa.b2; ta.W3 = eff + oa.W3;
+          ta.W1s = eff + pm.sw_w1[0]; ta.W2s = eff + pm.sw_w2[0]; ta.W2Ts = eff + pm.sw_w2t[0];
           ta.b3 = eff + oa.b3; ta.gW1 = w.grad + ga.W1; ta.gb1 = w.grad + ga.b1; ta.gW2 = w.grad + ga.W2;
           ta.gb2 = w.grad + ga.b2; ta.gW3 = w.grad + ga.W3; ta.gb3 = w.grad + ga.b3; ta.stats = w.sc->acc;
           ta.round_bf16 = d.bf16;
@@ -589,6 +611,7 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
           FusedTrainArgs ta{};
           ta.X = Xc; ta.S = Sc; ta.Din = d.Dc; ta.px = fused_train_px(d.Dc);
           ta.W1 = eff + oc.W1; ta.b1 = eff + oc.b1; ta.W2 = eff + oc.W2; ta.b2 = eff + oc.b2; ta.W3 = eff + oc.W3;
+          ta.W1s = eff + pm.sw_w1[1]; ta.W2s = eff + pm.sw_w2[1]; ta.W2Ts = eff + pm.sw_w2t[1];
           ta.b3 = eff + oc.b3; ta.gW1 = w.grad + gc.W1; ta.gb1 = w.grad + gc.b1; ta.gW2 = w.grad + gc.W2;
           ta.gb2 = w.grad + gc.b2; ta.gW3 = w.grad + gc.W3; ta.gb3 = w.grad + gc.b3; ta.stats = w.sc->acc;
           ta.round_bf16 = d.bf16;
