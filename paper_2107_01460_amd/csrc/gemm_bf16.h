@@ -149,28 +149,42 @@ __global__ void __launch_bounds__(256, 2) gemm_bf16_kernel(GemmBf16Args g) {
     return;
   }
 
+  bf16_t* T = smem;  // [128][PT]; the operand buffers are free (the k loop ended with a barrier)
+  if (EPI == BEPI_DTANH_T) {  // the aux tile comes in through LDS with 16-byte loads (element-wise 2-byte loads crawl)
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const int row = (tid >> 4) + 16 * q, sg = tid & 15;
+      const int64_t m = m0 + row, n = n0 + 8 * sg;
+      uint4 v = make_uint4(0u, 0u, 0u, 0u);
+      if (m < g.M && n < g.N) v = *reinterpret_cast<const uint4*>(&g.aux[m * g.ldaux + n]);
+      *reinterpret_cast<uint4*>(&T[row * PT + 8 * sg]) = v;
+    }
+    __syncthreads();
+  }
   // ---- element-wise epilogue in registers
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
-    const int64_t n = n0 + wn * 64 + j * 32 + lo;
+    const int nl = wn * 64 + j * 32 + lo;
+    const int64_t n = n0 + nl;
     const int64_t nc = min(n, g.N - 1);
     const float bias = EPI == BEPI_TANH ? g.bias[nc] : 0.f;
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int64_t m = m0 + wm * 64 + i * 32 + 8 * (r / 4) + 4 * hi + (r % 4);
+        const int ml = wm * 64 + i * 32 + 8 * (r / 4) + 4 * hi + (r % 4);
+        const int64_t m = m0 + ml;
         float v = acc[i][j][r];
         if (EPI == BEPI_TANH) {
           v = tanh_f32(v + bias);
         } else {
-          const float h = from_bf16(g.aux[min(m, g.M - 1) * g.ldaux + nc]);
+          const float h = from_bf16(T[ml * PT + nl]);
           v = v * (1.0f - h * h);
         }
         acc[i][j][r] = (m < g.M) ? v : 0.f;  // rows past the end leave as zeros (padding of the transposed copy)
       }
   }
-  bf16_t* T = smem;  // [128][PT]; the operand buffers are free (the k loop ended with a barrier)
+  if (EPI == BEPI_DTANH_T) __syncthreads();  // the aux tile has been consumed; T is reused for the output
   // ---- row-major copy C [m][n]
   if (EPI == BEPI_TANH && g.C != nullptr) {
 #pragma unroll

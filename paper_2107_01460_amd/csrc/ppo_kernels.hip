@@ -312,6 +312,133 @@ __global__ void __launch_bounds__(256) loss_head_kernel(const HT* __restrict__ H
   }
 }
 
+// Output layer + loss + W3 / b3 gradient for bf16 activations of up to HMAX hidden units.  The whole 64-sample
+// tile of h2 sits in LDS as bf16 (one pass over HBM, 16-byte loads) and serves both the output layer and the
+// W3 gradient.  Persistent over tiles so that the gradients and statistics leave a workgroup once.
+template <int NOUT, class LossFn, int HMAX>
+__global__ void __launch_bounds__(256) loss_head_bf16_kernel(const bf16_t* __restrict__ H2, int64_t S, int H,
+                                                             const float* __restrict__ W3, const float* __restrict__ b3,
+                                                             LossFn fn, float* __restrict__ dl_out, float* __restrict__ gW3,
+                                                             float* __restrict__ gb3, Scalars* sc) {
+  constexpr int PITCH = HMAX + 8;  // elements; an odd number of 16-byte units, so row-per-lane 16-byte reads spread over the banks
+  __shared__ __attribute__((aligned(16))) bf16_t T[kHeadTile * PITCH];
+  __shared__ __attribute__((aligned(16))) float W3s[HMAX * NOUT];
+  __shared__ float red[4 * NOUT * kHeadTile];
+  __shared__ __attribute__((aligned(16))) float dls[kHeadTile * 8];
+  const int tid = threadIdx.x, lane = tid & 63, grp = tid >> 6;
+  for (int e = tid; e < H * NOUT; e += 256) W3s[e] = W3[e];
+  const auto prep = fn.prepare();
+  constexpr int UMAX = HMAX / 256;  // hidden units per thread in the W3 gradient
+  float gw[UMAX][NOUT], gb[NOUT], st[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int k = 0; k < NOUT; ++k) {
+    gb[k] = 0.f;
+#pragma unroll
+    for (int u = 0; u < UMAX; ++u) gw[u][k] = 0.f;
+  }
+  const int vec_per_row = H / 8, per_grp = H / 4;
+  const int64_t ntiles = (S + kHeadTile - 1) / kHeadTile;
+  for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    const int64_t s0 = tile * kHeadTile;
+    __syncthreads();  // the previous tile has been consumed (and W3s is in place)
+    for (int f = tid; f < kHeadTile * vec_per_row; f += 256) {
+      const int r = f / vec_per_row, c8 = f - r * vec_per_row;
+      uint4 v = make_uint4(0u, 0u, 0u, 0u);
+      if (s0 + r < S) v = *reinterpret_cast<const uint4*>(&H2[(s0 + r) * H + 8 * c8]);
+      *reinterpret_cast<uint4*>(&T[r * PITCH + 8 * c8]) = v;
+    }
+    __syncthreads();
+    {  // output layer: thread -> sample `lane`, quarter `grp` of the hidden units
+      float part[NOUT];
+#pragma unroll
+      for (int k = 0; k < NOUT; ++k) part[k] = 0.f;
+      for (int i = grp * per_grp; i < (grp + 1) * per_grp; i += 8) {
+        const uint4 hv = *reinterpret_cast<const uint4*>(&T[lane * PITCH + i]);
+        const uint32_t hw[4] = {hv.x, hv.y, hv.z, hv.w};
+        float hh[8];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          hh[2 * q] = __uint_as_float(hw[q] << 16);
+          hh[2 * q + 1] = __uint_as_float(hw[q] & 0xffff0000u);
+        }
+        float wv[8 * NOUT];
+#pragma unroll
+        for (int q = 0; q < 2 * NOUT; ++q) {
+          const float4 t = *reinterpret_cast<const float4*>(&W3s[i * NOUT + 4 * q]);
+          wv[4 * q] = t.x; wv[4 * q + 1] = t.y; wv[4 * q + 2] = t.z; wv[4 * q + 3] = t.w;
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+          for (int k = 0; k < NOUT; ++k) part[k] = fmaf(hh[j], wv[j * NOUT + k], part[k]);
+      }
+#pragma unroll
+      for (int k = 0; k < NOUT; ++k) red[(grp * NOUT + k) * kHeadTile + lane] = part[k];
+    }
+    __syncthreads();
+    if (tid < kHeadTile) {
+      float out[NOUT], dl[NOUT];
+#pragma unroll
+      for (int k = 0; k < NOUT; ++k) {
+        out[k] = b3[k] + ((red[(0 * NOUT + k) * kHeadTile + tid] + red[(1 * NOUT + k) * kHeadTile + tid]) +
+                          (red[(2 * NOUT + k) * kHeadTile + tid] + red[(3 * NOUT + k) * kHeadTile + tid]));
+        dl[k] = 0.f;
+      }
+      const int64_t s = s0 + tid;
+      if (s < S) {
+        fn.compute(fn.load(s), prep, out, dl, st);
+#pragma unroll
+        for (int k = 0; k < NOUT; ++k) {
+          dl_out[s * NOUT + k] = dl[k];
+          gb[k] += dl[k];
+        }
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) dls[tid * 8 + k] = k < NOUT ? dl[k < NOUT ? k : 0] : 0.f;
+    }
+    __syncthreads();
+    // gW3[i][k] += sum_s h2[s][i] dl[s][k]: thread -> hidden units tid, tid + 256
+#pragma unroll 4
+    for (int s = 0; s < kHeadTile; ++s) {
+      const float4 d0 = *reinterpret_cast<const float4*>(&dls[s * 8]);
+      float dv[8] = {d0.x, d0.y, d0.z, d0.w, 0.f, 0.f, 0.f, 0.f};
+      if (NOUT > 4) {
+        const float4 d1 = *reinterpret_cast<const float4*>(&dls[s * 8 + 4]);
+        dv[4] = d1.x; dv[5] = d1.y; dv[6] = d1.z; dv[7] = d1.w;
+      }
+#pragma unroll
+      for (int u = 0; u < UMAX; ++u) {
+        const int i = tid + 256 * u;
+        const float h = i < H ? from_bf16(T[s * PITCH + i]) : 0.f;
+#pragma unroll
+        for (int k = 0; k < NOUT; ++k) gw[u][k] = fmaf(h, dv[k], gw[u][k]);
+      }
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < UMAX; ++u) {
+    const int i = tid + 256 * u;
+    if (i < H) {
+#pragma unroll
+      for (int k = 0; k < NOUT; ++k) atomicAdd(&gW3[(int64_t)i * NOUT + k], gw[u][k]);
+    }
+  }
+  if (tid < kHeadTile) {  // one wavefront
+#pragma unroll
+    for (int k = 0; k < NOUT; ++k) {
+      float v = gb[k];
+      for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+      if (tid == 0) atomicAdd(&gb3[k], v);
+    }
+#pragma unroll
+    for (int k = 0; k < 5; ++k) {
+      float v = st[k];
+      for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+      if (tid == 0 && v != 0.f) atomicAdd(&sc->acc[k], v);
+    }
+  }
+}
+
 // In place: H2[s][j] <- (sum_k dl[s][k] W3[j][k]) * (1 - H2[s][j]^2); column sums -> gb2.
 template <int NOUT>
 __global__ void __launch_bounds__(256) dz2_kernel(float* __restrict__ H2, const float* __restrict__ dl,
@@ -450,7 +577,10 @@ UpdateWsView carve_update_ws(const marl_config& c, void* ws, int64_t* total) {
 
 int64_t pick_k_split(int64_t K, int64_t tiles_mn) {
   // enough workgroups for ~4 per CU, each with a k range that is a multiple of the k tile
-  int64_t want = std::max<int64_t>(1, 1024 / std::max<int64_t>(1, tiles_mn));
+#ifndef MARL_KSPLIT_TARGET
+#define MARL_KSPLIT_TARGET 1024
+#endif
+  int64_t want = std::max<int64_t>(1, MARL_KSPLIT_TARGET / std::max<int64_t>(1, tiles_mn));
   int64_t per = (K + want - 1) / want;
   per = std::max<int64_t>(256, ((per + kGemmBK - 1) / kGemmBK) * kGemmBK);
   return per;
@@ -498,9 +628,9 @@ void train_net_bf16(const RowSrc& X, int64_t S, int Din, int H, const Bf16NetWei
   const int64_t Sp = round_up64(S);
   pack_obs_bf16(X, S, Din, bw.Dp, Sp, w.xb, w.xbT, s);
   mlp_hidden_forward_bf16(w.xb, S, Sp, H, bw, eff + o.b1, eff + o.b2, w.bh1, w.bh1T, w.bh2, s);
-  const unsigned nb = (unsigned)std::min<int64_t>(2048, (S + kHeadTile - 1) / kHeadTile);
-  hipLaunchKernelGGL((loss_head_kernel<NOUT, LossFn, bf16_t>), dim3(nb), dim3(256), 0, s, w.bh2, S, H, eff + o.W3,
-                     eff + o.b3, fn, dl, grad + go.W3, grad + go.b3, w.sc, 0.f);
+  const unsigned nb = (unsigned)std::min<int64_t>(512, (S + kHeadTile - 1) / kHeadTile);
+  hipLaunchKernelGGL((loss_head_bf16_kernel<NOUT, LossFn, 512>), dim3(nb), dim3(256), 0, s, w.bh2, S, H, eff + o.W3,
+                     eff + o.b3, fn, dl, grad + go.W3, grad + go.b3, w.sc);
   hipLaunchKernelGGL(bf16_detail::dz2_bf16_kernel<NOUT>, dim3((unsigned)(Sp / 64), (unsigned)((H + 63) / 64)), dim3(256), 0,
                      s, w.bh2, w.dz2T, dl, eff + o.W3, S, Sp, H);
   auto k_split = [&](int64_t tiles_mn) {  // ~4 workgroups per CU, k ranges in multiples of the k tile
