@@ -21,7 +21,7 @@ ORACLE_SAMPLE_ENVS = {1: 64, 2: 64, 3: 64, 4: 2, 5: 2048}
 PEAK = {"mfma_f32": 157.3, "mfma_bf16": 2500.0, "hbm": 8000.0}   # TFLOP/s, TFLOP/s, GB/s
 # HBM bytes per launch (read + write) of the dominant kernel, from the rocprofv3 PMC runs summarised in
 # profiles/bench_c3_pmc_hbm_traffic.txt (FETCH_SIZE x 2.000 and WRITE_SIZE x 1.000 after the 1 GiB copy calibration).
-PMC_TRAFFIC_BYTES = {("c3_15x15_4ag_mappo", "fused_train"): 450.1e6 + 52.0e6}
+PMC_TRAFFIC_BYTES = {("c3_15x15_4ag_mappo", "fused_train"): 447.9e6 + 47.5e6}
 
 
 def gemm_flops_per_step(cfg, W):
@@ -64,6 +64,8 @@ def main():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=3, help="1-based workload index (default 3: MAPPO 15x15, 16384 envs)")
+    ap.add_argument("--n-envs", type=int, default=0,
+                    help="override the number of environments of the workload (scalability sweep); 0 = the workload's own")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="run one plain 1 GiB device copy before the warm-up (a kernel of known traffic for scaling PMC counters)")
@@ -78,6 +80,8 @@ def main():
 
     torch.cuda.set_device(0)
     cfg = W.CONFIGS[args.config - 1]
+    if args.n_envs:
+        cfg = W.scaled(cfg, n_envs=args.n_envs, name="%s@N=%d" % (cfg["name"], args.n_envs))
     sizes = M.query_sizes(cfg)
     dev = lambda x: torch.from_numpy(np.ascontiguousarray(x)).cuda()
     state = M.EnvState(cfg)
@@ -109,12 +113,19 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    M.timing_enable(True)
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    # the same K steps once more with per-launch event timers on, for the per-kernel figures (the events cost a
+    # few microseconds per launch, so they stay out of the headline timing above)
+    M.timing_enable(True)
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt_timed = time.perf_counter() - t1
     classes = {}
     for name, cls in M.KERNEL_CLASSES.items():
         ms, n, work = M.timing_read(cls)
@@ -130,11 +141,11 @@ def main():
             a = work / (ms * 1e-3) / 1e12
             return {"kernel": name, "bound": "mfma", "achieved": a, "peak": mfma_peak, "unit": "TFLOP/s",
                     "frac": a / mfma_peak, "traffic": None, "launches": n, "avg_us": 1e3 * ms / n,
-                    "share_of_step": ms / (1e3 * dt)}
+                    "share_of_step": ms / (1e3 * dt_timed)}
         a = work / (ms * 1e-3) / 1e9
         return {"kernel": name, "bound": "hbm", "achieved": a, "peak": PEAK["hbm"], "unit": "GB/s",
                 "frac": a / PEAK["hbm"], "traffic": None, "launches": n, "avg_us": 1e3 * ms / n,
-                "share_of_step": ms / (1e3 * dt)}
+                "share_of_step": ms / (1e3 * dt_timed)}
 
     lines = [l for l in (line(k) for k in M.KERNEL_CLASSES) if l]
     roofline = dict(max((l for l in lines if l["bound"] == "mfma"), key=lambda l: l["share_of_step"]))
