@@ -79,6 +79,7 @@ def lib():
         _lib.orc_sample_uniforms.argtypes = [C.POINTER(Config), C.c_uint64, C.c_int32, C.c_int32, _F32P]
         _lib.orc_rollout.argtypes = [C.POINTER(Config), EnvStateC, _F32P, TrajC, C.c_uint64, _I32P, _F32P]
         _lib.orc_compute_gae.argtypes = [C.POINTER(Config), TrajC]
+        _lib.orc_evaluate.argtypes = [C.POINTER(Config), EnvStateC, _F32P, C.c_int32, _F32P, _I32P, _I32P, _F32P]
         _lib.orc_minibatch_loss_grad_f64.argtypes = [C.POINTER(Config), TrajC, _F64P, _I32P, C.c_int32,
                                                      _F64P, _F64P]
         _lib.orc_adam_step.argtypes = [C.POINTER(Config), _F32P, _F32P, _F32P, _F64P, C.c_int64, C.c_int64]
@@ -248,6 +249,17 @@ def rollout(cfg, state, params, traj, step_offset=0, forced_actions=None, forced
     fa = None if forced_actions is None else np.ascontiguousarray(forced_actions, np.int32)
     fu = None if forced_uniforms is None else np.ascontiguousarray(forced_uniforms, np.float32)
     lib().orc_rollout(C.byref(make_config(cfg)), state.c(), _ap(params), traj.c(), int(step_offset), _ap(fa), _ap(fu))
+
+
+def evaluate(cfg, state, params, n_episodes):
+    """Greedy evaluation block: (ret_sum [N] f32, len_sum [N] i32, episodes [N] i32, min_gap [N] f32)."""
+    N = cfg["n_envs"]
+    ret_sum, min_gap = np.zeros(N, np.float32), np.zeros(N, np.float32)
+    len_sum, episodes = np.zeros(N, np.int32), np.zeros(N, np.int32)
+    params = np.ascontiguousarray(params, np.float32)
+    lib().orc_evaluate(C.byref(make_config(cfg)), state.c(), _ap(params), int(n_episodes), _ap(ret_sum), _ap(len_sum),
+                       _ap(episodes), _ap(min_gap))
+    return ret_sum, len_sum, episodes, min_gap
 
 
 def compute_gae(cfg, traj):

@@ -693,6 +693,63 @@ void orc_rollout(const orc_config* c, orc_env_state s, const float* params, orc_
   }
 }
 
+// Greedy evaluation block (the paper's Section 2, "robust evaluation": training is frozen periodically and the
+// current policy is evaluated in blocks that run on the accelerator between training blocks).  The paper fixes
+// no protocol; the reading here: from the state passed in, every environment plays its first `n_episodes`
+// episodes with the greedy action (largest fp32 logit, lowest index on exact ties) of every agent.  Per
+// environment: ret_sum = sum over those episodes and their steps of the team reward of the step (the agents'
+// rewards added in ascending agent index, then added to the running sum, both in fp32, in time order), len_sum =
+// number of steps of those episodes, episodes = n_episodes.  Steps after an environment's n_episodes-th episode
+// are not counted; n_episodes * episode_cap steps are taken, which covers every counted episode.  min_gap
+// (nullable) = the smallest difference between the two largest logits over all counted decisions of the
+// environment (how close the run came to a tie that an fp32 evaluation might break the other way).
+void orc_evaluate(const orc_config* c, orc_env_state s, const float* params, int32_t n_episodes, float* ret_sum,
+                  int32_t* len_sum, int32_t* episodes, float* min_gap) {
+  const Dims d = dims_of(*c);
+  const std::vector<double> p = effective_params(*c, params);
+  std::vector<float> obs((size_t)d.A * d.D), reward(d.A);
+  std::vector<double> lg((size_t)d.A * kActions);
+  std::vector<int32_t> act(d.A);
+  for (int n = 0; n < d.N; ++n) {
+    ret_sum[n] = 0.0f;
+    len_sum[n] = 0;
+    episodes[n] = 0;
+    if (min_gap) min_gap[n] = INFINITY;
+  }
+  const int64_t steps = (int64_t)n_episodes * c->episode_cap;
+  for (int64_t t = 0; t < steps; ++t)
+    for (int n = 0; n < d.N; ++n) {
+      observe_one(*c, s, n, obs.data());
+      policy_row(d, p.data(), obs.data(), lg.data(), nullptr);
+      const bool counted = episodes[n] < n_episodes;
+      for (int a = 0; a < d.A; ++a) {
+        int best = 0;
+        float top = (float)lg[(size_t)a * kActions], second = -INFINITY;
+        for (int k = 1; k < kActions; ++k) {
+          const float v = (float)lg[(size_t)a * kActions + k];
+          if (v > top) {
+            second = top;
+            top = v;
+            best = k;
+          } else if (v > second) {
+            second = v;
+          }
+        }
+        act[a] = best;
+        if (counted && min_gap) min_gap[n] = std::min(min_gap[n], top - second);
+      }
+      uint8_t done = 0;
+      step_one(*c, s, n, act.data(), reward.data(), &done);
+      if (counted) {
+        float team = 0.0f;
+        for (int a = 0; a < d.A; ++a) team += reward[a];
+        ret_sum[n] += team;
+        len_sum[n] += 1;
+        if (done) episodes[n] += 1;
+      }
+    }
+}
+
 // Generalised advantage estimation, backwards in time per (env, agent) lane:
 //   delta_t = r_t + gamma (1 - d_t) V_{t+1} - V_t,  A_t = delta_t + gamma lambda (1 - d_t) A_{t+1},
 //   A_T = 0, V_T = last_value, ret_t = A_t + V_t.
