@@ -66,6 +66,8 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="1-based workload index (default 3: MAPPO 15x15, 16384 envs)")
     ap.add_argument("--n-envs", type=int, default=0,
                     help="override the number of environments of the workload (scalability sweep); 0 = the workload's own")
+    ap.add_argument("--eval-episodes", type=int, default=0,
+                    help="also time one greedy evaluation block of this many episodes per environment (reported as \"eval\")")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="run one plain 1 GiB device copy before the warm-up (a kernel of known traffic for scaling PMC counters)")
@@ -167,6 +169,23 @@ def main():
         "roofline_all": lines,
     }
     out["mlp_gemm_tflops_end_to_end"] = out["config"]["mlp_gemm_tflop_per_step"] / (dt / args.steps)
+    if args.eval_episodes > 0:
+        ev_state, ev_out = M.EnvState(cfg), M.EvalStats(cfg)
+        ws_e = M.alloc_workspace(sizes.eval_workspace_bytes)
+        ev_ms = []
+        for _ in range(2):  # the second call is the timed one
+            M.env_reset(cfg, ev_state)
+            torch.cuda.synchronize()
+            t2 = time.perf_counter()
+            M.evaluate(cfg, ev_state, params, args.eval_episodes, ev_out, ws_e)
+            torch.cuda.synchronize()
+            ev_ms.append(1e3 * (time.perf_counter() - t2))
+        n_steps = args.eval_episodes * cfg["episode_cap"]
+        counted = int(ev_out.len_sum.sum().item())
+        out["eval"] = {"episodes_per_env": args.eval_episodes, "env_steps_taken": n_steps, "ms": ev_ms[-1],
+                       "env_agent_steps_per_s": cfg["n_envs"] * cfg["n_agents"] * n_steps / (ev_ms[-1] * 1e-3),
+                       "counted_env_steps": counted,
+                       "mean_episode_return": float(ev_out.ret_sum.sum().item()) / float(ev_out.episodes.sum().item())}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = run_cpu_baseline(args.config, cfg, W)
     print(json.dumps(out))

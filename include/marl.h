@@ -98,7 +98,7 @@ typedef struct marl_sizes {
   int64_t state_entity_bytes_agents, state_entity_bytes_food, state_t_bytes, state_episode_bytes;
   int64_t obs_bytes, step_scalar_bytes /* action, logp, value, reward, adv, ret: each */, done_bytes, last_value_bytes,
       logits_bytes;
-  int64_t rollout_workspace_bytes, update_workspace_bytes;
+  int64_t rollout_workspace_bytes, update_workspace_bytes, eval_workspace_bytes;
 } marl_sizes;
 
 /* Parameter vector (fp32, one flat array, caller-owned):
@@ -166,6 +166,23 @@ int32_t marl_compute_gae(const marl_config* cfg, marl_traj traj, void* stream);
 int32_t marl_ppo_update(const marl_config* cfg, marl_traj traj, float* params, float* adam_m, float* adam_v,
                         int64_t adam_step0, const int32_t* perm, float* stats, float* grad_dump, void* workspace,
                         void* stream);
+
+/* Per-environment results of an evaluation block: device arrays of n_envs elements, caller-owned. */
+typedef struct marl_eval_stats {
+  float* ret_sum;    /* [N] team return (all agents' rewards) summed over the counted episodes, fp32 in time order */
+  int32_t* len_sum;  /* [N] steps of the counted episodes */
+  int32_t* episodes; /* [N] counted episodes completed (= n_episodes when the call returns) */
+} marl_eval_stats;
+
+/* Greedy evaluation block (Section 2: training is frozen periodically and the current policy evaluated on the
+ * accelerator, between training blocks).  From the state in `st` (the caller resets it; it is left at the state
+ * after the last step) every environment plays with action = argmax_k logits[k] (lowest k on exact ties) for
+ * every agent; its first n_episodes episodes are counted into `out`, later steps are not.  n_episodes *
+ * episode_cap steps are taken, which covers every counted episode.  Mean episode return = sum(ret_sum) /
+ * sum(episodes).  workspace: eval_workspace_bytes.  Errors: MARL_E_SIZE if n_episodes < 1 or n_episodes *
+ * episode_cap > 2^20. */
+int32_t marl_evaluate(const marl_config* cfg, marl_env_state st, const float* params, int32_t n_episodes,
+                      marl_eval_stats out, void* workspace, void* stream);
 
 /* Measurement hook for benchmarks (host state only, not thread-safe).  While enabled, every launch of
  * the instrumented kernel classes is bracketed by two HIP events recorded on the launch's own stream.

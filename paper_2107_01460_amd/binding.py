@@ -38,11 +38,15 @@ class Sizes(C.Structure):
         "obs_dim", "critic_in_dim", "n_params", "n_actor_params",
         "state_entity_bytes_agents", "state_entity_bytes_food", "state_t_bytes", "state_episode_bytes",
         "obs_bytes", "step_scalar_bytes", "done_bytes", "last_value_bytes", "logits_bytes",
-        "rollout_workspace_bytes", "update_workspace_bytes")]
+        "rollout_workspace_bytes", "update_workspace_bytes", "eval_workspace_bytes")]
+
+
+class EvalStatsC(C.Structure):
+    _fields_ = [("ret_sum", C.c_void_p), ("len_sum", C.c_void_p), ("episodes", C.c_void_p)]
 
 
 EXPORTS = ("marl_query_sizes", "marl_env_reset", "marl_observe", "marl_env_step", "marl_policy_forward",
-           "marl_sample_actions", "marl_rollout", "marl_compute_gae", "marl_ppo_update", "marl_timing_enable",
+           "marl_sample_actions", "marl_rollout", "marl_compute_gae", "marl_ppo_update", "marl_evaluate", "marl_timing_enable",
            "marl_timing_read", "marl_status_string")
 
 _lib = None
@@ -66,6 +70,7 @@ def lib():
         L.marl_rollout.argtypes = [cp, EnvStateC, vp, TrajC, C.c_uint64, vp, vp, vp, vp]
         L.marl_compute_gae.argtypes = [cp, TrajC, vp]
         L.marl_ppo_update.argtypes = [cp, TrajC, vp, vp, vp, C.c_int64, vp, vp, vp, vp, vp]
+        L.marl_evaluate.argtypes = [cp, EnvStateC, vp, C.c_int32, EvalStatsC, vp, vp]
         L.marl_timing_enable.argtypes = [C.c_int32]
         L.marl_timing_read.argtypes = [C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)]
         L.marl_status_string.argtypes = [C.c_int32]
@@ -204,6 +209,24 @@ def rollout(cfg, state, params, traj, step_offset, workspace, forced_actions=Non
 
 def compute_gae(cfg, traj, stream=None):
     _check(lib().marl_compute_gae(C.byref(make_config(cfg)), traj.c(), _stream(stream)))
+
+
+class EvalStats:
+    """Caller-owned device buffers of an evaluation block's per-environment results."""
+
+    def __init__(self, cfg, device="cuda"):
+        N = cfg["n_envs"]
+        self.ret_sum = torch.zeros((N,), dtype=torch.float32, device=device)
+        self.len_sum = torch.zeros((N,), dtype=torch.int32, device=device)
+        self.episodes = torch.zeros((N,), dtype=torch.int32, device=device)
+
+    def c(self):
+        return EvalStatsC(self.ret_sum.data_ptr(), self.len_sum.data_ptr(), self.episodes.data_ptr())
+
+
+def evaluate(cfg, state, params, n_episodes, out, workspace, stream=None):
+    _check(lib().marl_evaluate(C.byref(make_config(cfg)), state.c(), _ptr(params), int(n_episodes), out.c(),
+                               _ptr(workspace), _stream(stream)))
 
 
 KERNEL_CLASSES = {"gemm_nn": 0, "gemm_nt": 1, "gemm_tn": 2, "env_step": 3, "gae": 4, "fused_train": 5}

@@ -111,6 +111,7 @@ int32_t marl_query_sizes(const marl_config* cfg, marl_sizes* out) {
   out->logits_bytes = 4 * (int64_t)d.T * d.NA * kActions;
   out->rollout_workspace_bytes = rollout_workspace_bytes(*cfg, d.N);
   out->update_workspace_bytes = update_workspace_bytes(*cfg);
+  out->eval_workspace_bytes = eval_workspace_bytes(*cfg);
   return MARL_OK;
 }
 
@@ -179,6 +180,17 @@ int32_t marl_compute_gae(const marl_config* cfg, marl_traj traj, void* stream) {
   if (rc != MARL_OK) return rc;
   if ((rc = check_traj(traj, true)) != MARL_OK) return rc;
   return launch_gae(*cfg, traj, (hipStream_t)stream);
+}
+
+int32_t marl_evaluate(const marl_config* cfg, marl_env_state st, const float* params, int32_t n_episodes,
+                      marl_eval_stats out, void* workspace, void* stream) {
+  int32_t rc = validate_config(cfg);
+  if (rc != MARL_OK) return rc;
+  if ((rc = check_state(st)) != MARL_OK) return rc;
+  MARL_REQUIRE_PTR(params); MARL_REQUIRE_PTR(workspace);
+  MARL_REQUIRE_PTR(out.ret_sum); MARL_REQUIRE_PTR(out.len_sum); MARL_REQUIRE_PTR(out.episodes);
+  if (n_episodes < 1 || (int64_t)n_episodes * cfg->episode_cap > ((int64_t)1 << 20)) return MARL_E_SIZE;
+  return launch_evaluate(*cfg, st, params, n_episodes, out, workspace, (hipStream_t)stream);
 }
 
 int32_t marl_ppo_update(const marl_config* cfg, marl_traj traj, float* params, float* adam_m, float* adam_v,

@@ -173,6 +173,9 @@ int32_t launch_rollout(const marl_config& c, marl_env_state st, const float* par
                        uint64_t step_offset, const int32_t* forced_actions, const float* forced_uniforms,
                        void* workspace, hipStream_t s);
 int32_t launch_gae(const marl_config& c, marl_traj tr, hipStream_t s);
+int64_t eval_workspace_bytes(const marl_config& c);
+int32_t launch_evaluate(const marl_config& c, marl_env_state st, const float* params, int32_t n_episodes,
+                        marl_eval_stats out, void* workspace, hipStream_t s);
 int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, float* adam_m, float* adam_v,
                           int64_t adam_step0, const int32_t* perm, float* stats, float* grad_dump, void* workspace,
                           hipStream_t s);

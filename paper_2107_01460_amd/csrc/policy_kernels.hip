@@ -250,4 +250,106 @@ int32_t launch_rollout(const marl_config& c, marl_env_state st, const float* par
   return forward_rows(c, eff, tr.obs + (int64_t)d.T * slab, d.N, w, false, nullptr, nullptr, tr.last_value, s);
 }
 
+// ---- greedy evaluation block ---------------------------------------------------------------------------
+
+namespace {
+
+__global__ void eval_zero_kernel(marl_eval_stats out, int N) {
+  const int n = blockIdx.x * blockDim.x + threadIdx.x;
+  if (n < N) {
+    out.ret_sum[n] = 0.f;
+    out.len_sum[n] = 0;
+    out.episodes[n] = 0;
+  }
+}
+
+// action = index of the largest logit, lowest index on exact ties
+__global__ void __launch_bounds__(256) greedy_kernel(const float* __restrict__ logits, int32_t* __restrict__ action, int64_t S) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= S) return;
+  int best = 0;
+  float top = logits[i * kActions];
+#pragma unroll
+  for (int k = 1; k < kActions; ++k) {
+    const float v = logits[i * kActions + k];
+    if (v > top) {
+      top = v;
+      best = k;
+    }
+  }
+  action[i] = best;
+}
+
+// Books one step into the statistics of the environments that are still inside their first n_episodes episodes:
+// team reward = the agents' rewards added in ascending agent index, then added to the running sum (fp32).
+__global__ void __launch_bounds__(256) eval_accumulate_kernel(const float* __restrict__ reward, const uint8_t* __restrict__ done,
+                                                              marl_eval_stats out, int N, int A, int n_episodes) {
+  const int n = blockIdx.x * blockDim.x + threadIdx.x;
+  if (n >= N) return;
+  const int e = out.episodes[n];
+  if (e >= n_episodes) return;
+  float team = 0.f;
+  for (int a = 0; a < A; ++a) team += reward[(int64_t)n * A + a];
+  out.ret_sum[n] += team;
+  out.len_sum[n] += 1;
+  if (done[n]) out.episodes[n] = e + 1;
+}
+
+struct EvalWsView {
+  void* rollout_ws;
+  float *obs, *logits, *reward;
+  int32_t* action;
+  uint8_t* done;
+};
+
+EvalWsView carve_eval_ws(const marl_config& c, void* ws, int64_t* total) {
+  const Dims d = dims_of(c);
+  char* p = static_cast<char*>(ws);
+  int64_t off = 0;
+  auto take = [&](int64_t bytes) {
+    char* r = p + off;
+    off += align256(bytes);
+    return r;
+  };
+  EvalWsView v;
+  v.rollout_ws = take(rollout_workspace_bytes(c, d.N));
+  v.obs = (float*)take(d.NA * d.D * 4);
+  v.logits = (float*)take(d.NA * kActions * 4);
+  v.reward = (float*)take(d.NA * 4);
+  v.action = (int32_t*)take(d.NA * 4);
+  v.done = (uint8_t*)take(d.N);
+  if (total) *total = off;
+  return v;
+}
+
+}  // namespace
+
+int64_t eval_workspace_bytes(const marl_config& c) {
+  int64_t total = 0;
+  carve_eval_ws(c, nullptr, &total);
+  return total;
+}
+
+int32_t launch_evaluate(const marl_config& c, marl_env_state st, const float* params, int32_t n_episodes,
+                        marl_eval_stats out, void* workspace, hipStream_t s) {
+  const Dims d = dims_of(c);
+  const EvalWsView e = carve_eval_ws(c, workspace, nullptr);
+  const RolloutWsView w = carve_rollout_ws(c, d.N, e.rollout_ws, nullptr);
+  const float* eff = effective_params(c, params, w.eff_params, s);
+  const unsigned nb_env = (unsigned)((d.N + 255) / 256), nb_s = (unsigned)((d.NA + 255) / 256);
+  hipLaunchKernelGGL(eval_zero_kernel, dim3(nb_env), dim3(256), 0, s, out, d.N);
+  int32_t rc = launch_env_step(c, st, nullptr, e.obs, nullptr, nullptr, /*do_step=*/false, s);
+  if (rc != MARL_OK) return rc;
+  const int64_t steps = (int64_t)n_episodes * c.episode_cap;
+  for (int64_t t = 0; t < steps; ++t) {
+    rc = forward_rows(c, eff, e.obs, d.N, w, true, e.logits, nullptr, nullptr, s);
+    if (rc != MARL_OK) return rc;
+    hipLaunchKernelGGL(greedy_kernel, dim3(nb_s), dim3(256), 0, s, e.logits, e.action, d.NA);
+    rc = launch_env_step(c, st, e.action, e.obs, e.reward, e.done, true, s);
+    if (rc != MARL_OK) return rc;
+    hipLaunchKernelGGL(eval_accumulate_kernel, dim3(nb_env), dim3(256), 0, s, e.reward, e.done, out, d.N, d.A, (int)n_episodes);
+  }
+  return launch_status();
+}
+
 }  // namespace marl

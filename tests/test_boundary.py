@@ -83,6 +83,11 @@ def test_null_and_misaligned_pointers_rejected_before_launch(M):
     assert L.marl_ppo_update(C.byref(cfg), traj, good, good, good, 0, good + 2, good, None, good, None) == -2
     assert L.marl_policy_forward(C.byref(cfg), good, good, -1, good, good, good, None) == -5
     assert L.marl_sample_actions(C.byref(cfg), good, None, None, 1 << 31, 0, good, None, good, None) == -5
+    ev = M.binding.EvalStatsC(good, good, good)
+    assert L.marl_evaluate(C.byref(cfg), ok_state, good, 0, ev, good, None) == -5
+    assert L.marl_evaluate(C.byref(cfg), ok_state, good, 1 << 20, ev, good, None) == -5
+    assert L.marl_evaluate(C.byref(cfg), ok_state, None, 1, ev, good, None) == -1
+    assert L.marl_evaluate(C.byref(cfg), ok_state, good, 1, M.binding.EvalStatsC(good, None, good), good, None) == -1
     assert L.marl_query_sizes(None, None) == -1
     assert M.status_string(0) == "ok" and "null" in M.status_string(-1)
     d, n, w = C.c_double(), C.c_int64(), C.c_double()

@@ -277,3 +277,46 @@ def test_ppo_update_epochs_and_minibatches(M, orc, k):
     orc.ppo_update(cfg, otr, po2, mo2, vo2, adam_step0=3, perm=None)
     if cfg["precision"] == 0:
         assert rel_err(gp2.cpu().numpy() - params, po2 - params, floor=1.0) < 0.05
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 5])
+def test_greedy_evaluation_block(M, orc, k):
+    """Per-environment return / length / episode counts of the greedy evaluation block, bit for bit, for every
+    environment whose run stayed clear of a near-tie between its two largest logits (an fp32 evaluation may break
+    such a tie the other way, after which the two runs are different episodes)."""
+    n_envs = {1: 200, 2: 130, 3: 90, 4: 80, 5: 300}[k]
+    cfg = small(k, n_envs=n_envs, n_minibatches=1, episode_cap={1: 12, 2: 10, 3: 9, 4: 6, 5: 12}[k])
+    E = {1: 3, 2: 3, 3: 2, 4: 2, 5: 3}[k]
+    print("case", cfg["name"], n_envs, E, flush=True)
+    params = W.init_params(cfg, bias_scale=0.3)
+    off = 0
+    for name, shape in W.param_layout(cfg):   # a bias towards "load", so that food is lifted and episodes end early
+        if name == "actor.b3":
+            params[off + 5] += 1.0
+        off += int(np.prod(shape))
+    os_ = orc.EnvState(cfg)
+    orc.env_reset(cfg, os_)
+    oret, olen, oeps, gap = orc.evaluate(cfg, os_, params, E)
+    gs = M.EnvState(cfg)
+    M.env_reset(cfg, gs)
+    out = M.EvalStats(cfg)
+    out.ret_sum.fill_(7.0)      # the call clears its outputs
+    out.episodes.fill_(5)
+    ws = M.alloc_workspace(M.query_sizes(cfg).eval_workspace_bytes)
+    M.evaluate(cfg, gs, dev(params), E, out, ws)
+    torch.cuda.synchronize()
+    gret, glen, geps = out.ret_sum.cpu().numpy(), out.len_sum.cpu().numpy(), out.episodes.cpu().numpy()
+    assert np.all(geps == E) and np.all(oeps == E)
+    scale = float(np.abs(params).max())
+    # logits differ between the two sides by up to the tolerance times their scale (a few units here)
+    lim = (2e-4 if cfg["precision"] == 0 else 2.5e-2) * max(1.0, scale) * 4
+    clear = gap > lim
+    assert clear.mean() > (0.9 if cfg["precision"] == 0 else 0.15), clear.mean()
+    assert np.array_equal(gret[clear].view(np.uint32), oret[clear].view(np.uint32))
+    assert np.array_equal(glen[clear], olen[clear])
+    assert np.all(glen >= E) and np.all(glen <= E * cfg["episode_cap"])
+    assert oret[clear].sum() > 0
+    # final state of the clear environments
+    host = gs.to_host()
+    for f in M.EnvState.FIELDS:
+        assert np.array_equal(host[f][..., clear], getattr(os_, f)[..., clear]), f
