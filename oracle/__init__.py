@@ -34,7 +34,8 @@ class Config(C.Structure):
         "actor_hidden", "critic_hidden", "central_critic", "precision",
         "n_epochs", "n_minibatches", "normalize_adv", "clip_value")] + [(n, C.c_float) for n in (
         "gamma", "lambda_", "clip_eps", "ent_coef", "vf_coef", "max_grad_norm",
-        "lr", "beta1", "beta2", "adam_eps")] + [("seed", C.c_uint64)]
+        "lr", "beta1", "beta2", "adam_eps")] + [("seed", C.c_uint64), ("recurrent", C.c_int32),
+                                                   ("reserved", C.c_int32)]
 
 
 _U8P = C.POINTER(C.c_uint8)
@@ -48,6 +49,10 @@ class EnvStateC(C.Structure):
     _fields_ = [("agent_row", _U8P), ("agent_col", _U8P), ("agent_lvl", _U8P),
                 ("food_row", _U8P), ("food_col", _U8P), ("food_lvl", _U8P),
                 ("t_in_ep", _I32P), ("episode_id", _U32P)]
+
+
+class RecStateC(C.Structure):
+    _fields_ = [("ha0", _F32P), ("hc0", _F32P), ("ha1", _F32P), ("hc1", _F32P)]
 
 
 class TrajC(C.Structure):
@@ -79,6 +84,14 @@ def lib():
         _lib.orc_sample_uniforms.argtypes = [C.POINTER(Config), C.c_uint64, C.c_int32, C.c_int32, _F32P]
         _lib.orc_rollout.argtypes = [C.POINTER(Config), EnvStateC, _F32P, TrajC, C.c_uint64, _I32P, _F32P]
         _lib.orc_compute_gae.argtypes = [C.POINTER(Config), TrajC]
+        _lib.orc_rec_policy_step.argtypes = [C.POINTER(Config), _F32P, _F32P, _F32P, _F32P, C.c_int64, _F32P, _F32P,
+                                             _F32P, _F32P]
+        _lib.orc_rec_rollout.argtypes = [C.POINTER(Config), EnvStateC, _F32P, TrajC, RecStateC, C.c_uint64, _I32P,
+                                         _F32P]
+        _lib.orc_rec_minibatch_loss_grad_f64.argtypes = [C.POINTER(Config), TrajC, RecStateC, _F64P, _I32P, C.c_int32,
+                                                         _F64P, _F64P]
+        _lib.orc_rec_ppo_update.argtypes = [C.POINTER(Config), TrajC, RecStateC, _F32P, _F32P, _F32P, C.c_int64, _I32P,
+                                            _F32P, _F32P]
         _lib.orc_evaluate.argtypes = [C.POINTER(Config), EnvStateC, _F32P, C.c_int32, _F32P, _I32P, _I32P, _F32P]
         _lib.orc_minibatch_loss_grad_f64.argtypes = [C.POINTER(Config), TrajC, _F64P, _I32P, C.c_int32,
                                                      _F64P, _F64P]
@@ -92,7 +105,7 @@ def make_config(cfg: dict) -> Config:
     c = Config()
     for name, _ in Config._fields_:
         key = "lambda" if name == "lambda_" else name
-        setattr(c, name, cfg[key])
+        setattr(c, name, 0 if name == "reserved" else cfg.get(key, 0) if name == "recurrent" else cfg[key])
     return c
 
 
@@ -290,3 +303,62 @@ def ppo_update(cfg, traj, params, adam_m, adam_v, adam_step0=0, perm=None):
     lib().orc_ppo_update(C.byref(make_config(cfg)), traj.c(), _ap(params), _ap(adam_m), _ap(adam_v), int(adam_step0),
                          _ap(pm), _ap(stats), _ap(grad))
     return stats, grad
+
+
+# ---- recurrent networks ----------------------------------------------------------------------------------
+
+class RecState:
+    """Hidden states around one rollout: h*0 = state the rollout starts from, h*1 = state it leaves."""
+
+    def __init__(self, cfg):
+        N, A, Ha, Hc = cfg["n_envs"], cfg["n_agents"], cfg["actor_hidden"], cfg["critic_hidden"]
+        cshape = (N, Hc) if cfg["central_critic"] else (N, A, Hc)
+        self.ha0, self.ha1 = np.zeros((N, A, Ha), np.float32), np.zeros((N, A, Ha), np.float32)
+        self.hc0, self.hc1 = np.zeros(cshape, np.float32), np.zeros(cshape, np.float32)
+
+    def c(self):
+        return RecStateC(_ap(self.ha0), _ap(self.hc0), _ap(self.ha1), _ap(self.hc1))
+
+
+def rec_policy_step(cfg, params, obs_rows, ha_in, hc_in):
+    """(logits, value, ha_out, hc_out) of one step of both recurrent networks."""
+    obs_rows = np.ascontiguousarray(obs_rows, np.float32)
+    n = obs_rows.shape[0]
+    A = cfg["n_agents"]
+    ha_in, hc_in = np.ascontiguousarray(ha_in, np.float32), np.ascontiguousarray(hc_in, np.float32)
+    logits, value = np.zeros((n, A, N_ACTIONS), np.float32), np.zeros((n, A), np.float32)
+    ha_out, hc_out = np.zeros_like(ha_in), np.zeros_like(hc_in)
+    params = np.ascontiguousarray(params, np.float32)
+    lib().orc_rec_policy_step(C.byref(make_config(cfg)), _ap(params), _ap(obs_rows), _ap(ha_in), _ap(hc_in), n,
+                              _ap(logits), _ap(value), _ap(ha_out), _ap(hc_out))
+    return logits, value, ha_out, hc_out
+
+
+def rec_rollout(cfg, state, params, traj, rec, step_offset=0, forced_actions=None, forced_uniforms=None):
+    params = np.ascontiguousarray(params, np.float32)
+    fa = None if forced_actions is None else np.ascontiguousarray(forced_actions, np.int32)
+    fu = None if forced_uniforms is None else np.ascontiguousarray(forced_uniforms, np.float32)
+    lib().orc_rec_rollout(C.byref(make_config(cfg)), state.c(), _ap(params), traj.c(), rec.c(), int(step_offset),
+                          _ap(fa), _ap(fu))
+
+
+def rec_minibatch_loss_grad(cfg, traj, rec, params_f64, envs, want_grad=True):
+    params_f64 = np.ascontiguousarray(params_f64, np.float64)
+    envs = np.ascontiguousarray(envs, np.int32)
+    stats = np.zeros(6, np.float64)
+    grad = np.zeros(params_f64.size, np.float64) if want_grad else None
+    lib().orc_rec_minibatch_loss_grad_f64(C.byref(make_config(cfg)), traj.c(), rec.c(), _ap(params_f64), _ap(envs),
+                                          envs.size, _ap(stats), _ap(grad))
+    return stats, grad
+
+
+def rec_ppo_update(cfg, traj, rec, params, adam_m, adam_v, adam_step0=0, perm=None):
+    """In place on params / adam_m / adam_v (fp32).  perm [E][N] over environments.  Returns (stats, last gradient)."""
+    E, M = cfg["n_epochs"], cfg["n_minibatches"]
+    stats = np.zeros((E * M, 8), np.float32)
+    grad = np.zeros(params.size, np.float32)
+    pm = None if perm is None else np.ascontiguousarray(perm, np.int32)
+    lib().orc_rec_ppo_update(C.byref(make_config(cfg)), traj.c(), rec.c(), _ap(params), _ap(adam_m), _ap(adam_v),
+                             int(adam_step0), _ap(pm), _ap(stats), _ap(grad))
+    return stats, grad
+

@@ -27,6 +27,7 @@
 #include <cstdint>
 #include <cstdlib>
 #include <cstring>
+#include <functional>
 #include <vector>
 
 extern "C" {
@@ -39,6 +40,8 @@ typedef struct orc_config {
   float gamma, lambda, clip_eps, ent_coef, vf_coef, max_grad_norm;
   float lr, beta1, beta2, adam_eps;
   uint64_t seed;
+  int32_t recurrent;  // 0: feed-forward networks; 1: a GRU cell in place of the second hidden layer
+  int32_t reserved;
 } orc_config;
 
 // Environment state, structure of arrays, entity-major: x[e * n_envs + env].
@@ -64,6 +67,13 @@ typedef struct orc_traj {
   int32_t* sampled;   // nullable [T][N][A]  action the sampler drew (differs from action only when forced)
   float* gap;         // nullable [T][N][A]  top-two gap of the Gumbel-perturbed logits (fp64 -> fp32)
 } orc_traj;
+
+// Hidden states of the recurrent networks around one rollout: h0 = state the rollout starts from (already
+// zeroed where the previous step ended an episode), h1 = the same for the next rollout.
+typedef struct orc_rec_state {
+  float *ha0, *hc0;  // [N][A][Ha];  [N][A][Hc] (decentralised critic) or [N][Hc] (centralised)
+  float *ha1, *hc1;
+} orc_rec_state;
 
 }  // extern "C"
 
@@ -135,6 +145,10 @@ Dims dims_of(const orc_config& c) {
   d.Dc = d.central ? d.A * d.D : d.D;
   d.Pa = d.D * d.Ha + d.Ha + d.Ha * d.Ha + d.Ha + d.Ha * kActions + kActions;
   d.Pc = d.Dc * d.Hc + d.Hc + d.Hc * d.Hc + d.Hc + d.Hc + 1;
+  if (c.recurrent) {  // embedding, GRU cell (input and hidden weights of three gates), output layer
+    d.Pa = d.D * d.Ha + d.Ha + 2 * (d.Ha * 3 * d.Ha + 3 * d.Ha) + d.Ha * kActions + kActions;
+    d.Pc = d.Dc * d.Hc + d.Hc + 2 * (d.Hc * 3 * d.Hc + 3 * d.Hc) + d.Hc + 1;
+  }
   d.P = d.Pa + d.Pc;
   return d;
 }
@@ -567,6 +581,273 @@ MbStats minibatch_loss_grad(const orc_config& c, const orc_traj& tr, const doubl
   return st;
 }
 
+// ---------------------------------------------------------------------------------------
+// Recurrent networks (the paper's Section 2 and Section 4 list recurrent IPPO and MAPPO next to the feed-forward
+// systems; it gives no architecture).  Reading used here: the second hidden layer is replaced by a GRU cell.
+//   e  = tanh(x We + be)
+//   r  = sigma(e Wi[:, 0:H] + bi[0:H] + h Wh[:, 0:H] + bh[0:H])
+//   z  = sigma(e Wi[:, H:2H] + bi[H:2H] + h Wh[:, H:2H] + bh[H:2H])
+//   n  = tanh(e Wi[:, 2H:3H] + bi[2H:3H] + r * (h Wh[:, 2H:3H] + bh[2H:3H]))
+//   h' = (1 - z) * n + z * h,      out = h' W3 + b3
+// (the gate arrangement of Cho et al. 2014 as most libraries implement it: reset gate applied to the hidden
+// product).  The hidden state entering a step is zero if the previous step ended an episode.  Parameters of a
+// network, in order: We[Din][H] be[H] Wi[H][3H] bi[3H] Wh[H][3H] bh[3H] W3[H][Dout] b3[Dout].
+// The PPO update treats every environment's rollout as one sequence: minibatches are sets of environments, and
+// the gradient flows back through time from t = T-1 to 0, stopping at episode boundaries and at the state the
+// rollout started from.
+// ---------------------------------------------------------------------------------------
+struct RecNet {
+  int Din, H, Dout;
+  const double *We, *be, *Wi, *bi, *Wh, *bh, *W3, *b3;
+};
+struct RecGrad {
+  double *We, *be, *Wi, *bi, *Wh, *bh, *W3, *b3;
+};
+template <class NetT, class Ptr>
+NetT rec_at(Ptr p, int Din, int H, int Dout) {
+  NetT n{};
+  n.We = p; p += (size_t)Din * H;
+  n.be = p; p += H;
+  n.Wi = p; p += (size_t)H * 3 * H;
+  n.bi = p; p += 3 * H;
+  n.Wh = p; p += (size_t)H * 3 * H;
+  n.bh = p; p += 3 * H;
+  n.W3 = p; p += (size_t)H * Dout;
+  n.b3 = p;
+  return n;
+}
+RecNet rec_net_at(const double* p, int Din, int H, int Dout) {
+  RecNet n = rec_at<RecNet>(p, Din, H, Dout);
+  n.Din = Din; n.H = H; n.Dout = Dout;
+  return n;
+}
+
+inline double sigmoid(double x) { return 1.0 / (1.0 + std::exp(-x)); }
+
+// Everything one step of one sequence leaves behind for the backward pass.
+struct RecStep {
+  std::vector<double> x, e, r, z, n, ghn, hprev, h;
+  void size(int Din, int H) {
+    x.resize(Din); e.resize(H); r.resize(H); z.resize(H); n.resize(H); ghn.resize(H); hprev.resize(H); h.resize(H);
+  }
+};
+
+// st.x and st.hprev are inputs; fills the rest of st and out[Dout].
+void rec_forward(const RecNet& w, RecStep& st, double* out) {
+  const int H = w.H;
+  for (int j = 0; j < H; ++j) {
+    double acc = w.be[j];
+    for (int i = 0; i < w.Din; ++i) acc += st.x[i] * w.We[(size_t)i * H + j];
+    st.e[j] = std::tanh(acc);
+  }
+  for (int j = 0; j < H; ++j) {
+    double gi[3], gh[3];
+    for (int g = 0; g < 3; ++g) {
+      gi[g] = w.bi[g * H + j];
+      gh[g] = w.bh[g * H + j];
+      for (int i = 0; i < H; ++i) {
+        gi[g] += st.e[i] * w.Wi[(size_t)i * 3 * H + g * H + j];
+        gh[g] += st.hprev[i] * w.Wh[(size_t)i * 3 * H + g * H + j];
+      }
+    }
+    st.r[j] = sigmoid(gi[0] + gh[0]);
+    st.z[j] = sigmoid(gi[1] + gh[1]);
+    st.ghn[j] = gh[2];
+    st.n[j] = std::tanh(gi[2] + st.r[j] * gh[2]);
+    st.h[j] = (1.0 - st.z[j]) * st.n[j] + st.z[j] * st.hprev[j];
+  }
+  if (out)
+    for (int k = 0; k < w.Dout; ++k) {
+      double acc = w.b3[k];
+      for (int i = 0; i < H; ++i) acc += st.h[i] * w.W3[(size_t)i * w.Dout + k];
+      out[k] = acc;
+    }
+}
+
+// dh[H]: on entry the gradient arriving at h' from later steps; dout[Dout] the gradient of this step's output.
+// Accumulates parameter gradients; on exit dhprev[H] is the gradient with respect to the incoming hidden state.
+void rec_backward(const RecNet& w, const RecGrad& g, const RecStep& st, const double* dout, const double* dh_in,
+                  double* dhprev) {
+  const int H = w.H;
+  std::vector<double> dh(H), dgi(3 * H), dgh(3 * H), de(H);
+  for (int i = 0; i < H; ++i) {
+    double acc = dh_in[i];
+    for (int k = 0; k < w.Dout; ++k) {
+      acc += dout[k] * w.W3[(size_t)i * w.Dout + k];
+      g.W3[(size_t)i * w.Dout + k] += st.h[i] * dout[k];
+    }
+    dh[i] = acc;
+  }
+  for (int k = 0; k < w.Dout; ++k) g.b3[k] += dout[k];
+  for (int j = 0; j < H; ++j) {
+    const double dn = dh[j] * (1.0 - st.z[j]);
+    const double dz = dh[j] * (st.hprev[j] - st.n[j]);
+    dhprev[j] = dh[j] * st.z[j];
+    const double dpre_n = dn * (1.0 - st.n[j] * st.n[j]);
+    const double dr = dpre_n * st.ghn[j];
+    const double dpre_z = dz * st.z[j] * (1.0 - st.z[j]);
+    const double dpre_r = dr * st.r[j] * (1.0 - st.r[j]);
+    dgi[j] = dpre_r; dgi[H + j] = dpre_z; dgi[2 * H + j] = dpre_n;
+    dgh[j] = dpre_r; dgh[H + j] = dpre_z; dgh[2 * H + j] = dpre_n * st.r[j];
+  }
+  for (int c = 0; c < 3 * H; ++c) {
+    g.bi[c] += dgi[c];
+    g.bh[c] += dgh[c];
+  }
+  for (int i = 0; i < H; ++i) {
+    double ae = 0, ah = 0;
+    for (int c = 0; c < 3 * H; ++c) {
+      ae += dgi[c] * w.Wi[(size_t)i * 3 * H + c];
+      ah += dgh[c] * w.Wh[(size_t)i * 3 * H + c];
+      g.Wi[(size_t)i * 3 * H + c] += st.e[i] * dgi[c];
+      g.Wh[(size_t)i * 3 * H + c] += st.hprev[i] * dgh[c];
+    }
+    de[i] = ae * (1.0 - st.e[i] * st.e[i]);
+    dhprev[i] += ah;
+  }
+  for (int i = 0; i < w.Din; ++i)
+    for (int j = 0; j < H; ++j) g.We[(size_t)i * H + j] += st.x[i] * de[j];
+  for (int j = 0; j < H; ++j) g.be[j] += de[j];
+}
+
+// Sequence-minibatch loss and gradient over the environments envs[0 .. n_envs_mb).
+MbStats rec_minibatch_loss_grad(const orc_config& c, const orc_traj& tr, const orc_rec_state& rs, const double* p,
+                                const int32_t* envs, int n_envs_mb, double* grad /*nullable [P], overwritten*/) {
+  const Dims d = dims_of(c);
+  const double B = (double)n_envs_mb * d.T * d.A;
+  const size_t NA = (size_t)d.N * d.A;
+  double mean = 0, stdv = 1;
+  if (c.normalize_adv) {
+    double s = 0;
+    for (int i = 0; i < n_envs_mb; ++i)
+      for (int t = 0; t < d.T; ++t)
+        for (int a = 0; a < d.A; ++a) s += tr.adv[(size_t)t * NA + (size_t)envs[i] * d.A + a];
+    mean = s / B;
+    double q = 0;
+    for (int i = 0; i < n_envs_mb; ++i)
+      for (int t = 0; t < d.T; ++t)
+        for (int a = 0; a < d.A; ++a) {
+          const double e = tr.adv[(size_t)t * NA + (size_t)envs[i] * d.A + a] - mean;
+          q += e * e;
+        }
+    stdv = std::sqrt(q / B);
+  }
+  const RecNet actor = rec_net_at(p, d.D, d.Ha, kActions);
+  const RecNet critic = rec_net_at(p + d.Pa, d.Dc, d.Hc, 1);
+  RecGrad ga{}, gc{};
+  if (grad) {
+    std::fill(grad, grad + d.P, 0.0);
+    ga = rec_at<RecGrad>(grad, d.D, d.Ha, kActions);
+    gc = rec_at<RecGrad>(grad + d.Pa, d.Dc, d.Hc, 1);
+  }
+  MbStats st{0, 0, 0, 0, 0, 0};
+  const double eps = c.clip_eps;
+  auto value_term = [&](double v, double ret, double v_old, double* dv) {
+    double e = v - ret, loss = 0.5 * e * e, g = e;
+    if (c.clip_value) {
+      const double dvv = v - v_old;
+      const double vc = v_old + std::min(std::max(dvv, -eps), eps);
+      const double ec = vc - ret, lc = 0.5 * ec * ec;
+      if (lc > loss) {
+        loss = lc;
+        g = (dvv > -eps && dvv < eps) ? ec : 0.0;
+      }
+    }
+    *dv = g;
+    return loss;
+  };
+  std::vector<RecStep> steps(d.T);
+  std::vector<double> douts((size_t)d.T * kActions);
+
+  // one sequence of one network: forward over t storing the steps and dL/dout, then backward through time
+  auto run_sequence = [&](const RecNet& w, const RecGrad& g, int env, const float* h0, int Dout,
+                          const std::function<void(int, double*)>& load_x,
+                          const std::function<void(int, const double*, double*)>& loss_at) {
+    for (int t = 0; t < d.T; ++t) {
+      RecStep& s = steps[t];
+      s.size(w.Din, w.H);
+      load_x(t, s.x.data());
+      const bool cut = t > 0 && tr.done[(size_t)(t - 1) * d.N + env];
+      for (int j = 0; j < w.H; ++j) s.hprev[j] = t == 0 ? (double)h0[j] : (cut ? 0.0 : steps[t - 1].h[j]);
+      double out[kActions];
+      rec_forward(w, s, out);
+      loss_at(t, out, douts.data() + (size_t)t * kActions);
+    }
+    if (!grad) return;
+    std::vector<double> carry(w.H, 0.0), dhprev(w.H);
+    for (int t = d.T - 1; t >= 0; --t) {
+      rec_backward(w, g, steps[t], douts.data() + (size_t)t * kActions, carry.data(), dhprev.data());
+      const bool cut = t > 0 && tr.done[(size_t)(t - 1) * d.N + env];
+      for (int j = 0; j < w.H; ++j) carry[j] = cut ? 0.0 : dhprev[j];
+    }
+    (void)Dout;
+  };
+
+  for (int i = 0; i < n_envs_mb; ++i) {
+    const int env = envs[i];
+    for (int a = 0; a < d.A; ++a) {
+      auto load_obs = [&](int t, double* x) {
+        const float* o = tr.obs + ((size_t)t * NA + (size_t)env * d.A + a) * d.D;
+        for (int k = 0; k < d.D; ++k) x[k] = o[k];
+      };
+      run_sequence(actor, ga, env, rs.ha0 + ((size_t)env * d.A + a) * d.Ha, kActions, load_obs,
+                   [&](int t, const double* logits, double* dl) {
+                     const size_t s = (size_t)t * NA + (size_t)env * d.A + a;
+                     double m = logits[0];
+                     for (int k = 1; k < kActions; ++k) m = std::max(m, logits[k]);
+                     double se = 0;
+                     for (int k = 0; k < kActions; ++k) se += std::exp(logits[k] - m);
+                     const double lse = m + std::log(se);
+                     double pk[kActions], lpk[kActions], Hent = 0;
+                     for (int k = 0; k < kActions; ++k) {
+                       lpk[k] = logits[k] - lse;
+                       pk[k] = std::exp(lpk[k]);
+                       Hent -= pk[k] * lpk[k];
+                     }
+                     const int act = tr.action[s];
+                     const double log_ratio = lpk[act] - (double)tr.logp[s];
+                     const double ratio = std::exp(log_ratio);
+                     const double advn = c.normalize_adv ? ((double)tr.adv[s] - mean) / (stdv + 1e-8) : (double)tr.adv[s];
+                     const double rc = std::min(std::max(ratio, 1.0 - eps), 1.0 + eps);
+                     const double s1 = ratio * advn, s2 = rc * advn;
+                     st.pi_loss += -std::min(s1, s2) / B;
+                     st.entropy += Hent / B;
+                     st.approx_kl += ((ratio - 1.0) - log_ratio) / B;
+                     st.clip_frac += (std::fabs(ratio - 1.0) > eps ? 1.0 : 0.0) / B;
+                     const double dlogp = (s1 <= s2) ? -(advn * ratio) / B : 0.0;
+                     for (int k = 0; k < kActions; ++k)
+                       dl[k] = dlogp * ((k == act ? 1.0 : 0.0) - pk[k]) + (c.ent_coef / B) * pk[k] * (lpk[k] + Hent);
+                   });
+      if (!d.central)
+        run_sequence(critic, gc, env, rs.hc0 + ((size_t)env * d.A + a) * d.Hc, 1, load_obs,
+                     [&](int t, const double* v, double* dv) {
+                       const size_t s = (size_t)t * NA + (size_t)env * d.A + a;
+                       double g;
+                       st.v_loss += value_term(v[0], tr.ret[s], tr.value[s], &g) / B;
+                       dv[0] = g * c.vf_coef / B;
+                     });
+    }
+    if (d.central)
+      run_sequence(critic, gc, env, rs.hc0 + (size_t)env * d.Hc, 1,
+                   [&](int t, double* x) {
+                     const float* o = tr.obs + ((size_t)t * NA + (size_t)env * d.A) * d.D;
+                     for (int k = 0; k < d.Dc; ++k) x[k] = o[k];
+                   },
+                   [&](int t, const double* v, double* dv) {
+                     double sum = 0;
+                     for (int a = 0; a < d.A; ++a) {
+                       const size_t s = (size_t)t * NA + (size_t)env * d.A + a;
+                       double g;
+                       st.v_loss += value_term(v[0], tr.ret[s], tr.value[s], &g) / B;
+                       sum += g;
+                     }
+                     dv[0] = sum * c.vf_coef / B;
+                   });
+  }
+  st.total = st.pi_loss - c.ent_coef * st.entropy + c.vf_coef * st.v_loss;
+  return st;
+}
+
 }  // namespace
 
 // =========================================================================================
@@ -845,4 +1126,180 @@ void orc_ppo_update(const orc_config* c, orc_traj tr, float* params, float* adam
   }
 }
 
+// ---- recurrent networks ---------------------------------------------------------------------------------
+
+// One step of both recurrent networks on n_rows observation rows obs [n_rows][A][D] from the hidden states
+// ha_in [n_rows][A][Ha], hc_in [n_rows][A][Hc] (centralised critic: [n_rows][Hc]).  Any output may be NULL.
+void orc_rec_policy_step(const orc_config* c, const float* params, const float* obs, const float* ha_in,
+                         const float* hc_in, int64_t n_rows, float* logits, float* value, float* ha_out,
+                         float* hc_out) {
+  const Dims d = dims_of(*c);
+  const std::vector<double> p = effective_params(*c, params);
+  const RecNet actor = rec_net_at(p.data(), d.D, d.Ha, kActions);
+  const RecNet critic = rec_net_at(p.data() + d.Pa, d.Dc, d.Hc, 1);
+  RecStep sa, sc;
+  sa.size(d.D, d.Ha);
+  sc.size(d.Dc, d.Hc);
+  for (int64_t r = 0; r < n_rows; ++r) {
+    const float* row = obs + (size_t)r * d.A * d.D;
+    for (int a = 0; a < d.A; ++a) {
+      const size_t i = (size_t)r * d.A + a;
+      for (int k = 0; k < d.D; ++k) sa.x[k] = row[(size_t)a * d.D + k];
+      for (int j = 0; j < d.Ha; ++j) sa.hprev[j] = ha_in[i * d.Ha + j];
+      double lg[kActions];
+      rec_forward(actor, sa, lg);
+      if (logits)
+        for (int k = 0; k < kActions; ++k) logits[i * kActions + k] = (float)lg[k];
+      if (ha_out)
+        for (int j = 0; j < d.Ha; ++j) ha_out[i * d.Ha + j] = (float)sa.h[j];
+      if (!d.central) {
+        for (int k = 0; k < d.D; ++k) sc.x[k] = sa.x[k];
+        for (int j = 0; j < d.Hc; ++j) sc.hprev[j] = hc_in[i * d.Hc + j];
+        double v;
+        rec_forward(critic, sc, &v);
+        if (value) value[i] = (float)v;
+        if (hc_out)
+          for (int j = 0; j < d.Hc; ++j) hc_out[i * d.Hc + j] = (float)sc.h[j];
+      }
+    }
+    if (d.central) {
+      for (int k = 0; k < d.Dc; ++k) sc.x[k] = row[k];
+      for (int j = 0; j < d.Hc; ++j) sc.hprev[j] = hc_in[(size_t)r * d.Hc + j];
+      double v;
+      rec_forward(critic, sc, &v);
+      if (value)
+        for (int a = 0; a < d.A; ++a) value[(size_t)r * d.A + a] = (float)v;
+      if (hc_out)
+        for (int j = 0; j < d.Hc; ++j) hc_out[(size_t)r * d.Hc + j] = (float)sc.h[j];
+    }
+  }
+}
+
+// Rollout with the recurrent networks: as orc_rollout, the hidden states carried in fp64 from rs.h*0 through the
+// T steps (zeroed where the previous step ended an episode) and left in rs.h*1 for the next rollout.
+void orc_rec_rollout(const orc_config* c, orc_env_state s, const float* params, orc_traj tr, orc_rec_state rs,
+                     uint64_t step_offset, const int32_t* forced_actions, const float* forced_uniforms) {
+  const Dims d = dims_of(*c);
+  const std::vector<double> p = effective_params(*c, params);
+  const RecNet actor = rec_net_at(p.data(), d.D, d.Ha, kActions);
+  const RecNet critic = rec_net_at(p.data() + d.Pa, d.Dc, d.Hc, 1);
+  const size_t NA = (size_t)d.N * d.A;
+  const size_t nc = d.central ? (size_t)d.N : NA;  // critic sequences
+  std::vector<double> ha(NA * d.Ha), hc(nc * d.Hc);
+  for (size_t i = 0; i < ha.size(); ++i) ha[i] = rs.ha0[i];
+  for (size_t i = 0; i < hc.size(); ++i) hc[i] = rs.hc0[i];
+  RecStep sa, sc;
+  sa.size(d.D, d.Ha);
+  sc.size(d.Dc, d.Hc);
+  auto critic_step = [&](const float* obs_row, int n, int a, bool keep, double* v) {  // a ignored when centralised
+    const size_t q = d.central ? (size_t)n : (size_t)n * d.A + a;
+    const float* x = d.central ? obs_row : obs_row + (size_t)a * d.D;
+    for (int k = 0; k < d.Dc; ++k) sc.x[k] = x[k];
+    for (int j = 0; j < d.Hc; ++j) sc.hprev[j] = hc[q * d.Hc + j];
+    rec_forward(critic, sc, v);
+    if (keep)
+      for (int j = 0; j < d.Hc; ++j) hc[q * d.Hc + j] = sc.h[j];
+  };
+  for (int t = 0; t <= d.T; ++t) {
+    float* obs_t = tr.obs + (size_t)t * NA * d.D;
+    for (int n = 0; n < d.N; ++n) {
+      if (t > 0 && tr.done[(size_t)(t - 1) * d.N + n]) {  // a new episode starts from the zero state
+        for (int a = 0; a < d.A; ++a)
+          for (int j = 0; j < d.Ha; ++j) ha[((size_t)n * d.A + a) * d.Ha + j] = 0.0;
+        if (d.central) {
+          for (int j = 0; j < d.Hc; ++j) hc[(size_t)n * d.Hc + j] = 0.0;
+        } else {
+          for (int a = 0; a < d.A; ++a)
+            for (int j = 0; j < d.Hc; ++j) hc[((size_t)n * d.A + a) * d.Hc + j] = 0.0;
+        }
+      }
+      float* obs_row = obs_t + (size_t)n * d.A * d.D;
+      observe_one(*c, s, n, obs_row);
+      if (t == d.T) {  // bootstrap value of the post-rollout observation; the hidden states stay as they are
+        double v;
+        if (d.central) critic_step(obs_row, n, 0, false, &v);
+        for (int a = 0; a < d.A; ++a) {
+          if (!d.central) critic_step(obs_row, n, a, false, &v);
+          tr.last_value[(size_t)n * d.A + a] = (float)v;
+        }
+        continue;
+      }
+      double vc = 0;
+      if (d.central) critic_step(obs_row, n, 0, true, &vc);
+      for (int a = 0; a < d.A; ++a) {
+        const size_t i = (size_t)t * NA + (size_t)n * d.A + a, q = (size_t)n * d.A + a;
+        for (int k = 0; k < d.D; ++k) sa.x[k] = obs_row[(size_t)a * d.D + k];
+        for (int j = 0; j < d.Ha; ++j) sa.hprev[j] = ha[q * d.Ha + j];
+        double lg[kActions];
+        rec_forward(actor, sa, lg);
+        for (int j = 0; j < d.Ha; ++j) ha[q * d.Ha + j] = sa.h[j];
+        float lf[kActions], u[kActions];
+        for (int k = 0; k < kActions; ++k) lf[k] = (float)lg[k];
+        if (forced_uniforms)
+          std::memcpy(u, forced_uniforms + i * kActions, sizeof(u));
+        else
+          orc_sample_uniforms(c, step_offset + (uint64_t)t, n, a, u);
+        int32_t act;
+        float gp;
+        sample_one(lf, u, &act, &gp);
+        if (tr.sampled) tr.sampled[i] = act;
+        if (tr.gap) tr.gap[i] = gp;
+        if (tr.logits) std::memcpy(tr.logits + i * kActions, lf, sizeof(lf));
+        if (forced_actions) act = forced_actions[i];
+        tr.action[i] = act;
+        tr.logp[i] = (float)log_prob(lg, act);
+        double v = vc;
+        if (!d.central) critic_step(obs_row, n, a, true, &v);
+        tr.value[i] = (float)v;
+      }
+      step_one(*c, s, n, tr.action + (size_t)t * NA + (size_t)n * d.A, tr.reward + (size_t)t * NA + (size_t)n * d.A,
+               tr.done + (size_t)t * d.N + n);
+    }
+  }
+  for (size_t i = 0; i < ha.size(); ++i) rs.ha1[i] = (float)ha[i];
+  for (size_t i = 0; i < hc.size(); ++i) rs.hc1[i] = (float)hc[i];
+}
+
+void orc_rec_minibatch_loss_grad_f64(const orc_config* c, orc_traj tr, orc_rec_state rs, const double* params,
+                                     const int32_t* envs, int32_t n_envs_mb, double* out_stats, double* grad) {
+  const MbStats st = rec_minibatch_loss_grad(*c, tr, rs, params, envs, n_envs_mb, grad);
+  out_stats[0] = st.pi_loss; out_stats[1] = st.v_loss; out_stats[2] = st.entropy;
+  out_stats[3] = st.approx_kl; out_stats[4] = st.clip_frac; out_stats[5] = st.total;
+}
+
+// E epochs x M minibatches of N / M environments (whole T-step sequences).  perm nullable [E][N].
+void orc_rec_ppo_update(const orc_config* c, orc_traj tr, orc_rec_state rs, float* params, float* adam_m,
+                        float* adam_v, int64_t adam_step0, const int32_t* perm, float* stats, float* grad_dump) {
+  const Dims d = dims_of(*c);
+  const int M = c->n_minibatches, envs_mb = d.N / M;
+  std::vector<int32_t> ident(d.N);
+  for (int i = 0; i < d.N; ++i) ident[i] = i;
+  std::vector<double> grad(d.P);
+  int64_t k = adam_step0;
+  for (int e = 0; e < c->n_epochs; ++e) {
+    const int32_t* order = perm ? perm + (size_t)e * d.N : ident.data();
+    for (int mb = 0; mb < M; ++mb) {
+      const std::vector<double> p = effective_params(*c, params);
+      const MbStats st = rec_minibatch_loss_grad(*c, tr, rs, p.data(), order + (size_t)mb * envs_mb, envs_mb, grad.data());
+      double sq = 0;
+      for (int i = 0; i < d.P; ++i) sq += grad[i] * grad[i];
+      const double norm = std::sqrt(sq);
+      if (c->max_grad_norm > 0.f) {
+        const double scale = (double)c->max_grad_norm / std::max(norm, (double)c->max_grad_norm);
+        for (int i = 0; i < d.P; ++i) grad[i] *= scale;
+      }
+      ++k;
+      orc_adam_step(c, params, adam_m, adam_v, grad.data(), k, d.P);
+      float* so = stats + (size_t)(e * M + mb) * 8;
+      so[0] = (float)st.pi_loss; so[1] = (float)st.v_loss; so[2] = (float)st.entropy;
+      so[3] = (float)st.approx_kl; so[4] = (float)st.clip_frac; so[5] = (float)norm;
+      so[6] = (float)st.total;
+      so[7] = (std::isfinite(st.total) && std::isfinite(norm)) ? 0.f : 1.f;
+      if (grad_dump && e == c->n_epochs - 1 && mb == M - 1)
+        for (int i = 0; i < d.P; ++i) grad_dump[i] = (float)grad[i];
+    }
+  }
+}
+
 }  // extern "C"
+

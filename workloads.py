@@ -18,6 +18,7 @@ _COMMON = dict(
     # The paper and the workload list give no value for these; ordinary PPO defaults are used.
     ent_coef=0.01, vf_coef=0.5, normalize_adv=1, max_grad_norm=0.5, beta1=0.9, beta2=0.999,
     adam_eps=1e-5, clip_value=0,
+    recurrent=0,  # 1: a GRU cell in place of the second hidden layer of both networks (scaled(cfg, recurrent=1))
 )
 _COMMON["lambda"] = 0.95
 
@@ -66,6 +67,12 @@ def critic_in_dim(cfg):
 def param_layout(cfg):
     """[(name, shape)] of the flat fp32 parameter vector: actor then critic; y = x W + b, W is [in][out]."""
     D, Ha, Hc, Dc = obs_dim(cfg), cfg["actor_hidden"], cfg["critic_hidden"], critic_in_dim(cfg)
+    if cfg.get("recurrent", 0):
+        def net(prefix, din, h, dout):
+            return [(prefix + ".We", (din, h)), (prefix + ".be", (h,)), (prefix + ".Wi", (h, 3 * h)),
+                    (prefix + ".bi", (3 * h,)), (prefix + ".Wh", (h, 3 * h)), (prefix + ".bh", (3 * h,)),
+                    (prefix + ".W3", (h, dout)), (prefix + ".b3", (dout,))]
+        return net("actor", D, Ha, N_ACTIONS) + net("critic", Dc, Hc, 1)
     return [("actor.W1", (D, Ha)), ("actor.b1", (Ha,)), ("actor.W2", (Ha, Ha)), ("actor.b2", (Ha,)),
             ("actor.W3", (Ha, N_ACTIONS)), ("actor.b3", (N_ACTIONS,)),
             ("critic.W1", (Dc, Hc)), ("critic.b1", (Hc,)), ("critic.W2", (Hc, Hc)), ("critic.b2", (Hc,)),
@@ -90,6 +97,19 @@ def init_params(cfg, seed=None, bias_scale=0.0):
         else:
             parts.append(bias_scale * torch.randn(shape[0], generator=g, dtype=torch.float32))
     return torch.cat(parts).numpy().astype(np.float32)
+
+
+def make_env_perm(cfg, seed=None):
+    """[E][N] int32: one seeded permutation of the N environments per epoch (sequence minibatches of the
+    recurrent networks)."""
+    import torch
+
+    base = int(cfg["seed"] if seed is None else seed)
+    out = np.empty((cfg["n_epochs"], cfg["n_envs"]), np.int32)
+    for e in range(cfg["n_epochs"]):
+        g = torch.Generator().manual_seed(base + e)
+        out[e] = torch.randperm(cfg["n_envs"], generator=g).numpy().astype(np.int32)
+    return out
 
 
 def make_perm(cfg, seed=None):
