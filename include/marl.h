@@ -67,6 +67,9 @@ typedef struct marl_config {
   float max_grad_norm; /* <= 0: no global-norm clipping */
   float lr, beta1, beta2, adam_eps;
   uint64_t seed; /* Philox key */
+  int32_t recurrent; /* 0: feed-forward networks; 1: a GRU cell in place of the second hidden layer (fp32 only; sequence
+                        minibatches: n_envs must be divisible by n_minibatches).  Use the *_recurrent entry points. */
+  int32_t reserved;  /* 0 */
 } marl_config;
 
 /* Environment state: entity-major structure of arrays, x[e*N + n]. */
@@ -99,12 +102,25 @@ typedef struct marl_sizes {
   int64_t obs_bytes, step_scalar_bytes /* action, logp, value, reward, adv, ret: each */, done_bytes, last_value_bytes,
       logits_bytes;
   int64_t rollout_workspace_bytes, update_workspace_bytes, eval_workspace_bytes;
+  int64_t hidden_actor_bytes, hidden_critic_bytes; /* recurrent networks: one hidden-state array each (else 0) */
 } marl_sizes;
+
+/* Hidden states of the recurrent networks around one rollout (device, caller-owned, fp32): h*0 is the state the
+ * rollout starts from (zero before the first rollout), h*1 the state it leaves for the next rollout (already zero
+ * where the last step ended an episode).  Actor [N][A][Ha]; critic [N][A][Hc] (IPPO) or [N][Hc] (MAPPO). */
+typedef struct marl_rec_state {
+  float *ha0, *hc0;
+  float *ha1, *hc1;
+} marl_rec_state;
 
 /* Parameter vector (fp32, one flat array, caller-owned):
  *   actor  W1[D][Ha] b1[Ha] W2[Ha][Ha] b2[Ha] W3[Ha][6] b3[6]
  *   critic W1[Dc][Hc] b1[Hc] W2[Hc][Hc] b2[Hc] W3[Hc][1] b3[1]      y = x W + b, row-major
- * Dc = D (IPPO) or A*D (MAPPO: the agents' observations in agent order, i.e. one contiguous obs row). */
+ * Dc = D (IPPO) or A*D (MAPPO: the agents' observations in agent order, i.e. one contiguous obs row).
+ * Recurrent networks (cfg.recurrent = 1), per network with H hidden units, gates in the order reset, update, new:
+ *   We[Din][H] be[H] Wi[H][3H] bi[3H] Wh[H][3H] bh[3H] W3[H][Dout] b3[Dout]
+ *   e = tanh(x We + be); r = sigma(e Wi_r + bi_r + h Wh_r + bh_r); z likewise; n = tanh(e Wi_n + bi_n + r (h Wh_n + bh_n));
+ *   h' = (1 - z) n + z h; out = h' W3 + b3.  h is zero at the first step of an episode. */
 
 /* Fills *out; touches no GPU.  Errors: MARL_E_NULL, MARL_E_CONFIG. */
 int32_t marl_query_sizes(const marl_config* cfg, marl_sizes* out);
@@ -166,6 +182,21 @@ int32_t marl_compute_gae(const marl_config* cfg, marl_traj traj, void* stream);
 int32_t marl_ppo_update(const marl_config* cfg, marl_traj traj, float* params, float* adam_m, float* adam_v,
                         int64_t adam_step0, const int32_t* perm, float* stats, float* grad_dump, void* workspace,
                         void* stream);
+
+/* Recurrent IPPO / MAPPO (Section 2 and Section 4 list them beside the feed-forward systems).  As marl_rollout, with
+ * the hidden states carried from rec.h*0 through the T steps and left in rec.h*1.  workspace: rollout_workspace_bytes
+ * of the recurrent configuration.  MARL_E_CONFIG unless cfg->recurrent = 1. */
+int32_t marl_rollout_recurrent(const marl_config* cfg, marl_env_state st, const float* params, marl_traj traj,
+                               marl_rec_state rec, uint64_t step_offset, const int32_t* forced_actions,
+                               const float* forced_uniforms, void* workspace, void* stream);
+
+/* As marl_ppo_update for the recurrent networks: every environment's T-step rollout is one sequence, a minibatch is
+ * n_envs / n_minibatches environments (epoch e visits them in the order perm[e][0..N), NULL = identity), the loss
+ * is the PPO loss over all steps of those sequences, and the gradient flows back through time from step T-1 to 0,
+ * stopping at episode boundaries and at rec.h*0.  workspace: update_workspace_bytes of the recurrent configuration. */
+int32_t marl_ppo_update_recurrent(const marl_config* cfg, marl_traj traj, marl_rec_state rec, float* params,
+                                  float* adam_m, float* adam_v, int64_t adam_step0, const int32_t* perm, float* stats,
+                                  float* grad_dump, void* workspace, void* stream);
 
 /* Per-environment results of an evaluation block: device arrays of n_envs elements, caller-owned. */
 typedef struct marl_eval_stats {

@@ -20,7 +20,8 @@ class Config(C.Structure):
         "actor_hidden", "critic_hidden", "central_critic", "precision",
         "n_epochs", "n_minibatches", "normalize_adv", "clip_value")] + [(n, C.c_float) for n in (
         "gamma", "lambda_", "clip_eps", "ent_coef", "vf_coef", "max_grad_norm",
-        "lr", "beta1", "beta2", "adam_eps")] + [("seed", C.c_uint64)]
+        "lr", "beta1", "beta2", "adam_eps")] + [("seed", C.c_uint64), ("recurrent", C.c_int32),
+                                                   ("reserved", C.c_int32)]
 
 
 class EnvStateC(C.Structure):
@@ -38,15 +39,21 @@ class Sizes(C.Structure):
         "obs_dim", "critic_in_dim", "n_params", "n_actor_params",
         "state_entity_bytes_agents", "state_entity_bytes_food", "state_t_bytes", "state_episode_bytes",
         "obs_bytes", "step_scalar_bytes", "done_bytes", "last_value_bytes", "logits_bytes",
-        "rollout_workspace_bytes", "update_workspace_bytes", "eval_workspace_bytes")]
+        "rollout_workspace_bytes", "update_workspace_bytes", "eval_workspace_bytes",
+        "hidden_actor_bytes", "hidden_critic_bytes")]
 
 
 class EvalStatsC(C.Structure):
     _fields_ = [("ret_sum", C.c_void_p), ("len_sum", C.c_void_p), ("episodes", C.c_void_p)]
 
 
+class RecStateC(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("ha0", "hc0", "ha1", "hc1")]
+
+
 EXPORTS = ("marl_query_sizes", "marl_env_reset", "marl_observe", "marl_env_step", "marl_policy_forward",
-           "marl_sample_actions", "marl_rollout", "marl_compute_gae", "marl_ppo_update", "marl_evaluate", "marl_timing_enable",
+           "marl_sample_actions", "marl_rollout", "marl_compute_gae", "marl_ppo_update", "marl_evaluate", "marl_rollout_recurrent", "marl_ppo_update_recurrent",
+           "marl_timing_enable",
            "marl_timing_read", "marl_status_string")
 
 _lib = None
@@ -71,6 +78,8 @@ def lib():
         L.marl_compute_gae.argtypes = [cp, TrajC, vp]
         L.marl_ppo_update.argtypes = [cp, TrajC, vp, vp, vp, C.c_int64, vp, vp, vp, vp, vp]
         L.marl_evaluate.argtypes = [cp, EnvStateC, vp, C.c_int32, EvalStatsC, vp, vp]
+        L.marl_rollout_recurrent.argtypes = [cp, EnvStateC, vp, TrajC, RecStateC, C.c_uint64, vp, vp, vp, vp]
+        L.marl_ppo_update_recurrent.argtypes = [cp, TrajC, RecStateC, vp, vp, vp, C.c_int64, vp, vp, vp, vp, vp]
         L.marl_timing_enable.argtypes = [C.c_int32]
         L.marl_timing_read.argtypes = [C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)]
         L.marl_status_string.argtypes = [C.c_int32]
@@ -93,7 +102,9 @@ def _check(code):
 def make_config(cfg: dict) -> Config:
     c = Config()
     for name, _ in Config._fields_:
-        setattr(c, name, cfg["lambda" if name == "lambda_" else name])
+        if name == "reserved":
+            continue
+        setattr(c, name, cfg.get(name, 0) if name == "recurrent" else cfg["lambda" if name == "lambda_" else name])
     return c
 
 
@@ -227,6 +238,38 @@ class EvalStats:
 def evaluate(cfg, state, params, n_episodes, out, workspace, stream=None):
     _check(lib().marl_evaluate(C.byref(make_config(cfg)), state.c(), _ptr(params), int(n_episodes), out.c(),
                                _ptr(workspace), _stream(stream)))
+
+
+class RecState:
+    """Caller-owned hidden states of the recurrent networks around one rollout (h*0 in, h*1 out)."""
+
+    def __init__(self, cfg, device="cuda"):
+        N, A, Ha, Hc = cfg["n_envs"], cfg["n_agents"], cfg["actor_hidden"], cfg["critic_hidden"]
+        cshape = (N, Hc) if cfg["central_critic"] else (N, A, Hc)
+        f32 = dict(dtype=torch.float32, device=device)
+        self.ha0, self.ha1 = torch.zeros((N, A, Ha), **f32), torch.zeros((N, A, Ha), **f32)
+        self.hc0, self.hc1 = torch.zeros(cshape, **f32), torch.zeros(cshape, **f32)
+
+    def c(self):
+        return RecStateC(self.ha0.data_ptr(), self.hc0.data_ptr(), self.ha1.data_ptr(), self.hc1.data_ptr())
+
+    def advance(self):
+        """The state the last rollout left becomes the state the next one starts from."""
+        self.ha0, self.ha1 = self.ha1, self.ha0
+        self.hc0, self.hc1 = self.hc1, self.hc0
+
+
+def rollout_recurrent(cfg, state, params, traj, rec, step_offset, workspace, forced_actions=None, forced_uniforms=None,
+                      stream=None):
+    _check(lib().marl_rollout_recurrent(C.byref(make_config(cfg)), state.c(), _ptr(params), traj.c(), rec.c(),
+                                        int(step_offset), _ptr(forced_actions), _ptr(forced_uniforms), _ptr(workspace),
+                                        _stream(stream)))
+
+
+def ppo_update_recurrent(cfg, traj, rec, params, adam_m, adam_v, adam_step0, perm, stats, grad_dump, workspace, stream=None):
+    _check(lib().marl_ppo_update_recurrent(C.byref(make_config(cfg)), traj.c(), rec.c(), _ptr(params), _ptr(adam_m),
+                                           _ptr(adam_v), int(adam_step0), _ptr(perm), _ptr(stats), _ptr(grad_dump),
+                                           _ptr(workspace), _stream(stream)))
 
 
 KERNEL_CLASSES = {"gemm_nn": 0, "gemm_nt": 1, "gemm_tn": 2, "env_step": 3, "gae": 4, "fused_train": 5}

@@ -8,7 +8,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libmarl_gfx950.so")
-SOURCES = ["api.hip", "env_kernels.hip", "gae_kernels.hip", "policy_kernels.hip", "ppo_kernels.hip"]
+SOURCES = ["api.hip", "env_kernels.hip", "gae_kernels.hip", "policy_kernels.hip", "ppo_kernels.hip",
+           "recurrent_kernels.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", INCLUDE, "-I", CSRC,
          # packed fp32 ALU forms are kept off on this target
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -52,6 +52,8 @@ int32_t validate_config(const marl_config* c) {
     if (h < 32 || h > 512 || h % 32 != 0) return MARL_E_CONFIG;
   if (c->central_critic != 0 && c->central_critic != 1) return MARL_E_CONFIG;
   if (c->precision != 0 && c->precision != 1) return MARL_E_CONFIG;
+  if (c->recurrent != 0 && c->recurrent != 1) return MARL_E_CONFIG;
+  if (c->recurrent == 1 && (c->precision != 0 || c->n_envs % c->n_minibatches != 0)) return MARL_E_CONFIG;
   if (c->precision == 1 && (c->actor_hidden % 64 != 0 || c->critic_hidden % 64 != 0)) return MARL_E_CONFIG;  // bf16 k tile
   if (c->n_epochs < 1 || c->n_minibatches < 1) return MARL_E_CONFIG;
   const int64_t R = (int64_t)c->n_envs * c->rollout_len;
@@ -109,6 +111,15 @@ int32_t marl_query_sizes(const marl_config* cfg, marl_sizes* out) {
   out->done_bytes = (int64_t)d.T * d.N;
   out->last_value_bytes = 4 * d.NA;
   out->logits_bytes = 4 * (int64_t)d.T * d.NA * kActions;
+  out->hidden_actor_bytes = out->hidden_critic_bytes = 0;
+  if (d.recurrent) {
+    out->rollout_workspace_bytes = rec_rollout_workspace_bytes(*cfg);
+    out->update_workspace_bytes = rec_update_workspace_bytes(*cfg);
+    out->eval_workspace_bytes = 0;
+    out->hidden_actor_bytes = 4 * d.NA * d.Ha;
+    out->hidden_critic_bytes = 4 * (d.central ? (int64_t)d.N : d.NA) * d.Hc;
+    return MARL_OK;
+  }
   out->rollout_workspace_bytes = rollout_workspace_bytes(*cfg, d.N);
   out->update_workspace_bytes = update_workspace_bytes(*cfg);
   out->eval_workspace_bytes = eval_workspace_bytes(*cfg);
@@ -144,6 +155,7 @@ int32_t marl_policy_forward(const marl_config* cfg, const float* params, const f
                             float* logits, float* value, void* workspace, void* stream) {
   int32_t rc = validate_config(cfg);
   if (rc != MARL_OK) return rc;
+  if (cfg->recurrent) return MARL_E_CONFIG;  // the recurrent networks have entry points of their own
   MARL_REQUIRE_PTR(params); MARL_REQUIRE_PTR(obs); MARL_REQUIRE_PTR(workspace);
   MARL_OPTIONAL_PTR(logits); MARL_OPTIONAL_PTR(value);
   if (n_rows < 0 || n_rows * cfg->n_agents >= ((int64_t)1 << 31)) return MARL_E_SIZE;
@@ -167,6 +179,7 @@ int32_t marl_rollout(const marl_config* cfg, marl_env_state st, const float* par
                      void* workspace, void* stream) {
   int32_t rc = validate_config(cfg);
   if (rc != MARL_OK) return rc;
+  if (cfg->recurrent) return MARL_E_CONFIG;  // the recurrent networks have entry points of their own
   if ((rc = check_state(st)) != MARL_OK) return rc;
   if ((rc = check_traj(traj, false)) != MARL_OK) return rc;
   MARL_REQUIRE_PTR(params); MARL_REQUIRE_PTR(workspace);
@@ -186,6 +199,7 @@ int32_t marl_evaluate(const marl_config* cfg, marl_env_state st, const float* pa
                       marl_eval_stats out, void* workspace, void* stream) {
   int32_t rc = validate_config(cfg);
   if (rc != MARL_OK) return rc;
+  if (cfg->recurrent) return MARL_E_CONFIG;  // the recurrent networks have entry points of their own
   if ((rc = check_state(st)) != MARL_OK) return rc;
   MARL_REQUIRE_PTR(params); MARL_REQUIRE_PTR(workspace);
   MARL_REQUIRE_PTR(out.ret_sum); MARL_REQUIRE_PTR(out.len_sum); MARL_REQUIRE_PTR(out.episodes);
@@ -198,6 +212,7 @@ int32_t marl_ppo_update(const marl_config* cfg, marl_traj traj, float* params, f
                         void* stream) {
   int32_t rc = validate_config(cfg);
   if (rc != MARL_OK) return rc;
+  if (cfg->recurrent) return MARL_E_CONFIG;  // the recurrent networks have entry points of their own
   if ((rc = check_traj(traj, true)) != MARL_OK) return rc;
   MARL_REQUIRE_PTR(params); MARL_REQUIRE_PTR(adam_m); MARL_REQUIRE_PTR(adam_v); MARL_REQUIRE_PTR(stats);
   MARL_REQUIRE_PTR(workspace);
@@ -205,6 +220,42 @@ int32_t marl_ppo_update(const marl_config* cfg, marl_traj traj, float* params, f
   if (adam_step0 < 0) return MARL_E_SIZE;
   return launch_ppo_update(*cfg, traj, params, adam_m, adam_v, adam_step0, perm, stats, grad_dump, workspace,
                            (hipStream_t)stream);
+}
+
+static int32_t check_rec(const marl_rec_state& r) {
+  MARL_REQUIRE_PTR(r.ha0); MARL_REQUIRE_PTR(r.hc0); MARL_REQUIRE_PTR(r.ha1); MARL_REQUIRE_PTR(r.hc1);
+  return MARL_OK;
+}
+
+int32_t marl_rollout_recurrent(const marl_config* cfg, marl_env_state st, const float* params, marl_traj traj,
+                               marl_rec_state rec, uint64_t step_offset, const int32_t* forced_actions,
+                               const float* forced_uniforms, void* workspace, void* stream) {
+  int32_t rc = validate_config(cfg);
+  if (rc != MARL_OK) return rc;
+  if (!cfg->recurrent) return MARL_E_CONFIG;
+  if ((rc = check_state(st)) != MARL_OK) return rc;
+  if ((rc = check_traj(traj, false)) != MARL_OK) return rc;
+  if ((rc = check_rec(rec)) != MARL_OK) return rc;
+  MARL_REQUIRE_PTR(params); MARL_REQUIRE_PTR(workspace);
+  MARL_OPTIONAL_PTR(forced_actions); MARL_OPTIONAL_PTR(forced_uniforms);
+  return launch_rollout_recurrent(*cfg, st, params, traj, rec, step_offset, forced_actions, forced_uniforms, workspace,
+                                  (hipStream_t)stream);
+}
+
+int32_t marl_ppo_update_recurrent(const marl_config* cfg, marl_traj traj, marl_rec_state rec, float* params,
+                                  float* adam_m, float* adam_v, int64_t adam_step0, const int32_t* perm, float* stats,
+                                  float* grad_dump, void* workspace, void* stream) {
+  int32_t rc = validate_config(cfg);
+  if (rc != MARL_OK) return rc;
+  if (!cfg->recurrent) return MARL_E_CONFIG;
+  if ((rc = check_traj(traj, true)) != MARL_OK) return rc;
+  if ((rc = check_rec(rec)) != MARL_OK) return rc;
+  MARL_REQUIRE_PTR(params); MARL_REQUIRE_PTR(adam_m); MARL_REQUIRE_PTR(adam_v); MARL_REQUIRE_PTR(stats);
+  MARL_REQUIRE_PTR(workspace);
+  MARL_OPTIONAL_PTR(perm); MARL_OPTIONAL_PTR(grad_dump);
+  if (adam_step0 < 0) return MARL_E_SIZE;
+  return launch_ppo_update_recurrent(*cfg, traj, rec, params, adam_m, adam_v, adam_step0, perm, stats, grad_dump,
+                                     workspace, (hipStream_t)stream);
 }
 
 int32_t marl_timing_enable(int32_t on) {

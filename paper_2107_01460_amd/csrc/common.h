@@ -17,7 +17,7 @@ struct Dims {
   int Ha, Hc, Dc;
   int64_t Pa, Pc, P;   // parameter counts: actor, critic, total
   int64_t NA;          // N * A
-  bool central, bf16;
+  bool central, bf16, recurrent;
 };
 
 inline Dims dims_of(const marl_config& c) {
@@ -29,6 +29,11 @@ inline Dims dims_of(const marl_config& c) {
   d.Dc = d.central ? d.A * d.D : d.D;
   d.Pa = (int64_t)d.D * d.Ha + d.Ha + (int64_t)d.Ha * d.Ha + d.Ha + (int64_t)d.Ha * kActions + kActions;
   d.Pc = (int64_t)d.Dc * d.Hc + d.Hc + (int64_t)d.Hc * d.Hc + d.Hc + d.Hc + 1;
+  d.recurrent = c.recurrent != 0;
+  if (d.recurrent) {  // embedding, GRU cell (input and hidden weights of three gates), output layer
+    d.Pa = (int64_t)d.D * d.Ha + d.Ha + 2 * ((int64_t)d.Ha * 3 * d.Ha + 3 * d.Ha) + (int64_t)d.Ha * kActions + kActions;
+    d.Pc = (int64_t)d.Dc * d.Hc + d.Hc + 2 * ((int64_t)d.Hc * 3 * d.Hc + 3 * d.Hc) + d.Hc + 1;
+  }
   d.P = d.Pa + d.Pc;
   d.NA = (int64_t)d.N * d.A;
   return d;
@@ -174,6 +179,14 @@ int32_t launch_rollout(const marl_config& c, marl_env_state st, const float* par
                        void* workspace, hipStream_t s);
 int32_t launch_gae(const marl_config& c, marl_traj tr, hipStream_t s);
 int64_t eval_workspace_bytes(const marl_config& c);
+int64_t rec_rollout_workspace_bytes(const marl_config& c);
+int64_t rec_update_workspace_bytes(const marl_config& c);
+int32_t launch_rollout_recurrent(const marl_config& c, marl_env_state st, const float* params, marl_traj tr,
+                                 marl_rec_state rec, uint64_t step_offset, const int32_t* forced_actions,
+                                 const float* forced_uniforms, void* workspace, hipStream_t s);
+int32_t launch_ppo_update_recurrent(const marl_config& c, marl_traj tr, marl_rec_state rec, float* params, float* adam_m,
+                                    float* adam_v, int64_t adam_step0, const int32_t* perm, float* stats,
+                                    float* grad_dump, void* workspace, hipStream_t s);
 int32_t launch_evaluate(const marl_config& c, marl_env_state st, const float* params, int32_t n_episodes,
                         marl_eval_stats out, void* workspace, hipStream_t s);
 int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, float* adam_m, float* adam_v,

@@ -42,7 +42,8 @@ enum GemmMode { GEMM_NN = 0, GEMM_NT = 1, GEMM_TN = 2 };
 enum GemmEpi {
   EPI_BIAS_TANH = 0,  // C = tanh(acc + aux_vec[n])
   EPI_DTANH = 1,      // C = acc * (1 - aux_mat[m][n]^2);  column sums of C are added to colsum[n]
-  EPI_ATOMIC_ADD = 2  // C += acc (fp32 atomics; split-k partial results)
+  EPI_ATOMIC_ADD = 2, // C += acc (fp32 atomics; split-k partial results)
+  EPI_STORE = 3       // C = acc + aux_vec[n] (aux_vec nullable)
 };
 
 struct GemmArgs {
@@ -51,7 +52,7 @@ struct GemmArgs {
   int64_t ldb;
   float* C;          // [M][ldc]
   int64_t ldc;
-  const float* aux_vec;  // EPI_BIAS_TANH: bias [N]
+  const float* aux_vec;  // EPI_BIAS_TANH: bias [N]; EPI_STORE: nullable bias [N]
   const float* aux_mat;  // EPI_DTANH: previous activation [M][ldaux]
   int64_t ldaux;
   float* colsum;         // TN: column sums of B are added here ([N], atomic), nullable; EPI_DTANH: column sums of C
@@ -202,6 +203,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_f32_kernel(GemmArgs g) {
     float csum = 0.f;
     float bias = 0.f;
     if (EPI == EPI_BIAS_TANH && n_ok) bias = g.aux_vec[n];
+    if (EPI == EPI_STORE && n_ok && g.aux_vec != nullptr) bias = g.aux_vec[n];
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -219,6 +221,8 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_f32_kernel(GemmArgs g) {
             if (g.round_bf16) v = round_to_bf16(v);
             g.C[m * g.ldc + n] = v;
             csum += v;
+          } else if (EPI == EPI_STORE) {
+            g.C[m * g.ldc + n] = v + bias;
           } else {
             atomicAdd(&g.C[m * g.ldc + n], v);
           }
@@ -472,6 +476,7 @@ __global__ void __launch_bounds__(256, 2) gemm2_f32_kernel(GemmArgs g) {
       const int64_t n = n0 + wn * (BN / 2) + jn * 32 + lo;
       float csum = 0.f, bias = 0.f;
       if (EPI == EPI_BIAS_TANH) bias = g.aux_vec[n];
+      if (EPI == EPI_STORE && g.aux_vec != nullptr) bias = g.aux_vec[n];
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -489,6 +494,8 @@ __global__ void __launch_bounds__(256, 2) gemm2_f32_kernel(GemmArgs g) {
               if (g.round_bf16) v = round_to_bf16(v);
               g.C[m * g.ldc + n] = v;
               csum += v;
+            } else if (EPI == EPI_STORE) {
+              g.C[m * g.ldc + n] = v + bias;
             } else {
               atomicAdd(&g.C[m * g.ldc + n], v);
             }

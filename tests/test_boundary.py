@@ -59,6 +59,16 @@ def test_bad_config_rejected(M, field, value):
     assert M.lib().marl_env_reset(C.byref(M.make_config(cfg)), st, None) == -3
 
 
+def test_recurrent_sizes(M):
+    cfg = W.scaled(W.CONFIGS[2], recurrent=1)
+    sz = M.query_sizes(cfg)
+    assert sz.n_params == W.param_count(cfg)
+    assert sz.hidden_actor_bytes == 4 * cfg["n_envs"] * cfg["n_agents"] * cfg["actor_hidden"]
+    assert sz.hidden_critic_bytes == 4 * cfg["n_envs"] * cfg["critic_hidden"]
+    assert sz.rollout_workspace_bytes > 0 and sz.update_workspace_bytes > 0
+    assert M.query_sizes(W.CONFIGS[2]).hidden_actor_bytes == 0
+
+
 def test_too_many_entities_rejected(M):
     cfg = W.scaled(W.CONFIGS[0], grid=2, n_agents=3, n_food=2)
     s = M.binding.Sizes()
@@ -88,6 +98,18 @@ def test_null_and_misaligned_pointers_rejected_before_launch(M):
     assert L.marl_evaluate(C.byref(cfg), ok_state, good, 1 << 20, ev, good, None) == -5
     assert L.marl_evaluate(C.byref(cfg), ok_state, None, 1, ev, good, None) == -1
     assert L.marl_evaluate(C.byref(cfg), ok_state, good, 1, M.binding.EvalStatsC(good, None, good), good, None) == -1
+    rs = M.binding.RecStateC(good, good, good, good)
+    # the recurrent entry points take recurrent configurations only, and the feed-forward ones refuse them
+    assert L.marl_rollout_recurrent(C.byref(cfg), ok_state, good, traj, rs, 0, None, None, good, None) == -3
+    rcfg = M.make_config(W.scaled(W.CONFIGS[0], recurrent=1))
+    assert L.marl_rollout(C.byref(rcfg), ok_state, good, traj, 0, None, None, good, None) == -3
+    assert L.marl_ppo_update(C.byref(rcfg), traj, good, good, good, 0, None, good, None, good, None) == -3
+    assert L.marl_rollout_recurrent(C.byref(rcfg), ok_state, good, traj, M.binding.RecStateC(good, None, good, good), 0,
+                                    None, None, good, None) == -1
+    assert L.marl_ppo_update_recurrent(C.byref(rcfg), traj, rs, good, good, good, -1, None, good, None, good, None) == -5
+    assert L.marl_ppo_update_recurrent(C.byref(rcfg), traj, rs, good, good + 4, good, 0, None, good, None, good, None) == -2
+    bad = M.make_config(W.scaled(W.CONFIGS[0], recurrent=1, n_minibatches=3))     # 64 environments do not split in 3
+    assert L.marl_ppo_update_recurrent(C.byref(bad), traj, rs, good, good, good, 0, None, good, None, good, None) == -3
     assert L.marl_query_sizes(None, None) == -1
     assert M.status_string(0) == "ok" and "null" in M.status_string(-1)
     d, n, w = C.c_double(), C.c_int64(), C.c_double()
