@@ -30,6 +30,12 @@ def gemm_flops_per_step(cfg, W):
     Ha, Hc, Dc = cfg["actor_hidden"], cfg["critic_hidden"], W.critic_in_dim(cfg)
     S = N * A * T
     Sc = N * T if cfg["central_critic"] else S
+    if cfg.get("recurrent", 0):
+        # cell forward: embedding D*H + input and hidden gate products 3*H*H each; backward: the four gate-side
+        # products (dWi, dWh, dE, dh) 3*H*H each and dWe
+        fa, fc = 2 * (D * Ha + 6 * Ha * Ha), 2 * (Dc * Hc + 6 * Hc * Hc)
+        ba, bc = 2 * (D * Ha + 12 * Ha * Ha), 2 * (Dc * Hc + 12 * Hc * Hc)
+        return S * fa + (Sc + Sc // T) * fc + cfg["n_epochs"] * (S * (fa + ba) + Sc * (fc + bc))
     fwd_a, fwd_c = 2 * (D * Ha + Ha * Ha), 2 * (Dc * Hc + Hc * Hc)
     roll = S * fwd_a + (Sc + Sc // T) * fwd_c
     # update: forward + (dW2, dZ1, dW1) backward GEMMs = 2DH + 2HH + 2HH + 2HH + 2DH per sample and epoch
@@ -41,16 +47,24 @@ def run_cpu_baseline(cfg_id, cfg, W):
     import oracle as orc
     n_o = min(cfg["n_envs"], ORACLE_SAMPLE_ENVS[cfg_id])
     c = W.scaled(cfg, n_envs=n_o)
+    if c.get("recurrent", 0):
+        n_o = max(c["n_minibatches"], n_o // 4 // c["n_minibatches"] * c["n_minibatches"])
+        c = W.scaled(cfg, n_envs=n_o)
     params = W.init_params(c)
-    perm = W.make_perm(c)
     s = orc.EnvState(c)
     orc.env_reset(c, s)
     tr = orc.Traj(c)
     m, v = np.zeros_like(params), np.zeros_like(params)
     t0 = time.perf_counter()
-    orc.rollout(c, s, params, tr, 0)
-    orc.compute_gae(c, tr)
-    orc.ppo_update(c, tr, params, m, v, 0, perm)
+    if c.get("recurrent", 0):
+        rec = orc.RecState(c)
+        orc.rec_rollout(c, s, params, tr, rec, 0)
+        orc.compute_gae(c, tr)
+        orc.rec_ppo_update(c, tr, rec, params, m, v, 0, W.make_env_perm(c))
+    else:
+        orc.rollout(c, s, params, tr, 0)
+        orc.compute_gae(c, tr)
+        orc.ppo_update(c, tr, params, m, v, 0, W.make_perm(c))
     dt = time.perf_counter() - t0
     steps = n_o * c["n_agents"] * c["rollout_len"]
     return {"value": steps / dt, "unit": "env-agent steps/s", "cores": 1, "kind": "oracle",
@@ -66,6 +80,8 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="1-based workload index (default 3: MAPPO 15x15, 16384 envs)")
     ap.add_argument("--n-envs", type=int, default=0,
                     help="override the number of environments of the workload (scalability sweep); 0 = the workload's own")
+    ap.add_argument("--recurrent", action="store_true",
+                    help="the workload with recurrent networks (a GRU cell in place of the second hidden layer)")
     ap.add_argument("--eval-episodes", type=int, default=0,
                     help="also time one greedy evaluation block of this many episodes per environment (reported as \"eval\")")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -84,13 +100,19 @@ def main():
     cfg = W.CONFIGS[args.config - 1]
     if args.n_envs:
         cfg = W.scaled(cfg, n_envs=args.n_envs, name="%s@N=%d" % (cfg["name"], args.n_envs))
+    if args.recurrent:
+        if cfg["precision"] != 0:
+            print("the recurrent networks are fp32 only", file=sys.stderr)
+            sys.exit(2)
+        cfg = W.scaled(cfg, recurrent=1, name=cfg["name"] + "+gru")
     sizes = M.query_sizes(cfg)
     dev = lambda x: torch.from_numpy(np.ascontiguousarray(x)).cuda()
     state = M.EnvState(cfg)
     traj = M.Traj(cfg)
     params = dev(W.init_params(cfg))
     adam_m, adam_v = torch.zeros_like(params), torch.zeros_like(params)
-    perm = dev(W.make_perm(cfg))
+    perm = dev(W.make_env_perm(cfg) if args.recurrent else W.make_perm(cfg))
+    rec = M.RecState(cfg) if args.recurrent else None
     E, Mb = cfg["n_epochs"], cfg["n_minibatches"]
     stats = torch.zeros((E * Mb, 8), device="cuda")
     ws_r = M.alloc_workspace(sizes.rollout_workspace_bytes)
@@ -101,9 +123,15 @@ def main():
 
     def step():
         i = it[0]
-        M.rollout(cfg, state, params, traj, i * T, ws_r)
-        M.compute_gae(cfg, traj)
-        M.ppo_update(cfg, traj, params, adam_m, adam_v, i * E * Mb, perm, stats, None, ws_u)
+        if rec is not None:
+            M.rollout_recurrent(cfg, state, params, traj, rec, i * T, ws_r)
+            M.compute_gae(cfg, traj)
+            M.ppo_update_recurrent(cfg, traj, rec, params, adam_m, adam_v, i * E * Mb, perm, stats, None, ws_u)
+            rec.advance()
+        else:
+            M.rollout(cfg, state, params, traj, i * T, ws_r)
+            M.compute_gae(cfg, traj)
+            M.ppo_update(cfg, traj, params, adam_m, adam_v, i * E * Mb, perm, stats, None, ws_u)
         it[0] += 1
 
     if args.calibration_copy:
@@ -169,7 +197,7 @@ def main():
         "roofline_all": lines,
     }
     out["mlp_gemm_tflops_end_to_end"] = out["config"]["mlp_gemm_tflop_per_step"] / (dt / args.steps)
-    if args.eval_episodes > 0:
+    if args.eval_episodes > 0 and not args.recurrent:
         ev_state, ev_out = M.EnvState(cfg), M.EvalStats(cfg)
         ws_e = M.alloc_workspace(sizes.eval_workspace_bytes)
         ev_ms = []
