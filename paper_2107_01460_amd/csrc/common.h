@@ -142,7 +142,17 @@ __device__ __forceinline__ float round_to_bf16(float x) {
   u += 0x7fffu + ((u >> 16) & 1u);
   return __uint_as_float(u & 0xffff0000u);
 }
-__device__ __forceinline__ bf16_t to_bf16(float x) { return (bf16_t)(__float_as_uint(round_to_bf16(x)) >> 16); }
+// fp32 -> bf16 with the hardware conversion (round-to-nearest-even, two values per instruction on gfx950)
+__device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  typedef float f32x2_t __attribute__((ext_vector_type(2)));
+  const f32x2_t v = {lo, hi};
+  const bf16x2_t b = __builtin_convertvector(v, bf16x2_t);
+  uint32_t u;
+  __builtin_memcpy(&u, &b, 4);
+  return u;
+}
+__device__ __forceinline__ bf16_t to_bf16(float x) { return (bf16_t)(pack2_bf16(x, 0.f) & 0xffffu); }
 __device__ __forceinline__ float from_bf16(bf16_t h) { return __uint_as_float((uint32_t)h << 16); }
 __device__ __forceinline__ float load_act(const float* p, int64_t i) { return p[i]; }
 __device__ __forceinline__ float load_act(const bf16_t* p, int64_t i) { return from_bf16(p[i]); }

@@ -211,8 +211,8 @@ __global__ void __launch_bounds__(256, 2) gemm_bf16_kernel(GemmBf16Args g) {
       for (int j = 0; j < 2; ++j)
 #pragma unroll
         for (int gq = 0; gq < 4; ++gq) {
-          const uint32_t w0 = (uint32_t)to_bf16(acc[i][j][4 * gq + 0]) | ((uint32_t)to_bf16(acc[i][j][4 * gq + 1]) << 16);
-          const uint32_t w1 = (uint32_t)to_bf16(acc[i][j][4 * gq + 2]) | ((uint32_t)to_bf16(acc[i][j][4 * gq + 3]) << 16);
+          const uint32_t w0 = pack2_bf16(acc[i][j][4 * gq + 0], acc[i][j][4 * gq + 1]);
+          const uint32_t w1 = pack2_bf16(acc[i][j][4 * gq + 2], acc[i][j][4 * gq + 3]);
           *reinterpret_cast<uint2*>(&T[(wn * 64 + j * 32 + lo) * PT + wm * 64 + i * 32 + 8 * gq + 4 * hi]) = make_uint2(w0, w1);
         }
     __syncthreads();
@@ -225,6 +225,198 @@ __global__ void __launch_bounds__(256, 2) gemm_bf16_kernel(GemmBf16Args g) {
   }
 }
 
+// The same product on a 256 x 256 x 64 workgroup tile: four wavefronts, each a 128 x 128 quadrant (4 x 4 MFMA tiles,
+// accumulators in the upper half of the 512-register file, one wavefront per SIMD).  An operand fragment read from
+// LDS feeds four MFMAs instead of two, which halves the LDS bandwidth per flop: with 2 x 2 tiles per wavefront
+// the 128 B/clk of LDS saturate at half the bf16 matrix rate.  Results leave in two passes (one per row half)
+// through a tile staged in the operand buffers.
+template <int EPI>
+__global__ void __launch_bounds__(256, 1) gemm_bf16_big_kernel(GemmBf16Args g) {
+  constexpr int BM = 256, BN = 256, BK = 64, P = BK + 8;
+  constexpr int PTR = 256 + 8;  // pitch of the staged row-major half tile [128][256]
+  constexpr int PTT = 128 + 8;  // pitch of the staged transposed half tile [256][128]
+  static_assert(2 * BM * P >= 128 * PTR && 2 * BM * P >= 256 * PTT, "the output tiles reuse the operand buffers");
+  __shared__ __attribute__((aligned(16))) bf16_t smem[2 * BM * P];
+  bf16_t* As = smem;
+  bf16_t* Bs = smem + BM * P;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1, lo = lane & 31, hi = lane >> 5;
+  const int64_t m0 = (int64_t)blockIdx.x * BM, n0 = (int64_t)blockIdx.y * BN;
+  int64_t k_begin = 0, k_end = g.K;
+  if (EPI == BEPI_ATOMIC) {
+    k_begin = (int64_t)blockIdx.z * g.k_per_split;
+    k_end = min(g.K, k_begin + g.k_per_split);
+  }
+
+  floatx16 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // staging: thread -> rows tid/8 + 32p (p < 8), 16-byte segment tid%8 of the 128-byte k-chunk of each row
+  const int seg = tid & 7, srow = tid >> 3;
+  const bf16_t *arow[8], *brow[8];
+#pragma unroll
+  for (int p = 0; p < 8; ++p) {
+    arow[p] = g.A + min(m0 + srow + 32 * p, g.a_rows - 1) * g.lda + 8 * seg;  // rows past the end re-read the last one
+    brow[p] = g.B + min(n0 + srow + 32 * p, g.b_rows - 1) * g.ldb + 8 * seg;
+  }
+  uint4 ra[8], rb[8];
+  float bsum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  const bool want_bsum = EPI == BEPI_ATOMIC && g.rowsum_b != nullptr && blockIdx.x == 0;
+  auto fetch = [&](int64_t k0) {
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+      ra[p] = *reinterpret_cast<const uint4*>(arow[p] + k0);
+      rb[p] = *reinterpret_cast<const uint4*>(brow[p] + k0);
+    }
+  };
+  auto stage = [&]() {
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+      *reinterpret_cast<uint4*>(&As[(srow + 32 * p) * P + 8 * seg]) = ra[p];
+      *reinterpret_cast<uint4*>(&Bs[(srow + 32 * p) * P + 8 * seg]) = rb[p];
+    }
+    if (EPI == BEPI_ATOMIC && want_bsum) {
+#pragma unroll
+      for (int p = 0; p < 8; ++p) {
+        const uint32_t w[4] = {rb[p].x, rb[p].y, rb[p].z, rb[p].w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) bsum[p] += __uint_as_float(w[q] << 16) + __uint_as_float(w[q] & 0xffff0000u);
+      }
+    }
+  };
+
+  if (k_begin < k_end) fetch(k_begin);
+  for (int64_t k0 = k_begin; k0 < k_end; k0 += BK) {
+    stage();
+    __syncthreads();
+    if (k0 + BK < k_end) fetch(k0 + BK);
+#pragma unroll
+    for (int ks = 0; ks < BK; ks += 16) {
+      bf16x8 a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) a[i] = *reinterpret_cast<const bf16x8*>(&As[(wm * 128 + i * 32 + lo) * P + ks + 8 * hi]);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) b[j] = *reinterpret_cast<const bf16x8*>(&Bs[(wn * 128 + j * 32 + lo) * P + ks + 8 * hi]);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+    __syncthreads();
+  }
+
+  if (EPI == BEPI_ATOMIC) {
+    if (want_bsum) {
+#pragma unroll
+      for (int p = 0; p < 8; ++p) {
+        float v = bsum[p];
+        v += __shfl_xor(v, 1);
+        v += __shfl_xor(v, 2);
+        v += __shfl_xor(v, 4);
+        const int64_t n = n0 + srow + 32 * p;
+        if (seg == 0 && n < g.N) atomicAdd(&g.rowsum_b[n], v);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int64_t m = m0 + wm * 128 + i * 32 + 8 * (r / 4) + 4 * hi + (r % 4), n = n0 + wn * 128 + j * 32 + lo;
+          if (m < g.M && n < g.N) atomicAdd(&g.Cf[m * g.ldcf + n], acc[i][j][r]);
+        }
+    return;
+  }
+
+  bf16_t* T = smem;  // the operand buffers are free (the k loop ended with a barrier)
+#pragma unroll 1
+  for (int half = 0; half < 2; ++half) {  // rows m0 + 128 * half .. + 127: the quadrants of the wavefronts with wm == half
+    const int64_t mh = m0 + 128 * half;
+    if (EPI == BEPI_DTANH_T) {  // the aux half tile [128][256] comes in through LDS with 16-byte loads
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const int row = (tid >> 5) + 8 * q, sg = tid & 31;
+        const int64_t m = mh + row, n = n0 + 8 * sg;
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (m < g.M && n < g.N) v = *reinterpret_cast<const uint4*>(&g.aux[m * g.ldaux + n]);
+        *reinterpret_cast<uint4*>(&T[row * PTR + 8 * sg]) = v;
+      }
+      __syncthreads();
+    }
+    if (wm == half) {  // element-wise epilogue in registers
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int nl = wn * 128 + j * 32 + lo;
+        const int64_t nc = min(n0 + nl, g.N - 1);
+        const float bias = EPI == BEPI_TANH ? g.bias[nc] : 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int ml = i * 32 + 8 * (r / 4) + 4 * hi + (r % 4);
+            float v = acc[i][j][r];
+            if (EPI == BEPI_TANH) {
+              v = tanh_f32(v + bias);
+            } else {
+              const float h = from_bf16(T[ml * PTR + nl]);
+              v = v * (1.0f - h * h);
+            }
+            acc[i][j][r] = (mh + ml < g.M) ? v : 0.f;  // rows past the end leave as zeros (padding of the transposed copy)
+          }
+      }
+    }
+    if (EPI == BEPI_DTANH_T) __syncthreads();  // the aux tile has been consumed
+    if (EPI == BEPI_TANH && g.C != nullptr) {  // ---- row-major copy C [m][n]
+      if (wm == half) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+              T[(i * 32 + 8 * (r / 4) + 4 * hi + (r % 4)) * PTR + wn * 128 + j * 32 + lo] = to_bf16(acc[i][j][r]);
+      }
+      __syncthreads();
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const int row = (tid >> 5) + 8 * q, sg = tid & 31;
+        const int64_t m = mh + row, n = n0 + 8 * sg;
+        if (m < g.M && n < g.N) *reinterpret_cast<uint4*>(&g.C[m * g.ldc + n]) = *reinterpret_cast<const uint4*>(&T[row * PTR + 8 * sg]);
+      }
+      __syncthreads();
+    }
+    if (g.CT != nullptr) {  // ---- transposed copy CT [n][m]
+      if (wm == half) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+              const uint32_t w0 = pack2_bf16(acc[i][j][4 * gq + 0], acc[i][j][4 * gq + 1]);
+              const uint32_t w1 = pack2_bf16(acc[i][j][4 * gq + 2], acc[i][j][4 * gq + 3]);
+              *reinterpret_cast<uint2*>(&T[(wn * 128 + j * 32 + lo) * PTT + i * 32 + 8 * gq + 4 * hi]) = make_uint2(w0, w1);
+            }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const int row = (tid >> 4) + 16 * q, sg = tid & 15;
+        const int64_t n = n0 + row, m = mh + 8 * sg;
+        if (n < g.N && m < g.ct_cols) *reinterpret_cast<uint4*>(&g.CT[n * g.ldct + m]) = *reinterpret_cast<const uint4*>(&T[row * PTT + 8 * sg]);
+      }
+      __syncthreads();
+    }
+  }
+}
+
 template <int EPI>
 inline void launch_gemm_bf16(const GemmBf16Args& g, hipStream_t s) {
   TimedLaunch timed(EPI == BEPI_TANH ? KC_GEMM_NN : (EPI == BEPI_DTANH_T ? KC_GEMM_NT : KC_GEMM_TN),
@@ -232,6 +424,13 @@ inline void launch_gemm_bf16(const GemmBf16Args& g, hipStream_t s) {
   unsigned gz = 1;
   if (EPI == BEPI_ATOMIC) gz = (unsigned)((g.K + g.k_per_split - 1) / g.k_per_split);
   const int64_t mcover = (EPI == BEPI_ATOMIC || g.CT == nullptr) ? g.M : std::max(g.M, g.ct_cols);
+  if (EPI == BEPI_ATOMIC && mcover > 128 && g.N > 128) {
+    // 256 x 256 tiles for the weight gradients.  (For the products with an element-wise epilogue the big tile
+    // measured slower: 256 tanh evaluations per lane with one wavefront per SIMD are not hidden behind anything.)
+    dim3 grid((unsigned)((mcover + 255) / 256), (unsigned)((g.N + 255) / 256), gz);
+    hipLaunchKernelGGL(gemm_bf16_big_kernel<EPI>, grid, dim3(256), 0, s, g);
+    return;
+  }
   dim3 grid((unsigned)((mcover + 127) / 128), (unsigned)((g.N + 127) / 128), gz);
   hipLaunchKernelGGL(gemm_bf16_kernel<EPI>, grid, dim3(256), 0, s, g);
 }
