@@ -134,6 +134,16 @@ __device__ __forceinline__ uint32_t rand_below(uint32_t x, uint32_t n) { return 
 __device__ __forceinline__ float rand_unit(uint32_t x) { return ((float)(x >> 9) + 0.5f) * (1.0f / 8388608.0f); }
 constexpr uint32_t kStreamReset = 1, kStreamSample = 2;
 
+// ---- XCD-aware tile order ---------------------------------------------------------------------
+// Workgroups are dealt round-robin to the eight XCDs (each with its own L2), so consecutive workgroup ids never
+// share an L2.  This maps linear workgroup id L of `total` to a logical index such that every XCD walks a
+// contiguous run of logical indices: tiles that share an operand panel are made neighbours in logical order
+// and therefore meet in one L2.  (A bijection for any total.)
+__device__ __forceinline__ unsigned xcd_remap(unsigned L, unsigned total) {
+  const unsigned q = total / 8u, r = total % 8u, x = L % 8u;
+  return x * q + (x < r ? x : r) + L / 8u;
+}
+
 // ---- bfloat16: round-to-nearest-even, stored as the upper 16 bits of an fp32 -------------------
 typedef uint16_t bf16_t;
 __device__ __forceinline__ float round_to_bf16(float x) {

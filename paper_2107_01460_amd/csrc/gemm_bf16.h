@@ -43,23 +43,30 @@ struct GemmBf16Args {
   const bf16_t* aux;
   int64_t ldaux;
   float* rowsum_b;
+  unsigned tiles_m, tiles_n;  // filled by the launcher
 };
 
 template <int EPI>
 __global__ void __launch_bounds__(256, 2) gemm_bf16_kernel(GemmBf16Args g) {
   constexpr int BM = 128, BN = 128, BK = 64, P = BK + 8;  // pitch in elements (144 bytes)
   constexpr int PT = 128 + 8;                             // pitch of the output staging tile (272 bytes)
-  static_assert(2 * BM * P >= 128 * PT, "the output tile reuses the operand buffers");
-  __shared__ __attribute__((aligned(16))) bf16_t smem[2 * BM * P];
-  bf16_t* As = smem;
-  bf16_t* Bs = smem + BM * P;
+  static_assert(2 * 2 * BM * P >= 128 * PT, "the output tile reuses the operand buffers");
+  // two stages of operand tiles: while stage c is multiplied, stage c + 1 sits in LDS and stage c + 2 is on its way
+  // from memory in registers -- the loop is bound by (bytes in flight per CU) / (memory latency), not by the MFMAs
+  __shared__ __attribute__((aligned(16))) bf16_t smem[2 * 2 * BM * P];
+  constexpr int STAGE = 2 * BM * P;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1, lo = lane & 31, hi = lane >> 5;
-  const int64_t m0 = (int64_t)blockIdx.x * BM, n0 = (int64_t)blockIdx.y * BN;
+  // 1-D grid: logical index = (split, m tile, n tile) with the n tile fastest, in XCD-aware order, so that the
+  // workgroups that share an A panel (and, for the split products, a k slab) run on one XCD and meet in its L2
+  const unsigned logical = xcd_remap(blockIdx.x, gridDim.x);
+  const unsigned tn = logical % g.tiles_n, tmn = logical / g.tiles_n;
+  const unsigned tm = tmn % g.tiles_m, split = tmn / g.tiles_m;
+  const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
   int64_t k_begin = 0, k_end = g.K;
   if (EPI == BEPI_ATOMIC) {
-    k_begin = (int64_t)blockIdx.z * g.k_per_split;
+    k_begin = (int64_t)split * g.k_per_split;
     k_end = min(g.K, k_begin + g.k_per_split);
   }
 
@@ -79,17 +86,29 @@ __global__ void __launch_bounds__(256, 2) gemm_bf16_kernel(GemmBf16Args g) {
     arow[p] = g.A + min(m0 + srow + 32 * p, g.a_rows - 1) * g.lda + 8 * seg;  // rows past the end re-read the last one
     brow[p] = g.B + min(n0 + srow + 32 * p, g.b_rows - 1) * g.ldb + 8 * seg;
   }
-  uint4 ra[4], rb[4];
+  // Register sets R0 / R1 hold the chunks in flight: chunk j travels in set j & 1, is written to LDS stage j & 1 one
+  // iteration before it is multiplied, and was requested three iterations before -- two chunks of MFMA work hide
+  // its latency, and one barrier per chunk is all the synchronisation.
+  uint4 ra0[4], rb0[4], ra1[4], rb1[4];
   float bsum[4] = {0.f, 0.f, 0.f, 0.f};
-  const bool want_bsum = EPI == BEPI_ATOMIC && g.rowsum_b != nullptr && blockIdx.x == 0;
-  auto fetch = [&](int64_t k0) {
+  const bool want_bsum = EPI == BEPI_ATOMIC && g.rowsum_b != nullptr && tm == 0;
+  // Chunks are visited in a rotated order that differs from workgroup to workgroup: with a power-of-two row pitch
+  // every workgroup reading the same k offset at the same time would keep hitting the same few memory channels.
+  const int nchunks = (int)((k_end - k_begin + BK - 1) / BK);
+  const int rot = nchunks > 0 ? (int)((tm * 5u + tn * 3u + split) % (unsigned)nchunks) : 0;
+  auto chunk_k = [&](int i) { return k_begin + (int64_t)((i + rot) % nchunks) * BK; };
+  auto fetch = [&](int i, uint4 (&ra)[4], uint4 (&rb)[4]) {
+    if (i >= nchunks) return;
+    const int64_t k0 = chunk_k(i);
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
       ra[p] = *reinterpret_cast<const uint4*>(arow[p] + k0);
       rb[p] = *reinterpret_cast<const uint4*>(brow[p] + k0);
     }
   };
-  auto stage = [&]() {
+  auto stage = [&](int buf, const uint4 (&ra)[4], const uint4 (&rb)[4]) {
+    bf16_t* As = smem + buf * STAGE;
+    bf16_t* Bs = As + BM * P;
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
       *reinterpret_cast<uint4*>(&As[(srow + 32 * p) * P + 8 * seg]) = ra[p];
@@ -104,12 +123,9 @@ __global__ void __launch_bounds__(256, 2) gemm_bf16_kernel(GemmBf16Args g) {
       }
     }
   };
-
-  if (k_begin < k_end) fetch(k_begin);
-  for (int64_t k0 = k_begin; k0 < k_end; k0 += BK) {
-    stage();
-    __syncthreads();
-    if (k0 + BK < k_end) fetch(k0 + BK);
+  auto multiply = [&](int cur) {
+    const bf16_t* As = smem + cur * STAGE;
+    const bf16_t* Bs = As + BM * P;
 #pragma unroll
     for (int ks = 0; ks < BK; ks += 16) {
       bf16x8 a[2], b[2];
@@ -122,8 +138,26 @@ __global__ void __launch_bounds__(256, 2) gemm_bf16_kernel(GemmBf16Args g) {
 #pragma unroll
         for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     }
-    __syncthreads();
+  };
+  // one iteration: chunk at k0 sits in LDS stage `cur`; the next chunk goes from `ra/rb` into the other stage and
+  // the chunk three ahead is requested into the same registers
+  auto iteration = [&](int i, int cur, uint4 (&ra)[4], uint4 (&rb)[4]) {
+    __syncthreads();  // stage `cur` is complete; everybody is done reading the other one
+    if (i + 1 < nchunks) stage(cur ^ 1, ra, rb);
+    fetch(i + 3, ra, rb);
+    multiply(cur);
+  };
+  if (nchunks > 0) {
+    fetch(0, ra0, rb0);
+    fetch(1, ra1, rb1);
+    stage(0, ra0, rb0);
+    fetch(2, ra0, rb0);
   }
+  for (int i = 0; i < nchunks; i += 2) {
+    iteration(i, 0, ra1, rb1);
+    if (i + 1 < nchunks) iteration(i + 1, 1, ra0, rb0);
+  }
+  __syncthreads();  // the operand stages are free for the output tile
 
   if (EPI == BEPI_ATOMIC) {
     if (want_bsum) {
@@ -235,17 +269,23 @@ __global__ void __launch_bounds__(256, 1) gemm_bf16_big_kernel(GemmBf16Args g) {
   constexpr int BM = 256, BN = 256, BK = 64, P = BK + 8;
   constexpr int PTR = 256 + 8;  // pitch of the staged row-major half tile [128][256]
   constexpr int PTT = 128 + 8;  // pitch of the staged transposed half tile [256][128]
-  static_assert(2 * BM * P >= 128 * PTR && 2 * BM * P >= 256 * PTT, "the output tiles reuse the operand buffers");
-  __shared__ __attribute__((aligned(16))) bf16_t smem[2 * BM * P];
-  bf16_t* As = smem;
-  bf16_t* Bs = smem + BM * P;
+  static_assert(2 * 2 * BM * P >= 128 * PTR && 2 * 2 * BM * P >= 256 * PTT, "the output tiles reuse the operand buffers");
+  // two stages of operand tiles: while stage c is multiplied, stage c + 1 sits in LDS and stage c + 2 is on its way
+  // from memory in registers -- the loop is bound by (bytes in flight per CU) / (memory latency), not by the MFMAs
+  __shared__ __attribute__((aligned(16))) bf16_t smem[2 * 2 * BM * P];
+  constexpr int STAGE = 2 * BM * P;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1, lo = lane & 31, hi = lane >> 5;
-  const int64_t m0 = (int64_t)blockIdx.x * BM, n0 = (int64_t)blockIdx.y * BN;
+  // 1-D grid: logical index = (split, m tile, n tile) with the n tile fastest, in XCD-aware order, so that the
+  // workgroups that share an A panel (and, for the split products, a k slab) run on one XCD and meet in its L2
+  const unsigned logical = xcd_remap(blockIdx.x, gridDim.x);
+  const unsigned tn = logical % g.tiles_n, tmn = logical / g.tiles_n;
+  const unsigned tm = tmn % g.tiles_m, split = tmn / g.tiles_m;
+  const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
   int64_t k_begin = 0, k_end = g.K;
   if (EPI == BEPI_ATOMIC) {
-    k_begin = (int64_t)blockIdx.z * g.k_per_split;
+    k_begin = (int64_t)split * g.k_per_split;
     k_end = min(g.K, k_begin + g.k_per_split);
   }
 
@@ -265,17 +305,28 @@ __global__ void __launch_bounds__(256, 1) gemm_bf16_big_kernel(GemmBf16Args g) {
     arow[p] = g.A + min(m0 + srow + 32 * p, g.a_rows - 1) * g.lda + 8 * seg;  // rows past the end re-read the last one
     brow[p] = g.B + min(n0 + srow + 32 * p, g.b_rows - 1) * g.ldb + 8 * seg;
   }
-  uint4 ra[8], rb[8];
+  // One register set (a second one does not fit beside 256 accumulators): chunk j is requested two iterations before
+  // it is multiplied and written to LDS stage j & 1 one iteration before; one barrier per chunk.
+  uint4 ra0[8], rb0[8];
   float bsum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  const bool want_bsum = EPI == BEPI_ATOMIC && g.rowsum_b != nullptr && blockIdx.x == 0;
-  auto fetch = [&](int64_t k0) {
+  const bool want_bsum = EPI == BEPI_ATOMIC && g.rowsum_b != nullptr && tm == 0;
+  // Chunks are visited in a rotated order that differs from workgroup to workgroup: with a power-of-two row pitch
+  // every workgroup reading the same k offset at the same time would keep hitting the same few memory channels.
+  const int nchunks = (int)((k_end - k_begin + BK - 1) / BK);
+  const int rot = nchunks > 0 ? (int)((tm * 5u + tn * 3u + split) % (unsigned)nchunks) : 0;
+  auto chunk_k = [&](int i) { return k_begin + (int64_t)((i + rot) % nchunks) * BK; };
+  auto fetch = [&](int i, uint4 (&ra)[8], uint4 (&rb)[8]) {
+    if (i >= nchunks) return;
+    const int64_t k0 = chunk_k(i);
 #pragma unroll
     for (int p = 0; p < 8; ++p) {
       ra[p] = *reinterpret_cast<const uint4*>(arow[p] + k0);
       rb[p] = *reinterpret_cast<const uint4*>(brow[p] + k0);
     }
   };
-  auto stage = [&]() {
+  auto stage = [&](int buf, const uint4 (&ra)[8], const uint4 (&rb)[8]) {
+    bf16_t* As = smem + buf * STAGE;
+    bf16_t* Bs = As + BM * P;
 #pragma unroll
     for (int p = 0; p < 8; ++p) {
       *reinterpret_cast<uint4*>(&As[(srow + 32 * p) * P + 8 * seg]) = ra[p];
@@ -290,12 +341,9 @@ __global__ void __launch_bounds__(256, 1) gemm_bf16_big_kernel(GemmBf16Args g) {
       }
     }
   };
-
-  if (k_begin < k_end) fetch(k_begin);
-  for (int64_t k0 = k_begin; k0 < k_end; k0 += BK) {
-    stage();
-    __syncthreads();
-    if (k0 + BK < k_end) fetch(k0 + BK);
+  auto multiply = [&](int cur) {
+    const bf16_t* As = smem + cur * STAGE;
+    const bf16_t* Bs = As + BM * P;
 #pragma unroll
     for (int ks = 0; ks < BK; ks += 16) {
       bf16x8 a[4], b[4];
@@ -308,8 +356,20 @@ __global__ void __launch_bounds__(256, 1) gemm_bf16_big_kernel(GemmBf16Args g) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     }
-    __syncthreads();
+  };
+  if (nchunks > 0) {
+    fetch(0, ra0, rb0);
+    stage(0, ra0, rb0);
+    fetch(1, ra0, rb0);
   }
+  int cur = 0;
+  for (int i = 0; i < nchunks; ++i, cur ^= 1) {
+    __syncthreads();  // stage `cur` is complete; everybody is done reading the other one
+    if (i + 1 < nchunks) stage(cur ^ 1, ra0, rb0);
+    fetch(i + 2, ra0, rb0);
+    multiply(cur);
+  }
+  __syncthreads();  // the operand stages are free for the output tile
 
   if (EPI == BEPI_ATOMIC) {
     if (want_bsum) {
@@ -418,7 +478,8 @@ __global__ void __launch_bounds__(256, 1) gemm_bf16_big_kernel(GemmBf16Args g) {
 }
 
 template <int EPI>
-inline void launch_gemm_bf16(const GemmBf16Args& g, hipStream_t s) {
+inline void launch_gemm_bf16(const GemmBf16Args& g0, hipStream_t s) {
+  GemmBf16Args g = g0;
   TimedLaunch timed(EPI == BEPI_TANH ? KC_GEMM_NN : (EPI == BEPI_DTANH_T ? KC_GEMM_NT : KC_GEMM_TN),
                     2.0 * (double)g.M * (double)g.N * (double)g.K, s);
   unsigned gz = 1;
@@ -427,12 +488,14 @@ inline void launch_gemm_bf16(const GemmBf16Args& g, hipStream_t s) {
   if (EPI == BEPI_ATOMIC && mcover > 128 && g.N > 128) {
     // 256 x 256 tiles for the weight gradients.  (For the products with an element-wise epilogue the big tile
     // measured slower: 256 tanh evaluations per lane with one wavefront per SIMD are not hidden behind anything.)
-    dim3 grid((unsigned)((mcover + 255) / 256), (unsigned)((g.N + 255) / 256), gz);
-    hipLaunchKernelGGL(gemm_bf16_big_kernel<EPI>, grid, dim3(256), 0, s, g);
+    g.tiles_m = (unsigned)((mcover + 255) / 256);
+    g.tiles_n = (unsigned)((g.N + 255) / 256);
+    hipLaunchKernelGGL(gemm_bf16_big_kernel<EPI>, dim3(g.tiles_m * g.tiles_n * gz), dim3(256), 0, s, g);
     return;
   }
-  dim3 grid((unsigned)((mcover + 127) / 128), (unsigned)((g.N + 127) / 128), gz);
-  hipLaunchKernelGGL(gemm_bf16_kernel<EPI>, grid, dim3(256), 0, s, g);
+  g.tiles_m = (unsigned)((mcover + 127) / 128);
+  g.tiles_n = (unsigned)((g.N + 127) / 128);
+  hipLaunchKernelGGL(gemm_bf16_kernel<EPI>, dim3(g.tiles_m * g.tiles_n * gz), dim3(256), 0, s, g);
 }
 
 }  // namespace marl
