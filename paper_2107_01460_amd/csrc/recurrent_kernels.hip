@@ -42,6 +42,11 @@ RecOffsets rec_offsets(int64_t base, int Din, int H, int Dout) {
 // Working copy of the parameters with every block on a 64-float boundary (16-byte loads of weight rows).
 struct RecParamMap {
   int64_t src[17], dst[17];  // 16 blocks (actor 8, critic 8) + end
+  // per network, after the blocks: Wh and Wh transposed once more in the order a lane feeds them to the matrix cores
+  // straight from memory: element (k, n) of a [K][N] matrix at ((k / 4) * N + n) * 4 + k % 4
+  int64_t wh_op[2], wht_op[2];
+  int hidden[2];
+  int64_t total;
 };
 RecParamMap rec_param_map(const Dims& d) {
   RecParamMap m;
@@ -53,6 +58,16 @@ RecParamMap rec_param_map(const Dims& d) {
     m.dst[i] = off;
     if (i < 16) off += ((src[i + 1] - src[i] + 63) / 64) * 64;
   }
+  m.hidden[0] = d.Ha;
+  m.hidden[1] = d.Hc;
+  for (int n = 0; n < 2; ++n) {
+    const int64_t sz = (((int64_t)m.hidden[n] * 3 * m.hidden[n] + 63) / 64) * 64;
+    m.wh_op[n] = off;
+    off += sz;
+    m.wht_op[n] = off;
+    off += sz;
+  }
+  m.total = off;
   return m;
 }
 RecOffsets rec_padded(const RecParamMap& m, int net) {
@@ -66,7 +81,15 @@ __global__ void rec_stage_params_kernel(const float* __restrict__ src, float* __
   int b = 0;
 #pragma unroll
   for (int k = 1; k < 16; ++k) b += (i >= pm.src[k]) ? 1 : 0;
-  dst[pm.dst[b] + (i - pm.src[b])] = src[i];
+  const float v = src[i];
+  const int64_t e = i - pm.src[b];
+  dst[pm.dst[b] + e] = v;
+  if (b == 4 || b == 12) {  // a Wh block [H][3H]: also its two operand-order copies
+    const int net = b == 12, H = pm.hidden[net];
+    const int64_t k = e / (3 * H), c = e - k * (3 * H);
+    dst[pm.wh_op[net] + ((k / 4) * (3 * H) + c) * 4 + k % 4] = v;    // (k, c) of Wh
+    dst[pm.wht_op[net] + ((c / 4) * H + k) * 4 + c % 4] = v;          // (c, k) of Wh^T
+  }
 }
 
 __global__ void copy_f32_kernel(const float* __restrict__ src, float* __restrict__ dst, int64_t n) {
@@ -168,6 +191,220 @@ __global__ void gather_hidden_kernel(const float* __restrict__ h0, const int32_t
   dst[i] = h0[((int64_t)envs[j] * per + a) * H + u];
 }
 
+// ---- fused steps ---------------------------------------------------------------------------------------------
+// One time step of the cell in one kernel each way, for H <= 256: the product with the hidden-to-hidden weights runs
+// on the matrix cores with its A operand in LDS and the weights read in operand order straight from memory, and the
+// gate arithmetic is its epilogue (forward) or its prologue (backward).  A workgroup owns 32 samples and all H
+// units: H / 32 wavefronts, wavefront u the units 32 u .. 32 u + 31.
+
+constexpr int kStepRows = 32;
+inline bool fused_step_supported(int H) { return H % 32 == 0 && H <= 256; }
+inline size_t fused_fwd_lds(int H) { return sizeof(float) * kStepRows * (H + 4); }
+inline size_t fused_bwd_lds(int H) { return sizeof(float) * kStepRows * ((3 * H + 4) + (H + 4)); }
+
+// Forward: gates of one step from Gi (input products, no bias) and hprev; see gru_forward_kernel for the outputs.
+__global__ void __launch_bounds__(512) gru_step_fwd_kernel(const float* __restrict__ Gi, const float* __restrict__ Wh_op,
+                                                           const float* __restrict__ bi, const float* __restrict__ bh,
+                                                           const float* hprev, float* __restrict__ rzn,
+                                                           float* __restrict__ ghn, float* hout, float* __restrict__ hnext,
+                                                           const float* __restrict__ keep, int per, int64_t S, int H) {
+  extern __shared__ __attribute__((aligned(16))) float lds[];
+  const int PH = H + 4;
+  float* Hs = lds;  // [32][PH]
+  const int tid = threadIdx.x, lane = tid & 63, u = tid >> 6, lo = lane & 31, hi = lane >> 5;
+  const int nthreads = blockDim.x;
+  const int64_t s0 = (int64_t)blockIdx.x * kStepRows;
+  for (int f = tid; f < kStepRows * (H / 4); f += nthreads) {
+    const int r = f / (H / 4), c4 = f - r * (H / 4);
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (s0 + r < S) v = *reinterpret_cast<const float4*>(hprev + (s0 + r) * H + 4 * c4);
+    *reinterpret_cast<float4*>(&Hs[r * PH + 4 * c4]) = v;
+  }
+  const int n = u * 32 + lo;  // this lane's hidden unit
+  // the input products of this lane's 16 (sample, unit) elements, requested before the matrix loop
+  float gi[3][16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int64_t s = min(s0 + 8 * (r / 4) + 4 * hi + (r % 4), S - 1);
+#pragma unroll
+    for (int g = 0; g < 3; ++g) gi[g][r] = Gi[s * 3 * H + g * H + n];
+  }
+  __syncthreads();
+  floatx16 acc[3];
+#pragma unroll
+  for (int g = 0; g < 3; ++g)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[g][r] = 0.f;
+  const float* As = Hs + lo * PH + 4 * hi;
+  const float* Bg = Wh_op + ((int64_t)hi * 3 * H + n) * 4;  // quad `hi` of k group 0, column n of gate 0
+  const int ksteps = H / 8;  // a multiple of 4
+  // the weights of four k steps are in flight: a wavefront streams its own 3 x 32 columns of Wh from L2 and has
+  // nothing else to hide that latency behind
+  constexpr int kDepth = 4;
+  float4 bq[kDepth][3];
+  auto load_b = [&](int ks, float4 (&b3)[3]) {
+    const int kc = ks < ksteps ? ks : ksteps - 1;
+#pragma unroll
+    for (int g = 0; g < 3; ++g) b3[g] = *reinterpret_cast<const float4*>(Bg + ((int64_t)2 * kc * 3 * H + g * H) * 4);
+  };
+#pragma unroll
+  for (int d = 0; d < kDepth - 1; ++d) load_b(d, bq[d]);
+#pragma unroll 1
+  for (int k0 = 0; k0 < ksteps; k0 += kDepth) {
+#pragma unroll
+    for (int d = 0; d < kDepth; ++d) {
+      const int ks = k0 + d;
+      load_b(ks + kDepth - 1, bq[(d + kDepth - 1) % kDepth]);
+      const float4 av = *reinterpret_cast<const float4*>(As + 8 * ks);
+      const float af[4] = {av.x, av.y, av.z, av.w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int g = 0; g < 3; ++g) {
+          const float4 b = bq[d][g];
+          acc[g] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[j], j == 0 ? b.x : j == 1 ? b.y : j == 2 ? b.z : b.w, acc[g], 0, 0, 0);
+        }
+    }
+  }
+  const float bir = bi[n], biz = bi[H + n], bin_ = bi[2 * H + n];
+  const float bhr = bh[n], bhz = bh[H + n], bhn = bh[2 * H + n];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int m = 8 * (r / 4) + 4 * hi + (r % 4);
+    const int64_t s = s0 + m;
+    if (s < S) {
+      const float rr = sigmoid_f32((gi[0][r] + bir) + (acc[0][r] + bhr));
+      const float zz = sigmoid_f32((gi[1][r] + biz) + (acc[1][r] + bhz));
+      const float hn = acc[2][r] + bhn;
+      const float nn = tanh_f32((gi[2][r] + bin_) + rr * hn);
+      const float h = (1.0f - zz) * nn + zz * Hs[m * PH + n];
+      if (rzn != nullptr) {
+        rzn[s * 3 * H + n] = rr;
+        rzn[s * 3 * H + H + n] = zz;
+        rzn[s * 3 * H + 2 * H + n] = nn;
+      }
+      if (ghn != nullptr) ghn[s * H + n] = hn;
+      hout[s * H + n] = h;
+      if (hnext != nullptr) hnext[s * H + n] = h * keep[s / per];
+    }
+  }
+}
+
+// Backward: the gate gradients of one step (see gru_backward_kernel) and, when want_dhprev, the whole gradient with
+// respect to the incoming hidden state: dh * z + dgh Wh^T.
+template <int NOUT>
+__global__ void __launch_bounds__(512) gru_step_bwd_kernel(const float* __restrict__ dh_next, const float* __restrict__ keep_next,
+                                                           const float* __restrict__ dl, const float* __restrict__ W3,
+                                                           const float* __restrict__ rzn, const float* __restrict__ ghn,
+                                                           const float* __restrict__ hprev, const float* __restrict__ WhT_op,
+                                                           float* __restrict__ dgi, float* __restrict__ dgh,
+                                                           float* __restrict__ dhprev, int want_dhprev, int per, int64_t S,
+                                                           int H) {
+  extern __shared__ __attribute__((aligned(16))) float lds[];
+  const int PG = 3 * H + 4, PH = H + 4;
+  float* Gs = lds;                   // [32][PG]  dgh tile, the A operand
+  float* Ds = Gs + kStepRows * PG;   // [32][PH]  dh * z
+  const int tid = threadIdx.x, lane = tid & 63, u = tid >> 6, lo = lane & 31, hi = lane >> 5;
+  const int nthreads = blockDim.x;  // 2 H
+  const int64_t s0 = (int64_t)blockIdx.x * kStepRows;
+  {  // gate arithmetic: thread -> unit j = tid % H, samples tid / H + 2 q
+    const int j = tid % H, mq = tid / H;
+    float w3[NOUT];
+#pragma unroll
+    for (int k = 0; k < NOUT; ++k) w3[k] = W3[(int64_t)j * NOUT + k];
+#pragma unroll 4
+    for (int q = 0; q < kStepRows / 2; ++q) {
+      const int m = mq + 2 * q;
+      const int64_t s = s0 + m;
+      float g_r = 0.f, g_z = 0.f, g_n = 0.f, g_hn = 0.f, dz_direct = 0.f;
+      if (s < S) {
+        const int64_t i = s * H + j;
+        float dh = dh_next != nullptr ? dh_next[i] * keep_next[s / per] : 0.f;
+#pragma unroll
+        for (int k = 0; k < NOUT; ++k) dh = fmaf(dl[s * NOUT + k], w3[k], dh);
+        const float r = rzn[s * 3 * H + j], z = rzn[s * 3 * H + H + j], n = rzn[s * 3 * H + 2 * H + j];
+        const float dn = dh * (1.0f - z);
+        const float dz = dh * (hprev[i] - n);
+        const float dpre_n = dn * (1.0f - n * n);
+        const float dr = dpre_n * ghn[i];
+        g_z = dz * z * (1.0f - z);
+        g_r = dr * r * (1.0f - r);
+        g_n = dpre_n;
+        g_hn = dpre_n * r;
+        dz_direct = dh * z;
+        dgi[s * 3 * H + j] = g_r;
+        dgi[s * 3 * H + H + j] = g_z;
+        dgi[s * 3 * H + 2 * H + j] = g_n;
+        dgh[s * 3 * H + j] = g_r;
+        dgh[s * 3 * H + H + j] = g_z;
+        dgh[s * 3 * H + 2 * H + j] = g_hn;
+      }
+      Gs[m * PG + j] = g_r;
+      Gs[m * PG + H + j] = g_z;
+      Gs[m * PG + 2 * H + j] = g_hn;
+      Ds[m * PH + j] = dz_direct;
+    }
+  }
+  if (!want_dhprev) return;  // uniform
+  __syncthreads();
+  // dhprev tile = Ds + Gs WhT: wavefront u the 32 units 32 u .., contraction over the 3 H gate columns,
+  // two accumulators over alternate k steps so that consecutive MFMAs do not wait for each other
+  const int n = u * 32 + lo;
+  floatx16 acc[2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[a][r] = 0.f;
+  const float* As = Gs + lo * PG + 4 * hi;
+  const float* Bg = WhT_op + ((int64_t)hi * H + n) * 4;
+  const int ksteps = 3 * H / 8;  // a multiple of 12: H is a multiple of 32
+  constexpr int kDepth = 6;      // k steps in flight
+  float4 bq[kDepth];
+  auto load_b = [&](int ks, float4& b) {
+    const int kc = ks < ksteps ? ks : ksteps - 1;
+    b = *reinterpret_cast<const float4*>(Bg + (int64_t)2 * kc * H * 4);
+  };
+#pragma unroll
+  for (int d = 0; d < kDepth - 1; ++d) load_b(d, bq[d]);
+#pragma unroll 1
+  for (int k0 = 0; k0 < ksteps; k0 += kDepth) {
+#pragma unroll
+    for (int d = 0; d < kDepth; ++d) {
+      const int ks = k0 + d;
+      load_b(ks + kDepth - 1, bq[(d + kDepth - 1) % kDepth]);
+      const float4 av = *reinterpret_cast<const float4*>(As + 8 * ks);
+      const float4 b = bq[d];
+      acc[d & 1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av.x, b.x, acc[d & 1], 0, 0, 0);
+      acc[d & 1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av.y, b.y, acc[d & 1], 0, 0, 0);
+      acc[d & 1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av.z, b.z, acc[d & 1], 0, 0, 0);
+      acc[d & 1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av.w, b.w, acc[d & 1], 0, 0, 0);
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int m = 8 * (r / 4) + 4 * hi + (r % 4);
+    const int64_t s = s0 + m;
+    if (s < S) dhprev[s * H + n] = (acc[0][r] + acc[1][r]) + Ds[m * PH + n];
+  }
+}
+
+template <class K>
+int32_t allow_big_lds(K kern) {
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+    return MARL_E_LAUNCH;
+  return MARL_OK;
+}
+
+// One forward step: fused when the width allows it, else the GEMM + gate kernel pair.
+int32_t launch_step_forward(const float* Gi, const float* hprev, int64_t S, int H, const float* eff, const RecOffsets& o,
+                            const float* wh_op, float* GhT, float* rzn, float* ghn, float* hout, float* hnext,
+                            const float* keep, int per, hipStream_t s);
+template <int NOUT>
+int32_t launch_step_backward(const float* dh_next, const float* keep_next, const float* dl, const float* rzn,
+                             const float* ghn, const float* hprev, int64_t S, int H, const float* eff, const RecOffsets& o,
+                             const float* wht_op, float* dgi, float* dgh, float* dhprev, bool want_dhprev, int per,
+                             hipStream_t s);
+
 int64_t align256(int64_t x) { return (x + 255) & ~(int64_t)255; }
 unsigned blocks_for(int64_t n) { return (unsigned)((n + 255) / 256); }
 
@@ -202,6 +439,50 @@ void hidden_gates(const float* hprev, int64_t S, int H, const float* eff, const 
   launch_gemm<GEMM_NN, EPI_STORE>(g, s);
 }
 
+int32_t launch_step_forward(const float* Gi, const float* hprev, int64_t S, int H, const float* eff, const RecOffsets& o,
+                            const float* wh_op, float* GhT, float* rzn, float* ghn, float* hout, float* hnext,
+                            const float* keep, int per, hipStream_t s) {
+  if (fused_step_supported(H)) {
+    TimedLaunch timed(KC_GEMM_NN, 2.0 * (double)S * H * 3.0 * H, s);
+    hipLaunchKernelGGL(gru_step_fwd_kernel, dim3((unsigned)((S + kStepRows - 1) / kStepRows)), dim3(2 * H), fused_fwd_lds(H),
+                       s, Gi, wh_op, eff + o.bi, eff + o.bh, hprev, rzn, ghn, hout, hnext, keep, per, S, H);
+    return MARL_OK;
+  }
+  hidden_gates(hprev, S, H, eff, o, GhT, s);
+  hipLaunchKernelGGL(gru_forward_kernel, dim3(blocks_for(S * H)), dim3(256), 0, s, Gi, GhT, eff + o.bi, eff + o.bh, hprev, rzn,
+                     ghn, hout, hnext, keep, per, S, H);
+  return MARL_OK;
+}
+
+template <int NOUT>
+int32_t launch_step_backward(const float* dh_next, const float* keep_next, const float* dl, const float* rzn,
+                             const float* ghn, const float* hprev, int64_t S, int H, const float* eff, const RecOffsets& o,
+                             const float* wht_op, float* dgi, float* dgh, float* dhprev, bool want_dhprev, int per,
+                             hipStream_t s) {
+  if (fused_step_supported(H)) {
+    static bool configured = false;  // per NOUT
+    if (!configured) {
+      const int32_t rc = allow_big_lds(gru_step_bwd_kernel<NOUT>);
+      if (rc != MARL_OK) return rc;
+      configured = true;
+    }
+    TimedLaunch timed(KC_GEMM_NT, want_dhprev ? 2.0 * (double)S * H * 3.0 * H : 0.0, s);
+    hipLaunchKernelGGL(gru_step_bwd_kernel<NOUT>, dim3((unsigned)((S + kStepRows - 1) / kStepRows)), dim3(2 * H),
+                       fused_bwd_lds(H), s, dh_next, keep_next, dl, eff + o.W3, rzn, ghn, hprev, wht_op, dgi, dgh, dhprev,
+                       (int)want_dhprev, per, S, H);
+    return MARL_OK;
+  }
+  hipLaunchKernelGGL(gru_backward_kernel<NOUT>, dim3(blocks_for(S * H)), dim3(256), 0, s, dh_next, keep_next, dl, eff + o.W3,
+                     rzn, ghn, hprev, dgi, dgh, dhprev, per, S, H);
+  if (want_dhprev) {  // dL/dhprev += dgh Wh^T (what flows into the step before)
+    GemmArgs g{};
+    g.A = RowSrc{dgh, 3 * H, nullptr, 1, S}; g.B = eff + o.Wh; g.ldb = 3 * H; g.C = dhprev; g.ldc = H;
+    g.M = S; g.N = H; g.K = 3 * H;
+    launch_gemm<GEMM_NT, EPI_ATOMIC_ADD>(g, s);
+  }
+  return MARL_OK;
+}
+
 // ---- rollout ---------------------------------------------------------------------------------------------
 
 struct RecRolloutWs {
@@ -219,7 +500,7 @@ RecRolloutWs carve_rec_rollout(const marl_config& c, void* ws, int64_t* total) {
     return (float*)r;
   };
   RecRolloutWs w;
-  w.eff = take(rec_param_map(d).dst[16] * 4);
+  w.eff = take(rec_param_map(d).total * 4);
   w.ha = take(d.NA * d.Ha * 4);
   w.hc = take(Sc * d.Hc * 4);
   w.hc_tmp = take(Sc * d.Hc * 4);
@@ -231,12 +512,10 @@ RecRolloutWs carve_rec_rollout(const marl_config& c, void* ws, int64_t* total) {
 }
 
 // One step of one recurrent network on S samples: hidden state h_in -> h_out (may alias).
-void rec_cell_step(const RowSrc& X, int64_t S, int Din, int H, const float* eff, const RecOffsets& o, const float* h_in,
-                   float* h_out, const RecRolloutWs& w, hipStream_t s) {
+void rec_cell_step(const RowSrc& X, int64_t S, int Din, int H, const float* eff, const RecOffsets& o, const float* wh_op,
+                   const float* h_in, float* h_out, const RecRolloutWs& w, hipStream_t s) {
   embed_and_input_gates(X, S, Din, H, eff, o, w.E, w.Gi, s);
-  hidden_gates(h_in, S, H, eff, o, w.Gh, s);
-  hipLaunchKernelGGL(gru_forward_kernel, dim3(blocks_for(S * H)), dim3(256), 0, s, w.Gi, w.Gh, eff + o.bi, eff + o.bh, h_in,
-                     (float*)nullptr, (float*)nullptr, h_out, (float*)nullptr, (const float*)nullptr, 1, S, H);
+  launch_step_forward(w.Gi, h_in, S, H, eff, o, wh_op, w.Gh, nullptr, nullptr, h_out, nullptr, nullptr, 1, s);
 }
 
 }  // namespace
@@ -279,10 +558,10 @@ int32_t launch_rollout_recurrent(const marl_config& c, marl_env_state st, const 
     a.step = step_offset + (uint64_t)t;
     a.k0 = (uint32_t)(c.seed & 0xffffffffu);
     a.k1 = (uint32_t)(c.seed >> 32);
-    rec_cell_step(RowSrc{obs_t, d.D, nullptr, 1, NA}, NA, d.D, d.Ha, eff, oa, w.ha, w.ha, w, s);
+    rec_cell_step(RowSrc{obs_t, d.D, nullptr, 1, NA}, NA, d.D, d.Ha, eff, oa, eff + pm.wh_op[0], w.ha, w.ha, w, s);
     launch_actor_head_rollout(w.ha, NA, d.Ha, eff + oa.W3, eff + oa.b3,
                               tr.logits ? tr.logits + (int64_t)t * NA * kActions : (float*)nullptr, &a, s);
-    rec_cell_step(RowSrc{obs_t, d.Dc, nullptr, 1, Sc}, Sc, d.Dc, d.Hc, eff, oc, w.hc, w.hc, w, s);
+    rec_cell_step(RowSrc{obs_t, d.Dc, nullptr, 1, Sc}, Sc, d.Dc, d.Hc, eff, oc, eff + pm.wh_op[1], w.hc, w.hc, w, s);
     launch_critic_head_rollout(w.hc, Sc, d.Hc, eff + oc.W3, eff + oc.b3, tr.value + (int64_t)t * NA, d.central ? d.A : 1, s);
     rc = launch_env_step(c, st, a.action, tr.obs + (int64_t)(t + 1) * slab, tr.reward + (int64_t)t * NA,
                          tr.done + (int64_t)t * d.N, true, s);
@@ -292,7 +571,7 @@ int32_t launch_rollout_recurrent(const marl_config& c, marl_env_state st, const 
   hipLaunchKernelGGL(copy_f32_kernel, dim3(blocks_for(NA * d.Ha)), dim3(256), 0, s, w.ha, rec.ha1, NA * d.Ha);
   hipLaunchKernelGGL(copy_f32_kernel, dim3(blocks_for(Sc * d.Hc)), dim3(256), 0, s, w.hc, rec.hc1, Sc * d.Hc);
   // bootstrap value of the post-rollout observation; the hidden state of the next rollout stays as it is
-  rec_cell_step(RowSrc{tr.obs + (int64_t)d.T * slab, d.Dc, nullptr, 1, Sc}, Sc, d.Dc, d.Hc, eff, oc, w.hc, w.hc_tmp, w, s);
+  rec_cell_step(RowSrc{tr.obs + (int64_t)d.T * slab, d.Dc, nullptr, 1, Sc}, Sc, d.Dc, d.Hc, eff, oc, eff + pm.wh_op[1], w.hc, w.hc_tmp, w, s);
   launch_critic_head_rollout(w.hc_tmp, Sc, d.Hc, eff + oc.W3, eff + oc.b3, tr.last_value, d.central ? d.A : 1, s);
   return launch_status();
 }
@@ -324,7 +603,7 @@ RecUpdateWs carve_rec_update(const marl_config& c, void* ws, int64_t* total) {
     return r;
   };
   RecUpdateWs w;
-  w.eff = (float*)take(rec_param_map(d).dst[16] * 4);
+  w.eff = (float*)take(rec_param_map(d).total * 4);
   w.grad = (float*)take(d.P * 4);
   w.sc = (Scalars*)take(sizeof(Scalars));
   w.ident = (int32_t*)take((int64_t)d.N * 4);
@@ -347,19 +626,21 @@ RecUpdateWs carve_rec_update(const marl_config& c, void* ws, int64_t* total) {
 // Forward over the T steps, loss, and back-propagation through time of one network on a minibatch of J sequences
 // (`per` samples per environment row).  Samples are ordered [t][j][a].
 template <int NOUT, class LossFn>
-void train_net_recurrent(const RowSrc& X, int T, int64_t J, int per, int Din, int H, const float* h0,
-                         const int32_t* envs, const float* eff, const RecOffsets& o, float* grad, const RecOffsets& go,
-                         const LossFn& fn, const RecUpdateWs& w, hipStream_t s) {
+int32_t train_net_recurrent(const RowSrc& X, int T, int64_t J, int per, int Din, int H, const float* h0,
+                            const int32_t* envs, const float* eff, const RecOffsets& o, const float* wh_op,
+                            const float* wht_op, float* grad, const RecOffsets& go, const LossFn& fn, const RecUpdateWs& w,
+                            hipStream_t s) {
   const int64_t S1 = J * per, S = (int64_t)T * S1;
   hipLaunchKernelGGL(gather_hidden_kernel, dim3(blocks_for(S1 * H)), dim3(256), 0, s, h0, envs, (int)J, per, H, w.Hprev);
   embed_and_input_gates(X, S, Din, H, eff, o, w.E, w.G, s);
   for (int t = 0; t < T; ++t) {
     const float* hprev = w.Hprev + (int64_t)t * S1 * H;
-    hidden_gates(hprev, S1, H, eff, o, w.GhT, s);
-    hipLaunchKernelGGL(gru_forward_kernel, dim3(blocks_for(S1 * H)), dim3(256), 0, s, w.G + (int64_t)t * S1 * 3 * H, w.GhT,
-                       eff + o.bi, eff + o.bh, hprev, w.RZN + (int64_t)t * S1 * 3 * H, w.GHN + (int64_t)t * S1 * H,
-                       w.Hout + (int64_t)t * S1 * H, t + 1 < T ? w.Hprev + (int64_t)(t + 1) * S1 * H : (float*)nullptr,
-                       t + 1 < T ? w.keep + (int64_t)(t + 1) * J : (const float*)nullptr, per, S1, H);
+    const int32_t rc = launch_step_forward(w.G + (int64_t)t * S1 * 3 * H, hprev, S1, H, eff, o, wh_op, w.GhT,
+                                           w.RZN + (int64_t)t * S1 * 3 * H, w.GHN + (int64_t)t * S1 * H,
+                                           w.Hout + (int64_t)t * S1 * H,
+                                           t + 1 < T ? w.Hprev + (int64_t)(t + 1) * S1 * H : (float*)nullptr,
+                                           t + 1 < T ? w.keep + (int64_t)(t + 1) * J : (const float*)nullptr, per, s);
+    if (rc != MARL_OK) return rc;
   }
   {  // output layer, loss, dL/dout, W3 / b3 gradient over all steps
     const unsigned nb = (unsigned)std::min<int64_t>(2048, (S + kHeadTile - 1) / kHeadTile);
@@ -371,16 +652,11 @@ void train_net_recurrent(const RowSrc& X, int T, int64_t J, int per, int Din, in
     const float* dh_next = t + 1 < T ? w.dHp + (int64_t)((t + 1) & 1) * S1 * H : (const float*)nullptr;
     float* dgi = w.G + (int64_t)t * S1 * 3 * H;  // the input-gate products are no longer needed: their gradient takes their place
     float* dgh = w.dGh + (int64_t)t * S1 * 3 * H;
-    hipLaunchKernelGGL(gru_backward_kernel<NOUT>, dim3(blocks_for(S1 * H)), dim3(256), 0, s, dh_next,
-                       t + 1 < T ? w.keep + (int64_t)(t + 1) * J : (const float*)nullptr, w.dl + (int64_t)t * S1 * NOUT,
-                       eff + o.W3, w.RZN + (int64_t)t * S1 * 3 * H, w.GHN + (int64_t)t * S1 * H,
-                       w.Hprev + (int64_t)t * S1 * H, dgi, dgh, dhp, per, S1, H);
-    if (t > 0) {  // dL/dhprev += dgh Wh^T (what flows into step t - 1)
-      GemmArgs g{};
-      g.A = RowSrc{dgh, 3 * H, nullptr, 1, S1}; g.B = eff + o.Wh; g.ldb = 3 * H; g.C = dhp; g.ldc = H;
-      g.M = S1; g.N = H; g.K = 3 * H;
-      launch_gemm<GEMM_NT, EPI_ATOMIC_ADD>(g, s);
-    }
+    const int32_t rc = launch_step_backward<NOUT>(dh_next, t + 1 < T ? w.keep + (int64_t)(t + 1) * J : (const float*)nullptr,
+                                                  w.dl + (int64_t)t * S1 * NOUT, w.RZN + (int64_t)t * S1 * 3 * H,
+                                                  w.GHN + (int64_t)t * S1 * H, w.Hprev + (int64_t)t * S1 * H, S1, H, eff, o,
+                                                  wht_op, dgi, dgh, dhp, t > 0, per, s);
+    if (rc != MARL_OK) return rc;
   }
   const int64_t tiles_h3 = ((H + 127) / 128) * ((3 * H + 127) / 128);
   {  // gWh += Hprev^T dGh, gbh += column sums
@@ -408,6 +684,7 @@ void train_net_recurrent(const RowSrc& X, int T, int64_t J, int per, int Din, in
     g.k_per_split = k_split(S, ((Din + 127) / 128) * ((H + 127) / 128));
     launch_gemm<GEMM_TN, EPI_ATOMIC_ADD>(g, s);
   }
+  return MARL_OK;
 }
 
 }  // namespace
@@ -446,14 +723,17 @@ int32_t launch_ppo_update_recurrent(const marl_config& c, marl_traj tr, marl_rec
       }
       {
         ActorLoss fn{lc, tr.action, tr.logp, tr.adv};
-        train_net_recurrent<kActions>(RowSrc{tr.obs, d.D, w.rows, d.A, TJ * d.A}, d.T, J, d.A, d.D, d.Ha, rec.ha0, envs, eff,
-                                      oa, w.grad, ga, fn, w, s);
+        const int32_t rc = train_net_recurrent<kActions>(RowSrc{tr.obs, d.D, w.rows, d.A, TJ * d.A}, d.T, J, d.A, d.D, d.Ha,
+                                                         rec.ha0, envs, eff, oa, eff + pm.wh_op[0], eff + pm.wht_op[0], w.grad,
+                                                         ga, fn, w, s);
+        if (rc != MARL_OK) return rc;
       }
       {
         CriticLoss fn{lc, tr.ret, tr.value, d.central ? d.A : 1};
         const int per = d.central ? 1 : d.A;
-        train_net_recurrent<1>(RowSrc{tr.obs, d.Dc, w.rows, per, TJ * per}, d.T, J, per, d.Dc, d.Hc, rec.hc0, envs, eff, oc,
-                               w.grad, gc, fn, w, s);
+        const int32_t rc = train_net_recurrent<1>(RowSrc{tr.obs, d.Dc, w.rows, per, TJ * per}, d.T, J, per, d.Dc, d.Hc, rec.hc0,
+                                                  envs, eff, oc, eff + pm.wh_op[1], eff + pm.wht_op[1], w.grad, gc, fn, w, s);
+        if (rc != MARL_OK) return rc;
       }
       hipLaunchKernelGGL(grad_norm_kernel, dim3((unsigned)std::min<int64_t>(256, (d.P + 255) / 256)), dim3(256), 0, s,
                          w.grad, d.P, w.sc);
