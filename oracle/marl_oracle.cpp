@@ -41,7 +41,7 @@ typedef struct orc_config {
   float lr, beta1, beta2, adam_eps;
   uint64_t seed;
   int32_t recurrent;  // 0: feed-forward networks; 1: a GRU cell in place of the second hidden layer
-  int32_t reserved;
+  int32_t env_kind;   // 0: foraging world; 1: warehouse world; 2: warehouse world whose episodes end on a collision
 } orc_config;
 
 // Environment state, structure of arrays, entity-major: x[e * n_envs + env].
@@ -113,7 +113,7 @@ inline uint32_t rand_below(uint32_t x, uint32_t n) { return (uint32_t)(((uint64_
 // Uniform in the open interval (0,1): the top 23 bits, centred in their bucket.
 inline float rand_unit(uint32_t x) { return ((float)(x >> 9) + 0.5f) * (1.0f / 8388608.0f); }
 
-enum : uint32_t { kStreamReset = 1, kStreamSample = 2 };
+enum : uint32_t { kStreamReset = 1, kStreamSample = 2, kStreamRequest = 3 };
 
 // j-th 32-bit draw of the reset stream of (env, episode).
 struct ResetDraws {
@@ -157,8 +157,13 @@ Dims dims_of(const orc_config& c) {
 // Environment
 // ---------------------------------------------------------------------------------------
 
+void wh_reset_one(const orc_config& c, const orc_env_state& s, int env);
+void wh_step_one(const orc_config& c, const orc_env_state& s, int env, const int32_t* actions, float* reward, uint8_t* done);
+void wh_observe_one(const orc_config& c, const orc_env_state& s, int env, float* obs);
+
 // New episode for one env: levels, then A+F distinct cells, then food levels.
 void reset_one(const orc_config& c, const orc_env_state& s, int env) {
+  if (c.env_kind != 0) return wh_reset_one(c, s, env);
   const Dims d = dims_of(c);
   ResetDraws rng;
   rng.key[0] = (uint32_t)(c.seed & 0xffffffffu);
@@ -202,6 +207,7 @@ void reset_one(const orc_config& c, const orc_env_state& s, int env) {
 // One env, one step; actions[a]; writes reward[a] and *done; auto-resets.
 void step_one(const orc_config& c, const orc_env_state& s, int env, const int32_t* actions,
               float* reward, uint8_t* done) {
+  if (c.env_kind != 0) return wh_step_one(c, s, env, actions, reward, done);
   const Dims d = dims_of(c);
   const int N = d.N;
   std::vector<int> r0(d.A), c0(d.A), tr(d.A), tc(d.A);
@@ -282,6 +288,7 @@ void step_one(const orc_config& c, const orc_env_state& s, int env, const int32_
 
 // Egocentric V x V x 3 view of every agent of one env: (agent level, food level, wall).
 void observe_one(const orc_config& c, const orc_env_state& s, int env, float* obs /*[A][D]*/) {
+  if (c.env_kind != 0) return wh_observe_one(c, s, env, obs);
   const Dims d = dims_of(c);
   const int N = d.N, h = (d.V - 1) / 2;
   for (int a = 0; a < d.A; ++a) {
@@ -306,6 +313,213 @@ void observe_one(const orc_config& c, const orc_env_state& s, int env, float* ob
         o[cell * 3 + 0] = al;
         o[cell * 3 + 1] = fl;
         o[cell * 3 + 2] = wall;
+      }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Warehouse world (a second grid workload in the spirit of the multi-robot warehouse task the paper trains on in
+// Section 4; the paper gives no rules, and says only that the variant it uses ends the episode on collisions and
+// that it reports results with and without that feature.  The rules below are this build's own.)
+//
+// The same buffers as the foraging world: A robots (agent_row / agent_col), F shelves (food_row / food_col).
+// agent_lvl[a] = 0 when robot a carries nothing, else 1 + the index of the shelf it carries; food_lvl[f] = 1 for an
+// idle shelf, 2 for a requested one.  R = max_level shelves are requested at any time.  The two goal cells are
+// (G-1, G/2 - 1) and (G-1, G/2).
+//   Reset: A + F distinct cells as in the foraging world (robots first), then R distinct requested shelves: the
+//   j-th request draws r in [0, F - j) and takes the r-th idle shelf in ascending index.  Nothing is carried.
+//   Step (actions 0 stay, 1 north, 2 south, 3 west, 4 east, 5 toggle), against the start-of-step state:
+//   1. a move is valid iff its target is inside the grid, holds no robot, and -- for a loaded robot -- holds no
+//      shelf (a loaded robot's own shelf travels with it; unloaded robots pass under shelves);
+//   2. two or more valid movers onto one cell all stay;
+//   3. a robot whose in-grid move was refused because of another robot (occupied or contested cell) has collided;
+//   4. movers move, carried shelves with them;
+//   5. toggle: a loaded robot puts its shelf down; an unloaded robot standing on a shelf that nobody carries picks
+//      it up;
+//   6. delivery, robots in ascending index: a robot carrying a requested shelf on a goal cell earns 1.0, the shelf
+//      becomes idle, and one idle shelf other than the delivered one (the delivered one if there is no other)
+//      becomes requested: candidate r in ascending index, r = multiply-high of the candidate count with word
+//      (ordinal of the delivery in the step) % 4 of Philox counter (env, episode, 2 * steps taken in the episode
+//      before this one + ordinal / 4, stream 3);
+//   7. the episode ends at the cap, and in kind 2 also when any robot collided; then auto-reset.
+//   Observation: the same V x V x 3 window; channel 0: 0 / 1 unloaded robot / 2 loaded robot; channel 1: 0 / 1 idle
+//   shelf / 2 requested shelf; channel 2: 1 outside the grid, 0.5 on a goal cell, else 0.
+// ---------------------------------------------------------------------------------------
+inline bool wh_is_goal(int G, int r, int col) { return r == G - 1 && (col == G / 2 - 1 || col == G / 2); }
+
+void wh_reset_one(const orc_config& c, const orc_env_state& s, int env) {
+  const Dims d = dims_of(c);
+  ResetDraws rng;
+  rng.key[0] = (uint32_t)(c.seed & 0xffffffffu);
+  rng.key[1] = (uint32_t)(c.seed >> 32);
+  rng.env = (uint32_t)env;
+  rng.episode = s.episode_id[env];
+  int j = 0;
+  std::vector<int> chosen;  // kept sorted ascending
+  for (int e = 0; e < d.A + d.F; ++e) {
+    int r = (int)rand_below(rng.get(j++), (uint32_t)(d.G * d.G - e));
+    for (size_t q = 0; q < chosen.size(); ++q)
+      if (chosen[q] <= r) ++r;
+    chosen.insert(std::upper_bound(chosen.begin(), chosen.end(), r), r);
+    const uint8_t row = (uint8_t)(r / d.G), col = (uint8_t)(r % d.G);
+    if (e < d.A) {
+      s.agent_row[e * d.N + env] = row;
+      s.agent_col[e * d.N + env] = col;
+      s.agent_lvl[e * d.N + env] = 0;
+    } else {
+      s.food_row[(e - d.A) * d.N + env] = row;
+      s.food_col[(e - d.A) * d.N + env] = col;
+      s.food_lvl[(e - d.A) * d.N + env] = 1;
+    }
+  }
+  for (int q = 0; q < c.max_level; ++q) {
+    int r = (int)rand_below(rng.get(j++), (uint32_t)(d.F - q));
+    for (int f = 0; f < d.F; ++f)
+      if (s.food_lvl[f * d.N + env] == 1 && r-- == 0) {
+        s.food_lvl[f * d.N + env] = 2;
+        break;
+      }
+  }
+  s.t_in_ep[env] = 0;
+}
+
+void wh_step_one(const orc_config& c, const orc_env_state& s, int env, const int32_t* actions, float* reward,
+                 uint8_t* done) {
+  const Dims d = dims_of(c);
+  const int N = d.N;
+  std::vector<int> r0(d.A), c0(d.A), carry(d.A), tr(d.A), tc(d.A);
+  std::vector<char> moves(d.A, 0), robot_refused(d.A, 0);
+  for (int a = 0; a < d.A; ++a) {
+    r0[a] = s.agent_row[a * N + env];
+    c0[a] = s.agent_col[a * N + env];
+    carry[a] = s.agent_lvl[a * N + env];
+  }
+  // 1. targets against the start-of-step state
+  for (int a = 0; a < d.A; ++a) {
+    int nr = r0[a], nc = c0[a];
+    switch (actions[a]) {
+      case 1: nr -= 1; break;
+      case 2: nr += 1; break;
+      case 3: nc -= 1; break;
+      case 4: nc += 1; break;
+      default: break;
+    }
+    const bool wants = (nr != r0[a] || nc != c0[a]) && nr >= 0 && nr < d.G && nc >= 0 && nc < d.G;
+    bool ok = wants;
+    if (ok)
+      for (int b = 0; b < d.A; ++b)
+        if (r0[b] == nr && c0[b] == nc) {
+          ok = false;
+          robot_refused[a] = 1;
+        }
+    if (ok && carry[a] != 0)
+      for (int f = 0; f < d.F; ++f)
+        if (s.food_row[f * N + env] == nr && s.food_col[f * N + env] == nc) ok = false;
+    moves[a] = ok;
+    tr[a] = ok ? nr : r0[a];
+    tc[a] = ok ? nc : c0[a];
+  }
+  // 2. contested cells
+  std::vector<char> blocked(d.A, 0);
+  for (int a = 0; a < d.A; ++a)
+    for (int b = 0; b < d.A; ++b)
+      if (a != b && moves[a] && moves[b] && tr[a] == tr[b] && tc[a] == tc[b]) blocked[a] = 1;
+  // 3. collisions
+  bool collided = false;
+  for (int a = 0; a < d.A; ++a) collided |= robot_refused[a] || blocked[a];
+  // 4. movement, carried shelves with their robots
+  for (int a = 0; a < d.A; ++a)
+    if (moves[a] && !blocked[a]) {
+      s.agent_row[a * N + env] = (uint8_t)tr[a];
+      s.agent_col[a * N + env] = (uint8_t)tc[a];
+      if (carry[a] != 0) {
+        s.food_row[(carry[a] - 1) * N + env] = (uint8_t)tr[a];
+        s.food_col[(carry[a] - 1) * N + env] = (uint8_t)tc[a];
+      }
+    }
+  // 5. toggle (togglers have not moved)
+  for (int a = 0; a < d.A; ++a) {
+    if (actions[a] != 5) continue;
+    if (carry[a] != 0) {
+      s.agent_lvl[a * N + env] = 0;
+    } else {
+      for (int f = 0; f < d.F; ++f) {
+        if (s.food_row[f * N + env] != r0[a] || s.food_col[f * N + env] != c0[a]) continue;
+        bool carried = false;
+        for (int b = 0; b < d.A; ++b) carried |= (carry[b] == f + 1);
+        if (!carried) s.agent_lvl[a * N + env] = (uint8_t)(f + 1);
+      }
+    }
+  }
+  // 6. delivery
+  for (int a = 0; a < d.A; ++a) reward[a] = 0.0f;
+  uint32_t words[4] = {0, 0, 0, 0};
+  int have_call = -1;  // Philox call the words belong to: deliveries 4 q .. 4 q + 3 of the step use call q
+  int ordinal = 0;
+  for (int a = 0; a < d.A; ++a) {
+    const int cy = s.agent_lvl[a * N + env];
+    if (cy == 0) continue;
+    const int f = cy - 1;
+    if (s.food_lvl[f * N + env] != 2) continue;
+    if (!wh_is_goal(d.G, s.agent_row[a * N + env], s.agent_col[a * N + env])) continue;
+    reward[a] = 1.0f;
+    s.food_lvl[f * N + env] = 1;
+    int n_cand = 0;
+    for (int g = 0; g < d.F; ++g) n_cand += (g != f && s.food_lvl[g * N + env] == 1);
+    const int call = ordinal >> 2;
+    if (call != have_call) {
+      const uint32_t key[2] = {(uint32_t)(c.seed & 0xffffffffu), (uint32_t)(c.seed >> 32)};
+      const uint32_t ctr[4] = {(uint32_t)env, s.episode_id[env], (uint32_t)s.t_in_ep[env] * 2u + (uint32_t)call, kStreamRequest};
+      philox4x32_10(ctr, key, words);
+      have_call = call;
+    }
+    if (n_cand == 0) {
+      s.food_lvl[f * N + env] = 2;
+    } else {
+      int r = (int)rand_below(words[ordinal & 3], (uint32_t)n_cand);
+      for (int g = 0; g < d.F; ++g)
+        if (g != f && s.food_lvl[g * N + env] == 1 && r-- == 0) {
+          s.food_lvl[g * N + env] = 2;
+          break;
+        }
+    }
+    ++ordinal;
+  }
+  // 7. termination and auto-reset
+  s.t_in_ep[env] += 1;
+  const bool dn = s.t_in_ep[env] == c.episode_cap || (c.env_kind == 2 && collided);
+  *done = dn ? 1 : 0;
+  if (dn) {
+    s.episode_id[env] += 1;
+    reset_one(c, s, env);
+  }
+}
+
+void wh_observe_one(const orc_config& c, const orc_env_state& s, int env, float* obs /*[A][D]*/) {
+  const Dims d = dims_of(c);
+  const int N = d.N, h = (d.V - 1) / 2;
+  for (int a = 0; a < d.A; ++a) {
+    const int r = s.agent_row[a * N + env], col = s.agent_col[a * N + env];
+    float* o = obs + (size_t)a * d.D;
+    for (int dy = -h; dy <= h; ++dy)
+      for (int dx = -h; dx <= h; ++dx) {
+        const int rr = r + dy, cc = col + dx;
+        float robot = 0.f, shelf = 0.f, ground = 0.f;
+        if (rr < 0 || rr >= d.G || cc < 0 || cc >= d.G) {
+          ground = 1.f;
+        } else {
+          if (wh_is_goal(d.G, rr, cc)) ground = 0.5f;
+          for (int b = 0; b < d.A; ++b)
+            if (s.agent_row[b * N + env] == rr && s.agent_col[b * N + env] == cc)
+              robot = s.agent_lvl[b * N + env] != 0 ? 2.f : 1.f;
+          for (int f = 0; f < d.F; ++f)
+            if (s.food_row[f * N + env] == rr && s.food_col[f * N + env] == cc)
+              shelf = std::max(shelf, (float)s.food_lvl[f * N + env]);
+        }
+        const int cell = (dy + h) * d.V + (dx + h);
+        o[cell * 3 + 0] = robot;
+        o[cell * 3 + 1] = shelf;
+        o[cell * 3 + 2] = ground;
       }
   }
 }
