@@ -80,6 +80,9 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="1-based workload index (default 3: MAPPO 15x15, 16384 envs)")
     ap.add_argument("--n-envs", type=int, default=0,
                     help="override the number of environments of the workload (scalability sweep); 0 = the workload's own")
+    ap.add_argument("--env-kind", type=int, default=0,
+                    help="0: the foraging world of the workload list; 1 / 2: the warehouse world at the same shape "
+                         "(2: episodes also end on a collision)")
     ap.add_argument("--recurrent", action="store_true",
                     help="the workload with recurrent networks (a GRU cell in place of the second hidden layer)")
     ap.add_argument("--eval-episodes", type=int, default=0,
@@ -100,6 +103,9 @@ def main():
     cfg = W.CONFIGS[args.config - 1]
     if args.n_envs:
         cfg = W.scaled(cfg, n_envs=args.n_envs, name="%s@N=%d" % (cfg["name"], args.n_envs))
+    if args.env_kind:
+        cfg = W.scaled(cfg, env_kind=args.env_kind, max_level=min(cfg["max_level"], cfg["n_food"]),
+                       name=cfg["name"] + ("+warehouse" if args.env_kind == 1 else "+warehouse_collision_ends"))
     if args.recurrent:
         if cfg["precision"] != 0:
             print("the recurrent networks are fp32 only", file=sys.stderr)

@@ -49,7 +49,8 @@ typedef struct marl_config {
   int32_t grid;        /* G: side of the square grid, 2..64 */
   int32_t n_agents;    /* A: 1..8 */
   int32_t n_food;      /* F: 1..8; A + F <= G*G */
-  int32_t max_level;   /* agent levels are uniform in 1..max_level; max_level <= 3 */
+  int32_t max_level;   /* agent levels are uniform in 1..max_level; max_level <= 3.  Warehouse world: the number of
+                          shelves requested at any time, 1..n_food */
   int32_t episode_cap; /* an episode ends after this many steps at the latest */
   int32_t view;        /* V: odd side of the egocentric window, 3, 5 or 7 */
   int32_t n_envs;      /* N */
@@ -69,7 +70,8 @@ typedef struct marl_config {
   uint64_t seed; /* Philox key */
   int32_t recurrent; /* 0: feed-forward networks; 1: a GRU cell in place of the second hidden layer (fp32 only; sequence
                         minibatches: n_envs must be divisible by n_minibatches).  Use the *_recurrent entry points. */
-  int32_t reserved;  /* 0 */
+  int32_t env_kind;  /* 0: foraging world; 1: warehouse world (see marl_env_step); 2: warehouse world whose episodes also
+                        end when robots collide */
 } marl_config;
 
 /* Environment state: entity-major structure of arrays, x[e*N + n]. */
@@ -121,6 +123,21 @@ typedef struct marl_rec_state {
  *   We[Din][H] be[H] Wi[H][3H] bi[3H] Wh[H][3H] bh[3H] W3[H][Dout] b3[Dout]
  *   e = tanh(x We + be); r = sigma(e Wi_r + bi_r + h Wh_r + bh_r); z likewise; n = tanh(e Wi_n + bi_n + r (h Wh_n + bh_n));
  *   h' = (1 - z) n + z h; out = h' W3 + b3.  h is zero at the first step of an episode. */
+
+/* Warehouse world (cfg.env_kind = 1 or 2): a second grid workload in the spirit of the multi-robot warehouse task of
+ * Section 4; the rules are this library's own.  It lives in the same buffers: A robots in agent_row / agent_col,
+ * F shelves in food_row / food_col; agent_lvl[a] = 0 when robot a carries nothing, else 1 + the index of the shelf
+ * it carries; food_lvl[f] = 1 for an idle shelf, 2 for a requested one; max_level shelves are requested at any
+ * time; the goal cells are (G-1, G/2 - 1) and (G-1, G/2).  Reset: A + F distinct cells (robots first), then the
+ * requested shelves (the j-th request takes the r-th idle shelf, r drawn in [0, F - j)).  Step, actions 0 stay,
+ * 1..4 north / south / west / east, 5 toggle, against the start-of-step state: a move is valid iff its target is in
+ * the grid, holds no robot and -- for a loaded robot -- no shelf; two or more valid movers onto one cell all stay;
+ * a robot whose in-grid move was refused because of another robot has collided; carried shelves move with their
+ * robots; toggle puts a carried shelf down, or picks up the shelf the robot stands on; then, robots in ascending
+ * index, a robot carrying a requested shelf on a goal cell earns 1.0, the shelf becomes idle and another idle shelf
+ * (the delivered one if there is none) becomes requested, drawn from Philox keyed (seed; env, episode, step in the
+ * episode, ordinal of the delivery); the episode ends at the cap and, with env_kind = 2, on a collision.
+ * Observation channels: 0 / 1 unloaded / 2 loaded robot; 0 / 1 idle / 2 requested shelf; 1 outside the grid, 0.5 goal. */
 
 /* Fills *out; touches no GPU.  Errors: MARL_E_NULL, MARL_E_CONFIG. */
 int32_t marl_query_sizes(const marl_config* cfg, marl_sizes* out);

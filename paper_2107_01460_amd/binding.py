@@ -21,7 +21,7 @@ class Config(C.Structure):
         "n_epochs", "n_minibatches", "normalize_adv", "clip_value")] + [(n, C.c_float) for n in (
         "gamma", "lambda_", "clip_eps", "ent_coef", "vf_coef", "max_grad_norm",
         "lr", "beta1", "beta2", "adam_eps")] + [("seed", C.c_uint64), ("recurrent", C.c_int32),
-                                                   ("reserved", C.c_int32)]
+                                                   ("env_kind", C.c_int32)]
 
 
 class EnvStateC(C.Structure):
@@ -102,9 +102,7 @@ def _check(code):
 def make_config(cfg: dict) -> Config:
     c = Config()
     for name, _ in Config._fields_:
-        if name == "reserved":
-            continue
-        setattr(c, name, cfg.get(name, 0) if name == "recurrent" else cfg["lambda" if name == "lambda_" else name])
+        setattr(c, name, cfg.get(name, 0) if name in ("recurrent", "env_kind") else cfg["lambda" if name == "lambda_" else name])
     return c
 
 

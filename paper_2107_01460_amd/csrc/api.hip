@@ -52,6 +52,8 @@ int32_t validate_config(const marl_config* c) {
     if (h < 32 || h > 512 || h % 32 != 0) return MARL_E_CONFIG;
   if (c->central_critic != 0 && c->central_critic != 1) return MARL_E_CONFIG;
   if (c->precision != 0 && c->precision != 1) return MARL_E_CONFIG;
+  if (c->env_kind < 0 || c->env_kind > 2) return MARL_E_CONFIG;
+  if (c->env_kind != 0 && c->max_level > c->n_food) return MARL_E_CONFIG;  // requested shelves
   if (c->recurrent != 0 && c->recurrent != 1) return MARL_E_CONFIG;
   if (c->recurrent == 1 && (c->precision != 0 || c->n_envs % c->n_minibatches != 0)) return MARL_E_CONFIG;
   if (c->precision == 1 && (c->actor_hidden % 64 != 0 || c->critic_hidden % 64 != 0)) return MARL_E_CONFIG;  // bf16 k tile

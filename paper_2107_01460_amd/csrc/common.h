@@ -132,7 +132,7 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
 }
 __device__ __forceinline__ uint32_t rand_below(uint32_t x, uint32_t n) { return __umulhi(x, n); }
 __device__ __forceinline__ float rand_unit(uint32_t x) { return ((float)(x >> 9) + 0.5f) * (1.0f / 8388608.0f); }
-constexpr uint32_t kStreamReset = 1, kStreamSample = 2;
+constexpr uint32_t kStreamReset = 1, kStreamSample = 2, kStreamRequest = 3;
 
 // ---- XCD-aware tile order ---------------------------------------------------------------------
 // Workgroups are dealt round-robin to the eight XCDs (each with its own L2), so consecutive workgroup ids never

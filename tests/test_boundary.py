@@ -69,6 +69,16 @@ def test_recurrent_sizes(M):
     assert M.query_sizes(W.CONFIGS[2]).hidden_actor_bytes == 0
 
 
+def test_warehouse_config_checks(M):
+    L = M.lib()
+    sz = M.binding.Sizes()
+    ok = M.make_config(W.scaled(W.CONFIGS[1], env_kind=2, max_level=3))
+    assert L.marl_query_sizes(C.byref(ok), C.byref(sz)) == 0
+    assert L.marl_query_sizes(C.byref(M.make_config(W.scaled(W.CONFIGS[1], env_kind=3))), C.byref(sz)) == -3
+    # more requested shelves than shelves
+    assert L.marl_query_sizes(C.byref(M.make_config(W.scaled(W.CONFIGS[0], env_kind=1, max_level=2))), C.byref(sz)) == -3
+
+
 def test_too_many_entities_rejected(M):
     cfg = W.scaled(W.CONFIGS[0], grid=2, n_agents=3, n_food=2)
     s = M.binding.Sizes()

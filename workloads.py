@@ -18,6 +18,7 @@ _COMMON = dict(
     # The paper and the workload list give no value for these; ordinary PPO defaults are used.
     ent_coef=0.01, vf_coef=0.5, normalize_adv=1, max_grad_norm=0.5, beta1=0.9, beta2=0.999,
     adam_eps=1e-5, clip_value=0,
+    env_kind=0,   # 1 / 2: the warehouse world (2: episodes also end on a collision); max_level = requested shelves
     recurrent=0,  # 1: a GRU cell in place of the second hidden layer of both networks (scaled(cfg, recurrent=1))
 )
 _COMMON["lambda"] = 0.95
