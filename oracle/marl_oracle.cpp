@@ -20,7 +20,10 @@
 // has at least one pin that is not itself (known-answer vectors for Philox, hand-built
 // grids and a brute-force set-based stepper for the environment, brute-force discounted
 // sums for GAE, finite differences and float64 autograd for the loss gradients,
-// torch.optim.Adam for the optimiser).
+// torch.optim.Adam for the optimiser; closed forms and a step-by-step restatement for the
+// evaluation block; torch's GRUCell, float64 autograd through time and the feed-forward
+// special case for the recurrent networks; hand-built cases, invariants and an
+// independent set-based restatement for the warehouse world).
 
 #include <algorithm>
 #include <cmath>

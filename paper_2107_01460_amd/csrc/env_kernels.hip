@@ -1,9 +1,9 @@
-// Grid-foraging environment on the GPU: reset, lock-step transition and egocentric observation.
+// The two grid worlds on the GPU (foraging, warehouse): reset, lock-step transition and egocentric observation.
 //
 // One lane per env-agent, and a wavefront owns floor(64 / A) whole envs.  Every lane reads the small state of
 // its env into registers and resolves the whole transition redundantly there (targets of all agents, collisions,
-// cooperative loading, termination), so no lane waits for another; only the re-seeding of a finished episode
-// goes through LDS, executed by the env's first lane.  For the observation each lane paints its own V x V x 3
+// cooperative loading or deliveries, termination, and the re-seeding of a finished episode), so no lane waits
+// for another.  For the observation each lane paints its own V x V x 3
 // window into a wavefront-private LDS slab, which then leaves as one contiguous, 16-byte-coalesced run: the
 // slab of a wavefront is exactly a contiguous piece of the [N][A][D] output.
 #include <algorithm>

@@ -243,10 +243,7 @@ UpdateWsView carve_update_ws(const marl_config& c, void* ws, int64_t* total) {
 
 int64_t pick_k_split(int64_t K, int64_t tiles_mn) {
   // enough workgroups for ~4 per CU, each with a k range that is a multiple of the k tile
-#ifndef MARL_KSPLIT_TARGET
-#define MARL_KSPLIT_TARGET 1024
-#endif
-  int64_t want = std::max<int64_t>(1, MARL_KSPLIT_TARGET / std::max<int64_t>(1, tiles_mn));
+  int64_t want = std::max<int64_t>(1, 1024 / std::max<int64_t>(1, tiles_mn));
   int64_t per = (K + want - 1) / want;
   per = std::max<int64_t>(256, ((per + kGemmBK - 1) / kGemmBK) * kGemmBK);
   return per;
