@@ -322,9 +322,10 @@ __device__ __forceinline__ bool wh_goal(int G, int r, int c) { return r == G - 1
 
 // New episode: A + F distinct cells (robots first), then L requested shelves.  Draw j is word j % 4 of Philox
 // call j / 4 of the stream (env, episode).
-__device__ __forceinline__ void wh_reset_regs(uint32_t ag[kMaxAgents], uint32_t fd[kMaxFood], const EnvParams& p,
-                                              uint32_t env, uint32_t episode) {
-  constexpr int kMaxEnt = kMaxAgents + kMaxFood;
+template <int CA, int CF>
+__device__ __forceinline__ void wh_reset_regs(uint32_t ag[CA], uint32_t fd[CF], const EnvParams& p, uint32_t env,
+                                              uint32_t episode) {
+  constexpr int kMaxEnt = CA + CF;
   uint32_t buf[4] = {0, 0, 0, 0};
   int j = 0;
   auto draw = [&]() -> uint32_t {
@@ -353,19 +354,19 @@ __device__ __forceinline__ void wh_reset_regs(uint32_t ag[kMaxAgents], uint32_t 
       const uint32_t row = ((uint32_t)r * p.inv_g20) >> 20, col = (uint32_t)r - row * (uint32_t)p.G;
       const uint32_t cell = row | (col << 8);
 #pragma unroll
-      for (int a = 0; a < kMaxAgents; ++a)
+      for (int a = 0; a < CA; ++a)
         if (k == a) ag[a] = cell;  // nothing carried
 #pragma unroll
-      for (int f = 0; f < kMaxFood; ++f)
+      for (int f = 0; f < CF; ++f)
         if (k == p.A + f) fd[f] = cell | (1u << 16);  // idle
     }
   }
 #pragma unroll
-  for (int q = 0; q < kMaxFood; ++q) {
+  for (int q = 0; q < CF; ++q) {
     if (q < p.L) {
       int r = (int)rand_below(draw(), (uint32_t)(p.F - q));
 #pragma unroll
-      for (int f = 0; f < kMaxFood; ++f) {
+      for (int f = 0; f < CF; ++f) {
         const bool idle = f < p.F && e_lvl(fd[f]) == 1;
         if (idle && r == 0) fd[f] = (fd[f] & 0xffffu) | (2u << 16);
         r -= idle ? 1 : 0;  // after the hit r is negative and nothing else matches
@@ -378,7 +379,7 @@ __global__ void __launch_bounds__(64) wh_reset_kernel(EnvParams p, marl_env_stat
   const int n = blockIdx.x * 64 + threadIdx.x;
   if (n >= p.N) return;
   uint32_t ag[kMaxAgents], fd[kMaxFood];
-  wh_reset_regs(ag, fd, p, (uint32_t)n, 0u);
+  wh_reset_regs<kMaxAgents, kMaxFood>(ag, fd, p, (uint32_t)n, 0u);
 #pragma unroll
   for (int a = 0; a < kMaxAgents; ++a)
     if (a < p.A) {
@@ -398,11 +399,11 @@ __global__ void __launch_bounds__(64) wh_reset_kernel(EnvParams p, marl_env_stat
 }
 
 // Dynamic LDS per workgroup of NW wavefronts: float slab[NW][64 * D]
-template <int V, int NW>
+template <int V, int NW, int CA, int CF>
 __global__ void __launch_bounds__(64 * NW) wh_step_kernel(EnvParams p, marl_env_state st, const int32_t* __restrict__ actions,
                                                           float* __restrict__ obs, float* __restrict__ reward,
                                                           uint8_t* __restrict__ done, int do_step) {
-  constexpr int D = 3 * V * V, h = (V - 1) / 2, CA = kMaxAgents, CF = kMaxFood;
+  constexpr int D = 3 * V * V, h = (V - 1) / 2;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ew = 64 / p.A;
@@ -547,7 +548,7 @@ __global__ void __launch_bounds__(64 * NW) wh_step_kernel(EnvParams p, marl_env_
     }
     if (dn) {
       episode += 1;
-      wh_reset_regs(ag, fd, p, (uint32_t)n, episode);
+      wh_reset_regs<CA, CF>(ag, fd, p, (uint32_t)n, episode);
       t = 0;
     }
     if (active) {
@@ -617,13 +618,13 @@ __global__ void __launch_bounds__(64 * NW) wh_step_kernel(EnvParams p, marl_env_
   }
 }
 
-template <int V, int NW>
+template <int V, int NW, int CA, int CF>
 int32_t launch_wh_step_inst(const EnvParams& p, marl_env_state st, const int32_t* actions, float* obs, float* reward,
                             uint8_t* done, bool do_step, hipStream_t s) {
   const int ew = 64 / p.A;
   const int64_t waves = (p.N + ew - 1) / ew;
   const size_t lds = sizeof(float) * NW * 64 * 3 * V * V;
-  auto kern = wh_step_kernel<V, NW>;
+  auto kern = wh_step_kernel<V, NW, CA, CF>;
   static bool configured = false;
   if (!configured && lds > 64 * 1024) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
@@ -633,6 +634,14 @@ int32_t launch_wh_step_inst(const EnvParams& p, marl_env_state st, const int32_t
   hipLaunchKernelGGL(kern, dim3((unsigned)((waves + NW - 1) / NW)), dim3(64 * NW), lds, s, p, st, actions, obs, reward, done,
                      (int)do_step);
   return launch_status();
+}
+
+template <int V, int NW>
+int32_t launch_wh_step_caps(const EnvParams& p, marl_env_state st, const int32_t* actions, float* obs, float* reward,
+                            uint8_t* done, bool do_step, hipStream_t s) {
+  const int cap = std::max(p.A, p.F);  // every loop over entities is unrolled to the capacity
+  if (cap <= 4) return launch_wh_step_inst<V, NW, 4, 4>(p, st, actions, obs, reward, done, do_step, s);
+  return launch_wh_step_inst<V, NW, kMaxAgents, kMaxFood>(p, st, actions, obs, reward, done, do_step, s);
 }
 
 EnvParams env_params(const marl_config& c) {
@@ -694,9 +703,9 @@ int32_t launch_env_step(const marl_config& c, marl_env_state st, const int32_t* 
   TimedLaunch timed(KC_ENV_STEP, bytes, s);
   if (p.kind != 0) {
     switch (c.view) {
-      case 3: return launch_wh_step_inst<3, 4>(p, st, actions, obs, reward, done, do_step, s);
-      case 5: return launch_wh_step_inst<5, 4>(p, st, actions, obs, reward, done, do_step, s);
-      case 7: return launch_wh_step_inst<7, 2>(p, st, actions, obs, reward, done, do_step, s);
+      case 3: return launch_wh_step_caps<3, 4>(p, st, actions, obs, reward, done, do_step, s);
+      case 5: return launch_wh_step_caps<5, 4>(p, st, actions, obs, reward, done, do_step, s);
+      case 7: return launch_wh_step_caps<7, 2>(p, st, actions, obs, reward, done, do_step, s);
       default: return MARL_E_CONFIG;
     }
   }
