@@ -87,6 +87,9 @@ def main():
                     help="the workload with recurrent networks (a GRU cell in place of the second hidden layer)")
     ap.add_argument("--eval-episodes", type=int, default=0,
                     help="also time one greedy evaluation block of this many episodes per environment (reported as \"eval\")")
+    ap.add_argument("--graph", action="store_true",
+                    help="time replays of one HIP graph of the single-call training step (marl_train_step) instead of "
+                         "the three calls launched kernel by kernel: for the small, launch-bound workloads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="run one plain 1 GiB device copy before the warm-up (a kernel of known traffic for scaling PMC counters)")
@@ -111,6 +114,9 @@ def main():
             print("the recurrent networks are fp32 only", file=sys.stderr)
             sys.exit(2)
         cfg = W.scaled(cfg, recurrent=1, name=cfg["name"] + "+gru")
+    if args.graph and args.recurrent:
+        print("--graph covers the feed-forward training step only", file=sys.stderr)
+        sys.exit(2)
     sizes = M.query_sizes(cfg)
     dev = lambda x: torch.from_numpy(np.ascontiguousarray(x)).cuda()
     state = M.EnvState(cfg)
@@ -146,14 +152,30 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    if args.graph:
+        # one ordinary call (it also sets kernel attributes), then the same call captured once and replayed: the step
+        # offset of the sampling keys and Adam's step count live in device memory and advance there
+        counters = M.alloc_counters()
+        one_call = lambda: M.train_step(cfg, state, params, traj, adam_m, adam_v, counters, perm, stats, ws_r, ws_u)
+        one_call()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            one_call()
+        timed_step = graph.replay
+        it[0] = 1
+    else:
+        timed_step = step
     for _ in range(args.warmup):
-        step()
+        timed_step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        timed_step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    if args.graph:
+        it[0] += args.warmup + args.steps
     # the same K steps once more with per-launch event timers on, for the per-kernel figures (the events cost a
     # few microseconds per launch, so they stay out of the headline timing above)
     M.timing_enable(True)
@@ -197,7 +219,7 @@ def main():
         "vs_baseline": None, "dtype": "bf16" if cfg["precision"] == 1 else "f32", "data": "synthetic",
         "config": {"workload": cfg["name"], "config_index": args.config, "n_envs": cfg["n_envs"],
                    "n_agents": cfg["n_agents"], "rollout_len": T, "epochs": E, "minibatches": Mb,
-                   "env_agent_steps_per_step": S,
+                   "env_agent_steps_per_step": S, "launch": "hip_graph_replay" if args.graph else "per_kernel",
                    "mlp_gemm_tflop_per_step": gemm_flops_per_step(cfg, W) / 1e12},
         "roofline": roofline,
         "roofline_all": lines,

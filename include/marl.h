@@ -200,6 +200,26 @@ int32_t marl_ppo_update(const marl_config* cfg, marl_traj traj, float* params, f
                         int64_t adam_step0, const int32_t* perm, float* stats, float* grad_dump, void* workspace,
                         void* stream);
 
+/* Counters of a training run kept in device memory (caller-owned, 16 bytes, zero before the first step): the
+ * sampling-key offset of the next rollout and the number of optimiser steps taken so far. */
+typedef struct marl_counters {
+  uint64_t step;
+  int64_t adam_step;
+} marl_counters;
+
+/* One whole training iteration (Fig. 2: rollout -> loss -> gradient -> new parameters) as one call: marl_rollout
+ * with step_offset = counters->step, marl_compute_gae, marl_ppo_update with adam_step0 = counters->adam_step, then
+ * counters->step += rollout_len and counters->adam_step += n_epochs * n_minibatches, all on the device.  The
+ * sequence of launches and their arguments do not depend on the values of the counters, the call makes no
+ * allocation, no host-device copy and no synchronisation, so after one ordinary call (which sets kernel attributes)
+ * a capture of it into a HIP graph can be replayed for every following iteration; the caller may rewrite the
+ * contents of `perm` between replays.  Results equal those of the three separate calls, except that Adam's bias
+ * corrections 1 - beta^k are evaluated in fp64 on the device instead of on the host.  `counters` is device memory;
+ * the other arguments are those of the three calls.  Feed-forward networks only (MARL_E_CONFIG otherwise). */
+int32_t marl_train_step(const marl_config* cfg, marl_env_state st, float* params, marl_traj traj, float* adam_m,
+                        float* adam_v, marl_counters* counters, const int32_t* perm, float* stats,
+                        void* rollout_workspace, void* update_workspace, void* stream);
+
 /* Recurrent IPPO / MAPPO (Section 2 and Section 4 list them beside the feed-forward systems).  As marl_rollout, with
  * the hidden states carried from rec.h*0 through the T steps and left in rec.h*1.  workspace: rollout_workspace_bytes
  * of the recurrent configuration.  MARL_E_CONFIG unless cfg->recurrent = 1. */

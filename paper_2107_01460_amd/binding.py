@@ -52,7 +52,7 @@ class RecStateC(C.Structure):
 
 
 EXPORTS = ("marl_query_sizes", "marl_env_reset", "marl_observe", "marl_env_step", "marl_policy_forward",
-           "marl_sample_actions", "marl_rollout", "marl_compute_gae", "marl_ppo_update", "marl_evaluate", "marl_rollout_recurrent", "marl_ppo_update_recurrent",
+           "marl_sample_actions", "marl_rollout", "marl_compute_gae", "marl_ppo_update", "marl_train_step", "marl_evaluate", "marl_rollout_recurrent", "marl_ppo_update_recurrent",
            "marl_timing_enable",
            "marl_timing_read", "marl_status_string")
 
@@ -77,6 +77,7 @@ def lib():
         L.marl_rollout.argtypes = [cp, EnvStateC, vp, TrajC, C.c_uint64, vp, vp, vp, vp]
         L.marl_compute_gae.argtypes = [cp, TrajC, vp]
         L.marl_ppo_update.argtypes = [cp, TrajC, vp, vp, vp, C.c_int64, vp, vp, vp, vp, vp]
+        L.marl_train_step.argtypes = [cp, EnvStateC, vp, TrajC, vp, vp, vp, vp, vp, vp, vp, vp]
         L.marl_evaluate.argtypes = [cp, EnvStateC, vp, C.c_int32, EvalStatsC, vp, vp]
         L.marl_rollout_recurrent.argtypes = [cp, EnvStateC, vp, TrajC, RecStateC, C.c_uint64, vp, vp, vp, vp]
         L.marl_ppo_update_recurrent.argtypes = [cp, TrajC, RecStateC, vp, vp, vp, C.c_int64, vp, vp, vp, vp, vp]
@@ -268,6 +269,18 @@ def ppo_update_recurrent(cfg, traj, rec, params, adam_m, adam_v, adam_step0, per
     _check(lib().marl_ppo_update_recurrent(C.byref(make_config(cfg)), traj.c(), rec.c(), _ptr(params), _ptr(adam_m),
                                            _ptr(adam_v), int(adam_step0), _ptr(perm), _ptr(stats), _ptr(grad_dump),
                                            _ptr(workspace), _stream(stream)))
+
+
+def alloc_counters():
+    """Device memory of one marl_counters (step, adam_step), zeroed: a [2] int64 tensor."""
+    return torch.zeros(2, dtype=torch.int64, device="cuda")
+
+
+def train_step(cfg, state, params, traj, adam_m, adam_v, counters, perm, stats, rollout_workspace, update_workspace,
+               stream=None):
+    _check(lib().marl_train_step(C.byref(make_config(cfg)), state.c(), _ptr(params), traj.c(), _ptr(adam_m),
+                                 _ptr(adam_v), _ptr(counters), _ptr(perm), _ptr(stats), _ptr(rollout_workspace),
+                                 _ptr(update_workspace), _stream(stream)))
 
 
 KERNEL_CLASSES = {"gemm_nn": 0, "gemm_nt": 1, "gemm_tn": 2, "env_step": 3, "gae": 4, "fused_train": 5}

@@ -224,6 +224,27 @@ int32_t marl_ppo_update(const marl_config* cfg, marl_traj traj, float* params, f
                            (hipStream_t)stream);
 }
 
+int32_t marl_train_step(const marl_config* cfg, marl_env_state st, float* params, marl_traj traj, float* adam_m,
+                        float* adam_v, marl_counters* counters, const int32_t* perm, float* stats,
+                        void* rollout_workspace, void* update_workspace, void* stream) {
+  int32_t rc = validate_config(cfg);
+  if (rc != MARL_OK) return rc;
+  if (cfg->recurrent) return MARL_E_CONFIG;
+  if ((rc = check_state(st)) != MARL_OK) return rc;
+  if ((rc = check_traj(traj, true)) != MARL_OK) return rc;
+  MARL_REQUIRE_PTR(params); MARL_REQUIRE_PTR(adam_m); MARL_REQUIRE_PTR(adam_v); MARL_REQUIRE_PTR(stats);
+  MARL_REQUIRE_PTR(counters); MARL_REQUIRE_PTR(rollout_workspace); MARL_REQUIRE_PTR(update_workspace);
+  MARL_OPTIONAL_PTR(perm);
+  hipStream_t s = (hipStream_t)stream;
+  if ((rc = launch_rollout(*cfg, st, params, traj, 0, nullptr, nullptr, rollout_workspace, s, &counters->step)) != MARL_OK)
+    return rc;
+  if ((rc = launch_gae(*cfg, traj, s)) != MARL_OK) return rc;
+  if ((rc = launch_ppo_update(*cfg, traj, params, adam_m, adam_v, 0, perm, stats, nullptr, update_workspace, s,
+                              &counters->adam_step)) != MARL_OK)
+    return rc;
+  return launch_advance_counters(counters, (uint64_t)cfg->rollout_len, (int64_t)cfg->n_epochs * cfg->n_minibatches, s);
+}
+
 static int32_t check_rec(const marl_rec_state& r) {
   MARL_REQUIRE_PTR(r.ha0); MARL_REQUIRE_PTR(r.hc0); MARL_REQUIRE_PTR(r.ha1); MARL_REQUIRE_PTR(r.hc1);
   return MARL_OK;

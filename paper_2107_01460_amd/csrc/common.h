@@ -196,7 +196,7 @@ int32_t launch_sample(const marl_config& c, const float* logits, const float* un
                       int64_t n, uint64_t step, int32_t* action, int32_t* sampled, float* logp, hipStream_t s);
 int32_t launch_rollout(const marl_config& c, marl_env_state st, const float* params, marl_traj tr,
                        uint64_t step_offset, const int32_t* forced_actions, const float* forced_uniforms,
-                       void* workspace, hipStream_t s);
+                       void* workspace, hipStream_t s, const uint64_t* step_base = nullptr);
 int32_t launch_gae(const marl_config& c, marl_traj tr, hipStream_t s);
 int64_t eval_workspace_bytes(const marl_config& c);
 int64_t rec_rollout_workspace_bytes(const marl_config& c);
@@ -211,6 +211,9 @@ int32_t launch_evaluate(const marl_config& c, marl_env_state st, const float* pa
                         marl_eval_stats out, void* workspace, hipStream_t s);
 int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, float* adam_m, float* adam_v,
                           int64_t adam_step0, const int32_t* perm, float* stats, float* grad_dump, void* workspace,
-                          hipStream_t s);
+                          hipStream_t s, const int64_t* adam_step_base = nullptr);
+// step_base / adam_step_base (nullable, device memory): counters added on the device to step_offset / adam_step0, so
+// that the launch sequence of a call does not depend on how many steps came before it.
+int32_t launch_advance_counters(marl_counters* counters, uint64_t steps, int64_t adam_steps, hipStream_t s);
 
 }  // namespace marl

@@ -15,6 +15,7 @@ struct SampleArgs {
   float* logp;            // [S]
   uint64_t step;
   uint32_t k0, k1;
+  const uint64_t* step_base;  // nullable: a device-resident base that is added to `step`
 };
 
 struct HeadLds {
@@ -101,7 +102,7 @@ __device__ __forceinline__ void sample_and_store(const float lg[kActions], int64
 #pragma unroll
     for (int k = 0; k < kActions; ++k) u[k] = a.uniforms[s * kActions + k];
   } else {
-    sample_uniforms(a.step, (uint32_t)s, a.k0, a.k1, u);
+    sample_uniforms(a.step + (a.step_base != nullptr ? *a.step_base : 0), (uint32_t)s, a.k0, a.k1, u);
   }
   int act = gumbel_argmax(lg, u);
   if (a.sampled) a.sampled[s] = act;

@@ -223,7 +223,7 @@ int32_t launch_sample(const marl_config& c, const float* logits, const float* un
 
 int32_t launch_rollout(const marl_config& c, marl_env_state st, const float* params, marl_traj tr,
                        uint64_t step_offset, const int32_t* forced_actions, const float* forced_uniforms,
-                       void* workspace, hipStream_t s) {
+                       void* workspace, hipStream_t s, const uint64_t* step_base) {
   const Dims d = dims_of(c);
   const RolloutWsView w = carve_rollout_ws(c, d.N, workspace, nullptr);
   const float* eff = effective_params(c, params, w.eff_params, s);
@@ -238,6 +238,7 @@ int32_t launch_rollout(const marl_config& c, marl_env_state st, const float* par
     a.sampled = tr.sampled ? tr.sampled + (int64_t)t * NA : nullptr;
     a.logp = tr.logp + (int64_t)t * NA;
     a.step = step_offset + (uint64_t)t;
+    a.step_base = step_base;
     a.k0 = (uint32_t)(c.seed & 0xffffffffu);
     a.k1 = (uint32_t)(c.seed >> 32);
     rc = forward_rows(c, eff, tr.obs + (int64_t)t * slab, d.N, w, true,

@@ -314,6 +314,8 @@ __global__ void __launch_bounds__(256) grad_norm_kernel(const float* __restrict_
 
 struct AdamArgs {
   float lr, b1, b2, eps, bc1, bc2, max_norm, ent_coef, vf_coef;
+  const int64_t* k_base;  // nullable: device-resident count of optimiser steps taken before this call; then the bias
+  int k_local;            // corrections are computed on the device for step *k_base + k_local instead of bc1 / bc2
 };
 
 __global__ void __launch_bounds__(256) adam_kernel(float* __restrict__ params, float* __restrict__ m,
@@ -323,6 +325,11 @@ __global__ void __launch_bounds__(256) adam_kernel(float* __restrict__ params, f
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const float norm = sqrtf(sc->acc[5]);
   const float scale = a.max_norm > 0.f ? a.max_norm / fmaxf(norm, a.max_norm) : 1.0f;
+  if (a.k_base != nullptr) {
+    const double k = (double)(*a.k_base + a.k_local);
+    a.bc1 = (float)(1.0 - pow((double)a.b1, k));
+    a.bc2 = (float)(1.0 - pow((double)a.b2, k));
+  }
   if (i < P) {
     const float g = grad[i] * scale;
     const float mi = a.b1 * m[i] + (1.0f - a.b1) * g;

@@ -330,9 +330,23 @@ int64_t update_workspace_bytes(const marl_config& c) {
   return total;
 }
 
+namespace {
+__global__ void advance_counters_kernel(marl_counters* counters, uint64_t steps, int64_t adam_steps) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    counters->step += steps;
+    counters->adam_step += adam_steps;
+  }
+}
+}  // namespace
+
+int32_t launch_advance_counters(marl_counters* counters, uint64_t steps, int64_t adam_steps, hipStream_t s) {
+  hipLaunchKernelGGL(advance_counters_kernel, dim3(1), dim3(64), 0, s, counters, steps, adam_steps);
+  return launch_status();
+}
+
 int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, float* adam_m, float* adam_v,
                           int64_t adam_step0, const int32_t* perm, float* stats, float* grad_dump, void* workspace,
-                          hipStream_t s) {
+                          hipStream_t s, const int64_t* adam_step_base) {
   const Dims d = dims_of(c);
   const UpdateWsView w = carve_update_ws(c, workspace, nullptr);
   const int64_t R = (int64_t)d.T * d.N, rows_mb = R / c.n_minibatches;
@@ -432,7 +446,9 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
       hipLaunchKernelGGL(grad_norm_kernel, dim3((unsigned)std::min<int64_t>(256, (d.P + 255) / 256)), dim3(256), 0, s,
                          w.grad, d.P, w.sc);
       ++k;
-      AdamArgs a;
+      AdamArgs a{};
+      a.k_base = adam_step_base;
+      a.k_local = (int)k;
       a.lr = c.lr; a.b1 = c.beta1; a.b2 = c.beta2; a.eps = c.adam_eps;
       a.bc1 = (float)(1.0 - std::pow((double)c.beta1, (double)k));
       a.bc2 = (float)(1.0 - std::pow((double)c.beta2, (double)k));

@@ -738,7 +738,7 @@ int32_t launch_ppo_update_recurrent(const marl_config& c, marl_traj tr, marl_rec
       hipLaunchKernelGGL(grad_norm_kernel, dim3((unsigned)std::min<int64_t>(256, (d.P + 255) / 256)), dim3(256), 0, s,
                          w.grad, d.P, w.sc);
       ++k;
-      AdamArgs a;
+      AdamArgs a{};
       a.lr = c.lr; a.b1 = c.beta1; a.b2 = c.beta2; a.eps = c.adam_eps;
       a.bc1 = (float)(1.0 - std::pow((double)c.beta1, (double)k));
       a.bc2 = (float)(1.0 - std::pow((double)c.beta2, (double)k));

@@ -120,6 +120,11 @@ def test_null_and_misaligned_pointers_rejected_before_launch(M):
     assert L.marl_ppo_update_recurrent(C.byref(rcfg), traj, rs, good, good + 4, good, 0, None, good, None, good, None) == -2
     bad = M.make_config(W.scaled(W.CONFIGS[0], recurrent=1, n_minibatches=3))     # 64 environments do not split in 3
     assert L.marl_ppo_update_recurrent(C.byref(bad), traj, rs, good, good, good, 0, None, good, None, good, None) == -3
+    # the single-call training step: counters and both workspaces are required, feed-forward networks only
+    assert L.marl_train_step(C.byref(cfg), ok_state, good, traj, good, good, None, None, good, good, good, None) == -1
+    assert L.marl_train_step(C.byref(cfg), ok_state, good, traj, good, good, good, None, good, good, None, None) == -1
+    assert L.marl_train_step(C.byref(cfg), ok_state, good, traj, good, good, good + 8, None, good, good, good, None) == -2
+    assert L.marl_train_step(C.byref(rcfg), ok_state, good, traj, good, good, good, None, good, good, good, None) == -3
     assert L.marl_query_sizes(None, None) == -1
     assert M.status_string(0) == "ok" and "null" in M.status_string(-1)
     d, n, w = C.c_double(), C.c_int64(), C.c_double()
