@@ -9,3 +9,4 @@ from .binding import (  # noqa: F401
     policy_forward, sample_actions, rollout, compute_gae, ppo_update, status_string, alloc_workspace,
     timing_enable, timing_read, KERNEL_CLASSES, EvalStats, evaluate, RecState, rollout_recurrent, ppo_update_recurrent, train_step, alloc_counters,
 )
+from .trainer import Trainer  # noqa: F401,E402
