@@ -8,6 +8,7 @@
 #include "fused_forward.h"
 #include "fused_train.h"
 #include "gemm.h"
+#include "wreg_gemm.h"
 #include "heads.h"
 #include "ppo_common.h"
 
@@ -259,21 +260,33 @@ void mlp_backward(const RowSrc& X, int64_t S, int Din, int H, const float* W2, c
     dim3 grid((unsigned)((S + rpb - 1) / rpb), (unsigned)((H + cb - 1) / cb));
     hipLaunchKernelGGL(dz2_kernel<NOUT>, grid, dim3(256), 0, s, h2, dl, W3, (float*)nullptr, S, H, cb, rpb, (int)bf16);
   }
-  {  // gW2 += h1^T dz2
+  {  // gW2 += h1^T dz2, gb2 += column sums
     GemmArgs g{};
     g.A = RowSrc{h1, H, nullptr, 1, S}; g.B = h2; g.ldb = H; g.C = gW2; g.ldc = H;
     g.M = H; g.N = H; g.K = S; g.colsum = gb2;
     g.k_per_split = pick_k_split(S, ((H + 127) / 128) * ((H + 127) / 128));
     launch_gemm<GEMM_TN, EPI_ATOMIC_ADD>(g, s);
   }
-  {  // dz1 = (dz2 W2^T) * (1 - h1^2), gb1 += column sums
+  const RowSrc dz2_rows{h2, H, nullptr, 1, S};
+  if (!bf16 && wreg_gemm_supported<WREG_DTANH>(dz2_rows, H, H)) {
+    // dz1 = (dz2 W2^T) * (1 - h1^2) with W2 resident in registers
+    WregArgs g{};
+    g.A = dz2_rows; g.S = S; g.Kin = H; g.B = W2; g.ldb = H; g.b_kcont = 1; g.C = dz1; g.aux = h1;
+    TimedLaunch timed(KC_GEMM_NT, 2.0 * (double)S * H * H, s);
+    launch_wreg_gemm<WREG_DTANH>(g, s);
+  } else {  // dz1 = (dz2 W2^T) * (1 - h1^2), gb1 += column sums
     GemmArgs g{};
     g.A = RowSrc{h2, H, nullptr, 1, S}; g.B = W2; g.ldb = H; g.C = dz1; g.ldc = H;
     g.aux_mat = h1; g.ldaux = H; g.colsum = nullptr;
     g.M = S; g.N = H; g.K = H; g.round_bf16 = bf16;
     launch_gemm<GEMM_NT, EPI_DTANH>(g, s);
   }
-  {  // gW1 += X^T dz1
+  if (!bf16 && wacc_gemm_supported(X, Din, H)) {  // gW1 += X^T dz1, gb1 += column sums, the gradient resident in registers
+    WaccArgs g{};
+    g.A = X; g.S = S; g.B = dz1; g.C = gW1; g.colsum = gb1;
+    TimedLaunch timed(KC_GEMM_TN, 2.0 * (double)S * Din * H, s);
+    launch_wacc_gemm(g, Din, s);
+  } else {  // gW1 += X^T dz1
     GemmArgs g{};
     g.A = X; g.B = dz1; g.ldb = H; g.C = gW1; g.ldc = H;
     g.M = Din; g.N = H; g.K = S; g.colsum = gb1;

@@ -1,0 +1,441 @@
+// Row-streaming fp32 MFMA products with the weight matrix resident in registers, for the 256-wide layers.
+//
+//   C[m][n] = epilogue( sum_k A[m][k] * B(k, n) ),   m < S (hundreds of thousands of rows), n < 256, k < K <= 304
+//
+// A 256 x 256 fp32 weight matrix is 256 KB: half of the register file of one compute unit.  A workgroup of four
+// wavefronts (one per SIMD, up to 512 registers per lane) therefore keeps the whole matrix in registers for its
+// lifetime: wavefront w holds columns 64 w .. 64 w + 63 in the lane layout the matrix cores read their second operand
+// in.  The workgroup is persistent over tiles of 64 rows; a tile of A travels global -> registers -> LDS while the
+// previous one is multiplied (two LDS stages), every wavefront reads the same A fragments from LDS and multiplies
+// them into its own 64 columns (2 x 2 accumulator tiles of 32 x 32).  Nothing but A and C moves per tile: no weight
+// traffic at all, one barrier per tile.
+//
+// Within a group of eight k values the lower half-wavefront supplies k = 0..3 and the upper half k = 4..7 to four
+// consecutive v_mfma_f32_32x32x2_f32 steps, so that a lane's four A values are one 16-byte LDS read.
+#pragma once
+#include "gemm.h"
+
+namespace marl {
+
+enum WregEpi {
+  WREG_BIAS_TANH = 0,  // C = tanh(acc + bias[n])
+  WREG_DTANH = 1       // C = acc * (1 - aux[m][n]^2)
+};
+
+struct WregArgs {
+  RowSrc A;        // S rows of Kin floats (optionally gathered); rows must be 16-byte aligned, Kin % 4 == 0
+  int64_t S;
+  int Kin;         // columns of A actually present (<= K; the rest of the contraction is zero)
+  const float* B;  // b_kcont ? [256][ldb] with B(k, n) = B[n * ldb + k] : [Kin][ldb] with B(k, n) = B[k * ldb + n]
+  int ldb;
+  int b_kcont;
+  float* C;           // [S][256]
+  const float* bias;  // WREG_BIAS_TANH: [256]
+  const float* aux;   // WREG_DTANH: [S][256]
+};
+
+constexpr int kWregBM = 64;   // rows per tile
+constexpr int kWregN = 256;   // columns (4 wavefronts x 64)
+
+template <int K>
+struct WregShape {
+  static constexpr int P = K + 4;                      // LDS row pitch: 4 * odd, conflict-free 16-byte row-per-lane reads
+  static constexpr int VPR = K / 4;                    // 16-byte vectors per row
+  static constexpr int TOT = kWregBM * VPR / 256;      // vectors a thread stages per tile
+  static constexpr int NB = 4;                         // staging batches per tile
+  static constexpr int PER = (TOT + NB - 1) / NB;      // vectors per batch
+  static constexpr int GROUPS = K / 8;
+  static constexpr size_t lds_bytes = sizeof(float) * 2 * kWregBM * P + sizeof(int64_t) * 2 * kWregBM;
+  static_assert(K % 16 == 0 && (P / 4) % 2 == 1, "K a multiple of 16 with an odd K/4 + 1");
+};
+
+template <int K, int EPI>
+__global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a) {
+  using Sh = WregShape<K>;
+  constexpr int P = Sh::P, VPR = Sh::VPR, TOT = Sh::TOT, NB = Sh::NB, PER = Sh::PER, GROUPS = Sh::GROUPS, BM = kWregBM;
+  extern __shared__ __attribute__((aligned(16))) unsigned char wreg_smem[];
+  float* const As = reinterpret_cast<float*>(wreg_smem);                       // [2][BM][P]
+  int64_t* const ent = reinterpret_cast<int64_t*>(As + 2 * BM * P);            // [2][BM] offsets (floats) of a tile's rows
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lo = lane & 31, hi = lane >> 5;
+  const int64_t ntiles = (a.S + BM - 1) / BM;
+
+  // ---- the weights: breg[g][j][jn] = B(8 g + 4 hi + j, 64 wave + 32 jn + lo)
+  float breg[GROUPS][4][2];
+#pragma unroll
+  for (int g = 0; g < GROUPS; ++g)
+#pragma unroll
+    for (int jn = 0; jn < 2; ++jn) {
+      const int n = 64 * wave + 32 * jn + lo;
+      const int k = 8 * g + 4 * hi;
+      if (a.b_kcont) {
+        const float4 v = (k < a.Kin) ? *reinterpret_cast<const float4*>(a.B + (int64_t)n * a.ldb + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+        breg[g][0][jn] = v.x; breg[g][1][jn] = v.y; breg[g][2][jn] = v.z; breg[g][3][jn] = v.w;
+      } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) breg[g][j][jn] = (k + j < a.Kin) ? a.B[(int64_t)(k + j) * a.ldb + n] : 0.f;
+      }
+    }
+
+  // ---- staging of a tile of A: vector f = tid + 256 p of the tile is (row f / VPR, columns 4 (f % VPR) ..)
+  auto row_of = [&](int p) { return (tid + 256 * p) / VPR; };
+  auto col_of = [&](int p) { return 4 * ((tid + 256 * p) % VPR); };
+  float4 stg[PER];
+  auto fetch_batch = [&](int64_t tile, int slot, int b) {
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+      const int p = b * PER + q;
+      if (p < TOT) {
+        const int r = row_of(p), c = col_of(p);
+        const float* src = a.A.base + ent[slot * BM + r];
+        stg[q] = (c < a.Kin) ? *reinterpret_cast<const float4*>(src + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+    }
+  };
+  auto store_batch = [&](int stage, int b) {
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+      const int p = b * PER + q;
+      if (p < TOT) *reinterpret_cast<float4*>(&As[(stage * BM + row_of(p)) * P + col_of(p)]) = stg[q];
+    }
+  };
+  // offset of row tid of a tile (threads tid < BM); rows past the end repeat the last row, whose results are never stored
+  auto load_entries = [&](int64_t tile) -> int64_t {
+    if (tid >= BM || tile >= ntiles) return 0;
+    const int64_t row = min(tile * BM + tid, a.S - 1);
+    return a.A.ptr(row) - a.A.base;
+  };
+
+  // ---- prologue: entries of the first two tiles, then the first tile itself
+  int64_t tile = blockIdx.x;
+  if (tile >= ntiles) return;  // uniform per workgroup
+  {
+    const int64_t e0 = load_entries(tile), e1 = load_entries(tile + gridDim.x);
+    if (tid < BM) {
+      ent[0 * BM + tid] = e0;
+      ent[1 * BM + tid] = e1;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      fetch_batch(tile, 0, b);
+      store_batch(0, b);
+    }
+    __syncthreads();
+  }
+
+  int it = 0;
+  for (; tile < ntiles; tile += gridDim.x, ++it) {
+    const int stage = it & 1;
+    const int64_t next = tile + gridDim.x;
+    const bool has_next = next < ntiles;  // uniform
+    const int64_t e2 = load_entries(next + gridDim.x);  // consumed at the end of this tile
+    const float* const At = As + stage * BM * P;
+    const int64_t m0 = tile * BM;
+    const int rows_left = (int)min((int64_t)BM, a.S - m0);
+
+    // what the epilogue needs from memory, requested before the products start
+    float auxv[2][2][16];
+    if (EPI == WREG_DTANH) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int jn = 0; jn < 2; ++jn)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int m = 32 * i + 8 * (r / 4) + 4 * hi + (r % 4);
+            const int64_t row = min(m0 + m, a.S - 1);
+            auxv[i][jn][r] = a.aux[row * kWregN + 64 * wave + 32 * jn + lo];
+          }
+    }
+
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int jn = 0; jn < 2; ++jn)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][jn][r] = 0.f;
+
+    if (has_next) fetch_batch(next, stage ^ 1, 0);
+#pragma unroll
+    for (int g = 0; g < GROUPS; ++g) {
+      const float4 a0 = *reinterpret_cast<const float4*>(&At[lo * P + 8 * g + 4 * hi]);
+      const float4 a1 = *reinterpret_cast<const float4*>(&At[(32 + lo) * P + 8 * g + 4 * hi]);
+      const float af[2][4] = {{a0.x, a0.y, a0.z, a0.w}, {a1.x, a1.y, a1.z, a1.w}};
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int jn = 0; jn < 2; ++jn)
+            acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i][j], breg[g][j][jn], acc[i][jn], 0, 0, 0);
+      // the next tile moves in NB batches spread over the products: registers -> the other LDS stage, then the next request
+#pragma unroll
+      for (int b = 0; b < NB; ++b)
+        if (g == ((b + 1) * GROUPS) / NB - 1 && has_next) {
+          store_batch(stage ^ 1, b);
+          if (b + 1 < NB) fetch_batch(next, stage ^ 1, b + 1);
+        }
+    }
+
+    // ---- epilogue (accumulator register r of a lane holds C[8 (r/4) + 4 hi + r%4][lo] of its 32 x 32 tile)
+#pragma unroll
+    for (int jn = 0; jn < 2; ++jn) {
+      const int n = 64 * wave + 32 * jn + lo;
+      const float bias = EPI == WREG_BIAS_TANH ? a.bias[n] : 0.f;
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int m = 32 * i + 8 * (r / 4) + 4 * hi + (r % 4);
+          float v = acc[i][jn][r];
+          if (EPI == WREG_BIAS_TANH) {
+            v = tanh_f32(v + bias);
+          } else {
+            const float h = auxv[i][jn][r];
+            v = v * (1.0f - h * h);
+          }
+          if (m < rows_left) a.C[(m0 + m) * kWregN + n] = v;
+        }
+    }
+    if (tid < BM) ent[stage * BM + tid] = e2;  // this tile's entries were last read while the previous tile was multiplied
+    __syncthreads();  // the other stage is complete; this one may be overwritten
+  }
+}
+
+template <int K, int EPI>
+inline int32_t launch_wreg_gemm_inst(const WregArgs& a, hipStream_t s) {
+  auto kern = wreg_gemm_kernel<K, EPI>;
+  static bool configured = false;  // per instantiation
+  if (!configured) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+      return MARL_E_LAUNCH;
+    configured = true;
+  }
+  const int64_t tiles = (a.S + kWregBM - 1) / kWregBM;
+  hipLaunchKernelGGL(kern, dim3((unsigned)std::min<int64_t>(tiles, 256)), dim3(256), WregShape<K>::lds_bytes, s, a);
+  return MARL_OK;
+}
+
+// Shapes this kernel serves: 256 output columns, 16-byte aligned rows, a contraction of at most 304 (256 with the
+// WREG_DTANH epilogue, whose prefetched operand needs the registers the longer contraction would take).
+template <int EPI>
+inline bool wreg_gemm_supported(const RowSrc& A, int Kin, int N) {
+  return N == kWregN && Kin <= (EPI == WREG_DTANH ? 256 : 304) && Kin % 4 == 0 && A.ld % 4 == 0 && aligned16(A.base);
+}
+
+template <int EPI>
+inline int32_t launch_wreg_gemm(const WregArgs& a, hipStream_t s) {
+  if (EPI == WREG_DTANH || a.Kin <= 256) return launch_wreg_gemm_inst<256, EPI>(a, s);
+  return launch_wreg_gemm_inst<EPI == WREG_DTANH ? 256 : 304, EPI>(a, s);
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// The transposed product of the backward pass with the OUTPUT resident in registers:
+//
+//   C[m][n] += sum_s A[s][m] * B[s][n],   m < MIN <= 320, n < 256, s < S (hundreds of thousands of rows)
+//
+// A weight gradient of 320 x 256 floats fits the accumulators of one workgroup (wavefront w owns columns
+// 64 w .. 64 w + 63 of all rows: MT x 2 tiles of 32 x 32, 32 MT registers per lane).  The workgroup is persistent over
+// tiles of 32 rows of A and B, which travel global -> registers -> LDS (two stages) while the previous tile is
+// multiplied; at the end every workgroup adds its partial sum to C with fp32 atomics.  Column sums of B (the bias
+// gradient) ride along in the staging registers.
+// ---------------------------------------------------------------------------------------------------------------
+struct WaccArgs {
+  RowSrc A;       // S rows of MIN floats (optionally gathered); rows 16-byte aligned
+  int64_t S;
+  const float* B;  // [S][256]
+  float* C;        // [MIN][256], accumulated
+  float* colsum;   // nullable [256]: column sums of B, accumulated
+};
+
+template <int MIN, int WM>
+struct WaccShape {
+  static constexpr int NT = 256 * WM;           // threads: WM x 4 wavefronts
+  static constexpr int BS = 32;                 // rows (the contraction) per tile
+  static constexpr int MT = (MIN + 31) / 32;    // 32-row tiles of the output
+  static constexpr int MTW = MT / WM;           // ... of one wavefront
+  static constexpr int PA = 32 * MT + 4;        // pitch of the A tile (covers the padded output rows)
+  static constexpr int PB = kWregN + 4;
+  static constexpr int VA = MIN / 4;            // 16-byte vectors per row of A
+  static constexpr int TOT_A = (BS * VA + NT - 1) / NT;
+  static constexpr int TOT_B = BS * (kWregN / 4) / NT;
+  static constexpr size_t lds_bytes = sizeof(float) * 2 * BS * (PA + PB) + sizeof(int64_t) * 2 * BS;
+  static_assert(MIN % 4 == 0 && MT % WM == 0 && MTW * 32 <= 256, "whole 16-byte vectors; the accumulators of a wavefront fit its registers");
+};
+
+// WM = 1: four wavefronts, each all MT row tiles of its 64 columns (up to 256 accumulator registers, one wavefront
+// per SIMD).  WM = 2: eight wavefronts, each half of the row tiles (two wavefronts per SIMD, 256 registers each).
+template <int MIN, int WM>
+__global__ void __launch_bounds__(256 * WM, 1) wacc_gemm_kernel(WaccArgs a) {
+  using Sh = WaccShape<MIN, WM>;
+  constexpr int NT = Sh::NT, BS = Sh::BS, MTW = Sh::MTW, PA = Sh::PA, PB = Sh::PB, VA = Sh::VA, TOT_A = Sh::TOT_A, TOT_B = Sh::TOT_B;
+  extern __shared__ __attribute__((aligned(16))) unsigned char wreg_smem[];
+  float* const As = reinterpret_cast<float*>(wreg_smem);             // [2][BS][PA]
+  float* const Bs = As + 2 * BS * PA;                                 // [2][BS][PB]
+  int64_t* const ent = reinterpret_cast<int64_t*>(Bs + 2 * BS * PB);  // [2][BS] offsets (floats) of a tile's rows of A
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wn = wave & 3, wm = wave >> 2;
+  const int lo = lane & 31, hi = lane >> 5;
+  const int64_t ntiles = (a.S + BS - 1) / BS;
+
+  // columns of the A tiles past MIN are never staged: they feed output rows that are never stored, zero all the same
+  for (int i = tid; i < 2 * BS * PA; i += NT) As[i] = 0.f;
+
+  // The next tile moves in two halves through one set of registers: its rows of A are requested when a tile's
+  // products start and stored half-way, its rows of B are requested then and stored at the end.
+  constexpr int TOT_MAX = TOT_A > TOT_B ? TOT_A : TOT_B;
+  float4 stg[TOT_MAX];
+  float4 bsum = make_float4(0.f, 0.f, 0.f, 0.f);
+  auto fetch_a = [&](int64_t tile, int slot) {
+#pragma unroll
+    for (int q = 0; q < TOT_A; ++q) {
+      const int f = tid + NT * q;
+      if (f < BS * VA) {
+        const int r = f / VA, c = 4 * (f % VA);
+        const bool live = tile * BS + r < a.S;
+        stg[q] = live ? *reinterpret_cast<const float4*>(a.A.base + ent[slot * BS + r] + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+    }
+  };
+  auto store_a = [&](int stage) {
+#pragma unroll
+    for (int q = 0; q < TOT_A; ++q) {
+      const int f = tid + NT * q;
+      if (f < BS * VA) *reinterpret_cast<float4*>(&As[(stage * BS + f / VA) * PA + 4 * (f % VA)]) = stg[q];
+    }
+  };
+  auto fetch_b = [&](int64_t tile) {
+#pragma unroll
+    for (int q = 0; q < TOT_B; ++q) {
+      const int f = tid + NT * q;
+      const int r = f / (kWregN / 4), c = 4 * (f % (kWregN / 4));
+      const int64_t row = tile * BS + r;
+      stg[q] = row < a.S ? *reinterpret_cast<const float4*>(a.B + row * kWregN + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  };
+  auto store_b = [&](int stage) {
+#pragma unroll
+    for (int q = 0; q < TOT_B; ++q) {
+      const int f = tid + NT * q;
+      *reinterpret_cast<float4*>(&Bs[(stage * BS + f / (kWregN / 4)) * PB + 4 * (f % (kWregN / 4))]) = stg[q];
+      bsum.x += stg[q].x; bsum.y += stg[q].y; bsum.z += stg[q].z; bsum.w += stg[q].w;  // this thread's columns: 4 (tid % 64) ..
+    }
+  };
+  auto load_entries = [&](int64_t tile) -> int64_t {
+    if (tid >= BS || tile >= ntiles) return 0;
+    const int64_t row = min(tile * BS + tid, a.S - 1);
+    return a.A.ptr(row) - a.A.base;
+  };
+
+  floatx16 acc[MTW][2];
+#pragma unroll
+  for (int mi = 0; mi < MTW; ++mi)
+#pragma unroll
+    for (int jn = 0; jn < 2; ++jn)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mi][jn][r] = 0.f;
+
+  int64_t tile = blockIdx.x;
+  if (tile < ntiles) {
+    const int64_t e0 = load_entries(tile), e1 = load_entries(tile + gridDim.x);
+    if (tid < BS) {
+      ent[0 * BS + tid] = e0;
+      ent[1 * BS + tid] = e1;
+    }
+    __syncthreads();  // also orders the zero fill before the first staging stores
+    fetch_a(tile, 0);
+    store_a(0);
+    fetch_b(tile);
+    store_b(0);
+    __syncthreads();
+  }
+
+  int it = 0;
+  for (; tile < ntiles; tile += gridDim.x, ++it) {
+    const int stage = it & 1;
+    const int64_t next = tile + gridDim.x;
+    const bool has_next = next < ntiles;  // uniform
+    const int64_t e2 = load_entries(next + gridDim.x);
+    const float* const At = As + stage * BS * PA + 32 * MTW * wm;
+    const float* const Bt = Bs + stage * BS * PB + 64 * wn;
+    if (has_next) fetch_a(next, stage ^ 1);
+#pragma unroll
+    for (int t = 0; t < BS / 2; ++t) {  // matrix-core step t contracts rows 2 t and 2 t + 1 of the tile
+      float af[MTW], bf[2];
+#pragma unroll
+      for (int mi = 0; mi < MTW; ++mi) af[mi] = At[(2 * t + hi) * PA + 32 * mi + lo];
+#pragma unroll
+      for (int jn = 0; jn < 2; ++jn) bf[jn] = Bt[(2 * t + hi) * PB + 32 * jn + lo];
+#pragma unroll
+      for (int mi = 0; mi < MTW; ++mi)
+#pragma unroll
+        for (int jn = 0; jn < 2; ++jn) acc[mi][jn] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[mi], bf[jn], acc[mi][jn], 0, 0, 0);
+      if (t == BS / 4 - 1 && has_next) {
+        store_a(stage ^ 1);
+        fetch_b(next);
+      }
+    }
+    if (has_next) store_b(stage ^ 1);
+    if (tid < BS) ent[stage * BS + tid] = e2;
+    __syncthreads();
+  }
+
+  // ---- this workgroup's partial sums
+#pragma unroll
+  for (int mi = 0; mi < MTW; ++mi)
+#pragma unroll
+    for (int jn = 0; jn < 2; ++jn)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = 32 * (MTW * wm + mi) + 8 * (r / 4) + 4 * hi + (r % 4);
+        if (m < MIN) atomicAdd(&a.C[m * kWregN + 64 * wn + 32 * jn + lo], acc[mi][jn][r]);
+      }
+  if (a.colsum != nullptr) {
+    float4* red = reinterpret_cast<float4*>(Bs);  // the loop ended with a barrier
+    red[tid] = bsum;
+    __syncthreads();
+    if (tid < 64) {
+      float4 v = red[tid];
+#pragma unroll
+      for (int q = 1; q < NT / 64; ++q) {
+        const float4 o = red[tid + 64 * q];
+        v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
+      }
+      float* dst = a.colsum + 4 * tid;
+      atomicAdd(dst + 0, v.x); atomicAdd(dst + 1, v.y); atomicAdd(dst + 2, v.z); atomicAdd(dst + 3, v.w);
+    }
+  }
+}
+
+template <int MIN, int WM>
+inline int32_t launch_wacc_gemm_inst(const WaccArgs& a, hipStream_t s) {
+  using Sh = WaccShape<MIN, WM>;
+  auto kern = wacc_gemm_kernel<MIN, WM>;
+  static bool configured = false;  // per instantiation
+  if (!configured) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+      return MARL_E_LAUNCH;
+    configured = true;
+  }
+  const int64_t tiles = (a.S + Sh::BS - 1) / Sh::BS;
+  hipLaunchKernelGGL(kern, dim3((unsigned)std::min<int64_t>(tiles, 256)), dim3(Sh::NT), Sh::lds_bytes, s, a);
+  return MARL_OK;
+}
+
+// The instantiated shape: 256 columns and the 300 output rows of the centralised critic's first layer (4 x 75 inputs),
+// eight wavefronts.  (For 256 output rows the split-k tile kernel of gemm.h measured faster: 310 against 361 us per
+// 262 144 rows, with either four or eight wavefronts here.)
+inline bool wacc_gemm_supported(const RowSrc& A, int M, int N) {
+  return N == kWregN && M == 300 && A.ld % 4 == 0 && aligned16(A.base);
+}
+
+inline int32_t launch_wacc_gemm(const WaccArgs& a, int M, hipStream_t s) {
+  (void)M;
+  return launch_wacc_gemm_inst<300, 2>(a, s);
+}
+
+}  // namespace marl
