@@ -217,13 +217,15 @@ UpdateWsView carve_update_ws(const marl_config& c, void* ws, int64_t* total) {
   v.sc = (Scalars*)take(sizeof(Scalars));
   v.ident = (int32_t*)take(R * 4);
   if (!d.bf16) {
-    v.h1a = (float*)take(Sa * d.Ha * 4);
-    v.h2a = (float*)take(Sa * d.Ha * 4);
-    v.dz1a = (float*)take(Sa * d.Ha * 4);
+    // activations: rows rounded up to the 64-row tiles of the register-resident kernels, which store whole tiles
+    const int64_t Sap = round_up64(Sa), Scp = round_up64(Sc);
+    v.h1a = (float*)take(Sap * d.Ha * 4);
+    v.h2a = (float*)take(Sap * d.Ha * 4);
+    v.dz1a = (float*)take(Sap * d.Ha * 4);
     v.dla = (float*)take(Sa * kActions * 4);
-    v.h1c = (float*)take(Sc * d.Hc * 4);
-    v.h2c = (float*)take(Sc * d.Hc * 4);
-    v.dz1c = (float*)take(Sc * d.Hc * 4);
+    v.h1c = (float*)take(Scp * d.Hc * 4);
+    v.h2c = (float*)take(Scp * d.Hc * 4);
+    v.dz1c = (float*)take(Scp * d.Hc * 4);
     v.dlc = (float*)take(Sc * 4);
   } else {
     const int64_t Sp = round_up64(std::max(Sa, Sc));
@@ -248,6 +250,30 @@ int64_t pick_k_split(int64_t K, int64_t tiles_mn) {
   int64_t per = (K + want - 1) / want;
   per = std::max<int64_t>(256, ((per + kGemmBK - 1) / kGemmBK) * kGemmBK);
   return per;
+}
+
+// Forward and loss of one 256-wide fp32 network with each layer's weights resident in registers: h1 goes to HBM,
+// the second hidden activation never does, `dz2` gets dL/d(pre-activation of layer 2), the output layer's gradient
+// and the loss statistics are accumulated.
+inline bool wreg_forward_supported(const RowSrc& X, int Din, int H) {
+  return H == kWregN && wreg_gemm_supported<WREG_BIAS_TANH>(X, Din, H);
+}
+template <int NOUT, class LossFn>
+int32_t train_forward_wreg(const RowSrc& X, int64_t S, int Din, const float* W1, const float* b1, const float* W2,
+                           const float* b2, const float* W3, const float* b3, float* h1, float* dz2, float* gW3,
+                           float* gb3, float* stats, const LossFn& fn, hipStream_t s) {
+  {
+    WregArgs g{};
+    g.A = X; g.S = S; g.Kin = Din; g.B = W1; g.ldb = kWregN; g.b_kcont = 0; g.C = h1; g.bias = b1;
+    TimedLaunch timed(KC_GEMM_NN, 2.0 * (double)S * Din * kWregN, s);
+    const int32_t rc = launch_wreg_gemm<WREG_BIAS_TANH>(g, s);
+    if (rc != MARL_OK) return rc;
+  }
+  WregArgs g{};
+  g.A = RowSrc{h1, kWregN, nullptr, 1, S}; g.S = S; g.Kin = kWregN; g.B = W2; g.ldb = kWregN; g.b_kcont = 0; g.C = dz2;
+  g.bias = b2; g.W3 = W3; g.b3 = b3; g.gW3 = gW3; g.gb3 = gb3; g.stats = stats;
+  TimedLaunch timed(KC_GEMM_NN, 2.0 * (double)S * kWregN * kWregN, s);
+  return launch_wreg_loss<NOUT>(g, fn, s);
 }
 
 // Backward through one network given dL/d(output layer) in dl; h2 is overwritten by dz2.
@@ -438,7 +464,12 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
           const int32_t rc = launch_fused_train<1>(d.Hc, ta, fn, s);
           if (rc != MARL_OK) return rc;
         } else {
-          if (fused_c) {
+          if (wreg_forward_supported(Xc, d.Dc, d.Hc)) {
+            const int32_t rc = train_forward_wreg<1>(Xc, Sc, d.Dc, eff + oc.W1, eff + oc.b1, eff + oc.W2, eff + oc.b2,
+                                                     eff + oc.W3, eff + oc.b3, w.h1c, w.h2c, w.grad + gc.W3,
+                                                     w.grad + gc.b3, w.sc->acc, fn, s);
+            if (rc != MARL_OK) return rc;
+          } else if (fused_c) {
             FusedFwdArgs fa{};
             fa.X = Xc; fa.S = Sc; fa.Din = d.Dc; fa.xvec = aligned16(Xc.base) && Xc.ld % 4 == 0 && d.Dc % 4 == 0;
             fa.W1 = eff + oc.W1; fa.b1 = eff + oc.b1; fa.W2 = eff + oc.W2; fa.b2 = eff + oc.b2; fa.W3 = eff + oc.W3;

@@ -19,7 +19,11 @@ namespace marl {
 
 enum WregEpi {
   WREG_BIAS_TANH = 0,  // C = tanh(acc + bias[n])
-  WREG_DTANH = 1       // C = acc * (1 - aux[m][n]^2)
+  WREG_DTANH = 1,      // C = acc * (1 - aux[m][n]^2)
+  // The last hidden layer of a network in training: h = tanh(acc + bias[n]) stays in registers, the output layer
+  // out = h W3 + b3 and the loss functor turn it into dL/d(out), and C = (dL/d(out) W3^T) * (1 - h^2), the gradient
+  // with respect to this layer's pre-activation; the output layer's own gradient is accumulated on the way.
+  WREG_TANH_LOSS = 2
 };
 
 struct WregArgs {
@@ -29,9 +33,26 @@ struct WregArgs {
   const float* B;  // b_kcont ? [256][ldb] with B(k, n) = B[n * ldb + k] : [Kin][ldb] with B(k, n) = B[k * ldb + n]
   int ldb;
   int b_kcont;
+  // C and aux have room for S rounded up to whole tiles of 64 rows: the kernel stores (and reads) whole tiles without
+  // row checks, what lands in the rows past S is never used
   float* C;           // [S][256]
-  const float* bias;  // WREG_BIAS_TANH: [256]
+  const float* bias;  // WREG_BIAS_TANH, WREG_TANH_LOSS: [256]
   const float* aux;   // WREG_DTANH: [S][256]
+  // WREG_TANH_LOSS: the output layer W3 [256][NOUT], b3 [NOUT]; its gradient and the loss statistics (5 floats),
+  // accumulated with atomics
+  const float *W3, *b3;
+  float *gW3, *gb3, *stats;
+};
+
+// The loss functor of WREG_TANH_LOSS splits into load (the trajectory values of a sample, requested while the tile is
+// still being multiplied) and compute (out -> dL/d(out), statistics); this one stands in for the other epilogues.
+struct WregNoFinish {
+  struct In {};
+  struct Prep {};
+  __device__ int32_t row_entry(int64_t) const { return 0; }
+  __device__ In load_with(int64_t, int32_t) const { return In{}; }
+  __device__ Prep prepare() const { return Prep{}; }
+  __device__ void compute(const In&, const Prep&, const float*, float*, float*) const {}
 };
 
 constexpr int kWregBM = 64;   // rows per tile
@@ -42,20 +63,26 @@ struct WregShape {
   static constexpr int P = K + 4;                      // LDS row pitch: 4 * odd, conflict-free 16-byte row-per-lane reads
   static constexpr int VPR = K / 4;                    // 16-byte vectors per row
   static constexpr int TOT = kWregBM * VPR / 256;      // vectors a thread stages per tile
-  static constexpr int NB = 4;                         // staging batches per tile
+  static constexpr int NB = 8;                         // staging batches per tile
   static constexpr int PER = (TOT + NB - 1) / NB;      // vectors per batch
   static constexpr int GROUPS = K / 8;
   static constexpr size_t lds_bytes = sizeof(float) * 2 * kWregBM * P + sizeof(int64_t) * 2 * kWregBM;
+  // WREG_TANH_LOSS adds: W3 [256][NOUT], partial outputs [4][BM][NOUT], dL/d(out) [BM][8]
+  static constexpr size_t loss_lds_bytes(int nout) { return sizeof(float) * (kWregN * nout + 4 * kWregBM * nout + kWregBM * 8); }
   static_assert(K % 16 == 0 && (P / 4) % 2 == 1, "K a multiple of 16 with an odd K/4 + 1");
 };
 
-template <int K, int EPI>
-__global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a) {
+template <int K, int EPI, int NOUT = 1, class Fin = WregNoFinish>
+__global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) {
   using Sh = WregShape<K>;
   constexpr int P = Sh::P, VPR = Sh::VPR, TOT = Sh::TOT, NB = Sh::NB, PER = Sh::PER, GROUPS = Sh::GROUPS, BM = kWregBM;
   extern __shared__ __attribute__((aligned(16))) unsigned char wreg_smem[];
   float* const As = reinterpret_cast<float*>(wreg_smem);                       // [2][BM][P]
   int64_t* const ent = reinterpret_cast<int64_t*>(As + 2 * BM * P);            // [2][BM] offsets (floats) of a tile's rows
+  float* const W3s = reinterpret_cast<float*>(ent + 2 * BM);                    // WREG_TANH_LOSS only, as are the next two
+  float* const red = W3s + kWregN * NOUT;                                       // [4][BM][NOUT]
+  float* const dls = red + 4 * BM * NOUT;                                       // [BM][8]
+  static_assert(EPI != WREG_TANH_LOSS || K == kWregN, "the activation tile reuses the stage of A it came from");
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lo = lane & 31, hi = lane >> 5;
@@ -110,6 +137,13 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a) {
   // ---- prologue: entries of the first two tiles, then the first tile itself
   int64_t tile = blockIdx.x;
   if (tile >= ntiles) return;  // uniform per workgroup
+  // output-layer gradient of hidden unit tid, the bias gradient and the loss statistics, summed over this workgroup's tiles
+  float gw[NOUT], gb[NOUT], st[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int k = 0; k < NOUT; ++k) gw[k] = gb[k] = 0.f;
+  if (EPI == WREG_TANH_LOSS)
+    for (int i = tid; i < kWregN * NOUT; i += 256) W3s[i] = a.W3[i];  // ordered before its first use by the barriers below
+  const auto prep = fin.prepare();
   {
     const int64_t e0 = load_entries(tile), e1 = load_entries(tile + gridDim.x);
     if (tid < BM) {
@@ -133,22 +167,26 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a) {
     const int64_t e2 = load_entries(next + gridDim.x);  // consumed at the end of this tile
     const float* const At = As + stage * BM * P;
     const int64_t m0 = tile * BM;
-    const int rows_left = (int)min((int64_t)BM, a.S - m0);
 
+    // A lane's 64 outputs sit at fixed offsets from one address: rows 32 i + 8 (r/4) + r%4 below row m0 + 4 hi,
+    // columns 32 jn right of column 64 wave + lo.
+    const int64_t lane_off = (m0 + 4 * hi) * kWregN + 64 * wave + lo;
     // what the epilogue needs from memory, requested before the products start
     float auxv[2][2][16];
     if (EPI == WREG_DTANH) {
+      const float* const aux = a.aux + lane_off;
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int jn = 0; jn < 2; ++jn)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int m = 32 * i + 8 * (r / 4) + 4 * hi + (r % 4);
-            const int64_t row = min(m0 + m, a.S - 1);
-            auxv[i][jn][r] = a.aux[row * kWregN + 64 * wave + 32 * jn + lo];
-          }
+          for (int r = 0; r < 16; ++r) auxv[i][jn][r] = aux[(32 * i + 8 * (r / 4) + (r % 4)) * kWregN + 32 * jn];
     }
+
+    // the loss inputs of sample tid of this tile (threads tid < BM): the row entry now, the values half-way through
+    const int64_t my_sample = min(m0 + tid, a.S - 1);
+    const int32_t loss_entry = (EPI == WREG_TANH_LOSS && tid < BM) ? fin.row_entry(my_sample) : 0;
+    typename Fin::In loss_in{};
 
     floatx16 acc[2][2];
 #pragma unroll
@@ -171,6 +209,7 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a) {
 #pragma unroll
           for (int jn = 0; jn < 2; ++jn)
             acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i][j], breg[g][j][jn], acc[i][jn], 0, 0, 0);
+      if (EPI == WREG_TANH_LOSS && g == GROUPS / 2 && tid < BM) loss_in = fin.load_with(my_sample, loss_entry);
       // the next tile moves in NB batches spread over the products: registers -> the other LDS stage, then the next request
 #pragma unroll
       for (int b = 0; b < NB; ++b)
@@ -181,33 +220,135 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a) {
     }
 
     // ---- epilogue (accumulator register r of a lane holds C[8 (r/4) + 4 hi + r%4][lo] of its 32 x 32 tile)
+    float* const out = a.C + lane_off;
+    if (EPI != WREG_TANH_LOSS) {
 #pragma unroll
-    for (int jn = 0; jn < 2; ++jn) {
-      const int n = 64 * wave + 32 * jn + lo;
-      const float bias = EPI == WREG_BIAS_TANH ? a.bias[n] : 0.f;
+      for (int jn = 0; jn < 2; ++jn) {
+        const float bias = EPI == WREG_BIAS_TANH ? a.bias[64 * wave + 32 * jn + lo] : 0.f;
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int m = 32 * i + 8 * (r / 4) + 4 * hi + (r % 4);
-          float v = acc[i][jn][r];
-          if (EPI == WREG_BIAS_TANH) {
-            v = tanh_f32(v + bias);
-          } else {
-            const float h = auxv[i][jn][r];
-            v = v * (1.0f - h * h);
+          for (int r = 0; r < 16; ++r) {
+            float v = acc[i][jn][r];
+            if (EPI == WREG_BIAS_TANH) {
+              v = tanh_f32(v + bias);
+            } else {
+              const float h = auxv[i][jn][r];
+              v = v * (1.0f - h * h);
+            }
+            out[(32 * i + 8 * (r / 4) + (r % 4)) * kWregN + 32 * jn] = v;
           }
-          if (m < rows_left) a.C[(m0 + m) * kWregN + n] = v;
+      }
+    } else {
+      // h = tanh(acc + bias) stays in the accumulators and goes to LDS, into the stage of A this tile came from
+      float* const Hs = As + stage * BM * P;
+      __syncthreads();  // every wavefront has read its last fragment of A
+#pragma unroll
+      for (int jn = 0; jn < 2; ++jn) {
+        const int n = 64 * wave + 32 * jn + lo;
+        const float bias = a.bias[n];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int m = 32 * i + 8 * (r / 4) + 4 * hi + (r % 4);
+            const float v = tanh_f32(acc[i][jn][r] + bias);
+            acc[i][jn][r] = v;
+            Hs[m * P + n] = v;
+          }
+      }
+      __syncthreads();
+      // output layer on the ALUs: thread -> (sample tid % 64, hidden units 64 (tid / 64) ..)
+      {
+        const int smp = tid & 63, grp = tid >> 6;
+        float part[NOUT];
+#pragma unroll
+        for (int k = 0; k < NOUT; ++k) part[k] = 0.f;
+#pragma unroll 8
+        for (int i = 64 * grp; i < 64 * grp + 64; ++i) {
+          const float h = Hs[smp * P + i];
+#pragma unroll
+          for (int k = 0; k < NOUT; ++k) part[k] = fmaf(h, W3s[i * NOUT + k], part[k]);
         }
+#pragma unroll
+        for (int k = 0; k < NOUT; ++k) red[(grp * BM + smp) * NOUT + k] = part[k];
+      }
+      __syncthreads();
+      if (tid < BM) {
+        float out[NOUT], dl[NOUT];
+#pragma unroll
+        for (int k = 0; k < NOUT; ++k) {
+          float v = a.b3[k];
+#pragma unroll
+          for (int gq = 0; gq < 4; ++gq) v += red[(gq * BM + tid) * NOUT + k];
+          out[k] = v;
+          dl[k] = 0.f;
+        }
+        if (m0 + tid < a.S) fin.compute(loss_in, prep, out, dl, st);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) dls[tid * 8 + k] = k < NOUT ? dl[k < NOUT ? k : 0] : 0.f;
+#pragma unroll
+        for (int k = 0; k < NOUT; ++k) gb[k] += dl[k];
+      }
+      __syncthreads();
+      // C = (dl W3^T) * (1 - h^2): the rank-NOUT product runs on the matrix cores (k padded to 8) and lands in the
+      // lane layout of the register-resident h
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const float4 av = *reinterpret_cast<const float4*>(&dls[(32 * i + lo) * 8 + 4 * hi]);
+        const float af[4] = {av.x, av.y, av.z, av.w};
+#pragma unroll
+        for (int jn = 0; jn < 2; ++jn) {
+          const int n = 64 * wave + 32 * jn + lo;
+          float bf[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) bf[j] = (4 * hi + j < NOUT) ? W3s[n * NOUT + (4 * hi + j < NOUT ? 4 * hi + j : 0)] : 0.f;
+          floatx16 gacc;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) gacc[r] = 0.f;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) gacc = __builtin_amdgcn_mfma_f32_32x32x2f32(af[j], bf[j], gacc, 0, 0, 0);
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const float h = acc[i][jn][r];
+            out[(32 * i + 8 * (r / 4) + (r % 4)) * kWregN + 32 * jn] = gacc[r] * (1.0f - h * h);
+          }
+        }
+      }
+      // gW3[tid][k] += sum_s h[s][tid] dl[s][k] (rows past the end carry dl = 0)
+#pragma unroll 8
+      for (int smp = 0; smp < BM; ++smp) {
+        const float h = Hs[smp * P + tid];
+#pragma unroll
+        for (int k = 0; k < NOUT; ++k) gw[k] = fmaf(h, dls[smp * 8 + k], gw[k]);
+      }
     }
     if (tid < BM) ent[stage * BM + tid] = e2;  // this tile's entries were last read while the previous tile was multiplied
     __syncthreads();  // the other stage is complete; this one may be overwritten
   }
+  if (EPI == WREG_TANH_LOSS) {
+#pragma unroll
+    for (int k = 0; k < NOUT; ++k) atomicAdd(&a.gW3[tid * NOUT + k], gw[k]);
+    if (wave == 0) {  // samples live in threads tid < 64
+#pragma unroll
+      for (int k = 0; k < NOUT; ++k) {
+        float v = gb[k];
+        for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+        if (lane == 0) atomicAdd(&a.gb3[k], v);
+      }
+#pragma unroll
+      for (int k = 0; k < 5; ++k) {
+        float v = st[k];
+        for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+        if (lane == 0 && v != 0.f) atomicAdd(&a.stats[k], v);
+      }
+    }
+  }
 }
 
-template <int K, int EPI>
-inline int32_t launch_wreg_gemm_inst(const WregArgs& a, hipStream_t s) {
-  auto kern = wreg_gemm_kernel<K, EPI>;
+template <int K, int EPI, int NOUT = 1, class Fin = WregNoFinish>
+inline int32_t launch_wreg_gemm_inst(const WregArgs& a, hipStream_t s, const Fin& fin = Fin()) {
+  auto kern = wreg_gemm_kernel<K, EPI, NOUT, Fin>;
   static bool configured = false;  // per instantiation
   if (!configured) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
@@ -215,21 +356,29 @@ inline int32_t launch_wreg_gemm_inst(const WregArgs& a, hipStream_t s) {
     configured = true;
   }
   const int64_t tiles = (a.S + kWregBM - 1) / kWregBM;
-  hipLaunchKernelGGL(kern, dim3((unsigned)std::min<int64_t>(tiles, 256)), dim3(256), WregShape<K>::lds_bytes, s, a);
+  const size_t lds = WregShape<K>::lds_bytes + (EPI == WREG_TANH_LOSS ? WregShape<K>::loss_lds_bytes(NOUT) : 0);
+  hipLaunchKernelGGL(kern, dim3((unsigned)std::min<int64_t>(tiles, 256)), dim3(256), lds, s, a, fin);
   return MARL_OK;
 }
 
-// Shapes this kernel serves: 256 output columns, 16-byte aligned rows, a contraction of at most 304 (256 with the
-// WREG_DTANH epilogue, whose prefetched operand needs the registers the longer contraction would take).
+// Shapes this kernel serves: 256 output columns, 16-byte aligned rows, a contraction of at most 304 for
+// WREG_BIAS_TANH and of at most 256 otherwise (WREG_DTANH keeps its prefetched operand in the registers the longer
+// contraction would take; WREG_TANH_LOSS reuses the stage of A for the 256-wide activation tile).
 template <int EPI>
 inline bool wreg_gemm_supported(const RowSrc& A, int Kin, int N) {
-  return N == kWregN && Kin <= (EPI == WREG_DTANH ? 256 : 304) && Kin % 4 == 0 && A.ld % 4 == 0 && aligned16(A.base);
+  return N == kWregN && Kin <= (EPI == WREG_BIAS_TANH ? 304 : 256) && Kin % 4 == 0 && A.ld % 4 == 0 && aligned16(A.base);
 }
 
 template <int EPI>
 inline int32_t launch_wreg_gemm(const WregArgs& a, hipStream_t s) {
+  static_assert(EPI != WREG_TANH_LOSS, "launch_wreg_loss");
   if (EPI == WREG_DTANH || a.Kin <= 256) return launch_wreg_gemm_inst<256, EPI>(a, s);
   return launch_wreg_gemm_inst<EPI == WREG_DTANH ? 256 : 304, EPI>(a, s);
+}
+
+template <int NOUT, class Fin>
+inline int32_t launch_wreg_loss(const WregArgs& a, const Fin& fin, hipStream_t s) {
+  return launch_wreg_gemm_inst<256, WREG_TANH_LOSS, NOUT, Fin>(a, s, fin);
 }
 
 // ---------------------------------------------------------------------------------------------------------------
