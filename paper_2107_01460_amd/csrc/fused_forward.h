@@ -24,7 +24,6 @@ struct FusedFwdArgs {
   float* gW3;      // training: [H][NOUT] accumulated with atomics
   float* gb3;      // training: [NOUT]
   float* stats;    // training: 5 floats accumulated with atomics (policy loss, value loss, entropy, KL, clip fraction)
-  int round_bf16;
 };
 
 template <int H, int BM, int NOUT>
@@ -175,7 +174,6 @@ __global__ void __launch_bounds__(256, 2) fused_forward_kernel(FusedFwdArgs a, F
       for (int r = 0; r < 16; ++r) {
         const int m = mt * 32 + 8 * (r / 4) + 4 * hi + (r % 4);
         float v = tanh_f32(acc[q][r] + bias);
-        if (a.round_bf16) v = round_to_bf16(v);
         L.Hs[m * PH + n] = v;
         if (TRAIN && m < rows_left) h1_tile[m * H + n] = v;
         if ((r & 3) == 3) __builtin_amdgcn_sched_barrier(0);  // four elements in flight at a time keeps registers bounded
@@ -199,7 +197,6 @@ __global__ void __launch_bounds__(256, 2) fused_forward_kernel(FusedFwdArgs a, F
       for (int r = 0; r < 16; ++r) {
         const int m = mt * 32 + 8 * (r / 4) + 4 * hi + (r % 4);
         float v = tanh_f32(acc[q][r] + bias);
-        if (a.round_bf16) v = round_to_bf16(v);
         acc[q][r] = v;
         L.Hs[m * PH + n] = v;  // every wavefront is past its last read of h1 (barrier above)
         if ((r & 3) == 3) __builtin_amdgcn_sched_barrier(0);
@@ -264,7 +261,6 @@ __global__ void __launch_bounds__(256, 2) fused_forward_kernel(FusedFwdArgs a, F
           const int m = mt * 32 + 8 * (r / 4) + 4 * hi + (r % 4);
           const float h = acc[q][r];
           float v = gacc[r] * (1.0f - h * h);
-          if (a.round_bf16) v = round_to_bf16(v);
           if (m < rows_left) dz2_tile[m * H + n] = v;
           if ((r & 3) == 3) __builtin_amdgcn_sched_barrier(0);
         }

@@ -41,7 +41,6 @@ struct FusedTrainArgs {
   const float *W1s, *W2s, *W2Ts;             // operand-order copies: (k, n) at ((k / 4) * H + n) * 4 + k % 4; W1s zero-padded to 16-row groups
   float *gW1, *gb1, *gW2, *gb2, *gW3, *gb3;  // gradient blocks, accumulated with atomics
   float* stats;                              // 5 floats, atomics
-  int round_bf16;
 };
 
 // acc[q] += A^T B_q over the samples kb0 .. kb0 + klen of a row tile held in LDS: A column block at Ap (pitch pa),
@@ -244,7 +243,6 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
       for (int r = 0; r < 16; ++r) {
         const int m = mt * 32 + 8 * (r / 4) + 4 * hi + (r % 4);
         float v = tanh_f32(acc[r] + bias);
-        if (a.round_bf16) v = round_to_bf16(v);
         H1[m * PH + n] = v;
         acc[r] = 0.f;
         if ((r & 3) == 3) __builtin_amdgcn_sched_barrier(0);
@@ -264,7 +262,6 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
       for (int r = 0; r < 16; ++r) {
         const int m = mt * 32 + 8 * (r / 4) + 4 * hi + (r % 4);
         float v = tanh_f32(acc[r] + bias);
-        if (a.round_bf16) v = round_to_bf16(v);
         h2r[r] = v;
         H2[m * PH + n] = v;
         if ((r & 3) == 3) __builtin_amdgcn_sched_barrier(0);
@@ -356,7 +353,6 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
       for (int r = 0; r < 16; ++r) {
         const int m = mt * 32 + 8 * (r / 4) + 4 * hi + (r % 4);
         float v = acc[r] * (1.0f - h2r[r] * h2r[r]);
-        if (a.round_bf16) v = round_to_bf16(v);
         H2[m * PH + n] = v;
         csum += v;
       }
@@ -388,7 +384,6 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
         const int m = mt * 32 + 8 * (r / 4) + 4 * hi + (r % 4);
         const float h = H1[m * PH + n];
         float v = acc[r] * (1.0f - h * h);
-        if (a.round_bf16) v = round_to_bf16(v);
         H1[m * PH + n] = v;  // only this wavefront touches its tile of h1 from here on until the barrier
         csum += v;
       }

@@ -68,7 +68,6 @@ FusedFwdArgs fused_args(const RowSrc& X, int64_t S, int Din, const float* eff, c
   a.X = X; a.S = S; a.Din = Din;
   a.xvec = aligned16(X.base) && X.ld % 4 == 0 && Din % 4 == 0;
   a.W1 = eff + o.W1; a.b1 = eff + o.b1; a.W2 = eff + o.W2; a.b2 = eff + o.b2; a.W3 = eff + o.W3; a.b3 = eff + o.b3;
-  a.round_bf16 = bf16;
   return a;
 }
 

@@ -425,7 +425,6 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
           ta.W1s = eff + pm.sw_w1[0]; ta.W2s = eff + pm.sw_w2[0]; ta.W2Ts = eff + pm.sw_w2t[0];
           ta.b3 = eff + oa.b3; ta.gW1 = w.grad + ga.W1; ta.gb1 = w.grad + ga.b1; ta.gW2 = w.grad + ga.W2;
           ta.gb2 = w.grad + ga.b2; ta.gW3 = w.grad + ga.W3; ta.gb3 = w.grad + ga.b3; ta.stats = w.sc->acc;
-          ta.round_bf16 = d.bf16;
           const int32_t rc = launch_fused_train<kActions>(d.Ha, ta, fn, s);
           if (rc != MARL_OK) return rc;
         } else {
@@ -434,7 +433,7 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
             fa.X = Xa; fa.S = Sa; fa.Din = d.D; fa.xvec = aligned16(Xa.base) && Xa.ld % 4 == 0 && d.D % 4 == 0;
             fa.W1 = eff + oa.W1; fa.b1 = eff + oa.b1; fa.W2 = eff + oa.W2; fa.b2 = eff + oa.b2; fa.W3 = eff + oa.W3;
             fa.b3 = eff + oa.b3; fa.h1_out = w.h1a; fa.dz2_out = w.h2a; fa.gW3 = w.grad + ga.W3; fa.gb3 = w.grad + ga.b3;
-            fa.stats = w.sc->acc; fa.round_bf16 = d.bf16;
+            fa.stats = w.sc->acc;
             launch_fused_forward<kActions, true>(d.Ha, fa, fn, s);
           } else {
             mlp_hidden_forward(Xa, Sa, d.D, d.Ha, eff + oa.W1, eff + oa.b1, eff + oa.W2, eff + oa.b2, w.h1a, w.h2a, d.bf16, s);
@@ -460,7 +459,6 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
           ta.W1s = eff + pm.sw_w1[1]; ta.W2s = eff + pm.sw_w2[1]; ta.W2Ts = eff + pm.sw_w2t[1];
           ta.b3 = eff + oc.b3; ta.gW1 = w.grad + gc.W1; ta.gb1 = w.grad + gc.b1; ta.gW2 = w.grad + gc.W2;
           ta.gb2 = w.grad + gc.b2; ta.gW3 = w.grad + gc.W3; ta.gb3 = w.grad + gc.b3; ta.stats = w.sc->acc;
-          ta.round_bf16 = d.bf16;
           const int32_t rc = launch_fused_train<1>(d.Hc, ta, fn, s);
           if (rc != MARL_OK) return rc;
         } else {
@@ -474,7 +472,7 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
             fa.X = Xc; fa.S = Sc; fa.Din = d.Dc; fa.xvec = aligned16(Xc.base) && Xc.ld % 4 == 0 && d.Dc % 4 == 0;
             fa.W1 = eff + oc.W1; fa.b1 = eff + oc.b1; fa.W2 = eff + oc.W2; fa.b2 = eff + oc.b2; fa.W3 = eff + oc.W3;
             fa.b3 = eff + oc.b3; fa.h1_out = w.h1c; fa.dz2_out = w.h2c; fa.gW3 = w.grad + gc.W3; fa.gb3 = w.grad + gc.b3;
-            fa.stats = w.sc->acc; fa.round_bf16 = d.bf16;
+            fa.stats = w.sc->acc;
             launch_fused_forward<1, true>(d.Hc, fa, fn, s);
           } else {
             mlp_hidden_forward(Xc, Sc, d.Dc, d.Hc, eff + oc.W1, eff + oc.b1, eff + oc.W2, eff + oc.b2, w.h1c, w.h2c, d.bf16, s);
