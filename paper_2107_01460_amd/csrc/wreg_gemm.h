@@ -83,6 +83,11 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) 
   float* const red = W3s + kWregN * NOUT;                                       // [4][BM][NOUT]
   float* const dls = red + 4 * BM * NOUT;                                       // [BM][8]
   static_assert(EPI != WREG_TANH_LOSS || K == kWregN, "the activation tile reuses the stage of A it came from");
+  // The two plain epilogues are deferred where the registers allow: a tile's accumulators move to a second register set and are finished two
+  // elements per k group INSIDE the next tile's stream of matrix instructions, so that the single wavefront of a SIMD
+  // keeps its matrix core busy while it applies tanh and stores (only a workgroup's last tile finishes on its own).
+  constexpr bool DEFER = EPI != WREG_TANH_LOSS && K <= 256;  // a longer contraction leaves no room for the second set
+  constexpr int LOOK = 8;  // WREG_DTANH: k groups between the request of an element's operand and its use
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lo = lane & 31, hi = lane >> 5;
@@ -108,15 +113,25 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) 
   // ---- staging of a tile of A: vector f = tid + 256 p of the tile is (row f / VPR, columns 4 (f % VPR) ..)
   auto row_of = [&](int p) { return (tid + 256 * p) / VPR; };
   auto col_of = [&](int p) { return 4 * ((tid + 256 * p) % VPR); };
-  float4 stg[PER];
-  auto fetch_batch = [&](int64_t tile, int slot, int b) {
+  // A batch is requested SETS batch intervals before it is stored (one register set each), and the row offsets it needs
+  // are read from LDS one k group before the request.
+  constexpr int SETS = K <= 256 ? 2 : 1;  // the longer contraction has registers for one batch in flight only
+  float4 stg[SETS][PER];
+  int64_t eoff[PER];
+  auto read_offsets = [&](int slot, int b) {
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+      const int p = b * PER + q;
+      if (p < TOT) eoff[q] = ent[slot * BM + row_of(p)];
+    }
+  };
+  auto fetch_batch = [&](int b) {
 #pragma unroll
     for (int q = 0; q < PER; ++q) {
       const int p = b * PER + q;
       if (p < TOT) {
-        const int r = row_of(p), c = col_of(p);
-        const float* src = a.A.base + ent[slot * BM + r];
-        stg[q] = (c < a.Kin) ? *reinterpret_cast<const float4*>(src + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+        const int c = col_of(p);
+        stg[b % SETS][q] = (c < a.Kin) ? *reinterpret_cast<const float4*>(a.A.base + eoff[q] + c) : make_float4(0.f, 0.f, 0.f, 0.f);
       }
     }
   };
@@ -124,7 +139,7 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) 
 #pragma unroll
     for (int q = 0; q < PER; ++q) {
       const int p = b * PER + q;
-      if (p < TOT) *reinterpret_cast<float4*>(&As[(stage * BM + row_of(p)) * P + col_of(p)]) = stg[q];
+      if (p < TOT) *reinterpret_cast<float4*>(&As[(stage * BM + row_of(p)) * P + col_of(p)]) = stg[b % SETS][q];
     }
   };
   // offset of row tid of a tile (threads tid < BM); rows past the end repeat the last row, whose results are never stored
@@ -153,17 +168,45 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) 
     __syncthreads();
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
-      fetch_batch(tile, 0, b);
+      read_offsets(0, b);
+      fetch_batch(b);
       store_batch(0, b);
     }
     __syncthreads();
   }
 
+  floatx16 prev[2][2];     // DEFER: the previous tile's accumulators ...
+  int64_t prev_off = 0;    // ... and where its outputs go.  Before the first tile: zeros, "finished" into the first
+#pragma unroll
+  for (int i = 0; i < 2; ++i)  // tile's own place, where the real values overwrite them one tile later (same lane, same
+#pragma unroll
+    for (int jn = 0; jn < 2; ++jn)  // addresses, program order)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) prev[i][jn][r] = 0.f;
+  float bias2[2] = {0.f, 0.f};
+  if (EPI == WREG_BIAS_TANH) {
+    bias2[0] = a.bias[64 * wave + lo];
+    bias2[1] = a.bias[64 * wave + 32 + lo];
+  }
+  // element e = 32 jn + 16 i + r of a lane's 64 outputs: offset from the lane's address, and its finish
+  auto elem_off = [](int e) { return (32 * ((e >> 4) & 1) + 8 * ((e & 15) / 4) + (e & 3)) * kWregN + 32 * (e >> 5); };
+  float auxr[64];
+  auto finish_elem = [&](int e, int64_t off) {
+    const int jn = e >> 5, i = (e >> 4) & 1, r = e & 15;
+    float v = prev[i][jn][r];
+    if (EPI == WREG_BIAS_TANH) {
+      v = tanh_f32(v + bias2[jn]);
+    } else {
+      const float h = auxr[e];
+      v = v * (1.0f - h * h);
+    }
+    a.C[off + elem_off(e)] = v;
+  };
+
   int it = 0;
   for (; tile < ntiles; tile += gridDim.x, ++it) {
     const int stage = it & 1;
     const int64_t next = tile + gridDim.x;
-    const bool has_next = next < ntiles;  // uniform
     const int64_t e2 = load_entries(next + gridDim.x);  // consumed at the end of this tile
     const float* const At = As + stage * BM * P;
     const int64_t m0 = tile * BM;
@@ -171,16 +214,10 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) 
     // A lane's 64 outputs sit at fixed offsets from one address: rows 32 i + 8 (r/4) + r%4 below row m0 + 4 hi,
     // columns 32 jn right of column 64 wave + lo.
     const int64_t lane_off = (m0 + 4 * hi) * kWregN + 64 * wave + lo;
-    // what the epilogue needs from memory, requested before the products start
-    float auxv[2][2][16];
-    if (EPI == WREG_DTANH) {
-      const float* const aux = a.aux + lane_off;
+    if (it == 0) prev_off = lane_off;
+    if (DEFER && EPI == WREG_DTANH) {  // operands of the first elements of the previous tile's finish
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int jn = 0; jn < 2; ++jn)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) auxv[i][jn][r] = aux[(32 * i + 8 * (r / 4) + (r % 4)) * kWregN + 32 * jn];
+      for (int e = 0; e < 2 * LOOK; ++e) auxr[e] = a.aux[prev_off + elem_off(e)];
     }
 
     // the loss inputs of sample tid of this tile (threads tid < BM): the row entry now, the values half-way through
@@ -196,11 +233,32 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) 
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][jn][r] = 0.f;
 
-    if (has_next) fetch_batch(next, stage ^ 1, 0);
+    // (after a workgroup's last tile the same requests run once more on the row offsets 0 that load_entries left for
+    // tiles past the end: harmless reads into a stage nobody uses, and a loop body without branches)
+#pragma unroll
+    for (int b = 0; b < SETS; ++b) {
+      read_offsets(stage ^ 1, b);
+      fetch_batch(b);
+    }
+    // fragments of A: those of group g + 1 are read from LDS before the products of group g are issued (SETS == 2;
+    // the longer contraction has no registers for the second pair and reads each group's fragments at its top)
+    float4 fa[2][2];
+    if (SETS == 2) {
+      fa[0][0] = *reinterpret_cast<const float4*>(&At[lo * P + 4 * hi]);
+      fa[0][1] = *reinterpret_cast<const float4*>(&At[(32 + lo) * P + 4 * hi]);
+    }
 #pragma unroll
     for (int g = 0; g < GROUPS; ++g) {
-      const float4 a0 = *reinterpret_cast<const float4*>(&At[lo * P + 8 * g + 4 * hi]);
-      const float4 a1 = *reinterpret_cast<const float4*>(&At[(32 + lo) * P + 8 * g + 4 * hi]);
+      if (SETS == 2 && g + 1 < GROUPS) {
+        fa[(g + 1) & 1][0] = *reinterpret_cast<const float4*>(&At[lo * P + 8 * (g + 1) + 4 * hi]);
+        fa[(g + 1) & 1][1] = *reinterpret_cast<const float4*>(&At[(32 + lo) * P + 8 * (g + 1) + 4 * hi]);
+        __builtin_amdgcn_sched_barrier(0);  // keep these reads ahead of this group's matrix instructions
+      }
+      if (SETS == 1) {
+        fa[g & 1][0] = *reinterpret_cast<const float4*>(&At[lo * P + 8 * g + 4 * hi]);
+        fa[g & 1][1] = *reinterpret_cast<const float4*>(&At[(32 + lo) * P + 8 * g + 4 * hi]);
+      }
+      const float4 a0 = fa[g & 1][0], a1 = fa[g & 1][1];
       const float af[2][4] = {{a0.x, a0.y, a0.z, a0.w}, {a1.x, a1.y, a1.z, a1.w}};
 #pragma unroll
       for (int j = 0; j < 4; ++j)
@@ -210,35 +268,50 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) 
           for (int jn = 0; jn < 2; ++jn)
             acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i][j], breg[g][j][jn], acc[i][jn], 0, 0, 0);
       if (EPI == WREG_TANH_LOSS && g == GROUPS / 2 && tid < BM) loss_in = fin.load_with(my_sample, loss_entry);
-      // the next tile moves in NB batches spread over the products: registers -> the other LDS stage, then the next request
-#pragma unroll
-      for (int b = 0; b < NB; ++b)
-        if (g == ((b + 1) * GROUPS) / NB - 1 && has_next) {
-          store_batch(stage ^ 1, b);
-          if (b + 1 < NB) fetch_batch(next, stage ^ 1, b + 1);
+      if (DEFER && g < 32) {  // two elements of the previous tile per k group
+        if (EPI == WREG_DTANH && g + LOOK < 32) {
+          auxr[2 * (g + LOOK)] = a.aux[prev_off + elem_off(2 * (g + LOOK))];
+          auxr[2 * (g + LOOK) + 1] = a.aux[prev_off + elem_off(2 * (g + LOOK) + 1)];
         }
+        finish_elem(2 * g, prev_off);
+        finish_elem(2 * g + 1, prev_off);
+      }
+      // the next tile moves in NB batches spread over the products: batch b leaves its registers for the other LDS
+      // stage at the end of its interval and batch b + 2 is requested into them; its row offsets were read a group earlier
+#pragma unroll
+      for (int b = 0; b < NB; ++b) {
+        if (g == ((b + 1) * GROUPS) / NB - SETS && b + SETS < NB) read_offsets(stage ^ 1, b + SETS);
+        if (g == ((b + 1) * GROUPS) / NB - 1) {
+          store_batch(stage ^ 1, b);
+          if (b + SETS < NB) fetch_batch(b + SETS);
+        }
+      }
     }
 
     // ---- epilogue (accumulator register r of a lane holds C[8 (r/4) + 4 hi + r%4][lo] of its 32 x 32 tile)
     float* const out = a.C + lane_off;
-    if (EPI != WREG_TANH_LOSS) {
+    if (DEFER) {
 #pragma unroll
-      for (int jn = 0; jn < 2; ++jn) {
-        const float bias = EPI == WREG_BIAS_TANH ? a.bias[64 * wave + 32 * jn + lo] : 0.f;
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int jn = 0; jn < 2; ++jn) prev[i][jn] = acc[i][jn];
+      prev_off = lane_off;
+    } else if (EPI != WREG_TANH_LOSS) {
+#pragma unroll
+      for (int jn = 0; jn < 2; ++jn)
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             float v = acc[i][jn][r];
             if (EPI == WREG_BIAS_TANH) {
-              v = tanh_f32(v + bias);
+              v = tanh_f32(v + bias2[jn]);
             } else {
-              const float h = auxv[i][jn][r];
+              const float h = a.aux[lane_off + elem_off(32 * jn + 16 * i + r)];
               v = v * (1.0f - h * h);
             }
-            out[(32 * i + 8 * (r / 4) + (r % 4)) * kWregN + 32 * jn] = v;
+            out[elem_off(32 * jn + 16 * i + r)] = v;
           }
-      }
     } else {
       // h = tanh(acc + bias) stays in the accumulators and goes to LDS, into the stage of A this tile came from
       float* const Hs = As + stage * BM * P;
@@ -325,6 +398,14 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) 
     }
     if (tid < BM) ent[stage * BM + tid] = e2;  // this tile's entries were last read while the previous tile was multiplied
     __syncthreads();  // the other stage is complete; this one may be overwritten
+  }
+  if (DEFER) {  // the last tile of this workgroup
+    if (EPI == WREG_DTANH) {
+#pragma unroll
+      for (int e = 0; e < 64; ++e) auxr[e] = a.aux[prev_off + elem_off(e)];
+    }
+#pragma unroll
+    for (int e = 0; e < 64; ++e) finish_elem(e, prev_off);
   }
   if (EPI == WREG_TANH_LOSS) {
 #pragma unroll
