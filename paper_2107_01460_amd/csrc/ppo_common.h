@@ -12,7 +12,7 @@ namespace {
 
 // Device scalars of one minibatch step.
 struct Scalars {
-  double adv_sum, adv_sq;  // sum of advantages, sum of squared deviations
+  double adv_sum, adv_sq;  // sum of the minibatch's advantages, sum of their squares
   float acc[8];            // 0 policy loss, 1 value loss, 2 entropy, 3 approx KL, 4 clip fraction, 5 |grad|^2
 };
 
@@ -53,21 +53,25 @@ __device__ __forceinline__ double block_sum_f64(double v, double* red) {
   return t;  // valid in thread 0
 }
 
-// pass 0: sum; pass 1: sum of squared deviations from the mean of pass 0
-__global__ void __launch_bounds__(256) adv_stats_kernel(const float* __restrict__ adv, LossCommon lc, Scalars* sc,
-                                                        int pass) {
-  __shared__ double red[4];
+// Sum and sum of squares of the minibatch's advantages, both in fp64 (the variance is their difference: with fp32
+// inputs and fp64 sums the cancellation costs nothing that matters until the spread is 1e-6 of the mean).
+__global__ void __launch_bounds__(256) adv_stats_kernel(const float* __restrict__ adv, LossCommon lc, Scalars* sc) {
+  __shared__ double red[2][4];
   const int64_t B = lc.rows_mb * lc.A;
-  const double mean = pass ? sc->adv_sum / (double)B : 0.0;
-  double part = 0;
+  double sum = 0, sq = 0;
   for (int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; s < B; s += (int64_t)gridDim.x * blockDim.x) {
     const int64_t row = s / lc.A;
     const int a = (int)(s - row * lc.A);
     const double x = adv[(int64_t)lc.rows[row] * lc.A + a];
-    part += pass ? (x - mean) * (x - mean) : x;
+    sum += x;
+    sq += x * x;
   }
-  const double t = block_sum_f64(part, red);
-  if (threadIdx.x == 0) atomicAdd(pass ? &sc->adv_sq : &sc->adv_sum, t);
+  const double t0 = block_sum_f64(sum, red[0]);
+  const double t1 = block_sum_f64(sq, red[1]);
+  if (threadIdx.x == 0) {
+    atomicAdd(&sc->adv_sum, t0);
+    atomicAdd(&sc->adv_sq, t1);
+  }
 }
 
 // exp and log on the hardware exp2 / log2 units (1 ulp each; the arguments here are O(1))
@@ -101,8 +105,9 @@ struct ActorLoss {
     LossPrep p{0.f, 1.f};
     if (lc.normalize) {
       const double B = (double)lc.rows_mb * lc.A;
-      p.mean = (float)(lc.sc->adv_sum / B);
-      p.rstd = (float)(1.0 / (sqrt(lc.sc->adv_sq / B) + 1e-8));
+      const double mean = lc.sc->adv_sum / B;
+      p.mean = (float)mean;
+      p.rstd = (float)(1.0 / (sqrt(fmax(lc.sc->adv_sq / B - mean * mean, 0.0)) + 1e-8));
     }
     return p;
   }

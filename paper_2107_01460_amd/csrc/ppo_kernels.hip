@@ -408,8 +408,7 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
       lc.vf_coef = c.vf_coef; lc.clip_value = c.clip_value;
       if (c.normalize_adv) {
         const unsigned nb = (unsigned)std::min<int64_t>(1024, (Sa + 255) / 256);
-        hipLaunchKernelGGL(adv_stats_kernel, dim3(nb), dim3(256), 0, s, tr.adv, lc, w.sc, 0);
-        hipLaunchKernelGGL(adv_stats_kernel, dim3(nb), dim3(256), 0, s, tr.adv, lc, w.sc, 1);
+        hipLaunchKernelGGL(adv_stats_kernel, dim3(nb), dim3(256), 0, s, tr.adv, lc, w.sc);
       }
       // ---- actor
       const RowSrc Xa{tr.obs, d.D, rows, d.A, Sa};

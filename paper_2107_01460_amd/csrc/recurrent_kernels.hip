@@ -718,8 +718,7 @@ int32_t launch_ppo_update_recurrent(const marl_config& c, marl_traj tr, marl_rec
       lc.vf_coef = c.vf_coef; lc.clip_value = c.clip_value;
       if (c.normalize_adv) {
         const unsigned nb = (unsigned)std::min<int64_t>(1024, (TJ * d.A + 255) / 256);
-        hipLaunchKernelGGL(adv_stats_kernel, dim3(nb), dim3(256), 0, s, tr.adv, lc, w.sc, 0);
-        hipLaunchKernelGGL(adv_stats_kernel, dim3(nb), dim3(256), 0, s, tr.adv, lc, w.sc, 1);
+        hipLaunchKernelGGL(adv_stats_kernel, dim3(nb), dim3(256), 0, s, tr.adv, lc, w.sc);
       }
       {
         ActorLoss fn{lc, tr.action, tr.logp, tr.adv};
