@@ -14,6 +14,7 @@
 // staged in LDS with a 144-byte row pitch so that the 16-byte operand reads of eight consecutive rows fall into
 // eight different bank groups; results leave through an LDS-staged tile with 16-byte stores in both orientations.
 #pragma once
+#include <type_traits>
 #include "gemm.h"
 
 namespace marl {
@@ -97,27 +98,38 @@ __global__ void __launch_bounds__(256, 2) gemm_bf16_kernel(GemmBf16Args g) {
   const int nchunks = (int)((k_end - k_begin + BK - 1) / BK);
   const int rot = nchunks > 0 ? (int)((tm * 5u + tn * 3u + split) % (unsigned)nchunks) : 0;
   auto chunk_k = [&](int i) { return k_begin + (int64_t)((i + rot) % nchunks) * BK; };
-  auto fetch = [&](int i, uint4 (&ra)[4], uint4 (&rb)[4]) {
-    if (i >= nchunks) return;
-    const int64_t k0 = chunk_k(i);
+  // (the two register sets are named, never passed by reference: a set that is selected at run time, or handed to a
+  // helper through a reference, ends up in scratch memory, and a load whose destination is memory is waited for at once)
+  auto fetch = [&](int i, auto set) {
+    // past the end: the last chunk once more (an L2 hit, never staged) -- a branch here would make every wait in the
+    // loop a wait for all outstanding loads
+    const int64_t k0 = chunk_k(i < nchunks ? i : nchunks - 1);
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-      ra[p] = *reinterpret_cast<const uint4*>(arow[p] + k0);
-      rb[p] = *reinterpret_cast<const uint4*>(brow[p] + k0);
+      if constexpr (decltype(set)::value == 0) {
+        ra0[p] = *reinterpret_cast<const uint4*>(arow[p] + k0);
+        rb0[p] = *reinterpret_cast<const uint4*>(brow[p] + k0);
+      } else {
+        ra1[p] = *reinterpret_cast<const uint4*>(arow[p] + k0);
+        rb1[p] = *reinterpret_cast<const uint4*>(brow[p] + k0);
+      }
     }
   };
-  auto stage = [&](int buf, const uint4 (&ra)[4], const uint4 (&rb)[4]) {
+  auto stage = [&](int buf, auto set) {
     bf16_t* As = smem + buf * STAGE;
     bf16_t* Bs = As + BM * P;
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-      *reinterpret_cast<uint4*>(&As[(srow + 32 * p) * P + 8 * seg]) = ra[p];
-      *reinterpret_cast<uint4*>(&Bs[(srow + 32 * p) * P + 8 * seg]) = rb[p];
-    }
-    if (EPI == BEPI_ATOMIC && want_bsum) {
-#pragma unroll
-      for (int p = 0; p < 4; ++p) {
-        const uint32_t w[4] = {rb[p].x, rb[p].y, rb[p].z, rb[p].w};
+      uint4 va, vb;
+      if constexpr (decltype(set)::value == 0) {
+        va = ra0[p]; vb = rb0[p];
+      } else {
+        va = ra1[p]; vb = rb1[p];
+      }
+      *reinterpret_cast<uint4*>(&As[(srow + 32 * p) * P + 8 * seg]) = va;
+      *reinterpret_cast<uint4*>(&Bs[(srow + 32 * p) * P + 8 * seg]) = vb;
+      if (EPI == BEPI_ATOMIC && want_bsum) {
+        const uint32_t w[4] = {vb.x, vb.y, vb.z, vb.w};
 #pragma unroll
         for (int q = 0; q < 4; ++q) bsum[p] += __uint_as_float(w[q] << 16) + __uint_as_float(w[q] & 0xffff0000u);
       }
@@ -139,23 +151,27 @@ __global__ void __launch_bounds__(256, 2) gemm_bf16_kernel(GemmBf16Args g) {
         for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     }
   };
-  // one iteration: chunk at k0 sits in LDS stage `cur`; the next chunk goes from `ra/rb` into the other stage and
-  // the chunk three ahead is requested into the same registers
-  auto iteration = [&](int i, int cur, uint4 (&ra)[4], uint4 (&rb)[4]) {
-    __syncthreads();  // stage `cur` is complete; everybody is done reading the other one
-    if (i + 1 < nchunks) stage(cur ^ 1, ra, rb);
-    fetch(i + 3, ra, rb);
-    multiply(cur);
-  };
+  using Set0 = std::integral_constant<int, 0>;
+  using Set1 = std::integral_constant<int, 1>;
+  // one iteration: chunk i sits in LDS stage `cur`; chunk i + 1 goes from its register set into the other stage and
+  // chunk i + 3 is requested into the same registers.  Chunk j travels in set j & 1.
   if (nchunks > 0) {
-    fetch(0, ra0, rb0);
-    fetch(1, ra1, rb1);
-    stage(0, ra0, rb0);
-    fetch(2, ra0, rb0);
+    fetch(0, Set0{});
+    fetch(1, Set1{});
+    stage(0, Set0{});
+    fetch(2, Set0{});
   }
   for (int i = 0; i < nchunks; i += 2) {
-    iteration(i, 0, ra1, rb1);
-    if (i + 1 < nchunks) iteration(i + 1, 1, ra0, rb0);
+    __syncthreads();  // stage 0 is complete; everybody is done reading stage 1
+    if (i + 1 < nchunks) stage(1, Set1{});
+    fetch(i + 3, Set1{});
+    multiply(0);
+    if (i + 1 < nchunks) {
+      __syncthreads();
+      if (i + 2 < nchunks) stage(0, Set0{});
+      fetch(i + 4, Set0{});
+      multiply(1);
+    }
   }
   __syncthreads();  // the operand stages are free for the output tile
 
@@ -315,29 +331,29 @@ __global__ void __launch_bounds__(256, 1) gemm_bf16_big_kernel(GemmBf16Args g) {
   const int nchunks = (int)((k_end - k_begin + BK - 1) / BK);
   const int rot = nchunks > 0 ? (int)((tm * 5u + tn * 3u + split) % (unsigned)nchunks) : 0;
   auto chunk_k = [&](int i) { return k_begin + (int64_t)((i + rot) % nchunks) * BK; };
-  auto fetch = [&](int i, uint4 (&ra)[8], uint4 (&rb)[8]) {
+  // (the register set is named, not handed to these helpers through a reference: see gemm_bf16_kernel)
+  auto fetch = [&](int i) {
     if (i >= nchunks) return;
     const int64_t k0 = chunk_k(i);
 #pragma unroll
     for (int p = 0; p < 8; ++p) {
-      ra[p] = *reinterpret_cast<const uint4*>(arow[p] + k0);
-      rb[p] = *reinterpret_cast<const uint4*>(brow[p] + k0);
+      ra0[p] = *reinterpret_cast<const uint4*>(arow[p] + k0);
+      rb0[p] = *reinterpret_cast<const uint4*>(brow[p] + k0);
     }
   };
-  auto stage = [&](int buf, const uint4 (&ra)[8], const uint4 (&rb)[8]) {
+  auto stage = [&](int buf) {
     bf16_t* As = smem + buf * STAGE;
     bf16_t* Bs = As + BM * P;
 #pragma unroll
     for (int p = 0; p < 8; ++p) {
-      *reinterpret_cast<uint4*>(&As[(srow + 32 * p) * P + 8 * seg]) = ra[p];
-      *reinterpret_cast<uint4*>(&Bs[(srow + 32 * p) * P + 8 * seg]) = rb[p];
-    }
-    if (EPI == BEPI_ATOMIC && want_bsum) {
-#pragma unroll
-      for (int p = 0; p < 8; ++p) {
-        const uint32_t w[4] = {rb[p].x, rb[p].y, rb[p].z, rb[p].w};
-#pragma unroll
-        for (int q = 0; q < 4; ++q) bsum[p] += __uint_as_float(w[q] << 16) + __uint_as_float(w[q] & 0xffff0000u);
+      const uint4 va = ra0[p], vb = rb0[p];
+      *reinterpret_cast<uint4*>(&As[(srow + 32 * p) * P + 8 * seg]) = va;
+      *reinterpret_cast<uint4*>(&Bs[(srow + 32 * p) * P + 8 * seg]) = vb;
+      if (EPI == BEPI_ATOMIC && want_bsum) {
+        bsum[p] += (__uint_as_float(vb.x << 16) + __uint_as_float(vb.x & 0xffff0000u)) +
+                   (__uint_as_float(vb.y << 16) + __uint_as_float(vb.y & 0xffff0000u)) +
+                   (__uint_as_float(vb.z << 16) + __uint_as_float(vb.z & 0xffff0000u)) +
+                   (__uint_as_float(vb.w << 16) + __uint_as_float(vb.w & 0xffff0000u));
       }
     }
   };
@@ -358,15 +374,15 @@ __global__ void __launch_bounds__(256, 1) gemm_bf16_big_kernel(GemmBf16Args g) {
     }
   };
   if (nchunks > 0) {
-    fetch(0, ra0, rb0);
-    stage(0, ra0, rb0);
-    fetch(1, ra0, rb0);
+    fetch(0);
+    stage(0);
+    fetch(1);
   }
   int cur = 0;
   for (int i = 0; i < nchunks; ++i, cur ^= 1) {
     __syncthreads();  // stage `cur` is complete; everybody is done reading the other one
-    if (i + 1 < nchunks) stage(cur ^ 1, ra0, rb0);
-    fetch(i + 2, ra0, rb0);
+    if (i + 1 < nchunks) stage(cur ^ 1);
+    fetch(i + 2);
     multiply(cur);
   }
   __syncthreads();  // the operand stages are free for the output tile
