@@ -172,8 +172,10 @@ static int32_t forward_rows(const marl_config& c, const float* eff, const float*
       const NetOffsets o = padded_offsets(param_map(d), 1);
       const Bf16NetWeights bw = effective_bf16_weights(c, eff, 1);
       const int64_t Sc = d.central ? n_rows : S;
-      pack_obs_bf16(RowSrc{obs, d.Dc, nullptr, 1, Sc}, Sc, d.Dc, bw.Dp, Sc, w.xbc, nullptr, s);
-      mlp_hidden_forward_bf16(w.xbc, Sc, Sc, d.Hc, bw, eff + o.b1, eff + o.b2, w.bh1c, nullptr, w.bh2c, s);
+      // IPPO: the critic reads the rows packed for the actor (same rows, same width)
+      const bool shared = want_actor && !d.central;
+      if (!shared) pack_obs_bf16(RowSrc{obs, d.Dc, nullptr, 1, Sc}, Sc, d.Dc, bw.Dp, Sc, w.xbc, nullptr, s);
+      mlp_hidden_forward_bf16(shared ? w.xba : w.xbc, Sc, Sc, d.Hc, bw, eff + o.b1, eff + o.b2, w.bh1c, nullptr, w.bh2c, s);
       launch_critic_head_rollout(w.bh2c, Sc, d.Hc, eff + o.W3, eff + o.b3, value_out, d.central ? d.A : 1, s);
     }
     return launch_status();

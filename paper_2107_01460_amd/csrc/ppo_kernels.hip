@@ -49,20 +49,37 @@ __global__ void __launch_bounds__(256) loss_head_bf16_kernel(const bf16_t* __res
   }
   const int vec_per_row = H / 8, per_grp = H / 4;
   const int64_t ntiles = (S + kHeadTile - 1) / kHeadTile;
+  // A tile travels global -> registers -> LDS: all of a thread's 16-byte pieces are requested at once, and the next
+  // tile's are requested before this tile's arithmetic, so that no load is waited for on its own.
+  constexpr int NV = kHeadTile * (HMAX / 8) / 256;  // pieces per thread at the full width
+  uint4 tv[NV];
+  auto fetch_tile = [&](int64_t tile) {
+    const int64_t s0 = tile * kHeadTile;
+#pragma unroll
+    for (int q = 0; q < NV; ++q) {
+      const int f = tid + 256 * q;
+      const int r = f / vec_per_row, c8 = f - r * vec_per_row;
+      tv[q] = make_uint4(0u, 0u, 0u, 0u);
+      if (f < kHeadTile * vec_per_row && s0 + r < S) tv[q] = *reinterpret_cast<const uint4*>(&H2[(s0 + r) * H + 8 * c8]);
+    }
+  };
+  if ((int64_t)blockIdx.x < ntiles) fetch_tile(blockIdx.x);
   for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
     const int64_t s0 = tile * kHeadTile;
     __syncthreads();  // the previous tile has been consumed (and W3s is in place)
-    for (int f = tid; f < kHeadTile * vec_per_row; f += 256) {
+#pragma unroll
+    for (int q = 0; q < NV; ++q) {
+      const int f = tid + 256 * q;
       const int r = f / vec_per_row, c8 = f - r * vec_per_row;
-      uint4 v = make_uint4(0u, 0u, 0u, 0u);
-      if (s0 + r < S) v = *reinterpret_cast<const uint4*>(&H2[(s0 + r) * H + 8 * c8]);
-      *reinterpret_cast<uint4*>(&T[r * PITCH + 8 * c8]) = v;
+      if (f < kHeadTile * vec_per_row) *reinterpret_cast<uint4*>(&T[r * PITCH + 8 * c8]) = tv[q];
     }
     __syncthreads();
+    if (tile + gridDim.x < ntiles) fetch_tile(tile + gridDim.x);
     {  // output layer: thread -> sample `lane`, quarter `grp` of the hidden units
       float part[NOUT];
 #pragma unroll
       for (int k = 0; k < NOUT; ++k) part[k] = 0.f;
+#pragma unroll 4
       for (int i = grp * per_grp; i < (grp + 1) * per_grp; i += 8) {
         const uint4 hv = *reinterpret_cast<const uint4*>(&T[lane * PITCH + i]);
         const uint32_t hw[4] = {hv.x, hv.y, hv.z, hv.w};
@@ -109,7 +126,7 @@ __global__ void __launch_bounds__(256) loss_head_bf16_kernel(const bf16_t* __res
     }
     __syncthreads();
     // gW3[i][k] += sum_s h2[s][i] dl[s][k]: thread -> hidden units tid, tid + 256
-#pragma unroll 4
+#pragma unroll 8
     for (int s = 0; s < kHeadTile; ++s) {
       const float4 d0 = *reinterpret_cast<const float4*>(&dls[s * 8]);
       float dv[8] = {d0.x, d0.y, d0.z, d0.w, 0.f, 0.f, 0.f, 0.f};
@@ -326,9 +343,9 @@ void mlp_backward(const RowSrc& X, int64_t S, int Din, int H, const float* W2, c
 template <int NOUT, class LossFn>
 void train_net_bf16(const RowSrc& X, int64_t S, int Din, int H, const Bf16NetWeights& bw, const float* eff,
                     const NetOffsets& o, float* grad, const NetOffsets& go, const LossFn& fn, float* dl,
-                    const UpdateWsView& w, hipStream_t s) {
+                    const UpdateWsView& w, bool packed, hipStream_t s) {
   const int64_t Sp = round_up64(S);
-  pack_obs_bf16(X, S, Din, bw.Dp, Sp, w.xb, w.xbT, s);
+  if (!packed) pack_obs_bf16(X, S, Din, bw.Dp, Sp, w.xb, w.xbT, s);  // packed: the previous network left these very rows there
   mlp_hidden_forward_bf16(w.xb, S, Sp, H, bw, eff + o.b1, eff + o.b2, w.bh1, w.bh1T, w.bh2, s);
   const unsigned nb = (unsigned)std::min<int64_t>(512, (S + kHeadTile - 1) / kHeadTile);
   hipLaunchKernelGGL((loss_head_bf16_kernel<NOUT, LossFn, 512>), dim3(nb), dim3(256), 0, s, w.bh2, S, H, eff + o.W3,
@@ -416,7 +433,7 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
       {
         ActorLoss fn{lc, tr.action, tr.logp, tr.adv};
         if (d.bf16) {
-          train_net_bf16<kActions>(Xa, Sa, d.D, d.Ha, effective_bf16_weights(c, eff, 0), eff, oa, w.grad, ga, fn, w.dla, w, s);
+          train_net_bf16<kActions>(Xa, Sa, d.D, d.Ha, effective_bf16_weights(c, eff, 0), eff, oa, w.grad, ga, fn, w.dla, w, false, s);
         } else if (fused_train_supported(d.Ha, d.D)) {
           FusedTrainArgs ta{};
           ta.X = Xa; ta.S = Sa; ta.Din = d.D; ta.px = fused_train_px(d.D);
@@ -450,7 +467,8 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
       {
         CriticLoss fn{lc, tr.ret, tr.value, d.central ? d.A : 1};
         if (d.bf16) {
-          train_net_bf16<1>(Xc, Sc, d.Dc, d.Hc, effective_bf16_weights(c, eff, 1), eff, oc, w.grad, gc, fn, w.dlc, w, s);
+          // IPPO: the critic reads the rows the actor has just packed (same rows, same width)
+          train_net_bf16<1>(Xc, Sc, d.Dc, d.Hc, effective_bf16_weights(c, eff, 1), eff, oc, w.grad, gc, fn, w.dlc, w, !d.central, s);
         } else if (fused_train_supported(d.Hc, d.Dc)) {
           FusedTrainArgs ta{};
           ta.X = Xc; ta.S = Sc; ta.Din = d.Dc; ta.px = fused_train_px(d.Dc);
