@@ -272,8 +272,13 @@ int64_t pick_k_split(int64_t K, int64_t tiles_mn) {
 // Forward and loss of one 256-wide fp32 network with each layer's weights resident in registers: h1 goes to HBM,
 // the second hidden activation never does, `dz2` gets dL/d(pre-activation of layer 2), the output layer's gradient
 // and the loss statistics are accumulated.
-inline bool wreg_forward_supported(const RowSrc& X, int Din, int H) {
-  return H == kWregN && wreg_gemm_supported<WREG_BIAS_TANH>(X, Din, H);
+// The register-resident kernels pay for loading a whole weight matrix per workgroup (and for one round of atomics per
+// workgroup in the transposed product): they win from about four 64-row tiles per workgroup on, i.e. 65 536 rows on
+// 256 compute units (measured at the shape of workload 3: 16 384 rows 28.1 against 24.7 ms per step with the LDS-tiled
+// kernels, 65 536 rows equal, 262 144 rows 134 against 152 ms).
+inline bool wreg_worthwhile(int64_t S) { return S >= 256 * kWregBM * 4; }
+inline bool wreg_forward_supported(const RowSrc& X, int64_t S, int Din, int H) {
+  return H == kWregN && wreg_worthwhile(S) && wreg_gemm_supported<WREG_BIAS_TANH>(X, Din, H);
 }
 template <int NOUT, class LossFn>
 int32_t train_forward_wreg(const RowSrc& X, int64_t S, int Din, const float* W1, const float* b1, const float* W2,
@@ -311,7 +316,7 @@ void mlp_backward(const RowSrc& X, int64_t S, int Din, int H, const float* W2, c
     launch_gemm<GEMM_TN, EPI_ATOMIC_ADD>(g, s);
   }
   const RowSrc dz2_rows{h2, H, nullptr, 1, S};
-  if (!bf16 && wreg_gemm_supported<WREG_DTANH>(dz2_rows, H, H)) {
+  if (!bf16 && wreg_worthwhile(S) && wreg_gemm_supported<WREG_DTANH>(dz2_rows, H, H)) {
     // dz1 = (dz2 W2^T) * (1 - h1^2) with W2 resident in registers
     WregArgs g{};
     g.A = dz2_rows; g.S = S; g.Kin = H; g.B = W2; g.ldb = H; g.b_kcont = 1; g.C = dz1; g.aux = h1;
@@ -324,7 +329,7 @@ void mlp_backward(const RowSrc& X, int64_t S, int Din, int H, const float* W2, c
     g.M = S; g.N = H; g.K = H; g.round_bf16 = bf16;
     launch_gemm<GEMM_NT, EPI_DTANH>(g, s);
   }
-  if (!bf16 && wacc_gemm_supported(X, Din, H)) {  // gW1 += X^T dz1, gb1 += column sums, the gradient resident in registers
+  if (!bf16 && wreg_worthwhile(S) && wacc_gemm_supported(X, Din, H)) {  // gW1 += X^T dz1, gb1 += column sums, the gradient resident in registers
     WaccArgs g{};
     g.A = X; g.S = S; g.B = dz1; g.C = gW1; g.colsum = gb1;
     TimedLaunch timed(KC_GEMM_TN, 2.0 * (double)S * Din * H, s);
@@ -479,7 +484,7 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
           const int32_t rc = launch_fused_train<1>(d.Hc, ta, fn, s);
           if (rc != MARL_OK) return rc;
         } else {
-          if (wreg_forward_supported(Xc, d.Dc, d.Hc)) {
+          if (wreg_forward_supported(Xc, Sc, d.Dc, d.Hc)) {
             const int32_t rc = train_forward_wreg<1>(Xc, Sc, d.Dc, eff + oc.W1, eff + oc.b1, eff + oc.W2, eff + oc.b2,
                                                      eff + oc.W3, eff + oc.b3, w.h1c, w.h2c, w.grad + gc.W3,
                                                      w.grad + gc.b3, w.sc->acc, fn, s);

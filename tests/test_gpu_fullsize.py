@@ -146,13 +146,18 @@ def tiled_perm(cfg_full, cfg_small, perm_small, seed):
     return out
 
 
-@pytest.mark.parametrize("k", [1, 2, 3, 4, 5])
-def test_full_size_ppo_update_tiled(M, orc, k):
+# The last case is workload 3 at 4097 = 17 x 241 environments: minibatches of 65 552 rows, the smallest size at which
+# the update takes the register-resident critic kernels, with a ragged last tile (65 552 = 1024 x 64 + 16).
+@pytest.mark.parametrize("k,n_envs,tile", [(1, None, None), (2, None, None), (3, None, None), (4, None, None),
+                                           (5, None, None), (3, 4097, 17)])
+def test_full_size_ppo_update_tiled(M, orc, k, n_envs, tile):
     cfg = dict(W.CONFIGS[k - 1])
+    if n_envs is not None:
+        cfg["n_envs"] = n_envs
     if k == 4:
         cfg["n_epochs"] = 2   # oracle time; the launch configuration of a minibatch does not depend on it
     N, T, E, Mb = cfg["n_envs"], cfg["rollout_len"], cfg["n_epochs"], cfg["n_minibatches"]
-    n_s = N_ORACLE[k]
+    n_s = tile if tile is not None else N_ORACLE[k]
     K = N // n_s
     assert N % n_s == 0 and (T * n_s) % Mb == 0
     cs = W.scaled(cfg, n_envs=n_s)
