@@ -41,7 +41,30 @@ struct FusedTrainArgs {
   const float *W1s, *W2s, *W2Ts;             // operand-order copies: (k, n) at ((k / 4) * H + n) * 4 + k % 4; W1s zero-padded to 16-row groups
   float *gW1, *gb1, *gW2, *gb2, *gW3, *gb3;  // gradient blocks, accumulated with atomics
   float* stats;                              // 5 floats, atomics
+  // Two-stage reduction of the gradient (nullable): the six blocks above are one contiguous range of `gcount` floats
+  // starting at gW1; workgroup b accumulates into its own copy of that range at partial + b * gcount (which it zeroes
+  // first) and reduce_partials_kernel adds the copies to the gradient afterwards.  Several hundred workgroups adding
+  // to the same few hundred cache lines at the same moment is what the direct atomics cost: 60-180 us per launch.
+  float* partial;
+  int64_t gcount;
 };
+
+// grad[i] += sum_b partial[b * count + i]
+static __global__ void __launch_bounds__(256) reduce_partials_kernel(const float* __restrict__ partial, int nblocks, int64_t count,
+                                                                     float* __restrict__ grad) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= count) return;
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  int b = 0;
+  for (; b + 4 <= nblocks; b += 4) {
+    s0 += partial[(int64_t)b * count + i];
+    s1 += partial[(int64_t)(b + 1) * count + i];
+    s2 += partial[(int64_t)(b + 2) * count + i];
+    s3 += partial[(int64_t)(b + 3) * count + i];
+  }
+  for (; b < nblocks; ++b) s0 += partial[(int64_t)b * count + i];
+  grad[i] += (s0 + s1) + (s2 + s3);
+}
 
 // acc[q] += A^T B_q over the samples kb0 .. kb0 + klen of a row tile held in LDS: A column block at Ap (pitch pa),
 // B column blocks at Bp + 32 q (pitch pb).  The operands of the next k step are read before the MFMAs of the
@@ -141,6 +164,17 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lo = lane & 31, hi = lane >> 5;
   const int mt = wave / NTN, nt = wave % NTN;  // forward / dz tile of this wavefront
+  // where this workgroup's gradient goes: the gradient itself, or its own zeroed copy of the range (ordered before
+  // the flush at the end by the barriers of the tile loop)
+  float* const gout = a.partial != nullptr ? a.partial + (int64_t)blockIdx.x * a.gcount : a.gW1;
+  if (a.partial != nullptr)
+    for (int64_t i = tid; i < a.gcount; i += NT) gout[i] = 0.f;
+  float* const gW1 = gout;
+  float* const gb1 = gout + (a.gb1 - a.gW1);
+  float* const gW2 = gout + (a.gW2 - a.gW1);
+  float* const gb2 = gout + (a.gb2 - a.gW1);
+  float* const gW3 = gout + (a.gW3 - a.gW1);
+  float* const gb3 = gout + (a.gb3 - a.gW1);
   const int px = a.px;
   const int MT1 = (a.Din + 31) / 32;           // 32-row tiles of dW1
   const int tiles1 = MT1 * NTN;
@@ -414,7 +448,7 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int i = it * 32 + 8 * (r / 4) + 4 * hi + (r % 4), j = (jt + q) * 32 + lo;
-        atomicAdd(&a.gW2[i * H + j], acc2[q][r]);
+        atomicAdd(&gW2[i * H + j], acc2[q][r]);
       }
   }
 #pragma unroll
@@ -425,25 +459,25 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int d = dt * 32 + 8 * (r / 4) + 4 * hi + (r % 4), j = jt * 32 + lo;
-        if (d < a.Din) atomicAdd(&a.gW1[d * H + j], acc1[q][r]);
+        if (d < a.Din) atomicAdd(&gW1[d * H + j], acc1[q][r]);
       }
     }
   }
   if (hi == 0) {
-    atomicAdd(&a.gb1[nt * 32 + lo], gb1r);
-    atomicAdd(&a.gb2[nt * 32 + lo], gb2r);
+    atomicAdd(&gb1[nt * 32 + lo], gb1r);
+    atomicAdd(&gb2[nt * 32 + lo], gb2r);
   }
   {
     const int i = tid % H;
 #pragma unroll
-    for (int k = 0; k < NOUT; ++k) atomicAdd(&a.gW3[i * NOUT + k], gw[k]);
+    for (int k = 0; k < NOUT; ++k) atomicAdd(&gW3[i * NOUT + k], gw[k]);
   }
   if (tid < (BM < 64 ? 64 : BM)) {  // whole wavefronts; lanes past BM hold zeros
 #pragma unroll
     for (int k = 0; k < NOUT; ++k) {
       float v = gb[k];
       for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-      if (lane == 0) atomicAdd(&a.gb3[k], v);
+      if (lane == 0) atomicAdd(&gb3[k], v);
     }
 #pragma unroll
     for (int k = 0; k < 5; ++k) {
@@ -476,8 +510,14 @@ inline int32_t launch_fused_train_inst(const FusedTrainArgs& a, const LossFn& fn
   const int64_t tiles = (a.S + BM - 1) / BM;
   const unsigned grid = (unsigned)std::min<int64_t>(tiles, NW == 4 ? 512 : 256);  // resident workgroups: two per CU with four wavefronts
   hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * NW), bytes, s, a, fn);
+  if (a.partial != nullptr)
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((a.gcount + 255) / 256)), dim3(256), 0, s, a.partial, (int)grid,
+                       a.gcount, a.gW1);
   return launch_status();
 }
+
+// Workgroups a launch can have (the copies of the gradient range the caller provides room for).
+constexpr int kFusedTrainMaxGrid = 512;
 
 template <int NOUT, class LossFn>
 inline int32_t launch_fused_train(int H, const FusedTrainArgs& a, const LossFn& fn, hipStream_t s) {

@@ -211,6 +211,7 @@ struct UpdateWsView {
   int32_t* ident;
   float *h1a, *h2a, *dz1a, *dla;
   float *h1c, *h2c, *dz1c, *dlc;
+  float* partial;  // per-workgroup copies of one network's gradient (two-stage reduction of the fused training kernel)
   // bf16 configuration: one set of activation buffers, used by the actor and then by the critic
   bf16_t *xb, *xbT, *bh1, *bh1T, *bh2, *dz2T, *dz1T;
 };
@@ -244,6 +245,10 @@ UpdateWsView carve_update_ws(const marl_config& c, void* ws, int64_t* total) {
     v.h2c = (float*)take(Scp * d.Hc * 4);
     v.dz1c = (float*)take(Scp * d.Hc * 4);
     v.dlc = (float*)take(Sc * 4);
+    int64_t pmax = 0;
+    if (fused_train_supported(d.Ha, d.D)) pmax = std::max<int64_t>(pmax, d.Pa);
+    if (fused_train_supported(d.Hc, d.Dc)) pmax = std::max<int64_t>(pmax, d.P - d.Pa);
+    v.partial = pmax > 0 ? (float*)take((int64_t)kFusedTrainMaxGrid * pmax * 4) : nullptr;
   } else {
     const int64_t Sp = round_up64(std::max(Sa, Sc));
     const int64_t Dp = round_up64(std::max(d.D, d.Dc)), H = std::max(d.Ha, d.Hc);
@@ -446,6 +451,7 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
           ta.W1s = eff + pm.sw_w1[0]; ta.W2s = eff + pm.sw_w2[0]; ta.W2Ts = eff + pm.sw_w2t[0];
           ta.b3 = eff + oa.b3; ta.gW1 = w.grad + ga.W1; ta.gb1 = w.grad + ga.b1; ta.gW2 = w.grad + ga.W2;
           ta.gb2 = w.grad + ga.b2; ta.gW3 = w.grad + ga.W3; ta.gb3 = w.grad + ga.b3; ta.stats = w.sc->acc;
+          ta.partial = w.partial; ta.gcount = d.Pa;
           const int32_t rc = launch_fused_train<kActions>(d.Ha, ta, fn, s);
           if (rc != MARL_OK) return rc;
         } else {
@@ -481,6 +487,7 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
           ta.W1s = eff + pm.sw_w1[1]; ta.W2s = eff + pm.sw_w2[1]; ta.W2Ts = eff + pm.sw_w2t[1];
           ta.b3 = eff + oc.b3; ta.gW1 = w.grad + gc.W1; ta.gb1 = w.grad + gc.b1; ta.gW2 = w.grad + gc.W2;
           ta.gb2 = w.grad + gc.b2; ta.gW3 = w.grad + gc.W3; ta.gb3 = w.grad + gc.b3; ta.stats = w.sc->acc;
+          ta.partial = w.partial; ta.gcount = d.P - d.Pa;
           const int32_t rc = launch_fused_train<1>(d.Hc, ta, fn, s);
           if (rc != MARL_OK) return rc;
         } else {
