@@ -49,23 +49,6 @@ struct FusedTrainArgs {
   int64_t gcount;
 };
 
-// grad[i] += sum_b partial[b * count + i]
-static __global__ void __launch_bounds__(256) reduce_partials_kernel(const float* __restrict__ partial, int nblocks, int64_t count,
-                                                                     float* __restrict__ grad) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= count) return;
-  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-  int b = 0;
-  for (; b + 4 <= nblocks; b += 4) {
-    s0 += partial[(int64_t)b * count + i];
-    s1 += partial[(int64_t)(b + 1) * count + i];
-    s2 += partial[(int64_t)(b + 2) * count + i];
-    s3 += partial[(int64_t)(b + 3) * count + i];
-  }
-  for (; b < nblocks; ++b) s0 += partial[(int64_t)b * count + i];
-  grad[i] += (s0 + s1) + (s2 + s3);
-}
-
 // acc[q] += A^T B_q over the samples kb0 .. kb0 + klen of a row tile held in LDS: A column block at Ap (pitch pa),
 // B column blocks at Bp + 32 q (pitch pb).  The operands of the next k step are read before the MFMAs of the
 // current one are issued, so the LDS latency hides behind the matrix pipe even with one wavefront per SIMD.
@@ -510,9 +493,7 @@ inline int32_t launch_fused_train_inst(const FusedTrainArgs& a, const LossFn& fn
   const int64_t tiles = (a.S + BM - 1) / BM;
   const unsigned grid = (unsigned)std::min<int64_t>(tiles, NW == 4 ? 512 : 256);  // resident workgroups: two per CU with four wavefronts
   hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * NW), bytes, s, a, fn);
-  if (a.partial != nullptr)
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((a.gcount + 255) / 256)), dim3(256), 0, s, a.partial, (int)grid,
-                       a.gcount, a.gW1);
+  if (a.partial != nullptr) launch_reduce_partials(a.partial, (int)grid, a.gcount, a.gW1, s);
   return launch_status();
 }
 

@@ -61,6 +61,32 @@ struct GemmArgs {
   int round_bf16;        // round stored results to bf16 precision (kept in fp32 storage)
 };
 
+// The kernels that finish with one partial result per workgroup (the fused training kernel, the accumulator-resident
+// transposed product) store those with plain stores and add them up here: a few hundred workgroups adding to the same
+// cache lines with atomics at the same moment queue up at the L2 (60-180 us per launch).  The split-k tile kernel below
+// keeps its atomics: its workgroups finish spread over time, and the two-stage form measured no faster (324 against
+// 315 us).
+
+// out[i] += sum_b partial[b * count + i]
+static __global__ void __launch_bounds__(256) reduce_partials_kernel(const float* __restrict__ partial, int nblocks, int64_t count,
+                                                                     float* __restrict__ out) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= count) return;
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  int b = 0;
+  for (; b + 4 <= nblocks; b += 4) {
+    s0 += partial[(int64_t)b * count + i];
+    s1 += partial[(int64_t)(b + 1) * count + i];
+    s2 += partial[(int64_t)(b + 2) * count + i];
+    s3 += partial[(int64_t)(b + 3) * count + i];
+  }
+  for (; b < nblocks; ++b) s0 += partial[(int64_t)b * count + i];
+  out[i] += (s0 + s1) + (s2 + s3);
+}
+inline void launch_reduce_partials(const float* partial, int nblocks, int64_t count, float* out, hipStream_t s) {
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s, partial, nblocks, count, out);
+}
+
 // tanh(x) = 1 - 2 / (e^{2x} + 1) with the hardware exp2 and reciprocal: absolute error ~1e-7 (the values feed
 // sums of O(1) activations, so an absolute bound is what the 1e-4 tolerance on the outputs needs); saturates
 // cleanly to +-1 when e^{2x} overflows or underflows.

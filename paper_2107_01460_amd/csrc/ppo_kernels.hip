@@ -212,6 +212,7 @@ struct UpdateWsView {
   float *h1a, *h2a, *dz1a, *dla;
   float *h1c, *h2c, *dz1c, *dlc;
   float* partial;  // per-workgroup copies of one network's gradient (two-stage reduction of the fused training kernel)
+  float* partial_w1;
   // bf16 configuration: one set of activation buffers, used by the actor and then by the critic
   bf16_t *xb, *xbT, *bh1, *bh1T, *bh2, *dz2T, *dz1T;
 };
@@ -249,6 +250,8 @@ UpdateWsView carve_update_ws(const marl_config& c, void* ws, int64_t* total) {
     if (fused_train_supported(d.Ha, d.D)) pmax = std::max<int64_t>(pmax, d.Pa);
     if (fused_train_supported(d.Hc, d.Dc)) pmax = std::max<int64_t>(pmax, d.P - d.Pa);
     v.partial = pmax > 0 ? (float*)take((int64_t)kFusedTrainMaxGrid * pmax * 4) : nullptr;
+    // ... and of the first-layer gradient of the 256-wide critic (accumulator-resident transposed product)
+    v.partial_w1 = (d.Hc == kWregN && d.Dc == 300) ? (float*)take((int64_t)kWaccMaxGrid * (300 + 1) * kWregN * 4) : nullptr;
   } else {
     const int64_t Sp = round_up64(std::max(Sa, Sc));
     const int64_t Dp = round_up64(std::max(d.D, d.Dc)), H = std::max(d.Ha, d.Hc);
@@ -307,7 +310,7 @@ int32_t train_forward_wreg(const RowSrc& X, int64_t S, int Din, const float* W1,
 template <int NOUT>
 void mlp_backward(const RowSrc& X, int64_t S, int Din, int H, const float* W2, const float* W3, float* h1, float* h2,
                   float* dz1, const float* dl, float* gW1, float* gb1, float* gW2, float* gb2, bool bf16,
-                  bool dz2_ready, hipStream_t s) {
+                  bool dz2_ready, float* wacc_partial, hipStream_t s) {
   if (!dz2_ready) {
     const int cb = std::min(H, 256), rpb = 256;
     dim3 grid((unsigned)((S + rpb - 1) / rpb), (unsigned)((H + cb - 1) / cb));
@@ -337,6 +340,7 @@ void mlp_backward(const RowSrc& X, int64_t S, int Din, int H, const float* W2, c
   if (!bf16 && wreg_worthwhile(S) && wacc_gemm_supported(X, Din, H)) {  // gW1 += X^T dz1, gb1 += column sums, the gradient resident in registers
     WaccArgs g{};
     g.A = X; g.S = S; g.B = dz1; g.C = gW1; g.colsum = gb1;
+    g.partial = (gb1 == gW1 + (int64_t)Din * H) ? wacc_partial : nullptr;  // the bias gradient directly follows the weight gradient
     TimedLaunch timed(KC_GEMM_TN, 2.0 * (double)S * Din * H, s);
     launch_wacc_gemm(g, Din, s);
   } else {  // gW1 += X^T dz1
@@ -469,7 +473,7 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
                                eff + oa.W3, eff + oa.b3, fn, w.dla, w.grad + ga.W3, w.grad + ga.b3, w.sc, 0.f);
           }
           mlp_backward<kActions>(Xa, Sa, d.D, d.Ha, eff + oa.W2, eff + oa.W3, w.h1a, w.h2a, w.dz1a, w.dla, w.grad + ga.W1,
-                                 w.grad + ga.b1, w.grad + ga.W2, w.grad + ga.b2, d.bf16, fused_a, s);
+                                 w.grad + ga.b1, w.grad + ga.W2, w.grad + ga.b2, d.bf16, fused_a, nullptr, s);
         }
       }
       // ---- critic
@@ -510,7 +514,7 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
                                eff + oc.b3, fn, w.dlc, w.grad + gc.W3, w.grad + gc.b3, w.sc, 0.f);
           }
           mlp_backward<1>(Xc, Sc, d.Dc, d.Hc, eff + oc.W2, eff + oc.W3, w.h1c, w.h2c, w.dz1c, w.dlc, w.grad + gc.W1,
-                          w.grad + gc.b1, w.grad + gc.W2, w.grad + gc.b2, d.bf16, fused_c, s);
+                          w.grad + gc.b1, w.grad + gc.W2, w.grad + gc.b2, d.bf16, fused_c, w.partial_w1, s);
         }
       }
       // ---- clip + Adam

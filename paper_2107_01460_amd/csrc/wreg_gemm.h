@@ -479,7 +479,14 @@ struct WaccArgs {
   const float* B;  // [S][256]
   float* C;        // [MIN][256], accumulated
   float* colsum;   // nullable [256]: column sums of B, accumulated
+  // Two-stage reduction (nullable): workgroup b stores its partial results -- MIN x 256 of C, then the 256 column sums --
+  // at partial + b * (MIN + 1) * 256 with plain stores, and the caller adds the copies up afterwards
+  // (reduce_partials_kernel); colsum must then directly follow C in memory.  Without it every workgroup adds to C with
+  // atomics, and a few hundred workgroups doing that to the same cache lines at the same moment queue up at the L2.
+  float* partial;
 };
+
+constexpr int kWaccMaxGrid = 256;  // workgroups of a launch (the copies a caller's `partial` has room for)
 
 template <int MIN, int WM>
 struct WaccShape {
@@ -622,7 +629,10 @@ __global__ void __launch_bounds__(256 * WM, 1) wacc_gemm_kernel(WaccArgs a) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int m = 32 * (MTW * wm + mi) + 8 * (r / 4) + 4 * hi + (r % 4);
-        if (m < MIN) atomicAdd(&a.C[m * kWregN + 64 * wn + 32 * jn + lo], acc[mi][jn][r]);
+        if (m < MIN) {
+          if (a.partial != nullptr) a.partial[(int64_t)blockIdx.x * (MIN + 1) * kWregN + m * kWregN + 64 * wn + 32 * jn + lo] = acc[mi][jn][r];
+          else atomicAdd(&a.C[m * kWregN + 64 * wn + 32 * jn + lo], acc[mi][jn][r]);
+        }
       }
   if (a.colsum != nullptr) {
     float4* red = reinterpret_cast<float4*>(Bs);  // the loop ended with a barrier
@@ -635,8 +645,12 @@ __global__ void __launch_bounds__(256 * WM, 1) wacc_gemm_kernel(WaccArgs a) {
         const float4 o = red[tid + 64 * q];
         v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
       }
-      float* dst = a.colsum + 4 * tid;
-      atomicAdd(dst + 0, v.x); atomicAdd(dst + 1, v.y); atomicAdd(dst + 2, v.z); atomicAdd(dst + 3, v.w);
+      if (a.partial != nullptr) {
+        *reinterpret_cast<float4*>(a.partial + (int64_t)blockIdx.x * (MIN + 1) * kWregN + MIN * kWregN + 4 * tid) = v;
+      } else {
+        float* dst = a.colsum + 4 * tid;
+        atomicAdd(dst + 0, v.x); atomicAdd(dst + 1, v.y); atomicAdd(dst + 2, v.z); atomicAdd(dst + 3, v.w);
+      }
     }
   }
 }
@@ -652,7 +666,9 @@ inline int32_t launch_wacc_gemm_inst(const WaccArgs& a, hipStream_t s) {
     configured = true;
   }
   const int64_t tiles = (a.S + Sh::BS - 1) / Sh::BS;
-  hipLaunchKernelGGL(kern, dim3((unsigned)std::min<int64_t>(tiles, 256)), dim3(Sh::NT), Sh::lds_bytes, s, a);
+  const unsigned grid = (unsigned)std::min<int64_t>(tiles, kWaccMaxGrid);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(Sh::NT), Sh::lds_bytes, s, a);
+  if (a.partial != nullptr) launch_reduce_partials(a.partial, (int)grid, (int64_t)(MIN + 1) * kWregN, a.C, s);  // C and the column sums behind it
   return MARL_OK;
 }
 
