@@ -30,7 +30,9 @@ template <int NOUT, class LossFn, int HMAX>
 __global__ void __launch_bounds__(256) loss_head_bf16_kernel(const bf16_t* __restrict__ H2, int64_t S, int H,
                                                              const float* __restrict__ W3, const float* __restrict__ b3,
                                                              LossFn fn, float* __restrict__ dl_out, float* __restrict__ gW3,
-                                                             float* __restrict__ gb3, Scalars* sc) {
+                                                             float* __restrict__ gb3, Scalars* sc, float* __restrict__ partial) {
+  // partial (nullable): this workgroup's W3 / b3 gradient goes to partial + blockIdx.x * (H * NOUT + NOUT) with plain
+  // stores and is added to gW3 (with gb3 directly behind it) by the reduction kernel afterwards
   constexpr int PITCH = HMAX + 8;  // elements; an odd number of 16-byte units, so row-per-lane 16-byte reads spread over the banks
   __shared__ __attribute__((aligned(16))) bf16_t T[kHeadTile * PITCH];
   __shared__ __attribute__((aligned(16))) float W3s[HMAX * NOUT];
@@ -148,7 +150,10 @@ __global__ void __launch_bounds__(256) loss_head_bf16_kernel(const bf16_t* __res
     const int i = tid + 256 * u;
     if (i < H) {
 #pragma unroll
-      for (int k = 0; k < NOUT; ++k) atomicAdd(&gW3[(int64_t)i * NOUT + k], gw[u][k]);
+      for (int k = 0; k < NOUT; ++k) {
+        if (partial != nullptr) partial[(int64_t)blockIdx.x * (H * NOUT + NOUT) + (int64_t)i * NOUT + k] = gw[u][k];
+        else atomicAdd(&gW3[(int64_t)i * NOUT + k], gw[u][k]);
+      }
     }
   }
   if (tid < kHeadTile) {  // one wavefront
@@ -156,7 +161,10 @@ __global__ void __launch_bounds__(256) loss_head_bf16_kernel(const bf16_t* __res
     for (int k = 0; k < NOUT; ++k) {
       float v = gb[k];
       for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-      if (tid == 0) atomicAdd(&gb3[k], v);
+      if (tid == 0) {
+        if (partial != nullptr) partial[(int64_t)blockIdx.x * (H * NOUT + NOUT) + (int64_t)H * NOUT + k] = v;
+        else atomicAdd(&gb3[k], v);
+      }
     }
 #pragma unroll
     for (int k = 0; k < 5; ++k) {
@@ -213,6 +221,7 @@ struct UpdateWsView {
   float *h1c, *h2c, *dz1c, *dlc;
   float* partial;  // per-workgroup copies of one network's gradient (two-stage reduction of the fused training kernel)
   float* partial_w1;
+  float* partial_head;  // bf16 configuration: per-workgroup W3 / b3 gradients of the output-layer kernel
   // bf16 configuration: one set of activation buffers, used by the actor and then by the critic
   bf16_t *xb, *xbT, *bh1, *bh1T, *bh2, *dz2T, *dz1T;
 };
@@ -264,6 +273,7 @@ UpdateWsView carve_update_ws(const marl_config& c, void* ws, int64_t* total) {
     v.bh2 = (bf16_t*)take(Sp * H * 2);
     v.dz2T = (bf16_t*)take(Sp * H * 2);
     v.dz1T = (bf16_t*)take(Sp * H * 2);
+    v.partial_head = (float*)take((int64_t)512 * (H * kActions + kActions) * 4);
   }
   if (total) *total = off;
   return v;
@@ -362,8 +372,10 @@ void train_net_bf16(const RowSrc& X, int64_t S, int Din, int H, const Bf16NetWei
   if (!packed) pack_obs_bf16(X, S, Din, bw.Dp, Sp, w.xb, w.xbT, s);  // packed: the previous network left these very rows there
   mlp_hidden_forward_bf16(w.xb, S, Sp, H, bw, eff + o.b1, eff + o.b2, w.bh1, w.bh1T, w.bh2, s);
   const unsigned nb = (unsigned)std::min<int64_t>(512, (S + kHeadTile - 1) / kHeadTile);
+  float* const hp = (go.b3 == go.W3 + (int64_t)H * NOUT) ? w.partial_head : nullptr;  // b3's gradient directly follows W3's
   hipLaunchKernelGGL((loss_head_bf16_kernel<NOUT, LossFn, 512>), dim3(nb), dim3(256), 0, s, w.bh2, S, H, eff + o.W3,
-                     eff + o.b3, fn, dl, grad + go.W3, grad + go.b3, w.sc);
+                     eff + o.b3, fn, dl, grad + go.W3, grad + go.b3, w.sc, hp);
+  if (hp != nullptr) launch_reduce_partials(hp, (int)nb, (int64_t)H * NOUT + NOUT, grad + go.W3, s);
   hipLaunchKernelGGL(bf16_detail::dz2_bf16_kernel<NOUT>, dim3((unsigned)(Sp / 64), (unsigned)((H + 63) / 64)), dim3(256), 0,
                      s, w.bh2, w.dz2T, dl, eff + o.W3, S, Sp, H);
   auto k_split = [&](int64_t tiles_mn) {  // ~4 workgroups per CU, k ranges in multiples of the k tile
@@ -438,7 +450,7 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
       lc.sc = w.sc; lc.normalize = c.normalize_adv; lc.clip_eps = c.clip_eps; lc.ent_coef = c.ent_coef;
       lc.vf_coef = c.vf_coef; lc.clip_value = c.clip_value;
       if (c.normalize_adv) {
-        const unsigned nb = (unsigned)std::min<int64_t>(1024, (Sa + 255) / 256);
+        const unsigned nb = (unsigned)std::min<int64_t>(256, (Sa + 255) / 256);  // every workgroup ends with two atomics on the same two doubles
         hipLaunchKernelGGL(adv_stats_kernel, dim3(nb), dim3(256), 0, s, tr.adv, lc, w.sc);
       }
       // ---- actor

@@ -717,7 +717,7 @@ int32_t launch_ppo_update_recurrent(const marl_config& c, marl_traj tr, marl_rec
       lc.sc = w.sc; lc.normalize = c.normalize_adv; lc.clip_eps = c.clip_eps; lc.ent_coef = c.ent_coef;
       lc.vf_coef = c.vf_coef; lc.clip_value = c.clip_value;
       if (c.normalize_adv) {
-        const unsigned nb = (unsigned)std::min<int64_t>(1024, (TJ * d.A + 255) / 256);
+        const unsigned nb = (unsigned)std::min<int64_t>(256, (TJ * d.A + 255) / 256);
         hipLaunchKernelGGL(adv_stats_kernel, dim3(nb), dim3(256), 0, s, tr.adv, lc, w.sc);
       }
       {
