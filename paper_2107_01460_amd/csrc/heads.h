@@ -36,9 +36,20 @@ __device__ __forceinline__ void head_tile(const HT* __restrict__ H2, int64_t s0,
   for (int h0 = 0; h0 < H; h0 += kHeadChunk) {
     const int hc = min(kHeadChunk, H - h0);
     __syncthreads();
-    for (int r = grp; r < kHeadTile; r += 4) {
-      const int64_t s = s0 + r;
-      for (int c = lane; c < hc; c += 64) L.tile[r * (kHeadChunk + 1) + c] = s < S ? load_act(H2, s * H + h0 + c) : 0.f;
+    {  // the chunk of the tile: all of a thread's elements are requested before the first is stored
+      constexpr int PER = kHeadTile * kHeadChunk / 256;
+      float v[PER];
+#pragma unroll
+      for (int q = 0; q < PER; ++q) {
+        const int idx = tid + 256 * q, r = idx / kHeadChunk, c = idx % kHeadChunk;
+        const int64_t s = s0 + r;
+        v[q] = (s < S && c < hc) ? load_act(H2, s * H + h0 + c) : 0.f;
+      }
+#pragma unroll
+      for (int q = 0; q < PER; ++q) {
+        const int idx = tid + 256 * q, r = idx / kHeadChunk, c = idx % kHeadChunk;
+        L.tile[r * (kHeadChunk + 1) + c] = v[q];
+      }
     }
     for (int e = tid; e < hc * NOUT; e += 256) L.w3[e] = W3[(int64_t)h0 * NOUT + e];
     __syncthreads();
