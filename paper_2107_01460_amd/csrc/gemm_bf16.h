@@ -278,14 +278,12 @@ __global__ void __launch_bounds__(256, 2) gemm_bf16_kernel(GemmBf16Args g) {
 // The same product on a 256 x 256 x 64 workgroup tile: four wavefronts, each a 128 x 128 quadrant (4 x 4 MFMA tiles,
 // accumulators in the upper half of the 512-register file, one wavefront per SIMD).  An operand fragment read from
 // LDS feeds four MFMAs instead of two, which halves the LDS bandwidth per flop: with 2 x 2 tiles per wavefront
-// the 128 B/clk of LDS saturate at half the bf16 matrix rate.  Results leave in two passes (one per row half)
-// through a tile staged in the operand buffers.
+// the 128 B/clk of LDS saturate at half the bf16 matrix rate.  Serves the weight gradients (split over the samples,
+// fp32 atomics) only: with an element-wise epilogue its 256 values per lane cost more than the tile gains.
 template <int EPI>
 __global__ void __launch_bounds__(256, 1) gemm_bf16_big_kernel(GemmBf16Args g) {
+  static_assert(EPI == BEPI_ATOMIC, "weight gradients only");
   constexpr int BM = 256, BN = 256, BK = 64, P = BK + 8;
-  constexpr int PTR = 256 + 8;  // pitch of the staged row-major half tile [128][256]
-  constexpr int PTT = 128 + 8;  // pitch of the staged transposed half tile [256][128]
-  static_assert(2 * 2 * BM * P >= 128 * PTR && 2 * 2 * BM * P >= 256 * PTT, "the output tiles reuse the operand buffers");
   // two stages of operand tiles: while stage c is multiplied, stage c + 1 sits in LDS and stage c + 2 is on its way
   // from memory in registers -- the loop is bound by (bytes in flight per CU) / (memory latency), not by the MFMAs
   __shared__ __attribute__((aligned(16))) bf16_t smem[2 * 2 * BM * P];
@@ -385,9 +383,7 @@ __global__ void __launch_bounds__(256, 1) gemm_bf16_big_kernel(GemmBf16Args g) {
     fetch(i + 2);
     multiply(cur);
   }
-  __syncthreads();  // the operand stages are free for the output tile
-
-  if (EPI == BEPI_ATOMIC) {
+  {
     if (want_bsum) {
 #pragma unroll
       for (int p = 0; p < 8; ++p) {
@@ -408,88 +404,6 @@ __global__ void __launch_bounds__(256, 1) gemm_bf16_big_kernel(GemmBf16Args g) {
           const int64_t m = m0 + wm * 128 + i * 32 + 8 * (r / 4) + 4 * hi + (r % 4), n = n0 + wn * 128 + j * 32 + lo;
           if (m < g.M && n < g.N) atomicAdd(&g.Cf[m * g.ldcf + n], acc[i][j][r]);
         }
-    return;
-  }
-
-  bf16_t* T = smem;  // the operand buffers are free (the k loop ended with a barrier)
-#pragma unroll 1
-  for (int half = 0; half < 2; ++half) {  // rows m0 + 128 * half .. + 127: the quadrants of the wavefronts with wm == half
-    const int64_t mh = m0 + 128 * half;
-    if (EPI == BEPI_DTANH_T) {  // the aux half tile [128][256] comes in through LDS with 16-byte loads
-#pragma unroll
-      for (int q = 0; q < 16; ++q) {
-        const int row = (tid >> 5) + 8 * q, sg = tid & 31;
-        const int64_t m = mh + row, n = n0 + 8 * sg;
-        uint4 v = make_uint4(0u, 0u, 0u, 0u);
-        if (m < g.M && n < g.N) v = *reinterpret_cast<const uint4*>(&g.aux[m * g.ldaux + n]);
-        *reinterpret_cast<uint4*>(&T[row * PTR + 8 * sg]) = v;
-      }
-      __syncthreads();
-    }
-    if (wm == half) {  // element-wise epilogue in registers
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int nl = wn * 128 + j * 32 + lo;
-        const int64_t nc = min(n0 + nl, g.N - 1);
-        const float bias = EPI == BEPI_TANH ? g.bias[nc] : 0.f;
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int ml = i * 32 + 8 * (r / 4) + 4 * hi + (r % 4);
-            float v = acc[i][j][r];
-            if (EPI == BEPI_TANH) {
-              v = tanh_f32(v + bias);
-            } else {
-              const float h = from_bf16(T[ml * PTR + nl]);
-              v = v * (1.0f - h * h);
-            }
-            acc[i][j][r] = (mh + ml < g.M) ? v : 0.f;  // rows past the end leave as zeros (padding of the transposed copy)
-          }
-      }
-    }
-    if (EPI == BEPI_DTANH_T) __syncthreads();  // the aux tile has been consumed
-    if (EPI == BEPI_TANH && g.C != nullptr) {  // ---- row-major copy C [m][n]
-      if (wm == half) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-          for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-              T[(i * 32 + 8 * (r / 4) + 4 * hi + (r % 4)) * PTR + wn * 128 + j * 32 + lo] = to_bf16(acc[i][j][r]);
-      }
-      __syncthreads();
-#pragma unroll
-      for (int q = 0; q < 16; ++q) {
-        const int row = (tid >> 5) + 8 * q, sg = tid & 31;
-        const int64_t m = mh + row, n = n0 + 8 * sg;
-        if (m < g.M && n < g.N) *reinterpret_cast<uint4*>(&g.C[m * g.ldc + n]) = *reinterpret_cast<const uint4*>(&T[row * PTR + 8 * sg]);
-      }
-      __syncthreads();
-    }
-    if (g.CT != nullptr) {  // ---- transposed copy CT [n][m]
-      if (wm == half) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-          for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int gq = 0; gq < 4; ++gq) {
-              const uint32_t w0 = pack2_bf16(acc[i][j][4 * gq + 0], acc[i][j][4 * gq + 1]);
-              const uint32_t w1 = pack2_bf16(acc[i][j][4 * gq + 2], acc[i][j][4 * gq + 3]);
-              *reinterpret_cast<uint2*>(&T[(wn * 128 + j * 32 + lo) * PTT + i * 32 + 8 * gq + 4 * hi]) = make_uint2(w0, w1);
-            }
-      }
-      __syncthreads();
-#pragma unroll
-      for (int q = 0; q < 16; ++q) {
-        const int row = (tid >> 4) + 16 * q, sg = tid & 15;
-        const int64_t n = n0 + row, m = mh + 8 * sg;
-        if (n < g.N && m < g.ct_cols) *reinterpret_cast<uint4*>(&g.CT[n * g.ldct + m]) = *reinterpret_cast<const uint4*>(&T[row * PTT + 8 * sg]);
-      }
-      __syncthreads();
-    }
   }
 }
 
@@ -501,7 +415,7 @@ inline void launch_gemm_bf16(const GemmBf16Args& g0, hipStream_t s) {
   unsigned gz = 1;
   if (EPI == BEPI_ATOMIC) gz = (unsigned)((g.K + g.k_per_split - 1) / g.k_per_split);
   const int64_t mcover = (EPI == BEPI_ATOMIC || g.CT == nullptr) ? g.M : std::max(g.M, g.ct_cols);
-  if (EPI == BEPI_ATOMIC && mcover > 128 && g.N > 128) {
+  if constexpr (EPI == BEPI_ATOMIC) if (mcover > 128 && g.N > 128) {
     // 256 x 256 tiles for the weight gradients.  (For the products with an element-wise epilogue the big tile
     // measured slower, 466 against 291 us for layer 2 and 725 against 298 us for dz1 at 262 144 rows: 256 tanh
     // evaluations per lane with one wavefront per SIMD are not hidden behind anything.)

@@ -305,7 +305,6 @@ __global__ void __launch_bounds__(512) gru_step_bwd_kernel(const float* __restri
   float* Gs = lds;                   // [32][PG]  dgh tile, the A operand
   float* Ds = Gs + kStepRows * PG;   // [32][PH]  dh * z
   const int tid = threadIdx.x, lane = tid & 63, u = tid >> 6, lo = lane & 31, hi = lane >> 5;
-  const int nthreads = blockDim.x;  // 2 H
   const int64_t s0 = (int64_t)blockIdx.x * kStepRows;
   {  // gate arithmetic: thread -> unit j = tid % H, samples tid / H + 2 q
     const int j = tid % H, mq = tid / H;
