@@ -231,6 +231,10 @@ int32_t launch_rollout(const marl_config& c, marl_env_state st, const float* par
   const int64_t NA = d.NA, slab = NA * d.D;
   int32_t rc = launch_env_step(c, st, nullptr, tr.obs, nullptr, nullptr, /*do_step=*/false, s);
   if (rc != MARL_OK) return rc;
+  // The values do not steer the rollout (the parameters are constant during it): where the critic's forward pass
+  // needs no per-row workspace (the fused fp32 kernel), all T steps' values are computed in one pass over the stored
+  // observations afterwards instead of one small launch per step.
+  const bool batch_values = !d.bf16 && fused_forward_supported(d.Hc);
   for (int t = 0; t < d.T; ++t) {
     SampleArgs a{};
     a.uniforms = forced_uniforms ? forced_uniforms + (int64_t)t * NA * kActions : nullptr;
@@ -243,10 +247,15 @@ int32_t launch_rollout(const marl_config& c, marl_env_state st, const float* par
     a.k0 = (uint32_t)(c.seed & 0xffffffffu);
     a.k1 = (uint32_t)(c.seed >> 32);
     rc = forward_rows(c, eff, tr.obs + (int64_t)t * slab, d.N, w, true,
-                      tr.logits ? tr.logits + (int64_t)t * NA * kActions : nullptr, &a, tr.value + (int64_t)t * NA, s);
+                      tr.logits ? tr.logits + (int64_t)t * NA * kActions : nullptr, &a,
+                      batch_values ? nullptr : tr.value + (int64_t)t * NA, s);
     if (rc != MARL_OK) return rc;
     rc = launch_env_step(c, st, a.action, tr.obs + (int64_t)(t + 1) * slab, tr.reward + (int64_t)t * NA,
                          tr.done + (int64_t)t * d.N, true, s);
+    if (rc != MARL_OK) return rc;
+  }
+  if (batch_values) {
+    rc = forward_rows(c, eff, tr.obs, (int64_t)d.T * d.N, w, false, nullptr, nullptr, tr.value, s);
     if (rc != MARL_OK) return rc;
   }
   return forward_rows(c, eff, tr.obs + (int64_t)d.T * slab, d.N, w, false, nullptr, nullptr, tr.last_value, s);
