@@ -20,6 +20,7 @@
 namespace marl {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));  // 16 bytes in flight between a load and an LDS store
 
 enum Bf16Epi {
   BEPI_TANH = 0,     // v = tanh(acc + bias[n]) -> C [m][n] (nullable) and CT [n][m] (nullable)
@@ -407,6 +408,224 @@ __global__ void __launch_bounds__(256, 1) gemm_bf16_big_kernel(GemmBf16Args g) {
   }
 }
 
+// The products with an element-wise epilogue (forward layers, dz1) when the weight matrix is small enough to LIVE IN
+// REGISTERS: a persistent workgroup of eight wavefronts owns a 256-column panel of the output, wavefront w holds the
+// B rows n0 + 32 w .. + 31 for all of k as MFMA operand fragments (4 KG registers per lane), and 64-row tiles of A
+// stream through LDS as one continuous sequence of 64 x BK chunks that runs across tile boundaries, so the loads of
+// the next tile are in flight during the epilogue of the current one.  Against the 128 x 128 tile kernel above this
+// halves twice what a workgroup pulls through the L2 per flop (no B traffic at all, and A is read by N / 256
+// workgroups instead of N / 128), which is what bounded that kernel: per 64-row tile only 64 x K elements arrive.
+// Chunk j travels in register set j % NS and LDS stage j % NS: it is requested NS + 1 iterations before it is
+// multiplied and written to LDS one iteration before; one barrier per chunk.  NS divides the chunks per tile, so
+// every set / stage / fragment index is a compile-time constant after unrolling.
+// The forward products run the MFMA with the operands swapped (weights as the row operand), so that a lane ends up
+// with four consecutive columns of one output row and the row-major tile is staged with 8-byte LDS stores; dz1, whose
+// only output is the transposed copy, keeps the activations as the row operand for the same reason.
+// Grid: a multiple of 8 * (N / 256) workgroups; consecutive slots of one XCD take the panels of the same row tiles,
+// so an A chunk is fetched from HBM once and found in that XCD's L2 by the other panels.
+// What bounds it: the bytes a CU keeps in flight.  128 of a lane's 256 registers hold weights, which leaves room for
+// NS = 4 chunks of 8 KB on their way; a k-loop iteration therefore lasts a quarter of the loaded memory latency, not
+// its 512 MFMA cycles (two stages of 128-wide chunks measure the same).  The staging registers are native vectors:
+// an array of HIP's uint4 structs stays in scratch memory here, and every load is then waited for at once.
+template <int KG, int BK, int NS, int EPI>
+__global__ void __launch_bounds__(512, 1) gemm_bf16_wres_kernel(GemmBf16Args g) {
+  static_assert(EPI == BEPI_TANH || EPI == BEPI_DTANH_T, "element-wise epilogues only");
+  constexpr int BM = 64, BN = 256, P = BK + 8, KS = BK / 16, NCH = 16 * KG / BK, CPT = BK / 64;
+  constexpr int PT = BN + 8, PT2 = BM + 8;  // pitches of the row-major and of the transposed output tile
+  constexpr bool SWAP = EPI == BEPI_TANH;   // weights as the MFMA row operand
+  static_assert(BK % 64 == 0 && (16 * KG) % BK == 0 && NS >= 2 && NS <= NCH && NCH % NS == 0, "chunks per tile are a multiple of the stages");
+  static_assert(EPI == BEPI_TANH || NCH >= 3, "the aux tile is fetched during the k loop");
+  extern __shared__ __attribute__((aligned(16))) bf16_t wres_lds[];
+  bf16_t* const As = wres_lds;             // [NS][BM][P]
+  bf16_t* const T = As + NS * BM * P;      // [BM][PT]   C tile (row-major) / aux tile
+  bf16_t* const T2 = T + BM * PT;          // [BN][PT2]  C^T tile
+  float* const biasS = reinterpret_cast<float*>(T2 + BN * PT2);  // [BN]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lo = lane & 31, hi = lane >> 5;
+  const unsigned xcd = blockIdx.x & 7u, slot = blockIdx.x >> 3;
+  const unsigned panels = g.tiles_n, panel = slot % panels;
+  const int64_t stream = (int64_t)(slot / panels) * 8 + xcd, nstreams = gridDim.x / panels;
+  if (stream >= (int64_t)g.tiles_m) return;  // the whole workgroup
+  const int nt = (int)(((int64_t)g.tiles_m - stream + nstreams - 1) / nstreams);  // row tiles of this workgroup
+  const int64_t n0 = (int64_t)panel * BN;
+
+  bf16x8 breg[KG];
+  {
+    const bf16_t* brow = g.B + min(n0 + 32 * wave + lo, g.b_rows - 1) * g.ldb + 8 * hi;
+#pragma unroll
+    for (int s = 0; s < KG; ++s) breg[s] = *reinterpret_cast<const bf16x8*>(brow + 16 * s);
+  }
+  if (EPI == BEPI_TANH && tid < BN) biasS[tid] = g.bias[n0 + tid];  // read after the barriers of the first k loop
+
+  // staging: thread -> row tid / 8 of the tile, 16-byte segments tid % 8 + 8 u of the row's chunk
+  const int srow = tid >> 3, seg = tid & 7;
+  auto a_ptr = [&](int ti, int kc) -> const bf16_t* {  // tiles past the last one: the last one again (never multiplied)
+    const int64_t tm = stream + (int64_t)min(ti, nt - 1) * nstreams;
+    return g.A + min(tm * BM + srow, g.a_rows - 1) * g.lda + kc * BK + 8 * seg;
+  };
+  u32x4 R[NS][CPT];
+  {
+    const bf16_t* p0 = a_ptr(0, 0);
+#pragma unroll
+    for (int u = 0; u < CPT; ++u) R[0][u] = *reinterpret_cast<const u32x4*>(p0 + 64 * u);
+#pragma unroll
+    for (int u = 0; u < CPT; ++u) *reinterpret_cast<u32x4*>(&As[srow * P + 8 * seg + 64 * u]) = R[0][u];
+  }
+#pragma unroll
+  for (int j = 1; j <= NS; ++j) {
+    const bf16_t* pj = a_ptr(j / NCH, j % NCH);
+#pragma unroll
+    for (int u = 0; u < CPT; ++u) R[j % NS][u] = *reinterpret_cast<const u32x4*>(pj + 64 * u);
+  }
+
+  floatx16 acc[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+
+  for (int t = 0; t < nt; ++t) {
+    const int64_t m0 = (stream + (int64_t)t * nstreams) * BM;
+    u32x4 xr[4];  // aux tile of this row tile (BEPI_DTANH_T): thread -> rows tid / 32 + 16 q, 16-byte segment tid % 32
+    if (EPI == BEPI_DTANH_T) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int64_t m = min(m0 + (tid >> 5) + 16 * q, g.M - 1);  // rows past the end: any row (their results are zeroed)
+        xr[q] = *reinterpret_cast<const u32x4*>(&g.aux[m * g.ldaux + n0 + 8 * (tid & 31)]);
+      }
+    }
+#pragma unroll
+    for (int kc = 0; kc < NCH; ++kc) {
+      __syncthreads();  // stage kc % NS is complete; everybody is done reading the stage written next
+      const int nset = (kc + 1) % NS;
+#pragma unroll
+      for (int u = 0; u < CPT; ++u) *reinterpret_cast<u32x4*>(&As[(nset * BM + srow) * P + 8 * seg + 64 * u]) = R[nset][u];
+      {
+        const bf16_t* pn = a_ptr(t + (kc + 1 + NS) / NCH, (kc + 1 + NS) % NCH);
+#pragma unroll
+        for (int u = 0; u < CPT; ++u) R[nset][u] = *reinterpret_cast<const u32x4*>(pn + 64 * u);
+      }
+      if (EPI == BEPI_DTANH_T && kc == NCH - 2) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) *reinterpret_cast<u32x4*>(&T[((tid >> 5) + 16 * q) * PT + 8 * (tid & 31)]) = xr[q];
+      }
+      const bf16_t* Ab = As + (kc % NS) * BM * P + lo * P + 8 * hi;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(Ab + 16 * ks);
+        const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(Ab + 32 * P + 16 * ks);
+        const bf16x8 b = breg[KS * kc + ks];
+        if (SWAP) {
+          acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, a0, acc[0], 0, 0, 0);
+          acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, a1, acc[1], 0, 0, 0);
+        } else {
+          acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b, acc[0], 0, 0, 0);
+          acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b, acc[1], 0, 0, 0);
+        }
+      }
+    }
+    // ---- epilogue.  T, T2 (and biasS) were last touched before the barriers of this tile's k loop.
+    if (SWAP) {
+      // acc[i][4 gq + j] = element (row 32 i + lo, column 32 wave + 8 gq + 4 hi + j) of the tile
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const bool live = m0 + 32 * i + lo < g.M;  // rows past the end leave as zeros (padding of the transposed copy)
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+          const int nc = 32 * wave + 8 * gq + 4 * hi;
+          const float4 bq = *reinterpret_cast<const float4*>(&biasS[nc]);
+          const float bb[4] = {bq.x, bq.y, bq.z, bq.w};
+          float v[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const float x = tanh_f32(acc[i][4 * gq + j] + bb[j]);
+            v[j] = live ? x : 0.f;
+            acc[i][4 * gq + j] = 0.f;
+          }
+          if (g.C != nullptr)
+            *reinterpret_cast<uint2*>(&T[(32 * i + lo) * PT + nc]) = make_uint2(pack2_bf16(v[0], v[1]), pack2_bf16(v[2], v[3]));
+          if (g.CT != nullptr) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) T2[(nc + j) * PT2 + 32 * i + lo] = to_bf16(v[j]);
+          }
+        }
+      }
+    } else {
+      // acc[i][r] = element (row 32 i + 8 (r / 4) + 4 hi + r % 4, column 32 wave + lo) of the tile
+      const int nl = 32 * wave + lo;
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+          float v[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const int ml = 32 * i + 8 * gq + 4 * hi + j;
+            const float h = from_bf16(T[ml * PT + nl]);
+            const float x = acc[i][4 * gq + j] * (1.0f - h * h);
+            v[j] = (m0 + ml < g.M) ? x : 0.f;
+            acc[i][4 * gq + j] = 0.f;
+          }
+          *reinterpret_cast<uint2*>(&T2[nl * PT2 + 32 * i + 8 * gq + 4 * hi]) = make_uint2(pack2_bf16(v[0], v[1]), pack2_bf16(v[2], v[3]));
+        }
+    }
+    __syncthreads();
+    if (EPI == BEPI_TANH && g.C != nullptr) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int row = (tid >> 5) + 16 * q, sg = tid & 31;
+        if (m0 + row < g.M)
+          *reinterpret_cast<uint4*>(&g.C[(m0 + row) * g.ldc + n0 + 8 * sg]) = *reinterpret_cast<const uint4*>(&T[row * PT + 8 * sg]);
+      }
+    }
+    if (g.CT != nullptr) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int nrow = (tid >> 3) + 64 * q, sg = tid & 7;
+        if (m0 + 8 * sg < g.ct_cols)
+          *reinterpret_cast<uint4*>(&g.CT[(n0 + nrow) * g.ldct + m0 + 8 * sg]) = *reinterpret_cast<const uint4*>(&T2[nrow * PT2 + 8 * sg]);
+      }
+    }
+  }
+}
+
+// Workgroups of a gemm_bf16_wres_kernel launch: one per CU.
+constexpr unsigned kWresGrid = 256;
+
+template <int EPI>
+inline bool gemm_bf16_wres_supported(const GemmBf16Args& g) {
+  if (EPI == BEPI_ATOMIC) return false;
+  const int64_t panels = g.N / 256;
+  if (g.N % 256 != 0 || !(panels == 1 || panels == 2 || panels == 4) || g.b_rows < g.N) return false;
+  if (EPI == BEPI_TANH) return g.K == 128 || g.K == 192 || g.K == 256 || g.K == 512;
+  return g.K == 512;
+}
+
+template <int KG, int BK, int NS, int EPI>
+inline void launch_gemm_bf16_wres_inst(const GemmBf16Args& g, hipStream_t s) {
+  auto kern = gemm_bf16_wres_kernel<KG, BK, NS, EPI>;
+  const size_t bytes = ((size_t)NS * 64 * (BK + 8) + 64 * 264 + 256 * 72) * sizeof(bf16_t) + 256 * sizeof(float);
+  static bool configured = false;  // per instantiation
+  if (!configured) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return;
+    configured = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(kWresGrid), dim3(512), bytes, s, g);
+}
+
+template <int EPI>
+inline void launch_gemm_bf16_wres(GemmBf16Args g, hipStream_t s) {
+  const int64_t mcover = g.CT == nullptr ? g.M : std::max(g.M, g.ct_cols);
+  g.tiles_m = (unsigned)((mcover + 63) / 64);
+  g.tiles_n = (unsigned)(g.N / 256);
+  if constexpr (EPI == BEPI_TANH) {
+    if (g.K == 128) return launch_gemm_bf16_wres_inst<8, 64, 2, EPI>(g, s);
+    if (g.K == 192) return launch_gemm_bf16_wres_inst<12, 64, 3, EPI>(g, s);
+    if (g.K == 256) return launch_gemm_bf16_wres_inst<16, 64, 4, EPI>(g, s);
+  }
+  if constexpr (EPI != BEPI_ATOMIC) return launch_gemm_bf16_wres_inst<32, 64, 4, EPI>(g, s);
+}
+
 template <int EPI>
 inline void launch_gemm_bf16(const GemmBf16Args& g0, hipStream_t s) {
   GemmBf16Args g = g0;
@@ -414,6 +633,9 @@ inline void launch_gemm_bf16(const GemmBf16Args& g0, hipStream_t s) {
                     2.0 * (double)g.M * (double)g.N * (double)g.K, s);
   unsigned gz = 1;
   if (EPI == BEPI_ATOMIC) gz = (unsigned)((g.K + g.k_per_split - 1) / g.k_per_split);
+  if constexpr (EPI != BEPI_ATOMIC) {
+    if (gemm_bf16_wres_supported<EPI>(g)) return launch_gemm_bf16_wres<EPI>(g, s);
+  }
   const int64_t mcover = (EPI == BEPI_ATOMIC || g.CT == nullptr) ? g.M : std::max(g.M, g.ct_cols);
   if constexpr (EPI == BEPI_ATOMIC) if (mcover > 128 && g.N > 128) {
     // 256 x 256 tiles for the weight gradients.  (For the products with an element-wise epilogue the big tile

@@ -77,7 +77,10 @@ def test_env_single_env_and_large_grid(M, orc):
 
 @pytest.mark.parametrize("k", [1, 2, 3, 4, 5])
 def test_policy_forward(M, orc, k):
-    cfg = small(k)
+    check_policy_forward(M, orc, small(k), k)
+
+
+def check_policy_forward(M, orc, cfg, k):
     A, D = cfg["n_agents"], W.obs_dim(cfg)
     rows = 333
     print("case", cfg["name"], rows, flush=True)
@@ -201,6 +204,21 @@ def oracle_traj(orc, cfg, bias_scale=0.1):
 def test_ppo_single_minibatch_gradient(M, orc, k, clipv, norm):
     """One minibatch over the whole (small) trajectory at perturbed parameters: loss terms and gradient."""
     cfg = small(k, n_epochs=1, n_minibatches=1, clip_value=clipv, normalize_adv=norm, max_grad_norm=0.0)
+    check_single_minibatch_gradient(M, orc, cfg, k)
+
+
+@pytest.mark.parametrize("ha,hc,view", [(128, 64, 7), (256, 256, 5), (512, 256, 5), (256, 512, 7)])
+def test_bf16_other_widths(M, orc, ha, hc, view):
+    """bf16 networks of other widths than config 4's 147-512-512.  Which GEMM kernel a product takes depends on
+    them: output widths that are no multiple of 256 take the 128 x 128 tile kernel, the others the kernel with
+    the weights resident in registers, in a different instantiation for every contraction length (padded input
+    width 128 or 192, hidden width 256 or 512); dz1 at width 256 takes the tile kernel again."""
+    kw = dict(actor_hidden=ha, critic_hidden=hc, view=view)
+    check_policy_forward(M, orc, small(4, **kw), 40 + view)
+    check_single_minibatch_gradient(M, orc, small(4, n_epochs=1, n_minibatches=1, max_grad_norm=0.0, **kw), 4)
+
+
+def check_single_minibatch_gradient(M, orc, cfg, k):
     print("case", cfg["name"], flush=True)
     params0, otr = oracle_traj(orc, cfg)
     rng = np.random.default_rng(100 + k)
