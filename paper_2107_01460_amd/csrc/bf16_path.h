@@ -43,7 +43,8 @@ static __global__ void stage_weights_bf16_kernel(const float* __restrict__ W1, c
   }
 }
 
-// Xb [S][Dp] = bf16(X), zero-padded columns; XbT [Dp][Sp] its transpose with zero-padded samples (nullable).
+// Xb [S][Dp] = bf16(X), zero-padded columns; XbT its transpose ([Dp][Sp], stored sample-blocked: see gemm_bf16.h) with
+// zero-padded samples (nullable).
 static __global__ void __launch_bounds__(256) pack_obs_bf16_kernel(RowSrc X, int64_t S, int Din, int Dp, int64_t Sp,
                                                                    bf16_t* __restrict__ Xb, bf16_t* __restrict__ XbT) {
   __shared__ float tile[64][65];
@@ -72,14 +73,14 @@ static __global__ void __launch_bounds__(256) pack_obs_bf16_kernel(RowSrc X, int
 #pragma unroll
       for (int q = 0; q < 16; ++q) {
         const int dd = (tid >> 6) + 4 * q, ss = tid & 63;
-        if (d0 + dd < Dp && s0 + ss < Sp) XbT[(int64_t)(d0 + dd) * Sp + s0 + ss] = to_bf16(tile[ss][dd]);
+        if (d0 + dd < Dp && s0 + ss < Sp) XbT[((s0 >> 6) * Dp + d0 + dd) * 64 + ss] = to_bf16(tile[ss][dd]);
       }
     }
     __syncthreads();
   }
 }
 
-// In place: H2[s][j] <- (sum_k dl[s][k] W3[j][k]) * (1 - H2[s][j]^2); dz2T [H][Sp] gets the transposed copy (zeros past S).
+// In place: H2[s][j] <- (sum_k dl[s][k] W3[j][k]) * (1 - H2[s][j]^2); dz2T [H][Sp] (sample-blocked) gets the transposed copy (zeros past S).
 // One workgroup per tile of 64 samples x 64 hidden units; a thread owns eight consecutive hidden units of two rows
 // (16-byte loads and stores, no branches: rows past the end are clamped for the loads and produce zeros), and eight
 // consecutive samples of two hidden units for the transposed copy, which goes through an LDS tile.
@@ -139,7 +140,7 @@ static __global__ void __launch_bounds__(256) dz2_bf16_kernel(bf16_t* __restrict
 #pragma unroll
     for (int p = 0; p < 4; ++p)
       ow[p] = (uint32_t)tile[(ss + 2 * p) * PT + dd] | ((uint32_t)tile[(ss + 2 * p + 1) * PT + dd] << 16);
-    if (s0 + ss < Sp) *reinterpret_cast<uint4*>(&dz2T[(int64_t)(j0 + dd) * Sp + s0 + ss]) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+    if (s0 + ss < Sp) *reinterpret_cast<uint4*>(&dz2T[((s0 >> 6) * H + j0 + dd) * 64 + ss]) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
   }
 }
 
@@ -162,7 +163,7 @@ inline void mlp_hidden_forward_bf16(const bf16_t* Xb, int64_t S, int64_t Sp, int
                                     const float* b2, bf16_t* h1, bf16_t* h1T, bf16_t* h2, hipStream_t s) {
   GemmBf16Args g{};
   g.A = Xb; g.lda = w.Dp; g.a_rows = S; g.B = w.W1t; g.ldb = w.Dp; g.b_rows = H;
-  g.M = S; g.N = H; g.K = w.Dp; g.C = h1; g.ldc = H; g.CT = h1T; g.ldct = Sp; g.ct_cols = Sp; g.bias = b1;
+  g.M = S; g.N = H; g.K = w.Dp; g.C = h1; g.ldc = H; g.CT = h1T; g.ct_cols = Sp; g.bias = b1;
   launch_gemm_bf16<BEPI_TANH>(g, s);
   GemmBf16Args g2{};
   g2.A = h1; g2.lda = H; g2.a_rows = S; g2.B = w.W2t; g2.ldb = H; g2.b_rows = H;

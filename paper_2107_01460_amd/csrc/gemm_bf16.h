@@ -10,6 +10,11 @@
 //   dW2 = h1T dz2T^T                A = h1T [H][Sp]   B = dz2T [H][Sp]   -> fp32 atomics (k split over workgroups)
 //   dz1 = (dz2 W2^T) (1 - h1^2)     A = dz2 [S][H]    B = W2  [H][H]     -> dz1T [H][Sp] only
 //   dW1 = XbT dz1T^T                A = XbT [Dp][Sp]  B = dz1T [H][Sp]   -> fp32 atomics
+// The transposed copies are stored SAMPLE-BLOCKED: element (row r, sample s) of an R-row copy sits at
+// ((s / 64) R + r) 64 + s % 64, i.e. the R rows of 64 consecutive samples form one contiguous block of 128 R bytes.
+// A 64-sample chunk of any range of rows is then one contiguous piece of memory for the weight-gradient kernels (with
+// plain [R][Sp] rows of 512 KB pitch every row of a chunk lay in another page and on the same memory channel), and
+// the producers write their 64-sample tiles as one contiguous piece too.
 // Tile 128 x 128 x 64 per workgroup of four wavefronts (2 x 2, each 2 x 2 MFMA tiles of 32 x 32); operands are
 // staged in LDS with a 144-byte row pitch so that the 16-byte operand reads of eight consecutive rows fall into
 // eight different bank groups; results leave through an LDS-staged tile with 16-byte stores in both orientations.
@@ -29,16 +34,16 @@ enum Bf16Epi {
 };
 
 struct GemmBf16Args {
-  const bf16_t* A;  // [a_rows][lda]
+  const bf16_t* A;  // [a_rows][lda]; BEPI_ATOMIC: sample-blocked transposed copy of a_rows rows (lda unused)
   int64_t lda, a_rows;
-  const bf16_t* B;  // [b_rows][ldb]
+  const bf16_t* B;  // [b_rows][ldb]; BEPI_ATOMIC: sample-blocked transposed copy of b_rows rows (ldb unused)
   int64_t ldb, b_rows;
   int64_t M, N, K;  // K a multiple of 64 (buffers are zero-padded along k)
   int64_t k_per_split;
   bf16_t* C;
   int64_t ldc;
   bf16_t* CT;
-  int64_t ldct, ct_cols;  // columns m in [M, ct_cols) of CT are written as zeros (ct_cols a multiple of 8)
+  int64_t ct_cols;  // CT is the sample-blocked transposed copy with N rows; samples m in [M, ct_cols) are written as zeros (ct_cols a multiple of 64)
   float* Cf;
   int64_t ldcf;
   const float* bias;
@@ -51,6 +56,7 @@ struct GemmBf16Args {
 template <int EPI>
 __global__ void __launch_bounds__(256, 2) gemm_bf16_kernel(GemmBf16Args g) {
   constexpr int BM = 128, BN = 128, BK = 64, P = BK + 8;  // pitch in elements (144 bytes)
+  constexpr bool KBLK = EPI == BEPI_ATOMIC;               // the operands are sample-blocked transposed copies
   constexpr int PT = 128 + 8;                             // pitch of the output staging tile (272 bytes)
   static_assert(2 * 2 * BM * P >= 128 * PT, "the output tile reuses the operand buffers");
   // two stages of operand tiles: while stage c is multiplied, stage c + 1 sits in LDS and stage c + 2 is on its way
@@ -85,8 +91,8 @@ __global__ void __launch_bounds__(256, 2) gemm_bf16_kernel(GemmBf16Args g) {
   const bf16_t *arow[4], *brow[4];
 #pragma unroll
   for (int p = 0; p < 4; ++p) {
-    arow[p] = g.A + min(m0 + srow + 32 * p, g.a_rows - 1) * g.lda + 8 * seg;  // rows past the end re-read the last one
-    brow[p] = g.B + min(n0 + srow + 32 * p, g.b_rows - 1) * g.ldb + 8 * seg;
+    arow[p] = g.A + min(m0 + srow + 32 * p, g.a_rows - 1) * (KBLK ? 64 : g.lda) + 8 * seg;  // rows past the end re-read the last one
+    brow[p] = g.B + min(n0 + srow + 32 * p, g.b_rows - 1) * (KBLK ? 64 : g.ldb) + 8 * seg;
   }
   // Register sets R0 / R1 hold the chunks in flight: chunk j travels in set j & 1, is written to LDS stage j & 1 one
   // iteration before it is multiplied, and was requested three iterations before -- two chunks of MFMA work hide
@@ -97,22 +103,25 @@ __global__ void __launch_bounds__(256, 2) gemm_bf16_kernel(GemmBf16Args g) {
   // Chunks are visited in a rotated order that differs from workgroup to workgroup: with a power-of-two row pitch
   // every workgroup reading the same k offset at the same time would keep hitting the same few memory channels.
   const int nchunks = (int)((k_end - k_begin + BK - 1) / BK);
-  const int rot = nchunks > 0 ? (int)((tm * 5u + tn * 3u + split) % (unsigned)nchunks) : 0;
-  auto chunk_k = [&](int i) { return k_begin + (int64_t)((i + rot) % nchunks) * BK; };
+  // (not for the sample-blocked operands, whose chunks are contiguous: there the workgroups that share a panel walk in step)
+  const int rot = (!KBLK && nchunks > 0) ? (int)((tm * 5u + tn * 3u + split) % (unsigned)nchunks) : 0;
+  const int64_t astep = KBLK ? g.a_rows * 64 : BK, bstep = KBLK ? g.b_rows * 64 : BK;  // elements from one chunk to the next
+  auto chunk_c = [&](int i) { return k_begin / BK + (int64_t)((i + rot) % nchunks); };
   // (the two register sets are named, never passed by reference: a set that is selected at run time, or handed to a
   // helper through a reference, ends up in scratch memory, and a load whose destination is memory is waited for at once)
   auto fetch = [&](int i, auto set) {
     // past the end: the last chunk once more (an L2 hit, never staged) -- a branch here would make every wait in the
     // loop a wait for all outstanding loads
-    const int64_t k0 = chunk_k(i < nchunks ? i : nchunks - 1);
+    const int64_t c = chunk_c(i < nchunks ? i : nchunks - 1);
+    const int64_t ka = c * astep, kb = c * bstep;
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
       if constexpr (decltype(set)::value == 0) {
-        ra0[p] = *reinterpret_cast<const uint4*>(arow[p] + k0);
-        rb0[p] = *reinterpret_cast<const uint4*>(brow[p] + k0);
+        ra0[p] = *reinterpret_cast<const uint4*>(arow[p] + ka);
+        rb0[p] = *reinterpret_cast<const uint4*>(brow[p] + kb);
       } else {
-        ra1[p] = *reinterpret_cast<const uint4*>(arow[p] + k0);
-        rb1[p] = *reinterpret_cast<const uint4*>(brow[p] + k0);
+        ra1[p] = *reinterpret_cast<const uint4*>(arow[p] + ka);
+        rb1[p] = *reinterpret_cast<const uint4*>(brow[p] + kb);
       }
     }
   };
@@ -271,7 +280,8 @@ __global__ void __launch_bounds__(256, 2) gemm_bf16_kernel(GemmBf16Args g) {
     for (int q = 0; q < 8; ++q) {
       const int row = (tid >> 4) + 16 * q, sg = tid & 15;
       const int64_t n = n0 + row, m = m0 + 8 * sg;
-      if (n < g.N && m < g.ct_cols) *reinterpret_cast<uint4*>(&g.CT[n * g.ldct + m]) = *reinterpret_cast<const uint4*>(&T[row * PT + 8 * sg]);
+      if (n < g.N && m < g.ct_cols)
+        *reinterpret_cast<uint4*>(&g.CT[((m >> 6) * g.N + n) * 64 + (m & 63)]) = *reinterpret_cast<const uint4*>(&T[row * PT + 8 * sg]);
     }
   }
 }
@@ -285,6 +295,7 @@ template <int EPI>
 __global__ void __launch_bounds__(256, 1) gemm_bf16_big_kernel(GemmBf16Args g) {
   static_assert(EPI == BEPI_ATOMIC, "weight gradients only");
   constexpr int BM = 256, BN = 256, BK = 64, P = BK + 8;
+  constexpr bool KBLK = true;  // the operands are sample-blocked transposed copies
   // two stages of operand tiles: while stage c is multiplied, stage c + 1 sits in LDS and stage c + 2 is on its way
   // from memory in registers -- the loop is bound by (bytes in flight per CU) / (memory latency), not by the MFMAs
   __shared__ __attribute__((aligned(16))) bf16_t smem[2 * 2 * BM * P];
@@ -314,30 +325,30 @@ __global__ void __launch_bounds__(256, 1) gemm_bf16_big_kernel(GemmBf16Args g) {
 
   // staging: thread -> rows tid/8 + 32p (p < 8), 16-byte segment tid%8 of the 128-byte k-chunk of each row
   const int seg = tid & 7, srow = tid >> 3;
-  const bf16_t *arow[8], *brow[8];
+  // element offsets inside a chunk of the sample-blocked operands (64 elements per row); the chunk's base is uniform
+  uint32_t aoff[8], boff[8];
 #pragma unroll
   for (int p = 0; p < 8; ++p) {
-    arow[p] = g.A + min(m0 + srow + 32 * p, g.a_rows - 1) * g.lda + 8 * seg;  // rows past the end re-read the last one
-    brow[p] = g.B + min(n0 + srow + 32 * p, g.b_rows - 1) * g.ldb + 8 * seg;
+    aoff[p] = (uint32_t)min(m0 + srow + 32 * p, g.a_rows - 1) * 64u + 8u * seg;  // rows past the end re-read the last one
+    boff[p] = (uint32_t)min(n0 + srow + 32 * p, g.b_rows - 1) * 64u + 8u * seg;
   }
-  // One register set (a second one does not fit beside 256 accumulators): chunk j is requested two iterations before
+  // One register set (a second one spills beside 256 accumulators): chunk j is requested two iterations before
   // it is multiplied and written to LDS stage j & 1 one iteration before; one barrier per chunk.
-  uint4 ra0[8], rb0[8];
+  u32x4 ra0[8], rb0[8];
   float bsum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   const bool want_bsum = EPI == BEPI_ATOMIC && g.rowsum_b != nullptr && tm == 0;
-  // Chunks are visited in a rotated order that differs from workgroup to workgroup: with a power-of-two row pitch
-  // every workgroup reading the same k offset at the same time would keep hitting the same few memory channels.
   const int nchunks = (int)((k_end - k_begin + BK - 1) / BK);
-  const int rot = nchunks > 0 ? (int)((tm * 5u + tn * 3u + split) % (unsigned)nchunks) : 0;
-  auto chunk_k = [&](int i) { return k_begin + (int64_t)((i + rot) % nchunks) * BK; };
+  const int64_t astep = g.a_rows * 64, bstep = g.b_rows * 64;  // elements from one chunk to the next
   // (the register set is named, not handed to these helpers through a reference: see gemm_bf16_kernel)
   auto fetch = [&](int i) {
     if (i >= nchunks) return;
-    const int64_t k0 = chunk_k(i);
+    const int64_t c = k_begin / BK + i;
+    const bf16_t* const pa = g.A + c * astep;
+    const bf16_t* const pb = g.B + c * bstep;
 #pragma unroll
     for (int p = 0; p < 8; ++p) {
-      ra0[p] = *reinterpret_cast<const uint4*>(arow[p] + k0);
-      rb0[p] = *reinterpret_cast<const uint4*>(brow[p] + k0);
+      ra0[p] = *reinterpret_cast<const u32x4*>(pa + aoff[p]);
+      rb0[p] = *reinterpret_cast<const u32x4*>(pb + boff[p]);
     }
   };
   auto stage = [&](int buf) {
@@ -345,9 +356,9 @@ __global__ void __launch_bounds__(256, 1) gemm_bf16_big_kernel(GemmBf16Args g) {
     bf16_t* Bs = As + BM * P;
 #pragma unroll
     for (int p = 0; p < 8; ++p) {
-      const uint4 va = ra0[p], vb = rb0[p];
-      *reinterpret_cast<uint4*>(&As[(srow + 32 * p) * P + 8 * seg]) = va;
-      *reinterpret_cast<uint4*>(&Bs[(srow + 32 * p) * P + 8 * seg]) = vb;
+      const u32x4 va = ra0[p], vb = rb0[p];
+      *reinterpret_cast<u32x4*>(&As[(srow + 32 * p) * P + 8 * seg]) = va;
+      *reinterpret_cast<u32x4*>(&Bs[(srow + 32 * p) * P + 8 * seg]) = vb;
       if (EPI == BEPI_ATOMIC && want_bsum) {
         bsum[p] += (__uint_as_float(vb.x << 16) + __uint_as_float(vb.x & 0xffff0000u)) +
                    (__uint_as_float(vb.y << 16) + __uint_as_float(vb.y & 0xffff0000u)) +
@@ -356,20 +367,31 @@ __global__ void __launch_bounds__(256, 1) gemm_bf16_big_kernel(GemmBf16Args g) {
       }
     }
   };
+  // The operand fragments of k step ks + 1 are read while the 16 MFMAs of step ks run (two fragment sets; the
+  // scheduling barriers keep the compiler from folding them back into one set and waiting for every read).
   auto multiply = [&](int cur) {
-    const bf16_t* As = smem + cur * STAGE;
-    const bf16_t* Bs = As + BM * P;
+    const bf16_t* As = smem + cur * STAGE + (wm * 128 + lo) * P + 8 * hi;
+    const bf16_t* Bs = smem + cur * STAGE + BM * P + (wn * 128 + lo) * P + 8 * hi;
+    bf16x8 a[2][4], b[2][4];
 #pragma unroll
-    for (int ks = 0; ks < BK; ks += 16) {
-      bf16x8 a[4], b[4];
+    for (int i = 0; i < 4; ++i) a[0][i] = *reinterpret_cast<const bf16x8*>(As + i * 32 * P);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) a[i] = *reinterpret_cast<const bf16x8*>(&As[(wm * 128 + i * 32 + lo) * P + ks + 8 * hi]);
+    for (int j = 0; j < 4; ++j) b[0][j] = *reinterpret_cast<const bf16x8*>(Bs + j * 32 * P);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) b[j] = *reinterpret_cast<const bf16x8*>(&Bs[(wn * 128 + j * 32 + lo) * P + ks + 8 * hi]);
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      if (ks + 1 < BK / 16) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) a[(ks + 1) & 1][i] = *reinterpret_cast<const bf16x8*>(As + i * 32 * P + 16 * (ks + 1));
+#pragma unroll
+        for (int j = 0; j < 4; ++j) b[(ks + 1) & 1][j] = *reinterpret_cast<const bf16x8*>(Bs + j * 32 * P + 16 * (ks + 1));
+      }
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < 4; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks & 1][i], b[ks & 1][j], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
   if (nchunks > 0) {
@@ -583,7 +605,7 @@ __global__ void __launch_bounds__(512, 1) gemm_bf16_wres_kernel(GemmBf16Args g) 
       for (int q = 0; q < 4; ++q) {
         const int nrow = (tid >> 3) + 64 * q, sg = tid & 7;
         if (m0 + 8 * sg < g.ct_cols)
-          *reinterpret_cast<uint4*>(&g.CT[(n0 + nrow) * g.ldct + m0 + 8 * sg]) = *reinterpret_cast<const uint4*>(&T2[nrow * PT2 + 8 * sg]);
+          *reinterpret_cast<uint4*>(&g.CT[((m0 >> 6) * g.N + n0 + nrow) * 64 + 8 * sg]) = *reinterpret_cast<const uint4*>(&T2[nrow * PT2 + 8 * sg]);
       }
     }
   }

@@ -384,7 +384,7 @@ void train_net_bf16(const RowSrc& X, int64_t S, int Din, int H, const Bf16NetWei
   };
   {  // gW2 += h1^T dz2, gb2 += column sums of dz2
     GemmBf16Args g{};
-    g.A = w.bh1T; g.lda = Sp; g.a_rows = H; g.B = w.dz2T; g.ldb = Sp; g.b_rows = H;
+    g.A = w.bh1T; g.a_rows = H; g.B = w.dz2T; g.b_rows = H;
     g.M = H; g.N = H; g.K = Sp; g.Cf = grad + go.W2; g.ldcf = H; g.rowsum_b = grad + go.b2;
     g.k_per_split = k_split(((H + 127) / 128) * ((H + 127) / 128));
     launch_gemm_bf16<BEPI_ATOMIC>(g, s);
@@ -392,12 +392,12 @@ void train_net_bf16(const RowSrc& X, int64_t S, int Din, int H, const Bf16NetWei
   {  // dz1 = (dz2 W2^T) * (1 - h1^2), transposed copy only
     GemmBf16Args g{};
     g.A = w.bh2; g.lda = H; g.a_rows = S; g.B = bw.W2; g.ldb = H; g.b_rows = H;
-    g.M = S; g.N = H; g.K = H; g.CT = w.dz1T; g.ldct = Sp; g.ct_cols = Sp; g.aux = w.bh1; g.ldaux = H;
+    g.M = S; g.N = H; g.K = H; g.CT = w.dz1T; g.ct_cols = Sp; g.aux = w.bh1; g.ldaux = H;
     launch_gemm_bf16<BEPI_DTANH_T>(g, s);
   }
   {  // gW1 += X^T dz1, gb1 += column sums of dz1
     GemmBf16Args g{};
-    g.A = w.xbT; g.lda = Sp; g.a_rows = bw.Dp; g.B = w.dz1T; g.ldb = Sp; g.b_rows = H;
+    g.A = w.xbT; g.a_rows = bw.Dp; g.B = w.dz1T; g.b_rows = H;
     g.M = Din; g.N = H; g.K = Sp; g.Cf = grad + go.W1; g.ldcf = H; g.rowsum_b = grad + go.b1;
     g.k_per_split = k_split(((Din + 127) / 128) * ((H + 127) / 128));
     launch_gemm_bf16<BEPI_ATOMIC>(g, s);
