@@ -42,6 +42,7 @@ __global__ void __launch_bounds__(256) loss_head_bf16_kernel(const bf16_t* __res
   for (int e = tid; e < H * NOUT; e += 256) W3s[e] = W3[e];
   const auto prep = fn.prepare();
   constexpr int UMAX = HMAX / 256;  // hidden units per thread in the W3 gradient
+  static_assert(UMAX == 2, "a thread owns one pair of neighbouring hidden units");
   float gw[UMAX][NOUT], gb[NOUT], st[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int k = 0; k < NOUT; ++k) {
@@ -54,26 +55,39 @@ __global__ void __launch_bounds__(256) loss_head_bf16_kernel(const bf16_t* __res
   // A tile travels global -> registers -> LDS: all of a thread's 16-byte pieces are requested at once, and the next
   // tile's are requested before this tile's arithmetic, so that no load is waited for on its own.
   constexpr int NV = kHeadTile * (HMAX / 8) / 256;  // pieces per thread at the full width
+  constexpr int CPR = HMAX / 8;                     // 16-byte pieces of a row at the full width
+  static_assert(256 % CPR == 0 && NV * (256 / CPR) == kHeadTile, "a thread's pieces are one column of the tile");
   uint4 tv[NV];
   auto fetch_tile = [&](int64_t tile) {
     const int64_t s0 = tile * kHeadTile;
 #pragma unroll
-    for (int q = 0; q < NV; ++q) {
-      const int f = tid + 256 * q;
-      const int r = f / vec_per_row, c8 = f - r * vec_per_row;
+    for (int q = 0; q < NV; ++q) {  // thread -> rows tid / CPR + (256 / CPR) q, 16-byte piece tid % CPR of the row
+      const int r = tid / CPR + (256 / CPR) * q, c8 = tid % CPR;
       tv[q] = make_uint4(0u, 0u, 0u, 0u);
-      if (f < kHeadTile * vec_per_row && s0 + r < S) tv[q] = *reinterpret_cast<const uint4*>(&H2[(s0 + r) * H + 8 * c8]);
+      if (c8 < vec_per_row && s0 + r < S) tv[q] = *reinterpret_cast<const uint4*>(&H2[(s0 + r) * H + 8 * c8]);
     }
   };
-  if ((int64_t)blockIdx.x < ntiles) fetch_tile(blockIdx.x);
+  // The loss inputs of a sample sit behind a dependent pair of loads (row order entry, then the row): the first
+  // wavefront requests the entries of the next tile at the top of a tile and the rows after the output layer, so
+  // that neither is waited for in front of the loss.
+  typename LossFn::In lin_next{};
+  int32_t lentry = 0;
+  if ((int64_t)blockIdx.x < ntiles) {
+    fetch_tile(blockIdx.x);
+    const int64_t s = (int64_t)blockIdx.x * kHeadTile + tid;
+    if (tid < kHeadTile && s < S) lin_next = fn.load(s);
+  }
   for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
     const int64_t s0 = tile * kHeadTile;
+    const int64_t s_next = (tile + gridDim.x) * kHeadTile + tid;  // this thread's sample of the next tile
+    const bool next_live = tid < kHeadTile && tile + gridDim.x < ntiles && s_next < S;
+    const typename LossFn::In lin = lin_next;
+    if (next_live) lentry = fn.row_entry(s_next);
     __syncthreads();  // the previous tile has been consumed (and W3s is in place)
 #pragma unroll
     for (int q = 0; q < NV; ++q) {
-      const int f = tid + 256 * q;
-      const int r = f / vec_per_row, c8 = f - r * vec_per_row;
-      if (f < kHeadTile * vec_per_row) *reinterpret_cast<uint4*>(&T[r * PITCH + 8 * c8]) = tv[q];
+      const int r = tid / CPR + (256 / CPR) * q, c8 = tid % CPR;
+      if (c8 < vec_per_row) *reinterpret_cast<uint4*>(&T[r * PITCH + 8 * c8]) = tv[q];
     }
     __syncthreads();
     if (tile + gridDim.x < ntiles) fetch_tile(tile + gridDim.x);
@@ -105,6 +119,7 @@ __global__ void __launch_bounds__(256) loss_head_bf16_kernel(const bf16_t* __res
 #pragma unroll
       for (int k = 0; k < NOUT; ++k) red[(grp * NOUT + k) * kHeadTile + lane] = part[k];
     }
+    if (next_live) lin_next = fn.load_with(s_next, lentry);
     __syncthreads();
     if (tid < kHeadTile) {
       float out[NOUT], dl[NOUT];
@@ -116,7 +131,7 @@ __global__ void __launch_bounds__(256) loss_head_bf16_kernel(const bf16_t* __res
       }
       const int64_t s = s0 + tid;
       if (s < S) {
-        fn.compute(fn.load(s), prep, out, dl, st);
+        fn.compute(lin, prep, out, dl, st);
 #pragma unroll
         for (int k = 0; k < NOUT; ++k) {
           dl_out[s * NOUT + k] = dl[k];
@@ -127,7 +142,7 @@ __global__ void __launch_bounds__(256) loss_head_bf16_kernel(const bf16_t* __res
       for (int k = 0; k < 8; ++k) dls[tid * 8 + k] = k < NOUT ? dl[k < NOUT ? k : 0] : 0.f;
     }
     __syncthreads();
-    // gW3[i][k] += sum_s h2[s][i] dl[s][k]: thread -> hidden units tid, tid + 256
+    // gW3[i][k] += sum_s h2[s][i] dl[s][k]: thread -> hidden units 2 tid, 2 tid + 1 (one 4-byte LDS read per sample)
 #pragma unroll 8
     for (int s = 0; s < kHeadTile; ++s) {
       const float4 d0 = *reinterpret_cast<const float4*>(&dls[s * 8]);
@@ -136,18 +151,17 @@ __global__ void __launch_bounds__(256) loss_head_bf16_kernel(const bf16_t* __res
         const float4 d1 = *reinterpret_cast<const float4*>(&dls[s * 8 + 4]);
         dv[4] = d1.x; dv[5] = d1.y; dv[6] = d1.z; dv[7] = d1.w;
       }
+      const uint32_t hw = 2 * tid < H ? *reinterpret_cast<const uint32_t*>(&T[s * PITCH + 2 * tid]) : 0u;
+      const float hp[2] = {__uint_as_float(hw << 16), __uint_as_float(hw & 0xffff0000u)};
 #pragma unroll
-      for (int u = 0; u < UMAX; ++u) {
-        const int i = tid + 256 * u;
-        const float h = i < H ? from_bf16(T[s * PITCH + i]) : 0.f;
+      for (int u = 0; u < UMAX; ++u)
 #pragma unroll
-        for (int k = 0; k < NOUT; ++k) gw[u][k] = fmaf(h, dv[k], gw[u][k]);
-      }
+        for (int k = 0; k < NOUT; ++k) gw[u][k] = fmaf(hp[u], dv[k], gw[u][k]);
     }
   }
 #pragma unroll
   for (int u = 0; u < UMAX; ++u) {
-    const int i = tid + 256 * u;
+    const int i = 2 * tid + u;
     if (i < H) {
 #pragma unroll
       for (int k = 0; k < NOUT; ++k) {
