@@ -5,8 +5,10 @@
 // output-layer gradient (W3, b3) is accumulated in registers across the row tiles a workgroup owns.
 //
 // Workgroup = 4 wavefronts on a tile of BM samples x H hidden units: (BM/32) x (H/32) MFMA tiles of
-// 32x32, one or two per wavefront; several small workgroups per CU overlap each other's phases.  Weights stream from L2 through a 32-row LDS buffer; the next chunk
-// travels global -> registers while the current one is multiplied.
+// 32x32, one or two per wavefront; several small workgroups per CU overlap each other's phases.  The row tile of
+// the input sits in LDS at its whole width; the weights go straight from the operand-order copies in global memory
+// (L2-resident) into registers with 16-byte loads (gemm_phase_regs), so a layer has no staging buffer and no barrier
+// of its own.
 #pragma once
 #include "gemm.h"
 #include "heads.h"
@@ -19,6 +21,9 @@ struct FusedFwdArgs {
   int Din;
   int xvec;   // rows are 16-byte aligned and Din % 4 == 0: 16-byte loads of X
   const float *W1, *b1, *W2, *b2, *W3, *b3;  // aligned working copy, W[in][H]
+  const float *W1s, *W2s;  // operand-order copies: (k, n) at ((k / 4) * H + n) * 4 + k % 4; W1s zero-padded to kpad1 rows
+  int kpad1;               // Din rounded up to a multiple of 16
+  int px;                  // pitch of the X tile in LDS: a multiple of 4 with px / 4 odd, >= kpad1
   float* h1_out;   // training: [S][H]
   float* dz2_out;  // training: [S][H]
   float* gW3;      // training: [H][NOUT] accumulated with atomics
@@ -26,31 +31,30 @@ struct FusedFwdArgs {
   float* stats;    // training: 5 floats accumulated with atomics (policy loss, value loss, entropy, KL, clip fraction)
 };
 
-template <int H, int BM, int NOUT>
-struct FusedFwdLds {
-  static constexpr int PX = 36;     // pitch of the X chunk (k-contiguous, 16-byte reads)
-  static constexpr int PH = H + 4;  // pitch of the activation tile
-  static constexpr int GROUPS = 256 / BM;
-  float Xc[BM * PX];
-  float Ws[32 * H];
-  float Hs[BM * PH];
-  float red[GROUPS * BM * NOUT];
-  float dls[BM * 8];  // dL/d(outputs) of the tile, rows padded to 8 with zeros (MFMA operand)
-  float W3s[H * NOUT];
-};
+inline int fused_forward_px(int Din) {
+  int px = (Din + 15) / 16 * 16;
+  while ((px / 4) % 2 == 0) px += 4;
+  return px;
+}
 
 template <int H, int BM, int NOUT, bool TRAIN, class Finish>
 __global__ void __launch_bounds__(256, 2) fused_forward_kernel(FusedFwdArgs a, Finish fin) {
-  using Lds = FusedFwdLds<H, BM, NOUT>;
-  constexpr int PX = Lds::PX, PH = Lds::PH, GROUPS = Lds::GROUPS;
+  constexpr int PH = H + 4, GROUPS = 256 / BM;
   constexpr int NTN = H / 32, MT = BM / 32, TILES = MT * NTN, TPW = TILES / 4;
   static_assert(TILES % 4 == 0 && (TPW == 1 || TPW == 2), "4 wavefronts share the tile evenly");
   static_assert(TPW == 1 || NTN % 2 == 0, "two tiles of a wavefront share their rows");
   constexpr int NTH = 256;
-  constexpr int WV = H / 32;   // 16-byte vectors of a weight chunk per thread
-  constexpr int XS = BM / 8;   // scalars of an X chunk per thread
-  constexpr int XV = BM / 32;  // 16-byte vectors of an X chunk per thread
-  __shared__ __attribute__((aligned(16))) Lds L;
+  constexpr int TPR = NTH / BM;  // threads staging one row of X
+  extern __shared__ __attribute__((aligned(16))) float lds[];
+  struct {
+    float *Xs, *Hs, *red, *dls, *W3s;
+  } L;
+  const int px = a.px;
+  L.Xs = lds;                          // [BM][px]   input rows, k-contiguous; columns Din .. px stay zero
+  L.Hs = L.Xs + BM * px;               // [BM][PH]   h1, then h2
+  L.red = L.Hs + BM * PH;              // [GROUPS][BM][NOUT]
+  L.dls = L.red + GROUPS * BM * NOUT;  // [BM][8]    dL/d(outputs), rows padded to 8 with zeros (MFMA operand)
+  L.W3s = L.dls + BM * 8;              // [H][NOUT]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lo = lane & 31, hi = lane >> 5;
@@ -64,65 +68,45 @@ __global__ void __launch_bounds__(256, 2) fused_forward_kernel(FusedFwdArgs a, F
   for (int k = 0; k < NOUT; ++k) gw[k] = gb[k] = 0.f;
 
   for (int i = tid; i < H * NOUT; i += NTH) L.W3s[i] = a.W3[i];  // ordered before its first use by the barriers of layer 1
-  const int nk1 = (a.Din + 31) / 32;
+  for (int i = tid; i < BM * px; i += NTH) L.Xs[i] = 0.f;        // the padding columns stay zero for good
+  __syncthreads();
   const int64_t ntiles = (a.S + BM - 1) / BM;
   for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
     const int64_t s0 = tile * BM;
     const int rows_left = (int)min((int64_t)BM, a.S - s0);
     float* const h1_tile = TRAIN ? a.h1_out + s0 * H : nullptr;    // uniform bases: lanes add 32-bit offsets
     float* const dz2_tile = TRAIN ? a.dz2_out + s0 * H : nullptr;
-    // rows of X this thread stages
-    const float* xrow[XS];
-    if (a.xvec) {
-#pragma unroll
-      for (int p = 0; p < XV; ++p) xrow[p] = a.X.ptr(min(s0 + ((tid + NTH * p) >> 3), a.S - 1));
-    } else {
-#pragma unroll
-      for (int p = 0; p < XS; ++p) xrow[p] = a.X.ptr(min(s0 + ((tid + NTH * p) >> 5), a.S - 1));
-    }
-    float xr[XS];
-    float4 wr[WV];
-    auto fetch_x = [&](int k0) {
+    // ---- this tile's rows to LDS: thread -> row tid / TPR, every TPR-th 16-byte (or 4-byte) piece of it, four
+    // loads in flight at a time.  Rows past the end re-read the last row (their results are never stored).
+    {
+      const int xr_row = tid / TPR, c0 = tid % TPR;
+      const float* xrow = a.X.ptr(min(s0 + xr_row, a.S - 1));
+      float* xdst = L.Xs + xr_row * px;
       if (a.xvec) {
-        const int k = k0 + 4 * (tid & 7);
+        const int nv = a.Din / 4;
+        for (int c = c0; c < nv; c += 4 * TPR) {
+          float4 v[4];
 #pragma unroll
-        for (int p = 0; p < XV; ++p) {
-          float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-          if (k < a.Din) v = *reinterpret_cast<const float4*>(xrow[p] + k);
-          xr[4 * p] = v.x; xr[4 * p + 1] = v.y; xr[4 * p + 2] = v.z; xr[4 * p + 3] = v.w;
+          for (int u = 0; u < 4; ++u) {
+            const int cu = min(c + u * TPR, nv - 1);
+            v[u] = *reinterpret_cast<const float4*>(xrow + 4 * cu);
+          }
+#pragma unroll
+          for (int u = 0; u < 4; ++u)
+            if (c + u * TPR < nv) *reinterpret_cast<float4*>(xdst + 4 * (c + u * TPR)) = v[u];
         }
       } else {
-        const int k = k0 + (tid & 31);
+        for (int c = c0; c < a.Din; c += 4 * TPR) {
+          float v[4];
 #pragma unroll
-        for (int p = 0; p < XS; ++p) xr[p] = k < a.Din ? xrow[p][k] : 0.f;
+          for (int u = 0; u < 4; ++u) v[u] = xrow[min(c + u * TPR, a.Din - 1)];
+#pragma unroll
+          for (int u = 0; u < 4; ++u)
+            if (c + u * TPR < a.Din) xdst[c + u * TPR] = v[u];
+        }
       }
-    };
-    auto stage_x = [&]() {
-      if (a.xvec) {
-#pragma unroll
-        for (int p = 0; p < XV; ++p)
-          *reinterpret_cast<float4*>(&L.Xc[((tid + NTH * p) >> 3) * PX + 4 * (tid & 7)]) =
-              make_float4(xr[4 * p], xr[4 * p + 1], xr[4 * p + 2], xr[4 * p + 3]);
-      } else {
-#pragma unroll
-        for (int p = 0; p < XS; ++p) L.Xc[((tid + NTH * p) >> 5) * PX + (tid & 31)] = xr[p];
-      }
-    };
-    auto fetch_w = [&](const float* W, int k0, int K) {
-#pragma unroll
-      for (int p = 0; p < WV; ++p) {
-        const int f = tid + NTH * p, row = f / (H / 4), c4 = f % (H / 4);
-        wr[p] = (k0 + row < K) ? *reinterpret_cast<const float4*>(W + (int64_t)(k0 + row) * H + 4 * c4)
-                               : make_float4(0.f, 0.f, 0.f, 0.f);
-      }
-    };
-    auto stage_w = [&]() {
-#pragma unroll
-      for (int p = 0; p < WV; ++p) {
-        const int f = tid + NTH * p;
-        *reinterpret_cast<float4*>(&L.Ws[(f / (H / 4)) * H + 4 * (f % (H / 4))]) = wr[p];
-      }
-    };
+    }
+    __syncthreads();
     floatx16 acc[TPW];
     auto zero_acc = [&]() {
 #pragma unroll
@@ -130,42 +114,11 @@ __global__ void __launch_bounds__(256, 2) fused_forward_kernel(FusedFwdArgs a, F
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[q][r] = 0.f;
     };
-    // acc += A[32 rows of mt][32 k] * Ws[32 k][32 cols of each tile]; A is k-contiguous in LDS
-    auto mma_chunk = [&](const float* A, int pitch, int koff) {
-#pragma unroll
-      for (int kb = 0; kb < 32; kb += 8) {
-        const float4 av = *reinterpret_cast<const float4*>(&A[(mt * 32 + lo) * pitch + koff + kb + 4 * hi]);
-        const float af[4] = {av.x, av.y, av.z, av.w};
-        float bf[TPW][4];
-#pragma unroll
-        for (int q = 0; q < TPW; ++q)
-#pragma unroll
-          for (int j = 0; j < 4; ++j) bf[q][j] = L.Ws[(kb + 4 * hi + j) * H + (nt0 + q) * 32 + lo];
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-          for (int q = 0; q < TPW; ++q) acc[q] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[j], bf[q][j], acc[q], 0, 0, 0);
-      }
-    };
-
     // ---- layer 1: h1 = tanh(X W1 + b1) -> LDS (and HBM when training)
     zero_acc();
-    fetch_x(0);
-    fetch_w(a.W1, 0, a.Din);
-#pragma unroll 1
-    for (int c = 0; c < nk1; ++c) {
-      stage_x();
-      stage_w();
-      __syncthreads();
-      if (c + 1 < nk1) {
-        fetch_x(32 * (c + 1));
-        fetch_w(a.W1, 32 * (c + 1), a.Din);
-      } else {
-        fetch_w(a.W2, 0, H);
-      }
-      mma_chunk(L.Xc, PX, 0);
-      __syncthreads();
-    }
+#pragma unroll
+    for (int q = 0; q < TPW; ++q)
+      gemm_phase_regs<H>(L.Xs + (mt * 32 + lo) * px + 4 * hi, a.W1s + (hi * H + (nt0 + q) * 32 + lo) * 4, a.kpad1 / 16, acc[q]);
 #pragma unroll
     for (int q = 0; q < TPW; ++q) {
       const int n = (nt0 + q) * 32 + lo;
@@ -179,16 +132,13 @@ __global__ void __launch_bounds__(256, 2) fused_forward_kernel(FusedFwdArgs a, F
         if ((r & 3) == 3) __builtin_amdgcn_sched_barrier(0);  // four elements in flight at a time keeps registers bounded
       }
     }
+    __syncthreads();  // the h1 tile is complete
     // ---- layer 2: h2 = tanh(h1 W2 + b2), kept in registers
     zero_acc();
-#pragma unroll 1
-    for (int c = 0; c < H / 32; ++c) {
-      stage_w();
-      __syncthreads();  // also orders the h1 tile before its first use
-      if (c + 1 < H / 32) fetch_w(a.W2, 32 * (c + 1), H);
-      mma_chunk(L.Hs, PH, 32 * c);
-      __syncthreads();
-    }
+#pragma unroll
+    for (int q = 0; q < TPW; ++q)
+      gemm_phase_regs<H>(L.Hs + (mt * 32 + lo) * PH + 4 * hi, a.W2s + (hi * H + (nt0 + q) * 32 + lo) * 4, H / 16, acc[q]);
+    __syncthreads();  // every wavefront is past its last read of h1
 #pragma unroll
     for (int q = 0; q < TPW; ++q) {
       const int n = (nt0 + q) * 32 + lo;
@@ -198,7 +148,7 @@ __global__ void __launch_bounds__(256, 2) fused_forward_kernel(FusedFwdArgs a, F
         const int m = mt * 32 + 8 * (r / 4) + 4 * hi + (r % 4);
         float v = tanh_f32(acc[q][r] + bias);
         acc[q][r] = v;
-        L.Hs[m * PH + n] = v;  // every wavefront is past its last read of h1 (barrier above)
+        L.Hs[m * PH + n] = v;
         if ((r & 3) == 3) __builtin_amdgcn_sched_barrier(0);
       }
     }
@@ -300,18 +250,37 @@ __global__ void __launch_bounds__(256, 2) fused_forward_kernel(FusedFwdArgs a, F
 }
 
 // Which (H, BM) pairs exist: H = 64 -> BM 64; H = 128 or 256 -> BM 32.
-inline bool fused_forward_supported(int H) { return H == 64 || H == 128 || H == 256; }
+inline size_t fused_forward_lds_bytes(int H, int Din, int nout) {
+  const size_t bm = H == 64 ? 64 : 32;
+  return (bm * fused_forward_px(Din) + bm * (H + 4) + 256 * (size_t)nout + bm * 8 + (size_t)H * nout) * sizeof(float);
+}
+// The row tile of the input sits in LDS at its whole width, which bounds the input width (two workgroups per CU up
+// to about 320 inputs at H = 256, one up to about 950); wider networks take the layer-by-layer kernels.
+inline bool fused_forward_supported(int H, int Din) {
+  return (H == 64 || H == 128 || H == 256) && fused_forward_lds_bytes(H, Din, 6) <= 160 * 1024;
+}
+
+template <int H, int BM, int NOUT, bool TRAIN, class Finish>
+inline void launch_fused_forward_inst(const FusedFwdArgs& a, const Finish& fin, hipStream_t s) {
+  auto kern = fused_forward_kernel<H, BM, NOUT, TRAIN, Finish>;
+  const size_t bytes = fused_forward_lds_bytes(H, a.Din, NOUT);
+  static bool configured = false;  // per instantiation
+  if (!configured) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return;
+    configured = true;
+  }
+  const int64_t tiles = (a.S + BM - 1) / BM;
+  const unsigned grid = (unsigned)std::min<int64_t>(tiles, TRAIN ? 1024 : 2048);  // persistent when training (register-resident W3 gradient)
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), bytes, s, a, fin);
+}
 
 template <int NOUT, bool TRAIN, class Finish>
 inline void launch_fused_forward(int H, const FusedFwdArgs& a, const Finish& fin, hipStream_t s) {
   // algorithmic flops of the two hidden layers
   TimedLaunch timed(KC_GEMM_NN, 2.0 * (double)a.S * ((double)a.Din * H + (double)H * H), s);
-  const int64_t bm = H == 64 ? 64 : 32;
-  const int64_t tiles = (a.S + bm - 1) / bm;
-  const unsigned grid = (unsigned)std::min<int64_t>(tiles, TRAIN ? 1024 : 2048);  // persistent when training (register-resident W3 gradient)
-  if (H == 64) hipLaunchKernelGGL((fused_forward_kernel<64, 64, NOUT, TRAIN, Finish>), dim3(grid), dim3(256), 0, s, a, fin);
-  else if (H == 128) hipLaunchKernelGGL((fused_forward_kernel<128, 32, NOUT, TRAIN, Finish>), dim3(grid), dim3(256), 0, s, a, fin);
-  else hipLaunchKernelGGL((fused_forward_kernel<256, 32, NOUT, TRAIN, Finish>), dim3(grid), dim3(256), 0, s, a, fin);
+  if (H == 64) launch_fused_forward_inst<64, 64, NOUT, TRAIN, Finish>(a, fin, s);
+  else if (H == 128) launch_fused_forward_inst<128, 32, NOUT, TRAIN, Finish>(a, fin, s);
+  else launch_fused_forward_inst<256, 32, NOUT, TRAIN, Finish>(a, fin, s);
 }
 
 }  // namespace marl

@@ -98,6 +98,46 @@ __device__ __forceinline__ float tanh_f32(float x) {
   return 1.0f - 2.0f * __builtin_amdgcn_rcpf(e + 1.0f);
 }
 
+// acc += A B for this wavefront's 32x32 tile: A rows in LDS (As points at this lane's row, + 4 * hi), B in global
+// memory in operand order (element (k, n) of the [K][LDB] matrix at ((k / 4) * LDB + n) * 4 + k % 4; Bg points at
+// this lane's 16 bytes of k quad `hi`), `kgroups` groups of 16 along k.  B goes straight from the cache hierarchy
+// into registers with 16-byte loads that are contiguous across the wavefront, one group ahead of its use, so a
+// layer needs no staging buffer and no barrier of its own.  Both operands must be readable (zero-padded) up to
+// 16 * kgroups along k.
+template <int LDB>
+__device__ __forceinline__ void gemm_phase_regs(const float* __restrict__ As, const float* __restrict__ Bg, int kgroups,
+                                                floatx16& acc) {
+  constexpr int kDepth = 3;  // groups in flight: the one in use and two on their way
+  float4 av[kDepth][2], bv[kDepth][2];
+  auto load = [&](int g, float4 (&a2)[2], float4 (&b2)[2]) {
+    const int gc = g < kgroups ? g : kgroups - 1;  // past the end: re-read the last group
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      a2[u] = *reinterpret_cast<const float4*>(As + 16 * gc + 8 * u);
+      b2[u] = *reinterpret_cast<const float4*>(Bg + ((int64_t)16 * gc + 8 * u) * LDB);
+    }
+  };
+#pragma unroll
+  for (int d = 0; d < kDepth - 1; ++d) load(d, av[d], bv[d]);
+#pragma unroll 1
+  for (int g0 = 0; g0 < kgroups; g0 += kDepth) {
+#pragma unroll
+    for (int d = 0; d < kDepth; ++d) {
+      const int g = g0 + d;
+      if (g < kgroups) {  // uniform
+        load(g + kDepth - 1, av[(d + kDepth - 1) % kDepth], bv[(d + kDepth - 1) % kDepth]);
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const float af[4] = {av[d][u].x, av[d][u].y, av[d][u].z, av[d][u].w};
+          const float bf[4] = {bv[d][u].x, bv[d][u].y, bv[d][u].z, bv[d][u].w};
+#pragma unroll
+          for (int j = 0; j < 4; ++j) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(af[j], bf[j], acc, 0, 0, 0);
+        }
+      }
+    }
+  }
+}
+
 constexpr int kGemmBK = 16;
 
 template <int MODE, int EPI, int BM, int BN, int WGM, int WGN>

@@ -63,11 +63,13 @@ struct CriticRolloutFinish {
   }
 };
 
-FusedFwdArgs fused_args(const RowSrc& X, int64_t S, int Din, const float* eff, const NetOffsets& o, bool bf16) {
+FusedFwdArgs fused_args(const RowSrc& X, int64_t S, int Din, const float* eff, const ParamMap& pm, int net) {
+  const NetOffsets o = padded_offsets(pm, net);
   FusedFwdArgs a{};
   a.X = X; a.S = S; a.Din = Din;
   a.xvec = aligned16(X.base) && X.ld % 4 == 0 && Din % 4 == 0;
   a.W1 = eff + o.W1; a.b1 = eff + o.b1; a.W2 = eff + o.W2; a.b2 = eff + o.b2; a.W3 = eff + o.W3; a.b3 = eff + o.b3;
+  a.W1s = eff + pm.sw_w1[net]; a.W2s = eff + pm.sw_w2[net]; a.kpad1 = pm.kpad1[net]; a.px = fused_forward_px(Din);
   return a;
 }
 
@@ -183,9 +185,9 @@ static int32_t forward_rows(const marl_config& c, const float* eff, const float*
   if (want_actor) {
     const NetOffsets o = padded_offsets(param_map(d), 0);
     const RowSrc X{obs, d.D, nullptr, 1, S};
-    if (fused_forward_supported(d.Ha)) {
+    if (fused_forward_supported(d.Ha, d.D)) {
       ActorRolloutFinish fin{logits_out, sample ? *sample : SampleArgs{}, sample ? 1 : 0};
-      launch_fused_forward<kActions, false>(d.Ha, fused_args(X, S, d.D, eff, o, d.bf16), fin, s);
+      launch_fused_forward<kActions, false>(d.Ha, fused_args(X, S, d.D, eff, param_map(d), 0), fin, s);
     } else {
       mlp_hidden_forward(X, S, d.D, d.Ha, eff + o.W1, eff + o.b1, eff + o.W2, eff + o.b2, w.h1a, w.h2a, d.bf16, s);
       launch_actor_head_rollout(w.h2a, S, d.Ha, eff + o.W3, eff + o.b3, logits_out, sample, s);
@@ -195,9 +197,9 @@ static int32_t forward_rows(const marl_config& c, const float* eff, const float*
     const NetOffsets o = padded_offsets(param_map(d), 1);
     const int64_t Sc = d.central ? n_rows : S;
     const RowSrc X{obs, d.Dc, nullptr, 1, Sc};
-    if (fused_forward_supported(d.Hc)) {
+    if (fused_forward_supported(d.Hc, d.Dc)) {
       CriticRolloutFinish fin{value_out, d.central ? d.A : 1};
-      launch_fused_forward<1, false>(d.Hc, fused_args(X, Sc, d.Dc, eff, o, d.bf16), fin, s);
+      launch_fused_forward<1, false>(d.Hc, fused_args(X, Sc, d.Dc, eff, param_map(d), 1), fin, s);
     } else {
       mlp_hidden_forward(X, Sc, d.Dc, d.Hc, eff + o.W1, eff + o.b1, eff + o.W2, eff + o.b2, w.h1c, w.h2c, d.bf16, s);
       launch_critic_head_rollout(w.h2c, Sc, d.Hc, eff + o.W3, eff + o.b3, value_out, d.central ? d.A : 1, s);
@@ -234,7 +236,7 @@ int32_t launch_rollout(const marl_config& c, marl_env_state st, const float* par
   // The values do not steer the rollout (the parameters are constant during it): where the critic's forward pass
   // needs no per-row workspace (the fused fp32 kernel), all T steps' values are computed in one pass over the stored
   // observations afterwards instead of one small launch per step.
-  const bool batch_values = !d.bf16 && fused_forward_supported(d.Hc);
+  const bool batch_values = !d.bf16 && fused_forward_supported(d.Hc, d.Dc);
   for (int t = 0; t < d.T; ++t) {
     SampleArgs a{};
     a.uniforms = forced_uniforms ? forced_uniforms + (int64_t)t * NA * kActions : nullptr;

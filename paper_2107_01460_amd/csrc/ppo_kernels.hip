@@ -469,7 +469,7 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
       }
       // ---- actor
       const RowSrc Xa{tr.obs, d.D, rows, d.A, Sa};
-      const bool fused_a = fused_forward_supported(d.Ha);
+      const bool fused_a = fused_forward_supported(d.Ha, d.D);
       {
         ActorLoss fn{lc, tr.action, tr.logp, tr.adv};
         if (d.bf16) {
@@ -491,6 +491,7 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
             fa.W1 = eff + oa.W1; fa.b1 = eff + oa.b1; fa.W2 = eff + oa.W2; fa.b2 = eff + oa.b2; fa.W3 = eff + oa.W3;
             fa.b3 = eff + oa.b3; fa.h1_out = w.h1a; fa.dz2_out = w.h2a; fa.gW3 = w.grad + ga.W3; fa.gb3 = w.grad + ga.b3;
             fa.stats = w.sc->acc;
+            fa.W1s = eff + pm.sw_w1[0]; fa.W2s = eff + pm.sw_w2[0]; fa.kpad1 = pm.kpad1[0]; fa.px = fused_forward_px(d.D);
             launch_fused_forward<kActions, true>(d.Ha, fa, fn, s);
           } else {
             mlp_hidden_forward(Xa, Sa, d.D, d.Ha, eff + oa.W1, eff + oa.b1, eff + oa.W2, eff + oa.b2, w.h1a, w.h2a, d.bf16, s);
@@ -504,7 +505,7 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
       }
       // ---- critic
       const RowSrc Xc{tr.obs, d.Dc, rows, d.central ? 1 : d.A, Sc};
-      const bool fused_c = fused_forward_supported(d.Hc);
+      const bool fused_c = fused_forward_supported(d.Hc, d.Dc);
       {
         CriticLoss fn{lc, tr.ret, tr.value, d.central ? d.A : 1};
         if (d.bf16) {
@@ -532,6 +533,7 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
             fa.W1 = eff + oc.W1; fa.b1 = eff + oc.b1; fa.W2 = eff + oc.W2; fa.b2 = eff + oc.b2; fa.W3 = eff + oc.W3;
             fa.b3 = eff + oc.b3; fa.h1_out = w.h1c; fa.dz2_out = w.h2c; fa.gW3 = w.grad + gc.W3; fa.gb3 = w.grad + gc.b3;
             fa.stats = w.sc->acc;
+            fa.W1s = eff + pm.sw_w1[1]; fa.W2s = eff + pm.sw_w2[1]; fa.kpad1 = pm.kpad1[1]; fa.px = fused_forward_px(d.Dc);
             launch_fused_forward<1, true>(d.Hc, fa, fn, s);
           } else {
             mlp_hidden_forward(Xc, Sc, d.Dc, d.Hc, eff + oc.W1, eff + oc.b1, eff + oc.W2, eff + oc.b2, w.h1c, w.h2c, d.bf16, s);
