@@ -218,6 +218,14 @@ def test_bf16_other_widths(M, orc, ha, hc, view):
     check_single_minibatch_gradient(M, orc, small(4, n_epochs=1, n_minibatches=1, max_grad_norm=0.0, **kw), 4)
 
 
+def test_wide_central_critic(M, orc):
+    """A centralised critic whose input (8 agents x 147 = 1176 values) is wider than the fused forward kernel
+    keeps in LDS: its forward pass, loss and gradient take the layer-by-layer kernels."""
+    kw = dict(n_agents=8, view=7, n_food=5)
+    check_policy_forward(M, orc, small(3, **kw), 31)
+    check_single_minibatch_gradient(M, orc, small(3, n_epochs=1, n_minibatches=1, max_grad_norm=0.0, **kw), 3)
+
+
 def check_single_minibatch_gradient(M, orc, cfg, k):
     print("case", cfg["name"], flush=True)
     params0, otr = oracle_traj(orc, cfg)
