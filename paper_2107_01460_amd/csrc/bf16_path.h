@@ -80,70 +80,6 @@ static __global__ void __launch_bounds__(256) pack_obs_bf16_kernel(RowSrc X, int
   }
 }
 
-// In place: H2[s][j] <- (sum_k dl[s][k] W3[j][k]) * (1 - H2[s][j]^2); dz2T [H][Sp] (sample-blocked) gets the transposed copy (zeros past S).
-// One workgroup per tile of 64 samples x 64 hidden units; a thread owns eight consecutive hidden units of two rows
-// (16-byte loads and stores, no branches: rows past the end are clamped for the loads and produce zeros), and eight
-// consecutive samples of two hidden units for the transposed copy, which goes through an LDS tile.
-template <int NOUT>
-static __global__ void __launch_bounds__(256) dz2_bf16_kernel(bf16_t* __restrict__ H2, bf16_t* __restrict__ dz2T,
-                                                              const float* __restrict__ dl, const float* __restrict__ W3,
-                                                              int64_t S, int64_t Sp, int H) {
-  constexpr int PT = 72;  // pitch of the tile in elements: 16-byte aligned rows, 36 dwords (4 * odd)
-  __shared__ __attribute__((aligned(16))) bf16_t tile[64 * PT];
-  const int tid = threadIdx.x;
-  const int64_t s0 = (int64_t)blockIdx.x * 64;
-  const int j0 = blockIdx.y * 64;
-  const int c8 = tid & 7, j = j0 + 8 * c8;  // H is a multiple of 64
-  float w[8][NOUT];
-#pragma unroll
-  for (int e = 0; e < 8; ++e)
-#pragma unroll
-    for (int k = 0; k < NOUT; ++k) w[e][k] = W3[(int64_t)(j + e) * NOUT + k];
-  uint4 hv[2];
-  float dlv[2][NOUT];
-#pragma unroll
-  for (int q = 0; q < 2; ++q) {
-    const int64_t s = min(s0 + (tid >> 3) + 32 * q, S - 1);
-    hv[q] = *reinterpret_cast<const uint4*>(&H2[s * H + j]);
-#pragma unroll
-    for (int k = 0; k < NOUT; ++k) dlv[q][k] = dl[s * NOUT + k];
-  }
-#pragma unroll
-  for (int q = 0; q < 2; ++q) {
-    const int r = (tid >> 3) + 32 * q;
-    const bool live = s0 + r < S;
-    const uint32_t hw[4] = {hv[q].x, hv[q].y, hv[q].z, hv[q].w};
-    uint32_t ow[4];
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      float o2[2];
-#pragma unroll
-      for (int z = 0; z < 2; ++z) {
-        const float h = __uint_as_float(z == 0 ? hw[p] << 16 : hw[p] & 0xffff0000u);
-        float g = 0.f;
-#pragma unroll
-        for (int k = 0; k < NOUT; ++k) g = fmaf(dlv[q][k], w[2 * p + z][k], g);
-        o2[z] = live ? g * (1.0f - h * h) : 0.f;
-      }
-      ow[p] = pack2_bf16(o2[0], o2[1]);
-    }
-    const uint4 ov = make_uint4(ow[0], ow[1], ow[2], ow[3]);
-    if (live) *reinterpret_cast<uint4*>(&H2[(s0 + r) * H + j]) = ov;
-    *reinterpret_cast<uint4*>(&tile[r * PT + 8 * c8]) = ov;
-  }
-  __syncthreads();
-  // transposed copy: thread -> hidden unit dd = tid / 8 + 32 q, samples 8 (tid % 8) .. + 7
-#pragma unroll
-  for (int q = 0; q < 2; ++q) {
-    const int dd = (tid >> 3) + 32 * q, ss = 8 * (tid & 7);
-    uint32_t ow[4];
-#pragma unroll
-    for (int p = 0; p < 4; ++p)
-      ow[p] = (uint32_t)tile[(ss + 2 * p) * PT + dd] | ((uint32_t)tile[(ss + 2 * p + 1) * PT + dd] << 16);
-    if (s0 + ss < Sp) *reinterpret_cast<uint4*>(&dz2T[((s0 >> 6) * H + j0 + dd) * 64 + ss]) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
-  }
-}
-
 }  // namespace bf16_detail
 
 inline void stage_weights_bf16(const float* W1, const float* W2, int Din, int H, const Bf16NetWeights& w, hipStream_t s) {

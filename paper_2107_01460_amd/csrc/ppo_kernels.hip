@@ -23,13 +23,15 @@ Bf16NetWeights effective_bf16_weights(const marl_config& c, const float* eff, in
 
 namespace {
 
-// Output layer + loss + W3 / b3 gradient for bf16 activations of up to HMAX hidden units.  The whole 64-sample
-// tile of h2 sits in LDS as bf16 (one pass over HBM, 16-byte loads) and serves both the output layer and the
-// W3 gradient.  Persistent over tiles so that the gradients and statistics leave a workgroup once.
+// Output layer + loss + W3 / b3 gradient + dz2 for bf16 activations of up to HMAX hidden units.  The whole 64-sample
+// tile of h2 sits in LDS as bf16 (one pass over HBM, 16-byte loads) and serves the output layer, the W3 gradient
+// and dz2 = (dL/dout W3^T) * (1 - h2^2), which overwrites h2 in place (row-major, the A operand of dz1) and goes to
+// the sample-blocked transposed copy dz2T (zeros for the samples S .. 64 * tiles; the B operand of the W2 gradient).
+// Persistent over tiles so that the gradients and statistics leave a workgroup once.
 template <int NOUT, class LossFn, int HMAX>
-__global__ void __launch_bounds__(256) loss_head_bf16_kernel(const bf16_t* __restrict__ H2, int64_t S, int H,
+__global__ void __launch_bounds__(256) loss_head_bf16_kernel(bf16_t* __restrict__ H2, int64_t S, int H,
                                                              const float* __restrict__ W3, const float* __restrict__ b3,
-                                                             LossFn fn, float* __restrict__ dl_out, float* __restrict__ gW3,
+                                                             LossFn fn, bf16_t* __restrict__ dz2T, float* __restrict__ gW3,
                                                              float* __restrict__ gb3, Scalars* sc, float* __restrict__ partial) {
   // partial (nullable): this workgroup's W3 / b3 gradient goes to partial + blockIdx.x * (H * NOUT + NOUT) with plain
   // stores and is added to gW3 (with gb3 directly behind it) by the reduction kernel afterwards
@@ -41,6 +43,15 @@ __global__ void __launch_bounds__(256) loss_head_bf16_kernel(const bf16_t* __res
   const int tid = threadIdx.x, lane = tid & 63, grp = tid >> 6;
   for (int e = tid; e < H * NOUT; e += 256) W3s[e] = W3[e];
   const auto prep = fn.prepare();
+  // dz2: thread -> the eight hidden units 8 (tid % CPR) .. + 7 of the rows tid / CPR + (256 / CPR) q; their W3 rows
+  float w8[8][NOUT];
+#pragma unroll
+  for (int e = 0; e < 8; ++e)
+#pragma unroll
+    for (int k = 0; k < NOUT; ++k) {
+      const int i = 8 * (tid % (HMAX / 8)) + e;
+      w8[e][k] = i < H ? W3[(int64_t)i * NOUT + k] : 0.f;
+    }
   constexpr int UMAX = HMAX / 256;  // hidden units per thread in the W3 gradient
   static_assert(UMAX == 2, "a thread owns one pair of neighbouring hidden units");
   float gw[UMAX][NOUT], gb[NOUT], st[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
@@ -133,10 +144,7 @@ __global__ void __launch_bounds__(256) loss_head_bf16_kernel(const bf16_t* __res
       if (s < S) {
         fn.compute(lin, prep, out, dl, st);
 #pragma unroll
-        for (int k = 0; k < NOUT; ++k) {
-          dl_out[s * NOUT + k] = dl[k];
-          gb[k] += dl[k];
-        }
+        for (int k = 0; k < NOUT; ++k) gb[k] += dl[k];
       }
 #pragma unroll
       for (int k = 0; k < 8; ++k) dls[tid * 8 + k] = k < NOUT ? dl[k < NOUT ? k : 0] : 0.f;
@@ -157,6 +165,48 @@ __global__ void __launch_bounds__(256) loss_head_bf16_kernel(const bf16_t* __res
       for (int u = 0; u < UMAX; ++u)
 #pragma unroll
         for (int k = 0; k < NOUT; ++k) gw[u][k] = fmaf(hp[u], dv[k], gw[u][k]);
+    }
+    __syncthreads();  // every thread has read the h2 it needs; the tile is overwritten with dz2
+#pragma unroll 4
+    for (int q = 0; q < NV; ++q) {
+      const int r = tid / CPR + (256 / CPR) * q, c8 = tid % CPR;
+      if (c8 < vec_per_row) {
+        const uint4 hv = *reinterpret_cast<const uint4*>(&T[r * PITCH + 8 * c8]);
+        const float4 d0 = *reinterpret_cast<const float4*>(&dls[r * 8]);
+        float dv[8] = {d0.x, d0.y, d0.z, d0.w, 0.f, 0.f, 0.f, 0.f};
+        if (NOUT > 4) {
+          const float4 d1 = *reinterpret_cast<const float4*>(&dls[r * 8 + 4]);
+          dv[4] = d1.x; dv[5] = d1.y; dv[6] = d1.z; dv[7] = d1.w;
+        }
+        const uint32_t hw[4] = {hv.x, hv.y, hv.z, hv.w};
+        uint32_t ow[4];
+#pragma unroll
+        for (int p2 = 0; p2 < 4; ++p2) {
+          float o2[2];
+#pragma unroll
+          for (int z = 0; z < 2; ++z) {
+            const float h = __uint_as_float(z == 0 ? hw[p2] << 16 : hw[p2] & 0xffff0000u);
+            float g = 0.f;
+#pragma unroll
+            for (int k = 0; k < NOUT; ++k) g = fmaf(dv[k], w8[2 * p2 + z][k], g);
+            o2[z] = g * (1.0f - h * h);  // rows past the end carry dl = 0
+          }
+          ow[p2] = pack2_bf16(o2[0], o2[1]);
+        }
+        const uint4 ov = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+        if (s0 + r < S) *reinterpret_cast<uint4*>(&H2[(s0 + r) * H + 8 * c8]) = ov;
+        *reinterpret_cast<uint4*>(&T[r * PITCH + 8 * c8]) = ov;
+      }
+    }
+    __syncthreads();
+    // transposed copy: thread -> hidden unit tid / 8 + 32 q, samples 8 (tid % 8) .. + 7 (a wavefront writes 1 KB in one piece)
+    for (int q = 0; 32 * q < H; ++q) {
+      const int dd = (tid >> 3) + 32 * q, ss = 8 * (tid & 7);
+      uint32_t ow[4];
+#pragma unroll
+      for (int p2 = 0; p2 < 4; ++p2)
+        ow[p2] = (uint32_t)T[(ss + 2 * p2) * PITCH + dd] | ((uint32_t)T[(ss + 2 * p2 + 1) * PITCH + dd] << 16);
+      *reinterpret_cast<uint4*>(&dz2T[((s0 >> 6) * H + dd) * 64 + ss]) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
     }
   }
 #pragma unroll
@@ -387,11 +437,10 @@ void train_net_bf16(const RowSrc& X, int64_t S, int Din, int H, const Bf16NetWei
   mlp_hidden_forward_bf16(w.xb, S, Sp, H, bw, eff + o.b1, eff + o.b2, w.bh1, w.bh1T, w.bh2, s);
   const unsigned nb = (unsigned)std::min<int64_t>(512, (S + kHeadTile - 1) / kHeadTile);
   float* const hp = (go.b3 == go.W3 + (int64_t)H * NOUT) ? w.partial_head : nullptr;  // b3's gradient directly follows W3's
+  // output layer, loss and dz2 in one pass over h2 (the tiles cover the samples up to Sp: dz2T is zero-padded)
   hipLaunchKernelGGL((loss_head_bf16_kernel<NOUT, LossFn, 512>), dim3(nb), dim3(256), 0, s, w.bh2, S, H, eff + o.W3,
-                     eff + o.b3, fn, dl, grad + go.W3, grad + go.b3, w.sc, hp);
+                     eff + o.b3, fn, w.dz2T, grad + go.W3, grad + go.b3, w.sc, hp);
   if (hp != nullptr) launch_reduce_partials(hp, (int)nb, (int64_t)H * NOUT + NOUT, grad + go.W3, s);
-  hipLaunchKernelGGL(bf16_detail::dz2_bf16_kernel<NOUT>, dim3((unsigned)(Sp / 64), (unsigned)((H + 63) / 64)), dim3(256), 0,
-                     s, w.bh2, w.dz2T, dl, eff + o.W3, S, Sp, H);
   auto k_split = [&](int64_t tiles_mn) {  // ~4 workgroups per CU, k ranges in multiples of the k tile
     const int64_t want = std::max<int64_t>(1, 1024 / std::max<int64_t>(1, tiles_mn));
     return std::max<int64_t>(512, round_up64((Sp + want - 1) / want));
