@@ -286,80 +286,79 @@ __global__ void __launch_bounds__(256, 2) gemm_bf16_kernel(GemmBf16Args g) {
   }
 }
 
-// The same product on a 256 x 256 x 64 workgroup tile: four wavefronts, each a 128 x 128 quadrant (4 x 4 MFMA tiles,
-// accumulators in the upper half of the 512-register file, one wavefront per SIMD).  An operand fragment read from
-// LDS feeds four MFMAs instead of two, which halves the LDS bandwidth per flop: with 2 x 2 tiles per wavefront
-// the 128 B/clk of LDS saturate at half the bf16 matrix rate.  Serves the weight gradients (split over the samples,
-// fp32 atomics) only: with an element-wise epilogue its 256 values per lane cost more than the tile gains.
+// The weight gradients (k split over workgroups, fp32 atomics) on a 256 x 256 x 64 workgroup tile: eight wavefronts
+// (2 x 4, each 128 x 64: 4 x 2 MFMA tiles, 128 accumulators).  An operand fragment read from LDS feeds more MFMAs
+// than in the 128 x 128 kernel, two wavefronts per SIMD cover each other's LDS and barrier latencies, and two
+// register sets of staged operands keep two 64 KB chunks per CU on their way.  (A four-wavefront form with 256
+// accumulators per lane has room for one set only and measured 10 % slower; with an element-wise epilogue the big
+// tile loses more than it gains, so the products with an epilogue do not use it.)  The operands are the sample-blocked
+// transposed copies: a chunk of 256 rows is 32 KB of contiguous memory.
 template <int EPI>
-__global__ void __launch_bounds__(256, 1) gemm_bf16_big_kernel(GemmBf16Args g) {
+__global__ void __launch_bounds__(512, 1) gemm_bf16_big_kernel(GemmBf16Args g) {
   static_assert(EPI == BEPI_ATOMIC, "weight gradients only");
   constexpr int BM = 256, BN = 256, BK = 64, P = BK + 8;
-  constexpr bool KBLK = true;  // the operands are sample-blocked transposed copies
-  // two stages of operand tiles: while stage c is multiplied, stage c + 1 sits in LDS and stage c + 2 is on its way
-  // from memory in registers -- the loop is bound by (bytes in flight per CU) / (memory latency), not by the MFMAs
-  __shared__ __attribute__((aligned(16))) bf16_t smem[2 * 2 * BM * P];
+  extern __shared__ __attribute__((aligned(16))) bf16_t big_lds[];  // two stages of [A 256 rows | B 256 rows] x P
+  bf16_t* const smem = big_lds;
   constexpr int STAGE = 2 * BM * P;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1, lo = lane & 31, hi = lane >> 5;
-  // 1-D grid: logical index = (split, m tile, n tile) with the n tile fastest, in XCD-aware order, so that the
-  // workgroups that share an A panel (and, for the split products, a k slab) run on one XCD and meet in its L2
+  const int wm = wave >> 2, wn = wave & 3, lo = lane & 31, hi = lane >> 5;
   const unsigned logical = xcd_remap(blockIdx.x, gridDim.x);
   const unsigned tn = logical % g.tiles_n, tmn = logical / g.tiles_n;
   const unsigned tm = tmn % g.tiles_m, split = tmn / g.tiles_m;
   const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
-  int64_t k_begin = 0, k_end = g.K;
-  if (EPI == BEPI_ATOMIC) {
-    k_begin = (int64_t)split * g.k_per_split;
-    k_end = min(g.K, k_begin + g.k_per_split);
-  }
+  const int64_t k_begin = (int64_t)split * g.k_per_split, k_end = min(g.K, k_begin + g.k_per_split);
 
-  floatx16 acc[4][4];
+  floatx16 acc[4][2];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  // staging: thread -> rows tid/8 + 32p (p < 8), 16-byte segment tid%8 of the 128-byte k-chunk of each row
+  // staging: thread -> rows tid / 8 + 64 p (p < 4) of each operand, 16-byte segment tid % 8 of the row's chunk
   const int seg = tid & 7, srow = tid >> 3;
-  // element offsets inside a chunk of the sample-blocked operands (64 elements per row); the chunk's base is uniform
-  uint32_t aoff[8], boff[8];
+  uint32_t aoff[4], boff[4];
 #pragma unroll
-  for (int p = 0; p < 8; ++p) {
-    aoff[p] = (uint32_t)min(m0 + srow + 32 * p, g.a_rows - 1) * 64u + 8u * seg;  // rows past the end re-read the last one
-    boff[p] = (uint32_t)min(n0 + srow + 32 * p, g.b_rows - 1) * 64u + 8u * seg;
+  for (int p = 0; p < 4; ++p) {
+    aoff[p] = (uint32_t)min(m0 + srow + 64 * p, g.a_rows - 1) * 64u + 8u * seg;  // rows past the end re-read the last one
+    boff[p] = (uint32_t)min(n0 + srow + 64 * p, g.b_rows - 1) * 64u + 8u * seg;
   }
-  // One register set (a second one spills beside 256 accumulators): chunk j is requested two iterations before
-  // it is multiplied and written to LDS stage j & 1 one iteration before; one barrier per chunk.
-  u32x4 ra0[8], rb0[8];
-  float bsum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  const bool want_bsum = EPI == BEPI_ATOMIC && g.rowsum_b != nullptr && tm == 0;
+  u32x4 ra0[4], rb0[4], ra1[4], rb1[4];
+  float bsum[4] = {0.f, 0.f, 0.f, 0.f};
+  const bool want_bsum = g.rowsum_b != nullptr && tm == 0;
   const int nchunks = (int)((k_end - k_begin + BK - 1) / BK);
   const int64_t astep = g.a_rows * 64, bstep = g.b_rows * 64;  // elements from one chunk to the next
-  // (the register set is named, not handed to these helpers through a reference: see gemm_bf16_kernel)
-  auto fetch = [&](int i) {
-    if (i >= nchunks) return;
-    const int64_t c = k_begin / BK + i;
+  auto fetch = [&](int i, auto set) {
+    const int64_t c = k_begin / BK + (i < nchunks ? i : nchunks - 1);  // past the end: the last chunk again, never staged
     const bf16_t* const pa = g.A + c * astep;
     const bf16_t* const pb = g.B + c * bstep;
 #pragma unroll
-    for (int p = 0; p < 8; ++p) {
-      ra0[p] = *reinterpret_cast<const u32x4*>(pa + aoff[p]);
-      rb0[p] = *reinterpret_cast<const u32x4*>(pb + boff[p]);
+    for (int p = 0; p < 4; ++p) {
+      if constexpr (decltype(set)::value == 0) {
+        ra0[p] = *reinterpret_cast<const u32x4*>(pa + aoff[p]);
+        rb0[p] = *reinterpret_cast<const u32x4*>(pb + boff[p]);
+      } else {
+        ra1[p] = *reinterpret_cast<const u32x4*>(pa + aoff[p]);
+        rb1[p] = *reinterpret_cast<const u32x4*>(pb + boff[p]);
+      }
     }
   };
-  auto stage = [&](int buf) {
+  auto stage = [&](int buf, auto set, bool live) {  // live: the chunk exists (one past the end is staged but never multiplied)
     bf16_t* As = smem + buf * STAGE;
     bf16_t* Bs = As + BM * P;
 #pragma unroll
-    for (int p = 0; p < 8; ++p) {
-      const u32x4 va = ra0[p], vb = rb0[p];
-      *reinterpret_cast<u32x4*>(&As[(srow + 32 * p) * P + 8 * seg]) = va;
-      *reinterpret_cast<u32x4*>(&Bs[(srow + 32 * p) * P + 8 * seg]) = vb;
-      if (EPI == BEPI_ATOMIC && want_bsum) {
+    for (int p = 0; p < 4; ++p) {
+      u32x4 va, vb;
+      if constexpr (decltype(set)::value == 0) {
+        va = ra0[p]; vb = rb0[p];
+      } else {
+        va = ra1[p]; vb = rb1[p];
+      }
+      *reinterpret_cast<u32x4*>(&As[(srow + 64 * p) * P + 8 * seg]) = va;
+      *reinterpret_cast<u32x4*>(&Bs[(srow + 64 * p) * P + 8 * seg]) = vb;
+      if (want_bsum && live) {
         bsum[p] += (__uint_as_float(vb.x << 16) + __uint_as_float(vb.x & 0xffff0000u)) +
                    (__uint_as_float(vb.y << 16) + __uint_as_float(vb.y & 0xffff0000u)) +
                    (__uint_as_float(vb.z << 16) + __uint_as_float(vb.z & 0xffff0000u)) +
@@ -367,67 +366,69 @@ __global__ void __launch_bounds__(256, 1) gemm_bf16_big_kernel(GemmBf16Args g) {
       }
     }
   };
-  // The operand fragments of k step ks + 1 are read while the 16 MFMAs of step ks run (two fragment sets; the
-  // scheduling barriers keep the compiler from folding them back into one set and waiting for every read).
   auto multiply = [&](int cur) {
     const bf16_t* As = smem + cur * STAGE + (wm * 128 + lo) * P + 8 * hi;
-    const bf16_t* Bs = smem + cur * STAGE + BM * P + (wn * 128 + lo) * P + 8 * hi;
-    bf16x8 a[2][4], b[2][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) a[0][i] = *reinterpret_cast<const bf16x8*>(As + i * 32 * P);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) b[0][j] = *reinterpret_cast<const bf16x8*>(Bs + j * 32 * P);
+    const bf16_t* Bs = smem + cur * STAGE + BM * P + (wn * 64 + lo) * P + 8 * hi;
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
-      if (ks + 1 < BK / 16) {
+      bf16x8 a[4], b[2];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) a[(ks + 1) & 1][i] = *reinterpret_cast<const bf16x8*>(As + i * 32 * P + 16 * (ks + 1));
+      for (int i = 0; i < 4; ++i) a[i] = *reinterpret_cast<const bf16x8*>(As + i * 32 * P + 16 * ks);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) b[(ks + 1) & 1][j] = *reinterpret_cast<const bf16x8*>(Bs + j * 32 * P + 16 * (ks + 1));
-      }
-      __builtin_amdgcn_sched_barrier(0);
+      for (int j = 0; j < 2; ++j) b[j] = *reinterpret_cast<const bf16x8*>(Bs + j * 32 * P + 16 * ks);
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks & 1][i], b[ks & 1][j], acc[i][j], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
+        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     }
   };
+  using Set0 = std::integral_constant<int, 0>;
+  using Set1 = std::integral_constant<int, 1>;
+  // chunk j travels in set j & 1, is written to LDS stage j & 1 one iteration before it is multiplied and was
+  // requested three iterations before
+  // requested three iterations before.  The loop body has no branch (a uniform branch around a stage or a request
+  // makes every wait in the loop a wait for all outstanding loads): chunks are taken in pairs, a chunk past the end
+  // is the last one read once more, and an odd last chunk is multiplied after the loop.
   if (nchunks > 0) {
-    fetch(0);
-    stage(0);
-    fetch(1);
+    fetch(0, Set0{});
+    fetch(1, Set1{});
+    stage(0, Set0{}, true);
+    fetch(2, Set0{});
   }
-  int cur = 0;
-  for (int i = 0; i < nchunks; ++i, cur ^= 1) {
-    __syncthreads();  // stage `cur` is complete; everybody is done reading the other one
-    if (i + 1 < nchunks) stage(cur ^ 1);
-    fetch(i + 2);
-    multiply(cur);
+  for (int i = 0; i + 1 < nchunks; i += 2) {
+    __syncthreads();  // stage 0 is complete; everybody is done reading stage 1
+    stage(1, Set1{}, true);
+    fetch(i + 3, Set1{});
+    multiply(0);
+    __syncthreads();
+    stage(0, Set0{}, i + 2 < nchunks);
+    fetch(i + 4, Set0{});
+    multiply(1);
   }
-  {
-    if (want_bsum) {
+  if (nchunks & 1) {
+    __syncthreads();
+    multiply(0);
+  }
+  if (want_bsum) {
 #pragma unroll
-      for (int p = 0; p < 8; ++p) {
-        float v = bsum[p];
-        v += __shfl_xor(v, 1);
-        v += __shfl_xor(v, 2);
-        v += __shfl_xor(v, 4);
-        const int64_t n = n0 + srow + 32 * p;
-        if (seg == 0 && n < g.N) atomicAdd(&g.rowsum_b[n], v);
-      }
+    for (int p = 0; p < 4; ++p) {
+      float v = bsum[p];
+      v += __shfl_xor(v, 1);
+      v += __shfl_xor(v, 2);
+      v += __shfl_xor(v, 4);
+      const int64_t n = n0 + srow + 64 * p;
+      if (seg == 0 && n < g.N) atomicAdd(&g.rowsum_b[n], v);
     }
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int64_t m = m0 + wm * 128 + i * 32 + 8 * (r / 4) + 4 * hi + (r % 4), n = n0 + wn * 128 + j * 32 + lo;
-          if (m < g.M && n < g.N) atomicAdd(&g.Cf[m * g.ldcf + n], acc[i][j][r]);
-        }
   }
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int64_t m = m0 + wm * 128 + i * 32 + 8 * (r / 4) + 4 * hi + (r % 4), n = n0 + wn * 64 + j * 32 + lo;
+        if (m < g.M && n < g.N) atomicAdd(&g.Cf[m * g.ldcf + n], acc[i][j][r]);
+      }
 }
 
 // The products with an element-wise epilogue (forward layers, dz1) when the weight matrix is small enough to LIVE IN
@@ -665,7 +666,15 @@ inline void launch_gemm_bf16(const GemmBf16Args& g0, hipStream_t s) {
     // evaluations per lane with one wavefront per SIMD are not hidden behind anything.)
     g.tiles_m = (unsigned)((mcover + 255) / 256);
     g.tiles_n = (unsigned)((g.N + 255) / 256);
-    hipLaunchKernelGGL(gemm_bf16_big_kernel<EPI>, dim3(g.tiles_m * g.tiles_n * gz), dim3(256), 0, s, g);
+    {
+      auto kern = gemm_bf16_big_kernel<EPI>;
+      static bool configured = false;
+      if (!configured) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return;
+        configured = true;
+      }
+      hipLaunchKernelGGL(kern, dim3(g.tiles_m * g.tiles_n * gz), dim3(512), 2 * 2 * 256 * 72 * sizeof(bf16_t), s, g);
+    }
     return;
   }
   g.tiles_m = (unsigned)((mcover + 127) / 128);
