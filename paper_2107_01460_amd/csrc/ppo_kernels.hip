@@ -28,8 +28,8 @@ namespace {
 // and dz2 = (dL/dout W3^T) * (1 - h2^2), which overwrites h2 in place (row-major, the A operand of dz1) and goes to
 // the sample-blocked transposed copy dz2T (zeros for the samples S .. 64 * tiles; the B operand of the W2 gradient).
 // Persistent over tiles so that the gradients and statistics leave a workgroup once.
-template <int NOUT, class LossFn, int HMAX>
-__global__ void __launch_bounds__(256) loss_head_bf16_kernel(bf16_t* __restrict__ H2, int64_t S, int H,
+template <int NOUT, class LossFn, int HMAX, int NT>
+__global__ void __launch_bounds__(NT) loss_head_bf16_kernel(bf16_t* __restrict__ H2, int64_t S, int H,
                                                              const float* __restrict__ W3, const float* __restrict__ b3,
                                                              LossFn fn, bf16_t* __restrict__ dz2T, float* __restrict__ gW3,
                                                              float* __restrict__ gb3, Scalars* sc, float* __restrict__ partial) {
@@ -38,12 +38,13 @@ __global__ void __launch_bounds__(256) loss_head_bf16_kernel(bf16_t* __restrict_
   constexpr int PITCH = HMAX + 8;  // elements; an odd number of 16-byte units, so row-per-lane 16-byte reads spread over the banks
   __shared__ __attribute__((aligned(16))) bf16_t T[kHeadTile * PITCH];
   __shared__ __attribute__((aligned(16))) float W3s[HMAX * NOUT];
-  __shared__ float red[4 * NOUT * kHeadTile];
+  constexpr int NG = NT / 64;  // wavefronts: eight (two per SIMD cover each other's LDS latencies) where there is enough work per tile, else four
+  __shared__ float red[NG * NOUT * kHeadTile];
   __shared__ __attribute__((aligned(16))) float dls[kHeadTile * 8];
   const int tid = threadIdx.x, lane = tid & 63, grp = tid >> 6;
-  for (int e = tid; e < H * NOUT; e += 256) W3s[e] = W3[e];
+  for (int e = tid; e < H * NOUT; e += NT) W3s[e] = W3[e];
   const auto prep = fn.prepare();
-  // dz2: thread -> the eight hidden units 8 (tid % CPR) .. + 7 of the rows tid / CPR + (256 / CPR) q; their W3 rows
+  // dz2: thread -> the eight hidden units 8 (tid % CPR) .. + 7 of the rows tid / CPR + (NT / CPR) q; their W3 rows
   float w8[8][NOUT];
 #pragma unroll
   for (int e = 0; e < 8; ++e)
@@ -52,8 +53,9 @@ __global__ void __launch_bounds__(256) loss_head_bf16_kernel(bf16_t* __restrict_
       const int i = 8 * (tid % (HMAX / 8)) + e;
       w8[e][k] = i < H ? W3[(int64_t)i * NOUT + k] : 0.f;
     }
-  constexpr int UMAX = HMAX / 256;  // hidden units per thread in the W3 gradient
-  static_assert(UMAX == 2, "a thread owns one pair of neighbouring hidden units");
+  constexpr int UMAX = 2;  // W3 gradient: thread -> the pair of hidden units 2 (tid % 256), + 1 and one share of the tile's samples
+  constexpr int SHARES = NT / 256;
+  static_assert(HMAX == 512 && (NT == 256 || NT == 512), "256 pairs of hidden units x 1 or 2 shares of the samples");
   float gw[UMAX][NOUT], gb[NOUT], st[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int k = 0; k < NOUT; ++k) {
@@ -61,19 +63,19 @@ __global__ void __launch_bounds__(256) loss_head_bf16_kernel(bf16_t* __restrict_
 #pragma unroll
     for (int u = 0; u < UMAX; ++u) gw[u][k] = 0.f;
   }
-  const int vec_per_row = H / 8, per_grp = H / 4;
+  const int vec_per_row = H / 8, per_grp = H / NG;
   const int64_t ntiles = (S + kHeadTile - 1) / kHeadTile;
   // A tile travels global -> registers -> LDS: all of a thread's 16-byte pieces are requested at once, and the next
   // tile's are requested before this tile's arithmetic, so that no load is waited for on its own.
-  constexpr int NV = kHeadTile * (HMAX / 8) / 256;  // pieces per thread at the full width
+  constexpr int NV = kHeadTile * (HMAX / 8) / NT;  // pieces per thread at the full width
   constexpr int CPR = HMAX / 8;                     // 16-byte pieces of a row at the full width
-  static_assert(256 % CPR == 0 && NV * (256 / CPR) == kHeadTile, "a thread's pieces are one column of the tile");
+  static_assert(NT % CPR == 0 && NV * (NT / CPR) == kHeadTile, "a thread's pieces are one column of the tile");
   uint4 tv[NV];
   auto fetch_tile = [&](int64_t tile) {
     const int64_t s0 = tile * kHeadTile;
 #pragma unroll
-    for (int q = 0; q < NV; ++q) {  // thread -> rows tid / CPR + (256 / CPR) q, 16-byte piece tid % CPR of the row
-      const int r = tid / CPR + (256 / CPR) * q, c8 = tid % CPR;
+    for (int q = 0; q < NV; ++q) {  // thread -> rows tid / CPR + (NT / CPR) q, 16-byte piece tid % CPR of the row
+      const int r = tid / CPR + (NT / CPR) * q, c8 = tid % CPR;
       tv[q] = make_uint4(0u, 0u, 0u, 0u);
       if (c8 < vec_per_row && s0 + r < S) tv[q] = *reinterpret_cast<const uint4*>(&H2[(s0 + r) * H + 8 * c8]);
     }
@@ -97,12 +99,12 @@ __global__ void __launch_bounds__(256) loss_head_bf16_kernel(bf16_t* __restrict_
     __syncthreads();  // the previous tile has been consumed (and W3s is in place)
 #pragma unroll
     for (int q = 0; q < NV; ++q) {
-      const int r = tid / CPR + (256 / CPR) * q, c8 = tid % CPR;
+      const int r = tid / CPR + (NT / CPR) * q, c8 = tid % CPR;
       if (c8 < vec_per_row) *reinterpret_cast<uint4*>(&T[r * PITCH + 8 * c8]) = tv[q];
     }
     __syncthreads();
     if (tile + gridDim.x < ntiles) fetch_tile(tile + gridDim.x);
-    {  // output layer: thread -> sample `lane`, quarter `grp` of the hidden units
+    {  // output layer: thread -> sample `lane`, share `grp` (one of NG) of the hidden units
       float part[NOUT];
 #pragma unroll
       for (int k = 0; k < NOUT; ++k) part[k] = 0.f;
@@ -136,8 +138,10 @@ __global__ void __launch_bounds__(256) loss_head_bf16_kernel(bf16_t* __restrict_
       float out[NOUT], dl[NOUT];
 #pragma unroll
       for (int k = 0; k < NOUT; ++k) {
-        out[k] = b3[k] + ((red[(0 * NOUT + k) * kHeadTile + tid] + red[(1 * NOUT + k) * kHeadTile + tid]) +
-                          (red[(2 * NOUT + k) * kHeadTile + tid] + red[(3 * NOUT + k) * kHeadTile + tid]));
+        float v = 0.f;
+#pragma unroll
+        for (int gq = 0; gq < NG; ++gq) v += red[(gq * NOUT + k) * kHeadTile + tid];
+        out[k] = b3[k] + v;
         dl[k] = 0.f;
       }
       const int64_t s = s0 + tid;
@@ -150,16 +154,18 @@ __global__ void __launch_bounds__(256) loss_head_bf16_kernel(bf16_t* __restrict_
       for (int k = 0; k < 8; ++k) dls[tid * 8 + k] = k < NOUT ? dl[k < NOUT ? k : 0] : 0.f;
     }
     __syncthreads();
-    // gW3[i][k] += sum_s h2[s][i] dl[s][k]: thread -> hidden units 2 tid, 2 tid + 1 (one 4-byte LDS read per sample)
+    // gW3[i][k] += sum_s h2[s][i] dl[s][k]: thread -> hidden units 2 (tid % 256), + 1 (one 4-byte LDS read per sample),
+    // samples (64 / SHARES) (tid / 256) .. 
+    const int pr = tid & 255, s_lo = (tid >> 8) * (kHeadTile / SHARES);
 #pragma unroll 8
-    for (int s = 0; s < kHeadTile; ++s) {
+    for (int s = s_lo; s < s_lo + kHeadTile / SHARES; ++s) {
       const float4 d0 = *reinterpret_cast<const float4*>(&dls[s * 8]);
       float dv[8] = {d0.x, d0.y, d0.z, d0.w, 0.f, 0.f, 0.f, 0.f};
       if (NOUT > 4) {
         const float4 d1 = *reinterpret_cast<const float4*>(&dls[s * 8 + 4]);
         dv[4] = d1.x; dv[5] = d1.y; dv[6] = d1.z; dv[7] = d1.w;
       }
-      const uint32_t hw = 2 * tid < H ? *reinterpret_cast<const uint32_t*>(&T[s * PITCH + 2 * tid]) : 0u;
+      const uint32_t hw = 2 * pr < H ? *reinterpret_cast<const uint32_t*>(&T[s * PITCH + 2 * pr]) : 0u;
       const float hp[2] = {__uint_as_float(hw << 16), __uint_as_float(hw & 0xffff0000u)};
 #pragma unroll
       for (int u = 0; u < UMAX; ++u)
@@ -169,7 +175,7 @@ __global__ void __launch_bounds__(256) loss_head_bf16_kernel(bf16_t* __restrict_
     __syncthreads();  // every thread has read the h2 it needs; the tile is overwritten with dz2
 #pragma unroll 4
     for (int q = 0; q < NV; ++q) {
-      const int r = tid / CPR + (256 / CPR) * q, c8 = tid % CPR;
+      const int r = tid / CPR + (NT / CPR) * q, c8 = tid % CPR;
       if (c8 < vec_per_row) {
         const uint4 hv = *reinterpret_cast<const uint4*>(&T[r * PITCH + 8 * c8]);
         const float4 d0 = *reinterpret_cast<const float4*>(&dls[r * 8]);
@@ -199,9 +205,9 @@ __global__ void __launch_bounds__(256) loss_head_bf16_kernel(bf16_t* __restrict_
       }
     }
     __syncthreads();
-    // transposed copy: thread -> hidden unit tid / 8 + 32 q, samples 8 (tid % 8) .. + 7 (a wavefront writes 1 KB in one piece)
-    for (int q = 0; 32 * q < H; ++q) {
-      const int dd = (tid >> 3) + 32 * q, ss = 8 * (tid & 7);
+    // transposed copy: thread -> hidden unit tid / 8 + (NT / 8) q, samples 8 (tid % 8) .. + 7 (a wavefront writes 1 KB in one piece)
+    for (int q = 0; (NT / 8) * q < H; ++q) {
+      const int dd = (tid >> 3) + (NT / 8) * q, ss = 8 * (tid & 7);
       uint32_t ow[4];
 #pragma unroll
       for (int p2 = 0; p2 < 4; ++p2)
@@ -209,10 +215,25 @@ __global__ void __launch_bounds__(256) loss_head_bf16_kernel(bf16_t* __restrict_
       *reinterpret_cast<uint4*>(&dz2T[((s0 >> 6) * H + dd) * 64 + ss]) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
     }
   }
+  // two shares of the samples meet in LDS (the tile buffer is free after the last barrier of the loop)
+  float* const comb = reinterpret_cast<float*>(T);
+  if (SHARES == 2) {
+    __syncthreads();
+    if (tid >= 256) {
+#pragma unroll
+      for (int u = 0; u < UMAX; ++u)
+#pragma unroll
+        for (int k = 0; k < NOUT; ++k) comb[(u * NOUT + k) * 256 + (tid & 255)] = gw[u][k];
+    }
+    __syncthreads();
+  }
 #pragma unroll
   for (int u = 0; u < UMAX; ++u) {
     const int i = 2 * tid + u;
-    if (i < H) {
+    if (tid < 256 && i < H) {
+#pragma unroll
+      for (int k = 0; k < NOUT; ++k)
+        if (SHARES == 2) gw[u][k] += comb[(u * NOUT + k) * 256 + tid];
 #pragma unroll
       for (int k = 0; k < NOUT; ++k) {
         if (partial != nullptr) partial[(int64_t)blockIdx.x * (H * NOUT + NOUT) + (int64_t)i * NOUT + k] = gw[u][k];
@@ -438,7 +459,8 @@ void train_net_bf16(const RowSrc& X, int64_t S, int Din, int H, const Bf16NetWei
   const unsigned nb = (unsigned)std::min<int64_t>(512, (S + kHeadTile - 1) / kHeadTile);
   float* const hp = (go.b3 == go.W3 + (int64_t)H * NOUT) ? w.partial_head : nullptr;  // b3's gradient directly follows W3's
   // output layer, loss and dz2 in one pass over h2 (the tiles cover the samples up to Sp: dz2T is zero-padded)
-  hipLaunchKernelGGL((loss_head_bf16_kernel<NOUT, LossFn, 512>), dim3(nb), dim3(256), 0, s, w.bh2, S, H, eff + o.W3,
+  constexpr int HEAD_NT = NOUT > 1 ? 512 : 256;  // the one-output head has too little work per tile for eight wavefronts
+  hipLaunchKernelGGL((loss_head_bf16_kernel<NOUT, LossFn, 512, HEAD_NT>), dim3(nb), dim3(HEAD_NT), 0, s, w.bh2, S, H, eff + o.W3,
                      eff + o.b3, fn, w.dz2T, grad + go.W3, grad + go.b3, w.sc, hp);
   if (hp != nullptr) launch_reduce_partials(hp, (int)nb, (int64_t)H * NOUT + NOUT, grad + go.W3, s);
   auto k_split = [&](int64_t tiles_mn) {  // ~4 workgroups per CU, k ranges in multiples of the k tile
