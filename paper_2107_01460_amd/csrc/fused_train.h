@@ -89,7 +89,8 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
   constexpr int NTN = H / 32, MTF = BM / 32, PH = H + 4, GROUPS = NT / BM;
   static_assert(NTN * MTF == NW, "one forward tile per wavefront");
   constexpr int TPR = NT / BM;           // threads staging one row of X
-  constexpr int XP = DMAX / TPR;         // X elements per thread
+  constexpr int XV = DMAX / TPR / 4;     // 16-byte chunks of an X row per thread
+  static_assert(DMAX % (4 * TPR) == 0, "whole chunks per thread");
   constexpr int DW2_TPW = NTN * NTN >= NW ? NTN * NTN / NW : 1;  // dW2 tiles per wavefront (one row of tiles at most)
   constexpr int DW2_KS = NTN * NTN >= NW ? 1 : NW / (NTN * NTN);  // split of the sample range when there are fewer tiles than wavefronts
   static_assert(DW2_TPW <= NTN && NTN % DW2_TPW == 0, "a wavefront's dW2 tiles share their row of tiles");
@@ -103,6 +104,7 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
   float* red = H2 + BM * PH;               // [GROUPS][NOUT][BM]
   float* dls = red + NT * NOUT;           // [BM][8]
   float* W3s = dls + BM * 8;               // [H][NOUT]
+  float* const xdump = W3s + H * NOUT;     // one float: where the staged values that are not part of a row go
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lo = lane & 31, hi = lane >> 5;
@@ -162,7 +164,13 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
 
   // ---- staging helpers.  The inputs of the next tile come in two steps: the gather entries at the top of a
   // tile, the rows themselves half a tile later, so that neither dependent load is ever waited for.
-  float xr[XP];
+  // A row of X starts at any 4-byte boundary (its width need not be a multiple of four), so it is fetched as the
+  // aligned 16-byte chunks that cover it -- a few wide loads per thread instead of one 4-byte load per element,
+  // which the address path serves no faster -- and sorted out on the way into LDS: element j of chunk q is column
+  // 4 q + j - xoff of the row, xoff being where the row starts inside its first chunk.  (The base of X is 16-byte
+  // aligned and rows before / after a row exist, so the chunks never leave the buffer.)
+  float4 xr[XV];
+  int xoff = 0;
   typename LossFn::In lin_next{};
   int32_t xentry = 0, lentry = 0;
   const int xrow_l = tid / TPR, xcol0 = tid % TPR;
@@ -172,19 +180,25 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
     if (tid < BM && s0 + tid < a.S) lentry = fn.row_entry(s0 + tid);
   };
   auto fetch_tile_inputs = [&](int64_t s0) {
-    const float* row = a.X.ptr_with(min(s0 + xrow_l, a.S - 1), xentry);
+    const uintptr_t addr = reinterpret_cast<uintptr_t>(a.X.ptr_with(min(s0 + xrow_l, a.S - 1), xentry));
+    const float4* const chunk = reinterpret_cast<const float4*>(addr & ~(uintptr_t)15);
+    xoff = (int)((addr >> 2) & 3);
+    const int last = ((xoff + a.Din + 3) >> 2) - 1;  // chunks past the row: the last one again (none of its elements is stored)
 #pragma unroll
-    for (int p = 0; p < XP; ++p) {
-      const int c = xcol0 + TPR * p;
-      xr[p] = c < a.Din ? row[c] : 0.f;
-    }
+    for (int p = 0; p < XV; ++p) xr[p] = chunk[min(xcol0 + TPR * p, last)];
     if (tid < BM && s0 + tid < a.S) lin_next = fn.load_with(s0 + tid, lentry);
   };
   auto store_tile_inputs = [&]() {
+    float* const xdst = Xs + xrow_l * px - xoff;
 #pragma unroll
-    for (int p = 0; p < XP; ++p) {
-      const int c = xcol0 + TPR * p;
-      if (c < a.Din) Xs[xrow_l * px + c] = xr[p];
+    for (int p = 0; p < XV; ++p) {
+      const float v[4] = {xr[p].x, xr[p].y, xr[p].z, xr[p].w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int c = 4 * (xcol0 + TPR * p) + j - xoff;
+        float* const dst = (c >= 0 && c < a.Din) ? xdst + 4 * (xcol0 + TPR * p) + j : xdump;
+        *dst = v[j];
+      }
     }
   };
   const int64_t ntiles = (a.S + BM - 1) / BM;
@@ -431,7 +445,8 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
   }
 }
 
-inline bool fused_train_supported(int H, int Din) { return (H == 64 || H == 128) && Din <= 96; }
+// (an input row is staged as the aligned 16-byte chunks that cover it: up to three values more than its width)
+inline bool fused_train_supported(int H, int Din) { return (H == 64 || H == 128) && Din <= 93; }
 
 inline int fused_train_px(int Din) {
   int px = 32 * ((Din + 31) / 32);
@@ -442,7 +457,7 @@ inline int fused_train_px(int Din) {
 template <int H, int BM, int NOUT, int DMAX, int NW, class LossFn>
 inline int32_t launch_fused_train_inst(const FusedTrainArgs& a, const LossFn& fn, hipStream_t s) {
   auto kern = fused_train_kernel<H, BM, NOUT, DMAX, NW, LossFn>;
-  const size_t floats = (size_t)BM * a.px + 2 * (size_t)BM * (H + 4) + 64 * NW * NOUT + BM * 8 + H * NOUT;
+  const size_t floats = (size_t)BM * a.px + 2 * (size_t)BM * (H + 4) + 64 * NW * NOUT + BM * 8 + H * NOUT + 4;
   const size_t bytes = floats * 4;
   static bool configured = false;  // per instantiation
   if (!configured) {
@@ -465,10 +480,10 @@ inline int32_t launch_fused_train(int H, const FusedTrainArgs& a, const LossFn& 
   // algorithmic flops: forward 2S(DH + HH), backward 2S(HH + HH + DH)
   TimedLaunch timed(KC_FUSED_TRAIN, 2.0 * (double)a.S * (2.0 * a.Din * H + 3.0 * H * H), s);
   if (H == 128) {
-    if (a.Din <= 32) return launch_fused_train_inst<128, 64, NOUT, 32, 8, LossFn>(a, fn, s);
+    if (a.Din <= 29) return launch_fused_train_inst<128, 64, NOUT, 32, 8, LossFn>(a, fn, s);
     return launch_fused_train_inst<128, 64, NOUT, 96, 8, LossFn>(a, fn, s);
   }
-  if (a.Din <= 32) return launch_fused_train_inst<64, 128, NOUT, 32, 8, LossFn>(a, fn, s);
+  if (a.Din <= 29) return launch_fused_train_inst<64, 128, NOUT, 32, 8, LossFn>(a, fn, s);
   return launch_fused_train_inst<64, 128, NOUT, 96, 8, LossFn>(a, fn, s);
 }
 
