@@ -218,6 +218,12 @@ def test_bf16_other_widths(M, orc, ha, hc, view):
     check_single_minibatch_gradient(M, orc, small(4, n_epochs=1, n_minibatches=1, max_grad_norm=0.0, **kw), 4)
 
 
+def test_bf16_odd_chunk_count(M, orc):
+    """816 samples (17 environments): the weight-gradient kernel's k ranges hold 8 and 5 chunks of 64 samples, so
+    the chunk-pair loop ends on a single chunk, and the last 64-row tile of the other kernels is ragged."""
+    check_single_minibatch_gradient(M, orc, small(4, n_envs=17, n_epochs=1, n_minibatches=1, max_grad_norm=0.0), 4)
+
+
 def test_wide_central_critic(M, orc):
     """A centralised critic whose input (8 agents x 147 = 1176 values) is wider than the fused forward kernel
     keeps in LDS: its forward pass, loss and gradient take the layer-by-layer kernels."""
