@@ -405,7 +405,10 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int i = it * 32 + 8 * (r / 4) + 4 * hi + (r % 4), j = (jt + q) * 32 + lo;
-        atomicAdd(&gW2[i * H + j], acc2[q][r]);
+        // a tile with one owner goes into the workgroup's own (zeroed) copy with a plain store: a quarter of a
+        // million atomics per workgroup is what the flush otherwise costs, 25 us per launch
+        if (DW2_KS == 1 && a.partial != nullptr) gW2[i * H + j] = acc2[q][r];
+        else atomicAdd(&gW2[i * H + j], acc2[q][r]);
       }
   }
 #pragma unroll
@@ -416,7 +419,10 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int d = dt * 32 + 8 * (r / 4) + 4 * hi + (r % 4), j = jt * 32 + lo;
-        if (d < a.Din) atomicAdd(&gW1[d * H + j], acc1[q][r]);
+        if (d < a.Din) {
+          if (balanced1 && q == 0 && a.partial != nullptr) gW1[d * H + j] = acc1[q][r];  // a whole tile of this wavefront's own
+          else atomicAdd(&gW1[d * H + j], acc1[q][r]);
+        }
       }
     }
   }
