@@ -22,6 +22,7 @@ struct LossCommon {
   int64_t rows_mb;
   float inv_B;  // 1 / (rows_mb * A)
   const Scalars* sc;
+  const double* adv_stats;  // sum and sum of squares of this minibatch's advantages
   int normalize;
   float clip_eps, ent_coef, vf_coef;
   int clip_value;
@@ -32,14 +33,17 @@ __global__ void iota_kernel(int32_t* p, int64_t n) {
   if (i < n) p[i] = (int32_t)i;
 }
 
-__global__ void zero_step_kernel(float* grad, int64_t P, Scalars* sc) {
+// Zeroes the gradient, `nsc` sets of scalars and `nextra` doubles (nullable).
+__global__ void zero_step_kernel(float* grad, int64_t P, Scalars* sc, int nsc, double* extra, int nextra) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < P) grad[i] = 0.f;
-  if (i == 0) {
-    sc->adv_sum = 0.0;
-    sc->adv_sq = 0.0;
-    for (int k = 0; k < 8; ++k) sc->acc[k] = 0.f;
+  if (i < nsc) {
+    sc[i].adv_sum = 0.0;
+    sc[i].adv_sq = 0.0;
+    for (int k = 0; k < 8; ++k) sc[i].acc[k] = 0.f;
   }
+  if (extra != nullptr)
+    for (int64_t j = i; j < nextra; j += (int64_t)gridDim.x * blockDim.x) extra[j] = 0.0;
 }
 
 __device__ __forceinline__ double block_sum_f64(double v, double* red) {
@@ -74,6 +78,32 @@ __global__ void __launch_bounds__(256) adv_stats_kernel(const float* __restrict_
   }
 }
 
+// The same for every minibatch of an update in one launch: blockIdx.y = e * n_minibatches + mb; the row order of
+// epoch e starts at rows + e * epoch_stride, minibatch mb takes its rows mb * rows_mb .. ; out[2 (e * n_minibatches + mb)]
+// gets the sum, the next double the sum of squares (zeroed before the launch).
+__global__ void __launch_bounds__(256) adv_stats_all_kernel(const float* __restrict__ adv, const int32_t* __restrict__ rows,
+                                                            int64_t epoch_stride, int n_minibatches, int64_t rows_mb, int A,
+                                                            double* __restrict__ out) {
+  __shared__ double red[2][4];
+  const int m = blockIdx.y, e = m / n_minibatches, mb = m - e * n_minibatches;
+  const int32_t* const r0 = rows + e * epoch_stride + (int64_t)mb * rows_mb;
+  const int64_t B = rows_mb * A;
+  double sum = 0, sq = 0;
+  for (int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; s < B; s += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t row = s / A;
+    const int a = (int)(s - row * A);
+    const double x = adv[(int64_t)r0[row] * A + a];
+    sum += x;
+    sq += x * x;
+  }
+  const double t0 = block_sum_f64(sum, red[0]);
+  const double t1 = block_sum_f64(sq, red[1]);
+  if (threadIdx.x == 0) {
+    atomicAdd(&out[2 * m], t0);
+    atomicAdd(&out[2 * m + 1], t1);
+  }
+}
+
 // exp and log on the hardware exp2 / log2 units (1 ulp each; the arguments here are O(1))
 __device__ __forceinline__ float fast_exp(float x) { return __builtin_amdgcn_exp2f(x * 1.4426950408889634f); }
 __device__ __forceinline__ float fast_log(float x) { return __builtin_amdgcn_logf(x) * 0.6931471805599453f; }
@@ -105,9 +135,9 @@ struct ActorLoss {
     LossPrep p{0.f, 1.f};
     if (lc.normalize) {
       const double B = (double)lc.rows_mb * lc.A;
-      const double mean = lc.sc->adv_sum / B;
+      const double mean = lc.adv_stats[0] / B;
       p.mean = (float)mean;
-      p.rstd = (float)(1.0 / (sqrt(fmax(lc.sc->adv_sq / B - mean * mean, 0.0)) + 1e-8));
+      p.rstd = (float)(1.0 / (sqrt(fmax(lc.adv_stats[1] / B - mean * mean, 0.0)) + 1e-8));
     }
     return p;
   }
@@ -323,10 +353,12 @@ struct AdamArgs {
   int k_local;            // corrections are computed on the device for step *k_base + k_local instead of bc1 / bc2
 };
 
+// sc_next (nullable): the gradient and that set of scalars are zeroed for the next optimiser step, which accumulates
+// into them (two sets of scalars alternate, so nobody reads the one being zeroed).
 __global__ void __launch_bounds__(256) adam_kernel(float* __restrict__ params, float* __restrict__ m,
-                                                   float* __restrict__ v, const float* __restrict__ grad, int64_t P,
+                                                   float* __restrict__ v, float* __restrict__ grad, int64_t P,
                                                    AdamArgs a, const Scalars* sc, float* __restrict__ stats_row,
-                                                   float* __restrict__ grad_dump) {
+                                                   float* __restrict__ grad_dump, Scalars* sc_next) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const float norm = sqrtf(sc->acc[5]);
   const float scale = a.max_norm > 0.f ? a.max_norm / fmaxf(norm, a.max_norm) : 1.0f;
@@ -343,6 +375,12 @@ __global__ void __launch_bounds__(256) adam_kernel(float* __restrict__ params, f
     v[i] = vi;
     params[i] -= a.lr * (mi / a.bc1) / (sqrtf(vi / a.bc2) + a.eps);
     if (grad_dump) grad_dump[i] = g;
+    if (sc_next != nullptr) grad[i] = 0.f;
+  }
+  if (i == 0 && sc_next != nullptr) {
+    sc_next->adv_sum = 0.0;
+    sc_next->adv_sq = 0.0;
+    for (int k = 0; k < 8; ++k) sc_next->acc[k] = 0.f;
   }
   if (i == 0) {
     const float total = sc->acc[0] - a.ent_coef * sc->acc[2] + a.vf_coef * sc->acc[1];

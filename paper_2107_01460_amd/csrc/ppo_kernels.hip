@@ -300,7 +300,8 @@ __global__ void __launch_bounds__(256) dz2_kernel(float* __restrict__ H2, const 
 
 struct UpdateWsView {
   float *eff_params, *grad;
-  Scalars* sc;
+  Scalars* sc;        // two sets: optimiser step k accumulates into set k % 2 while its Adam kernel zeroes the other
+  double* adv_stats;  // [n_epochs * n_minibatches][2]: sum and sum of squares of every minibatch's advantages
   int32_t* ident;
   float *h1a, *h2a, *dz1a, *dla;
   float *h1c, *h2c, *dz1c, *dlc;
@@ -327,7 +328,8 @@ UpdateWsView carve_update_ws(const marl_config& c, void* ws, int64_t* total) {
   UpdateWsView v{};
   v.eff_params = (float*)take(effective_param_floats(c) * 4);
   v.grad = (float*)take(d.P * 4);
-  v.sc = (Scalars*)take(sizeof(Scalars));
+  v.sc = (Scalars*)take(2 * sizeof(Scalars));
+  v.adv_stats = (double*)take((int64_t)c.n_epochs * c.n_minibatches * 2 * sizeof(double));
   v.ident = (int32_t*)take(R * 4);
   if (!d.bf16) {
     // activations: rows rounded up to the 64-row tiles of the register-resident kernels, which store whole tiles
@@ -525,33 +527,43 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
   const ParamMap pm = param_map(d);
   const NetOffsets oa = padded_offsets(pm, 0), oc = padded_offsets(pm, 1);
   int64_t k = adam_step0;
+  // Once per update: the gradient, both sets of scalars and the advantage statistics start at zero (afterwards every
+  // Adam kernel zeroes the gradient and the scalars of the next step), and the advantage statistics of ALL minibatches
+  // of all epochs are summed in one launch -- the row orders are known up front.
+  const int n_steps = c.n_epochs * c.n_minibatches;
+  hipLaunchKernelGGL(zero_step_kernel, dim3((unsigned)((d.P + 255) / 256)), dim3(256), 0, s, w.grad, d.P, w.sc, 2,
+                     w.adv_stats, 2 * n_steps);
+  if (c.normalize_adv) {
+    const unsigned nb = (unsigned)std::min<int64_t>(std::max(1, 256 / c.n_minibatches), (Sa + 255) / 256);  // every workgroup ends with two atomics on its minibatch's two doubles
+    hipLaunchKernelGGL(adv_stats_all_kernel, dim3(nb, (unsigned)n_steps), dim3(256), 0, s, tr.adv, perm ? perm : w.ident,
+                       perm ? R : (int64_t)0, c.n_minibatches, rows_mb, d.A, w.adv_stats);
+  }
   for (int e = 0; e < c.n_epochs; ++e) {
     for (int mb = 0; mb < c.n_minibatches; ++mb) {
+      const int step = e * c.n_minibatches + mb;
+      Scalars* const sck = w.sc + (step & 1);
+      UpdateWsView wk = w;  // the view the helpers get: this step's scalars
+      wk.sc = sck;
       const int32_t* rows = (perm ? perm + (int64_t)e * R : w.ident) + (int64_t)mb * rows_mb;
       const float* eff = effective_params(c, params, w.eff_params, s);
-      hipLaunchKernelGGL(zero_step_kernel, dim3((unsigned)((d.P + 255) / 256)), dim3(256), 0, s, w.grad, d.P, w.sc);
       LossCommon lc{};
       lc.rows = rows; lc.A = d.A; lc.rows_mb = rows_mb; lc.inv_B = (float)(1.0 / (double)(rows_mb * d.A));
-      lc.sc = w.sc; lc.normalize = c.normalize_adv; lc.clip_eps = c.clip_eps; lc.ent_coef = c.ent_coef;
-      lc.vf_coef = c.vf_coef; lc.clip_value = c.clip_value;
-      if (c.normalize_adv) {
-        const unsigned nb = (unsigned)std::min<int64_t>(256, (Sa + 255) / 256);  // every workgroup ends with two atomics on the same two doubles
-        hipLaunchKernelGGL(adv_stats_kernel, dim3(nb), dim3(256), 0, s, tr.adv, lc, w.sc);
-      }
+      lc.sc = sck; lc.adv_stats = w.adv_stats + 2 * step; lc.normalize = c.normalize_adv; lc.clip_eps = c.clip_eps;
+      lc.ent_coef = c.ent_coef; lc.vf_coef = c.vf_coef; lc.clip_value = c.clip_value;
       // ---- actor
       const RowSrc Xa{tr.obs, d.D, rows, d.A, Sa};
       const bool fused_a = fused_forward_supported(d.Ha, d.D);
       {
         ActorLoss fn{lc, tr.action, tr.logp, tr.adv};
         if (d.bf16) {
-          train_net_bf16<kActions>(Xa, Sa, d.D, d.Ha, effective_bf16_weights(c, eff, 0), eff, oa, w.grad, ga, fn, w.dla, w, false, s);
+          train_net_bf16<kActions>(Xa, Sa, d.D, d.Ha, effective_bf16_weights(c, eff, 0), eff, oa, w.grad, ga, fn, w.dla, wk, false, s);
         } else if (fused_train_supported(d.Ha, d.D)) {
           FusedTrainArgs ta{};
           ta.X = Xa; ta.S = Sa; ta.Din = d.D; ta.px = fused_train_px(d.D);
           ta.W1 = eff + oa.W1; ta.b1 = eff + oa.b1; ta.W2 = eff + oa.W2; ta.b2 = eff + oa.b2; ta.W3 = eff + oa.W3;
           ta.W1s = eff + pm.sw_w1[0]; ta.W2s = eff + pm.sw_w2[0]; ta.W2Ts = eff + pm.sw_w2t[0];
           ta.b3 = eff + oa.b3; ta.gW1 = w.grad + ga.W1; ta.gb1 = w.grad + ga.b1; ta.gW2 = w.grad + ga.W2;
-          ta.gb2 = w.grad + ga.b2; ta.gW3 = w.grad + ga.W3; ta.gb3 = w.grad + ga.b3; ta.stats = w.sc->acc;
+          ta.gb2 = w.grad + ga.b2; ta.gW3 = w.grad + ga.W3; ta.gb3 = w.grad + ga.b3; ta.stats = sck->acc;
           ta.partial = w.partial; ta.gcount = d.Pa;
           const int32_t rc = launch_fused_train<kActions>(d.Ha, ta, fn, s);
           if (rc != MARL_OK) return rc;
@@ -561,14 +573,14 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
             fa.X = Xa; fa.S = Sa; fa.Din = d.D; fa.xvec = aligned16(Xa.base) && Xa.ld % 4 == 0 && d.D % 4 == 0;
             fa.W1 = eff + oa.W1; fa.b1 = eff + oa.b1; fa.W2 = eff + oa.W2; fa.b2 = eff + oa.b2; fa.W3 = eff + oa.W3;
             fa.b3 = eff + oa.b3; fa.h1_out = w.h1a; fa.dz2_out = w.h2a; fa.gW3 = w.grad + ga.W3; fa.gb3 = w.grad + ga.b3;
-            fa.stats = w.sc->acc;
+            fa.stats = sck->acc;
             fa.W1s = eff + pm.sw_w1[0]; fa.W2s = eff + pm.sw_w2[0]; fa.kpad1 = pm.kpad1[0]; fa.px = fused_forward_px(d.D);
             launch_fused_forward<kActions, true>(d.Ha, fa, fn, s);
           } else {
             mlp_hidden_forward(Xa, Sa, d.D, d.Ha, eff + oa.W1, eff + oa.b1, eff + oa.W2, eff + oa.b2, w.h1a, w.h2a, d.bf16, s);
             const unsigned nb = (unsigned)std::min<int64_t>(2048, (Sa + kHeadTile - 1) / kHeadTile);
             hipLaunchKernelGGL((loss_head_kernel<kActions, ActorLoss, float>), dim3(nb), dim3(256), 0, s, w.h2a, Sa, d.Ha,
-                               eff + oa.W3, eff + oa.b3, fn, w.dla, w.grad + ga.W3, w.grad + ga.b3, w.sc, 0.f);
+                               eff + oa.W3, eff + oa.b3, fn, w.dla, w.grad + ga.W3, w.grad + ga.b3, sck, 0.f);
           }
           mlp_backward<kActions>(Xa, Sa, d.D, d.Ha, eff + oa.W2, eff + oa.W3, w.h1a, w.h2a, w.dz1a, w.dla, w.grad + ga.W1,
                                  w.grad + ga.b1, w.grad + ga.W2, w.grad + ga.b2, d.bf16, fused_a, nullptr, s);
@@ -581,14 +593,14 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
         CriticLoss fn{lc, tr.ret, tr.value, d.central ? d.A : 1};
         if (d.bf16) {
           // IPPO: the critic reads the rows the actor has just packed (same rows, same width)
-          train_net_bf16<1>(Xc, Sc, d.Dc, d.Hc, effective_bf16_weights(c, eff, 1), eff, oc, w.grad, gc, fn, w.dlc, w, !d.central, s);
+          train_net_bf16<1>(Xc, Sc, d.Dc, d.Hc, effective_bf16_weights(c, eff, 1), eff, oc, w.grad, gc, fn, w.dlc, wk, !d.central, s);
         } else if (fused_train_supported(d.Hc, d.Dc)) {
           FusedTrainArgs ta{};
           ta.X = Xc; ta.S = Sc; ta.Din = d.Dc; ta.px = fused_train_px(d.Dc);
           ta.W1 = eff + oc.W1; ta.b1 = eff + oc.b1; ta.W2 = eff + oc.W2; ta.b2 = eff + oc.b2; ta.W3 = eff + oc.W3;
           ta.W1s = eff + pm.sw_w1[1]; ta.W2s = eff + pm.sw_w2[1]; ta.W2Ts = eff + pm.sw_w2t[1];
           ta.b3 = eff + oc.b3; ta.gW1 = w.grad + gc.W1; ta.gb1 = w.grad + gc.b1; ta.gW2 = w.grad + gc.W2;
-          ta.gb2 = w.grad + gc.b2; ta.gW3 = w.grad + gc.W3; ta.gb3 = w.grad + gc.b3; ta.stats = w.sc->acc;
+          ta.gb2 = w.grad + gc.b2; ta.gW3 = w.grad + gc.W3; ta.gb3 = w.grad + gc.b3; ta.stats = sck->acc;
           ta.partial = w.partial; ta.gcount = d.P - d.Pa;
           const int32_t rc = launch_fused_train<1>(d.Hc, ta, fn, s);
           if (rc != MARL_OK) return rc;
@@ -596,21 +608,21 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
           if (wreg_forward_supported(Xc, Sc, d.Dc, d.Hc)) {
             const int32_t rc = train_forward_wreg<1>(Xc, Sc, d.Dc, eff + oc.W1, eff + oc.b1, eff + oc.W2, eff + oc.b2,
                                                      eff + oc.W3, eff + oc.b3, w.h1c, w.h2c, w.grad + gc.W3,
-                                                     w.grad + gc.b3, w.sc->acc, fn, s);
+                                                     w.grad + gc.b3, sck->acc, fn, s);
             if (rc != MARL_OK) return rc;
           } else if (fused_c) {
             FusedFwdArgs fa{};
             fa.X = Xc; fa.S = Sc; fa.Din = d.Dc; fa.xvec = aligned16(Xc.base) && Xc.ld % 4 == 0 && d.Dc % 4 == 0;
             fa.W1 = eff + oc.W1; fa.b1 = eff + oc.b1; fa.W2 = eff + oc.W2; fa.b2 = eff + oc.b2; fa.W3 = eff + oc.W3;
             fa.b3 = eff + oc.b3; fa.h1_out = w.h1c; fa.dz2_out = w.h2c; fa.gW3 = w.grad + gc.W3; fa.gb3 = w.grad + gc.b3;
-            fa.stats = w.sc->acc;
+            fa.stats = sck->acc;
             fa.W1s = eff + pm.sw_w1[1]; fa.W2s = eff + pm.sw_w2[1]; fa.kpad1 = pm.kpad1[1]; fa.px = fused_forward_px(d.Dc);
             launch_fused_forward<1, true>(d.Hc, fa, fn, s);
           } else {
             mlp_hidden_forward(Xc, Sc, d.Dc, d.Hc, eff + oc.W1, eff + oc.b1, eff + oc.W2, eff + oc.b2, w.h1c, w.h2c, d.bf16, s);
             const unsigned nb = (unsigned)std::min<int64_t>(2048, (Sc + kHeadTile - 1) / kHeadTile);
             hipLaunchKernelGGL((loss_head_kernel<1, CriticLoss, float>), dim3(nb), dim3(256), 0, s, w.h2c, Sc, d.Hc, eff + oc.W3,
-                               eff + oc.b3, fn, w.dlc, w.grad + gc.W3, w.grad + gc.b3, w.sc, 0.f);
+                               eff + oc.b3, fn, w.dlc, w.grad + gc.W3, w.grad + gc.b3, sck, 0.f);
           }
           mlp_backward<1>(Xc, Sc, d.Dc, d.Hc, eff + oc.W2, eff + oc.W3, w.h1c, w.h2c, w.dz1c, w.dlc, w.grad + gc.W1,
                           w.grad + gc.b1, w.grad + gc.W2, w.grad + gc.b2, d.bf16, fused_c, w.partial_w1, s);
@@ -618,7 +630,7 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
       }
       // ---- clip + Adam
       hipLaunchKernelGGL(grad_norm_kernel, dim3((unsigned)std::min<int64_t>(256, (d.P + 255) / 256)), dim3(256), 0, s,
-                         w.grad, d.P, w.sc);
+                         w.grad, d.P, sck);
       ++k;
       AdamArgs a{};
       a.k_base = adam_step_base;
@@ -629,8 +641,8 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
       a.max_norm = c.max_grad_norm; a.ent_coef = c.ent_coef; a.vf_coef = c.vf_coef;
       const bool last = (e == c.n_epochs - 1 && mb == c.n_minibatches - 1);
       hipLaunchKernelGGL(adam_kernel, dim3((unsigned)((d.P + 255) / 256)), dim3(256), 0, s, params, adam_m, adam_v,
-                         w.grad, d.P, a, w.sc, stats + (int64_t)(e * c.n_minibatches + mb) * MARL_N_STATS,
-                         (last ? grad_dump : nullptr));
+                         w.grad, d.P, a, sck, stats + (int64_t)(e * c.n_minibatches + mb) * MARL_N_STATS,
+                         (last ? grad_dump : nullptr), w.sc + ((step + 1) & 1));
       const int32_t rc = launch_status();
       if (rc != MARL_OK) return rc;
     }

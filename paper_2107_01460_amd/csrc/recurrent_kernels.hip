@@ -709,11 +709,11 @@ int32_t launch_ppo_update_recurrent(const marl_config& c, marl_traj tr, marl_rec
     for (int mb = 0; mb < c.n_minibatches; ++mb) {
       const int32_t* envs = (perm ? perm + (int64_t)e * d.N : w.ident) + (int64_t)mb * J;
       const float* eff = stage_params(d, params, w.eff, s);
-      hipLaunchKernelGGL(zero_step_kernel, dim3(blocks_for(d.P)), dim3(256), 0, s, w.grad, d.P, w.sc);
+      hipLaunchKernelGGL(zero_step_kernel, dim3(blocks_for(d.P)), dim3(256), 0, s, w.grad, d.P, w.sc, 1, (double*)nullptr, 0);
       hipLaunchKernelGGL(seq_index_kernel, dim3(blocks_for(TJ)), dim3(256), 0, s, envs, tr.done, (int)J, d.N, d.T, w.rows, w.keep);
       LossCommon lc{};
       lc.rows = w.rows; lc.A = d.A; lc.rows_mb = TJ; lc.inv_B = (float)(1.0 / (double)(TJ * d.A));
-      lc.sc = w.sc; lc.normalize = c.normalize_adv; lc.clip_eps = c.clip_eps; lc.ent_coef = c.ent_coef;
+      lc.sc = w.sc; lc.adv_stats = &w.sc->adv_sum; lc.normalize = c.normalize_adv; lc.clip_eps = c.clip_eps; lc.ent_coef = c.ent_coef;
       lc.vf_coef = c.vf_coef; lc.clip_value = c.clip_value;
       if (c.normalize_adv) {
         const unsigned nb = (unsigned)std::min<int64_t>(256, (TJ * d.A + 255) / 256);
@@ -743,7 +743,8 @@ int32_t launch_ppo_update_recurrent(const marl_config& c, marl_traj tr, marl_rec
       a.max_norm = c.max_grad_norm; a.ent_coef = c.ent_coef; a.vf_coef = c.vf_coef;
       const bool last = (e == c.n_epochs - 1 && mb == c.n_minibatches - 1);
       hipLaunchKernelGGL(adam_kernel, dim3(blocks_for(d.P)), dim3(256), 0, s, params, adam_m, adam_v, w.grad, d.P, a, w.sc,
-                         stats + (int64_t)(e * c.n_minibatches + mb) * MARL_N_STATS, (last ? grad_dump : (float*)nullptr));
+                         stats + (int64_t)(e * c.n_minibatches + mb) * MARL_N_STATS, (last ? grad_dump : (float*)nullptr),
+                         (Scalars*)nullptr);
       const int32_t rc = launch_status();
       if (rc != MARL_OK) return rc;
     }
