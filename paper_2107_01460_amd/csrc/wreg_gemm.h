@@ -337,11 +337,14 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) 
         float part[NOUT];
 #pragma unroll
         for (int k = 0; k < NOUT; ++k) part[k] = 0.f;
-#pragma unroll 8
-        for (int i = 64 * grp; i < 64 * grp + 64; ++i) {
-          const float h = Hs[smp * P + i];
+#pragma unroll 4
+        for (int i = 64 * grp; i < 64 * grp + 64; i += 4) {  // 16-byte reads of the row (P is a multiple of 4)
+          const float4 hv = *reinterpret_cast<const float4*>(&Hs[smp * P + i]);
+          const float hh[4] = {hv.x, hv.y, hv.z, hv.w};
 #pragma unroll
-          for (int k = 0; k < NOUT; ++k) part[k] = fmaf(h, W3s[i * NOUT + k], part[k]);
+          for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int k = 0; k < NOUT; ++k) part[k] = fmaf(hh[j], W3s[(i + j) * NOUT + k], part[k]);
         }
 #pragma unroll
         for (int k = 0; k < NOUT; ++k) red[(grp * BM + smp) * NOUT + k] = part[k];
