@@ -161,11 +161,21 @@ __global__ void __launch_bounds__(256, 2) fused_forward_kernel(FusedFwdArgs a, F
       float part[NOUT];
 #pragma unroll
       for (int k = 0; k < NOUT; ++k) part[k] = 0.f;
-#pragma unroll 4
-      for (int i = grp * PER; i < (grp + 1) * PER; ++i) {
-        const float h = L.Hs[s * PH + i];
+      static_assert(PER % 4 == 0, "hidden units are read four at a time");
+#pragma unroll 2
+      for (int i = grp * PER; i < (grp + 1) * PER; i += 4) {
+        const float4 hv = *reinterpret_cast<const float4*>(&L.Hs[s * PH + i]);
+        const float hh[4] = {hv.x, hv.y, hv.z, hv.w};
+        float wv[4 * NOUT];  // W3 rows i..i+3: 4 * NOUT consecutive floats, the same for every lane of the wavefront
 #pragma unroll
-        for (int k = 0; k < NOUT; ++k) part[k] = fmaf(h, L.W3s[i * NOUT + k], part[k]);
+        for (int q = 0; q < NOUT; ++q) {
+          const float4 t = *reinterpret_cast<const float4*>(&L.W3s[i * NOUT + 4 * q]);
+          wv[4 * q] = t.x; wv[4 * q + 1] = t.y; wv[4 * q + 2] = t.z; wv[4 * q + 3] = t.w;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int k = 0; k < NOUT; ++k) part[k] = fmaf(hh[j], wv[j * NOUT + k], part[k]);
       }
 #pragma unroll
       for (int k = 0; k < NOUT; ++k) L.red[(grp * BM + s) * NOUT + k] = part[k];
