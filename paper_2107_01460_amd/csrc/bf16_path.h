@@ -50,30 +50,37 @@ static __global__ void __launch_bounds__(256) pack_obs_bf16_kernel(RowSrc X, int
   __shared__ float tile[64][65];
   const int tid = threadIdx.x;
   const int64_t s0 = (int64_t)blockIdx.x * 64;
-  const float* rows[16];  // thread stages rows tid/64 + 4q, column tid%64
+  const float* rows[16];  // thread stages rows tid/64 + 4q, column tid%64; rows past the end: the last row, zeroed below
 #pragma unroll
-  for (int q = 0; q < 16; ++q) {
-    const int64_t s = s0 + (tid >> 6) + 4 * q;
-    rows[q] = s < S ? X.ptr(s) : nullptr;
-  }
+  for (int q = 0; q < 16; ++q) rows[q] = X.ptr(min(s0 + (tid >> 6) + 4 * q, S - 1));
   for (int d0 = 0; d0 < Dp; d0 += 64) {
-    const int cc = tid & 63;
+    const int cc = tid & 63, csrc = min(d0 + cc, Din - 1);
+    float v[16];  // all loads of the chunk before the first store (no branch around a load)
+#pragma unroll
+    for (int q = 0; q < 16; ++q) v[q] = rows[q][csrc];
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
       const int r = (tid >> 6) + 4 * q;
-      tile[r][cc] = (rows[q] != nullptr && d0 + cc < Din) ? rows[q][d0 + cc] : 0.f;
+      tile[r][cc] = (s0 + r < S && d0 + cc < Din) ? v[q] : 0.f;
     }
     __syncthreads();
+    // both copies leave with 16-byte stores: eight columns of a row, eight samples of a column (Dp is a multiple of 64)
 #pragma unroll
-    for (int q = 0; q < 16; ++q) {
-      const int r = (tid >> 6) + 4 * q;
-      if (s0 + r < S && d0 + cc < Dp) Xb[(s0 + r) * Dp + d0 + cc] = to_bf16(tile[r][cc]);
+    for (int q = 0; q < 2; ++q) {
+      const int r = (tid >> 3) + 32 * q, c0 = 8 * (tid & 7);
+      uint32_t w[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) w[j] = pack2_bf16(tile[r][c0 + 2 * j], tile[r][c0 + 2 * j + 1]);
+      if (s0 + r < S) *reinterpret_cast<uint4*>(&Xb[(s0 + r) * Dp + d0 + c0]) = make_uint4(w[0], w[1], w[2], w[3]);
     }
     if (XbT != nullptr) {
 #pragma unroll
-      for (int q = 0; q < 16; ++q) {
-        const int dd = (tid >> 6) + 4 * q, ss = tid & 63;
-        if (d0 + dd < Dp && s0 + ss < Sp) XbT[((s0 >> 6) * Dp + d0 + dd) * 64 + ss] = to_bf16(tile[ss][dd]);
+      for (int q = 0; q < 2; ++q) {
+        const int dd = (tid >> 3) + 32 * q, ss = 8 * (tid & 7);
+        uint32_t w[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) w[j] = pack2_bf16(tile[ss + 2 * j][dd], tile[ss + 2 * j + 1][dd]);
+        if (s0 + ss < Sp) *reinterpret_cast<uint4*>(&XbT[((s0 >> 6) * Dp + d0 + dd) * 64 + ss]) = make_uint4(w[0], w[1], w[2], w[3]);
       }
     }
     __syncthreads();
