@@ -330,14 +330,26 @@ __global__ void __launch_bounds__(256, 2) gemm2_f32_kernel(GemmArgs g) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int lo = lane & 31, hi = lane >> 5;
-  const int64_t n0 = (int64_t)blockIdx.y * BN;
+  // TN: the tiles of one k slab are made neighbours on one XCD (workgroups are dealt round-robin to the eight XCDs in
+  // the order x, y, z), so that a slab of A / B is fetched from HBM once and found in that XCD's L2 by the other tiles
+  // that contract over it; with the plain (x, y, z) order every tile of a slab ran on another XCD and the operands
+  // were read twice (1074 MB per launch at 256 x 256 outputs where 537 are algorithmic).
+  unsigned bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z;
+  if (MODE == GEMM_TN) {
+    const unsigned lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+    const unsigned lg = xcd_remap(lin, gridDim.x * gridDim.y * gridDim.z);
+    bx = lg % gridDim.x;
+    by = (lg / gridDim.x) % gridDim.y;
+    bz = lg / (gridDim.x * gridDim.y);
+  }
+  const int64_t n0 = (int64_t)by * BN;
   // NN / NT: the workgroup is persistent over row tiles (tile, tile + gridDim.x, ...) and the first k-tile of
   // the next row tile is already in flight while the current one finishes, so that neither the first load
   // latency nor the epilogue of a row tile leaves the memory pipe idle.  TN: one output tile, k split over z.
   const int64_t num_mt = (g.M + BM - 1) / BM;
   int64_t k_begin = 0, k_end = g.K;
   if (MODE == GEMM_TN) {
-    k_begin = (int64_t)blockIdx.z * g.k_per_split;
+    k_begin = (int64_t)bz * g.k_per_split;
     k_end = min(g.K, k_begin + g.k_per_split);
   }
 
@@ -351,7 +363,7 @@ __global__ void __launch_bounds__(256, 2) gemm2_f32_kernel(GemmArgs g) {
   constexpr int A_REGS = 16;
   float ra[A_REGS];
   const float* arow[AVEC ? 4 : 16];
-  int64_t m0_fetch = (int64_t)blockIdx.x * BM;  // row tile the staging registers belong to
+  int64_t m0_fetch = (int64_t)bx * BM;  // row tile the staging registers belong to
   auto set_rows = [&](int64_t m0) {
     m0_fetch = m0;
     if (A_KCONT) {
@@ -453,9 +465,9 @@ __global__ void __launch_bounds__(256, 2) gemm2_f32_kernel(GemmArgs g) {
 
   // TN: column sums of B (the bias gradient) ride along: each thread adds up the values it stages
   float4 bsum = make_float4(0.f, 0.f, 0.f, 0.f);
-  const bool want_bsum = MODE == GEMM_TN && g.colsum != nullptr && blockIdx.x == 0;
+  const bool want_bsum = MODE == GEMM_TN && g.colsum != nullptr && bx == 0;
 
-  int64_t tile = blockIdx.x;
+  int64_t tile = bx;
   if (tile < num_mt && k_begin < k_end) {
     set_rows(tile * BM);
     fetch(k_begin);
