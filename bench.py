@@ -21,7 +21,7 @@ ORACLE_SAMPLE_ENVS = {1: 64, 2: 64, 3: 64, 4: 2, 5: 2048}
 PEAK = {"mfma_f32": 157.3, "mfma_bf16": 2500.0, "hbm": 8000.0}   # TFLOP/s, TFLOP/s, GB/s
 # HBM bytes per launch (read + write) of the dominant kernel, from the rocprofv3 PMC runs summarised in
 # profiles/bench_c3_pmc_hbm_traffic.txt (FETCH_SIZE x 2.000 and WRITE_SIZE x 1.000 after the 1 GiB copy calibration).
-PMC_TRAFFIC_BYTES = {("c3_15x15_4ag_mappo", "fused_train"): 447.9e6 + 47.5e6}
+PMC_TRAFFIC_BYTES = {("c3_15x15_4ag_mappo", "fused_train"): 450.4e6 + 80.8e6}
 
 
 def gemm_flops_per_step(cfg, W):
