@@ -211,7 +211,10 @@ __global__ void __launch_bounds__(512) gru_step_fwd_kernel(const float* __restri
   extern __shared__ __attribute__((aligned(16))) float lds[];
   const int PH = H + 4;
   float* Hs = lds;  // [32][PH]
-  const int tid = threadIdx.x, lane = tid & 63, u = tid >> 6, lo = lane & 31, hi = lane >> 5;
+  // blockIdx.y: which share of the units this workgroup computes (blockDim.x / 64 wavefronts of 32 units each).  With
+  // few samples per step the units of a tile are split over several workgroups so that every CU has work; every one of
+  // them stages the whole h tile, so hout / hnext must then not alias hprev.
+  const int tid = threadIdx.x, lane = tid & 63, u = blockIdx.y * (blockDim.x >> 6) + (tid >> 6), lo = lane & 31, hi = lane >> 5;
   const int nthreads = blockDim.x;
   const int64_t s0 = (int64_t)blockIdx.x * kStepRows;
   for (int f = tid; f < kStepRows * (H / 4); f += nthreads) {
@@ -443,7 +446,12 @@ int32_t launch_step_forward(const float* Gi, const float* hprev, int64_t S, int 
                             const float* keep, int per, hipStream_t s) {
   if (fused_step_supported(H)) {
     TimedLaunch timed(KC_GEMM_NN, 2.0 * (double)S * H * 3.0 * H, s);
-    hipLaunchKernelGGL(gru_step_fwd_kernel, dim3((unsigned)((S + kStepRows - 1) / kStepRows)), dim3(2 * H), fused_fwd_lds(H),
+    const int64_t tiles = (S + kStepRows - 1) / kStepRows;
+    int ysplit = 1;  // workgroups per tile: enough for one per CU where the state is not updated in place
+    if (hprev != hout && hprev != hnext)
+      while (tiles * ysplit < 256 && ysplit < H / 32) ysplit *= 2;
+    while ((H / 32) % ysplit != 0) ysplit /= 2;
+    hipLaunchKernelGGL(gru_step_fwd_kernel, dim3((unsigned)tiles, (unsigned)ysplit), dim3(2 * H / ysplit), fused_fwd_lds(H),
                        s, Gi, wh_op, eff + o.bi, eff + o.bh, hprev, rzn, ghn, hout, hnext, keep, per, S, H);
     return MARL_OK;
   }
