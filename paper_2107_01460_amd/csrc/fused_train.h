@@ -105,6 +105,10 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
   float* dls = red + NT * NOUT;           // [BM][8]
   float* W3s = dls + BM * 8;               // [H][NOUT]
   float* const xdump = W3s + H * NOUT;     // one float: where the staged values that are not part of a row go
+  // per-sample-slot sums that only the first BM threads touch, once per tile (b3 gradient, loss statistics): in LDS
+  // rather than in 11 registers of every thread, which this kernel does not have to spare
+  constexpr int AS = NOUT + 5;
+  float* const accS = xdump + 4;           // [max(BM, 64)][AS]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lo = lane & 31, hi = lane >> 5;
@@ -157,9 +161,10 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
   for (int q = 0; q < DW2_TPW; ++q)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc2[q][r] = 0.f;
-  float gw[NOUT], gb[NOUT], st[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
+  float gw[NOUT];
 #pragma unroll
-  for (int k = 0; k < NOUT; ++k) gw[k] = gb[k] = 0.f;
+  for (int k = 0; k < NOUT; ++k) gw[k] = 0.f;
+  for (int i = tid; i < (BM < 64 ? 64 : BM) * AS; i += NT) accS[i] = 0.f;  // ordered before its first use by the barriers below
   float gb1r = 0.f, gb2r = 0.f;  // bias gradients of column nt*32+lo (lanes hi == 0)
 
   // ---- staging helpers.  The inputs of the next tile come in two steps: the gather entries at the top of a
@@ -186,6 +191,9 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
     const int last = ((xoff + a.Din + 3) >> 2) - 1;  // chunks past the row: the last one again (none of its elements is stored)
 #pragma unroll
     for (int p = 0; p < XV; ++p) xr[p] = chunk[min(xcol0 + TPR * p, last)];
+  };
+  // (the loss inputs of the next tile are requested right after the loss of the current one, into the same registers)
+  auto fetch_tile_loss_inputs = [&](int64_t s0) {
     if (tid < BM && s0 + tid < a.S) lin_next = fn.load_with(s0 + tid, lentry);
   };
   auto store_tile_inputs = [&]() {
@@ -207,6 +215,7 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
   if (tile < ntiles) {
     fetch_tile_entries(tile * BM);
     fetch_tile_inputs(tile * BM);
+    fetch_tile_loss_inputs(tile * BM);
   }
 #ifdef MARL_PHASE_TIMERS
   long long phase_t0_ = (long long)__builtin_amdgcn_s_memtime();
@@ -216,7 +225,6 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
     const bool have_next = tile + gridDim.x < ntiles;
     // ---- this tile's observations to LDS
     store_tile_inputs();
-    const typename LossFn::In lin = lin_next;
     if (have_next) fetch_tile_entries((tile + gridDim.x) * BM);
     __syncthreads();
 
@@ -298,15 +306,19 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
         out[k] = v;
         dl[k] = 0.f;
       }
-      if (s0 + tid < a.S) fn.compute(lin, prep, out, dl, st);
+      float st[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
+      if (s0 + tid < a.S) fn.compute(lin_next, prep, out, dl, st);
       float d8[8];
 #pragma unroll
       for (int k = 0; k < 8; ++k) d8[k] = k < NOUT ? dl[k < NOUT ? k : 0] : 0.f;
       *reinterpret_cast<float4*>(&dls[tid * 8]) = make_float4(d8[0], d8[1], d8[2], d8[3]);
       *reinterpret_cast<float4*>(&dls[tid * 8 + 4]) = make_float4(d8[4], d8[5], d8[6], d8[7]);
 #pragma unroll
-      for (int k = 0; k < NOUT; ++k) gb[k] += dl[k];
+      for (int k = 0; k < NOUT; ++k) accS[tid * AS + k] += dl[k];
+#pragma unroll
+      for (int k = 0; k < 5; ++k) accS[tid * AS + NOUT + k] += st[k];
     }
+    if (have_next) fetch_tile_loss_inputs((tile + gridDim.x) * BM);
     __syncthreads();
     PHASE_MARK(6);
     // ---- W3 gradient: gW3[i][k] += sum_s h2[s][i] dl[s][k]   (thread -> hidden unit tid % H, a share of the samples)
@@ -438,13 +450,13 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
   if (tid < (BM < 64 ? 64 : BM)) {  // whole wavefronts; lanes past BM hold zeros
 #pragma unroll
     for (int k = 0; k < NOUT; ++k) {
-      float v = gb[k];
+      float v = accS[tid * AS + k];
       for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
       if (lane == 0) atomicAdd(&gb3[k], v);
     }
 #pragma unroll
     for (int k = 0; k < 5; ++k) {
-      float v = st[k];
+      float v = accS[tid * AS + NOUT + k];
       for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
       if (lane == 0 && v != 0.f) atomicAdd(&a.stats[k], v);
     }
@@ -463,7 +475,7 @@ inline int fused_train_px(int Din) {
 template <int H, int BM, int NOUT, int DMAX, int NW, class LossFn>
 inline int32_t launch_fused_train_inst(const FusedTrainArgs& a, const LossFn& fn, hipStream_t s) {
   auto kern = fused_train_kernel<H, BM, NOUT, DMAX, NW, LossFn>;
-  const size_t floats = (size_t)BM * a.px + 2 * (size_t)BM * (H + 4) + 64 * NW * NOUT + BM * 8 + H * NOUT + 4;
+  const size_t floats = (size_t)BM * a.px + 2 * (size_t)BM * (H + 4) + 64 * NW * NOUT + BM * 8 + H * NOUT + 4 + (BM < 64 ? 64 : BM) * (NOUT + 5);
   const size_t bytes = floats * 4;
   static bool configured = false;  // per instantiation
   if (!configured) {
