@@ -77,7 +77,7 @@ __global__ void __launch_bounds__(256, 2) fused_forward_kernel(FusedFwdArgs a, F
     float* const h1_tile = TRAIN ? a.h1_out + s0 * H : nullptr;    // uniform bases: lanes add 32-bit offsets
     float* const dz2_tile = TRAIN ? a.dz2_out + s0 * H : nullptr;
     // ---- this tile's rows to LDS: thread -> row tid / TPR, every TPR-th 16-byte (or 4-byte) piece of it, four
-    // loads in flight at a time.  Rows past the end re-read the last row (their results are never stored).
+    // (twelve) loads in flight at a time.  Rows past the end re-read the last row (their results are never stored).
     {
       const int xr_row = tid / TPR, c0 = tid % TPR;
       const float* xrow = a.X.ptr(min(s0 + xr_row, a.S - 1));
@@ -96,12 +96,13 @@ __global__ void __launch_bounds__(256, 2) fused_forward_kernel(FusedFwdArgs a, F
             if (c + u * TPR < nv) *reinterpret_cast<float4*>(xdst + 4 * (c + u * TPR)) = v[u];
         }
       } else {
-        for (int c = c0; c < a.Din; c += 4 * TPR) {
-          float v[4];
+        constexpr int XB = 12;  // loads in flight per thread: a 75- or 27-wide row is one batch
+        for (int c = c0; c < a.Din; c += XB * TPR) {
+          float v[XB];
 #pragma unroll
-          for (int u = 0; u < 4; ++u) v[u] = xrow[min(c + u * TPR, a.Din - 1)];
+          for (int u = 0; u < XB; ++u) v[u] = xrow[min(c + u * TPR, a.Din - 1)];
 #pragma unroll
-          for (int u = 0; u < 4; ++u)
+          for (int u = 0; u < XB; ++u)
             if (c + u * TPR < a.Din) xdst[c + u * TPR] = v[u];
         }
       }
