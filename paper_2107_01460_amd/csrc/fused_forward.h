@@ -19,7 +19,8 @@ struct FusedFwdArgs {
   RowSrc X;   // S rows of Din floats (optionally gathered)
   int64_t S;
   int Din;
-  int xvec;   // rows are 16-byte aligned and Din % 4 == 0: 16-byte loads of X
+  int xvec;   // 1: rows are 16-byte aligned and Din % 4 == 0: 16-byte loads of X.  2: rows start at any 4-byte boundary of a
+              // buffer whose two ends are 16-byte aligned: a row is fetched as the aligned 16-byte chunks that cover it
   const float *W1, *b1, *W2, *b2, *W3, *b3;  // aligned working copy, W[in][H]
   const float *W1s, *W2s;  // operand-order copies: (k, n) at ((k / 4) * H + n) * 4 + k % 4; W1s zero-padded to kpad1 rows
   int kpad1;               // Din rounded up to a multiple of 16
@@ -82,7 +83,27 @@ __global__ void __launch_bounds__(256, 2) fused_forward_kernel(FusedFwdArgs a, F
       const int xr_row = tid / TPR, c0 = tid % TPR;
       const float* xrow = a.X.ptr(min(s0 + xr_row, a.S - 1));
       float* xdst = L.Xs + xr_row * px;
-      if (a.xvec) {
+      if (a.xvec == 2) {
+        // element j of chunk q is column 4 q + j - xo of the row; the chunks never leave the buffer (its ends are aligned)
+        const uintptr_t addr = reinterpret_cast<uintptr_t>(xrow);
+        const float4* const chunk = reinterpret_cast<const float4*>(addr & ~(uintptr_t)15);
+        const int xo = (int)((addr >> 2) & 3), last = ((xo + a.Din + 3) >> 2) - 1;
+        constexpr int XC = 3;  // chunks in flight per thread: a 75-wide row is one batch
+        for (int q = c0; q <= last; q += XC * TPR) {
+          float4 v[XC];
+#pragma unroll
+          for (int u = 0; u < XC; ++u) v[u] = chunk[min(q + u * TPR, last)];
+#pragma unroll
+          for (int u = 0; u < XC; ++u) {
+            const float e[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              const int c = 4 * (q + u * TPR) + j - xo;
+              if (c >= 0 && c < a.Din && q + u * TPR <= last) xdst[c] = e[j];
+            }
+          }
+        }
+      } else if (a.xvec) {
         const int nv = a.Din / 4;
         for (int c = c0; c < nv; c += 4 * TPR) {
           float4 v[4];

@@ -68,6 +68,7 @@ FusedFwdArgs fused_args(const RowSrc& X, int64_t S, int Din, const float* eff, c
   FusedFwdArgs a{};
   a.X = X; a.S = S; a.Din = Din;
   a.xvec = aligned16(X.base) && X.ld % 4 == 0 && Din % 4 == 0;
+  if (!a.xvec && X.gather == nullptr && aligned16(X.base) && (X.nrows * X.ld) % 4 == 0) a.xvec = 2;
   a.W1 = eff + o.W1; a.b1 = eff + o.b1; a.W2 = eff + o.W2; a.b2 = eff + o.b2; a.W3 = eff + o.W3; a.b3 = eff + o.b3;
   a.W1s = eff + pm.sw_w1[net]; a.W2s = eff + pm.sw_w2[net]; a.kpad1 = pm.kpad1[net]; a.px = fused_forward_px(Din);
   return a;
