@@ -223,6 +223,8 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
   for (; tile < ntiles; tile += gridDim.x) {
     const int64_t s0 = tile * BM;
     const bool have_next = tile + gridDim.x < ntiles;
+    // (the first weight groups of a layer are requested ahead of the barrier or epilogue in front of it)
+    const PhaseB pb1 = gemm_phase_prefetch<H>(a.W1s + (hi * H + nt * 32 + lo) * 4, kpad1 / 16);
     // ---- this tile's observations to LDS
     store_tile_inputs();
     if (have_next) fetch_tile_entries((tile + gridDim.x) * BM);
@@ -233,7 +235,8 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
     // ---- layer 1
-    gemm_phase_regs<H>(Xs + (mt * 32 + lo) * px + 4 * hi, a.W1s + (hi * H + nt * 32 + lo) * 4, kpad1 / 16, acc);
+    gemm_phase_regs<H, true>(Xs + (mt * 32 + lo) * px + 4 * hi, a.W1s + (hi * H + nt * 32 + lo) * 4, kpad1 / 16, acc, pb1);
+    const PhaseB pb2 = gemm_phase_prefetch<H>(a.W2s + (hi * H + nt * 32 + lo) * 4, H / 16);
     PHASE_MARK(1);
     {
       const int n = nt * 32 + lo;
@@ -250,7 +253,7 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
     PHASE_MARK(2);
     // ---- layer 2
     __syncthreads();  // the h1 tile is complete
-    gemm_phase_regs<H>(H1 + (mt * 32 + lo) * PH + 4 * hi, a.W2s + (hi * H + nt * 32 + lo) * 4, H / 16, acc);
+    gemm_phase_regs<H, true>(H1 + (mt * 32 + lo) * PH + 4 * hi, a.W2s + (hi * H + nt * 32 + lo) * 4, H / 16, acc, pb2);
     PHASE_MARK(3);
     if (have_next) fetch_tile_inputs((tile + gridDim.x) * BM);  // lands during the ALU phases and dW2
     floatx16 h2r;  // h2 of this wavefront's tile
@@ -364,6 +367,7 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
     }
     __syncthreads();
     PHASE_MARK(8);
+    const PhaseB pbz = gemm_phase_prefetch<H>(a.W2Ts + (hi * H + nt * 32 + lo) * 4, H / 16);
     // ---- dW2 += h1^T dz2   (k runs over the samples of the tile)
     {
       const int t0 = (wave * DW2_TPW) % (NTN * NTN);
@@ -376,7 +380,7 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
     // ---- dz1 = (dz2 W2^T) * (1 - h1^2), in place over h1
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-    gemm_phase_regs<H>(H2 + (mt * 32 + lo) * PH + 4 * hi, a.W2Ts + (hi * H + nt * 32 + lo) * 4, H / 16, acc);
+    gemm_phase_regs<H, true>(H2 + (mt * 32 + lo) * PH + 4 * hi, a.W2Ts + (hi * H + nt * 32 + lo) * 4, H / 16, acc, pbz);
     __syncthreads();  // every wavefront is done reading h1 (dW2) before its tiles are overwritten
     PHASE_MARK(10);
     {

@@ -104,9 +104,26 @@ __device__ __forceinline__ float tanh_f32(float x) {
 // into registers with 16-byte loads that are contiguous across the wavefront, one group ahead of its use, so a
 // layer needs no staging buffer and no barrier of its own.  Both operands must be readable (zero-padded) up to
 // 16 * kgroups along k.
+// B of the first two groups may come in already loaded (b00 b01: group 0, b10 b11: group 1; see gemm_phase_prefetch):
+// a phase that follows a barrier or an element-wise epilogue then starts on operands requested before it, instead of
+// waiting an L2 round trip for them.
+struct PhaseB {
+  float4 b00, b01, b10, b11;
+};
 template <int LDB>
+__device__ __forceinline__ PhaseB gemm_phase_prefetch(const float* __restrict__ Bg, int kgroups) {
+  const int g1 = kgroups > 1 ? 1 : 0;
+  PhaseB p;
+  p.b00 = *reinterpret_cast<const float4*>(Bg);
+  p.b01 = *reinterpret_cast<const float4*>(Bg + (int64_t)8 * LDB);
+  p.b10 = *reinterpret_cast<const float4*>(Bg + ((int64_t)16 * g1) * LDB);
+  p.b11 = *reinterpret_cast<const float4*>(Bg + ((int64_t)16 * g1 + 8) * LDB);
+  return p;
+}
+
+template <int LDB, bool PRE = false>
 __device__ __forceinline__ void gemm_phase_regs(const float* __restrict__ As, const float* __restrict__ Bg, int kgroups,
-                                                floatx16& acc) {
+                                                floatx16& acc, PhaseB pre = PhaseB()) {
   constexpr int kDepth = 3;  // groups in flight: the one in use and two on their way
   float4 av[kDepth][2], bv[kDepth][2];
   auto load = [&](int g, float4 (&a2)[2], float4 (&b2)[2]) {
@@ -119,6 +136,9 @@ __device__ __forceinline__ void gemm_phase_regs(const float* __restrict__ As, co
   };
 #pragma unroll
   for (int d = 0; d < kDepth - 1; ++d) load(d, av[d], bv[d]);
+  if (PRE) {
+    bv[0][0] = pre.b00; bv[0][1] = pre.b01; bv[1][0] = pre.b10; bv[1][1] = pre.b11;
+  }
 #pragma unroll 1
   for (int g0 = 0; g0 < kgroups; g0 += kDepth) {
 #pragma unroll
