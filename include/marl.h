@@ -16,6 +16,8 @@
  *     (256 recommended); a misaligned or null required pointer is rejected before any launch.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls are
  *     asynchronous on that stream and ordered by it.
+ *     The one exception is the measurement hook marl_timing_enable / marl_timing_read at the end of this header,
+ *     which keeps host state, is not thread-safe and waits for events; a product caller never needs it.
  *   - Return value: MARL_OK (0) or a negative marl_status.  Validation happens on the host
  *     before anything is launched; a call that returns an error has launched nothing.
  *   - Index conventions: N envs, A agents, F food items, D = 3*view*view observation floats,
@@ -49,7 +51,7 @@ typedef struct marl_config {
   int32_t grid;        /* G: side of the square grid, 2..64 */
   int32_t n_agents;    /* A: 1..8 */
   int32_t n_food;      /* F: 1..8; A + F <= G*G */
-  int32_t max_level;   /* agent levels are uniform in 1..max_level; max_level <= 3.  Warehouse world: the number of
+  int32_t max_level;   /* agent levels are uniform in 1..max_level; 1 <= max_level <= 15.  Warehouse world: the number of
                           shelves requested at any time, 1..n_food */
   int32_t episode_cap; /* an episode ends after this many steps at the latest */
   int32_t view;        /* V: odd side of the egocentric window, 3, 5 or 7 */
@@ -139,10 +141,15 @@ typedef struct marl_rec_state {
  * episode, ordinal of the delivery); the episode ends at the cap and, with env_kind = 2, on a collision.
  * Observation channels: 0 / 1 unloaded / 2 loaded robot; 0 / 1 idle / 2 requested shelf; 1 outside the grid, 0.5 goal. */
 
-/* Fills *out; touches no GPU.  Errors: MARL_E_NULL, MARL_E_CONFIG. */
+/* Buffer sizes of a configuration: what the caller has to allocate for the state, one rollout's experience
+ * (Section 2, Fig. 2: the experience a rollout hands to the loss) and the workspaces.  The paper gives no shapes;
+ * they follow from the workload list (grid, agents, view, networks).  Fills *out; touches no GPU.
+ * Errors: MARL_E_NULL, MARL_E_CONFIG. */
 int32_t marl_query_sizes(const marl_config* cfg, marl_sizes* out);
 
-/* Starts episode 0 in every env: agent levels, then A+F distinct cells (agents first), then food
+/* The vectorised environment's reset (Section 2: the environments are implemented on the accelerator so that they
+ * can be batched and compiled with the rest of the step; the paper names the task, Section 4, not its layout rules --
+ * those are the workload's).  Starts episode 0 in every env: agent levels, then A+F distinct cells (agents first), then food
  * levels (1..sum of the <=4 highest agent levels), all drawn from Philox4x32-10 keyed by
  * (seed; env, episode).  The layout of an env depends only on (seed, env index, episode id). */
 int32_t marl_env_reset(const marl_config* cfg, marl_env_state st, void* stream);
@@ -184,7 +191,9 @@ int32_t marl_rollout(const marl_config* cfg, marl_env_state st, const float* par
                      uint64_t step_offset, const int32_t* forced_actions, const float* forced_uniforms,
                      void* workspace, void* stream);
 
-/* Generalised advantage estimation per (env, agent), backwards in time:
+/* The advantage step between rollout and loss (Fig. 2: the experience is turned into a loss; the paper names PPO,
+ * Section 2, without its equations -- these are the standard ones the workload list states).
+ * Generalised advantage estimation per (env, agent), backwards in time:
  * delta_t = r_t + gamma (1-d_t) V_{t+1} - V_t;  adv_t = delta_t + gamma lambda (1-d_t) adv_{t+1};
  * adv_T = 0, V_T = last_value;  ret_t = adv_t + V_t.  Reads reward/value/done/last_value, writes adv/ret. */
 int32_t marl_compute_gae(const marl_config* cfg, marl_traj traj, void* stream);
@@ -265,7 +274,8 @@ int32_t marl_evaluate(const marl_config* cfg, marl_env_state st, const float* pa
 int32_t marl_timing_enable(int32_t on);
 int32_t marl_timing_read(int32_t kernel_class, double* total_ms, int64_t* launches, double* work);
 
-/* Human-readable name of a status code (static storage, host). */
+/* Human-readable name of a status code (static storage, host).  Part of the error convention of this boundary,
+ * not of the paper's method. */
 const char* marl_status_string(int32_t status);
 
 #ifdef __cplusplus

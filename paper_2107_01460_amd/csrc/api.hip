@@ -48,6 +48,7 @@ int32_t validate_config(const marl_config* c) {
   if (c->episode_cap < 1) return MARL_E_CONFIG;
   if (c->view != 3 && c->view != 5 && c->view != 7) return MARL_E_CONFIG;
   if (c->n_envs < 1 || c->rollout_len < 1) return MARL_E_CONFIG;
+  if (c->n_epochs < 1 || c->n_minibatches < 1) return MARL_E_CONFIG;  // before any use as a divisor
   for (int h : {c->actor_hidden, c->critic_hidden})
     if (h < 32 || h > 512 || h % 32 != 0) return MARL_E_CONFIG;
   if (c->central_critic != 0 && c->central_critic != 1) return MARL_E_CONFIG;
@@ -57,7 +58,6 @@ int32_t validate_config(const marl_config* c) {
   if (c->recurrent != 0 && c->recurrent != 1) return MARL_E_CONFIG;
   if (c->recurrent == 1 && (c->precision != 0 || c->n_envs % c->n_minibatches != 0)) return MARL_E_CONFIG;
   if (c->precision == 1 && (c->actor_hidden % 64 != 0 || c->critic_hidden % 64 != 0)) return MARL_E_CONFIG;  // bf16 k tile
-  if (c->n_epochs < 1 || c->n_minibatches < 1) return MARL_E_CONFIG;
   const int64_t R = (int64_t)c->n_envs * c->rollout_len;
   if (R % c->n_minibatches != 0) return MARL_E_CONFIG;
   if (R * c->n_agents >= ((int64_t)1 << 31)) return MARL_E_CONFIG;  // sample and row indices are 32-bit

@@ -293,26 +293,27 @@ inline bool fused_forward_supported(int H, int Din) {
 }
 
 template <int H, int BM, int NOUT, bool TRAIN, class Finish>
-inline void launch_fused_forward_inst(const FusedFwdArgs& a, const Finish& fin, hipStream_t s) {
+inline int32_t launch_fused_forward_inst(const FusedFwdArgs& a, const Finish& fin, hipStream_t s) {
   auto kern = fused_forward_kernel<H, BM, NOUT, TRAIN, Finish>;
   const size_t bytes = fused_forward_lds_bytes(H, a.Din, NOUT);
   static bool configured = false;  // per instantiation
   if (!configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return;
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return MARL_E_LAUNCH;
     configured = true;
   }
   const int64_t tiles = (a.S + BM - 1) / BM;
   const unsigned grid = (unsigned)std::min<int64_t>(tiles, TRAIN ? 1024 : 2048);  // persistent when training (register-resident W3 gradient)
   hipLaunchKernelGGL(kern, dim3(grid), dim3(256), bytes, s, a, fin);
+  return launch_status();
 }
 
 template <int NOUT, bool TRAIN, class Finish>
-inline void launch_fused_forward(int H, const FusedFwdArgs& a, const Finish& fin, hipStream_t s) {
+inline int32_t launch_fused_forward(int H, const FusedFwdArgs& a, const Finish& fin, hipStream_t s) {
   // algorithmic flops of the two hidden layers
   TimedLaunch timed(KC_GEMM_NN, 2.0 * (double)a.S * ((double)a.Din * H + (double)H * H), s);
-  if (H == 64) launch_fused_forward_inst<64, 64, NOUT, TRAIN, Finish>(a, fin, s);
-  else if (H == 128) launch_fused_forward_inst<128, 32, NOUT, TRAIN, Finish>(a, fin, s);
-  else launch_fused_forward_inst<256, 32, NOUT, TRAIN, Finish>(a, fin, s);
+  if (H == 64) return launch_fused_forward_inst<64, 64, NOUT, TRAIN, Finish>(a, fin, s);
+  if (H == 128) return launch_fused_forward_inst<128, 32, NOUT, TRAIN, Finish>(a, fin, s);
+  return launch_fused_forward_inst<256, 32, NOUT, TRAIN, Finish>(a, fin, s);
 }
 
 }  // namespace marl

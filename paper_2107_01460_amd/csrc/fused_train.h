@@ -1,18 +1,20 @@
-// Whole-network training pass for the small networks (hidden width 64 or 128, input width <= 96):
+// Whole-network training pass for the small networks (hidden width 64 or 128, input width <= 93):
 // forward, PPO loss, and the complete backward pass of one network in ONE kernel.  Nothing but the
 // observations and a few scalars per sample is read from HBM and nothing but the parameter gradient is
 // written: h1, h2, dz2, dz1 live in LDS / registers for the lifetime of a row tile, and the weight
 // gradients are accumulated in registers over all row tiles a workgroup owns.
 //
-// Workgroup = NW wavefronts, persistent.  Row tile = BM samples with (BM/32)(H/32) = NW, so that a layer
-// output is exactly NW 32x32 MFMA tiles, one per wavefront.  With NW = 4 (BM 32 for H = 128, 64 for H = 64)
-// two workgroups share a CU: their phases drift apart, so the ALU phases of one (tanh epilogues, output
-// layer, loss) run in the shadow of the other's MFMA phases.  Per tile:
-//   X -> LDS | L1 (W1 streamed in 32-row chunks) -> h1 (LDS) | L2 -> h2 (registers + LDS) |
+// Workgroup = 8 wavefronts, persistent, one per CU.  Row tile = BM samples (64 at H = 128, 128 at H = 64), so
+// that a layer output is 8 MFMA tiles of 32x32, one per wavefront.  The three products against weights (layer 1,
+// layer 2, dz1) take their A operand from the tile in LDS and their B operand straight from the operand-order
+// weight copies in global memory (L2-resident) into registers with 16-byte loads, three k groups in flight: no
+// weight staging buffer and no barrier inside a layer.  Per tile:
+//   X -> LDS | layer 1 -> h1 (LDS) | layer 2 -> h2 (registers + LDS) |
 //   output layer on the ALUs -> loss -> dL/dout | W3 gradient | dz2 = (dL/dout W3^T)(1-h2^2) -> LDS |
-//   dW2 += h1^T dz2 | dz1 = (dz2 W2^T)(1-h1^2) -> LDS (W2 streamed as k-contiguous chunks) | dW1 += X^T dz1
-// The observations and loss inputs of the NEXT tile are fetched into registers at the start of the
-// current one, so their HBM latency is hidden behind a whole tile of arithmetic.
+//   dW2 += h1^T dz2 | dz1 = (dz2 W2^T)(1-h1^2) -> LDS | dW1 += X^T dz1
+// The gather entries of the NEXT tile are fetched at the top of the current one and its observation rows (as the
+// aligned 16-byte chunks that cover each row) after layer 2, so neither dependent load is waited for.  At the end
+// a workgroup stores its partial gradient into a copy of its own; reduce_partials_kernel adds the copies.
 #pragma once
 #include "gemm.h"
 

@@ -188,7 +188,8 @@ static int32_t forward_rows(const marl_config& c, const float* eff, const float*
     const RowSrc X{obs, d.D, nullptr, 1, S};
     if (fused_forward_supported(d.Ha, d.D)) {
       ActorRolloutFinish fin{logits_out, sample ? *sample : SampleArgs{}, sample ? 1 : 0};
-      launch_fused_forward<kActions, false>(d.Ha, fused_args(X, S, d.D, eff, param_map(d), 0), fin, s);
+      const int32_t rc = launch_fused_forward<kActions, false>(d.Ha, fused_args(X, S, d.D, eff, param_map(d), 0), fin, s);
+      if (rc != MARL_OK) return rc;
     } else {
       mlp_hidden_forward(X, S, d.D, d.Ha, eff + o.W1, eff + o.b1, eff + o.W2, eff + o.b2, w.h1a, w.h2a, d.bf16, s);
       launch_actor_head_rollout(w.h2a, S, d.Ha, eff + o.W3, eff + o.b3, logits_out, sample, s);
@@ -200,7 +201,8 @@ static int32_t forward_rows(const marl_config& c, const float* eff, const float*
     const RowSrc X{obs, d.Dc, nullptr, 1, Sc};
     if (fused_forward_supported(d.Hc, d.Dc)) {
       CriticRolloutFinish fin{value_out, d.central ? d.A : 1};
-      launch_fused_forward<1, false>(d.Hc, fused_args(X, Sc, d.Dc, eff, param_map(d), 1), fin, s);
+      const int32_t rc = launch_fused_forward<1, false>(d.Hc, fused_args(X, Sc, d.Dc, eff, param_map(d), 1), fin, s);
+      if (rc != MARL_OK) return rc;
     } else {
       mlp_hidden_forward(X, Sc, d.Dc, d.Hc, eff + o.W1, eff + o.b1, eff + o.W2, eff + o.b2, w.h1c, w.h2c, d.bf16, s);
       launch_critic_head_rollout(w.h2c, Sc, d.Hc, eff + o.W3, eff + o.b3, value_out, d.central ? d.A : 1, s);

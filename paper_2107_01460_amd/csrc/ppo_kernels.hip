@@ -575,7 +575,8 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
             fa.b3 = eff + oa.b3; fa.h1_out = w.h1a; fa.dz2_out = w.h2a; fa.gW3 = w.grad + ga.W3; fa.gb3 = w.grad + ga.b3;
             fa.stats = sck->acc;
             fa.W1s = eff + pm.sw_w1[0]; fa.W2s = eff + pm.sw_w2[0]; fa.kpad1 = pm.kpad1[0]; fa.px = fused_forward_px(d.D);
-            launch_fused_forward<kActions, true>(d.Ha, fa, fn, s);
+            const int32_t rc = launch_fused_forward<kActions, true>(d.Ha, fa, fn, s);
+            if (rc != MARL_OK) return rc;
           } else {
             mlp_hidden_forward(Xa, Sa, d.D, d.Ha, eff + oa.W1, eff + oa.b1, eff + oa.W2, eff + oa.b2, w.h1a, w.h2a, d.bf16, s);
             const unsigned nb = (unsigned)std::min<int64_t>(2048, (Sa + kHeadTile - 1) / kHeadTile);
@@ -617,7 +618,8 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
             fa.b3 = eff + oc.b3; fa.h1_out = w.h1c; fa.dz2_out = w.h2c; fa.gW3 = w.grad + gc.W3; fa.gb3 = w.grad + gc.b3;
             fa.stats = sck->acc;
             fa.W1s = eff + pm.sw_w1[1]; fa.W2s = eff + pm.sw_w2[1]; fa.kpad1 = pm.kpad1[1]; fa.px = fused_forward_px(d.Dc);
-            launch_fused_forward<1, true>(d.Hc, fa, fn, s);
+            const int32_t rc = launch_fused_forward<1, true>(d.Hc, fa, fn, s);
+            if (rc != MARL_OK) return rc;
           } else {
             mlp_hidden_forward(Xc, Sc, d.Dc, d.Hc, eff + oc.W1, eff + oc.b1, eff + oc.W2, eff + oc.b2, w.h1c, w.h2c, d.bf16, s);
             const unsigned nb = (unsigned)std::min<int64_t>(2048, (Sc + kHeadTile - 1) / kHeadTile);

@@ -683,7 +683,7 @@ inline bool wacc_gemm_supported(const RowSrc& A, int M, int N) {
 }
 
 inline int32_t launch_wacc_gemm(const WaccArgs& a, int M, hipStream_t s) {
-  (void)M;
+  if (M != 300) return MARL_E_CONFIG;  // the only instantiated shape; callers ask wacc_gemm_supported first
   return launch_wacc_gemm_inst<300, 2>(a, s);
 }
 

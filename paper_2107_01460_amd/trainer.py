@@ -1,5 +1,5 @@
 """A training run around the library: the loop of Fig. 2 (rollout -> loss -> gradient -> new parameters) with
-evaluation blocks in between (Section 3: training is interleaved with greedy evaluation).
+evaluation blocks in between (Section 2: training is interleaved with evaluation blocks).
 
 Host logic only.  Every step of the path runs in the library's kernels; this class owns the device buffers,
 draws the per-epoch row permutations with torch on the device and calls the entry points in order.  The

@@ -49,7 +49,7 @@ def test_query_sizes_and_parameter_counts(M):
 @pytest.mark.parametrize("field,value", [
     ("grid", 1), ("grid", 65), ("n_agents", 9), ("n_food", 0), ("view", 4), ("actor_hidden", 100),
     ("critic_hidden", 1024), ("n_minibatches", 7), ("precision", 2), ("clip_eps", 0.0), ("gamma", 1.5),
-    ("max_level", 0), ("central_critic", 2), ("lr", 0.0)])
+    ("max_level", 0), ("max_level", 16), ("central_critic", 2), ("lr", 0.0), ("n_minibatches", 0), ("n_epochs", 0)])
 def test_bad_config_rejected(M, field, value):
     cfg = W.scaled(W.CONFIGS[1], **{field: value})
     s = M.binding.Sizes()
@@ -57,6 +57,14 @@ def test_bad_config_rejected(M, field, value):
     assert rc == -3, (field, rc)
     st = M.binding.EnvStateC(*([0x1000] * 8))
     assert M.lib().marl_env_reset(C.byref(M.make_config(cfg)), st, None) == -3
+
+
+def test_zero_minibatches_rejected_for_recurrent_networks(M):
+    """n_minibatches is a divisor in the checks of the recurrent configuration: zero must be an error, not a trap."""
+    s = M.binding.Sizes()
+    for nm in (0, -1):
+        cfg = W.scaled(W.CONFIGS[0], recurrent=1, n_minibatches=nm)
+        assert M.lib().marl_query_sizes(C.byref(M.make_config(cfg)), C.byref(s)) == -3
 
 
 def test_recurrent_sizes(M):
