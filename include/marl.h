@@ -12,7 +12,7 @@
  * Conventions for every entry point
  *   - All array arguments are DEVICE pointers unless a comment says "host".  The library never
  *     allocates, frees or synchronises: every buffer, including workspaces, is owned by the
- *     caller, and sizes come from marl_query_sizes().  Device pointers must be 16-byte aligned
+ *     caller, and sizes come from marl_query_sizes() (marl_rollout_static brings its own fixed scratch instead).  Device pointers must be 16-byte aligned
  *     (256 recommended); a misaligned or null required pointer is rejected before any launch.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls are
  *     asynchronous on that stream and ordered by it.
@@ -190,6 +190,19 @@ int32_t marl_sample_actions(const marl_config* cfg, const float* logits, const f
 int32_t marl_rollout(const marl_config* cfg, marl_env_state st, const float* params, marl_traj traj,
                      uint64_t step_offset, const int32_t* forced_actions, const float* forced_uniforms,
                      void* workspace, void* stream);
+
+/* marl_rollout for callers that cannot allocate or hold a workspace (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): same arguments without `workspace`, same results.  The working copy of the
+ * parameters (and, for networks the fused forward kernel does not cover, one step's hidden activations) lives in a
+ * device array built into the library, MARL_STATIC_SCRATCH_BYTES per GPU for the life of the process.  The call
+ * allocates and frees nothing.  MARL_E_SIZE when marl_query_sizes' rollout_workspace_bytes exceeds that size (the bf16
+ * configuration and unfused wide networks with many environments do), MARL_E_LAUNCH when the array's address cannot
+ * be obtained.  Nothing in the array has to start at zero and nothing in it is kept between calls; every call on a
+ * GPU uses that GPU's one array, so calls that overlap on one GPU (different streams, different host threads) race. */
+#define MARL_STATIC_SCRATCH_BYTES (8 * 1024 * 1024)
+int32_t marl_rollout_static(const marl_config* cfg, marl_env_state st, const float* params, marl_traj traj,
+                            uint64_t step_offset, const int32_t* forced_actions, const float* forced_uniforms,
+                            void* stream);
 
 /* The advantage step between rollout and loss (Fig. 2: the experience is turned into a loss; the paper names PPO,
  * Section 2, without its equations -- these are the standard ones the workload list states).

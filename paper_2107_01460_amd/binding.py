@@ -52,7 +52,7 @@ class RecStateC(C.Structure):
 
 
 EXPORTS = ("marl_query_sizes", "marl_env_reset", "marl_observe", "marl_env_step", "marl_policy_forward",
-           "marl_sample_actions", "marl_rollout", "marl_compute_gae", "marl_ppo_update", "marl_train_step", "marl_evaluate", "marl_rollout_recurrent", "marl_ppo_update_recurrent",
+           "marl_sample_actions", "marl_rollout", "marl_rollout_static", "marl_compute_gae", "marl_ppo_update", "marl_train_step", "marl_evaluate", "marl_rollout_recurrent", "marl_ppo_update_recurrent",
            "marl_timing_enable",
            "marl_timing_read", "marl_status_string")
 
@@ -75,6 +75,7 @@ def lib():
         L.marl_policy_forward.argtypes = [cp, vp, vp, C.c_int64, vp, vp, vp, vp]
         L.marl_sample_actions.argtypes = [cp, vp, vp, vp, C.c_int64, C.c_uint64, vp, vp, vp, vp]
         L.marl_rollout.argtypes = [cp, EnvStateC, vp, TrajC, C.c_uint64, vp, vp, vp, vp]
+        L.marl_rollout_static.argtypes = [cp, EnvStateC, vp, TrajC, C.c_uint64, vp, vp, vp]
         L.marl_compute_gae.argtypes = [cp, TrajC, vp]
         L.marl_ppo_update.argtypes = [cp, TrajC, vp, vp, vp, C.c_int64, vp, vp, vp, vp, vp]
         L.marl_train_step.argtypes = [cp, EnvStateC, vp, TrajC, vp, vp, vp, vp, vp, vp, vp, vp]
@@ -215,6 +216,12 @@ def sample_actions(cfg, logits, uniforms, forced, n, step, action, sampled, logp
 def rollout(cfg, state, params, traj, step_offset, workspace, forced_actions=None, forced_uniforms=None, stream=None):
     _check(lib().marl_rollout(C.byref(make_config(cfg)), state.c(), _ptr(params), traj.c(), int(step_offset),
                               _ptr(forced_actions), _ptr(forced_uniforms), _ptr(workspace), _stream(stream)))
+
+
+def rollout_static(cfg, state, params, traj, step_offset, forced_actions=None, forced_uniforms=None, stream=None):
+    """marl_rollout on the library's built-in scratch: no workspace argument, no allocation inside the call."""
+    _check(lib().marl_rollout_static(C.byref(make_config(cfg)), state.c(), _ptr(params), traj.c(), int(step_offset),
+                                     _ptr(forced_actions), _ptr(forced_uniforms), _stream(stream)))
 
 
 def compute_gae(cfg, traj, stream=None):

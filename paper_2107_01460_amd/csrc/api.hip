@@ -1,4 +1,5 @@
 // C ABI entry points: argument validation on the host, then the launchers.
+#include <mutex>
 #include <vector>
 
 #include "common.h"
@@ -25,6 +26,32 @@ TimerState g_timer;
 }  // namespace
 
 bool timing_on() { return g_timer.on; }
+
+// ---- scratch of the entry point that allocates nothing ------------------------------------------------------------
+// Device memory that is part of the loaded code object: every GPU the library runs on holds its own copy, at its own
+// address, until the process ends.  In host code the array's name is only a handle for hipGetSymbolAddress; the
+// kernels are given the address that call returns.
+constexpr int64_t kStaticScratchBytes = MARL_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};  // per device, filled on the first call made with that device current
+
+// Address of the current device's copy of `scratch` (nullptr on error).
+void* static_scratch() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    g_scratch_ptr[dev] = p;
+  }
+  return g_scratch_ptr[dev];
+}
+}  // namespace
 
 TimedLaunch::TimedLaunch(int c, double work, hipStream_t st) : cls(c), s(st), active(g_timer.on) {
   if (!active) return;
@@ -190,6 +217,22 @@ int32_t marl_rollout(const marl_config* cfg, marl_env_state st, const float* par
                         (hipStream_t)stream);
 }
 
+int32_t marl_rollout_static(const marl_config* cfg, marl_env_state st, const float* params, marl_traj traj,
+                            uint64_t step_offset, const int32_t* forced_actions, const float* forced_uniforms,
+                            void* stream) {
+  int32_t rc = validate_config(cfg);
+  if (rc != MARL_OK) return rc;
+  if (cfg->recurrent) return MARL_E_CONFIG;
+  if ((rc = check_state(st)) != MARL_OK) return rc;
+  if ((rc = check_traj(traj, false)) != MARL_OK) return rc;
+  MARL_REQUIRE_PTR(params);
+  MARL_OPTIONAL_PTR(forced_actions); MARL_OPTIONAL_PTR(forced_uniforms);
+  if (rollout_workspace_bytes(*cfg, cfg->n_envs) > kStaticScratchBytes) return MARL_E_SIZE;
+  void* ws = static_scratch();
+  if (ws == nullptr) return MARL_E_LAUNCH;
+  return launch_rollout(*cfg, st, params, traj, step_offset, forced_actions, forced_uniforms, ws, (hipStream_t)stream);
+}
+
 int32_t marl_compute_gae(const marl_config* cfg, marl_traj traj, void* stream) {
   int32_t rc = validate_config(cfg);
   if (rc != MARL_OK) return rc;
@@ -315,7 +358,7 @@ const char* marl_status_string(int32_t status) {
     case MARL_E_ALIGN: return "a device pointer is not 16-byte aligned";
     case MARL_E_CONFIG: return "unsupported or inconsistent configuration";
     case MARL_E_LAUNCH: return "the HIP runtime reported a launch error";
-    case MARL_E_SIZE: return "a size argument is out of range";
+    case MARL_E_SIZE: return "a size argument is out of range, or the configuration needs more than the built-in scratch";
     default: return "unknown status";
   }
 }

@@ -94,10 +94,15 @@ RolloutWsView carve_rollout_ws(const marl_config& c, int64_t n_rows, void* ws, i
   RolloutWsView v{};
   v.eff_params = (float*)take(effective_param_floats(c) * 4);
   if (!d.bf16) {
-    v.h1a = (float*)take(S * d.Ha * 4);
-    v.h2a = (float*)take(S * d.Ha * 4);
-    v.h1c = (float*)take(Sc * d.Hc * 4);
-    v.h2c = (float*)take(Sc * d.Hc * 4);
+    // hidden activations of one pass: only the layer-by-layer path stores them (the fused kernel keeps them on chip)
+    if (!fused_forward_supported(d.Ha, d.D)) {
+      v.h1a = (float*)take(S * d.Ha * 4);
+      v.h2a = (float*)take(S * d.Ha * 4);
+    }
+    if (!fused_forward_supported(d.Hc, d.Dc)) {
+      v.h1c = (float*)take(Sc * d.Hc * 4);
+      v.h2c = (float*)take(Sc * d.Hc * 4);
+    }
   } else {
     v.xba = (bf16_t*)take(S * round_up64(d.D) * 2);
     v.bh1a = (bf16_t*)take(S * d.Ha * 2);
