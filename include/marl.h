@@ -278,8 +278,9 @@ int32_t marl_evaluate(const marl_config* cfg, marl_env_state st, const float* pa
  * the instrumented kernel classes is bracketed by two HIP events recorded on the launch's own stream.
  * Classes: 0 forward GEMM (activations x weights), 1 backward-data GEMM (gradient x weights^T),
  * 2 weight-gradient GEMM (activations^T x gradient, split over samples), 3 env step / observe, 4 GAE,
- * 5 whole-network training kernel of the small networks (forward + backward flops).  Fused forward kernels
- * are booked under class 0 with the flops of their two hidden layers.
+ * 5 whole-network training kernel of the small networks (forward + backward flops), 6 the fused rollout kernel
+ * (all T steps of actor inference, sampling and environment transition in one launch; booked with the flops of the
+ * actor's two hidden layers).  Fused forward kernels are booked under class 0 with the flops of their two hidden layers.
  * marl_timing_enable(1) clears earlier records; marl_timing_read waits for the class's events and
  * returns the summed kernel time, the number of launches and the summed algorithmic work (flops for the
  * GEMMs: 2*M*N*K of the unpadded problem; bytes for env step and GAE).  Errors: MARL_E_NULL, MARL_E_SIZE,

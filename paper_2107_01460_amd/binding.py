@@ -290,7 +290,7 @@ def train_step(cfg, state, params, traj, adam_m, adam_v, counters, perm, stats, 
                                  _ptr(update_workspace), _stream(stream)))
 
 
-KERNEL_CLASSES = {"gemm_nn": 0, "gemm_nt": 1, "gemm_tn": 2, "env_step": 3, "gae": 4, "fused_train": 5}
+KERNEL_CLASSES = {"gemm_nn": 0, "gemm_nt": 1, "gemm_tn": 2, "env_step": 3, "gae": 4, "fused_train": 5, "rollout": 6}
 
 
 def timing_enable(on):

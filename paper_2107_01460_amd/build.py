@@ -9,7 +9,7 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libmarl_gfx950.so")
 SOURCES = ["api.hip", "env_kernels.hip", "gae_kernels.hip", "policy_kernels.hip", "ppo_kernels.hip",
-           "recurrent_kernels.hip"]
+           "recurrent_kernels.hip", "rollout_v3.hip", "rollout_v5.hip", "rollout_v7.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", INCLUDE, "-I", CSRC,
          # packed fp32 ALU forms are kept off on this target
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -23,7 +23,7 @@ def _compile(src):
 
 
 def build(verbose=True):
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=min(os.cpu_count() or 8, len(SOURCES))) as ex:
         objs = list(ex.map(_compile, SOURCES))
     subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
     if verbose:

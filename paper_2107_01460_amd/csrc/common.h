@@ -168,7 +168,7 @@ __device__ __forceinline__ float load_act(const float* p, int64_t i) { return p[
 __device__ __forceinline__ float load_act(const bf16_t* p, int64_t i) { return from_bf16(p[i]); }
 
 // ---- optional per-kernel timing with HIP events (measurement hook, host side) -----------------
-enum KernelClass { KC_GEMM_NN = 0, KC_GEMM_NT = 1, KC_GEMM_TN = 2, KC_ENV_STEP = 3, KC_GAE = 4, KC_FUSED_TRAIN = 5, KC_COUNT = 6 };
+enum KernelClass { KC_GEMM_NN = 0, KC_GEMM_NT = 1, KC_GEMM_TN = 2, KC_ENV_STEP = 3, KC_GAE = 4, KC_FUSED_TRAIN = 5, KC_ROLLOUT = 6, KC_COUNT = 7 };
 bool timing_on();
 // Records an event on `s` before and after the launch bracketed by the guard's lifetime and books
 // `work` (flops or bytes) to the class.

@@ -61,7 +61,7 @@ __device__ __forceinline__ void reset_regs(uint32_t ag[CA], uint32_t fd[CF], con
       const uint32_t cell = row | (col << 8);
 #pragma unroll
       for (int a = 0; a < CA; ++a)
-        if (k == a) ag[a] = cell | ((uint32_t)lvl[a] << 16);
+        if (k == a && a < p.A) ag[a] = cell | ((uint32_t)lvl[a] << 16);  // slots past A keep their off-grid marker
 #pragma unroll
       for (int f = 0; f < CF; ++f)
         if (k == p.A + f) fd[f] = cell;
@@ -289,7 +289,7 @@ __device__ __forceinline__ void wh_reset_regs(uint32_t ag[CA], uint32_t fd[CF], 
       const uint32_t cell = row | (col << 8);
 #pragma unroll
       for (int a = 0; a < CA; ++a)
-        if (k == a) ag[a] = cell;  // nothing carried
+        if (k == a && a < p.A) ag[a] = cell;  // nothing carried; slots past A keep their off-grid marker
 #pragma unroll
       for (int f = 0; f < CF; ++f)
         if (k == p.A + f) fd[f] = cell | (1u << 16);  // idle

@@ -108,7 +108,8 @@ __device__ __forceinline__ float log_softmax_at(const float lg[kActions], int a)
   return la - m - logf(se);
 }
 
-__device__ __forceinline__ void sample_and_store(const float lg[kActions], int64_t s, const SampleArgs& a) {
+// Returns the action taken (the forced one if given).
+__device__ __forceinline__ int sample_and_store(const float lg[kActions], int64_t s, const SampleArgs& a) {
   float u[kActions];
   if (a.uniforms) {
 #pragma unroll
@@ -121,6 +122,7 @@ __device__ __forceinline__ void sample_and_store(const float lg[kActions], int64
   if (a.forced) act = a.forced[s];
   a.action[s] = act;
   a.logp[s] = log_softmax_at(lg, act);
+  return act;
 }
 
 namespace heads_detail {

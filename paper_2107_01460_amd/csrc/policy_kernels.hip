@@ -7,6 +7,7 @@
 #include "fused_forward.h"
 #include "gemm.h"
 #include "heads.h"
+#include "rollout_fused.h"
 
 namespace marl {
 
@@ -55,11 +56,16 @@ struct ActorRolloutFinish {
     if (do_sample) sample_and_store(out, s, sa);
   }
 };
+// Rows below `split` go to value_out, the rest (the rows of the post-rollout observation, when one pass covers all
+// T + 1 slabs) to tail_out.
 struct CriticRolloutFinish {
   float* value_out;
   int broadcast;
+  int64_t split;
+  float* tail_out;
   __device__ __forceinline__ void operator()(int64_t s, const float out[1], float*, float*) const {
-    for (int k = 0; k < broadcast; ++k) value_out[s * broadcast + k] = out[0];
+    float* const dst = s < split ? value_out + s * broadcast : tail_out + (s - split) * broadcast;
+    for (int k = 0; k < broadcast; ++k) dst[k] = out[0];
   }
 };
 
@@ -163,9 +169,10 @@ int64_t rollout_workspace_bytes(const marl_config& c, int64_t n_rows) {
 }
 
 // One forward pass over n_rows observation rows.  Any of logits / value / sampling outputs may be absent.
+// value_tail (nullable): the values of rows value_split .. n_rows go there instead (fused critic kernel only).
 static int32_t forward_rows(const marl_config& c, const float* eff, const float* obs, int64_t n_rows,
                             const RolloutWsView& w, bool want_actor, float* logits_out, const SampleArgs* sample,
-                            float* value_out, hipStream_t s) {
+                            float* value_out, hipStream_t s, int64_t value_split = -1, float* value_tail = nullptr) {
   const Dims d = dims_of(c);
   const int64_t S = n_rows * d.A;
   if (d.bf16) {
@@ -205,7 +212,7 @@ static int32_t forward_rows(const marl_config& c, const float* eff, const float*
     const int64_t Sc = d.central ? n_rows : S;
     const RowSrc X{obs, d.Dc, nullptr, 1, Sc};
     if (fused_forward_supported(d.Hc, d.Dc)) {
-      CriticRolloutFinish fin{value_out, d.central ? d.A : 1};
+      CriticRolloutFinish fin{value_out, d.central ? d.A : 1, value_tail ? value_split : Sc, value_tail};
       const int32_t rc = launch_fused_forward<1, false>(d.Hc, fused_args(X, Sc, d.Dc, eff, param_map(d), 1), fin, s);
       if (rc != MARL_OK) return rc;
     } else {
@@ -232,6 +239,34 @@ int32_t launch_sample(const marl_config& c, const float* logits, const float* un
   return launch_status();
 }
 
+static int32_t launch_rollout_fused(const marl_config& c, bool eval, const RolloutFusedArgs& a, hipStream_t s) {
+  switch (c.view) {
+    case 3: return launch_rollout_fused_v3(c.actor_hidden, eval, a, s);
+    case 5: return launch_rollout_fused_v5(c.actor_hidden, eval, a, s);
+    case 7: return launch_rollout_fused_v7(c.actor_hidden, eval, a, s);
+    default: return MARL_E_CONFIG;
+  }
+}
+
+// The actor's part of the arguments of the fused rollout kernel.
+static RolloutFusedArgs rollout_fused_args(const marl_config& c, marl_env_state st, const float* eff) {
+  const Dims d = dims_of(c);
+  const ParamMap pm = param_map(d);
+  const NetOffsets o = padded_offsets(pm, 0);
+  RolloutFusedArgs a{};
+  a.p = env_params(c);
+  a.st = st;
+  a.W1s = eff + pm.sw_w1[0]; a.W2s = eff + pm.sw_w2[0]; a.b1 = eff + o.b1; a.b2 = eff + o.b2; a.W3 = eff + o.W3; a.b3 = eff + o.b3;
+  a.kpad1 = pm.kpad1[0];
+  a.px = fused_forward_px(d.D);
+  return a;
+}
+
+static bool use_fused_rollout(const marl_config& c) {
+  const Dims d = dims_of(c);
+  return !d.bf16 && rollout_fused_supported(d.Ha, d.A) && fused_forward_supported(d.Ha, d.D);
+}
+
 int32_t launch_rollout(const marl_config& c, marl_env_state st, const float* params, marl_traj tr,
                        uint64_t step_offset, const int32_t* forced_actions, const float* forced_uniforms,
                        void* workspace, hipStream_t s, const uint64_t* step_base) {
@@ -239,34 +274,55 @@ int32_t launch_rollout(const marl_config& c, marl_env_state st, const float* par
   const RolloutWsView w = carve_rollout_ws(c, d.N, workspace, nullptr);
   const float* eff = effective_params(c, params, w.eff_params, s);
   const int64_t NA = d.NA, slab = NA * d.D;
-  int32_t rc = launch_env_step(c, st, nullptr, tr.obs, nullptr, nullptr, /*do_step=*/false, s);
-  if (rc != MARL_OK) return rc;
+  int32_t rc;
   // The values do not steer the rollout (the parameters are constant during it): where the critic's forward pass
-  // needs no per-row workspace (the fused fp32 kernel), all T steps' values are computed in one pass over the stored
-  // observations afterwards instead of one small launch per step.
+  // needs no per-row workspace (the fused fp32 kernel), the values of all T steps and of the post-rollout observation
+  // are computed in one pass over the stored observations afterwards instead of one small launch per step.
   const bool batch_values = !d.bf16 && fused_forward_supported(d.Hc, d.Dc);
-  for (int t = 0; t < d.T; ++t) {
-    SampleArgs a{};
-    a.uniforms = forced_uniforms ? forced_uniforms + (int64_t)t * NA * kActions : nullptr;
-    a.forced = forced_actions ? forced_actions + (int64_t)t * NA : nullptr;
-    a.action = tr.action + (int64_t)t * NA;
-    a.sampled = tr.sampled ? tr.sampled + (int64_t)t * NA : nullptr;
-    a.logp = tr.logp + (int64_t)t * NA;
-    a.step = step_offset + (uint64_t)t;
-    a.step_base = step_base;
-    a.k0 = (uint32_t)(c.seed & 0xffffffffu);
-    a.k1 = (uint32_t)(c.seed >> 32);
-    rc = forward_rows(c, eff, tr.obs + (int64_t)t * slab, d.N, w, true,
-                      tr.logits ? tr.logits + (int64_t)t * NA * kActions : nullptr, &a,
-                      batch_values ? nullptr : tr.value + (int64_t)t * NA, s);
+  if (use_fused_rollout(c)) {
+    // all T steps in one launch: a workgroup keeps its environments on chip and streams the trajectory out
+    RolloutFusedArgs a = rollout_fused_args(c, st, eff);
+    a.T = d.T;
+    a.obs = tr.obs; a.action = tr.action; a.logp = tr.logp; a.reward = tr.reward; a.done = tr.done;
+    a.logits = tr.logits; a.sampled = tr.sampled; a.uniforms = forced_uniforms; a.forced = forced_actions;
+    a.step0 = step_offset; a.step_base = step_base;
+    {
+      // booked with the algorithmic flops of the actor's two hidden layers over all T steps
+      const double flops = 2.0 * (double)d.T * NA * ((double)d.D * d.Ha + (double)d.Ha * d.Ha);
+      TimedLaunch timed(KC_ROLLOUT, flops, s);
+      if ((rc = launch_rollout_fused(c, false, a, s)) != MARL_OK) return rc;
+    }
+    if (!batch_values) {
+      for (int t = 0; t < d.T; ++t)
+        if ((rc = forward_rows(c, eff, tr.obs + (int64_t)t * slab, d.N, w, false, nullptr, nullptr, tr.value + (int64_t)t * NA, s)) != MARL_OK)
+          return rc;
+    }
+  } else {
+    rc = launch_env_step(c, st, nullptr, tr.obs, nullptr, nullptr, /*do_step=*/false, s);
     if (rc != MARL_OK) return rc;
-    rc = launch_env_step(c, st, a.action, tr.obs + (int64_t)(t + 1) * slab, tr.reward + (int64_t)t * NA,
-                         tr.done + (int64_t)t * d.N, true, s);
-    if (rc != MARL_OK) return rc;
+    for (int t = 0; t < d.T; ++t) {
+      SampleArgs a{};
+      a.uniforms = forced_uniforms ? forced_uniforms + (int64_t)t * NA * kActions : nullptr;
+      a.forced = forced_actions ? forced_actions + (int64_t)t * NA : nullptr;
+      a.action = tr.action + (int64_t)t * NA;
+      a.sampled = tr.sampled ? tr.sampled + (int64_t)t * NA : nullptr;
+      a.logp = tr.logp + (int64_t)t * NA;
+      a.step = step_offset + (uint64_t)t;
+      a.step_base = step_base;
+      a.k0 = (uint32_t)(c.seed & 0xffffffffu);
+      a.k1 = (uint32_t)(c.seed >> 32);
+      rc = forward_rows(c, eff, tr.obs + (int64_t)t * slab, d.N, w, true,
+                        tr.logits ? tr.logits + (int64_t)t * NA * kActions : nullptr, &a,
+                        batch_values ? nullptr : tr.value + (int64_t)t * NA, s);
+      if (rc != MARL_OK) return rc;
+      rc = launch_env_step(c, st, a.action, tr.obs + (int64_t)(t + 1) * slab, tr.reward + (int64_t)t * NA,
+                           tr.done + (int64_t)t * d.N, true, s);
+      if (rc != MARL_OK) return rc;
+    }
   }
-  if (batch_values) {
-    rc = forward_rows(c, eff, tr.obs, (int64_t)d.T * d.N, w, false, nullptr, nullptr, tr.value, s);
-    if (rc != MARL_OK) return rc;
+  if (batch_values) {  // slabs 0 .. T in one launch: rows of slab T go to last_value
+    const int64_t Sc_split = (int64_t)d.T * (d.central ? d.N : NA);
+    return forward_rows(c, eff, tr.obs, (int64_t)(d.T + 1) * d.N, w, false, nullptr, nullptr, tr.value, s, Sc_split, tr.last_value);
   }
   return forward_rows(c, eff, tr.obs + (int64_t)d.T * slab, d.N, w, false, nullptr, nullptr, tr.last_value, s);
 }
@@ -357,11 +413,18 @@ int32_t launch_evaluate(const marl_config& c, marl_env_state st, const float* pa
   const EvalWsView e = carve_eval_ws(c, workspace, nullptr);
   const RolloutWsView w = carve_rollout_ws(c, d.N, e.rollout_ws, nullptr);
   const float* eff = effective_params(c, params, w.eff_params, s);
+  const int64_t steps = (int64_t)n_episodes * c.episode_cap;
+  if (use_fused_rollout(c)) {  // the whole block in one launch, statistics in registers
+    RolloutFusedArgs a = rollout_fused_args(c, st, eff);
+    a.T = (int)steps;
+    a.ev = out;
+    a.n_episodes = n_episodes;
+    return launch_rollout_fused(c, true, a, s);
+  }
   const unsigned nb_env = (unsigned)((d.N + 255) / 256), nb_s = (unsigned)((d.NA + 255) / 256);
   hipLaunchKernelGGL(eval_zero_kernel, dim3(nb_env), dim3(256), 0, s, out, d.N);
   int32_t rc = launch_env_step(c, st, nullptr, e.obs, nullptr, nullptr, /*do_step=*/false, s);
   if (rc != MARL_OK) return rc;
-  const int64_t steps = (int64_t)n_episodes * c.episode_cap;
   for (int64_t t = 0; t < steps; ++t) {
     rc = forward_rows(c, eff, e.obs, d.N, w, true, e.logits, nullptr, nullptr, s);
     if (rc != MARL_OK) return rc;

@@ -172,6 +172,39 @@ def test_rollout_teacher_forced(M, orc, k):
     assert otr.done.sum() > 0
 
 
+@pytest.mark.parametrize("k,kind,agents,food", [(2, 0, 3, 3), (2, 0, 3, 1), (5, 0, 1, 2), (2, 1, 3, 4), (4, 0, 5, 6), (3, 2, 2, 3)])
+def test_long_rollout_through_many_resets(M, orc, k, kind, agents, food):
+    """Many episodes per environment inside ONE rollout (the state of an environment stays on chip for the whole
+    rollout), with agent and food counts below the unrolled capacities: the oracle, forced with the GPU's own actions,
+    must reproduce every observation, reward, done flag and the final state bit for bit."""
+    cfg = small(k, n_envs=53, rollout_len=96, n_minibatches=1, episode_cap=7, n_agents=agents, n_food=food,
+                env_kind=kind, precision=0)
+    if kind:
+        cfg = W.scaled(cfg, max_level=min(cfg["max_level"], food))
+    if cfg["actor_hidden"] > 256:
+        cfg = W.scaled(cfg, actor_hidden=128, critic_hidden=128)
+    print("case", cfg["name"], "kind", kind, "A", agents, "F", food, flush=True)
+    params = W.init_params(cfg, bias_scale=0.1)
+    gs = M.EnvState(cfg)
+    M.env_reset(cfg, gs)
+    gtr = M.Traj(cfg, debug=True)
+    ws = M.alloc_workspace(M.query_sizes(cfg).rollout_workspace_bytes)
+    M.rollout(cfg, gs, dev(params), gtr, 31, ws)
+    torch.cuda.synchronize()
+    os_ = orc.EnvState(cfg)
+    orc.env_reset(cfg, os_)
+    otr = orc.Traj(cfg)
+    orc.rollout(cfg, os_, params, otr, step_offset=31, forced_actions=gtr.action.cpu().numpy())
+    assert np.array_equal(gtr.obs.cpu().numpy(), otr.obs)
+    assert np.array_equal(gtr.reward.cpu().numpy().view(np.uint32), otr.reward.view(np.uint32))
+    assert np.array_equal(gtr.done.cpu().numpy(), otr.done)
+    assert_state_equal(M, gs, os_)
+    assert otr.done.sum() >= 10 * cfg["n_envs"]
+    assert err(gtr.logits.cpu().numpy(), otr.logits, cfg) < REL_TOL[0]
+    assert err(gtr.value.cpu().numpy(), otr.value, cfg) < REL_TOL[0]
+    assert err(gtr.last_value.cpu().numpy(), otr.last_value, cfg) < REL_TOL[0]
+
+
 @pytest.mark.parametrize("k", [1, 3, 5])
 def test_gae(M, orc, k):
     cfg = small(k, n_envs=300, rollout_len=37, n_minibatches=1)
