@@ -414,52 +414,82 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
     PHASE_MARK(13);
   }
 
-  // ---- flush the register-resident gradients
-  {
-    const int t0 = (wave * DW2_TPW) % (NTN * NTN);
-    const int it = t0 / NTN, jt = t0 % NTN;
+  // ---- flush the register-resident gradients.  Into the workgroup's own zeroed copy (a.partial): a tile with one
+  // owner leaves with plain stores; where several wavefronts (or threads) hold parts of one sum they add them in a
+  // FIXED order, one contributor per round with a barrier between rounds, so that the copy -- and, with the
+  // fixed-order reduction of the copies, the gradient -- comes out the same bits in every run.  Without a copy the
+  // parts meet in atomics on the gradient itself.
+  const bool own = a.partial != nullptr;
+  constexpr int ROUNDS = 8;
+  static_assert(DW2_KS <= ROUNDS && HPARTS <= ROUNDS && MTF <= ROUNDS && NW <= ROUNDS, "every contributor has a round");
+#pragma unroll 1
+  for (int round = 0; round < (own ? ROUNDS : 1); ++round) {
+    {
+      const int t0 = (wave * DW2_TPW) % (NTN * NTN);
+      const int it = t0 / NTN, jt = t0 % NTN;
+      const int rank = DW2_KS == 1 ? 0 : (wave * DW2_TPW) / (NTN * NTN);
+      if (!own || rank == round) {
 #pragma unroll
-    for (int q = 0; q < DW2_TPW; ++q)
+        for (int q = 0; q < DW2_TPW; ++q)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int i = it * 32 + 8 * (r / 4) + 4 * hi + (r % 4), j = (jt + q) * 32 + lo;
-        // a tile with one owner goes into the workgroup's own (zeroed) copy with a plain store: a quarter of a
-        // million atomics per workgroup is what the flush otherwise costs, 25 us per launch
-        if (DW2_KS == 1 && a.partial != nullptr) gW2[i * H + j] = acc2[q][r];
-        else atomicAdd(&gW2[i * H + j], acc2[q][r]);
+          for (int r = 0; r < 16; ++r) {
+            const int i = it * 32 + 8 * (r / 4) + 4 * hi + (r % 4), j = (jt + q) * 32 + lo;
+            if (!own) atomicAdd(&gW2[i * H + j], acc2[q][r]);
+            else if (DW2_KS == 1) gW2[i * H + j] = acc2[q][r];
+            else gW2[i * H + j] += acc2[q][r];
+          }
       }
-  }
+    }
 #pragma unroll
-  for (int q = 0; q < Q1; ++q) {
-    int t, kb0, klen;
-    if (dw1_item(q, t, kb0, klen)) {
-      const int dt = t / NTN, jt = t % NTN;
+    for (int q = 0; q < Q1; ++q) {
+      int t, kb0, klen;
+      if (dw1_item(q, t, kb0, klen)) {
+        const int dt = t / NTN, jt = t % NTN;
+        const int rank = kb0 / klen;  // which share of the row tile's samples this item summed
+        if (!own || rank == round) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int d = dt * 32 + 8 * (r / 4) + 4 * hi + (r % 4), j = jt * 32 + lo;
-        if (d < a.Din) {
-          if (balanced1 && q == 0 && a.partial != nullptr) gW1[d * H + j] = acc1[q][r];  // a whole tile of this wavefront's own
-          else atomicAdd(&gW1[d * H + j], acc1[q][r]);
+          for (int r = 0; r < 16; ++r) {
+            const int d = dt * 32 + 8 * (r / 4) + 4 * hi + (r % 4), j = jt * 32 + lo;
+            if (d < a.Din) {
+              if (!own) atomicAdd(&gW1[d * H + j], acc1[q][r]);
+              else if (klen == BM) gW1[d * H + j] = acc1[q][r];  // a whole tile of this wavefront's own
+              else gW1[d * H + j] += acc1[q][r];
+            }
+          }
         }
       }
     }
-  }
-  if (hi == 0) {
-    atomicAdd(&gb1[nt * 32 + lo], gb1r);
-    atomicAdd(&gb2[nt * 32 + lo], gb2r);
-  }
-  {
-    const int i = tid % H;
-#pragma unroll
-    for (int k = 0; k < NOUT; ++k) atomicAdd(&gW3[i * NOUT + k], gw[k]);
-  }
-  if (tid < (BM < 64 ? 64 : BM)) {  // whole wavefronts; lanes past BM hold zeros
-#pragma unroll
-    for (int k = 0; k < NOUT; ++k) {
-      float v = accS[tid * AS + k];
-      for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-      if (lane == 0) atomicAdd(&gb3[k], v);
+    if (hi == 0 && (!own || mt == round)) {
+      if (!own) {
+        atomicAdd(&gb1[nt * 32 + lo], gb1r);
+        atomicAdd(&gb2[nt * 32 + lo], gb2r);
+      } else {
+        gb1[nt * 32 + lo] += gb1r;
+        gb2[nt * 32 + lo] += gb2r;
+      }
     }
+    if (!own || tid / H == round) {
+      const int i = tid % H;
+#pragma unroll
+      for (int k = 0; k < NOUT; ++k) {
+        if (!own) atomicAdd(&gW3[i * NOUT + k], gw[k]);
+        else gW3[i * NOUT + k] += gw[k];
+      }
+    }
+    if (tid < (BM < 64 ? 64 : BM) && (!own || wave == round)) {  // whole wavefronts; lanes past BM hold zeros
+#pragma unroll
+      for (int k = 0; k < NOUT; ++k) {
+        float v = accS[tid * AS + k];
+        for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+        if (lane == 0) {
+          if (!own) atomicAdd(&gb3[k], v);
+          else gb3[k] += v;
+        }
+      }
+    }
+    if (own) __syncthreads();  // the next contributor sees this round's sums
+  }
+  if (tid < (BM < 64 ? 64 : BM)) {  // loss statistics: reported only, summed over the workgroups with atomics
 #pragma unroll
     for (int k = 0; k < 5; ++k) {
       float v = accS[tid * AS + NOUT + k];

@@ -67,27 +67,24 @@ struct GemmArgs {
 // keeps its atomics: its workgroups finish spread over time, and the two-stage form measured no faster (324 against
 // 315 us).
 
-// out[i] += sum_b partial[b * count + i].  blockIdx.y takes 32 of the nblocks copies, so that a short range (a few
-// thousand floats) still has enough loads in flight; the up to nblocks / 32 sums per element meet in atomics.
+// out[i] += sum_b partial[b * count + i], the copies added in a fixed order (eight interleaved running sums, then a
+// fixed tree), so that the result does not depend on the run.  One thread per element reads all nblocks copies:
+// consecutive threads read consecutive floats of a copy, and the independent sums keep eight loads in flight.
 static __global__ void __launch_bounds__(256) reduce_partials_kernel(const float* __restrict__ partial, int nblocks, int64_t count,
                                                                      float* __restrict__ out) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= count) return;
-  const int b0 = blockIdx.y * 32, b1 = min(nblocks, b0 + 32);
-  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-  int b = b0;
-  for (; b + 4 <= b1; b += 4) {
-    s0 += partial[(int64_t)b * count + i];
-    s1 += partial[(int64_t)(b + 1) * count + i];
-    s2 += partial[(int64_t)(b + 2) * count + i];
-    s3 += partial[(int64_t)(b + 3) * count + i];
+  float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  int b = 0;
+  for (; b + 8 <= nblocks; b += 8) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s[u] += partial[(int64_t)(b + u) * count + i];
   }
-  for (; b < b1; ++b) s0 += partial[(int64_t)b * count + i];
-  atomicAdd(&out[i], (s0 + s1) + (s2 + s3));
+  for (; b < nblocks; ++b) s[0] += partial[(int64_t)b * count + i];
+  out[i] += ((s[0] + s[1]) + (s[2] + s[3])) + ((s[4] + s[5]) + (s[6] + s[7]));
 }
 inline void launch_reduce_partials(const float* partial, int nblocks, int64_t count, float* out, hipStream_t s) {
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((count + 255) / 256), (unsigned)((nblocks + 31) / 32)), dim3(256), 0, s,
-                     partial, nblocks, count, out);
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s, partial, nblocks, count, out);
 }
 
 // tanh(x) = 1 - 2 / (e^{2x} + 1) with the hardware exp2 and reciprocal: absolute error ~1e-7 (the values feed

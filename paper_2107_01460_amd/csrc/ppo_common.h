@@ -2,6 +2,7 @@
 // the actor and critic loss functors (loss terms and dL/d(output) of one sample), the output-layer + loss
 // kernel of the layer-wise paths, advantage statistics, gradient-norm and Adam kernels.
 #pragma once
+#include <algorithm>
 #include <cmath>
 
 #include "gemm.h"
@@ -10,10 +11,13 @@
 namespace marl {
 namespace {
 
+constexpr int kNormBlocks = 64;
+
 // Device scalars of one minibatch step.
 struct Scalars {
   double adv_sum, adv_sq;  // sum of the minibatch's advantages, sum of their squares
-  float acc[8];            // 0 policy loss, 1 value loss, 2 entropy, 3 approx KL, 4 clip fraction, 5 |grad|^2
+  float acc[8];            // 0 policy loss, 1 value loss, 2 entropy, 3 approx KL, 4 clip fraction
+  double norm_part[kNormBlocks];  // |grad|^2 summed per workgroup of grad_norm_kernel; adam_kernel adds them in order
 };
 
 struct LossCommon {
@@ -336,6 +340,8 @@ __global__ void __launch_bounds__(256) loss_head_kernel(const HT* __restrict__ H
   }
 }
 
+// Squared gradient norm in two fixed-order stages (no atomics, so the clipping factor is the same bits in every run):
+// workgroup b of at most kNormBlocks sums its grid-stride share in fp64 and stores it; adam_kernel adds the shares.
 __global__ void __launch_bounds__(256) grad_norm_kernel(const float* __restrict__ grad, int64_t P, Scalars* sc) {
   __shared__ double red[4];
   double part = 0;
@@ -344,11 +350,13 @@ __global__ void __launch_bounds__(256) grad_norm_kernel(const float* __restrict_
     part += g * g;
   }
   const double t = block_sum_f64(part, red);
-  if (threadIdx.x == 0) atomicAdd(&sc->acc[5], (float)t);
+  if (threadIdx.x == 0) sc->norm_part[blockIdx.x] = t;
 }
+inline unsigned grad_norm_blocks(int64_t P) { return (unsigned)std::min<int64_t>(kNormBlocks, (P + 255) / 256); }
 
 struct AdamArgs {
   float lr, b1, b2, eps, bc1, bc2, max_norm, ent_coef, vf_coef;
+  int norm_blocks;        // workgroups grad_norm_kernel ran with
   const int64_t* k_base;  // nullable: device-resident count of optimiser steps taken before this call; then the bias
   int k_local;            // corrections are computed on the device for step *k_base + k_local instead of bc1 / bc2
 };
@@ -360,7 +368,9 @@ __global__ void __launch_bounds__(256) adam_kernel(float* __restrict__ params, f
                                                    AdamArgs a, const Scalars* sc, float* __restrict__ stats_row,
                                                    float* __restrict__ grad_dump, Scalars* sc_next) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const float norm = sqrtf(sc->acc[5]);
+  double norm2 = 0.0;
+  for (int b = 0; b < a.norm_blocks; ++b) norm2 += sc->norm_part[b];
+  const float norm = sqrtf((float)norm2);
   const float scale = a.max_norm > 0.f ? a.max_norm / fmaxf(norm, a.max_norm) : 1.0f;
   if (a.k_base != nullptr) {
     const double k = (double)(*a.k_base + a.k_local);

@@ -631,10 +631,11 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
         }
       }
       // ---- clip + Adam
-      hipLaunchKernelGGL(grad_norm_kernel, dim3((unsigned)std::min<int64_t>(256, (d.P + 255) / 256)), dim3(256), 0, s,
+      hipLaunchKernelGGL(grad_norm_kernel, dim3(grad_norm_blocks(d.P)), dim3(256), 0, s,
                          w.grad, d.P, sck);
       ++k;
       AdamArgs a{};
+      a.norm_blocks = (int)grad_norm_blocks(d.P);
       a.k_base = adam_step_base;
       a.k_local = (int)k;
       a.lr = c.lr; a.b1 = c.beta1; a.b2 = c.beta2; a.eps = c.adam_eps;

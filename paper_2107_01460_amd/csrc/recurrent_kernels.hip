@@ -741,10 +741,11 @@ int32_t launch_ppo_update_recurrent(const marl_config& c, marl_traj tr, marl_rec
                                                   envs, eff, oc, eff + pm.wh_op[1], eff + pm.wht_op[1], w.grad, gc, fn, w, s);
         if (rc != MARL_OK) return rc;
       }
-      hipLaunchKernelGGL(grad_norm_kernel, dim3((unsigned)std::min<int64_t>(256, (d.P + 255) / 256)), dim3(256), 0, s,
+      hipLaunchKernelGGL(grad_norm_kernel, dim3(grad_norm_blocks(d.P)), dim3(256), 0, s,
                          w.grad, d.P, w.sc);
       ++k;
       AdamArgs a{};
+      a.norm_blocks = (int)grad_norm_blocks(d.P);
       a.lr = c.lr; a.b1 = c.beta1; a.b2 = c.beta2; a.eps = c.adam_eps;
       a.bc1 = (float)(1.0 - std::pow((double)c.beta1, (double)k));
       a.bc2 = (float)(1.0 - std::pow((double)c.beta2, (double)k));

@@ -1,0 +1,68 @@
+"""Run-to-run determinism on the GPU: the same rollout + GAE + update from the same buffers, twice.
+
+The environment, the sampler and GAE have no reductions, so state and trajectory must be equal bit for bit.  The
+gradient of the networks that take the whole-network training kernel is reduced in a fixed order (per-workgroup copies
+added by one thread per element, the shares inside a workgroup added in turn, the gradient norm in two ordered stages),
+so their parameters must be equal bit for bit as well; the layer-by-layer kernels of the wide networks (256-wide
+centralised critic, the bf16 configuration) still meet in fp32 atomics and are held to 1e-5 of the largest parameter
+change.  The reported loss statistics are summed with atomics in every configuration."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from gpu_util import dev, small
+
+pytestmark = pytest.mark.gpu
+
+TRAJ = ("obs", "action", "logp", "value", "reward", "done", "last_value", "adv", "ret")
+
+
+def one_run(M, cfg, params0, perm):
+    st = M.EnvState(cfg)
+    M.env_reset(cfg, st)
+    tr = M.Traj(cfg)
+    sizes = M.query_sizes(cfg)
+    ws_r, ws_u = M.alloc_workspace(sizes.rollout_workspace_bytes), M.alloc_workspace(sizes.update_workspace_bytes)
+    p = dev(params0)
+    m, v = torch.zeros_like(p), torch.zeros_like(p)
+    stats = torch.zeros((cfg["n_epochs"] * cfg["n_minibatches"], 8), device="cuda")
+    snaps = []
+    for it in range(2):
+        M.rollout(cfg, st, p, tr, it * cfg["rollout_len"], ws_r)
+        M.compute_gae(cfg, tr)
+        torch.cuda.synchronize()
+        out = {f: getattr(tr, f).cpu().numpy() for f in TRAJ}
+        out.update({"state." + f: x for f, x in st.to_host().items()})
+        snaps.append(out)
+        M.ppo_update(cfg, tr, p, m, v, it * cfg["n_epochs"] * cfg["n_minibatches"], dev(perm), stats, None, ws_u)
+    torch.cuda.synchronize()
+    return snaps, p.cpu().numpy(), m.cpu().numpy(), v.cpu().numpy(), stats.cpu().numpy()
+
+
+@pytest.mark.parametrize("k,exact", [(2, True), (3, False), (4, False), (1, True), (5, True)])
+def test_two_runs_agree(k, exact):
+    import paper_2107_01460_amd as M
+    cfg = small(k, n_envs={1: 700, 2: 1024, 3: 512, 4: 96, 5: 3000}[k], rollout_len=16, n_minibatches=2, n_epochs=2)
+    print("case", cfg["name"], flush=True)
+    params0 = W.init_params(cfg, bias_scale=0.1)
+    perm = W.make_perm(cfg)
+    a = one_run(M, cfg, params0, perm)
+    b = one_run(M, cfg, params0, perm)
+    for f in a[0][0]:
+        assert np.array_equal(a[0][0][f], b[0][0][f]), f
+    if exact:
+        for f in a[0][1]:                                  # the second rollout ran under the updated parameters
+            assert np.array_equal(a[0][1][f], b[0][1][f]), f
+        for x, y, name in zip(a[1:4], b[1:4], ("params", "adam_m", "adam_v")):
+            assert np.array_equal(x.view(np.uint32), y.view(np.uint32)), name
+    else:
+        scale = np.abs(a[1] - params0).max()
+        assert scale > 0
+        # 1e-5 of the largest parameter change, plus the rounding of the parameters themselves (an fp32 parameter of
+        # magnitude 0.3 moves in steps of 3e-8, more than 1e-5 of a 2e-3 change)
+        # (bf16 configuration: 1e-2 -- a master weight that differs in its last bit can round to the other bf16
+        # neighbour, which moves the next minibatch's activations by 2^-9 of that weight's contribution)
+        tol = 1e-2 if cfg["precision"] == 1 else 1e-5
+        assert np.abs(a[1] - b[1]).max() <= tol * scale + 2 * np.spacing(np.abs(a[1]).max())
+    assert np.allclose(a[4], b[4], rtol=1e-3 if cfg["precision"] == 1 else 1e-5, atol=1e-6)
