@@ -14,7 +14,9 @@
 // Arithmetic: the environment is integer-only except for the reward (IEEE fp32, one
 // division per loader and food, accumulated in ascending food index).  All network, loss,
 // GAE and optimiser arithmetic is carried out in fp64 and rounded to fp32 only where a
-// result is stored in an fp32 buffer.
+// result is stored in an fp32 buffer.  The bf16 configuration rounds the weights to bf16
+// (precision 1) and, in a second mode (precision 2, oracle only), also the inputs of every
+// matrix product where the method rounds them; see mlp_forward.
 //
 // Parity status of each function is listed in tests/test_oracle_*.py; every function here
 // has at least one pin that is not itself (known-answer vectors for Philox, hand-built
@@ -138,6 +140,7 @@ struct ResetDraws {
 struct Dims {
   int G, A, F, V, D, N, T, Ha, Hc, Dc, Pa, Pc, P;
   bool central;
+  bool round_act;  // precision 2: the inputs of every matrix product are rounded to bf16 (see mlp_forward)
 };
 
 Dims dims_of(const orc_config& c) {
@@ -145,6 +148,7 @@ Dims dims_of(const orc_config& c) {
   d.G = c.grid; d.A = c.n_agents; d.F = c.n_food; d.V = c.view; d.D = 3 * c.view * c.view;
   d.N = c.n_envs; d.T = c.rollout_len; d.Ha = c.actor_hidden; d.Hc = c.critic_hidden;
   d.central = c.central_critic != 0;
+  d.round_act = c.precision == 2;
   d.Dc = d.central ? d.A * d.D : d.D;
   d.Pa = d.D * d.Ha + d.Ha + d.Ha * d.Ha + d.Ha + d.Ha * kActions + kActions;
   d.Pc = d.Dc * d.Hc + d.Hc + d.Hc * d.Hc + d.Hc + d.Hc + 1;
@@ -533,13 +537,14 @@ void wh_observe_one(const orc_config& c, const orc_env_state& s, int env, float*
 struct Net {
   int Din, H, Dout;
   const double *W1, *b1, *W2, *b2, *W3, *b3;
+  bool round_act;
 };
 struct NetGrad {
   double *W1, *b1, *W2, *b2, *W3, *b3;
 };
 
-Net net_at(const double* p, int Din, int H, int Dout) {
-  Net n{Din, H, Dout, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+Net net_at(const double* p, int Din, int H, int Dout, bool round_act) {
+  Net n{Din, H, Dout, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, round_act};
   n.W1 = p; p += (size_t)Din * H;
   n.b1 = p; p += H;
   n.W2 = p; p += (size_t)H * H;
@@ -573,24 +578,33 @@ float round_bf16(float x) {
 }
 
 // Parameters as the networks see them: fp32 master widened to fp64; in the bf16
-// configuration every weight and bias is first rounded to bf16.
+// configuration (precision 1 and 2) every weight and bias is first rounded to bf16.
 std::vector<double> effective_params(const orc_config& c, const float* params) {
   const Dims d = dims_of(c);
   std::vector<double> p(d.P);
-  for (int i = 0; i < d.P; ++i) p[i] = c.precision == 1 ? (double)round_bf16(params[i]) : (double)params[i];
+  for (int i = 0; i < d.P; ++i) p[i] = c.precision >= 1 ? (double)round_bf16(params[i]) : (double)params[i];
   return p;
 }
+
+// The bf16 configuration of the workload list ("bf16 weights and activations with fp32 accumulation") has two
+// oracle modes.  precision 1 rounds the weights only and evaluates everything else exactly: the error of the
+// activation rounding is then what a comparison measures.  precision 2 also rounds every INPUT of a matrix product
+// to bf16 (round to nearest even, via fp32) where the method does: the hidden activations h1 and h2 after the tanh,
+// and in the backward pass dz2 and dz1, the gradients with respect to the pre-activations; tanh' is taken from the
+// rounded activation, the bias gradients are sums of the rounded dz, and the sums themselves stay exact.  (The
+// observations are small integers and halves, which bf16 holds exactly.)
+inline double act_round(const Net& n, double v) { return n.round_act ? (double)round_bf16((float)v) : v; }
 
 void mlp_forward(const Net& n, const double* x, double* h1, double* h2, double* out) {
   for (int j = 0; j < n.H; ++j) {
     double acc = n.b1[j];
     for (int i = 0; i < n.Din; ++i) acc += x[i] * n.W1[(size_t)i * n.H + j];
-    h1[j] = std::tanh(acc);
+    h1[j] = act_round(n, std::tanh(acc));
   }
   for (int j = 0; j < n.H; ++j) {
     double acc = n.b2[j];
     for (int i = 0; i < n.H; ++i) acc += h1[i] * n.W2[(size_t)i * n.H + j];
-    h2[j] = std::tanh(acc);
+    h2[j] = act_round(n, std::tanh(acc));
   }
   for (int k = 0; k < n.Dout; ++k) {
     double acc = n.b3[k];
@@ -608,7 +622,7 @@ void mlp_backward(const Net& n, const NetGrad& g, const double* x, const double*
       acc += dout[k] * n.W3[(size_t)i * n.Dout + k];
       g.W3[(size_t)i * n.Dout + k] += h2[i] * dout[k];
     }
-    dz2[i] = acc * (1.0 - h2[i] * h2[i]);
+    dz2[i] = act_round(n, acc * (1.0 - h2[i] * h2[i]));
   }
   for (int k = 0; k < n.Dout; ++k) g.b3[k] += dout[k];
   for (int i = 0; i < n.H; ++i) {
@@ -617,7 +631,7 @@ void mlp_backward(const Net& n, const NetGrad& g, const double* x, const double*
       acc += dz2[j] * n.W2[(size_t)i * n.H + j];
       g.W2[(size_t)i * n.H + j] += h1[i] * dz2[j];
     }
-    dz1[i] = acc * (1.0 - h1[i] * h1[i]);
+    dz1[i] = act_round(n, acc * (1.0 - h1[i] * h1[i]));
   }
   for (int j = 0; j < n.H; ++j) g.b2[j] += dz2[j];
   for (int i = 0; i < n.Din; ++i)
@@ -628,8 +642,8 @@ void mlp_backward(const Net& n, const NetGrad& g, const double* x, const double*
 // logits / value of every agent of one (t,n) row.  obs_row = [A][D] fp32.
 void policy_row(const Dims& d, const double* p, const float* obs_row, double* logits /*[A][6]*/,
                 double* value /*[A]*/) {
-  const Net actor = net_at(p, d.D, d.Ha, kActions);
-  const Net critic = net_at(p + d.Pa, d.Dc, d.Hc, 1);
+  const Net actor = net_at(p, d.D, d.Ha, kActions, d.round_act);
+  const Net critic = net_at(p + d.Pa, d.Dc, d.Hc, 1, d.round_act);
   std::vector<double> x(std::max(d.D, d.Dc)), h1(std::max(d.Ha, d.Hc)), h2(std::max(d.Ha, d.Hc));
   for (int a = 0; a < d.A; ++a) {
     for (int i = 0; i < d.D; ++i) x[i] = obs_row[(size_t)a * d.D + i];
@@ -697,8 +711,8 @@ MbStats minibatch_loss_grad(const orc_config& c, const orc_traj& tr, const doubl
       }
     stdv = std::sqrt(q / B);
   }
-  const Net actor = net_at(p, d.D, d.Ha, kActions);
-  const Net critic = net_at(p + d.Pa, d.Dc, d.Hc, 1);
+  const Net actor = net_at(p, d.D, d.Ha, kActions, d.round_act);
+  const Net critic = net_at(p + d.Pa, d.Dc, d.Hc, 1, d.round_act);
   NetGrad ga{}, gc{};
   if (grad) {
     std::fill(grad, grad + d.P, 0.0);

@@ -15,6 +15,31 @@ def err(got, ref, cfg):
     return rel_err(got, ref, FLOOR[cfg["precision"]])
 
 
+# The bf16 configuration is compared twice.  Against the oracle's weights-only mode (precision 1: everything but the
+# weight rounding exact) at the wide floor above, which measures the activation rounding itself; and against the
+# oracle's input-rounding mode (precision 2: h1, h2, dz2, dz1 rounded to bf16 where the method rounds them), where only
+# the fp32 accumulation order and activations that sit on a rounding boundary are left.  Such an activation (its fp32
+# and fp64 evaluations fall on different sides of a bf16 rounding boundary: about 3 % of the samples have one among
+# their 512 first-layer units) moves by a whole bf16 step, 2^-9, and the next layer amplifies it: the second-layer
+# pre-activations all move by ~1e-4, which flips ~5 % of THEIR roundings, and the output moves by ~3e-4 of its scale
+# (measured: 2.4e-4).  Hence a floor of 2.5e-2 (2e-2 * 2.5e-2 = 5e-4 of the scale) -- ten times below the first
+# comparison's -- at the same 2e-2 relative bound.
+# Gradients pass through two more rounded products (dz2, dz1) and are sums of per-sample terms that largely cancel, so
+# a moved sample shows more in them (at the 1000-sample test sizes: up to 1.1e-3 of the largest element, 2.2 % of an
+# element a twentieth of the largest): their floor is 0.1 (2e-3 of the largest element), against 0.25 in the first
+# comparison.
+TIGHT_TOL, TIGHT_FLOOR, TIGHT_FLOOR_GRAD = 2e-2, 2.5e-2, 0.1
+
+
+def tight_cfg(cfg):
+    """The oracle-side configuration of the second comparison (None for fp32 configurations)."""
+    return W.scaled(cfg, precision=2) if cfg["precision"] == 1 else None
+
+
+def err_tight(got, ref, grad=False):
+    return rel_err(got, ref, TIGHT_FLOOR_GRAD if grad else TIGHT_FLOOR)
+
+
 def rel_err(got, ref, floor=1e-2):
     """max_i |g_i - o_i| / max(|o_i|, floor * max|o|).
 

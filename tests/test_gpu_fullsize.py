@@ -19,7 +19,7 @@ import pytest
 import torch
 
 import workloads as W
-from gpu_util import REL_TOL, dev, err, rel_err
+from gpu_util import REL_TOL, TIGHT_TOL, dev, err, err_tight, rel_err, tight_cfg
 
 pytestmark = pytest.mark.gpu
 
@@ -91,6 +91,11 @@ def test_full_size_rollout_and_gae(M, orc, k):
     o_logp = np.take_along_axis(log_softmax(ol), act[..., None].astype(np.int64), axis=-1)[..., 0]
     assert err(gtr.value[ti, ni].cpu().numpy(), ov, cfg) < tol
     assert err(gtr.logp[ti, ni].cpu().numpy(), o_logp, cfg) < tol
+    if tight_cfg(cfg):   # bf16 configuration: also against the oracle mode that rounds the inputs of every product
+        ol2, ov2 = orc.policy_forward(tight_cfg(co), params, obs_rows)
+        o_logp2 = np.take_along_axis(log_softmax(ol2), act[..., None].astype(np.int64), axis=-1)[..., 0]
+        assert err_tight(gtr.value[ti, ni].cpu().numpy(), ov2) < TIGHT_TOL
+        assert err_tight(gtr.logp[ti, ni].cpu().numpy(), o_logp2) < TIGHT_TOL
 
     # ---- invariants of the rules over every environment of the final state
     cells_a = host["agent_row"].astype(np.int64) * G + host["agent_col"]
@@ -208,6 +213,12 @@ def test_full_size_ppo_update_tiled(M, orc, k, n_envs, tile):
     Pa = orc.actor_param_count(cs)
     assert err(g[:Pa], ograd[:Pa], cfg) < tol, "actor gradient"
     assert err(g[Pa:], ograd[Pa:], cfg) < tol, "critic gradient"
+    if tight_cfg(cfg):   # bf16 configuration: also against the oracle mode that rounds the inputs of every product
+        p2, m2, v2 = params.copy(), np.zeros_like(params), np.zeros_like(params)
+        _, ograd2 = orc.ppo_update(tight_cfg(ca_s), otr, p2, m2, v2, adam_step0=0, perm=perm_s[:1])
+        print("tight gradient", err_tight(g[:Pa], ograd2[:Pa], True), err_tight(g[Pa:], ograd2[Pa:], True), flush=True)
+        assert err_tight(g[:Pa], ograd2[:Pa], True) < TIGHT_TOL, "actor gradient against the input-rounding oracle mode"
+        assert err_tight(g[Pa:], ograd2[Pa:], True) < TIGHT_TOL, "critic gradient against the input-rounding oracle mode"
     st = stats.cpu().numpy()
     assert np.all((ostats[:, 4] > 0.0) & (ostats[:, 4] < 1.0))
     for i in (0, 1, 2, 3, 5, 6):

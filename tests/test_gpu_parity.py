@@ -4,7 +4,7 @@ import pytest
 import torch
 
 import workloads as W
-from gpu_util import REL_TOL, dev, err, load_traj, rel_err, small
+from gpu_util import REL_TOL, TIGHT_TOL, dev, err, err_tight, load_traj, rel_err, small, tight_cfg
 
 pytestmark = pytest.mark.gpu
 
@@ -95,6 +95,11 @@ def check_policy_forward(M, orc, cfg, k):
     tol = REL_TOL[cfg["precision"]]
     assert err(logits.cpu().numpy(), ol, cfg) < tol
     assert err(value.cpu().numpy(), ov, cfg) < tol
+    if tight_cfg(cfg):
+        ol2, ov2 = orc.policy_forward(tight_cfg(cfg), params, obs)
+        print("tight forward", err_tight(logits.cpu().numpy(), ol2), err_tight(value.cpu().numpy(), ov2), flush=True)
+        assert err_tight(logits.cpu().numpy(), ol2) < TIGHT_TOL
+        assert err_tight(value.cpu().numpy(), ov2) < TIGHT_TOL
     # either output alone
     l2 = torch.empty_like(logits)
     M.policy_forward(cfg, dev(params), dev(obs), rows, l2, None, ws)
@@ -161,6 +166,15 @@ def test_rollout_teacher_forced(M, orc, k):
     assert err(gtr.value.cpu().numpy(), otr.value, cfg) < tol
     assert err(gtr.last_value.cpu().numpy(), otr.last_value, cfg) < tol
     assert err(gtr.logp.cpu().numpy(), otr.logp, cfg) < tol
+    if tight_cfg(cfg):
+        os2 = orc.EnvState(cfg)
+        orc.env_reset(cfg, os2)
+        otr2 = orc.Traj(cfg)
+        orc.rollout(tight_cfg(cfg), os2, params, otr2, step_offset=1000, forced_actions=otr.action)
+        for f in ("logits", "value", "last_value", "logp"):
+            e = err_tight(getattr(gtr, f).cpu().numpy(), getattr(otr2, f))
+            print("tight rollout", f, e, flush=True)
+            assert e < TIGHT_TOL, f
     if cfg["precision"] == 0:
         # the sampler's own draw: equal to the oracle's except at near-ties of the perturbed logits
         mism = gtr.sampled.cpu().numpy() != otr.sampled
@@ -291,6 +305,12 @@ def check_single_minibatch_gradient(M, orc, cfg, k):
     Pa = orc.actor_param_count(cfg)
     assert err(g[:Pa], ograd[:Pa], cfg) < tol, "actor gradient"
     assert err(g[Pa:], ograd[Pa:], cfg) < tol, "critic gradient"
+    if tight_cfg(cfg):
+        p2, m2, v2 = params.copy(), np.zeros_like(params), np.zeros_like(params)
+        ostats2, ograd2 = orc.ppo_update(tight_cfg(cfg), otr, p2, m2, v2, adam_step0=0, perm=perm)
+        print("tight gradient", err_tight(g[:Pa], ograd2[:Pa], True), err_tight(g[Pa:], ograd2[Pa:], True), flush=True)
+        assert err_tight(g[:Pa], ograd2[:Pa], True) < TIGHT_TOL, "actor gradient against the input-rounding oracle mode"
+        assert err_tight(g[Pa:], ograd2[Pa:], True) < TIGHT_TOL, "critic gradient against the input-rounding oracle mode"
     st = stats.cpu().numpy()[0]
     assert 0.0 < ostats[0, 4] < 1.0           # clip fraction: both branches of the min are exercised
     for i in (0, 1, 2, 3, 5, 6):
@@ -361,7 +381,9 @@ def test_greedy_evaluation_block(M, orc, k):
         off += int(np.prod(shape))
     os_ = orc.EnvState(cfg)
     orc.env_reset(cfg, os_)
-    oret, olen, oeps, gap = orc.evaluate(cfg, os_, params, E)
+    # (bf16 configuration: the oracle in its input-rounding mode, so that the two sides' logits differ by the
+    # accumulation order only and most environments stay clear of a tie that the difference could break)
+    oret, olen, oeps, gap = orc.evaluate(tight_cfg(cfg) or cfg, os_, params, E)
     gs = M.EnvState(cfg)
     M.env_reset(cfg, gs)
     out = M.EvalStats(cfg)
@@ -374,9 +396,10 @@ def test_greedy_evaluation_block(M, orc, k):
     assert np.all(geps == E) and np.all(oeps == E)
     scale = float(np.abs(params).max())
     # logits differ between the two sides by up to the tolerance times their scale (a few units here)
-    lim = (2e-4 if cfg["precision"] == 0 else 2.5e-2) * max(1.0, scale) * 4
+    lim = (2e-4 if cfg["precision"] == 0 else 4e-3) * max(1.0, scale) * 4
     clear = gap > lim
-    assert clear.mean() > (0.9 if cfg["precision"] == 0 else 0.15), clear.mean()
+    print("clear environments", clear.mean(), flush=True)
+    assert clear.mean() > (0.9 if cfg["precision"] == 0 else 0.6), clear.mean()
     assert np.array_equal(gret[clear].view(np.uint32), oret[clear].view(np.uint32))
     assert np.array_equal(glen[clear], olen[clear])
     assert np.all(glen >= E) and np.all(glen <= E * cfg["episode_cap"])

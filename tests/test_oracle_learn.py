@@ -1,6 +1,8 @@
 """Pins for the oracle's networks, sampler, GAE, PPO loss/gradient and Adam: float64 autograd
 and library routines of torch (CPU) as special cases, central finite differences, brute-force
 sums and closed forms."""
+import sys
+
 import numpy as np
 import pytest
 import torch
@@ -100,6 +102,88 @@ def test_bf16_config_uses_rounded_weights(orc):
     assert np.array_equal(l16, l32) and np.array_equal(v16, v32)
     lraw, _ = orc.policy_forward(W.scaled(cfg, precision=0), params, obs)
     assert not np.array_equal(lraw, l32)
+
+
+class _TanhBf16(torch.autograd.Function):
+    """tanh whose output, and whose gradient with respect to its input, are rounded to bf16 (torch's own casts);
+    the derivative is taken from the rounded output."""
+
+    @staticmethod
+    def forward(ctx, z):
+        h = torch.tanh(z).float().bfloat16().double()
+        ctx.save_for_backward(h)
+        return h
+
+    @staticmethod
+    def backward(ctx, g):
+        (h,) = ctx.saved_tensors
+        return (g * (1 - h * h)).float().bfloat16().double()
+
+
+def _mlp_bf16_inputs(P, prefix, x):
+    h1 = _TanhBf16.apply(x @ P[prefix + ".W1"] + P[prefix + ".b1"])
+    h2 = _TanhBf16.apply(h1 @ P[prefix + ".W2"] + P[prefix + ".b2"])
+    return h2 @ P[prefix + ".W3"] + P[prefix + ".b3"]
+
+
+@pytest.mark.parametrize("central", [0, 1])
+def test_bf16_input_rounding_mode_against_torch_casts(orc, central, monkeypatch):
+    """precision 2 (weights AND the inputs of every matrix product in bf16): the forward pass and the gradient must
+    equal a float64 torch evaluation with bfloat16 casts at the same points (library rounding, library autograd for
+    the products), and the mode must really differ from the weights-only mode by about one bf16 rounding."""
+    cfg1 = small_cfg(central, precision=1, ent_coef=0.05)
+    cfg2 = W.scaled(cfg1, precision=2)
+    params, tr, _ = make_traj(orc, cfg1)
+    rng = np.random.default_rng(11)
+    moved = (params.astype(np.float64) + 0.15 * rng.normal(size=params.size) * np.abs(params).mean()).astype(np.float32)
+    p64 = torch.tensor(moved).to(torch.bfloat16).double().numpy()        # the weights as the networks see them
+    rows = rng.permutation(cfg1["rollout_len"] * cfg1["n_envs"])[:24].astype(np.int32)
+    stats2, grad2 = orc.minibatch_loss_grad(cfg2, tr, p64, rows)
+    stats1, grad1 = orc.minibatch_loss_grad(cfg1, tr, p64, rows)
+    P = {k: torch.tensor(v, dtype=torch.float64, requires_grad=True) for k, v in split_params(cfg1, p64).items()}
+    monkeypatch.setattr(sys.modules[__name__], "torch_mlp", _mlp_bf16_inputs)
+    loss, _ = torch_minibatch_loss(cfg2, tr, P, rows)
+    loss.backward()
+    ref = np.concatenate([P[n].grad.reshape(-1).numpy() for n, _ in W.param_layout(cfg1)])
+    assert abs(stats2[5] - loss.item()) < 1e-12 * max(1, abs(loss.item()))
+    assert np.abs(grad2 - ref).max() < 1e-10 * max(1.0, np.abs(ref).max())
+    # the mode is switched on and is a perturbation (one bf16 rounding, 2^-9 relative, per input of a product; the
+    # value gradient is proportional to v - ret, a difference that a small change of v can move by much more)
+    d = np.linalg.norm(grad2 - grad1) / np.linalg.norm(grad1)
+    assert 1e-5 < d < 0.5, d
+    # forward pass through the public entry point: logits and values against the same torch evaluation
+    obs = rng.integers(0, 4, size=(40, cfg1["n_agents"], W.obs_dim(cfg1))).astype(np.float32)
+    l2, v2 = orc.policy_forward(cfg2, moved, obs)
+    with torch.no_grad():
+        x = torch.tensor(obs, dtype=torch.float64)
+        ref_l = _mlp_bf16_inputs(P, "actor", x.reshape(-1, W.obs_dim(cfg1))).reshape(40, -1, 6).numpy()
+        ref_v = (_mlp_bf16_inputs(P, "critic", x.reshape(40, -1)).expand(-1, cfg1["n_agents"]) if central else
+                 _mlp_bf16_inputs(P, "critic", x.reshape(-1, W.obs_dim(cfg1))).reshape(40, -1)).numpy()
+    assert np.allclose(l2, ref_l, rtol=0, atol=2e-7 * np.abs(ref_l).max())
+    assert np.allclose(v2, ref_v, rtol=0, atol=2e-7 * np.abs(ref_v).max())
+
+
+def test_bf16_input_rounding_mode_is_the_weights_only_mode_on_representable_activations(orc):
+    """With saturated hidden units (|pre-activation| > 20: tanh is exactly +-1 in float64, which bf16 holds) the two
+    bf16 modes are the same function, bit for bit."""
+    cfg1 = small_cfg(0, precision=1)
+    params = W.init_params(cfg1, bias_scale=0.3)
+    P = split_params(cfg1, params)
+    for net in ("actor", "critic"):
+        P[net + ".W1"] *= 0.0
+        P[net + ".b1"][:] = np.where(np.arange(P[net + ".b1"].size) % 2 == 0, 30.0, -30.0)
+        P[net + ".W2"] *= 0.0
+        P[net + ".b2"][:] = np.where(np.arange(P[net + ".b2"].size) % 3 == 0, -25.0, 25.0)
+    sat = np.concatenate([P[n].reshape(-1) for n, _ in W.param_layout(cfg1)]).astype(np.float32)
+    obs = np.random.default_rng(2).integers(0, 4, size=(12, cfg1["n_agents"], W.obs_dim(cfg1))).astype(np.float32)
+    l1, v1 = orc.policy_forward(cfg1, sat, obs)
+    l2, v2 = orc.policy_forward(W.scaled(cfg1, precision=2), sat, obs)
+    assert np.array_equal(l1, l2) and np.array_equal(v1, v2) and np.abs(l1).max() > 0
+    # and on ordinary activations they differ
+    plain = W.init_params(cfg1, bias_scale=0.3)          # (split_params hands out views: `params` is saturated now)
+    l1, _ = orc.policy_forward(cfg1, plain, obs)
+    l2, _ = orc.policy_forward(W.scaled(cfg1, precision=2), plain, obs)
+    assert not np.array_equal(l1, l2)
 
 
 def test_sampler_logp_argmax_and_frequencies(orc):
