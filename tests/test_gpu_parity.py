@@ -265,6 +265,15 @@ def test_bf16_other_widths(M, orc, ha, hc, view):
     check_single_minibatch_gradient(M, orc, small(4, n_epochs=1, n_minibatches=1, max_grad_norm=0.0, **kw), 4)
 
 
+@pytest.mark.parametrize("ha,hc", [(96, 512), (32, 160), (224, 192)])
+def test_fp32_other_widths(M, orc, ha, hc):
+    """fp32 networks of hidden widths that none of the workloads uses (any multiple of 32 up to 512 is accepted): they
+    take the generic tile GEMMs with the separate output-layer / loss / dz2 kernels instead of the fused ones."""
+    kw = dict(actor_hidden=ha, critic_hidden=hc)
+    check_policy_forward(M, orc, small(2, **kw), 60 + ha // 32)
+    check_single_minibatch_gradient(M, orc, small(2, n_epochs=1, n_minibatches=1, max_grad_norm=0.0, **kw), 2)
+
+
 def test_bf16_odd_chunk_count(M, orc):
     """816 samples (17 environments): the weight-gradient kernel's k ranges hold 8 and 5 chunks of 64 samples, so
     the chunk-pair loop ends on a single chunk, and the last 64-row tile of the other kernels is ragged."""
