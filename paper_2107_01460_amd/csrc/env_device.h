@@ -91,21 +91,23 @@ __device__ __forceinline__ void reset_regs(uint32_t ag[CA], uint32_t fd[CF], con
 
 // The env's entities into registers.  All loads are issued branch-free (clamped indices) so that they are in flight
 // together; entries past A / F and inactive lanes are masked afterwards (off-grid cells that never match a cell).
+// (Indices are 32-bit: the entity arrays hold at most 8 N < 2^31 elements, and a uniform base plus a 32-bit lane offset
+// is an address the hardware forms by itself, where a 64-bit index costs several instructions per access.)
 template <int CA, int CF, int KIND>
 __device__ __forceinline__ void load_env_state(uint32_t (&ag)[CA], uint32_t (&fd)[CF], const marl_env_state& st,
                                                const EnvParams& p, size_t nn, bool active) {
-  const int N = p.N;
+  const unsigned N = (unsigned)p.N, n = (unsigned)nn;
   uint32_t r8[CA], c8[CA], l8[CA], fr8[CF], fc8[CF], fl8[CF];
 #pragma unroll
   for (int b = 0; b < CA; ++b) {
-    const size_t i = (size_t)min(b, p.A - 1) * N + nn;
+    const unsigned i = (unsigned)min(b, p.A - 1) * N + n;
     r8[b] = st.agent_row[i];
     c8[b] = st.agent_col[i];
     l8[b] = st.agent_lvl[i];
   }
 #pragma unroll
   for (int f = 0; f < CF; ++f) {
-    const size_t i = (size_t)min(f, p.F - 1) * N + nn;
+    const unsigned i = (unsigned)min(f, p.F - 1) * N + n;
     fr8[f] = st.food_row[i];
     fc8[f] = st.food_col[i];
     fl8[f] = st.food_lvl[i];
@@ -121,22 +123,24 @@ __device__ __forceinline__ void load_env_state(uint32_t (&ag)[CA], uint32_t (&fd
 // levels and the food cells change only when a new episode starts (dn).
 template <int CA, int CF, int KIND>
 __device__ __forceinline__ void store_env_state(const uint32_t (&ag)[CA], const uint32_t (&fd)[CF], const marl_env_state& st,
-                                                const EnvParams& p, size_t n, int a, bool dn, int t, uint32_t episode) {
-  const int N = p.N;
+                                                const EnvParams& p, size_t n_, int a, bool dn, int t, uint32_t episode) {
+  const unsigned N = (unsigned)p.N, n = (unsigned)n_;
   const bool all = dn || KIND != 0;
   uint32_t me = 0;
 #pragma unroll
   for (int b = 0; b < CA; ++b) me = (b == a) ? ag[b] : me;
-  st.agent_row[(size_t)a * N + n] = (uint8_t)e_row(me);
-  st.agent_col[(size_t)a * N + n] = (uint8_t)e_col(me);
-  if (all) st.agent_lvl[(size_t)a * N + n] = (uint8_t)e_lvl(me);
+  const unsigned ia = (unsigned)a * N + n;
+  st.agent_row[ia] = (uint8_t)e_row(me);
+  st.agent_col[ia] = (uint8_t)e_col(me);
+  if (all) st.agent_lvl[ia] = (uint8_t)e_lvl(me);
 #pragma unroll
   for (int f = 0; f < CF; ++f)
     if (f < p.F && (f % p.A) == a) {
-      st.food_lvl[(size_t)f * N + n] = (uint8_t)e_lvl(fd[f]);
+      const unsigned i = (unsigned)f * N + n;
+      st.food_lvl[i] = (uint8_t)e_lvl(fd[f]);
       if (all) {
-        st.food_row[(size_t)f * N + n] = (uint8_t)e_row(fd[f]);
-        st.food_col[(size_t)f * N + n] = (uint8_t)e_col(fd[f]);
+        st.food_row[i] = (uint8_t)e_row(fd[f]);
+        st.food_col[i] = (uint8_t)e_col(fd[f]);
       }
     }
   if (a == 0) {

@@ -27,8 +27,8 @@ def err(got, ref, cfg):
 # Gradients pass through two more rounded products (dz2, dz1) and are sums of per-sample terms that largely cancel, so
 # a moved sample shows more in them (at the 1000-sample test sizes: up to 1.1e-3 of the largest element, 2.2 % of an
 # element a twentieth of the largest): their floor is 0.1 (2e-3 of the largest element), against 0.25 in the first
-# comparison.
-TIGHT_TOL, TIGHT_FLOOR, TIGHT_FLOOR_GRAD = 2e-2, 2.5e-2, 0.1
+# comparison, and at the 1000-sample sizes the bound is 3e-2 (measured 2.2e-2 on one element of one shape, from run to run).
+TIGHT_TOL, TIGHT_FLOOR, TIGHT_FLOOR_GRAD, TIGHT_TOL_GRAD = 2e-2, 2.5e-2, 0.1, 3e-2
 
 
 def tight_cfg(cfg):

@@ -59,10 +59,19 @@ def test_two_runs_agree(k, exact):
     else:
         scale = np.abs(a[1] - params0).max()
         assert scale > 0
-        # 1e-5 of the largest parameter change, plus the rounding of the parameters themselves (an fp32 parameter of
-        # magnitude 0.3 moves in steps of 3e-8, more than 1e-5 of a 2e-3 change)
-        # (bf16 configuration: 1e-2 -- a master weight that differs in its last bit can round to the other bf16
-        # neighbour, which moves the next minibatch's activations by 2^-9 of that weight's contribution)
-        tol = 1e-2 if cfg["precision"] == 1 else 1e-5
-        assert np.abs(a[1] - b[1]).max() <= tol * scale + 2 * np.spacing(np.abs(a[1]).max())
-    assert np.allclose(a[4], b[4], rtol=1e-3 if cfg["precision"] == 1 else 1e-5, atol=1e-6)
+        if cfg["precision"] == 0:
+            # 1e-5 of the largest parameter change, plus the rounding of the parameters themselves (an fp32 parameter
+            # of magnitude 0.3 moves in steps of 3e-8, more than 1e-5 of a 2e-3 change)
+            assert np.abs(a[1] - b[1]).max() <= 1e-5 * scale + 2 * np.spacing(np.abs(a[1]).max())
+        else:
+            # bf16 configuration: a master weight that differs in its last bit can round to the other bf16 neighbour,
+            # which moves the next minibatch's gradient by 2^-9 of that weight's contribution; Adam then turns a
+            # near-zero gradient element of either sign into a full step of lr, so single parameters may differ by
+            # whole steps between two runs.  The runs are compared in the norm of the parameter change.
+            da, db = a[1].astype(np.float64) - params0, b[1].astype(np.float64) - params0
+            assert np.linalg.norm(da - db) <= 0.1 * np.linalg.norm(da)
+    if cfg["precision"] == 0:
+        assert np.allclose(a[4], b[4], rtol=1e-5, atol=1e-6)
+    else:   # the first minibatch runs on identical parameters; later ones on weights that may have rounded differently
+        assert np.allclose(a[4][0], b[4][0], rtol=1e-4, atol=1e-6)
+        assert np.allclose(a[4], b[4], rtol=0.2, atol=2e-3)
