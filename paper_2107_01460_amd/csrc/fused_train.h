@@ -44,8 +44,8 @@ struct FusedTrainArgs {
   float *gW1, *gb1, *gW2, *gb2, *gW3, *gb3;  // gradient blocks, accumulated with atomics
   float* stats;                              // 5 floats, atomics
   // Two-stage reduction of the gradient (nullable): the six blocks above are one contiguous range of `gcount` floats
-  // starting at gW1; workgroup b accumulates into its own copy of that range at partial + b * gcount (which it zeroes
-  // first) and reduce_partials_kernel adds the copies to the gradient afterwards.  Several hundred workgroups adding
+  // starting at gW1; workgroup b writes its sums into its own copy of that range at partial + b * gcount
+  // and reduce_partials_kernel adds the copies to the gradient afterwards.  Several hundred workgroups adding
   // to the same few hundred cache lines at the same moment is what the direct atomics cost: 60-180 us per launch.
   float* partial;
   int64_t gcount;
@@ -115,11 +115,9 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lo = lane & 31, hi = lane >> 5;
   const int mt = wave / NTN, nt = wave % NTN;  // forward / dz tile of this wavefront
-  // where this workgroup's gradient goes: the gradient itself, or its own zeroed copy of the range (ordered before
-  // the flush at the end by the barriers of the tile loop)
+  // where this workgroup's gradient goes: the gradient itself, or its own copy of the range
   float* const gout = a.partial != nullptr ? a.partial + (int64_t)blockIdx.x * a.gcount : a.gW1;
-  if (a.partial != nullptr)
-    for (int64_t i = tid; i < a.gcount; i += NT) gout[i] = 0.f;
+  // (a copy needs no zeroing: the flush at the end writes every one of its elements exactly once)
   float* const gW1 = gout;
   float* const gb1 = gout + (a.gb1 - a.gW1);
   float* const gW2 = gout + (a.gW2 - a.gW1);
@@ -414,80 +412,125 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
     PHASE_MARK(13);
   }
 
-  // ---- flush the register-resident gradients.  Into the workgroup's own zeroed copy (a.partial): a tile with one
-  // owner leaves with plain stores; where several wavefronts (or threads) hold parts of one sum they add them in a
-  // FIXED order, one contributor per round with a barrier between rounds, so that the copy -- and, with the
-  // fixed-order reduction of the copies, the gradient -- comes out the same bits in every run.  Without a copy the
-  // parts meet in atomics on the gradient itself.
+  // ---- flush the register-resident gradients.  Into the workgroup's own copy (a.partial): where several wavefronts
+  // (or threads) hold parts of one sum, the parts of all but the first contributor go through LDS (the tile buffers
+  // are free now) and the first contributor adds them in a FIXED order before one plain store, so that the copy --
+  // and, with the fixed-order reduction of the copies, the gradient -- comes out the same bits in every run.  Without
+  // a copy the parts meet in atomics on the gradient itself.
   const bool own = a.partial != nullptr;
-  constexpr int ROUNDS = 8;
-  static_assert(DW2_KS <= ROUNDS && HPARTS <= ROUNDS && MTF <= ROUNDS && NW <= ROUNDS, "every contributor has a round");
-#pragma unroll 1
-  for (int round = 0; round < (own ? ROUNDS : 1); ++round) {
-    {
-      const int t0 = (wave * DW2_TPW) % (NTN * NTN);
-      const int it = t0 / NTN, jt = t0 % NTN;
-      const int rank = DW2_KS == 1 ? 0 : (wave * DW2_TPW) / (NTN * NTN);
-      if (!own || rank == round) {
+  float* const L = lds;  // staging: at most NW tiles of 32 x 32 (the last barrier of the tile loop has passed)
+  static_assert(NW * 1024 <= BM * (2 * (H + 4)), "the staging tiles fit into the h1 / h2 tile buffers");
+  {  // dW2
+    const int t0 = (wave * DW2_TPW) % (NTN * NTN);
+    const int it = t0 / NTN, jt = t0 % NTN;
+    const int rank = (wave * DW2_TPW) / (NTN * NTN);  // 0 unless the sample range of a tile is split over wavefronts
+    if (own && DW2_KS > 1) {
+      if (rank > 0) {
 #pragma unroll
-        for (int q = 0; q < DW2_TPW; ++q)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int i = it * 32 + 8 * (r / 4) + 4 * hi + (r % 4), j = (jt + q) * 32 + lo;
-            if (!own) atomicAdd(&gW2[i * H + j], acc2[q][r]);
-            else if (DW2_KS == 1) gW2[i * H + j] = acc2[q][r];
-            else gW2[i * H + j] += acc2[q][r];
-          }
+        for (int r = 0; r < 16; ++r) L[wave * 1024 + r * 64 + lane] = acc2[0][r];
       }
+      __syncthreads();
+      if (rank == 0) {
+#pragma unroll 1
+        for (int k = 1; k < DW2_KS; ++k) {
+          const int pw = wave + k * (NTN * NTN / DW2_TPW);
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc2[0][r] += L[pw * 1024 + r * 64 + lane];
+        }
+      }
+      __syncthreads();
     }
+    if (!own || rank == 0) {
 #pragma unroll
-    for (int q = 0; q < Q1; ++q) {
-      int t, kb0, klen;
-      if (dw1_item(q, t, kb0, klen)) {
-        const int dt = t / NTN, jt = t % NTN;
-        const int rank = kb0 / klen;  // which share of the row tile's samples this item summed
-        if (!own || rank == round) {
+      for (int q = 0; q < DW2_TPW; ++q)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int d = dt * 32 + 8 * (r / 4) + 4 * hi + (r % 4), j = jt * 32 + lo;
-            if (d < a.Din) {
-              if (!own) atomicAdd(&gW1[d * H + j], acc1[q][r]);
-              else if (klen == BM) gW1[d * H + j] = acc1[q][r];  // a whole tile of this wavefront's own
-              else gW1[d * H + j] += acc1[q][r];
-            }
-          }
+        for (int r = 0; r < 16; ++r) {
+          const int i = it * 32 + 8 * (r / 4) + 4 * hi + (r % 4), j = (jt + q) * 32 + lo;
+          if (own) gW2[i * H + j] = acc2[q][r];
+          else atomicAdd(&gW2[i * H + j], acc2[q][r]);
+        }
+    }
+  }
+#pragma unroll
+  for (int q = 0; q < Q1; ++q) {  // dW1: the wavefronts that share a tile are neighbours with the same slot q
+    int t, kb0, klen;
+    const bool have = dw1_item(q, t, kb0, klen);
+    const int rank = have ? kb0 / klen : 0, shares = have ? BM / klen : 1;
+    if (own) {
+      if (have && rank > 0) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) L[wave * 1024 + r * 64 + lane] = acc1[q][r];
+      }
+      __syncthreads();
+      if (have && rank == 0) {
+#pragma unroll 1
+        for (int k = 1; k < shares; ++k) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc1[q][r] += L[(wave + k) * 1024 + r * 64 + lane];
+        }
+      }
+      __syncthreads();
+    }
+    if (have && (!own || rank == 0)) {
+      const int dt = t / NTN, jt = t % NTN;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int d = dt * 32 + 8 * (r / 4) + 4 * hi + (r % 4), j = jt * 32 + lo;
+        if (d < a.Din) {
+          if (own) gW1[d * H + j] = acc1[q][r];
+          else atomicAdd(&gW1[d * H + j], acc1[q][r]);
         }
       }
     }
-    if (hi == 0 && (!own || mt == round)) {
-      if (!own) {
-        atomicAdd(&gb1[nt * 32 + lo], gb1r);
-        atomicAdd(&gb2[nt * 32 + lo], gb2r);
-      } else {
-        gb1[nt * 32 + lo] += gb1r;
-        gb2[nt * 32 + lo] += gb2r;
-      }
+  }
+  if (!own) {
+    if (hi == 0) {
+      atomicAdd(&gb1[nt * 32 + lo], gb1r);
+      atomicAdd(&gb2[nt * 32 + lo], gb2r);
     }
-    if (!own || tid / H == round) {
-      const int i = tid % H;
+    const int i = tid % H;
 #pragma unroll
-      for (int k = 0; k < NOUT; ++k) {
-        if (!own) atomicAdd(&gW3[i * NOUT + k], gw[k]);
-        else gW3[i * NOUT + k] += gw[k];
-      }
-    }
-    if (tid < (BM < 64 ? 64 : BM) && (!own || wave == round)) {  // whole wavefronts; lanes past BM hold zeros
+    for (int k = 0; k < NOUT; ++k) atomicAdd(&gW3[i * NOUT + k], gw[k]);
+    if (tid < (BM < 64 ? 64 : BM)) {
 #pragma unroll
       for (int k = 0; k < NOUT; ++k) {
         float v = accS[tid * AS + k];
         for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-        if (lane == 0) {
-          if (!own) atomicAdd(&gb3[k], v);
-          else gb3[k] += v;
-        }
+        if (lane == 0) atomicAdd(&gb3[k], v);
       }
     }
-    if (own) __syncthreads();  // the next contributor sees this round's sums
+  } else {  // bias and output-layer gradients: every contributor's part to LDS, then one thread per element adds them in order
+    float* const Lb = L;                        // [MTF][2][H]
+    float* const Lw = Lb + MTF * 2 * H;         // [HPARTS][H * NOUT]
+    float* const L3 = Lw + HPARTS * H * NOUT;   // [2][NOUT]
+    static_assert(MTF * 2 * H + HPARTS * H * NOUT + 2 * NOUT <= BM * (2 * (H + 4)), "the parts fit into the tile buffers");
+    if (hi == 0) {
+      Lb[(mt * 2 + 0) * H + nt * 32 + lo] = gb1r;
+      Lb[(mt * 2 + 1) * H + nt * 32 + lo] = gb2r;
+    }
+#pragma unroll
+    for (int k = 0; k < NOUT; ++k) Lw[(tid / H) * H * NOUT + (tid % H) * NOUT + k] = gw[k];
+    if (tid < (BM < 64 ? 64 : BM)) {  // whole wavefronts; lanes past BM hold zeros
+#pragma unroll
+      for (int k = 0; k < NOUT; ++k) {
+        float v = accS[tid * AS + k];
+        for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+        if (lane == 0) L3[wave * NOUT + k] = v;
+      }
+    }
+    __syncthreads();
+    for (int e = tid; e < 2 * H; e += NT) {
+      const int which = e / H, col = e - which * H;
+      float v = Lb[which * H + col];
+      for (int m = 1; m < MTF; ++m) v += Lb[(m * 2 + which) * H + col];
+      (which == 0 ? gb1 : gb2)[col] = v;
+    }
+    for (int e = tid; e < H * NOUT; e += NT) {
+      float v = Lw[e];
+      for (int part = 1; part < HPARTS; ++part) v += Lw[part * H * NOUT + e];
+      gW3[e] = v;
+    }
+    if (tid < NOUT) gb3[tid] = (BM > 64) ? L3[tid] + L3[NOUT + tid] : L3[tid];
   }
   if (tid < (BM < 64 ? 64 : BM)) {  // loss statistics: reported only, summed over the workgroups with atomics
 #pragma unroll
