@@ -67,24 +67,35 @@ struct GemmArgs {
 // keeps its atomics: its workgroups finish spread over time, and the two-stage form measured no faster (324 against
 // 315 us).
 
-// out[i] += sum_b partial[b * count + i], the copies added in a fixed order (eight interleaved running sums, then a
-// fixed tree), so that the result does not depend on the run.  One thread per element reads all nblocks copies:
-// consecutive threads read consecutive floats of a copy, and the independent sums keep eight loads in flight.
+// out[i] += sum_b partial[b * count + i], the copies added in a fixed order, so that the result does not depend on the
+// run.  A workgroup takes 32 consecutive elements; its 8 thread groups sum the copies b = g, g + 8, g + 16, ... of an
+// element (four interleaved running sums each, so that four loads are in flight), and one thread per element adds the
+// eight group sums through LDS, again in a fixed order.
 static __global__ void __launch_bounds__(256) reduce_partials_kernel(const float* __restrict__ partial, int nblocks, int64_t count,
                                                                      float* __restrict__ out) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= count) return;
-  float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  int b = 0;
-  for (; b + 8 <= nblocks; b += 8) {
+  __shared__ float part[8][32];
+  const int e = threadIdx.x & 31, g = threadIdx.x >> 5;
+  const int64_t i = (int64_t)blockIdx.x * 32 + e;
+  float s[4] = {0.f, 0.f, 0.f, 0.f};
+  if (i < count) {
+    int b = g;
+    for (; b + 24 < nblocks; b += 32) {
 #pragma unroll
-    for (int u = 0; u < 8; ++u) s[u] += partial[(int64_t)(b + u) * count + i];
+      for (int u = 0; u < 4; ++u) s[u] += partial[(int64_t)(b + 8 * u) * count + i];
+    }
+    for (; b < nblocks; b += 8) s[0] += partial[(int64_t)b * count + i];
   }
-  for (; b < nblocks; ++b) s[0] += partial[(int64_t)b * count + i];
-  out[i] += ((s[0] + s[1]) + (s[2] + s[3])) + ((s[4] + s[5]) + (s[6] + s[7]));
+  part[g][e] = (s[0] + s[1]) + (s[2] + s[3]);
+  __syncthreads();
+  if (g == 0 && i < count) {
+    float v = part[0][e];
+#pragma unroll
+    for (int q = 1; q < 8; ++q) v += part[q][e];
+    out[i] += v;
+  }
 }
 inline void launch_reduce_partials(const float* partial, int nblocks, int64_t count, float* out, hipStream_t s) {
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s, partial, nblocks, count, out);
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((count + 31) / 32)), dim3(256), 0, s, partial, nblocks, count, out);
 }
 
 // tanh(x) = 1 - 2 / (e^{2x} + 1) with the hardware exp2 and reciprocal: absolute error ~1e-7 (the values feed

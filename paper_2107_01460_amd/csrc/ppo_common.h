@@ -11,7 +11,7 @@
 namespace marl {
 namespace {
 
-constexpr int kNormBlocks = 64;
+constexpr int kNormBlocks = 256;
 
 // Device scalars of one minibatch step.
 struct Scalars {
@@ -341,7 +341,8 @@ __global__ void __launch_bounds__(256) loss_head_kernel(const HT* __restrict__ H
 }
 
 // Squared gradient norm in two fixed-order stages (no atomics, so the clipping factor is the same bits in every run):
-// workgroup b of at most kNormBlocks sums its grid-stride share in fp64 and stores it; adam_kernel adds the shares.
+// workgroup b of at most kNormBlocks sums its grid-stride share in fp64 and stores it; adam_kernel (256 threads per
+// workgroup = kNormBlocks) adds the shares.
 __global__ void __launch_bounds__(256) grad_norm_kernel(const float* __restrict__ grad, int64_t P, Scalars* sc) {
   __shared__ double red[4];
   double part = 0;
@@ -368,9 +369,15 @@ __global__ void __launch_bounds__(256) adam_kernel(float* __restrict__ params, f
                                                    AdamArgs a, const Scalars* sc, float* __restrict__ stats_row,
                                                    float* __restrict__ grad_dump, Scalars* sc_next) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  double norm2 = 0.0;
-  for (int b = 0; b < a.norm_blocks; ++b) norm2 += sc->norm_part[b];
-  const float norm = sqrtf((float)norm2);
+  // the workgroups' shares of |grad|^2, added by a fixed tree (the same in every workgroup and every run)
+  __shared__ double nparts[kNormBlocks];
+  nparts[threadIdx.x] = (int)threadIdx.x < a.norm_blocks ? sc->norm_part[threadIdx.x] : 0.0;
+  __syncthreads();
+  for (int o = kNormBlocks / 2; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o) nparts[threadIdx.x] += nparts[threadIdx.x + o];
+    __syncthreads();
+  }
+  const float norm = sqrtf((float)nparts[0]);
   const float scale = a.max_norm > 0.f ? a.max_norm / fmaxf(norm, a.max_norm) : 1.0f;
   if (a.k_base != nullptr) {
     const double k = (double)(*a.k_base + a.k_local);

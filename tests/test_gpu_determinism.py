@@ -36,7 +36,8 @@ def one_run(M, cfg, params0, perm):
         out.update({"state." + f: x for f, x in st.to_host().items()})
         snaps.append(out)
         M.ppo_update(cfg, tr, p, m, v, it * cfg["n_epochs"] * cfg["n_minibatches"], dev(perm), stats, None, ws_u)
-    torch.cuda.synchronize()
+        torch.cuda.synchronize()
+        snaps[-1]["stats"] = stats.cpu().numpy().copy()
     return snaps, p.cpu().numpy(), m.cpu().numpy(), v.cpu().numpy(), stats.cpu().numpy()
 
 
@@ -50,10 +51,12 @@ def test_two_runs_agree(k, exact):
     a = one_run(M, cfg, params0, perm)
     b = one_run(M, cfg, params0, perm)
     for f in a[0][0]:
-        assert np.array_equal(a[0][0][f], b[0][0][f]), f
+        if f != "stats":
+            assert np.array_equal(a[0][0][f], b[0][0][f]), f
     if exact:
         for f in a[0][1]:                                  # the second rollout ran under the updated parameters
-            assert np.array_equal(a[0][1][f], b[0][1][f]), f
+            if f != "stats":
+                assert np.array_equal(a[0][1][f], b[0][1][f]), f
         for x, y, name in zip(a[1:4], b[1:4], ("params", "adam_m", "adam_v")):
             assert np.array_equal(x.view(np.uint32), y.view(np.uint32)), name
     else:
@@ -72,6 +75,7 @@ def test_two_runs_agree(k, exact):
             assert np.linalg.norm(da - db) <= 0.1 * np.linalg.norm(da)
     if cfg["precision"] == 0:
         assert np.allclose(a[4], b[4], rtol=1e-5, atol=1e-6)
-    else:   # the first minibatch runs on identical parameters; later ones on weights that may have rounded differently
-        assert np.allclose(a[4][0], b[4][0], rtol=1e-4, atol=1e-6)
+    else:   # the first minibatch of the first update runs on identical parameters; later ones on weights that may have
+        # rounded differently
+        assert np.allclose(a[0][0]["stats"][0], b[0][0]["stats"][0], rtol=1e-4, atol=1e-6)
         assert np.allclose(a[4], b[4], rtol=0.2, atol=2e-3)
