@@ -28,8 +28,10 @@ PEAK = {"mfma_f32": 157.3, "mfma_bf16": 2500.0, "hbm": 8000.0}   # TFLOP/s, TFLO
 SIDE_RUNS = {1: (300, 30), 2: (30, 4), 3: (8, 2), 4: (4, 1), 5: (20, 3)}
 # rocprofv3 PMC summaries (FETCH_SIZE / WRITE_SIZE per launch, scaled by a plain copy of known size) by workload, and
 # the kernel-name prefix of each timed kernel class in them
-PMC_PROFILE = {"c3_15x15_4ag_mappo": "profiles/bench_c3_pmc_hbm_traffic.txt"}
-CLASS_KERNEL = {"fused_train": "fused_train_kernel<", "env_step": "env_step_kernel<", "gae": "gae_kernel"}
+PMC_PROFILE = {"c3_15x15_4ag_mappo": "profiles/bench_c3_pmc_hbm_traffic.txt",
+               "c5_8x8_2ag_ippo_wide": "profiles/bench_c5_pmc_hbm_traffic.txt"}
+CLASS_KERNEL = {"fused_train": "fused_train_kernel<", "env_step": "env_step_kernel<", "gae": "gae_kernel",
+                "rollout": "rollout_fused_kernel<"}
 
 
 def gemm_flops_per_step(cfg, W):
