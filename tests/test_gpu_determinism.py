@@ -1,8 +1,9 @@
 """Run-to-run determinism on the GPU: the same rollout + GAE + update from the same buffers, twice.
 
 The environment, the sampler and GAE have no reductions, so state and trajectory must be equal bit for bit.  The
-gradient of the networks that take the whole-network training kernel is reduced in a fixed order (per-workgroup copies
-added by one thread per element, the shares inside a workgroup added in turn, the gradient norm in two ordered stages),
+gradient of the networks that take the whole-network training kernel is reduced in a fixed order (the shares inside a
+workgroup added in turn through LDS, the per-workgroup copies added in a fixed grouping, the gradient norm as per-block
+shares added by a fixed tree),
 so their parameters must be equal bit for bit as well; the layer-by-layer kernels of the wide networks (256-wide
 centralised critic, the bf16 configuration) still meet in fp32 atomics and are held to 1e-5 of the largest parameter
 change.  The reported loss statistics are summed with atomics in every configuration."""
