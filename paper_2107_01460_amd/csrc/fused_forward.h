@@ -85,9 +85,9 @@ __global__ void __launch_bounds__(256, 2) fused_forward_kernel(FusedFwdArgs a, F
       float* xdst = L.Xs + xr_row * px;
       if (a.xvec == 2) {
         // element j of chunk q is column 4 q + j - xo of the row; the chunks never leave the buffer (its ends are aligned)
-        const uintptr_t addr = reinterpret_cast<uintptr_t>(xrow);
-        const float4* const chunk = reinterpret_cast<const float4*>(addr & ~(uintptr_t)15);
-        const int xo = (int)((addr >> 2) & 3), last = ((xo + a.Din + 3) >> 2) - 1;
+        // (pointer arithmetic, not an integer round trip, so that the loads stay global loads)
+        const int xo = (int)((reinterpret_cast<uintptr_t>(xrow) >> 2) & 3), last = ((xo + a.Din + 3) >> 2) - 1;
+        const float4* const chunk = reinterpret_cast<const float4*>(xrow - xo);
         constexpr int XC = 3;  // chunks in flight per thread: a 75-wide row is one batch
         for (int q = c0; q <= last; q += XC * TPR) {
           float4 v[XC];

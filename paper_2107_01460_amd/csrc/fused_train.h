@@ -20,6 +20,13 @@
 
 namespace marl {
 
+#ifndef MARL_FT_XDB
+#define MARL_FT_XDB 1
+#endif
+#ifndef MARL_FT_ENTRIES_LATE
+#define MARL_FT_ENTRIES_LATE 1
+#endif
+
 #ifdef MARL_PHASE_TIMERS
 __device__ long long g_phase_cycles[16];
 #define PHASE_MARK(i)                                                    \
@@ -50,6 +57,63 @@ struct FusedTrainArgs {
   float* partial;
   int64_t gcount;
 };
+
+// All B fragments of one product against weights, for this lane: KG groups of 16 along k, two 16-byte loads each
+// (operand-order copy: element (k, n) at ((k / 4) * LDB + n) * 4 + k % 4; lane_off is this lane's offset
+// (hi * LDB + n) * 4 in floats).  The loads are buffer loads -- a resource descriptor in scalar registers, ONE vector
+// register with the lane's byte offset for all of them, the group's offset as a scalar: as global loads each of them
+// got a 64-bit address register pair of its own, computed outside the tile loop and kept (or spilled) across it.  The whole set is requested one phase AHEAD of the product that uses it -- during the element-wise epilogue
+// or the LDS-only product in front of it -- so that the product never waits for the L2: with two or three groups in
+// flight (gemm_phase_regs) every workgroup of the chip asks the same few cache lines at the same moment and the
+// answers take longer than the 16 matrix instructions that were meant to cover them.
+template <int KG>
+struct PhaseW {
+  float4 w[KG][2];
+};
+typedef __amdgpu_buffer_rsrc_t WeightRsrc;
+// descriptor of `floats` floats at p (raw buffer, no swizzle; reads past the end return zero)
+__device__ __forceinline__ WeightRsrc weight_rsrc(const float* p, int floats) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p), (short)0, floats * 4, 0x00020000);
+}
+template <int LDB, int KG, int G0 = 0, int G1 = KG>  // groups G0 .. G1 - 1
+__device__ __forceinline__ void phase_w_request(PhaseW<KG>& pw, WeightRsrc B, int lane_off, int kgroups) {
+#pragma unroll
+  for (int g = G0; g < G1; ++g) {
+    const int gc = g < kgroups ? g : kgroups - 1;  // past the end: the last group again (never used)
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+      pw.w[g][u] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(B, lane_off * 4, (16 * gc + 8 * u) * LDB * 4, 0));
+  }
+}
+// acc += A B for this wavefront's 32x32 tile: A rows in LDS (As points at this lane's row, + 4 * hi; the fragments of
+// the next group are read before the matrix instructions of the current one), B from pw.
+template <int KG>
+__device__ __forceinline__ void gemm_phase_w(const float* __restrict__ As, int kgroups, floatx16& acc, const PhaseW<KG>& pw) {
+  float4 av[2][2];
+  av[0][0] = *reinterpret_cast<const float4*>(As);
+  av[0][1] = *reinterpret_cast<const float4*>(As + 8);
+#pragma unroll
+  for (int g = 0; g < KG; ++g) {
+    if (g < kgroups) {  // uniform
+      const int gn = g + 1 < kgroups ? g + 1 : g;
+      av[(g + 1) & 1][0] = *reinterpret_cast<const float4*>(As + 16 * gn);
+      av[(g + 1) & 1][1] = *reinterpret_cast<const float4*>(As + 16 * gn + 8);
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const float af[4] = {av[g & 1][u].x, av[g & 1][u].y, av[g & 1][u].z, av[g & 1][u].w};
+        const float bf[4] = {pw.w[g][u].x, pw.w[g][u].y, pw.w[g][u].z, pw.w[g][u].w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(af[j], bf[j], acc, 0, 0, 0);
+      }
+    }
+  }
+}
+
+// Floats of LDS the kernel lays out for a tile of BM samples at X pitch px with `xtiles` X tiles.
+constexpr size_t fused_train_lds_floats(int H, int BM, int NOUT, int NW, int px, int xtiles) {
+  return (size_t)xtiles * BM * px + 2 * (size_t)BM * (H + 4) + 64 * (size_t)NW * NOUT + BM * 8 + H * NOUT + 4 + 8 +
+         (size_t)(BM < 64 ? 64 : BM) * (NOUT + 5);
+}
 
 // acc[q] += A^T B_q over the samples kb0 .. kb0 + klen of a row tile held in LDS: A column block at Ap (pitch pa),
 // B column blocks at Bp + 32 q (pitch pb).  The operands of the next k step are read before the MFMAs of the
@@ -85,6 +149,39 @@ __device__ __forceinline__ void outer_product_accumulate(const float* __restrict
   }
 }
 
+// acc[q] += A_q^T B over the samples kb0 .. kb0 + klen: the NA row blocks A_q at Ap + 32 q (pitch pa) share the
+// column block B at Bp (pitch pb).  NA independent accumulation chains keep the matrix pipe fed from one wavefront.
+template <int NA>
+__device__ __forceinline__ void outer_product_accumulate_rows(const float* __restrict__ Ap, int pa, const float* __restrict__ Bp,
+                                                              int pb, int kb0, int klen, int hi, floatx16* acc) {
+  float af[NA][4], bf[4];
+  auto read = [&](int kb, float (&x)[NA][4], float (&y)[4]) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      y[j] = Bp[(kb + 4 * hi + j) * pb];
+#pragma unroll
+      for (int q = 0; q < NA; ++q) x[q][j] = Ap[(kb + 4 * hi + j) * pa + 32 * q];
+    }
+  };
+  read(kb0, af, bf);
+#pragma unroll 2
+  for (int kb = kb0; kb < kb0 + klen; kb += 8) {
+    float an[NA][4], bn[4];
+    const int kn = kb + 8 < kb0 + klen ? kb + 8 : kb;  // the last step re-reads its own operands
+    read(kn, an, bn);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int q = 0; q < NA; ++q) acc[q] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[q][j], bf[j], acc[q], 0, 0, 0);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      bf[j] = bn[j];
+#pragma unroll
+      for (int q = 0; q < NA; ++q) af[q][j] = an[q][j];
+    }
+  }
+}
+
 template <int H, int BM, int NOUT, int DMAX, int NW, class LossFn>
 __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(FusedTrainArgs a, LossFn fn) {
   constexpr int NT = 64 * NW;
@@ -96,21 +193,29 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
   constexpr int DW2_TPW = NTN * NTN >= NW ? NTN * NTN / NW : 1;  // dW2 tiles per wavefront (one row of tiles at most)
   constexpr int DW2_KS = NTN * NTN >= NW ? 1 : NW / (NTN * NTN);  // split of the sample range when there are fewer tiles than wavefronts
   static_assert(DW2_TPW <= NTN && NTN % DW2_TPW == 0, "a wavefront's dW2 tiles share their row of tiles");
-  constexpr int Q1 = ((DMAX / 32) * NTN + NW - 1) / NW;  // dW1 work items per wavefront
+  // dW1: wavefront -> (column tile wave % NTN of the gradient, share wave / NTN of the tile's samples); it holds all
+  // Q1 row tiles of that column (they share the dz1 operand), Q1 independent accumulation chains
+  constexpr int Q1 = DMAX / 32, KS1 = NW / NTN, KLEN1 = BM / KS1;
+  static_assert(NW % NTN == 0 && BM % KS1 == 0 && KLEN1 % 8 == 0, "dW1 sample shares");
   constexpr int HPARTS = NT / H, SPP = BM / HPARTS;
+  constexpr int KG1 = DMAX / 16, KG2 = H / 16;  // k groups of layer 1 (at most) and of the H-deep products
 
+  // Two X tiles when they fit: the next tile's rows then go to LDS inside the dz1 epilogue of the current one (the
+  // loads were requested after layer 2), and a tile starts with layer 1 instead of a staging phase and its barrier.
+  constexpr bool XDB = MARL_FT_XDB && fused_train_lds_floats(H, BM, NOUT, NW, DMAX + 4, 2) * 4 <= 160 * 1024;
   extern __shared__ __attribute__((aligned(16))) float lds[];
-  float* Xs = lds;                         // [BM][px]
-  float* H1 = Xs + BM * a.px;              // [BM][PH]  h1, later dz1
+  float* const Xs0 = lds;                  // [XDB ? 2 : 1][BM][px]
+  float* H1 = Xs0 + (XDB ? 2 : 1) * BM * a.px;  // [BM][PH]  h1, later dz1
   float* H2 = H1 + BM * PH;                // [BM][PH]  h2, later dz2
   float* red = H2 + BM * PH;               // [GROUPS][NOUT][BM]
   float* dls = red + NT * NOUT;           // [BM][8]
   float* W3s = dls + BM * 8;               // [H][NOUT]
   float* const xdump = W3s + H * NOUT;     // one float: where the staged values that are not part of a row go
+  float* const b3s = xdump + 4;            // [8] the output layer's bias
   // per-sample-slot sums that only the first BM threads touch, once per tile (b3 gradient, loss statistics): in LDS
   // rather than in 11 registers of every thread, which this kernel does not have to spare
   constexpr int AS = NOUT + 5;
-  float* const accS = xdump + 4;           // [max(BM, 64)][AS]
+  float* const accS = b3s + 8;             // [max(BM, 64)][AS]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lo = lane & 31, hi = lane >> 5;
@@ -125,31 +230,9 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
   float* const gW3 = gout + (a.gW3 - a.gW1);
   float* const gb3 = gout + (a.gb3 - a.gW1);
   const int px = a.px;
-  const int MT1 = (a.Din + 31) / 32;           // 32-row tiles of dW1
-  const int tiles1 = MT1 * NTN;
-  // dW1 work items of this wavefront (slot q < Q1): 32x32 tiles of the gradient, whole or split over the samples
-  // of the row tile.  With more tiles than wavefronts (but no more than twice as many, and a remainder that
-  // divides the wavefront count) every wavefront takes one whole tile and an equal share of the remaining ones;
-  // otherwise every tile is split KS1 ways and the items are dealt round-robin.
-  const int rem1 = tiles1 - NW;
-  const bool balanced1 = Q1 >= 2 && rem1 > 0 && rem1 <= NW && NW % rem1 == 0 && (BM / (NW / rem1)) % 8 == 0;
-  const int KS1 = tiles1 * 4 <= Q1 * NW ? 4 : (tiles1 * 2 <= Q1 * NW ? 2 : 1);
-  auto dw1_item = [&](int q, int& t, int& kb0, int& klen) -> bool {
-    if (balanced1) {
-      if (q == 0) {
-        t = wave; kb0 = 0; klen = BM;
-        return true;
-      }
-      const int ks = NW / rem1;
-      t = NW + wave / ks; klen = BM / ks; kb0 = (wave % ks) * klen;
-      return q == 1;
-    }
-    const int item = wave + NW * q;
-    t = item / KS1; klen = BM / KS1; kb0 = (item - t * KS1) * klen;
-    return item < tiles1 * KS1;
-  };
-  for (int i = tid; i < BM * px; i += NT) Xs[i] = 0.f;  // the padding columns stay zero for good
+  for (int i = tid; i < (XDB ? 2 : 1) * BM * px; i += NT) Xs0[i] = 0.f;  // the padding columns stay zero for good
   for (int i = tid; i < H * NOUT; i += NT) W3s[i] = a.W3[i];
+  if (tid < NOUT) b3s[tid] = a.b3[tid];
   __syncthreads();
 
   floatx16 acc1[Q1], acc2[DW2_TPW];  // dW1 / dW2 tiles of this wavefront, persistent
@@ -166,6 +249,12 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
   for (int k = 0; k < NOUT; ++k) gw[k] = 0.f;
   for (int i = tid; i < (BM < 64 ? 64 : BM) * AS; i += NT) accS[i] = 0.f;  // ordered before its first use by the barriers below
   float gb1r = 0.f, gb2r = 0.f;  // bias gradients of column nt*32+lo (lanes hi == 0)
+  // the biases of this lane's column, once: a load inside the tile loop would be waited for on the spot, and with it
+  // (loads return in order) the next tile's rows requested just before
+  const float bias1 = a.b1[nt * 32 + lo], bias2 = a.b2[nt * 32 + lo];
+  const int kpad1 = 16 * ((a.Din + 15) / 16);  // layer 1 contracts over the input width rounded up to a k group (W1 is zero-padded to it)
+  const int wlane = (hi * H + nt * 32 + lo) * 4;  // this lane's 16 bytes of k quad `hi` in an operand-order weight copy
+  const WeightRsrc rsW1 = weight_rsrc(a.W1s, kpad1 * H), rsW2 = weight_rsrc(a.W2s, H * H), rsW2T = weight_rsrc(a.W2Ts, H * H);
 
   // ---- staging helpers.  The inputs of the next tile come in two steps: the gather entries at the top of a
   // tile, the rows themselves half a tile later, so that neither dependent load is ever waited for.
@@ -180,24 +269,29 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
   int32_t xentry = 0, lentry = 0;
   const int xrow_l = tid / TPR, xcol0 = tid % TPR;
   const auto prep = fn.prepare();
+  // These requests are issued for every tile slot, also past a workgroup's last tile (row indices are clamped to the
+  // last sample and the values never used): with the same loads in every iteration the compiler can count the loads
+  // in flight and wait for exactly the ones it needs, where a conditional request makes every wait a wait for all.
   auto fetch_tile_entries = [&](int64_t s0) {
-    xentry = a.X.gather_entry(min(s0 + xrow_l, a.S - 1));
-    if (tid < BM && s0 + tid < a.S) lentry = fn.row_entry(s0 + tid);
+    xentry = a.X.template gather_entry<true>(min(s0 + xrow_l, a.S - 1));
+    if (tid < BM) lentry = fn.template row_entry<true>(min(s0 + tid, a.S - 1));
   };
   auto fetch_tile_inputs = [&](int64_t s0) {
-    const uintptr_t addr = reinterpret_cast<uintptr_t>(a.X.ptr_with(min(s0 + xrow_l, a.S - 1), xentry));
-    const float4* const chunk = reinterpret_cast<const float4*>(addr & ~(uintptr_t)15);
-    xoff = (int)((addr >> 2) & 3);
+    const float* const row = a.X.template ptr_with<true>(min(s0 + xrow_l, a.S - 1), xentry);
+    xoff = (int)((reinterpret_cast<uintptr_t>(row) >> 2) & 3);
+    // (pointer arithmetic, not an integer round trip: the loads stay global loads -- a flat load also counts as an
+    // LDS operation, and every barrier would wait for these rows)
+    const float4* const chunk = reinterpret_cast<const float4*>(row - xoff);
     const int last = ((xoff + a.Din + 3) >> 2) - 1;  // chunks past the row: the last one again (none of its elements is stored)
 #pragma unroll
     for (int p = 0; p < XV; ++p) xr[p] = chunk[min(xcol0 + TPR * p, last)];
   };
   // (the loss inputs of the next tile are requested right after the loss of the current one, into the same registers)
   auto fetch_tile_loss_inputs = [&](int64_t s0) {
-    if (tid < BM && s0 + tid < a.S) lin_next = fn.load_with(s0 + tid, lentry);
+    if (tid < BM) lin_next = fn.template load_with<true>(min(s0 + tid, a.S - 1), lentry);
   };
-  auto store_tile_inputs = [&]() {
-    float* const xdst = Xs + xrow_l * px - xoff;
+  auto store_tile_inputs = [&](float* Xdst) {
+    float* const xdst = Xdst + xrow_l * px - xoff;
 #pragma unroll
     for (int p = 0; p < XV; ++p) {
       const float v[4] = {xr[p].x, xr[p].y, xr[p].z, xr[p].w};
@@ -210,37 +304,45 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
     }
   };
   const int64_t ntiles = (a.S + BM - 1) / BM;
-  const int kpad1 = 16 * ((a.Din + 15) / 16);  // layer 1 contracts over the input width rounded up to a k group (W1 is zero-padded to it)
   int64_t tile = blockIdx.x;
   if (tile < ntiles) {
     fetch_tile_entries(tile * BM);
     fetch_tile_inputs(tile * BM);
     fetch_tile_loss_inputs(tile * BM);
+    if (MARL_FT_ENTRIES_LATE) fetch_tile_entries((tile + gridDim.x) * BM);
   }
 #ifdef MARL_PHASE_TIMERS
   long long phase_t0_ = (long long)__builtin_amdgcn_s_memtime();
 #endif
-  for (; tile < ntiles; tile += gridDim.x) {
+  if (XDB && tile < ntiles) {
+    store_tile_inputs(Xs0);
+    __syncthreads();
+  }
+  PhaseW<KG1> pw1;  // layer 1's weights: the first half requested before dW1 of the tile before (here for the first tile)
+  phase_w_request<H, KG1, 0, KG1 / 2>(pw1, rsW1, wlane, kpad1 / 16);
+  for (int it = 0; tile < ntiles; tile += gridDim.x, ++it) {
     const int64_t s0 = tile * BM;
     const bool have_next = tile + gridDim.x < ntiles;
-    // (the first weight groups of a layer are requested ahead of the barrier or epilogue in front of it)
-    const PhaseB pb1 = gemm_phase_prefetch<H>(a.W1s + (hi * H + nt * 32 + lo) * 4, kpad1 / 16);
-    // ---- this tile's observations to LDS
-    store_tile_inputs();
-    if (have_next) fetch_tile_entries((tile + gridDim.x) * BM);
-    __syncthreads();
+    float* const Xs = XDB ? Xs0 + (it & 1) * BM * px : Xs0;
+    if (!XDB) {  // ---- this tile's observations to LDS
+      store_tile_inputs(Xs);
+    }
+    if (!MARL_FT_ENTRIES_LATE) fetch_tile_entries((tile + gridDim.x) * BM);
+    if (!XDB) __syncthreads();
 
     PHASE_MARK(0);
     floatx16 acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
     // ---- layer 1
-    gemm_phase_regs<H, true>(Xs + (mt * 32 + lo) * px + 4 * hi, a.W1s + (hi * H + nt * 32 + lo) * 4, kpad1 / 16, acc, pb1);
-    const PhaseB pb2 = gemm_phase_prefetch<H>(a.W2s + (hi * H + nt * 32 + lo) * 4, H / 16);
+    phase_w_request<H, KG1, KG1 / 2, KG1>(pw1, rsW1, wlane, kpad1 / 16);
+    gemm_phase_w<KG1>(Xs + (mt * 32 + lo) * px + 4 * hi, kpad1 / 16, acc, pw1);
+    PhaseW<KG2> pw2;  // layer 2's weights arrive during the tanh epilogue of layer 1
+    phase_w_request<H, KG2>(pw2, rsW2, wlane, KG2);
     PHASE_MARK(1);
     {
       const int n = nt * 32 + lo;
-      const float bias = a.b1[n];
+      const float bias = bias1;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int m = mt * 32 + 8 * (r / 4) + 4 * hi + (r % 4);
@@ -253,13 +355,13 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
     PHASE_MARK(2);
     // ---- layer 2
     __syncthreads();  // the h1 tile is complete
-    gemm_phase_regs<H, true>(H1 + (mt * 32 + lo) * PH + 4 * hi, a.W2s + (hi * H + nt * 32 + lo) * 4, H / 16, acc, pb2);
+    gemm_phase_w<KG2>(H1 + (mt * 32 + lo) * PH + 4 * hi, KG2, acc, pw2);
     PHASE_MARK(3);
-    if (have_next) fetch_tile_inputs((tile + gridDim.x) * BM);  // lands during the ALU phases and dW2
+    fetch_tile_inputs((tile + gridDim.x) * BM);  // lands during the ALU phases and dW2
     floatx16 h2r;  // h2 of this wavefront's tile
     {
       const int n = nt * 32 + lo;
-      const float bias = a.b2[n];
+      const float bias = bias2;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int m = mt * 32 + 8 * (r / 4) + 4 * hi + (r % 4);
@@ -303,7 +405,7 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
       float out[NOUT], dl[NOUT];
 #pragma unroll
       for (int k = 0; k < NOUT; ++k) {
-        float v = a.b3[k];
+        float v = b3s[k];
 #pragma unroll
         for (int gq = 0; gq < GROUPS; ++gq) v += red[(gq * NOUT + k) * BM + tid];
         out[k] = v;
@@ -321,7 +423,11 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
 #pragma unroll
       for (int k = 0; k < 5; ++k) accS[tid * AS + NOUT + k] += st[k];
     }
-    if (have_next) fetch_tile_loss_inputs((tile + gridDim.x) * BM);
+    fetch_tile_loss_inputs((tile + gridDim.x) * BM);
+    // the gather entries of the tile after the next: requested here, where the next wait on a global load (the weights
+    // of the dz1 product) is a whole dW2 phase away, and not in front of layer 1, whose first in-loop weight group
+    // would wait for them (loads return in order)
+    if (MARL_FT_ENTRIES_LATE) fetch_tile_entries((tile + 2 * (int64_t)gridDim.x) * BM);
     __syncthreads();
     PHASE_MARK(6);
     // ---- W3 gradient: gW3[i][k] += sum_s h2[s][i] dl[s][k]   (thread -> hidden unit tid % H, a share of the samples)
@@ -367,7 +473,8 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
     }
     __syncthreads();
     PHASE_MARK(8);
-    const PhaseB pbz = gemm_phase_prefetch<H>(a.W2Ts + (hi * H + nt * 32 + lo) * 4, H / 16);
+    PhaseW<KG2> pwz;  // the first half of the dz1 product's weights arrives during dW2, whose operands are all in LDS
+    phase_w_request<H, KG2, 0, KG2 / 2>(pwz, rsW2T, wlane, KG2);
     // ---- dW2 += h1^T dz2   (k runs over the samples of the tile)
     {
       const int t0 = (wave * DW2_TPW) % (NTN * NTN);
@@ -380,7 +487,8 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
     // ---- dz1 = (dz2 W2^T) * (1 - h1^2), in place over h1
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-    gemm_phase_regs<H, true>(H2 + (mt * 32 + lo) * PH + 4 * hi, a.W2Ts + (hi * H + nt * 32 + lo) * 4, H / 16, acc, pbz);
+    phase_w_request<H, KG2, KG2 / 2, KG2>(pwz, rsW2T, wlane, KG2);
+    gemm_phase_w<KG2>(H2 + (mt * 32 + lo) * PH + 4 * hi, KG2, acc, pwz);
     __syncthreads();  // every wavefront is done reading h1 (dW2) before its tiles are overwritten
     PHASE_MARK(10);
     {
@@ -397,16 +505,12 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
       csum += __shfl_xor(csum, 32);
       gb1r += csum;
     }
+    if (XDB && have_next) store_tile_inputs(Xs0 + ((it & 1) ^ 1) * BM * px);  // the next tile's observations
     __syncthreads();
     PHASE_MARK(11);
-    // ---- dW1 += X^T dz1
-#pragma unroll
-    for (int q = 0; q < Q1; ++q) {
-      int t, kb0, klen;
-      if (dw1_item(q, t, kb0, klen)) {
-        outer_product_accumulate<1>(Xs + (t / NTN) * 32 + lo, px, H1 + (t % NTN) * 32 + lo, PH, kb0, klen, hi, &acc1[q]);
-      }
-    }
+    // ---- dW1 += X^T dz1   (the next tile's layer-1 weights arrive meanwhile)
+    phase_w_request<H, KG1, 0, KG1 / 2>(pw1, rsW1, wlane, kpad1 / 16);
+    outer_product_accumulate_rows<Q1>(Xs + lo, px, H1 + (wave % NTN) * 32 + lo, PH, (wave / NTN) * KLEN1, KLEN1, hi, acc1);
     PHASE_MARK(12);
     __syncthreads();  // the tile buffers are reused by the next row tile
     PHASE_MARK(13);
@@ -452,30 +556,27 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
     }
   }
 #pragma unroll
-  for (int q = 0; q < Q1; ++q) {  // dW1: the wavefronts that share a tile are neighbours with the same slot q
-    int t, kb0, klen;
-    const bool have = dw1_item(q, t, kb0, klen);
-    const int rank = have ? kb0 / klen : 0, shares = have ? BM / klen : 1;
-    if (own) {
-      if (have && rank > 0) {
+  for (int q = 0; q < Q1; ++q) {  // dW1: the wavefronts wave % NTN + NTN k hold the shares of a tile
+    const int rank = wave / NTN, jt = wave % NTN;
+    if (own && KS1 > 1) {
+      if (rank > 0) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) L[wave * 1024 + r * 64 + lane] = acc1[q][r];
       }
       __syncthreads();
-      if (have && rank == 0) {
+      if (rank == 0) {
 #pragma unroll 1
-        for (int k = 1; k < shares; ++k) {
+        for (int k = 1; k < KS1; ++k) {
 #pragma unroll
-          for (int r = 0; r < 16; ++r) acc1[q][r] += L[(wave + k) * 1024 + r * 64 + lane];
+          for (int r = 0; r < 16; ++r) acc1[q][r] += L[(wave + k * NTN) * 1024 + r * 64 + lane];
         }
       }
       __syncthreads();
     }
-    if (have && (!own || rank == 0)) {
-      const int dt = t / NTN, jt = t % NTN;
+    if (!own || rank == 0) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int d = dt * 32 + 8 * (r / 4) + 4 * hi + (r % 4), j = jt * 32 + lo;
+        const int d = q * 32 + 8 * (r / 4) + 4 * hi + (r % 4), j = jt * 32 + lo;
         if (d < a.Din) {
           if (own) gW1[d * H + j] = acc1[q][r];
           else atomicAdd(&gW1[d * H + j], acc1[q][r]);
@@ -554,8 +655,8 @@ inline int fused_train_px(int Din) {
 template <int H, int BM, int NOUT, int DMAX, int NW, class LossFn>
 inline int32_t launch_fused_train_inst(const FusedTrainArgs& a, const LossFn& fn, hipStream_t s) {
   auto kern = fused_train_kernel<H, BM, NOUT, DMAX, NW, LossFn>;
-  const size_t floats = (size_t)BM * a.px + 2 * (size_t)BM * (H + 4) + 64 * NW * NOUT + BM * 8 + H * NOUT + 4 + (BM < 64 ? 64 : BM) * (NOUT + 5);
-  const size_t bytes = floats * 4;
+  constexpr bool XDB = MARL_FT_XDB && fused_train_lds_floats(H, BM, NOUT, NW, DMAX + 4, 2) * 4 <= 160 * 1024;  // as in the kernel
+  const size_t bytes = fused_train_lds_floats(H, BM, NOUT, NW, a.px, XDB ? 2 : 1) * 4;
   static bool configured = false;  // per instantiation
   if (!configured) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
@@ -574,9 +675,14 @@ constexpr int kFusedTrainMaxGrid = 512;
 
 template <int NOUT, class LossFn>
 inline int32_t launch_fused_train(int H, const FusedTrainArgs& a, const LossFn& fn, hipStream_t s) {
+  // the kernel divides sample indices by the rows' and the loss's agent counts with SmallDiv's product
+  if (!small_div_ok(a.X.pd, a.S) || !small_div_ok(fn.lc.ad, a.S)) return MARL_E_SIZE;
   // algorithmic flops: forward 2S(DH + HH), backward 2S(HH + HH + DH)
   TimedLaunch timed(KC_FUSED_TRAIN, 2.0 * (double)a.S * (2.0 * a.Din * H + 3.0 * H * H), s);
   if (H == 128) {
+#ifdef MARL_FT_NW4
+    if (a.Din > 29) return launch_fused_train_inst<128, 32, NOUT, 96, 4, LossFn>(a, fn, s);
+#endif
     if (a.Din <= 29) return launch_fused_train_inst<128, 64, NOUT, 32, 8, LossFn>(a, fn, s);
     return launch_fused_train_inst<128, 64, NOUT, 96, 8, LossFn>(a, fn, s);
   }

@@ -15,6 +15,32 @@ namespace marl {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
+// Division of a sample index by a small run-time divisor (agents per row) without the 64-bit division sequence,
+// which is about 180 vector instructions and sat on the critical path of every row tile: for s < 2^31 and
+// d <= 64, s / d = (s * magic) >> shift exactly, with magic = floor(2^shift / d) + 1 and
+// shift = 31 + ceil(log2 d) (the error term s * (magic * d - 2^shift) stays below 2^shift; d = 1 gives
+// magic 2^31 + 1, shift 31).  div<true> is that product and nothing else -- the caller has checked on the host that
+// the divisor has a magic number and that every index is below 2^31 (small_div_ok); div<false> is the plain division.
+// (One function that chooses at run time keeps the long sequence in the instruction stream and was slower.)
+struct SmallDiv {
+  uint32_t magic = 0;
+  int shift = 0;
+  template <bool FAST>
+  __device__ __forceinline__ int64_t div(int64_t s, int d) const {
+    if (FAST) return (int64_t)(((uint64_t)(uint32_t)s * magic) >> shift);
+    return s / d;
+  }
+};
+inline SmallDiv make_small_div(int d) {
+  SmallDiv v;
+  if (d < 1 || d > 64) return v;
+  int lg = 0;
+  while ((1 << lg) < d) ++lg;
+  v.shift = 31 + lg;
+  v.magic = (uint32_t)(((uint64_t)1 << v.shift) / (uint64_t)d + 1);
+  return v;
+}
+
 // Rows of a matrix: row r = base + (src(r/per) * per + r%per) * ld, src = gather ? gather[.] : identity.
 struct RowSrc {
   const float* base;
@@ -22,6 +48,7 @@ struct RowSrc {
   const int32_t* gather;
   int per;
   int64_t nrows;
+  SmallDiv pd{};  // make_small_div(per), or default
   __device__ __forceinline__ const float* ptr(int64_t r) const {
     if (r >= nrows) return nullptr;
     if (gather == nullptr) return base + r * ld;
@@ -30,13 +57,19 @@ struct RowSrc {
     return base + ((int64_t)gather[g] * per + a) * ld;
   }
   // The same address in two steps, so that the gather entry can be fetched long before the row is.
-  __device__ __forceinline__ int32_t gather_entry(int64_t r) const { return gather == nullptr ? 0 : gather[r / per]; }
+  template <bool FAST = false>
+  __device__ __forceinline__ int32_t gather_entry(int64_t r) const {
+    return gather == nullptr ? 0 : gather[pd.div<FAST>(r, per)];
+  }
+  template <bool FAST = false>
   __device__ __forceinline__ const float* ptr_with(int64_t r, int32_t entry) const {
     if (gather == nullptr) return base + r * ld;
-    const int a = (int)(r % per);
+    const int a = (int)(r - pd.div<FAST>(r, per) * per);
     return base + ((int64_t)entry * per + a) * ld;
   }
 };
+// div<true> may be used for indices below `count` with this divisor
+inline bool small_div_ok(const SmallDiv& v, int64_t count) { return v.magic != 0 && count < ((int64_t)1 << 31); }
 
 enum GemmMode { GEMM_NN = 0, GEMM_NT = 1, GEMM_TN = 2 };
 enum GemmEpi {

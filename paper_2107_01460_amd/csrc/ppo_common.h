@@ -23,6 +23,7 @@ struct Scalars {
 struct LossCommon {
   const int32_t* rows;  // [rows_mb] trajectory row of each minibatch row
   int A;
+  SmallDiv ad;          // make_small_div(A)
   int64_t rows_mb;
   float inv_B;  // 1 / (rows_mb * A)
   const Scalars* sc;
@@ -128,9 +129,12 @@ struct ActorLoss {
   };
   // the trajectory values of minibatch sample s (separate from the arithmetic so that they can be fetched early);
   // row_entry / load_with split the dependent pair of loads so that the first can be issued a phase ahead
-  __device__ __forceinline__ int32_t row_entry(int64_t s) const { return lc.rows[s / lc.A]; }
+  // (FAST: the magic-number division of SmallDiv, for callers that have checked small_div_ok(lc.ad, samples))
+  template <bool FAST = false>
+  __device__ __forceinline__ int32_t row_entry(int64_t s) const { return lc.rows[lc.ad.div<FAST>(s, lc.A)]; }
+  template <bool FAST = false>
   __device__ __forceinline__ In load_with(int64_t s, int32_t entry) const {
-    const int a = (int)(s % lc.A);
+    const int a = (int)(s - lc.ad.div<FAST>(s, lc.A) * lc.A);
     const int64_t src = (int64_t)entry * lc.A + a;
     return In{action[src], logp_old[src], adv[src]};
   }
@@ -195,13 +199,15 @@ struct CriticLoss {
   struct In {
     float ret[kMaxAgents], v_old[kMaxAgents];
   };
-  __device__ __forceinline__ int32_t row_entry(int64_t s) const { return lc.rows[per_row == 1 ? s / lc.A : s]; }
+  template <bool FAST = false>
+  __device__ __forceinline__ int32_t row_entry(int64_t s) const { return lc.rows[per_row == 1 ? lc.ad.div<FAST>(s, lc.A) : s]; }
   __device__ __forceinline__ In load(int64_t s) const { return load_with(s, row_entry(s)); }
   __device__ __forceinline__ LossPrep prepare() const { return LossPrep{0.f, 1.f}; }
+  template <bool FAST = false>
   __device__ __forceinline__ In load_with(int64_t s, int32_t entry) const {
     In in;
     if (per_row == 1) {
-      const int a = (int)(s % lc.A);
+      const int a = (int)(s - lc.ad.div<FAST>(s, lc.A) * lc.A);
       const int64_t src = (int64_t)entry * lc.A + a;
       in.ret[0] = ret[src];
       in.v_old[0] = v_old[src];

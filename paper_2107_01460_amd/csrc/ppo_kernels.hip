@@ -547,17 +547,17 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
       const int32_t* rows = (perm ? perm + (int64_t)e * R : w.ident) + (int64_t)mb * rows_mb;
       const float* eff = effective_params(c, params, w.eff_params, s);
       LossCommon lc{};
-      lc.rows = rows; lc.A = d.A; lc.rows_mb = rows_mb; lc.inv_B = (float)(1.0 / (double)(rows_mb * d.A));
+      lc.rows = rows; lc.A = d.A; lc.ad = make_small_div(d.A); lc.rows_mb = rows_mb; lc.inv_B = (float)(1.0 / (double)(rows_mb * d.A));
       lc.sc = sck; lc.adv_stats = w.adv_stats + 2 * step; lc.normalize = c.normalize_adv; lc.clip_eps = c.clip_eps;
       lc.ent_coef = c.ent_coef; lc.vf_coef = c.vf_coef; lc.clip_value = c.clip_value;
       // ---- actor
-      const RowSrc Xa{tr.obs, d.D, rows, d.A, Sa};
+      const RowSrc Xa{tr.obs, d.D, rows, d.A, Sa, make_small_div(d.A)};
       const bool fused_a = fused_forward_supported(d.Ha, d.D);
       {
         ActorLoss fn{lc, tr.action, tr.logp, tr.adv};
         if (d.bf16) {
           train_net_bf16<kActions>(Xa, Sa, d.D, d.Ha, effective_bf16_weights(c, eff, 0), eff, oa, w.grad, ga, fn, w.dla, wk, false, s);
-        } else if (fused_train_supported(d.Ha, d.D)) {
+        } else if (fused_train_supported(d.Ha, d.D) && Sa < ((int64_t)1 << 31)) {
           FusedTrainArgs ta{};
           ta.X = Xa; ta.S = Sa; ta.Din = d.D; ta.px = fused_train_px(d.D);
           ta.W1 = eff + oa.W1; ta.b1 = eff + oa.b1; ta.W2 = eff + oa.W2; ta.b2 = eff + oa.b2; ta.W3 = eff + oa.W3;
@@ -588,14 +588,14 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
         }
       }
       // ---- critic
-      const RowSrc Xc{tr.obs, d.Dc, rows, d.central ? 1 : d.A, Sc};
+      const RowSrc Xc{tr.obs, d.Dc, rows, d.central ? 1 : d.A, Sc, make_small_div(d.central ? 1 : d.A)};
       const bool fused_c = fused_forward_supported(d.Hc, d.Dc);
       {
         CriticLoss fn{lc, tr.ret, tr.value, d.central ? d.A : 1};
         if (d.bf16) {
           // IPPO: the critic reads the rows the actor has just packed (same rows, same width)
           train_net_bf16<1>(Xc, Sc, d.Dc, d.Hc, effective_bf16_weights(c, eff, 1), eff, oc, w.grad, gc, fn, w.dlc, wk, !d.central, s);
-        } else if (fused_train_supported(d.Hc, d.Dc)) {
+        } else if (fused_train_supported(d.Hc, d.Dc) && Sc < ((int64_t)1 << 31)) {
           FusedTrainArgs ta{};
           ta.X = Xc; ta.S = Sc; ta.Din = d.Dc; ta.px = fused_train_px(d.Dc);
           ta.W1 = eff + oc.W1; ta.b1 = eff + oc.b1; ta.W2 = eff + oc.W2; ta.b2 = eff + oc.b2; ta.W3 = eff + oc.W3;

@@ -720,7 +720,7 @@ int32_t launch_ppo_update_recurrent(const marl_config& c, marl_traj tr, marl_rec
       hipLaunchKernelGGL(zero_step_kernel, dim3(blocks_for(d.P)), dim3(256), 0, s, w.grad, d.P, w.sc, 1, (double*)nullptr, 0);
       hipLaunchKernelGGL(seq_index_kernel, dim3(blocks_for(TJ)), dim3(256), 0, s, envs, tr.done, (int)J, d.N, d.T, w.rows, w.keep);
       LossCommon lc{};
-      lc.rows = w.rows; lc.A = d.A; lc.rows_mb = TJ; lc.inv_B = (float)(1.0 / (double)(TJ * d.A));
+      lc.rows = w.rows; lc.A = d.A; lc.ad = make_small_div(d.A); lc.rows_mb = TJ; lc.inv_B = (float)(1.0 / (double)(TJ * d.A));
       lc.sc = w.sc; lc.adv_stats = &w.sc->adv_sum; lc.normalize = c.normalize_adv; lc.clip_eps = c.clip_eps; lc.ent_coef = c.ent_coef;
       lc.vf_coef = c.vf_coef; lc.clip_value = c.clip_value;
       if (c.normalize_adv) {
