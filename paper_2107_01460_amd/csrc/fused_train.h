@@ -20,6 +20,12 @@
 
 namespace marl {
 
+#ifndef MARL_FT_HALF1
+#define MARL_FT_HALF1 1
+#endif
+#ifndef MARL_FT_HALFZ
+#define MARL_FT_HALFZ 0
+#endif
 #ifndef MARL_FT_XDB
 #define MARL_FT_XDB 1
 #endif
@@ -319,7 +325,7 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
     __syncthreads();
   }
   PhaseW<KG1> pw1;  // layer 1's weights: the first half requested before dW1 of the tile before (here for the first tile)
-  phase_w_request<H, KG1, 0, KG1 / 2>(pw1, rsW1, wlane, kpad1 / 16);
+  phase_w_request<H, KG1, 0, (MARL_FT_HALF1 ? KG1 / 2 : KG1)>(pw1, rsW1, wlane, kpad1 / 16);
   for (int it = 0; tile < ntiles; tile += gridDim.x, ++it) {
     const int64_t s0 = tile * BM;
     const bool have_next = tile + gridDim.x < ntiles;
@@ -335,7 +341,7 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
     // ---- layer 1
-    phase_w_request<H, KG1, KG1 / 2, KG1>(pw1, rsW1, wlane, kpad1 / 16);
+    phase_w_request<H, KG1, (MARL_FT_HALF1 ? KG1 / 2 : KG1), KG1>(pw1, rsW1, wlane, kpad1 / 16);
     gemm_phase_w<KG1>(Xs + (mt * 32 + lo) * px + 4 * hi, kpad1 / 16, acc, pw1);
     PhaseW<KG2> pw2;  // layer 2's weights arrive during the tanh epilogue of layer 1
     phase_w_request<H, KG2>(pw2, rsW2, wlane, KG2);
@@ -474,7 +480,7 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
     __syncthreads();
     PHASE_MARK(8);
     PhaseW<KG2> pwz;  // the first half of the dz1 product's weights arrives during dW2, whose operands are all in LDS
-    phase_w_request<H, KG2, 0, KG2 / 2>(pwz, rsW2T, wlane, KG2);
+    phase_w_request<H, KG2, 0, (MARL_FT_HALFZ ? KG2 / 2 : KG2)>(pwz, rsW2T, wlane, KG2);
     // ---- dW2 += h1^T dz2   (k runs over the samples of the tile)
     {
       const int t0 = (wave * DW2_TPW) % (NTN * NTN);
@@ -487,7 +493,7 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
     // ---- dz1 = (dz2 W2^T) * (1 - h1^2), in place over h1
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-    phase_w_request<H, KG2, KG2 / 2, KG2>(pwz, rsW2T, wlane, KG2);
+    phase_w_request<H, KG2, (MARL_FT_HALFZ ? KG2 / 2 : KG2), KG2>(pwz, rsW2T, wlane, KG2);
     gemm_phase_w<KG2>(H2 + (mt * 32 + lo) * PH + 4 * hi, KG2, acc, pwz);
     __syncthreads();  // every wavefront is done reading h1 (dW2) before its tiles are overwritten
     PHASE_MARK(10);
@@ -509,7 +515,7 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
     __syncthreads();
     PHASE_MARK(11);
     // ---- dW1 += X^T dz1   (the next tile's layer-1 weights arrive meanwhile)
-    phase_w_request<H, KG1, 0, KG1 / 2>(pw1, rsW1, wlane, kpad1 / 16);
+    phase_w_request<H, KG1, 0, (MARL_FT_HALF1 ? KG1 / 2 : KG1)>(pw1, rsW1, wlane, kpad1 / 16);
     outer_product_accumulate_rows<Q1>(Xs + lo, px, H1 + (wave % NTN) * 32 + lo, PH, (wave / NTN) * KLEN1, KLEN1, hi, acc1);
     PHASE_MARK(12);
     __syncthreads();  // the tile buffers are reused by the next row tile
