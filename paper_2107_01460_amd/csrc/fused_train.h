@@ -686,9 +686,6 @@ inline int32_t launch_fused_train(int H, const FusedTrainArgs& a, const LossFn& 
   // algorithmic flops: forward 2S(DH + HH), backward 2S(HH + HH + DH)
   TimedLaunch timed(KC_FUSED_TRAIN, 2.0 * (double)a.S * (2.0 * a.Din * H + 3.0 * H * H), s);
   if (H == 128) {
-#ifdef MARL_FT_NW4
-    if (a.Din > 29) return launch_fused_train_inst<128, 32, NOUT, 96, 4, LossFn>(a, fn, s);
-#endif
     if (a.Din <= 29) return launch_fused_train_inst<128, 64, NOUT, 32, 8, LossFn>(a, fn, s);
     return launch_fused_train_inst<128, 64, NOUT, 96, 8, LossFn>(a, fn, s);
   }
