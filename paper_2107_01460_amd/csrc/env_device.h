@@ -18,21 +18,68 @@ __device__ __forceinline__ int e_row(uint32_t e) { return (int)(e & 0xff); }
 __device__ __forceinline__ int e_col(uint32_t e) { return (int)((e >> 8) & 0xff); }
 __device__ __forceinline__ int e_lvl(uint32_t e) { return (int)((e >> 16) & 0xff); }
 
-// New episode for one env, entirely in registers (every loop is unrolled over the at most 16 entities, so the
-// arrays never leave the register file).  Draw order: A agent levels, A + F cells (agents first), F food levels;
-// draw j is word j % 4 of Philox call j / 4 of the stream (env, episode).
-template <int CA, int CF>
-__device__ __forceinline__ void reset_regs(uint32_t ag[CA], uint32_t fd[CF], const EnvParams& p,
-                                           uint32_t env, uint32_t episode) {
-  constexpr int kMaxEnt = CA + CF;
-  uint32_t buf[4] = {0, 0, 0, 0};
-  int j = 0;
-  auto draw = [&]() -> uint32_t {
-    if ((j & 3) == 0) philox4x32_10(env, episode, (uint32_t)(j >> 2), kStreamReset, p.k0, p.k1, buf);
+// The draws of a new episode: draw j is word j % 4 of Philox call j / 4 of the stream (env, episode).
+// SHARE = false: the lane computes every call itself.  SHARE = true: the A lanes of the env's agents (consecutive lanes
+// of one wavefront, this one being agent a_idx, all of them in here together because the episode ended for the env)
+// split the calls -- lane a computes calls a, a + A, ... -- and fetch the others' words across lanes: a call is forty
+// quarter-rate multiplies, and every lane of an env computing all of them was a quarter of the env step's time.
+template <int NC, bool SHARE>
+struct ResetDraws {
+  uint32_t buf[4];
+  uint32_t mine[SHARE ? NC : 1][4];
+  int j, A, base;
+  uint32_t env, episode, k0, k1;
+  __device__ __forceinline__ void init(const EnvParams& p, uint32_t env_, uint32_t episode_, int ncalls, int a_idx) {
+    j = 0; A = p.A; env = env_; episode = episode_; k0 = p.k0; k1 = p.k1;
+    buf[0] = buf[1] = buf[2] = buf[3] = 0;
+    base = (int)(threadIdx.x & 63) - a_idx;
+    if (SHARE) {
+#pragma unroll
+      for (int s = 0; s < NC; ++s) {
+        mine[s][0] = mine[s][1] = mine[s][2] = mine[s][3] = 0;
+        const int c = a_idx + s * A;
+        if (c < ncalls) philox4x32_10(env, episode, (uint32_t)c, kStreamReset, k0, k1, mine[s]);
+      }
+    }
+  }
+  __device__ __forceinline__ uint32_t draw() {
+    if ((j & 3) == 0) {
+      const int c = j >> 2;
+      if (SHARE) {
+        int own = c, slot = 0;  // call c was computed by agent c % A as its call number c / A (uniform values)
+#pragma unroll
+        for (int q = 0; q < NC; ++q) {
+          const bool more = own >= A;
+          own -= more ? A : 0;
+          slot += more ? 1 : 0;
+        }
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          uint32_t v = mine[0][w];
+#pragma unroll
+          for (int s = 1; s < NC; ++s) v = (slot == s) ? mine[s][w] : v;
+          buf[w] = (uint32_t)__shfl((int)v, base + own);
+        }
+      } else {
+        philox4x32_10(env, episode, (uint32_t)c, kStreamReset, k0, k1, buf);
+      }
+    }
     const int w = j & 3;
     ++j;
     return w == 0 ? buf[0] : (w == 1 ? buf[1] : (w == 2 ? buf[2] : buf[3]));
-  };
+  }
+};
+
+// New episode for one env, entirely in registers (every loop is unrolled over the at most 16 entities, so the
+// arrays never leave the register file).  Draw order: A agent levels, A + F cells (agents first), F food levels;
+// draw j is word j % 4 of Philox call j / 4 of the stream (env, episode).
+template <int CA, int CF, bool SHARE = false>
+__device__ __forceinline__ void reset_regs(uint32_t ag[CA], uint32_t fd[CF], const EnvParams& p,
+                                           uint32_t env, uint32_t episode, int a_idx = 0) {
+  constexpr int kMaxEnt = CA + CF;
+  ResetDraws<(2 * kMaxEnt + 3) / 4, SHARE> rd;
+  rd.init(p, env, episode, (2 * (p.A + p.F) + 3) >> 2, a_idx);
+  auto draw = [&]() -> uint32_t { return rd.draw(); };
   int lvl[CA];
 #pragma unroll
   for (int a = 0; a < CA; ++a) lvl[a] = 0;
@@ -216,7 +263,7 @@ __device__ __forceinline__ void forage_transition(uint32_t (&ag)[CA], uint32_t (
   // ---- auto-reset: every lane of a finished env re-seeds it in its own registers (same result in each)
   if (dn) {
     episode += 1;
-    reset_regs<CA, CF>(ag, fd, p, env, episode);
+    reset_regs<CA, CF, true>(ag, fd, p, env, episode, a);
     t = 0;
   }
   rew_out = rew;
@@ -260,18 +307,13 @@ __device__ __forceinline__ bool wh_goal(int G, int r, int c) { return r == G - 1
 
 // New episode: A + F distinct cells (robots first), then L requested shelves.  Draw j is word j % 4 of Philox
 // call j / 4 of the stream (env, episode).
-template <int CA, int CF>
+template <int CA, int CF, bool SHARE = false>
 __device__ __forceinline__ void wh_reset_regs(uint32_t ag[CA], uint32_t fd[CF], const EnvParams& p, uint32_t env,
-                                              uint32_t episode) {
+                                              uint32_t episode, int a_idx = 0) {
   constexpr int kMaxEnt = CA + CF;
-  uint32_t buf[4] = {0, 0, 0, 0};
-  int j = 0;
-  auto draw = [&]() -> uint32_t {
-    if ((j & 3) == 0) philox4x32_10(env, episode, (uint32_t)(j >> 2), kStreamReset, p.k0, p.k1, buf);
-    const int w = j & 3;
-    ++j;
-    return w == 0 ? buf[0] : (w == 1 ? buf[1] : (w == 2 ? buf[2] : buf[3]));
-  };
+  ResetDraws<(kMaxEnt + CF + 3) / 4, SHARE> rd;
+  rd.init(p, env, episode, (p.A + p.F + p.L + 3) >> 2, a_idx);
+  auto draw = [&]() -> uint32_t { return rd.draw(); };
   int chosen[kMaxEnt];  // ascending
 #pragma unroll
   for (int q = 0; q < kMaxEnt; ++q) chosen[q] = 0x7fffffff;
@@ -427,7 +469,7 @@ __device__ __forceinline__ void wh_transition(uint32_t (&ag)[CA], uint32_t (&fd)
   const bool dn = active && (t == p.cap || (p.kind == 2 && collided));
   if (dn) {
     episode += 1;
-    wh_reset_regs<CA, CF>(ag, fd, p, env, episode);
+    wh_reset_regs<CA, CF, true>(ag, fd, p, env, episode, a);
     t = 0;
   }
   rew_out = rew;
