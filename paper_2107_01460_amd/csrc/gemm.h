@@ -199,6 +199,57 @@ __device__ __forceinline__ void gemm_phase_regs(const float* __restrict__ As, co
   }
 }
 
+// All B fragments of one product against weights, for this lane: KG groups of 16 along k, two 16-byte loads each
+// (operand-order copy: element (k, n) at ((k / 4) * LDB + n) * 4 + k % 4; lane_off is this lane's offset
+// (hi * LDB + n) * 4 in floats).  The loads are buffer loads -- a resource descriptor in scalar registers, ONE vector
+// register with the lane's byte offset for all of them, the group's offset as a scalar: as global loads each of them
+// got a 64-bit address register pair of its own, computed outside the tile loop and kept (or spilled) across it.  The whole set is requested one phase AHEAD of the product that uses it -- during the element-wise epilogue
+// or the LDS-only product in front of it -- so that the product never waits for the L2: with two or three groups in
+// flight (gemm_phase_regs) every workgroup of the chip asks the same few cache lines at the same moment and the
+// answers take longer than the 16 matrix instructions that were meant to cover them.
+template <int KG>
+struct PhaseW {
+  float4 w[KG][2];
+};
+typedef __amdgpu_buffer_rsrc_t WeightRsrc;
+// descriptor of `floats` floats at p (raw buffer, no swizzle; reads past the end return zero)
+__device__ __forceinline__ WeightRsrc weight_rsrc(const float* p, int floats) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p), (short)0, floats * 4, 0x00020000);
+}
+template <int LDB, int KG, int G0 = 0, int G1 = KG>  // groups G0 .. G1 - 1
+__device__ __forceinline__ void phase_w_request(PhaseW<KG>& pw, WeightRsrc B, int lane_off, int kgroups) {
+#pragma unroll
+  for (int g = G0; g < G1; ++g) {
+    const int gc = g < kgroups ? g : kgroups - 1;  // past the end: the last group again (never used)
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+      pw.w[g][u] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(B, lane_off * 4, (16 * gc + 8 * u) * LDB * 4, 0));
+  }
+}
+// acc += A B for this wavefront's 32x32 tile: A rows in LDS (As points at this lane's row, + 4 * hi; the fragments of
+// the next group are read before the matrix instructions of the current one), B from pw.
+template <int KG>
+__device__ __forceinline__ void gemm_phase_w(const float* __restrict__ As, int kgroups, floatx16& acc, const PhaseW<KG>& pw) {
+  float4 av[2][2];
+  av[0][0] = *reinterpret_cast<const float4*>(As);
+  av[0][1] = *reinterpret_cast<const float4*>(As + 8);
+#pragma unroll
+  for (int g = 0; g < KG; ++g) {
+    if (g < kgroups) {  // uniform
+      const int gn = g + 1 < kgroups ? g + 1 : g;
+      av[(g + 1) & 1][0] = *reinterpret_cast<const float4*>(As + 16 * gn);
+      av[(g + 1) & 1][1] = *reinterpret_cast<const float4*>(As + 16 * gn + 8);
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const float af[4] = {av[g & 1][u].x, av[g & 1][u].y, av[g & 1][u].z, av[g & 1][u].w};
+        const float bf[4] = {pw.w[g][u].x, pw.w[g][u].y, pw.w[g][u].z, pw.w[g][u].w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(af[j], bf[j], acc, 0, 0, 0);
+      }
+    }
+  }
+}
+
 constexpr int kGemmBK = 16;
 
 template <int MODE, int EPI, int BM, int BN, int WGM, int WGN>

@@ -56,7 +56,7 @@ __device__ __forceinline__ float log_softmax_fast(const float lg[kActions], int 
 }
 
 template <int H, int BM, int V, int CA, int KIND, bool EVAL>
-__global__ void __launch_bounds__(256) rollout_fused_kernel(RolloutFusedArgs a) {
+__global__ void __launch_bounds__(256, (H == 64 && CA <= 2) ? 3 : 1) rollout_fused_kernel(RolloutFusedArgs a) {
   constexpr int D = 3 * V * V, PH = H + 4, GROUPS = 256 / BM, NOUT = kActions;
   constexpr int NTN = H / 32, MT = BM / 32, TILES = MT * NTN;
   static_assert(TILES == 4, "one 32x32 MFMA tile per wavefront");
@@ -152,6 +152,12 @@ __global__ void __launch_bounds__(256) rollout_fused_kernel(RolloutFusedArgs a) 
     }
   };
 
+  // the weights of a whole layer are requested a phase ahead (buffer loads: one descriptor, one lane offset)
+  constexpr int KG1 = (D + 15) / 16, KG2 = H / 16;
+  const int wlane = (hi * H + nt * 32 + lo) * 4;
+  const WeightRsrc rsW1 = weight_rsrc(a.W1s, a.kpad1 * H), rsW2 = weight_rsrc(a.W2s, H * H);
+  PhaseW<KG1> pw1;
+  phase_w_request<H, KG1>(pw1, rsW1, wlane, a.kpad1 / 16);
   for (int t = 0;; ++t) {
     __syncthreads();  // the windows (and the noise) of step t are complete
     if (t == a.T) {
@@ -163,7 +169,9 @@ __global__ void __launch_bounds__(256) rollout_fused_kernel(RolloutFusedArgs a) 
     floatx16 acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-    gemm_phase_regs<H>(Xs + (mt * 32 + lo) * px + 4 * hi, a.W1s + (hi * H + nt * 32 + lo) * 4, a.kpad1 / 16, acc);
+    gemm_phase_w<KG1>(Xs + (mt * 32 + lo) * px + 4 * hi, a.kpad1 / 16, acc, pw1);
+    PhaseW<KG2> pw2;  // layer 2's weights arrive during the tanh of layer 1
+    phase_w_request<H, KG2>(pw2, rsW2, wlane, KG2);
     {
       const int col = nt * 32 + lo;
 #pragma unroll
@@ -176,7 +184,8 @@ __global__ void __launch_bounds__(256) rollout_fused_kernel(RolloutFusedArgs a) 
     // ---- layer 2: h2 = tanh(h1 W2 + b2)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-    gemm_phase_regs<H>(Hs + (mt * 32 + lo) * PH + 4 * hi, a.W2s + (hi * H + nt * 32 + lo) * 4, H / 16, acc);
+    gemm_phase_w<KG2>(Hs + (mt * 32 + lo) * PH + 4 * hi, KG2, acc, pw2);
+    phase_w_request<H, KG1>(pw1, rsW1, wlane, a.kpad1 / 16);  // layer 1 of the next step
     __syncthreads();  // every wavefront is past its last read of h1
     {
       const int col = nt * 32 + lo;
