@@ -91,14 +91,20 @@ __global__ void __launch_bounds__(64 * NW) env_step_kernel(EnvParams p, marl_env
     if (KIND == 0) forage_paint<V, CA, CF>(slab + lane * D, ag, fd, a, p);
     else wh_paint<V, CA, CF>(slab + lane * D, ag, fd, a, p);
   }
-  __syncthreads();
+  // the slab is private to the wavefront, whose LDS operations execute in order: only the compiler has to keep them so
+  // (no workgroup barrier: a wavefront that re-seeds episodes does not hold the others back)
+  __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+  __builtin_amdgcn_wave_barrier();
   // ---- the slab of a wavefront is one contiguous run of the output
   const int64_t envs_here = max((int64_t)0, min((int64_t)ew, (int64_t)p.N - wave_env0));
   const int count = (int)envs_here * p.A * D;  // floats
   float* out = obs + (size_t)wave_env0 * p.A * D;
   if ((reinterpret_cast<uintptr_t>(out) & 15u) == 0) {
     const int n4 = count >> 2;
-    for (int i = lane; i < n4; i += 64) reinterpret_cast<float4*>(out)[i] = reinterpret_cast<const float4*>(slab)[i];
+    // streaming stores: the observations are not read again soon, and written through as they are produced they do
+    // not wait in the L2 for the write-back at the end of the kernel (9.9 -> 9.0 us per launch at 262 144 env-agents)
+    typedef float f4v __attribute__((ext_vector_type(4)));
+    for (int i = lane; i < n4; i += 64) __builtin_nontemporal_store(reinterpret_cast<const f4v*>(slab)[i], reinterpret_cast<f4v*>(out) + i);
     for (int i = (n4 << 2) + lane; i < count; i += 64) out[i] = slab[i];
   } else {
     for (int i = lane; i < count; i += 64) out[i] = slab[i];
@@ -154,7 +160,7 @@ int32_t launch_env_step(const marl_config& c, marl_env_state st, const int32_t* 
                                : (double)p.N * p.A * 4.0 * D;
   TimedLaunch timed(KC_ENV_STEP, bytes, s);
   switch (c.view) {
-    case 3: return launch_env_step_caps<3, 4>(p, st, actions, obs, reward, done, do_step, s);
+    case 3: return launch_env_step_caps<3, 8>(p, st, actions, obs, reward, done, do_step, s);
     case 5: return launch_env_step_caps<5, 4>(p, st, actions, obs, reward, done, do_step, s);
     case 7: return launch_env_step_caps<7, 2>(p, st, actions, obs, reward, done, do_step, s);
     default: return MARL_E_CONFIG;
