@@ -536,8 +536,9 @@ __global__ void __launch_bounds__(256 * WM, 1) wacc_gemm_kernel(WaccArgs a) {
       const int f = tid + NT * q;
       if (f < BS * VA) {
         const int r = f / VA, c = 4 * (f % VA);
-        const bool live = tile * BS + r < a.S;
-        stg[q] = live ? *reinterpret_cast<const float4*>(a.A.base + ent[slot * BS + r] + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+        // (unconditional: the entries of rows past the end point at the last row, and those rows of B are zero -- a
+        // load under a branch of its own is waited for before the next one is issued, one memory latency per load)
+        stg[q] = *reinterpret_cast<const float4*>(a.A.base + ent[slot * BS + r] + c);
       }
     }
   };
@@ -554,7 +555,9 @@ __global__ void __launch_bounds__(256 * WM, 1) wacc_gemm_kernel(WaccArgs a) {
       const int f = tid + NT * q;
       const int r = f / (kWregN / 4), c = 4 * (f % (kWregN / 4));
       const int64_t row = tile * BS + r;
-      stg[q] = row < a.S ? *reinterpret_cast<const float4*>(a.B + row * kWregN + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+      float4 v = *reinterpret_cast<const float4*>(a.B + min(row, a.S - 1) * kWregN + c);
+      if (row >= a.S) v = make_float4(0.f, 0.f, 0.f, 0.f);
+      stg[q] = v;
     }
   };
   auto store_b = [&](int stage) {
