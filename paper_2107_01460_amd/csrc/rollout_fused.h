@@ -56,7 +56,7 @@ __device__ __forceinline__ float log_softmax_fast(const float lg[kActions], int 
 }
 
 template <int H, int BM, int V, int CA, int KIND, bool EVAL>
-__global__ void __launch_bounds__(256, (H == 64 && CA <= 2) ? 3 : 1) rollout_fused_kernel(RolloutFusedArgs a) {
+__global__ void __launch_bounds__(256, ((H == 64 && CA <= 2) || (CA <= 4 && V <= 5)) ? 3 : 1) rollout_fused_kernel(RolloutFusedArgs a) {
   constexpr int D = 3 * V * V, PH = H + 4, GROUPS = 256 / BM, NOUT = kActions;
   constexpr int NTN = H / 32, MT = BM / 32, TILES = MT * NTN;
   static_assert(TILES == 4, "one 32x32 MFMA tile per wavefront");
