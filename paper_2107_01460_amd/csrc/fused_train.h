@@ -6,32 +6,23 @@
 //
 // Workgroup = 8 wavefronts, persistent, one per CU.  Row tile = BM samples (64 at H = 128, 128 at H = 64), so
 // that a layer output is 8 MFMA tiles of 32x32, one per wavefront.  The three products against weights (layer 1,
-// layer 2, dz1) take their A operand from the tile in LDS and their B operand straight from the operand-order
-// weight copies in global memory (L2-resident) into registers with 16-byte loads, three k groups in flight: no
-// weight staging buffer and no barrier inside a layer.  Per tile:
-//   X -> LDS | layer 1 -> h1 (LDS) | layer 2 -> h2 (registers + LDS) |
+// layer 2, dz1) take their A operand from the tile in LDS and their B operand from registers: the weights of a whole
+// product are requested one phase ahead (buffer loads from the operand-order copies, L2-resident; see PhaseW in
+// gemm.h), so there is no weight staging buffer, no barrier inside a layer and no wait for the L2 inside a product.
+// Per tile:
+//   layer 1 -> h1 (LDS) | layer 2 -> h2 (registers + LDS) |
 //   output layer on the ALUs -> loss -> dL/dout | W3 gradient | dz2 = (dL/dout W3^T)(1-h2^2) -> LDS |
-//   dW2 += h1^T dz2 | dz1 = (dz2 W2^T)(1-h1^2) -> LDS | dW1 += X^T dz1
-// The gather entries of the NEXT tile are fetched at the top of the current one and its observation rows (as the
-// aligned 16-byte chunks that cover each row) after layer 2, so neither dependent load is waited for.  At the end
-// a workgroup stores its partial gradient into a copy of its own; reduce_partials_kernel adds the copies.
+//   dW2 += h1^T dz2 | dz1 = (dz2 W2^T)(1-h1^2) -> LDS, next tile's X -> LDS | dW1 += X^T dz1
+// (two X tiles where LDS allows; otherwise a tile starts with its own X -> LDS phase).  The inputs of later tiles are
+// requested for every tile slot, without conditions, far ahead of their use: the loss inputs of the next tile and the
+// gather entries of the tile after it right after the loss, the next tile's observation rows (as the aligned 16-byte
+// chunks that cover each row) after layer 2 -- no load is waited for where it is issued, and none sits in front of a
+// load that is.  At the end a workgroup stores its partial gradient into a copy of its own, every sum in a fixed
+// order; reduce_partials_kernel adds the copies.
 #pragma once
 #include "gemm.h"
 
 namespace marl {
-
-#ifndef MARL_FT_HALF1
-#define MARL_FT_HALF1 1
-#endif
-#ifndef MARL_FT_HALFZ
-#define MARL_FT_HALFZ 0
-#endif
-#ifndef MARL_FT_XDB
-#define MARL_FT_XDB 1
-#endif
-#ifndef MARL_FT_ENTRIES_LATE
-#define MARL_FT_ENTRIES_LATE 1
-#endif
 
 #ifdef MARL_PHASE_TIMERS
 __device__ long long g_phase_cycles[16];
@@ -157,7 +148,7 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
 
   // Two X tiles when they fit: the next tile's rows then go to LDS inside the dz1 epilogue of the current one (the
   // loads were requested after layer 2), and a tile starts with layer 1 instead of a staging phase and its barrier.
-  constexpr bool XDB = MARL_FT_XDB && fused_train_lds_floats(H, BM, NOUT, NW, DMAX + 4, 2) * 4 <= 160 * 1024;
+  constexpr bool XDB = fused_train_lds_floats(H, BM, NOUT, NW, DMAX + 4, 2) * 4 <= 160 * 1024;
   extern __shared__ __attribute__((aligned(16))) float lds[];
   float* const Xs0 = lds;                  // [XDB ? 2 : 1][BM][px]
   float* H1 = Xs0 + (XDB ? 2 : 1) * BM * a.px;  // [BM][PH]  h1, later dz1
@@ -264,7 +255,7 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
     fetch_tile_entries(tile * BM);
     fetch_tile_inputs(tile * BM);
     fetch_tile_loss_inputs(tile * BM);
-    if (MARL_FT_ENTRIES_LATE) fetch_tile_entries((tile + gridDim.x) * BM);
+    fetch_tile_entries((tile + gridDim.x) * BM);
   }
 #ifdef MARL_PHASE_TIMERS
   long long phase_t0_ = (long long)__builtin_amdgcn_s_memtime();
@@ -274,7 +265,7 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
     __syncthreads();
   }
   PhaseW<KG1> pw1;  // layer 1's weights: the first half requested before dW1 of the tile before (here for the first tile)
-  phase_w_request<H, KG1, 0, (MARL_FT_HALF1 ? KG1 / 2 : KG1)>(pw1, rsW1, wlane, kpad1 / 16);
+  phase_w_request<H, KG1, 0, KG1 / 2>(pw1, rsW1, wlane, kpad1 / 16);
   for (int it = 0; tile < ntiles; tile += gridDim.x, ++it) {
     const int64_t s0 = tile * BM;
     const bool have_next = tile + gridDim.x < ntiles;
@@ -282,7 +273,6 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
     if (!XDB) {  // ---- this tile's observations to LDS
       store_tile_inputs(Xs);
     }
-    if (!MARL_FT_ENTRIES_LATE) fetch_tile_entries((tile + gridDim.x) * BM);
     if (!XDB) __syncthreads();
 
     PHASE_MARK(0);
@@ -290,7 +280,7 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
     // ---- layer 1
-    phase_w_request<H, KG1, (MARL_FT_HALF1 ? KG1 / 2 : KG1), KG1>(pw1, rsW1, wlane, kpad1 / 16);
+    phase_w_request<H, KG1, KG1 / 2, KG1>(pw1, rsW1, wlane, kpad1 / 16);
     gemm_phase_w<KG1>(Xs + (mt * 32 + lo) * px + 4 * hi, kpad1 / 16, acc, pw1);
     PhaseW<KG2> pw2;  // layer 2's weights arrive during the tanh epilogue of layer 1
     phase_w_request<H, KG2>(pw2, rsW2, wlane, KG2);
@@ -382,7 +372,7 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
     // the gather entries of the tile after the next: requested here, where the next wait on a global load (the weights
     // of the dz1 product) is a whole dW2 phase away, and not in front of layer 1, whose first in-loop weight group
     // would wait for them (loads return in order)
-    if (MARL_FT_ENTRIES_LATE) fetch_tile_entries((tile + 2 * (int64_t)gridDim.x) * BM);
+    fetch_tile_entries((tile + 2 * (int64_t)gridDim.x) * BM);
     __syncthreads();
     PHASE_MARK(6);
     // ---- W3 gradient: gW3[i][k] += sum_s h2[s][i] dl[s][k]   (thread -> hidden unit tid % H, a share of the samples)
@@ -428,8 +418,8 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
     }
     __syncthreads();
     PHASE_MARK(8);
-    PhaseW<KG2> pwz;  // the first half of the dz1 product's weights arrives during dW2, whose operands are all in LDS
-    phase_w_request<H, KG2, 0, (MARL_FT_HALFZ ? KG2 / 2 : KG2)>(pwz, rsW2T, wlane, KG2);
+    PhaseW<KG2> pwz;  // the weights of the dz1 product arrive during dW2, whose operands are all in LDS
+    phase_w_request<H, KG2>(pwz, rsW2T, wlane, KG2);
     // ---- dW2 += h1^T dz2   (k runs over the samples of the tile)
     {
       const int t0 = (wave * DW2_TPW) % (NTN * NTN);
@@ -442,7 +432,6 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
     // ---- dz1 = (dz2 W2^T) * (1 - h1^2), in place over h1
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-    phase_w_request<H, KG2, (MARL_FT_HALFZ ? KG2 / 2 : KG2), KG2>(pwz, rsW2T, wlane, KG2);
     gemm_phase_w<KG2>(H2 + (mt * 32 + lo) * PH + 4 * hi, KG2, acc, pwz);
     __syncthreads();  // every wavefront is done reading h1 (dW2) before its tiles are overwritten
     PHASE_MARK(10);
@@ -464,7 +453,7 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
     __syncthreads();
     PHASE_MARK(11);
     // ---- dW1 += X^T dz1   (the next tile's layer-1 weights arrive meanwhile)
-    phase_w_request<H, KG1, 0, (MARL_FT_HALF1 ? KG1 / 2 : KG1)>(pw1, rsW1, wlane, kpad1 / 16);
+    phase_w_request<H, KG1, 0, KG1 / 2>(pw1, rsW1, wlane, kpad1 / 16);
     outer_product_accumulate_rows<Q1>(Xs + lo, px, H1 + (wave % NTN) * 32 + lo, PH, (wave / NTN) * KLEN1, KLEN1, hi, acc1);
     PHASE_MARK(12);
     __syncthreads();  // the tile buffers are reused by the next row tile
@@ -610,7 +599,7 @@ inline int fused_train_px(int Din) {
 template <int H, int BM, int NOUT, int DMAX, int NW, class LossFn>
 inline int32_t launch_fused_train_inst(const FusedTrainArgs& a, const LossFn& fn, hipStream_t s) {
   auto kern = fused_train_kernel<H, BM, NOUT, DMAX, NW, LossFn>;
-  constexpr bool XDB = MARL_FT_XDB && fused_train_lds_floats(H, BM, NOUT, NW, DMAX + 4, 2) * 4 <= 160 * 1024;  // as in the kernel
+  constexpr bool XDB = fused_train_lds_floats(H, BM, NOUT, NW, DMAX + 4, 2) * 4 <= 160 * 1024;  // as in the kernel
   const size_t bytes = fused_train_lds_floats(H, BM, NOUT, NW, a.px, XDB ? 2 : 1) * 4;
   static bool configured = false;  // per instantiation
   if (!configured) {
