@@ -30,7 +30,12 @@ struct FusedFwdArgs {
   float* gW3;      // training: [H][NOUT] accumulated with atomics
   float* gb3;      // training: [NOUT]
   float* stats;    // training: 5 floats accumulated with atomics (policy loss, value loss, entropy, KL, clip fraction)
+  // training, H = 256 (one thread per hidden unit), nullable: workgroup b stores its share of the W3 gradient and, behind
+  // it, of the b3 gradient at partial3 + b * (H * NOUT + NOUT) with plain stores; the launcher then adds the copies to
+  // gW3 (which gb3 must directly follow) in a fixed order.  Room for kFusedFwdTrainGrid copies.
+  float* partial3;
 };
+constexpr int kFusedFwdTrainGrid = 1024;  // workgroups of a training launch (persistent: register-resident W3 gradient)
 
 inline int fused_forward_px(int Din) {
   int px = (Din + 15) / 16 * 16;
@@ -262,14 +267,21 @@ __global__ void __launch_bounds__(256, 2) fused_forward_kernel(FusedFwdArgs a, F
   }
   if (TRAIN) {
     const int i = tid % H;
+    float* const own = (H == 256 && a.partial3 != nullptr) ? a.partial3 + (int64_t)blockIdx.x * (H * NOUT + NOUT) : nullptr;
 #pragma unroll
-    for (int k = 0; k < NOUT; ++k) atomicAdd(&a.gW3[i * NOUT + k], gw[k]);
+    for (int k = 0; k < NOUT; ++k) {
+      if (own != nullptr) own[i * NOUT + k] = gw[k];
+      else atomicAdd(&a.gW3[i * NOUT + k], gw[k]);
+    }
     if (wave == 0) {  // samples live in threads tid < BM <= 64
 #pragma unroll
       for (int k = 0; k < NOUT; ++k) {
         float v = gb[k];
         for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-        if (lane == 0) atomicAdd(&a.gb3[k], v);
+        if (lane == 0) {
+          if (own != nullptr) own[H * NOUT + k] = v;
+          else atomicAdd(&a.gb3[k], v);
+        }
       }
 #pragma unroll
       for (int k = 0; k < 5; ++k) {
@@ -302,9 +314,12 @@ inline int32_t launch_fused_forward_inst(const FusedFwdArgs& a, const Finish& fi
     configured = true;
   }
   const int64_t tiles = (a.S + BM - 1) / BM;
-  const unsigned grid = (unsigned)std::min<int64_t>(tiles, TRAIN ? 1024 : 2048);  // persistent when training (register-resident W3 gradient)
+  const unsigned grid = (unsigned)std::min<int64_t>(tiles, TRAIN ? kFusedFwdTrainGrid : 2048);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(256), bytes, s, a, fin);
-  return launch_status();
+  const int32_t rc = launch_status();
+  if (TRAIN && H == 256 && a.partial3 != nullptr && rc == MARL_OK)
+    launch_reduce_partials(a.partial3, (int)grid, (int64_t)H * NOUT + NOUT, a.gW3, s);
+  return rc;
 }
 
 template <int NOUT, bool TRAIN, class Finish>

@@ -92,13 +92,18 @@ struct GemmArgs {
   int64_t M, N, K;
   int64_t k_per_split;   // TN: k range of one blockIdx.z
   int round_bf16;        // round stored results to bf16 precision (kept in fp32 storage)
+  // TN with EPI_ATOMIC_ADD, nullable: k split z stores its products at split_out + z * split_count + m * ldc + n and its
+  // column sums of B behind them (at + M * ldc + n) with plain stores instead of adding to C / colsum with atomics; the
+  // caller then adds the splits in a fixed order (reduce_partials_kernel), which makes the result the same in every run.
+  // Only the large-tile kernel honours it: launch_gemm says whether it did.
+  float* split_out;
+  int64_t split_count;
 };
 
 // The kernels that finish with one partial result per workgroup (the fused training kernel, the accumulator-resident
 // transposed product) store those with plain stores and add them up here: a few hundred workgroups adding to the same
 // cache lines with atomics at the same moment queue up at the L2 (60-180 us per launch).  The split-k tile kernel below
-// keeps its atomics: its workgroups finish spread over time, and the two-stage form measured no faster (324 against
-// 315 us).
+// does the same with one slab per k split when the caller passes split_out; without it, it adds with atomics.
 
 // out[i] += sum_b partial[b * count + i], the copies added in a fixed order, so that the result does not depend on the
 // run.  A workgroup takes 32 consecutive elements; its 8 thread groups sum the copies b = g, g + 8, g + 16, ... of an
@@ -658,8 +663,12 @@ __global__ void __launch_bounds__(256, 2) gemm2_f32_kernel(GemmArgs g) {
           const float4 o = red[tid + q * (BN / 4)];
           t.x += o.x; t.y += o.y; t.z += o.z; t.w += o.w;
         }
-        float* dst = g.colsum + n0 + 4 * tid;
-        atomicAdd(dst + 0, t.x); atomicAdd(dst + 1, t.y); atomicAdd(dst + 2, t.z); atomicAdd(dst + 3, t.w);
+        if (g.split_out != nullptr) {  // this k split's column sums, directly behind its copy of C
+          *reinterpret_cast<float4*>(g.split_out + (int64_t)bz * g.split_count + g.M * g.ldc + n0 + 4 * tid) = t;
+        } else {
+          float* dst = g.colsum + n0 + 4 * tid;
+          atomicAdd(dst + 0, t.x); atomicAdd(dst + 1, t.y); atomicAdd(dst + 2, t.z); atomicAdd(dst + 3, t.w);
+        }
       }
     }
 
@@ -689,6 +698,8 @@ __global__ void __launch_bounds__(256, 2) gemm2_f32_kernel(GemmArgs g) {
               csum += v;
             } else if (EPI == EPI_STORE) {
               g.C[m * g.ldc + n] = v + bias;
+            } else if (g.split_out != nullptr) {
+              g.split_out[(int64_t)bz * g.split_count + m * g.ldc + n] = v;
             } else {
               atomicAdd(&g.C[m * g.ldc + n], v);
             }
@@ -706,8 +717,10 @@ __global__ void __launch_bounds__(256, 2) gemm2_f32_kernel(GemmArgs g) {
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // Host-side dispatch over the tile shapes used by the library.
+// Returns true when the launch wrote its k splits to g.split_out (false: it added to C / colsum directly).
 template <int MODE, int EPI>
-inline void launch_gemm(const GemmArgs& g, hipStream_t s) {
+inline bool launch_gemm(const GemmArgs& g_in, hipStream_t s) {
+  GemmArgs g = g_in;
   const int64_t M = g.M, N = g.N;
   TimedLaunch timed(MODE == GEMM_NN ? KC_GEMM_NN : (MODE == GEMM_NT ? KC_GEMM_NT : KC_GEMM_TN),
                     2.0 * (double)g.M * (double)g.N * (double)g.K, s);
@@ -722,6 +735,7 @@ inline void launch_gemm(const GemmArgs& g, hipStream_t s) {
     // (The kernel can also run persistently over row tiles with a smaller grid; measured slower here: stores
     // share the load counter on this target, so the next tile's staged loads wait for the epilogue's stores.)
     dim3 grid(gx, (unsigned)(N / bn), gz);
+    if (!(MODE == GEMM_TN && EPI == EPI_ATOMIC_ADD && g.ldc == N && N % 4 == 0)) g.split_out = nullptr;
     if (bn == 128) {
       if (avec) hipLaunchKernelGGL((gemm2_f32_kernel<MODE, EPI, 128, true>), grid, dim3(256), 0, s, g);
       else hipLaunchKernelGGL((gemm2_f32_kernel<MODE, EPI, 128, false>), grid, dim3(256), 0, s, g);
@@ -729,8 +743,9 @@ inline void launch_gemm(const GemmArgs& g, hipStream_t s) {
       if (avec) hipLaunchKernelGGL((gemm2_f32_kernel<MODE, EPI, 64, true>), grid, dim3(256), 0, s, g);
       else hipLaunchKernelGGL((gemm2_f32_kernel<MODE, EPI, 64, false>), grid, dim3(256), 0, s, g);
     }
-    return;
+    return g.split_out != nullptr;
   }
+  g.split_out = nullptr;
   if (MODE == GEMM_TN && M <= 32) {
     // very thin output (first-layer gradient of the small networks)
     dim3 grid(1, (unsigned)((N + 63) / 64), gz);
@@ -742,6 +757,7 @@ inline void launch_gemm(const GemmArgs& g, hipStream_t s) {
     dim3 grid((unsigned)((M + 127) / 128), (unsigned)((N + 63) / 64), gz);
     hipLaunchKernelGGL((gemm_f32_kernel<MODE, EPI, 128, 64, 2, 2>), grid, dim3(256), 0, s, g);
   }
+  return false;
 }
 
 }  // namespace marl

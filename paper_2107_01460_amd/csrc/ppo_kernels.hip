@@ -307,12 +307,21 @@ struct UpdateWsView {
   float *h1c, *h2c, *dz1c, *dlc;
   float* partial;  // per-workgroup copies of one network's gradient (two-stage reduction of the fused training kernel)
   float* partial_w1;
-  float* partial_head;  // bf16 configuration: per-workgroup W3 / b3 gradients of the output-layer kernel
+  float* partial_head;  // per-workgroup W3 / b3 gradients of the output-layer kernels (bf16 configuration; register-resident fp32 critic)
+  float* split_ws;      // fp32 layer-by-layer networks: the k splits of a weight-gradient product, added in a fixed order
+  int64_t split_floats;
   // bf16 configuration: one set of activation buffers, used by the actor and then by the critic
   bf16_t *xb, *xbT, *bh1, *bh1T, *bh2, *dz2T, *dz1T;
 };
 
 int64_t align256(int64_t x) { return (x + 255) & ~(int64_t)255; }
+
+int64_t split_want(int64_t tiles_mn) { return std::max<int64_t>(1, 1024 / std::max<int64_t>(1, tiles_mn)); }
+// floats of workspace for the k splits of dW2 (H x H + H) and dW1 (Din x H + H) of one layer-by-layer network
+int64_t split_ws_floats(int H, int Din) {
+  const int64_t t2 = ((H + 127) / 128) * ((H + 127) / 128), t1 = ((Din + 127) / 128) * ((H + 127) / 128);
+  return std::max(split_want(t2) * ((int64_t)H * H + H), split_want(t1) * ((int64_t)Din * H + H));
+}
 
 UpdateWsView carve_update_ws(const marl_config& c, void* ws, int64_t* total) {
   const Dims d = dims_of(c);
@@ -348,6 +357,12 @@ UpdateWsView carve_update_ws(const marl_config& c, void* ws, int64_t* total) {
     v.partial = pmax > 0 ? (float*)take((int64_t)kFusedTrainMaxGrid * pmax * 4) : nullptr;
     // ... and of the first-layer gradient of the 256-wide critic (accumulator-resident transposed product)
     v.partial_w1 = (d.Hc == kWregN && d.Dc == 300) ? (float*)take((int64_t)kWaccMaxGrid * (300 + 1) * kWregN * 4) : nullptr;
+    // the k splits of the layer-by-layer weight gradients (at most `want` splits of pick_k_split per product)
+    v.split_floats = 0;
+    if (!fused_train_supported(d.Ha, d.D)) v.split_floats = std::max(v.split_floats, split_ws_floats(d.Ha, d.D));
+    if (!fused_train_supported(d.Hc, d.Dc)) v.split_floats = std::max(v.split_floats, split_ws_floats(d.Hc, d.Dc));
+    v.split_ws = v.split_floats > 0 ? (float*)take(v.split_floats * 4) : nullptr;
+    v.partial_head = (d.Hc == kWregN || d.Ha == kWregN) ? (float*)take((int64_t)kFusedFwdTrainGrid * (kWregN * kActions + kActions) * 4) : nullptr;
   } else {
     const int64_t Sp = round_up64(std::max(Sa, Sc));
     const int64_t Dp = round_up64(std::max(d.D, d.Dc)), H = std::max(d.Ha, d.Hc);
@@ -368,7 +383,7 @@ UpdateWsView carve_update_ws(const marl_config& c, void* ws, int64_t* total) {
 
 int64_t pick_k_split(int64_t K, int64_t tiles_mn) {
   // enough workgroups for ~4 per CU, each with a k range that is a multiple of the k tile
-  int64_t want = std::max<int64_t>(1, 1024 / std::max<int64_t>(1, tiles_mn));
+  int64_t want = split_want(tiles_mn);
   int64_t per = (K + want - 1) / want;
   per = std::max<int64_t>(256, ((per + kGemmBK - 1) / kGemmBK) * kGemmBK);
   return per;
@@ -388,7 +403,7 @@ inline bool wreg_forward_supported(const RowSrc& X, int64_t S, int Din, int H) {
 template <int NOUT, class LossFn>
 int32_t train_forward_wreg(const RowSrc& X, int64_t S, int Din, const float* W1, const float* b1, const float* W2,
                            const float* b2, const float* W3, const float* b3, float* h1, float* dz2, float* gW3,
-                           float* gb3, float* stats, const LossFn& fn, hipStream_t s) {
+                           float* gb3, float* stats, const LossFn& fn, float* partial3, hipStream_t s) {
   {
     WregArgs g{};
     g.A = X; g.S = S; g.Kin = Din; g.B = W1; g.ldb = kWregN; g.b_kcont = 0; g.C = h1; g.bias = b1;
@@ -399,15 +414,34 @@ int32_t train_forward_wreg(const RowSrc& X, int64_t S, int Din, const float* W1,
   WregArgs g{};
   g.A = RowSrc{h1, kWregN, nullptr, 1, S}; g.S = S; g.Kin = kWregN; g.B = W2; g.ldb = kWregN; g.b_kcont = 0; g.C = dz2;
   g.bias = b2; g.W3 = W3; g.b3 = b3; g.gW3 = gW3; g.gb3 = gb3; g.stats = stats;
-  TimedLaunch timed(KC_GEMM_NN, 2.0 * (double)S * kWregN * kWregN, s);
-  return launch_wreg_loss<NOUT>(g, fn, s);
+  g.partial3 = partial3;  // (nullable) per-workgroup copies of the W3 / b3 gradient, added in a fixed order below
+  int32_t rc;
+  {
+    TimedLaunch timed(KC_GEMM_NN, 2.0 * (double)S * kWregN * kWregN, s);
+    rc = launch_wreg_loss<NOUT>(g, fn, s);
+  }
+  if (rc == MARL_OK && partial3 != nullptr) {
+    const int64_t tiles = (S + kWregBM - 1) / kWregBM;
+    launch_reduce_partials(partial3, (int)std::min<int64_t>(tiles, 256), (int64_t)kWregN * NOUT + NOUT, gW3, s);
+  }
+  return rc;
 }
 
 // Backward through one network given dL/d(output layer) in dl; h2 is overwritten by dz2.
 template <int NOUT>
 void mlp_backward(const RowSrc& X, int64_t S, int Din, int H, const float* W2, const float* W3, float* h1, float* h2,
                   float* dz1, const float* dl, float* gW1, float* gb1, float* gW2, float* gb2, bool bf16,
-                  bool dz2_ready, float* wacc_partial, hipStream_t s) {
+                  bool dz2_ready, float* wacc_partial, float* split_ws, int64_t split_floats, hipStream_t s) {
+  // a weight-gradient product writes its k splits to split_ws and has them added in a fixed order, where the workspace
+  // has room and the bias gradient directly follows the weight gradient (its column sums ride along)
+  auto split_launch = [&](GemmArgs& g, float* gW, float* gb, int64_t rows) {
+    const int64_t count = rows * H + H, nz = (g.K + g.k_per_split - 1) / g.k_per_split;
+    if (split_ws != nullptr && gb == gW + rows * H && nz * count <= split_floats) {
+      g.split_out = split_ws;
+      g.split_count = count;
+    }
+    if (launch_gemm<GEMM_TN, EPI_ATOMIC_ADD>(g, s)) launch_reduce_partials(split_ws, (int)nz, count, gW, s);
+  };
   if (!dz2_ready) {
     const int cb = std::min(H, 256), rpb = 256;
     dim3 grid((unsigned)((S + rpb - 1) / rpb), (unsigned)((H + cb - 1) / cb));
@@ -418,7 +452,7 @@ void mlp_backward(const RowSrc& X, int64_t S, int Din, int H, const float* W2, c
     g.A = RowSrc{h1, H, nullptr, 1, S}; g.B = h2; g.ldb = H; g.C = gW2; g.ldc = H;
     g.M = H; g.N = H; g.K = S; g.colsum = gb2;
     g.k_per_split = pick_k_split(S, ((H + 127) / 128) * ((H + 127) / 128));
-    launch_gemm<GEMM_TN, EPI_ATOMIC_ADD>(g, s);
+    split_launch(g, gW2, gb2, H);
   }
   const RowSrc dz2_rows{h2, H, nullptr, 1, S};
   if (!bf16 && wreg_worthwhile(S) && wreg_gemm_supported<WREG_DTANH>(dz2_rows, H, H)) {
@@ -445,7 +479,7 @@ void mlp_backward(const RowSrc& X, int64_t S, int Din, int H, const float* W2, c
     g.A = X; g.B = dz1; g.ldb = H; g.C = gW1; g.ldc = H;
     g.M = Din; g.N = H; g.K = S; g.colsum = gb1;
     g.k_per_split = pick_k_split(S, ((Din + 127) / 128) * ((H + 127) / 128));
-    launch_gemm<GEMM_TN, EPI_ATOMIC_ADD>(g, s);
+    split_launch(g, gW1, gb1, Din);
   }
 }
 
@@ -574,6 +608,7 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
             fa.W1 = eff + oa.W1; fa.b1 = eff + oa.b1; fa.W2 = eff + oa.W2; fa.b2 = eff + oa.b2; fa.W3 = eff + oa.W3;
             fa.b3 = eff + oa.b3; fa.h1_out = w.h1a; fa.dz2_out = w.h2a; fa.gW3 = w.grad + ga.W3; fa.gb3 = w.grad + ga.b3;
             fa.stats = sck->acc;
+            fa.partial3 = ga.b3 == ga.W3 + (int64_t)d.Ha * kActions ? w.partial_head : nullptr;
             fa.W1s = eff + pm.sw_w1[0]; fa.W2s = eff + pm.sw_w2[0]; fa.kpad1 = pm.kpad1[0]; fa.px = fused_forward_px(d.D);
             const int32_t rc = launch_fused_forward<kActions, true>(d.Ha, fa, fn, s);
             if (rc != MARL_OK) return rc;
@@ -584,7 +619,7 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
                                eff + oa.W3, eff + oa.b3, fn, w.dla, w.grad + ga.W3, w.grad + ga.b3, sck, 0.f);
           }
           mlp_backward<kActions>(Xa, Sa, d.D, d.Ha, eff + oa.W2, eff + oa.W3, w.h1a, w.h2a, w.dz1a, w.dla, w.grad + ga.W1,
-                                 w.grad + ga.b1, w.grad + ga.W2, w.grad + ga.b2, d.bf16, fused_a, nullptr, s);
+                                 w.grad + ga.b1, w.grad + ga.W2, w.grad + ga.b2, d.bf16, fused_a, nullptr, w.split_ws, w.split_floats, s);
         }
       }
       // ---- critic
@@ -609,7 +644,8 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
           if (wreg_forward_supported(Xc, Sc, d.Dc, d.Hc)) {
             const int32_t rc = train_forward_wreg<1>(Xc, Sc, d.Dc, eff + oc.W1, eff + oc.b1, eff + oc.W2, eff + oc.b2,
                                                      eff + oc.W3, eff + oc.b3, w.h1c, w.h2c, w.grad + gc.W3,
-                                                     w.grad + gc.b3, sck->acc, fn, s);
+                                                     w.grad + gc.b3, sck->acc, fn,
+                                                     gc.b3 == gc.W3 + (int64_t)kWregN ? w.partial_head : nullptr, s);
             if (rc != MARL_OK) return rc;
           } else if (fused_c) {
             FusedFwdArgs fa{};
@@ -617,6 +653,7 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
             fa.W1 = eff + oc.W1; fa.b1 = eff + oc.b1; fa.W2 = eff + oc.W2; fa.b2 = eff + oc.b2; fa.W3 = eff + oc.W3;
             fa.b3 = eff + oc.b3; fa.h1_out = w.h1c; fa.dz2_out = w.h2c; fa.gW3 = w.grad + gc.W3; fa.gb3 = w.grad + gc.b3;
             fa.stats = sck->acc;
+            fa.partial3 = gc.b3 == gc.W3 + (int64_t)d.Hc ? w.partial_head : nullptr;
             fa.W1s = eff + pm.sw_w1[1]; fa.W2s = eff + pm.sw_w2[1]; fa.kpad1 = pm.kpad1[1]; fa.px = fused_forward_px(d.Dc);
             const int32_t rc = launch_fused_forward<1, true>(d.Hc, fa, fn, s);
             if (rc != MARL_OK) return rc;
@@ -627,7 +664,7 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
                                eff + oc.b3, fn, w.dlc, w.grad + gc.W3, w.grad + gc.b3, sck, 0.f);
           }
           mlp_backward<1>(Xc, Sc, d.Dc, d.Hc, eff + oc.W2, eff + oc.W3, w.h1c, w.h2c, w.dz1c, w.dlc, w.grad + gc.W1,
-                          w.grad + gc.b1, w.grad + gc.W2, w.grad + gc.b2, d.bf16, fused_c, w.partial_w1, s);
+                          w.grad + gc.b1, w.grad + gc.W2, w.grad + gc.b2, d.bf16, fused_c, w.partial_w1, w.split_ws, w.split_floats, s);
         }
       }
       // ---- clip + Adam

@@ -42,6 +42,9 @@ struct WregArgs {
   // accumulated with atomics
   const float *W3, *b3;
   float *gW3, *gb3, *stats;
+  // (nullable) workgroup b writes its W3 / b3 gradient to partial3 + b * (256 * NOUT + NOUT) with plain stores instead;
+  // the caller adds the copies to gW3 (with gb3 directly behind it) in a fixed order
+  float* partial3;
 };
 
 // The loss functor of WREG_TANH_LOSS splits into load (the trajectory values of a sample, requested while the tile is
@@ -411,14 +414,21 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) 
     for (int e = 0; e < 64; ++e) finish_elem(e, prev_off);
   }
   if (EPI == WREG_TANH_LOSS) {
+    float* const own = a.partial3 != nullptr ? a.partial3 + (int64_t)blockIdx.x * (kWregN * NOUT + NOUT) : nullptr;
 #pragma unroll
-    for (int k = 0; k < NOUT; ++k) atomicAdd(&a.gW3[tid * NOUT + k], gw[k]);
+    for (int k = 0; k < NOUT; ++k) {
+      if (own != nullptr) own[tid * NOUT + k] = gw[k];
+      else atomicAdd(&a.gW3[tid * NOUT + k], gw[k]);
+    }
     if (wave == 0) {  // samples live in threads tid < 64
 #pragma unroll
       for (int k = 0; k < NOUT; ++k) {
         float v = gb[k];
         for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-        if (lane == 0) atomicAdd(&a.gb3[k], v);
+        if (lane == 0) {
+          if (own != nullptr) own[kWregN * NOUT + k] = v;
+          else atomicAdd(&a.gb3[k], v);
+        }
       }
 #pragma unroll
       for (int k = 0; k < 5; ++k) {

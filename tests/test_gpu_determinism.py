@@ -4,9 +4,9 @@ The environment, the sampler and GAE have no reductions, so state and trajectory
 gradient of the networks that take the whole-network training kernel is reduced in a fixed order (the shares inside a
 workgroup added in turn through LDS, the per-workgroup copies added in a fixed grouping, the gradient norm as per-block
 shares added by a fixed tree),
-so their parameters must be equal bit for bit as well; the layer-by-layer kernels of the wide networks (256-wide
-centralised critic, the bf16 configuration) still meet in fp32 atomics and are held to 1e-5 of the largest parameter
-change.  The reported loss statistics are summed with atomics in every configuration."""
+so their parameters must be equal bit for bit as well, and so are the layer-by-layer kernels of the 256-wide fp32
+critic (k splits and per-workgroup copies added in a fixed order); the bf16 configuration still meets in fp32 atomics and
+is held to 0.1 of the parameter change in its norm.  The reported loss statistics are summed with atomics in every configuration."""
 import numpy as np
 import pytest
 import torch
@@ -42,7 +42,7 @@ def one_run(M, cfg, params0, perm):
     return snaps, p.cpu().numpy(), m.cpu().numpy(), v.cpu().numpy(), stats.cpu().numpy()
 
 
-@pytest.mark.parametrize("k,exact", [(2, True), (3, False), (4, False), (1, True), (5, True)])
+@pytest.mark.parametrize("k,exact", [(2, True), (3, True), (4, False), (1, True), (5, True)])
 def test_two_runs_agree(k, exact):
     import paper_2107_01460_amd as M
     cfg = small(k, n_envs={1: 700, 2: 1024, 3: 512, 4: 96, 5: 3000}[k], rollout_len=16, n_minibatches=2, n_epochs=2)
