@@ -53,6 +53,31 @@ void* static_scratch() {
 }
 }  // namespace
 
+// ---- a second stream per device -----------------------------------------------------------------------------------
+namespace {
+struct SideState {
+  bool tried = false;
+  SideStream st{};
+  bool ok = false;
+};
+std::mutex g_side_mutex;
+SideState g_side[kMaxDevices];
+}  // namespace
+
+const SideStream* side_stream() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_side_mutex);
+  SideState& g = g_side[dev];
+  if (!g.tried) {
+    g.tried = true;
+    g.ok = hipStreamCreateWithFlags(&g.st.stream, hipStreamNonBlocking) == hipSuccess &&
+           hipEventCreateWithFlags(&g.st.fork, hipEventDisableTiming) == hipSuccess &&
+           hipEventCreateWithFlags(&g.st.join, hipEventDisableTiming) == hipSuccess;
+  }
+  return g.ok ? &g.st : nullptr;
+}
+
 TimedLaunch::TimedLaunch(int c, double work, hipStream_t st) : cls(c), s(st), active(g_timer.on) {
   if (!active) return;
   const size_t b = g_timer.used;

@@ -182,6 +182,19 @@ struct TimedLaunch {
   ~TimedLaunch();
 };
 
+// A second stream of the current device (default priority, created on the first call, kept until the process ends) with
+// the two events of a fork and join: work that is independent of what follows on the caller's stream -- the second
+// network of an update -- is launched there between
+//   hipEventRecord(fork, s); hipStreamWaitEvent(stream, fork, 0);   and   hipEventRecord(join, stream); hipStreamWaitEvent(s, join, 0);
+// so that it still starts after everything already queued on s and everything queued on s afterwards waits for it.
+// One fork at a time per device: calls that overlap on one device from several host threads would share the events.
+// nullptr when the stream cannot be created (the caller then stays on its own stream).
+struct SideStream {
+  hipStream_t stream;
+  hipEvent_t fork, join;
+};
+const SideStream* side_stream();
+
 // ---- launchers implemented in the kernel translation units ------------------------------------
 int32_t launch_env_reset(const marl_config& c, marl_env_state st, hipStream_t s);
 // do_step = false: only observe.  actions/reward/done may be null then.

@@ -53,6 +53,7 @@ struct FusedTrainArgs {
   // to the same few hundred cache lines at the same moment is what the direct atomics cost: 60-180 us per launch.
   float* partial;
   int64_t gcount;
+  int64_t pstride;  // distance between the copies of consecutive workgroups (0: gcount)
 };
 
 // Floats of LDS the kernel lays out for a tile of BM samples at X pitch px with `xtiles` X tiles.
@@ -128,8 +129,9 @@ __device__ __forceinline__ void outer_product_accumulate_rows(const float* __res
   }
 }
 
+// The kernel's body: workgroup `bid` of `nblk` that share the tiles of one network's minibatch.
 template <int H, int BM, int NOUT, int DMAX, int NW, class LossFn>
-__global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(FusedTrainArgs a, LossFn fn) {
+__device__ __forceinline__ void fused_train_body(const FusedTrainArgs& a, const LossFn& fn, const unsigned bid, const unsigned nblk) {
   constexpr int NT = 64 * NW;
   constexpr int NTN = H / 32, MTF = BM / 32, PH = H + 4, GROUPS = NT / BM;
   static_assert(NTN * MTF == NW, "one forward tile per wavefront");
@@ -167,7 +169,7 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
   const int lo = lane & 31, hi = lane >> 5;
   const int mt = wave / NTN, nt = wave % NTN;  // forward / dz tile of this wavefront
   // where this workgroup's gradient goes: the gradient itself, or its own copy of the range
-  float* const gout = a.partial != nullptr ? a.partial + (int64_t)blockIdx.x * a.gcount : a.gW1;
+  float* const gout = a.partial != nullptr ? a.partial + (int64_t)bid * (a.pstride != 0 ? a.pstride : a.gcount) : a.gW1;
   // (a copy needs no zeroing: the flush at the end writes every one of its elements exactly once)
   float* const gW1 = gout;
   float* const gb1 = gout + (a.gb1 - a.gW1);
@@ -250,12 +252,12 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
     }
   };
   const int64_t ntiles = (a.S + BM - 1) / BM;
-  int64_t tile = blockIdx.x;
+  int64_t tile = bid;
   if (tile < ntiles) {
     fetch_tile_entries(tile * BM);
     fetch_tile_inputs(tile * BM);
     fetch_tile_loss_inputs(tile * BM);
-    fetch_tile_entries((tile + gridDim.x) * BM);
+    fetch_tile_entries((tile + nblk) * BM);
   }
 #ifdef MARL_PHASE_TIMERS
   long long phase_t0_ = (long long)__builtin_amdgcn_s_memtime();
@@ -266,9 +268,9 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
   }
   PhaseW<KG1> pw1;  // layer 1's weights: the first half requested before dW1 of the tile before (here for the first tile)
   phase_w_request<H, KG1, 0, KG1 / 2>(pw1, rsW1, wlane, kpad1 / 16);
-  for (int it = 0; tile < ntiles; tile += gridDim.x, ++it) {
+  for (int it = 0; tile < ntiles; tile += nblk, ++it) {
     const int64_t s0 = tile * BM;
-    const bool have_next = tile + gridDim.x < ntiles;
+    const bool have_next = tile + nblk < ntiles;
     float* const Xs = XDB ? Xs0 + (it & 1) * BM * px : Xs0;
     if (!XDB) {  // ---- this tile's observations to LDS
       store_tile_inputs(Xs);
@@ -302,7 +304,7 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
     __syncthreads();  // the h1 tile is complete
     gemm_phase_w<KG2>(H1 + (mt * 32 + lo) * PH + 4 * hi, KG2, acc, pw2);
     PHASE_MARK(3);
-    fetch_tile_inputs((tile + gridDim.x) * BM);  // lands during the ALU phases and dW2
+    fetch_tile_inputs((tile + nblk) * BM);  // lands during the ALU phases and dW2
     floatx16 h2r;  // h2 of this wavefront's tile
     {
       const int n = nt * 32 + lo;
@@ -368,11 +370,11 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
 #pragma unroll
       for (int k = 0; k < 5; ++k) accS[tid * AS + NOUT + k] += st[k];
     }
-    fetch_tile_loss_inputs((tile + gridDim.x) * BM);
+    fetch_tile_loss_inputs((tile + nblk) * BM);
     // the gather entries of the tile after the next: requested here, where the next wait on a global load (the weights
     // of the dz1 product) is a whole dW2 phase away, and not in front of layer 1, whose first in-loop weight group
     // would wait for them (loads return in order)
-    fetch_tile_entries((tile + 2 * (int64_t)gridDim.x) * BM);
+    fetch_tile_entries((tile + 2 * (int64_t)nblk) * BM);
     __syncthreads();
     PHASE_MARK(6);
     // ---- W3 gradient: gW3[i][k] += sum_s h2[s][i] dl[s][k]   (thread -> hidden unit tid % H, a share of the samples)
@@ -587,6 +589,21 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(F
   }
 }
 
+template <int H, int BM, int NOUT, int DMAX, int NW, class LossFn>
+__global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_kernel(FusedTrainArgs a, LossFn fn) {
+  fused_train_body<H, BM, NOUT, DMAX, NW, LossFn>(a, fn, blockIdx.x, gridDim.x);
+}
+
+// Two networks of the same shape on the same number of samples in ONE launch: workgroups 0 .. grid_a - 1 train the
+// first, the others the second.  For minibatches so small that neither launch fills the compute units (a few tiles
+// each) the update is a chain of dependent launches, and this takes two links (a kernel and its reduction) out of it.
+template <int H, int BM, int NOUT_A, int NOUT_B, int DMAX, int NW, class LossA, class LossB>
+__global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) fused_train_pair_kernel(FusedTrainArgs a, LossA fa, FusedTrainArgs b,
+                                                                                   LossB fb, unsigned grid_a) {
+  if (blockIdx.x < grid_a) fused_train_body<H, BM, NOUT_A, DMAX, NW, LossA>(a, fa, blockIdx.x, grid_a);
+  else fused_train_body<H, BM, NOUT_B, DMAX, NW, LossB>(b, fb, blockIdx.x - grid_a, gridDim.x - grid_a);
+}
+
 // (an input row is staged as the aligned 16-byte chunks that cover it: up to three values more than its width)
 inline bool fused_train_supported(int H, int Din) { return (H == 64 || H == 128) && Din <= 93; }
 
@@ -614,6 +631,29 @@ inline int32_t launch_fused_train_inst(const FusedTrainArgs& a, const LossFn& fn
   return launch_status();
 }
 
+template <int H, int BM, int NOUT_A, int NOUT_B, int DMAX, int NW, class LossA, class LossB>
+inline int32_t launch_fused_train_pair_inst(const FusedTrainArgs& a, const LossA& fa, const FusedTrainArgs& b, const LossB& fb,
+                                            hipStream_t s) {
+  auto kern = fused_train_pair_kernel<H, BM, NOUT_A, NOUT_B, DMAX, NW, LossA, LossB>;
+  constexpr int NMAX = NOUT_A > NOUT_B ? NOUT_A : NOUT_B;
+  constexpr bool XDB_A = fused_train_lds_floats(H, BM, NOUT_A, NW, DMAX + 4, 2) * 4 <= 160 * 1024;  // as in the kernel
+  constexpr bool XDB_B = fused_train_lds_floats(H, BM, NOUT_B, NW, DMAX + 4, 2) * 4 <= 160 * 1024;
+  const size_t bytes = std::max(fused_train_lds_floats(H, BM, NOUT_A, NW, a.px, XDB_A ? 2 : 1),
+                                fused_train_lds_floats(H, BM, NOUT_B, NW, b.px, XDB_B ? 2 : 1)) * 4;
+  static_assert(fused_train_lds_floats(H, BM, NMAX, NW, DMAX + 4, 1) * 4 <= 160 * 1024, "fits");
+  static bool configured = false;  // per instantiation
+  if (!configured) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+      return MARL_E_LAUNCH;
+    configured = true;
+  }
+  const unsigned grid_a = (unsigned)((a.S + BM - 1) / BM);  // == the second network's (the caller checks the sizes)
+  hipLaunchKernelGGL(kern, dim3(2 * grid_a), dim3(64 * NW), bytes, s, a, fa, b, fb, grid_a);
+  // copy k of the first network's range is directly followed by copy k of the second's: one reduction for both
+  launch_reduce_partials(a.partial, (int)grid_a, a.gcount + b.gcount, a.gW1, s);
+  return launch_status();
+}
+
 // Workgroups a launch can have (the copies of the gradient range the caller provides room for).
 constexpr int kFusedTrainMaxGrid = 512;
 
@@ -629,6 +669,32 @@ inline int32_t launch_fused_train(int H, const FusedTrainArgs& a, const LossFn& 
   }
   if (a.Din <= 29) return launch_fused_train_inst<64, 128, NOUT, 32, 8, LossFn>(a, fn, s);
   return launch_fused_train_inst<64, 128, NOUT, 96, 8, LossFn>(a, fn, s);
+}
+
+// Whether two networks can share a launch: the same shape on the same number of samples, so few tiles that both
+// launches together have at most one workgroup per compute unit, and gradient ranges that follow one another (a's, then
+// b's) so that the interleaved copies reduce in one pass.
+inline bool fused_train_pair_supported(int Ha, int Da, int64_t Sa, int Hb, int Db, int64_t Sb) {
+  if (Ha != Hb || Da != Db || Sa != Sb || !fused_train_supported(Ha, Da)) return false;
+  const int BM = Ha == 128 ? 64 : 128;
+  return 2 * ((Sa + BM - 1) / BM) <= 256;
+}
+
+// a.partial must have room for (a.gcount + b.gcount) floats per workgroup of ONE network; a.gW1 + a.gcount == b.gW1.
+template <int NOUT_A, int NOUT_B, class LossA, class LossB>
+inline int32_t launch_fused_train_pair(int H, FusedTrainArgs a, const LossA& fa, FusedTrainArgs b, const LossB& fb, hipStream_t s) {
+  if (!small_div_ok(a.X.pd, a.S) || !small_div_ok(fa.lc.ad, a.S) || !small_div_ok(b.X.pd, b.S) || !small_div_ok(fb.lc.ad, b.S))
+    return MARL_E_SIZE;
+  if (a.partial == nullptr || b.gW1 != a.gW1 + a.gcount) return MARL_E_SIZE;
+  a.pstride = b.pstride = a.gcount + b.gcount;
+  b.partial = a.partial + a.gcount;
+  TimedLaunch timed(KC_FUSED_TRAIN, 2.0 * (double)(a.S + b.S) * (2.0 * a.Din * H + 3.0 * H * H), s);
+  if (H == 128) {
+    if (a.Din <= 29) return launch_fused_train_pair_inst<128, 64, NOUT_A, NOUT_B, 32, 8, LossA, LossB>(a, fa, b, fb, s);
+    return launch_fused_train_pair_inst<128, 64, NOUT_A, NOUT_B, 96, 8, LossA, LossB>(a, fa, b, fb, s);
+  }
+  if (a.Din <= 29) return launch_fused_train_pair_inst<64, 128, NOUT_A, NOUT_B, 32, 8, LossA, LossB>(a, fa, b, fb, s);
+  return launch_fused_train_pair_inst<64, 128, NOUT_A, NOUT_B, 96, 8, LossA, LossB>(a, fa, b, fb, s);
 }
 
 }  // namespace marl

@@ -584,10 +584,32 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
       lc.rows = rows; lc.A = d.A; lc.ad = make_small_div(d.A); lc.rows_mb = rows_mb; lc.inv_B = (float)(1.0 / (double)(rows_mb * d.A));
       lc.sc = sck; lc.adv_stats = w.adv_stats + 2 * step; lc.normalize = c.normalize_adv; lc.clip_eps = c.clip_eps;
       lc.ent_coef = c.ent_coef; lc.vf_coef = c.vf_coef; lc.clip_value = c.clip_value;
-      // ---- actor
       const RowSrc Xa{tr.obs, d.D, rows, d.A, Sa, make_small_div(d.A)};
+      const RowSrc Xc{tr.obs, d.Dc, rows, d.central ? 1 : d.A, Sc, make_small_div(d.central ? 1 : d.A)};
+      // ---- both networks in one launch (same shape, few tiles)
+      const bool pair = !d.bf16 && Sa < ((int64_t)1 << 31) && fused_train_pair_supported(d.Ha, d.D, Sa, d.Hc, d.Dc, Sc);
+      if (pair) {
+        ActorLoss fa{lc, tr.action, tr.logp, tr.adv};
+        CriticLoss fc{lc, tr.ret, tr.value, d.central ? d.A : 1};
+        FusedTrainArgs ta{}, tc{};
+        ta.X = Xa; ta.S = Sa; ta.Din = d.D; ta.px = fused_train_px(d.D);
+        ta.W1 = eff + oa.W1; ta.b1 = eff + oa.b1; ta.W2 = eff + oa.W2; ta.b2 = eff + oa.b2; ta.W3 = eff + oa.W3;
+        ta.W1s = eff + pm.sw_w1[0]; ta.W2s = eff + pm.sw_w2[0]; ta.W2Ts = eff + pm.sw_w2t[0];
+        ta.b3 = eff + oa.b3; ta.gW1 = w.grad + ga.W1; ta.gb1 = w.grad + ga.b1; ta.gW2 = w.grad + ga.W2;
+        ta.gb2 = w.grad + ga.b2; ta.gW3 = w.grad + ga.W3; ta.gb3 = w.grad + ga.b3; ta.stats = sck->acc;
+        ta.partial = w.partial; ta.gcount = d.Pa;
+        tc.X = Xc; tc.S = Sc; tc.Din = d.Dc; tc.px = fused_train_px(d.Dc);
+        tc.W1 = eff + oc.W1; tc.b1 = eff + oc.b1; tc.W2 = eff + oc.W2; tc.b2 = eff + oc.b2; tc.W3 = eff + oc.W3;
+        tc.W1s = eff + pm.sw_w1[1]; tc.W2s = eff + pm.sw_w2[1]; tc.W2Ts = eff + pm.sw_w2t[1];
+        tc.b3 = eff + oc.b3; tc.gW1 = w.grad + gc.W1; tc.gb1 = w.grad + gc.b1; tc.gW2 = w.grad + gc.W2;
+        tc.gb2 = w.grad + gc.b2; tc.gW3 = w.grad + gc.W3; tc.gb3 = w.grad + gc.b3; tc.stats = sck->acc;
+        tc.gcount = d.P - d.Pa;
+        const int32_t rc = (launch_fused_train_pair<kActions, 1>(d.Ha, ta, fa, tc, fc, s));
+        if (rc != MARL_OK) return rc;
+      }
+      // ---- actor
       const bool fused_a = fused_forward_supported(d.Ha, d.D);
-      {
+      if (!pair) {
         ActorLoss fn{lc, tr.action, tr.logp, tr.adv};
         if (d.bf16) {
           train_net_bf16<kActions>(Xa, Sa, d.D, d.Ha, effective_bf16_weights(c, eff, 0), eff, oa, w.grad, ga, fn, w.dla, wk, false, s);
@@ -623,9 +645,8 @@ int32_t launch_ppo_update(const marl_config& c, marl_traj tr, float* params, flo
         }
       }
       // ---- critic
-      const RowSrc Xc{tr.obs, d.Dc, rows, d.central ? 1 : d.A, Sc, make_small_div(d.central ? 1 : d.A)};
       const bool fused_c = fused_forward_supported(d.Hc, d.Dc);
-      {
+      if (!pair) {
         CriticLoss fn{lc, tr.ret, tr.value, d.central ? d.A : 1};
         if (d.bf16) {
           // IPPO: the critic reads the rows the actor has just packed (same rows, same width)

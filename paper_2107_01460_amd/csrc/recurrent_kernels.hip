@@ -200,7 +200,7 @@ __global__ void gather_hidden_kernel(const float* __restrict__ h0, const int32_t
 constexpr int kStepRows = 32;
 inline bool fused_step_supported(int H) { return H % 32 == 0 && H <= 256; }
 inline size_t fused_fwd_lds(int H) { return sizeof(float) * kStepRows * (H + 4); }
-inline size_t fused_bwd_lds(int H) { return sizeof(float) * kStepRows * ((3 * H + 4) + (H + 4)); }
+inline size_t fused_bwd_lds(int H) { return sizeof(float) * kStepRows * (3 * H + 4); }
 
 // Forward: gates of one step from Gi (input products, no bias) and hprev; see gru_forward_kernel for the outputs.
 __global__ void __launch_bounds__(512) gru_step_fwd_kernel(const float* __restrict__ Gi, const float* __restrict__ Wh_op,
@@ -301,12 +301,14 @@ __global__ void __launch_bounds__(512) gru_step_bwd_kernel(const float* __restri
                                                            const float* __restrict__ rzn, const float* __restrict__ ghn,
                                                            const float* __restrict__ hprev, const float* __restrict__ WhT_op,
                                                            float* __restrict__ dgi, float* __restrict__ dgh,
-                                                           float* __restrict__ dhprev, int want_dhprev, int per, int64_t S,
-                                                           int H) {
+                                                           float* dhprev, int want_dhprev, int per, int64_t S, int H) {
   extern __shared__ __attribute__((aligned(16))) float lds[];
-  const int PG = 3 * H + 4, PH = H + 4;
-  float* Gs = lds;                   // [32][PG]  dgh tile, the A operand
-  float* Ds = Gs + kStepRows * PG;   // [32][PH]  dh * z
+  // The dgh tile, the A operand, is all that is kept in LDS ([32][PG]): the direct term dh * z travels through dhprev
+  // itself (written here by the thread that computes it, read back after the barrier by the thread that finishes that
+  // element), so that the 256-wide instantiation leaves room on a compute unit for a workgroup of the other network's
+  // kernel, which runs beside it on a second stream.
+  const int PG = 3 * H + 4;
+  float* Gs = lds;
   const int tid = threadIdx.x, lane = tid & 63, u = tid >> 6, lo = lane & 31, hi = lane >> 5;
   const int64_t s0 = (int64_t)blockIdx.x * kStepRows;
   {  // gate arithmetic: thread -> unit j = tid % H, samples tid / H + 2 q
@@ -340,15 +342,15 @@ __global__ void __launch_bounds__(512) gru_step_bwd_kernel(const float* __restri
         dgh[s * 3 * H + j] = g_r;
         dgh[s * 3 * H + H + j] = g_z;
         dgh[s * 3 * H + 2 * H + j] = g_hn;
+        if (want_dhprev) dhprev[i] = dz_direct;
       }
       Gs[m * PG + j] = g_r;
       Gs[m * PG + H + j] = g_z;
       Gs[m * PG + 2 * H + j] = g_hn;
-      Ds[m * PH + j] = dz_direct;
     }
   }
   if (!want_dhprev) return;  // uniform
-  __syncthreads();
+  __syncthreads();  // orders the tile in LDS and this workgroup's stores to dhprev before the reads below
   // dhprev tile = Ds + Gs WhT: wavefront u the 32 units 32 u .., contraction over the 3 H gate columns,
   // two accumulators over alternate k steps so that consecutive MFMAs do not wait for each other
   const int n = u * 32 + lo;
@@ -357,6 +359,12 @@ __global__ void __launch_bounds__(512) gru_step_bwd_kernel(const float* __restri
   for (int a = 0; a < 2; ++a)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[a][r] = 0.f;
+  float direct[16];  // dh * z of this lane's output elements, requested before the product
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int64_t s = s0 + 8 * (r / 4) + 4 * hi + (r % 4);
+    direct[r] = s < S ? dhprev[s * H + n] : 0.f;
+  }
   const float* As = Gs + lo * PG + 4 * hi;
   const float* Bg = WhT_op + ((int64_t)hi * H + n) * 4;
   const int ksteps = 3 * H / 8;  // a multiple of 12: H is a multiple of 32
@@ -386,7 +394,7 @@ __global__ void __launch_bounds__(512) gru_step_bwd_kernel(const float* __restri
   for (int r = 0; r < 16; ++r) {
     const int m = 8 * (r / 4) + 4 * hi + (r % 4);
     const int64_t s = s0 + m;
-    if (s < S) dhprev[s * H + n] = (acc[0][r] + acc[1][r]) + Ds[m * PH + n];
+    if (s < S) dhprev[s * H + n] = (acc[0][r] + acc[1][r]) + direct[r];
   }
 }
 
@@ -587,13 +595,16 @@ int32_t launch_rollout_recurrent(const marl_config& c, marl_env_state st, const 
 
 namespace {
 
+// buffers of one network's forward and backward pass over a minibatch
+struct RecNetWs {
+  float *dl, *E, *G, *RZN, *GHN, *Hout, *Hprev, *GhT, *dGh, *dHp;
+};
 struct RecUpdateWs {
   float *eff, *grad;
   Scalars* sc;
   int32_t *ident, *rows;
-  float *keep, *dl;
-  // per network, sized for the larger of the two (used by the actor, then by the critic)
-  float *E, *G, *RZN, *GHN, *Hout, *Hprev, *GhT, *dGh, *dHp;
+  float* keep;
+  RecNetWs net[2];  // actor, critic: a set each, so that the two networks can run side by side
 };
 
 RecUpdateWs carve_rec_update(const marl_config& c, void* ws, int64_t* total) {
@@ -601,7 +612,6 @@ RecUpdateWs carve_rec_update(const marl_config& c, void* ws, int64_t* total) {
   const int64_t J = d.N / c.n_minibatches, TJ = (int64_t)d.T * J;
   const int64_t Sa = TJ * d.A, Sc = d.central ? TJ : Sa;                // samples of a minibatch over all steps
   const int64_t S1a = J * d.A, S1c = d.central ? J : S1a;              // samples of one step
-  const int64_t SH = std::max(Sa * d.Ha, Sc * d.Hc), S1H = std::max(S1a * d.Ha, S1c * d.Hc);
   char* p = static_cast<char*>(ws);
   int64_t off = 0;
   auto take = [&](int64_t bytes) {
@@ -616,16 +626,20 @@ RecUpdateWs carve_rec_update(const marl_config& c, void* ws, int64_t* total) {
   w.ident = (int32_t*)take((int64_t)d.N * 4);
   w.rows = (int32_t*)take(TJ * 4);
   w.keep = (float*)take(TJ * 4);
-  w.dl = (float*)take(Sa * kActions * 4);
-  w.E = (float*)take(SH * 4);
-  w.G = (float*)take(3 * SH * 4);
-  w.RZN = (float*)take(3 * SH * 4);
-  w.GHN = (float*)take(SH * 4);
-  w.Hout = (float*)take(SH * 4);
-  w.Hprev = (float*)take((SH + S1H) * 4);
-  w.GhT = (float*)take(3 * S1H * 4);
-  w.dGh = (float*)take(3 * SH * 4);
-  w.dHp = (float*)take(2 * S1H * 4);
+  for (int k = 0; k < 2; ++k) {
+    const int64_t SH = k == 0 ? Sa * d.Ha : Sc * d.Hc, S1H = k == 0 ? S1a * d.Ha : S1c * d.Hc;
+    RecNetWs& n = w.net[k];
+    n.dl = (float*)take((k == 0 ? Sa * kActions : Sc) * 4);
+    n.E = (float*)take(SH * 4);
+    n.G = (float*)take(3 * SH * 4);
+    n.RZN = (float*)take(3 * SH * 4);
+    n.GHN = (float*)take(SH * 4);
+    n.Hout = (float*)take(SH * 4);
+    n.Hprev = (float*)take((SH + S1H) * 4);
+    n.GhT = (float*)take(3 * S1H * 4);
+    n.dGh = (float*)take(3 * SH * 4);
+    n.dHp = (float*)take(2 * S1H * 4);
+  }
   if (total) *total = off;
   return w;
 }
@@ -635,8 +649,8 @@ RecUpdateWs carve_rec_update(const marl_config& c, void* ws, int64_t* total) {
 template <int NOUT, class LossFn>
 int32_t train_net_recurrent(const RowSrc& X, int T, int64_t J, int per, int Din, int H, const float* h0,
                             const int32_t* envs, const float* eff, const RecOffsets& o, const float* wh_op,
-                            const float* wht_op, float* grad, const RecOffsets& go, const LossFn& fn, const RecUpdateWs& w,
-                            hipStream_t s) {
+                            const float* wht_op, float* grad, const RecOffsets& go, const LossFn& fn, const RecNetWs& w,
+                            const float* keep, Scalars* sc, hipStream_t s) {
   const int64_t S1 = J * per, S = (int64_t)T * S1;
   hipLaunchKernelGGL(gather_hidden_kernel, dim3(blocks_for(S1 * H)), dim3(256), 0, s, h0, envs, (int)J, per, H, w.Hprev);
   embed_and_input_gates(X, S, Din, H, eff, o, w.E, w.G, s);
@@ -646,20 +660,20 @@ int32_t train_net_recurrent(const RowSrc& X, int T, int64_t J, int per, int Din,
                                            w.RZN + (int64_t)t * S1 * 3 * H, w.GHN + (int64_t)t * S1 * H,
                                            w.Hout + (int64_t)t * S1 * H,
                                            t + 1 < T ? w.Hprev + (int64_t)(t + 1) * S1 * H : (float*)nullptr,
-                                           t + 1 < T ? w.keep + (int64_t)(t + 1) * J : (const float*)nullptr, per, s);
+                                           t + 1 < T ? keep + (int64_t)(t + 1) * J : (const float*)nullptr, per, s);
     if (rc != MARL_OK) return rc;
   }
   {  // output layer, loss, dL/dout, W3 / b3 gradient over all steps
     const unsigned nb = (unsigned)std::min<int64_t>(2048, (S + kHeadTile - 1) / kHeadTile);
     hipLaunchKernelGGL((loss_head_kernel<NOUT, LossFn, float>), dim3(nb), dim3(256), 0, s, w.Hout, S, H, eff + o.W3,
-                       eff + o.b3, fn, w.dl, grad + go.W3, grad + go.b3, w.sc, 0.f);
+                       eff + o.b3, fn, w.dl, grad + go.W3, grad + go.b3, sc, 0.f);
   }
   for (int t = T - 1; t >= 0; --t) {
     float* dhp = w.dHp + (int64_t)(t & 1) * S1 * H;
     const float* dh_next = t + 1 < T ? w.dHp + (int64_t)((t + 1) & 1) * S1 * H : (const float*)nullptr;
     float* dgi = w.G + (int64_t)t * S1 * 3 * H;  // the input-gate products are no longer needed: their gradient takes their place
     float* dgh = w.dGh + (int64_t)t * S1 * 3 * H;
-    const int32_t rc = launch_step_backward<NOUT>(dh_next, t + 1 < T ? w.keep + (int64_t)(t + 1) * J : (const float*)nullptr,
+    const int32_t rc = launch_step_backward<NOUT>(dh_next, t + 1 < T ? keep + (int64_t)(t + 1) * J : (const float*)nullptr,
                                                   w.dl + (int64_t)t * S1 * NOUT, w.RZN + (int64_t)t * S1 * 3 * H,
                                                   w.GHN + (int64_t)t * S1 * H, w.Hprev + (int64_t)t * S1 * H, S1, H, eff, o,
                                                   wht_op, dgi, dgh, dhp, t > 0, per, s);
@@ -712,6 +726,7 @@ int32_t launch_ppo_update_recurrent(const marl_config& c, marl_traj tr, marl_rec
   const RecOffsets ga = rec_offsets(0, d.D, d.Ha, kActions), gc = rec_offsets(d.Pa, d.Dc, d.Hc, 1);
   const RecParamMap pm = rec_param_map(d);
   const RecOffsets oa = rec_padded(pm, 0), oc = rec_padded(pm, 1);
+  const SideStream* const side = side_stream();
   int64_t k = adam_step0;
   for (int e = 0; e < c.n_epochs; ++e) {
     for (int mb = 0; mb < c.n_minibatches; ++mb) {
@@ -727,20 +742,33 @@ int32_t launch_ppo_update_recurrent(const marl_config& c, marl_traj tr, marl_rec
         const unsigned nb = (unsigned)std::min<int64_t>(256, (TJ * d.A + 255) / 256);
         hipLaunchKernelGGL(adv_stats_kernel, dim3(nb), dim3(256), 0, s, tr.adv, lc, w.sc);
       }
+      // The two networks share nothing but their inputs and write disjoint parts of the gradient: the critic runs on the
+      // second stream beside the actor.  A time step of either is a short chain of dependent matrix instructions on a
+      // few hundred workgroups, so the two chains interleave on the compute units instead of following one another.
+      hipStream_t s2 = s;
+      if (side != nullptr && hipEventRecord(side->fork, s) == hipSuccess && hipStreamWaitEvent(side->stream, side->fork, 0) == hipSuccess)
+        s2 = side->stream;
+      int32_t rc_a, rc_c;
       {
         ActorLoss fn{lc, tr.action, tr.logp, tr.adv};
-        const int32_t rc = train_net_recurrent<kActions>(RowSrc{tr.obs, d.D, w.rows, d.A, TJ * d.A}, d.T, J, d.A, d.D, d.Ha,
-                                                         rec.ha0, envs, eff, oa, eff + pm.wh_op[0], eff + pm.wht_op[0], w.grad,
-                                                         ga, fn, w, s);
-        if (rc != MARL_OK) return rc;
+        rc_a = train_net_recurrent<kActions>(RowSrc{tr.obs, d.D, w.rows, d.A, TJ * d.A}, d.T, J, d.A, d.D, d.Ha, rec.ha0, envs,
+                                             eff, oa, eff + pm.wh_op[0], eff + pm.wht_op[0], w.grad, ga, fn, w.net[0], w.keep,
+                                             w.sc, s);
       }
       {
         CriticLoss fn{lc, tr.ret, tr.value, d.central ? d.A : 1};
         const int per = d.central ? 1 : d.A;
-        const int32_t rc = train_net_recurrent<1>(RowSrc{tr.obs, d.Dc, w.rows, per, TJ * per}, d.T, J, per, d.Dc, d.Hc, rec.hc0,
-                                                  envs, eff, oc, eff + pm.wh_op[1], eff + pm.wht_op[1], w.grad, gc, fn, w, s);
-        if (rc != MARL_OK) return rc;
+        rc_c = train_net_recurrent<1>(RowSrc{tr.obs, d.Dc, w.rows, per, TJ * per}, d.T, J, per, d.Dc, d.Hc, rec.hc0, envs, eff,
+                                      oc, eff + pm.wh_op[1], eff + pm.wht_op[1], w.grad, gc, fn, w.net[1], w.keep, w.sc, s2);
       }
+      if (s2 != s) {  // join also after an error, so that the caller's stream never runs ahead of work still queued beside it
+        if (hipEventRecord(side->join, s2) != hipSuccess || hipStreamWaitEvent(s, side->join, 0) != hipSuccess) {
+          (void)hipStreamSynchronize(s2);
+          return MARL_E_LAUNCH;
+        }
+      }
+      if (rc_a != MARL_OK) return rc_a;
+      if (rc_c != MARL_OK) return rc_c;
       hipLaunchKernelGGL(grad_norm_kernel, dim3(grad_norm_blocks(d.P)), dim3(256), 0, s,
                          w.grad, d.P, w.sc);
       ++k;
