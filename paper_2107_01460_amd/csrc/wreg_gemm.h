@@ -71,7 +71,9 @@ struct WregShape {
   static constexpr int GROUPS = K / 8;
   static constexpr size_t lds_bytes = sizeof(float) * 2 * kWregBM * P + sizeof(int64_t) * 2 * kWregBM;
   // WREG_TANH_LOSS adds: W3 [256][NOUT], partial outputs [4][BM][NOUT], dL/d(out) [BM][8]
-  static constexpr size_t loss_lds_bytes(int nout) { return sizeof(float) * (kWregN * nout + 4 * kWregBM * nout + kWregBM * 8); }
+  static constexpr size_t loss_lds_bytes(int nout) {
+    return sizeof(float) * (kWregN * nout + 4 * kWregBM * nout + kWregBM * 8 + kWregBM * (nout + 5));
+  }
   static_assert(K % 16 == 0 && (P / 4) % 2 == 1, "K a multiple of 16 with an odd K/4 + 1");
 };
 
@@ -85,6 +87,10 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) 
   float* const W3s = reinterpret_cast<float*>(ent + 2 * BM);                    // WREG_TANH_LOSS only, as are the next two
   float* const red = W3s + kWregN * NOUT;                                       // [4][BM][NOUT]
   float* const dls = red + 4 * BM * NOUT;                                       // [BM][8]
+  // per-sample-slot sums that only the first BM threads touch, once per tile (b3 gradient, loss statistics): in LDS rather
+  // than in registers of every thread, which this kernel does not have to spare
+  constexpr int AS = NOUT + 5;
+  float* const accS = dls + BM * 8;                                             // [BM][AS]
   static_assert(EPI != WREG_TANH_LOSS || K == kWregN, "the activation tile reuses the stage of A it came from");
   // The two plain epilogues are deferred where the registers allow: a tile's accumulators move to a second register set and are finished two
   // elements per k group INSIDE the next tile's stream of matrix instructions, so that the single wavefront of a SIMD
@@ -155,10 +161,14 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) 
   // ---- prologue: entries of the first two tiles, then the first tile itself
   int64_t tile = blockIdx.x;
   if (tile >= ntiles) return;  // uniform per workgroup
-  // output-layer gradient of hidden unit tid, the bias gradient and the loss statistics, summed over this workgroup's tiles
-  float gw[NOUT], gb[NOUT], st[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
+  // output-layer gradient of this lane's two columns (its half of the rows), the bias gradient and the loss statistics, summed over this workgroup's tiles
+  float gw[2][NOUT];
 #pragma unroll
-  for (int k = 0; k < NOUT; ++k) gw[k] = gb[k] = 0.f;
+  for (int k = 0; k < NOUT; ++k) gw[0][k] = gw[1][k] = 0.f;
+  if (EPI == WREG_TANH_LOSS && tid < BM) {  // read and written by thread tid only
+#pragma unroll
+    for (int k = 0; k < AS; ++k) accS[tid * AS + k] = 0.f;
+  }
   if (EPI == WREG_TANH_LOSS)
     for (int i = tid; i < kWregN * NOUT; i += 256) W3s[i] = a.W3[i];  // ordered before its first use by the barriers below
   const auto prep = fin.prepare();
@@ -363,11 +373,14 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) 
           out[k] = v;
           dl[k] = 0.f;
         }
+        float st[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
         if (m0 + tid < a.S) fin.compute(loss_in, prep, out, dl, st);
+#pragma unroll
+        for (int k = 0; k < 5; ++k) accS[tid * AS + NOUT + k] += st[k];
 #pragma unroll
         for (int k = 0; k < 8; ++k) dls[tid * 8 + k] = k < NOUT ? dl[k < NOUT ? k : 0] : 0.f;
 #pragma unroll
-        for (int k = 0; k < NOUT; ++k) gb[k] += dl[k];
+        for (int k = 0; k < NOUT; ++k) accS[tid * AS + k] += dl[k];
       }
       __syncthreads();
       // C = (dl W3^T) * (1 - h^2): the rank-NOUT product runs on the matrix cores (k padded to 8) and lands in the
@@ -394,13 +407,23 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) 
           }
         }
       }
-      // gW3[tid][k] += sum_s h[s][tid] dl[s][k] (rows past the end carry dl = 0)
-#pragma unroll 8
-      for (int smp = 0; smp < BM; ++smp) {
-        const float h = Hs[smp * P + tid];
+      // W3 gradient: sum_s h[s][n] dl[s][k] over the rows whose h this lane holds in registers (32 of the tile's 64 for
+      // each of its two columns; the lane 32 further on holds the other half, and the two meet after the last tile).
+      // Rows past the end carry dl = 0.
 #pragma unroll
-        for (int k = 0; k < NOUT; ++k) gw[k] = fmaf(h, dls[smp * 8 + k], gw[k]);
-      }
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int m = 32 * i + 8 * (r / 4) + 4 * hi + (r % 4);
+          float dlv[NOUT];
+#pragma unroll
+          for (int k = 0; k < NOUT; ++k) dlv[k] = dls[m * 8 + k];
+          if (r % 4 == 0) __builtin_amdgcn_sched_barrier(0);  // four rows' reads at a time: no more registers than that in flight
+#pragma unroll
+          for (int jn = 0; jn < 2; ++jn)
+#pragma unroll
+            for (int k = 0; k < NOUT; ++k) gw[jn][k] = fmaf(acc[i][jn][r], dlv[k], gw[jn][k]);
+        }
     }
     if (tid < BM) ent[stage * BM + tid] = e2;  // this tile's entries were last read while the previous tile was multiplied
     __syncthreads();  // the other stage is complete; this one may be overwritten
@@ -416,14 +439,20 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) 
   if (EPI == WREG_TANH_LOSS) {
     float* const own = a.partial3 != nullptr ? a.partial3 + (int64_t)blockIdx.x * (kWregN * NOUT + NOUT) : nullptr;
 #pragma unroll
-    for (int k = 0; k < NOUT; ++k) {
-      if (own != nullptr) own[tid * NOUT + k] = gw[k];
-      else atomicAdd(&a.gW3[tid * NOUT + k], gw[k]);
-    }
+    for (int jn = 0; jn < 2; ++jn)
+#pragma unroll
+      for (int k = 0; k < NOUT; ++k) {
+        const float v = gw[jn][k] + __shfl_xor(gw[jn][k], 32);  // the two halves of the rows
+        const int n = 64 * wave + 32 * jn + lo;
+        if (hi == 0) {
+          if (own != nullptr) own[n * NOUT + k] = v;
+          else atomicAdd(&a.gW3[n * NOUT + k], v);
+        }
+      }
     if (wave == 0) {  // samples live in threads tid < 64
 #pragma unroll
       for (int k = 0; k < NOUT; ++k) {
-        float v = gb[k];
+        float v = accS[tid * AS + k];
         for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
         if (lane == 0) {
           if (own != nullptr) own[kWregN * NOUT + k] = v;
@@ -432,7 +461,7 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) 
       }
 #pragma unroll
       for (int k = 0; k < 5; ++k) {
-        float v = st[k];
+        float v = accS[tid * AS + NOUT + k];
         for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
         if (lane == 0 && v != 0.f) atomicAdd(&a.stats[k], v);
       }
