@@ -252,7 +252,12 @@ int32_t marl_rollout_recurrent(const marl_config* cfg, marl_env_state st, const 
 /* As marl_ppo_update for the recurrent networks: every environment's T-step rollout is one sequence, a minibatch is
  * n_envs / n_minibatches environments (epoch e visits them in the order perm[e][0..N), NULL = identity), the loss
  * is the PPO loss over all steps of those sequences, and the gradient flows back through time from step T-1 to 0,
- * stopping at episode boundaries and at rec.h*0.  workspace: update_workspace_bytes of the recurrent configuration. */
+ * stopping at episode boundaries and at rec.h*0.  workspace: update_workspace_bytes of the recurrent configuration.
+ * The two networks of a minibatch run side by side: the critic's kernels go to a second stream that the library creates
+ * once per device (default priority, kept until the process ends), forked from `stream` and joined back into it with
+ * events inside the call, so for the caller everything is still ordered on `stream` and nothing is waited for on the
+ * host.  One such call at a time per device: calls that overlap on one device from several host threads would share
+ * that stream's two events.  If the stream cannot be created the critic simply follows the actor on `stream`. */
 int32_t marl_ppo_update_recurrent(const marl_config* cfg, marl_traj traj, marl_rec_state rec, float* params,
                                   float* adam_m, float* adam_v, int64_t adam_step0, const int32_t* perm, float* stats,
                                   float* grad_dump, void* workspace, void* stream);
