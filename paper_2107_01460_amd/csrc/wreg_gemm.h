@@ -3,9 +3,9 @@
 //   C[m][n] = epilogue( sum_k A[m][k] * B(k, n) ),   m < S (hundreds of thousands of rows), n < 256, k < K <= 304
 //
 // A 256 x 256 fp32 weight matrix is 256 KB: half of the register file of one compute unit.  A workgroup of four
-// wavefronts (one per SIMD, up to 512 registers per lane) therefore keeps the whole matrix in registers for its
-// lifetime: wavefront w holds columns 64 w .. 64 w + 63 in the lane layout the matrix cores read their second operand
-// in.  The workgroup is persistent over tiles of 64 rows; a tile of A travels global -> registers -> LDS while the
+// wavefronts (one per SIMD, up to 512 registers per lane) -- or of eight (two per SIMD, 256 registers each) -- therefore
+// keeps the whole matrix in registers for its lifetime: wavefront w holds columns 64 w .. 64 w + 63 (32 w .. 32 w + 31
+// with eight) in the lane layout the matrix cores read their second operand in.  The workgroup is persistent over tiles of 64 rows; a tile of A travels global -> registers -> LDS while the
 // previous one is multiplied (two LDS stages), every wavefront reads the same A fragments from LDS and multiplies
 // them into its own 64 columns (2 x 2 accumulator tiles of 32 x 32).  Nothing but A and C moves per tile: no weight
 // traffic at all, one barrier per tile.
@@ -65,28 +65,30 @@ template <int K>
 struct WregShape {
   static constexpr int P = K + 4;                      // LDS row pitch: 4 * odd, conflict-free 16-byte row-per-lane reads
   static constexpr int VPR = K / 4;                    // 16-byte vectors per row
-  static constexpr int TOT = kWregBM * VPR / 256;      // vectors a thread stages per tile
   static constexpr int NB = 8;                         // staging batches per tile
-  static constexpr int PER = (TOT + NB - 1) / NB;      // vectors per batch
   static constexpr int GROUPS = K / 8;
   static constexpr size_t lds_bytes = sizeof(float) * 2 * kWregBM * P + sizeof(int64_t) * 2 * kWregBM;
   // WREG_TANH_LOSS adds: W3 [256][NOUT], partial outputs [4][BM][NOUT], dL/d(out) [BM][8]
-  static constexpr size_t loss_lds_bytes(int nout) {
-    return sizeof(float) * (kWregN * nout + 4 * kWregBM * nout + kWregBM * 8 + kWregBM * (nout + 5));
+  static constexpr size_t loss_lds_bytes(int nout, int nwv) {
+    return sizeof(float) * (kWregN * nout + nwv * kWregBM * nout + kWregBM * 8 + kWregBM * (nout + 5));
   }
   static_assert(K % 16 == 0 && (P / 4) % 2 == 1, "K a multiple of 16 with an odd K/4 + 1");
 };
 
-template <int K, int EPI, int NOUT = 1, class Fin = WregNoFinish>
-__global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) {
+// NWV wavefronts (4: one per SIMD, 64 columns each; 8: two per SIMD, 32 columns each, half the registers per lane)
+template <int K, int EPI, int NOUT = 1, class Fin = WregNoFinish, int NWV = 4>
+__global__ void __launch_bounds__(64 * NWV, 1) wreg_gemm_kernel(WregArgs a, Fin fin) {
   using Sh = WregShape<K>;
-  constexpr int P = Sh::P, VPR = Sh::VPR, TOT = Sh::TOT, NB = Sh::NB, PER = Sh::PER, GROUPS = Sh::GROUPS, BM = kWregBM;
+  constexpr int NT = 64 * NWV, CW = kWregN / NWV, JN = CW / 32, EPL = 32 * JN;  // threads, columns per wavefront, column tiles, outputs per lane
+  constexpr int P = Sh::P, VPR = Sh::VPR, NB = Sh::NB, GROUPS = Sh::GROUPS, BM = kWregBM;
+  constexpr int TOT = (BM * VPR + NT - 1) / NT, PER = (TOT + NB - 1) / NB;  // vectors a thread stages per tile, per batch
+  constexpr bool RAGGED = (BM * VPR) % NT != 0;  // the last vector index of some threads lies past the tile
   extern __shared__ __attribute__((aligned(16))) unsigned char wreg_smem[];
   float* const As = reinterpret_cast<float*>(wreg_smem);                       // [2][BM][P]
   int64_t* const ent = reinterpret_cast<int64_t*>(As + 2 * BM * P);            // [2][BM] offsets (floats) of a tile's rows
   float* const W3s = reinterpret_cast<float*>(ent + 2 * BM);                    // WREG_TANH_LOSS only, as are the next two
-  float* const red = W3s + kWregN * NOUT;                                       // [4][BM][NOUT]
-  float* const dls = red + 4 * BM * NOUT;                                       // [BM][8]
+  float* const red = W3s + kWregN * NOUT;                                       // [NWV][BM][NOUT]
+  float* const dls = red + NWV * BM * NOUT;                                       // [BM][8]
   // per-sample-slot sums that only the first BM threads touch, once per tile (b3 gradient, loss statistics): in LDS rather
   // than in registers of every thread, which this kernel does not have to spare
   constexpr int AS = NOUT + 5;
@@ -95,7 +97,8 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) 
   // The two plain epilogues are deferred where the registers allow: a tile's accumulators move to a second register set and are finished two
   // elements per k group INSIDE the next tile's stream of matrix instructions, so that the single wavefront of a SIMD
   // keeps its matrix core busy while it applies tanh and stores (only a workgroup's last tile finishes on its own).
-  constexpr bool DEFER = EPI != WREG_TANH_LOSS && K <= 256;  // a longer contraction leaves no room for the second set
+  constexpr bool DEFER = EPI != WREG_TANH_LOSS && K <= 256;
+  constexpr int EPG = EPL / 32;  // deferred elements finished per k group  // a longer contraction leaves no room for the second set
   constexpr int LOOK = 8;  // WREG_DTANH: k groups between the request of an element's operand and its use
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -103,12 +106,12 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) 
   const int64_t ntiles = (a.S + BM - 1) / BM;
 
   // ---- the weights: breg[g][j][jn] = B(8 g + 4 hi + j, 64 wave + 32 jn + lo)
-  float breg[GROUPS][4][2];
+  float breg[GROUPS][4][JN];
 #pragma unroll
   for (int g = 0; g < GROUPS; ++g)
 #pragma unroll
-    for (int jn = 0; jn < 2; ++jn) {
-      const int n = 64 * wave + 32 * jn + lo;
+    for (int jn = 0; jn < JN; ++jn) {
+      const int n = CW * wave + 32 * jn + lo;
       const int k = 8 * g + 4 * hi;
       if (a.b_kcont) {
         const float4 v = (k < a.Kin) ? *reinterpret_cast<const float4*>(a.B + (int64_t)n * a.ldb + k) : make_float4(0.f, 0.f, 0.f, 0.f);
@@ -120,8 +123,9 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) 
     }
 
   // ---- staging of a tile of A: vector f = tid + 256 p of the tile is (row f / VPR, columns 4 (f % VPR) ..)
-  auto row_of = [&](int p) { return (tid + 256 * p) / VPR; };
-  auto col_of = [&](int p) { return 4 * ((tid + 256 * p) % VPR); };
+  auto row_of = [&](int p) { return (tid + NT * p) / VPR; };
+  auto col_of = [&](int p) { return 4 * ((tid + NT * p) % VPR); };
+  auto in_tile = [&](int p) { return !RAGGED || tid + NT * p < BM * VPR; };
   // A batch is requested SETS batch intervals before it is stored (one register set each), and the row offsets it needs
   // are read from LDS one k group before the request.
   constexpr int SETS = K <= 256 ? 2 : 1;  // the longer contraction has registers for one batch in flight only
@@ -131,14 +135,14 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) 
 #pragma unroll
     for (int q = 0; q < PER; ++q) {
       const int p = b * PER + q;
-      if (p < TOT) eoff[q] = ent[slot * BM + row_of(p)];
+      if (p < TOT && in_tile(p)) eoff[q] = ent[slot * BM + row_of(p)];
     }
   };
   auto fetch_batch = [&](int b) {
 #pragma unroll
     for (int q = 0; q < PER; ++q) {
       const int p = b * PER + q;
-      if (p < TOT) {
+      if (p < TOT && in_tile(p)) {
         const int c = col_of(p);
         stg[b % SETS][q] = (c < a.Kin) ? *reinterpret_cast<const float4*>(a.A.base + eoff[q] + c) : make_float4(0.f, 0.f, 0.f, 0.f);
       }
@@ -148,7 +152,7 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) 
 #pragma unroll
     for (int q = 0; q < PER; ++q) {
       const int p = b * PER + q;
-      if (p < TOT) *reinterpret_cast<float4*>(&As[(stage * BM + row_of(p)) * P + col_of(p)]) = stg[b % SETS][q];
+      if (p < TOT && in_tile(p)) *reinterpret_cast<float4*>(&As[(stage * BM + row_of(p)) * P + col_of(p)]) = stg[b % SETS][q];
     }
   };
   // offset of row tid of a tile (threads tid < BM); rows past the end repeat the last row, whose results are never stored
@@ -162,15 +166,17 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) 
   int64_t tile = blockIdx.x;
   if (tile >= ntiles) return;  // uniform per workgroup
   // output-layer gradient of this lane's two columns (its half of the rows), the bias gradient and the loss statistics, summed over this workgroup's tiles
-  float gw[2][NOUT];
+  float gw[JN][NOUT];
 #pragma unroll
-  for (int k = 0; k < NOUT; ++k) gw[0][k] = gw[1][k] = 0.f;
+  for (int jn = 0; jn < JN; ++jn)
+#pragma unroll
+    for (int k = 0; k < NOUT; ++k) gw[jn][k] = 0.f;
   if (EPI == WREG_TANH_LOSS && tid < BM) {  // read and written by thread tid only
 #pragma unroll
     for (int k = 0; k < AS; ++k) accS[tid * AS + k] = 0.f;
   }
   if (EPI == WREG_TANH_LOSS)
-    for (int i = tid; i < kWregN * NOUT; i += 256) W3s[i] = a.W3[i];  // ordered before its first use by the barriers below
+    for (int i = tid; i < kWregN * NOUT; i += NT) W3s[i] = a.W3[i];  // ordered before its first use by the barriers below
   const auto prep = fin.prepare();
   {
     const int64_t e0 = load_entries(tile), e1 = load_entries(tile + gridDim.x);
@@ -188,22 +194,20 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) 
     __syncthreads();
   }
 
-  floatx16 prev[2][2];     // DEFER: the previous tile's accumulators ...
+  floatx16 prev[2][JN];     // DEFER: the previous tile's accumulators ...
   int64_t prev_off = 0;    // ... and where its outputs go.  Before the first tile: zeros, "finished" into the first
 #pragma unroll
   for (int i = 0; i < 2; ++i)  // tile's own place, where the real values overwrite them one tile later (same lane, same
 #pragma unroll
-    for (int jn = 0; jn < 2; ++jn)  // addresses, program order)
+    for (int jn = 0; jn < JN; ++jn)  // addresses, program order)
 #pragma unroll
       for (int r = 0; r < 16; ++r) prev[i][jn][r] = 0.f;
-  float bias2[2] = {0.f, 0.f};
-  if (EPI == WREG_BIAS_TANH) {
-    bias2[0] = a.bias[64 * wave + lo];
-    bias2[1] = a.bias[64 * wave + 32 + lo];
-  }
+  float bias2[JN];
+#pragma unroll
+  for (int jn = 0; jn < JN; ++jn) bias2[jn] = EPI == WREG_BIAS_TANH ? a.bias[CW * wave + 32 * jn + lo] : 0.f;
   // element e = 32 jn + 16 i + r of a lane's 64 outputs: offset from the lane's address, and its finish
   auto elem_off = [](int e) { return (32 * ((e >> 4) & 1) + 8 * ((e & 15) / 4) + (e & 3)) * kWregN + 32 * (e >> 5); };
-  float auxr[64];
+  float auxr[EPL];
   auto finish_elem = [&](int e, int64_t off) {
     const int jn = e >> 5, i = (e >> 4) & 1, r = e & 15;
     float v = prev[i][jn][r];
@@ -226,11 +230,11 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) 
 
     // A lane's 64 outputs sit at fixed offsets from one address: rows 32 i + 8 (r/4) + r%4 below row m0 + 4 hi,
     // columns 32 jn right of column 64 wave + lo.
-    const int64_t lane_off = (m0 + 4 * hi) * kWregN + 64 * wave + lo;
+    const int64_t lane_off = (m0 + 4 * hi) * kWregN + CW * wave + lo;
     if (it == 0) prev_off = lane_off;
     if (DEFER && EPI == WREG_DTANH) {  // operands of the first elements of the previous tile's finish
 #pragma unroll
-      for (int e = 0; e < 2 * LOOK; ++e) auxr[e] = a.aux[prev_off + elem_off(e)];
+      for (int e = 0; e < EPG * LOOK; ++e) auxr[e] = a.aux[prev_off + elem_off(e)];
     }
 
     // the loss inputs of sample tid of this tile (threads tid < BM): the row entry now, the values half-way through
@@ -238,11 +242,11 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) 
     const int32_t loss_entry = (EPI == WREG_TANH_LOSS && tid < BM) ? fin.row_entry(my_sample) : 0;
     typename Fin::In loss_in{};
 
-    floatx16 acc[2][2];
+    floatx16 acc[2][JN];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int jn = 0; jn < 2; ++jn)
+      for (int jn = 0; jn < JN; ++jn)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][jn][r] = 0.f;
 
@@ -255,19 +259,21 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) 
     }
     // fragments of A: those of group g + 1 are read from LDS before the products of group g are issued (SETS == 2;
     // the longer contraction has no registers for the second pair and reads each group's fragments at its top)
+    // (with two wavefronts per SIMD the other wavefront covers the LDS latency, and the registers are needed elsewhere)
+    constexpr bool FPRE = SETS == 2 && NWV == 4;
     float4 fa[2][2];
-    if (SETS == 2) {
+    if (FPRE) {
       fa[0][0] = *reinterpret_cast<const float4*>(&At[lo * P + 4 * hi]);
       fa[0][1] = *reinterpret_cast<const float4*>(&At[(32 + lo) * P + 4 * hi]);
     }
 #pragma unroll
     for (int g = 0; g < GROUPS; ++g) {
-      if (SETS == 2 && g + 1 < GROUPS) {
+      if (FPRE && g + 1 < GROUPS) {
         fa[(g + 1) & 1][0] = *reinterpret_cast<const float4*>(&At[lo * P + 8 * (g + 1) + 4 * hi]);
         fa[(g + 1) & 1][1] = *reinterpret_cast<const float4*>(&At[(32 + lo) * P + 8 * (g + 1) + 4 * hi]);
         __builtin_amdgcn_sched_barrier(0);  // keep these reads ahead of this group's matrix instructions
       }
-      if (SETS == 1) {
+      if (!FPRE) {
         fa[g & 1][0] = *reinterpret_cast<const float4*>(&At[lo * P + 8 * g + 4 * hi]);
         fa[g & 1][1] = *reinterpret_cast<const float4*>(&At[(32 + lo) * P + 8 * g + 4 * hi]);
       }
@@ -278,16 +284,16 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) 
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
-          for (int jn = 0; jn < 2; ++jn)
+          for (int jn = 0; jn < JN; ++jn)
             acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i][j], breg[g][j][jn], acc[i][jn], 0, 0, 0);
       if (EPI == WREG_TANH_LOSS && g == GROUPS / 2 && tid < BM) loss_in = fin.load_with(my_sample, loss_entry);
-      if (DEFER && g < 32) {  // two elements of the previous tile per k group
+      if (DEFER && g < 32) {  // EPG elements of the previous tile per k group
         if (EPI == WREG_DTANH && g + LOOK < 32) {
-          auxr[2 * (g + LOOK)] = a.aux[prev_off + elem_off(2 * (g + LOOK))];
-          auxr[2 * (g + LOOK) + 1] = a.aux[prev_off + elem_off(2 * (g + LOOK) + 1)];
+#pragma unroll
+          for (int q = 0; q < EPG; ++q) auxr[EPG * (g + LOOK) + q] = a.aux[prev_off + elem_off(EPG * (g + LOOK) + q)];
         }
-        finish_elem(2 * g, prev_off);
-        finish_elem(2 * g + 1, prev_off);
+#pragma unroll
+        for (int q = 0; q < EPG; ++q) finish_elem(EPG * g + q, prev_off);
       }
       // the next tile moves in NB batches spread over the products: batch b leaves its registers for the other LDS
       // stage at the end of its interval and batch b + 2 is requested into them; its row offsets were read a group earlier
@@ -307,11 +313,11 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) 
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int jn = 0; jn < 2; ++jn) prev[i][jn] = acc[i][jn];
+        for (int jn = 0; jn < JN; ++jn) prev[i][jn] = acc[i][jn];
       prev_off = lane_off;
     } else if (EPI != WREG_TANH_LOSS) {
 #pragma unroll
-      for (int jn = 0; jn < 2; ++jn)
+      for (int jn = 0; jn < JN; ++jn)
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -330,8 +336,8 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) 
       float* const Hs = As + stage * BM * P;
       __syncthreads();  // every wavefront has read its last fragment of A
 #pragma unroll
-      for (int jn = 0; jn < 2; ++jn) {
-        const int n = 64 * wave + 32 * jn + lo;
+      for (int jn = 0; jn < JN; ++jn) {
+        const int n = CW * wave + 32 * jn + lo;
         const float bias = a.bias[n];
 #pragma unroll
         for (int i = 0; i < 2; ++i)
@@ -344,14 +350,14 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) 
           }
       }
       __syncthreads();
-      // output layer on the ALUs: thread -> (sample tid % 64, hidden units 64 (tid / 64) ..)
+      // output layer on the ALUs: thread -> (sample tid % 64, hidden units CW (tid / 64) ..)
       {
         const int smp = tid & 63, grp = tid >> 6;
         float part[NOUT];
 #pragma unroll
         for (int k = 0; k < NOUT; ++k) part[k] = 0.f;
 #pragma unroll 4
-        for (int i = 64 * grp; i < 64 * grp + 64; i += 4) {  // 16-byte reads of the row (P is a multiple of 4)
+        for (int i = CW * grp; i < CW * grp + CW; i += 4) {  // 16-byte reads of the row (P is a multiple of 4)
           const float4 hv = *reinterpret_cast<const float4*>(&Hs[smp * P + i]);
           const float hh[4] = {hv.x, hv.y, hv.z, hv.w};
 #pragma unroll
@@ -369,7 +375,7 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) 
         for (int k = 0; k < NOUT; ++k) {
           float v = a.b3[k];
 #pragma unroll
-          for (int gq = 0; gq < 4; ++gq) v += red[(gq * BM + tid) * NOUT + k];
+          for (int gq = 0; gq < NWV; ++gq) v += red[(gq * BM + tid) * NOUT + k];
           out[k] = v;
           dl[k] = 0.f;
         }
@@ -390,8 +396,8 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) 
         const float4 av = *reinterpret_cast<const float4*>(&dls[(32 * i + lo) * 8 + 4 * hi]);
         const float af[4] = {av.x, av.y, av.z, av.w};
 #pragma unroll
-        for (int jn = 0; jn < 2; ++jn) {
-          const int n = 64 * wave + 32 * jn + lo;
+        for (int jn = 0; jn < JN; ++jn) {
+          const int n = CW * wave + 32 * jn + lo;
           float bf[4];
 #pragma unroll
           for (int j = 0; j < 4; ++j) bf[j] = (4 * hi + j < NOUT) ? W3s[n * NOUT + (4 * hi + j < NOUT ? 4 * hi + j : 0)] : 0.f;
@@ -420,7 +426,7 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) 
           for (int k = 0; k < NOUT; ++k) dlv[k] = dls[m * 8 + k];
           if (r % 4 == 0) __builtin_amdgcn_sched_barrier(0);  // four rows' reads at a time: no more registers than that in flight
 #pragma unroll
-          for (int jn = 0; jn < 2; ++jn)
+          for (int jn = 0; jn < JN; ++jn)
 #pragma unroll
             for (int k = 0; k < NOUT; ++k) gw[jn][k] = fmaf(acc[i][jn][r], dlv[k], gw[jn][k]);
         }
@@ -431,19 +437,19 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) 
   if (DEFER) {  // the last tile of this workgroup
     if (EPI == WREG_DTANH) {
 #pragma unroll
-      for (int e = 0; e < 64; ++e) auxr[e] = a.aux[prev_off + elem_off(e)];
+      for (int e = 0; e < EPL; ++e) auxr[e] = a.aux[prev_off + elem_off(e)];
     }
 #pragma unroll
-    for (int e = 0; e < 64; ++e) finish_elem(e, prev_off);
+    for (int e = 0; e < EPL; ++e) finish_elem(e, prev_off);
   }
   if (EPI == WREG_TANH_LOSS) {
     float* const own = a.partial3 != nullptr ? a.partial3 + (int64_t)blockIdx.x * (kWregN * NOUT + NOUT) : nullptr;
 #pragma unroll
-    for (int jn = 0; jn < 2; ++jn)
+    for (int jn = 0; jn < JN; ++jn)
 #pragma unroll
       for (int k = 0; k < NOUT; ++k) {
         const float v = gw[jn][k] + __shfl_xor(gw[jn][k], 32);  // the two halves of the rows
-        const int n = 64 * wave + 32 * jn + lo;
+        const int n = CW * wave + 32 * jn + lo;
         if (hi == 0) {
           if (own != nullptr) own[n * NOUT + k] = v;
           else atomicAdd(&a.gW3[n * NOUT + k], v);
@@ -469,9 +475,9 @@ __global__ void __launch_bounds__(256, 1) wreg_gemm_kernel(WregArgs a, Fin fin) 
   }
 }
 
-template <int K, int EPI, int NOUT = 1, class Fin = WregNoFinish>
+template <int K, int EPI, int NOUT = 1, class Fin = WregNoFinish, int NWV = 4>
 inline int32_t launch_wreg_gemm_inst(const WregArgs& a, hipStream_t s, const Fin& fin = Fin()) {
-  auto kern = wreg_gemm_kernel<K, EPI, NOUT, Fin>;
+  auto kern = wreg_gemm_kernel<K, EPI, NOUT, Fin, NWV>;
   static bool configured = false;  // per instantiation
   if (!configured) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
@@ -479,8 +485,8 @@ inline int32_t launch_wreg_gemm_inst(const WregArgs& a, hipStream_t s, const Fin
     configured = true;
   }
   const int64_t tiles = (a.S + kWregBM - 1) / kWregBM;
-  const size_t lds = WregShape<K>::lds_bytes + (EPI == WREG_TANH_LOSS ? WregShape<K>::loss_lds_bytes(NOUT) : 0);
-  hipLaunchKernelGGL(kern, dim3((unsigned)std::min<int64_t>(tiles, 256)), dim3(256), lds, s, a, fin);
+  const size_t lds = WregShape<K>::lds_bytes + (EPI == WREG_TANH_LOSS ? WregShape<K>::loss_lds_bytes(NOUT, NWV) : 0);
+  hipLaunchKernelGGL(kern, dim3((unsigned)std::min<int64_t>(tiles, 256)), dim3(64 * NWV), lds, s, a, fin);
   return MARL_OK;
 }
 
@@ -495,13 +501,18 @@ inline bool wreg_gemm_supported(const RowSrc& A, int Kin, int N) {
 template <int EPI>
 inline int32_t launch_wreg_gemm(const WregArgs& a, hipStream_t s) {
   static_assert(EPI != WREG_TANH_LOSS, "launch_wreg_loss");
-  if (EPI == WREG_DTANH || a.Kin <= 256) return launch_wreg_gemm_inst<256, EPI>(a, s);
-  return launch_wreg_gemm_inst<EPI == WREG_DTANH ? 256 : 304, EPI>(a, s);
+  // Wavefronts per workgroup, by measurement at 262 144 rows: the padded contraction (no registers for the deferred
+  // epilogue either way) gains from two wavefronts per SIMD taking turns on the matrix core (368 -> 346 us); the
+  // kernels that finish a tile inside the next tile's products are faster with one (299 against 343 us).
+  if (EPI == WREG_DTANH || a.Kin <= 256) return launch_wreg_gemm_inst<256, EPI, 1, WregNoFinish, 4>(a, s);
+  return launch_wreg_gemm_inst<EPI == WREG_DTANH ? 256 : 304, EPI, 1, WregNoFinish, 8>(a, s);
 }
 
 template <int NOUT, class Fin>
 inline int32_t launch_wreg_loss(const WregArgs& a, const Fin& fin, hipStream_t s) {
-  return launch_wreg_gemm_inst<256, WREG_TANH_LOSS, NOUT, Fin>(a, s, fin);
+  // eight wavefronts: the barrier-separated phases of its epilogue are latency chains that a second wavefront per SIMD
+  // fills (371 -> 336 us at 262 144 rows)
+  return launch_wreg_gemm_inst<256, WREG_TANH_LOSS, NOUT, Fin, 8>(a, s, fin);
 }
 
 // ---------------------------------------------------------------------------------------------------------------
