@@ -204,7 +204,10 @@ __global__ void __launch_bounds__(64 * NWV, 1) wreg_gemm_kernel(WregArgs a, Fin 
       for (int r = 0; r < 16; ++r) prev[i][jn][r] = 0.f;
   float bias2[JN];
 #pragma unroll
-  for (int jn = 0; jn < JN; ++jn) bias2[jn] = EPI == WREG_BIAS_TANH ? a.bias[CW * wave + 32 * jn + lo] : 0.f;
+  for (int jn = 0; jn < JN; ++jn) bias2[jn] = EPI != WREG_DTANH ? a.bias[CW * wave + 32 * jn + lo] : 0.f;
+  float b3r[NOUT];  // WREG_TANH_LOSS: the output layer's bias (used by the threads that own a sample)
+#pragma unroll
+  for (int k = 0; k < NOUT; ++k) b3r[k] = EPI == WREG_TANH_LOSS ? a.b3[k] : 0.f;
   // element e = 32 jn + 16 i + r of a lane's 64 outputs: offset from the lane's address, and its finish
   auto elem_off = [](int e) { return (32 * ((e >> 4) & 1) + 8 * ((e & 15) / 4) + (e & 3)) * kWregN + 32 * (e >> 5); };
   float auxr[EPL];
@@ -338,7 +341,7 @@ __global__ void __launch_bounds__(64 * NWV, 1) wreg_gemm_kernel(WregArgs a, Fin 
 #pragma unroll
       for (int jn = 0; jn < JN; ++jn) {
         const int n = CW * wave + 32 * jn + lo;
-        const float bias = a.bias[n];
+        const float bias = bias2[jn];
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -373,7 +376,7 @@ __global__ void __launch_bounds__(64 * NWV, 1) wreg_gemm_kernel(WregArgs a, Fin 
         float out[NOUT], dl[NOUT];
 #pragma unroll
         for (int k = 0; k < NOUT; ++k) {
-          float v = a.b3[k];
+          float v = b3r[k];
 #pragma unroll
           for (int gq = 0; gq < NWV; ++gq) v += red[(gq * BM + tid) * NOUT + k];
           out[k] = v;
